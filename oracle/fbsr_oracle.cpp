@@ -1,0 +1,373 @@
+// fbsr_oracle.cpp -- TEST INFRASTRUCTURE ONLY.
+//
+// A plain, slow, serial CPU statement of few-bit stochastic rounding (FBSR),
+// written from "On Stochastic Rounding with Few Random Bits" (arXiv 2504.20634)
+// in the paper's real-number form: every step is exact arithmetic on doubles
+// (frexp/ldexp/floor of values with at most 24 significant bits), never a
+// manipulation of the fp32 bit pattern.  It exists so that tests, the smoke
+// check and the benchmark's CPU-baseline leg can compare the GPU library
+// against something that can be checked against the paper by eye.  The GPU
+// library never links, loads or calls it, and the two share no source.
+//
+// Paper passages followed:
+//   format model F(s,e,t;P,B), subnormals at e=0 ............ Sec. II, Eq. (1)
+//   exponent  e~ = max(floor(log2 x~), 1-B) .................. Sec. II-A, Eq. (2)
+//   scaled significand  s~ = x~ * 2^-e~ * 2^(P-1) ............ Sec. II-A, Eq. (3)
+//   sigma = floor(s~) + 1[R(s~ - floor(s~))] ................. Sec. II-A, Eq. (5)
+//   R_TNE (ties to nearest even) ............................. Sec. II-A
+//   R_SRFF(d,n) = d + n 2^-N >= 1 ............................ Sec. II-B
+//   R_SRF (d,n) = d + (n+1/2) 2^-N >= 1 ...................... Sec. II-B
+//   R_SRC (d,n) = R_SRFF(Round(d 2^N) 2^-N, n) ............... Sec. III-F, Eq. (7)
+//   out-of-range values round deterministically (IEEE RN) .... Sec. II
+//   weight update "w <- RoundTo(w + u), SR applied here" ..... Sec. III, Alg. 1
+//   per-input mean of rounded samples, bias in target ulps ... Fig. 1, Fig. 2, Sec. III
+//
+// Readings taken where the paper is silent (each is also listed in the design notes):
+//   * negative inputs: |x| is rounded and the sign re-applied (the paper rounds x~ > 0);
+//   * NaN -> the target's canonical quiet NaN with x's sign; +-0 -> +-0;
+//   * |x| > M: bf16 / E5M2 round to nearest on the unbounded-exponent grid
+//     (below M + ulp(M)/2 -> M, otherwise -> inf; the tie goes to inf because
+//     M's significand is odd); E4M3 has no infinity and saturates to +-M;
+//   * SRC's inner Round is round-to-nearest, ties to even;
+//   * the N random bits of element i are a slice of a Philox4x32-10 block
+//     (Salmon et al., SC'11) -- the paper leaves the generator open; the
+//     slicing convention is this build's and is restated in random_bits().
+//
+// Parity pins (tests/test_oracle_*.py): bracketing neighbours, identity on
+// representable inputs, N >= D gives exact SR, exhaustive expectations over all
+// 2^N draws, the closed-form biases of Sec. III / App. A, Fig. 1's -0.124 and
+// Fig. 2's printed biases, RNE against a library cast, Philox known answers.
+// Unpinned by anything outside this build: which slice of which Philox block an
+// element receives (a convention; the paper fixes no generator).
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <thread>
+#include <vector>
+
+namespace {
+
+// ---------------------------------------------------------------- formats ---
+// (K, P, B; M) of Sec. II.  has_inf: the format encodes infinities.
+struct Format {
+  int K;         // width in bits
+  int P;         // precision (one more than the stored trailing bits)
+  int B;         // exponent bias
+  double M;      // largest finite value
+  bool has_inf;  // e = all-ones, t = 0 is +-inf
+  uint32_t nan_code;  // canonical quiet NaN, sign bit clear
+  uint32_t inf_code;  // +inf (unused when !has_inf)
+};
+
+enum { FMT_BF16 = 0, FMT_E4M3 = 1, FMT_E5M2 = 2 };
+enum { VAR_RNE = 0, VAR_SRFF = 1, VAR_SRF = 2, VAR_SRC = 3 };
+
+bool get_format(int fmt, Format* f) {
+  switch (fmt) {
+    case FMT_BF16:  // (2 - 2^-7) * 2^127
+      *f = Format{16, 8, 127, std::ldexp(2.0 - std::ldexp(1.0, -7), 127), true, 0x7FC0u, 0x7F80u};
+      return true;
+    case FMT_E4M3:  // OCP E4M3: finite-only, S.1111.111 is NaN, max 1.75 * 2^8
+      *f = Format{8, 4, 7, 448.0, false, 0x7Fu, 0u};
+      return true;
+    case FMT_E5M2:  // OCP E5M2: IEEE-like, max 1.75 * 2^15
+      *f = Format{8, 3, 15, 57344.0, true, 0x7Eu, 0x7Cu};
+      return true;
+  }
+  return false;
+}
+
+// Eq. (1): the real value of (s,e,t); specials per format.
+double decode(uint32_t code, const Format& f) {
+  const int tbits = f.P - 1;
+  const uint32_t s = (code >> (f.K - 1)) & 1u;
+  const uint32_t e = (code >> tbits) & ((1u << (f.K - 1 - tbits)) - 1u);
+  const uint32_t t = code & ((1u << tbits) - 1u);
+  const uint32_t emax = (1u << (f.K - 1 - tbits)) - 1u;
+  const double sign = s ? -1.0 : 1.0;
+  if (f.has_inf && e == emax) {
+    if (t == 0) return sign * std::numeric_limits<double>::infinity();
+    return std::numeric_limits<double>::quiet_NaN();
+  }
+  if (!f.has_inf && (code & ((1u << (f.K - 1)) - 1u)) == f.nan_code)
+    return std::numeric_limits<double>::quiet_NaN();
+  if (e == 0) return sign * std::ldexp((double)t, 1 - f.P) * std::ldexp(1.0, 1 - f.B);
+  return sign * (1.0 + std::ldexp((double)t, 1 - f.P)) * std::ldexp(1.0, (int)e - f.B);
+}
+
+// Encode the non-negative finite value sigma * 2^(et - P + 1), sigma an integer in
+// [0, 2^P], et >= 1 - B, value <= M  (Sec. II-A: the trailing bits of sigma are
+// stored, the exponent is incremented when sigma = 2^P).
+uint32_t encode_magnitude(int64_t sigma, int et, const Format& f) {
+  if (sigma == ((int64_t)1 << f.P)) {
+    sigma = (int64_t)1 << (f.P - 1);
+    et += 1;
+  }
+  uint32_t e, t;
+  if (sigma < ((int64_t)1 << (f.P - 1))) {  // subnormal (only when et == 1 - B) or zero
+    e = 0;
+    t = (uint32_t)sigma;
+  } else {
+    e = (uint32_t)(et + f.B);
+    t = (uint32_t)(sigma - ((int64_t)1 << (f.P - 1)));
+  }
+  return (e << (f.P - 1)) | t;
+}
+
+// Eq. (2): e~ = max(floor(log2 a), 1 - B) for finite a > 0; a = 0 takes the floor 1 - B.
+int rounding_exponent(double a, const Format& f) {
+  if (a == 0.0) return 1 - f.B;
+  const int lg = std::ilogb(a);  // exact floor(log2 a) for finite positive a
+  return lg > 1 - f.B ? lg : 1 - f.B;
+}
+
+// ------------------------------------------------------------- predicates ---
+// All comparisons are in a form whose two sides are exactly representable:
+// delta has at most 24 + (tiny-exponent shift) significant bits but only ever
+// appears alone on one side; the other side is a dyadic with <= 26 bits.
+bool round_up(int variant, double fl, double delta, int N, uint64_t n) {
+  switch (variant) {
+    case VAR_RNE:  // R_TNE: delta > 1/2, or a tie and floor+1 is even
+      return delta > 0.5 || (delta == 0.5 && std::fmod(fl, 2.0) == 1.0);
+    case VAR_SRFF:  // delta + n 2^-N >= 1
+      return delta >= 1.0 - std::ldexp((double)n, -N);
+    case VAR_SRF:  // delta + (n + 1/2) 2^-N >= 1
+      return delta >= 1.0 - std::ldexp((double)(2 * n + 1), -(N + 1));
+    case VAR_SRC: {  // SRFF applied to Round(delta 2^N) 2^-N, Round = RN ties-to-even
+      const double h = std::nearbyint(std::ldexp(delta, N));  // default FE_TONEAREST
+      return h + (double)n >= std::ldexp(1.0, N);
+    }
+  }
+  return false;
+}
+
+// One element: fp32 value -> code of the target format, given the integer n < 2^N.
+uint32_t round_one(float xf, const Format& f, int variant, int N, uint64_t n) {
+  const uint32_t sign_code = (std::signbit(xf) ? 1u : 0u) << (f.K - 1);
+  if (std::isnan(xf)) return sign_code | f.nan_code;
+  const double a = std::fabs((double)xf);
+  if (a == 0.0) return sign_code;
+  if (a > f.M) {  // outside the finite range: deterministic
+    const int eM = std::ilogb(f.M);
+    const uint32_t m_code = encode_magnitude((int64_t)std::ldexp(f.M, -eM + f.P - 1), eM, f);  // M is on the grid
+    if (!f.has_inf) return sign_code | m_code;  // saturating format
+    const double half_ulp_M = std::ldexp(1.0, eM - f.P + 1) / 2.0;
+    return sign_code | (a < f.M + half_ulp_M ? m_code : f.inf_code);
+  }
+  const int et = rounding_exponent(a, f);                   // Eq. (2)
+  const double sig = std::ldexp(a, -et + f.P - 1);          // Eq. (3), exact
+  const double fl = std::floor(sig);
+  const double delta = sig - fl;                            // exact
+  const int64_t sigma = (int64_t)fl + (round_up(variant, fl, delta, N, n) ? 1 : 0);  // Eq. (5)
+  return sign_code | encode_magnitude(sigma, et, f);
+}
+
+// ----------------------------------------------------------------- Philox ---
+// Philox4x32-10 as published (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of
+//   (c0,c1,c2,c3) <- (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1, lo(M0 c0))
+// with the key bumped by the Weyl constants between rounds.
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  const uint64_t M0 = 0xD2511F53ull, M1 = 0xCD9E8D57ull;
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    const uint64_t p0 = M0 * c0;
+    const uint64_t p1 = M1 * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Slot width: the smallest power of two >= N (1, 2, 4, 8, 16 or 32).
+int slot_width(int N) {
+  int W = 1;
+  while (W < N) W *= 2;
+  return W;
+}
+
+// This build's convention for "the N random bits of element i" (global index
+// i, stream selected by (seed, step)):  a Philox block is 128 bits, words
+// out[0..3] little-endian (out[0] holds bits 0..31); it is cut into 128/W
+// slots of W bits; element i uses slot i mod (128/W) of block floor(i / (128/W));
+// n is the low N bits of its slot.  Counter = (block lo, block hi, step lo,
+// step hi), key = (seed lo, seed hi).
+uint64_t random_bits(uint64_t seed, uint64_t step, uint64_t i, int N) {
+  const int W = slot_width(N);
+  const uint64_t per_block = 128u / (unsigned)W;
+  const uint64_t blk = i / per_block;
+  const unsigned slot = (unsigned)(i % per_block);
+  const uint32_t ctr[4] = {(uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step, (uint32_t)(step >> 32)};
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t r[4];
+  philox4x32_10(ctr, key, r);
+  const unsigned bit = slot * (unsigned)W;
+  const uint64_t word = r[bit / 32];
+  const uint64_t mask = (N >= 64) ? ~0ull : ((1ull << N) - 1ull);
+  return (word >> (bit % 32)) & mask;
+}
+
+float bf16_to_float(uint16_t w) {
+  const uint32_t bits = (uint32_t)w << 16;
+  float f;
+  std::memcpy(&f, &bits, 4);
+  return f;
+}
+
+void store_code(void* out, uint64_t j, uint32_t code, const Format& f) {
+  if (f.K == 16) ((uint16_t*)out)[j] = (uint16_t)code;
+  else ((uint8_t*)out)[j] = (uint8_t)code;
+}
+
+bool args_ok(int fmt, int variant, int nbits, Format* f) {
+  if (!get_format(fmt, f)) return false;
+  if (variant < VAR_RNE || variant > VAR_SRC) return false;
+  if (variant != VAR_RNE && (nbits < 1 || nbits > 32)) return false;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Philox known-answer access.
+void oracle_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
+  philox4x32_10(ctr, key, out);
+}
+
+// The N-bit integer element `index` draws from stream (seed, step).
+uint64_t oracle_random_bits(uint64_t seed, uint64_t step, uint64_t index, int nbits) {
+  return random_bits(seed, step, index, nbits);
+}
+
+// One element with an explicit n (for exhaustive enumeration over all 2^N draws).
+// Returns the code, or 0xFFFFFFFF on invalid arguments.
+uint32_t oracle_round_with_n(float x, int fmt, int variant, int nbits, uint64_t n) {
+  Format f;
+  if (!args_ok(fmt, variant, nbits, &f)) return 0xFFFFFFFFu;
+  return round_one(x, f, variant, nbits, n);
+}
+
+// Eq. (1) value of a code (NaN / inf per format).
+double oracle_decode(uint32_t code, int fmt) {
+  Format f;
+  if (!get_format(fmt, &f)) return std::numeric_limits<double>::quiet_NaN();
+  return decode(code, f);
+}
+
+// Target ulp at x: 2^(e~ - P + 1) with e~ of Eq. (2); 1.0 for non-finite x.
+double oracle_ulp(float x, int fmt) {
+  Format f;
+  if (!get_format(fmt, &f)) return std::numeric_limits<double>::quiet_NaN();
+  const double a = std::fabs((double)x);
+  if (!std::isfinite(a)) return 1.0;
+  return std::ldexp(1.0, rounding_exponent(a, f) - f.P + 1);
+}
+
+// For each x[k]: the number of draws n in [0, 2^N) whose result differs from the draw-free
+// round-down code (i.e. how many draws round away from zero).  Plain enumeration, used by the
+// exhaustive-expectation pins.
+int oracle_count_up(const float* x, uint64_t count, int fmt, int variant, int nbits, uint64_t* ups) {
+  Format f;
+  if (!args_ok(fmt, variant, nbits, &f) || variant == VAR_RNE || nbits > 24) return 1;
+  for (uint64_t k = 0; k < count; ++k) {
+    // n = 0 under SRFF never rounds a non-representable value up (delta < 1): the floor code.
+    const uint32_t down = round_one(x[k], f, VAR_SRFF, nbits, 0);
+    uint64_t c = 0;
+    for (uint64_t n = 0; n < (1ull << nbits); ++n)
+      if (round_one(x[k], f, variant, nbits, n) != down) ++c;
+    ups[k] = c;
+  }
+  return 0;
+}
+
+// out[j] = FBSR(x[j]) with the bits of global element offset + j, stream (seed, 0).
+// out is uint16 codes for bf16, uint8 codes for the fp8 formats.  0 = ok.
+int oracle_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits,
+                 uint64_t seed, uint64_t offset) {
+  Format f;
+  if (!args_ok(fmt, variant, nbits, &f)) return 1;
+  for (uint64_t j = 0; j < n; ++j) {
+    const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, 0, offset + j, nbits);
+    store_code(out, j, round_one(x[j], f, variant, nbits, r), f);
+  }
+  return 0;
+}
+
+// The same, cut into `nthreads` contiguous index ranges (legal because the bits of an
+// element depend only on its global index).  Used by the benchmark's CPU-baseline leg.
+int oracle_round_threads(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits,
+                         uint64_t seed, uint64_t offset, int nthreads) {
+  Format f;
+  if (!args_ok(fmt, variant, nbits, &f) || nthreads < 1) return 1;
+  std::vector<std::thread> pool;
+  const uint64_t per = (n + (uint64_t)nthreads - 1) / (uint64_t)nthreads;
+  const uint64_t osize = f.K / 8;
+  for (int t = 0; t < nthreads; ++t) {
+    const uint64_t lo = per * (uint64_t)t;
+    if (lo >= n) break;
+    const uint64_t cnt = (lo + per <= n) ? per : n - lo;
+    pool.emplace_back([=]() {
+      oracle_round(x + lo, (char*)out + lo * osize, cnt, fmt, variant, nbits, seed, offset + lo);
+    });
+  }
+  for (auto& th : pool) th.join();
+  return 0;
+}
+
+// Alg. 1's "w <- RoundTo(w + u)" in the SGD form u = -lr * g: the bf16 weight is
+// widened exactly, the update is one fused multiply-add in fp32 (a single rounding),
+// and the fp32 result is rounded back to bf16 with the bits of (seed, step, offset + j).
+int oracle_sgd_update(uint16_t* w, const float* g, uint64_t n, float lr, int variant, int nbits,
+                      uint64_t seed, uint64_t step, uint64_t offset) {
+  Format f;
+  if (!args_ok(FMT_BF16, variant, nbits, &f)) return 1;
+  for (uint64_t j = 0; j < n; ++j) {
+    const float x = std::fmaf(-lr, g[j], bf16_to_float(w[j]));
+    const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, step, offset + j, nbits);
+    w[j] = (uint16_t)round_one(x, f, variant, nbits, r);
+  }
+  return 0;
+}
+
+// Per-bin statistics of the rounding error (the reduction behind Figs. 1 and 2: the mean of
+// the rounded samples per input bin, and the bias = mean of (rounded - input) in target
+// ulps).  Element j has global index i = offset + j and bin floor(i / group) - first_bin.
+// stats is nbins x 4 doubles {count, sum y, sum e, sum e^2}, ACCUMULATED into, where
+// y = decoded rounded value and e = (y - x) / ulp_t(x), ulp_t(x) = 2^(e~ - P + 1).
+// Non-finite y or x propagate through the sums by IEEE rules.  out may be null.
+// Returns 0 ok, 1 bad arguments, 3 an element falls outside [0, nbins).
+int oracle_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits,
+                      uint64_t seed, uint64_t offset, uint64_t group, uint64_t first_bin,
+                      uint32_t nbins, double* stats) {
+  Format f;
+  if (!args_ok(fmt, variant, nbits, &f) || group == 0) return 1;
+  if (n > 0) {
+    const uint64_t lo = offset / group, hi = (offset + n - 1) / group;
+    if (lo < first_bin || hi - first_bin >= nbins) return 3;
+  }
+  for (uint64_t j = 0; j < n; ++j) {
+    const uint64_t i = offset + j;
+    const uint64_t bin = i / group - first_bin;
+    const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, 0, i, nbits);
+    const uint32_t code = round_one(x[j], f, variant, nbits, r);
+    if (out) store_code(out, j, code, f);
+    const double y = decode(code, f);
+    const double e = (y - (double)x[j]) / oracle_ulp(x[j], fmt);
+    double* s = stats + 4 * bin;
+    s[0] += 1.0;
+    s[1] += y;
+    s[2] += e;
+    s[3] += e * e;
+  }
+  return 0;
+}
+
+}  // extern "C"

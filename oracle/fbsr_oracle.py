@@ -1,0 +1,148 @@
+"""ctypes access to the CPU oracle (oracle/fbsr_oracle.cpp).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+module.  It never imports the GPU package, and the GPU package never imports it.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+SOURCE = os.path.join(_HERE, "fbsr_oracle.cpp")
+LIB = os.path.join(_HERE, "liboracle_fbsr.so")
+
+FMT_BF16, FMT_E4M3, FMT_E5M2 = 0, 1, 2
+RNE, SRFF, SRF, SRC = 0, 1, 2, 3
+FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
+VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
+
+
+def build(force=False):
+    """Compile the oracle with the host compiler (no contraction: the SGD step's single
+    fused multiply-add must stay the only fused operation)."""
+    if force or not os.path.exists(LIB) or os.path.getmtime(LIB) < os.path.getmtime(SOURCE):
+        subprocess.check_call(
+            ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fPIC", "-shared", "-pthread",
+             "-o", LIB, SOURCE])
+    return LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        u64, u32, i32, f32, f64 = (ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int,
+                                   ctypes.c_float, ctypes.c_double)
+        vp = ctypes.c_void_p
+        L.oracle_philox4x32_10.argtypes = [vp, vp, vp]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_random_bits.argtypes = [u64, u64, u64, i32]
+        L.oracle_random_bits.restype = u64
+        L.oracle_round_with_n.argtypes = [f32, i32, i32, i32, u64]
+        L.oracle_round_with_n.restype = u32
+        L.oracle_decode.argtypes = [u32, i32]
+        L.oracle_decode.restype = f64
+        L.oracle_ulp.argtypes = [f32, i32]
+        L.oracle_ulp.restype = f64
+        L.oracle_count_up.argtypes = [vp, u64, i32, i32, i32, vp]
+        L.oracle_count_up.restype = i32
+        L.oracle_round.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64]
+        L.oracle_round.restype = i32
+        L.oracle_round_threads.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, i32]
+        L.oracle_round_threads.restype = i32
+        L.oracle_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64]
+        L.oracle_sgd_update.restype = i32
+        L.oracle_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp]
+        L.oracle_bias_stats.restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def code_dtype(fmt):
+    return np.uint16 if fmt == FMT_BF16 else np.uint8
+
+
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def random_bits(seed, step, index, nbits):
+    return int(lib().oracle_random_bits(seed, step, index, nbits))
+
+
+def round_with_n(x, fmt, variant, nbits, n):
+    code = lib().oracle_round_with_n(float(np.float32(x)), fmt, variant, nbits, n)
+    if code == 0xFFFFFFFF:
+        raise ValueError("oracle_round_with_n: bad arguments")
+    return int(code)
+
+
+def decode(code, fmt):
+    return float(lib().oracle_decode(int(code), fmt))
+
+
+def ulp(x, fmt):
+    return float(lib().oracle_ulp(float(np.float32(x)), fmt))
+
+
+def count_up(x, fmt, variant, nbits):
+    """For each x: how many of the 2^nbits draws round it away from zero."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    ups = np.zeros(x.size, dtype=np.uint64)
+    rc = lib().oracle_count_up(_ptr(x), x.size, fmt, variant, nbits, _ptr(ups))
+    if rc != 0:
+        raise ValueError("oracle_count_up: status %d" % rc)
+    return ups
+
+
+def round_(x, fmt, variant, nbits, seed, offset=0, nthreads=1):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.size, dtype=code_dtype(fmt))
+    if nthreads > 1:
+        rc = lib().oracle_round_threads(_ptr(x), _ptr(out), x.size, fmt, variant, nbits, seed,
+                                        offset, nthreads)
+    else:
+        rc = lib().oracle_round(_ptr(x), _ptr(out), x.size, fmt, variant, nbits, seed, offset)
+    if rc != 0:
+        raise ValueError("oracle_round: status %d" % rc)
+    return out
+
+
+def sgd_update(w, g, lr, variant, nbits, seed, step, offset=0):
+    """Returns the updated bf16 codes (the input array is not modified)."""
+    w = np.array(w, dtype=np.uint16, copy=True)
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    assert w.size == g.size
+    rc = lib().oracle_sgd_update(_ptr(w), _ptr(g), w.size, float(np.float32(lr)), variant, nbits,
+                                 seed, step, offset)
+    if rc != 0:
+        raise ValueError("oracle_sgd_update: status %d" % rc)
+    return w
+
+
+def bias_stats(x, fmt, variant, nbits, seed, offset, group, first_bin, nbins, stats=None,
+               want_out=False):
+    """Returns (stats[nbins,4], out or None); accumulates into `stats` when given."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if stats is None:
+        stats = np.zeros((nbins, 4), dtype=np.float64)
+    assert stats.dtype == np.float64 and stats.shape == (nbins, 4) and stats.flags.c_contiguous
+    out = np.empty(x.size, dtype=code_dtype(fmt)) if want_out else None
+    rc = lib().oracle_bias_stats(_ptr(x), _ptr(out) if want_out else None, x.size, fmt, variant,
+                                 nbits, seed, offset, group, first_bin, nbins, _ptr(stats))
+    if rc != 0:
+        raise ValueError("oracle_bias_stats: status %d" % rc)
+    return stats, out
