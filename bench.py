@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the FBSR hot path on one MI355X.
+
+Headline metric: fp32 -> fp8 few-bit stochastic rounding throughput (elements/s) and achieved
+HBM GB/s against the 8 TB/s peak, at N = 2, 4, 8 random bits, on 2^28 full-range elements
+(the benchmark's third workload, the size the 70 %-of-peak target is quoted on).
+
+One "step" = one pass over the batch for every (format, N, variant) of the headline sweep:
+{E4M3, E5M2} x {2, 4, 8} x {SRFF, SRF, SRC} = 18 fbsr_round launches of 2^28 elements each, all
+through the C ABI.  Inputs are resident in HBM before the timed region starts.  The other paths
+(bf16 rounding, fused SGD update, bias statistics, and the RNE launch that serves as a
+streaming ceiling) are timed separately and reported under "paths".
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+N_ELEMS = 1 << 28
+SGD_ELEMS = 1 << 27
+HEADLINE_NBITS = (2, 4, 8)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--elems-log2", type=int, default=28, help="log2 of the batch size (default 28)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-paths", action="store_true", help="skip the secondary paths (profiling runs)")
+    return ap.parse_args()
+
+
+def timed_launches(torch, fn, reps, warm=2):
+    """Average duration (ms) of fn()'s GPU work over `reps` launches, from events recorded on
+    the stream the kernels are launched on (torch's current stream)."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in evs) / reps
+
+
+def cpu_baseline(x_host, fmts, variants, threads):
+    """The oracle as it stands, timed on the host cores over a bounded sample of the same
+    workload: the first 2^24 elements, every (format, N, variant) of the headline sweep."""
+    from oracle import fbsr_oracle as oracle
+    sample = 1 << 24
+    done = 0
+    t0 = time.perf_counter()
+    for fmt in fmts:
+        xs = x_host[fmt][:sample]
+        for nbits in HEADLINE_NBITS:
+            for variant in variants:
+                oracle.round_(xs, fmt, variant, nbits, seed=2, offset=0, nthreads=threads)
+                done += xs.size
+    dt = time.perf_counter() - t0
+    return {"value": done / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+            "sample": "first 2^24 elements of the same inputs x 18 (format, N, variant) launches, "
+                      "oracle_round_threads with %d threads, %.1f s wall" % (threads, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards without communication, but no "
+              "multi-GPU run is part of it); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2504_20634_amd as fbsr
+    from paper_2504_20634_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    fbsr.binding.lib()
+    n = 1 << args.elems_log2
+    fmts = (fbsr.FMT_E4M3, fbsr.FMT_E5M2)
+    variants = (fbsr.SRFF, fbsr.SRF, fbsr.SRC)
+    target = {fbsr.FMT_E4M3: "e4m3", fbsr.FMT_E5M2: "e5m2", fbsr.FMT_BF16: "bf16"}
+
+    x_host = {f: workloads.full_range(n, target[f], seed=2) for f in fmts}
+    x_dev = {f: torch.from_numpy(x_host[f]).cuda() for f in fmts}
+    out8 = torch.empty(n, dtype=torch.uint8, device="cuda")
+    sweep = [(f, nb, v) for f in fmts for nb in HEADLINE_NBITS for v in variants]
+
+    def launch(f, nb, v):
+        fbsr.fbsr_round(x_dev[f], f, v, nb, seed=2, offset=0, out=out8)
+
+    def step():
+        for f, nb, v in sweep:
+            launch(f, nb, v)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # per-launch events inside the timed region give the kernels' own durations
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in sweep]
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        for i, (f, nb, v) in enumerate(sweep):
+            evs[k][i][0].record()
+            launch(f, nb, v)
+            evs[k][i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    value = len(sweep) * n * args.steps / wall
+
+    per = {}
+    for i, (f, nb, v) in enumerate(sweep):
+        ms = sum(evs[k][i][0].elapsed_time(evs[k][i][1]) for k in range(args.steps)) / args.steps
+        per["%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
+            "ms": round(ms, 4), "gelem_s": round(n / ms / 1e6, 2), "gb_s": round(5.0 * n / ms / 1e6, 1)}
+    avg_ms = sum(p["ms"] for p in per.values()) / len(per)
+    achieved = 5.0 * n / (avg_ms * 1e-3) / 1e9
+    by_n = {"N%d" % nb: round(sum(5.0 * n / p["ms"] / 1e6 for k, p in per.items() if "_N%d_" % nb in k) /
+                              sum(1 for k in per if "_N%d_" % nb in k), 1) for nb in HEADLINE_NBITS}
+
+    paths = {}
+    if not args.no_paths:
+        # streaming ceiling: the RNE launch draws no random bits (same 4:1 read:write byte mix)
+        ms = timed_launches(torch, lambda: fbsr.fbsr_round(x_dev[fbsr.FMT_E4M3], fbsr.FMT_E4M3, fbsr.RNE, 0, 2, 0, out=out8), 10)
+        paths["round_e4m3_rne_ceiling"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1)}
+        out16 = torch.empty(n, dtype=torch.uint16, device="cuda")
+        for nb in (4, 8, 16):
+            ms = timed_launches(torch, lambda: fbsr.fbsr_round(x_dev[fbsr.FMT_E5M2], fbsr.FMT_BF16, fbsr.SRF, nb, 2, 0, out=out16), 10)
+            paths["round_bf16_N%d_srf" % nb] = {"ms": round(ms, 4), "gb_s": round(6.0 * n / ms / 1e6, 1)}
+        del out16
+        ns = min(SGD_ELEMS, n)
+        w = torch.from_numpy(workloads.sgd_weights(ns, seed=3).view(np.int16)).cuda()
+        g = torch.from_numpy(workloads.sgd_grads(ns, 0, seed=3)).cuda()
+        step_no = [0]
+
+        def sgd(nb):
+            fbsr.fbsr_sgd_update(w, g, 1e-3, fbsr.SRF, nb, seed=4, step=step_no[0])
+            step_no[0] += 1
+        for nb in (2, 4, 8):
+            ms = timed_launches(torch, lambda: sgd(nb), 10)
+            paths["sgd_update_bf16_N%d_srf" % nb] = {"ms": round(ms, 4), "gb_s": round(8.0 * ns / ms / 1e6, 1)}
+        del w, g
+        group = 1 << 18
+        nbins = n // group
+        ws = torch.empty(fbsr.bias_stats_workspace_bytes(n, nbins) // 8 + 1, dtype=torch.float64, device="cuda")
+        stats = torch.zeros((nbins, 4), dtype=torch.float64, device="cuda")
+        for f, nb in ((fbsr.FMT_E4M3, 3), (fbsr.FMT_BF16, 8)):
+            xin = x_dev[fbsr.FMT_E4M3]
+            ms = timed_launches(torch, lambda: fbsr.fbsr_bias_stats(xin, f, fbsr.SRF, nb, 5, 0, group, 0, nbins,
+                                                                    stats=stats, workspace=ws), 5)
+            paths["bias_stats_%s_N%d_srf" % (target[f], nb)] = {"ms": round(ms, 4), "gb_s": round(4.0 * n / ms / 1e6, 1)}
+
+    result = {
+        "metric": "FBSR fp32->fp8 elements/s (achieved HBM GB/s and fraction of peak under roofline), N=2,4,8",
+        "value": value,
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": "full-range fp32 (random sign, exponent uniform over the target's range incl. "
+                               "subnormals and overflow, random mantissa), 2^%d elements, seed 2; "
+                               "step = {e4m3,e5m2} x N{2,4,8} x {srff,srf,src} = 18 launches" % args.elems_log2,
+                   "elements": n, "launches_per_step": len(sweep)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "round_tiles<fmt,variant,W> (average over the 18 launches of a step)",
+                     "bytes_per_launch": 5 * n, "avg_launch_ms": avg_ms, "gb_s_by_nbits": by_n},
+        "per_launch": per,
+        "paths": paths,
+    }
+    if not args.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        result["cpu_baseline"] = cpu_baseline(x_host, fmts, variants, threads)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,119 @@
+/* fbsr.h -- few-bit stochastic rounding (FBSR) on AMD MI355X (gfx950), C ABI.
+ *
+ * Implements the elementwise hot path of "On Stochastic Rounding with Few Random Bits"
+ * (arXiv 2504.20634): fp32 values are rounded to a narrower binary format using only
+ * N random bits per element.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library allocates and
+ *     frees nothing, enqueues its kernels on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and returns without synchronising.
+ *   - The return value is an fbsr_status; nothing throws or aborts.  Argument errors are
+ *     detected on the host before anything is launched (so they can be tested without a GPU).
+ *   - n == 0 is FBSR_OK and launches nothing.
+ *   - Results are a pure function of the arguments: the random bits of an element depend only
+ *     on (seed, step, global element index), so repeating a call, or cutting it into chunks
+ *     whose `offset` continues the index, gives identical bytes.
+ *   - Random bits (the paper leaves the source open, Sec. II-B): Philox4x32-10 with
+ *     key = (seed lo, seed hi) and counter = (block lo, block hi, step lo, step hi).  With
+ *     W = the smallest power of two >= nbits, a 128-bit block (word 0 = bits 0..31) is cut
+ *     into 128/W slots; element i uses the low nbits bits of slot i mod (128/W) of block
+ *     floor(i / (128/W)).  So one block serves 128/W elements.
+ *   - Formats follow the (K, P, B; M) model of Sec. II, Eq. (1); codes are the packed
+ *     sign | exponent | trailing-significand bits.
+ *   - Alignment: x / g need 4-byte, bf16 codes 2-byte alignment (else FBSR_EALIGN).  The
+ *     vectorised kernels are used when x is 16-byte aligned at the first element whose
+ *     global index is a multiple of 128/W and the output is aligned accordingly; otherwise,
+ *     and for ragged heads and tails, a slower per-element kernel gives the same bytes.
+ */
+#ifndef FBSR_H
+#define FBSR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Target formats (Sec. II).  Codes are uint16 for BF16, uint8 for the fp8 formats. */
+typedef enum {
+  FBSR_FMT_BF16 = 0, /* K=16 P=8 B=127, M=(2-2^-7)*2^127, has infinities               */
+  FBSR_FMT_E4M3 = 1, /* OCP E4M3: K=8 P=4 B=7, M=448, no infinities, S.1111.111 is NaN  */
+  FBSR_FMT_E5M2 = 2  /* OCP E5M2: K=8 P=3 B=15, M=57344, has infinities                 */
+} fbsr_fmt;
+
+/* Rounding predicates (delta = fractional part of the scaled significand, Sec. II-A Eq. (5);
+ * n = the element's nbits-bit random integer; N = nbits).                                    */
+typedef enum {
+  FBSR_RNE = 0,  /* round to nearest, ties to even (Sec. II-A); nbits ignored, no random bits */
+  FBSR_SRFF = 1, /* delta + n 2^-N >= 1             (Sec. II-B; biased by -2^-(N+1) ulp)      */
+  FBSR_SRF = 2,  /* delta + (n + 1/2) 2^-N >= 1     (Sec. II-B)                               */
+  FBSR_SRC = 3   /* SRFF on Round(delta 2^N) 2^-N, Round = nearest, ties to even (Eq. (7))    */
+} fbsr_variant;
+
+typedef enum {
+  FBSR_OK = 0,
+  FBSR_EINVAL = 1,  /* bad enum, nbits outside [1, FBSR_MAX_NBITS], null pointer, group == 0, ... */
+  FBSR_EALIGN = 2,  /* a pointer is not aligned to its element type                              */
+  FBSR_ERANGE = 3,  /* an element would fall outside the caller's bins / workspace too small     */
+  FBSR_EDEVICE = 4  /* the HIP runtime reported an error at launch                               */
+} fbsr_status;
+
+#define FBSR_MAX_NBITS 16
+
+/* Rounds n fp32 values to `fmt`:  out[j] = FBSR(x[j]; bits of global element offset + j,
+ * stream (seed, step = 0)).
+ *   Sign-magnitude: |x| is rounded and the sign re-applied (the paper rounds positive values),
+ *   so "up" is away from zero.  +-0 -> +-0.  NaN -> canonical quiet NaN with x's sign
+ *   (bf16 0x7FC0, E5M2 0x7E, E4M3 0x7F).  |x| > M is rounded deterministically (Sec. II):
+ *   bf16 / E5M2 to M below M + ulp(M)/2 and to infinity from there on, E4M3 saturates to +-M.
+ *   Target subnormals are rounded on the subnormal grid (Eq. (2): the exponent is clamped at
+ *   1 - B); fp32 subnormal inputs are ordinary values.
+ * x: n floats (device, read).  out: n codes (device, written; must not overlap x).
+ * Errors: FBSR_EINVAL (bad fmt / variant / nbits, null pointer with n > 0), FBSR_EALIGN,
+ * FBSR_EDEVICE. */
+int fbsr_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits,
+               uint64_t seed, uint64_t offset, void* stream);
+
+/* The weight update of Alg. 1 ("w <- RoundTo(w + u), SR applied here") fused into one pass,
+ * in SGD form:  w[j] <- FBSR_bf16( fma(-lr, g[j], float(w[j])) )  with the bits of
+ * (seed, step, offset + j).  The fma is a single-rounding fp32 fused multiply-add with IEEE
+ * subnormals.
+ * w: n bf16 codes (device, updated in place).  g: n floats (device, read).
+ * Errors as fbsr_round. */
+int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, int nbits,
+                    uint64_t seed, uint64_t step, uint64_t offset, void* stream);
+
+/* Rounds as fbsr_round and reduces the rounding error per bin -- the measurement behind
+ * Figs. 1 and 2 (mean of the rounded samples per input value; bias = mean of rounded minus
+ * input, Sec. III).  Element j has global index i = offset + j and bin
+ * floor(i / group) - first_bin, which must lie in [0, nbins) for every element
+ * (else FBSR_ERANGE).
+ * stats: nbins x 4 doubles {count, sum y, sum e, sum e^2} (device), ACCUMULATED into (the
+ *   caller zeroes them), where y is the decoded rounded value and e = (y - x) / ulp_t(x) with
+ *   ulp_t(x) = 2^(e~ - P + 1), e~ = max(floor(log2 |x|), 1 - B) (Eq. (2)), all in fp64.
+ *   Non-finite x or y propagate through the sums by IEEE rules.  The summation order is fixed,
+ *   so repeated calls give identical bits.
+ * out: n codes as in fbsr_round, or NULL to skip writing them.
+ * workspace: device scratch of at least fbsr_bias_stats_workspace_bytes(n, nbins) bytes,
+ *   8-byte aligned, contents irrelevant before and after (else FBSR_ERANGE / FBSR_EALIGN).
+ * Two calls that accumulate into the same stats must be ordered on the stream. */
+int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits,
+                    uint64_t seed, uint64_t offset, uint64_t group, uint64_t first_bin,
+                    uint32_t nbins, double* stats, void* workspace, uint64_t workspace_bytes,
+                    void* stream);
+
+/* Bytes of workspace fbsr_bias_stats needs for n elements (never 0; independent of nbins
+ * today, kept in the signature for layouts that are not). */
+uint64_t fbsr_bias_stats_workspace_bytes(uint64_t n, uint32_t nbins);
+
+/* Static description of a status code. */
+const char* fbsr_strerror(int status);
+
+/* Library version, major * 100 + minor. */
+int fbsr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FBSR_H */

@@ -1,0 +1,130 @@
+"""ctypes binding of the C ABI in include/fbsr.h.  Argument marshalling only: every step of
+the computation runs in the library's HIP kernels.  Tensors are torch tensors on the GPU
+(torch is used for device memory and streams, nothing else).
+
+The binding loads the in-tree libfbsr.so and raises if it is missing: there is no fallback.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfbsr.so")
+
+FMT_BF16, FMT_E4M3, FMT_E5M2 = 0, 1, 2
+RNE, SRFF, SRF, SRC = 0, 1, 2, 3
+OK, EINVAL, EALIGN, ERANGE, EDEVICE = 0, 1, 2, 3, 4
+MAX_NBITS = 16
+FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
+VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
+EXPORTS = ("fbsr_round", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
+           "fbsr_strerror", "fbsr_version")
+
+
+class FbsrError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (what, strerror(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises OSError if libfbsr.so has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise OSError("libfbsr.so is not built: run `python -m paper_2504_20634_amd.build` "
+                          "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        u64, u32, i32, f32, vp = (ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_float,
+                                  ctypes.c_void_p)
+        L.fbsr_round.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, vp]
+        L.fbsr_round.restype = i32
+        L.fbsr_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64, vp]
+        L.fbsr_sgd_update.restype = i32
+        L.fbsr_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp, vp, u64, vp]
+        L.fbsr_bias_stats.restype = i32
+        L.fbsr_bias_stats_workspace_bytes.argtypes = [u64, u32]
+        L.fbsr_bias_stats_workspace_bytes.restype = u64
+        L.fbsr_strerror.argtypes = [i32]
+        L.fbsr_strerror.restype = ctypes.c_char_p
+        L.fbsr_version.argtypes = []
+        L.fbsr_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def strerror(status):
+    return lib().fbsr_strerror(int(status)).decode()
+
+
+def _check(status, what):
+    if status != OK:
+        raise FbsrError(status, what)
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def code_dtype(fmt):
+    import torch
+    return torch.uint16 if fmt == FMT_BF16 else torch.uint8
+
+
+def fbsr_round(x, fmt, variant, nbits, seed, offset=0, out=None, stream=None):
+    """out[j] = FBSR(x[j]) with the random bits of global element offset + j.
+    x: float32 CUDA tensor (contiguous).  Returns the code tensor (uint16 for bf16, uint8 for
+    fp8), allocated with torch unless `out` is given."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    n = x.numel()
+    if out is None:
+        out = torch.empty(n, dtype=code_dtype(fmt), device=x.device)
+    assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.dtype == code_dtype(fmt)
+    _check(lib().fbsr_round(x.data_ptr(), out.data_ptr(), n, fmt, variant, nbits, seed, offset,
+                            _stream_handle(stream)), "fbsr_round")
+    return out
+
+
+def fbsr_sgd_update(w, g, lr, variant, nbits, seed, step, offset=0, stream=None):
+    """In place: w <- FBSR_bf16(fma(-lr, g, float(w))).  w: uint16 / int16 / bfloat16 CUDA tensor
+    holding bf16 codes; g: float32 CUDA tensor of the same length."""
+    import torch
+    assert w.is_cuda and g.is_cuda and w.is_contiguous() and g.is_contiguous()
+    assert w.element_size() == 2 and g.dtype == torch.float32 and w.numel() == g.numel()
+    _check(lib().fbsr_sgd_update(w.data_ptr(), g.data_ptr(), w.numel(), float(lr), variant, nbits,
+                                 seed, step, offset, _stream_handle(stream)), "fbsr_sgd_update")
+    return w
+
+
+def bias_stats_workspace_bytes(n, nbins):
+    return int(lib().fbsr_bias_stats_workspace_bytes(n, nbins))
+
+
+def fbsr_bias_stats(x, fmt, variant, nbits, seed, offset, group, first_bin, nbins, stats=None,
+                    out=None, workspace=None, stream=None):
+    """Accumulates {count, sum y, sum e, sum e^2} per bin into stats[nbins, 4] (float64 CUDA
+    tensor, created zeroed if None).  Returns (stats, out)."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    n = x.numel()
+    if stats is None:
+        stats = torch.zeros((nbins, 4), dtype=torch.float64, device=x.device)
+    assert stats.is_cuda and stats.dtype == torch.float64 and stats.is_contiguous()
+    assert stats.numel() == 4 * nbins
+    need = bias_stats_workspace_bytes(n, nbins)
+    if workspace is None:
+        workspace = torch.empty((need + 7) // 8, dtype=torch.float64, device=x.device)
+    wbytes = workspace.numel() * workspace.element_size()
+    if out is not None:
+        assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.dtype == code_dtype(fmt)
+    _check(lib().fbsr_bias_stats(x.data_ptr(), out.data_ptr() if out is not None else None, n, fmt,
+                                 variant, nbits, seed, offset, group, first_bin, nbins,
+                                 stats.data_ptr(), workspace.data_ptr(), wbytes,
+                                 _stream_handle(stream)), "fbsr_bias_stats")
+    return stats, out

@@ -1,0 +1,89 @@
+// fbsr_api.hip -- the C ABI declared in include/fbsr.h: host-side argument checking and
+// dispatch.  Every check happens before anything is enqueued.
+#include "../../include/fbsr.h"
+#include "fbsr_launch.h"
+
+namespace {
+
+bool valid_fmt(int fmt) { return fmt == FBSR_FMT_BF16 || fmt == FBSR_FMT_E4M3 || fmt == FBSR_FMT_E5M2; }
+
+int check_common(int variant, int nbits, uint64_t n, uint64_t offset) {
+  if (variant < FBSR_RNE || variant > FBSR_SRC) return FBSR_EINVAL;
+  if (variant != FBSR_RNE && (nbits < 1 || nbits > FBSR_MAX_NBITS)) return FBSR_EINVAL;
+  if (n > fbsr::kMaxElems || offset > UINT64_MAX - n) return FBSR_EINVAL;
+  return FBSR_OK;
+}
+
+bool misaligned(const void* p, uintptr_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
+
+uint64_t code_bytes(int fmt) { return fmt == FBSR_FMT_BF16 ? 2 : 1; }
+
+}  // namespace
+
+extern "C" {
+
+int fbsr_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
+               uint64_t offset, void* stream) {
+  if (!valid_fmt(fmt)) return FBSR_EINVAL;
+  const int c = check_common(variant, nbits, n, offset);
+  if (c != FBSR_OK) return c;
+  if (n == 0) return FBSR_OK;
+  if (x == nullptr || out == nullptr) return FBSR_EINVAL;
+  if (misaligned(x, 4) || misaligned(out, code_bytes(fmt))) return FBSR_EALIGN;
+  const hipError_t e = fbsr::launch_round(x, out, n, fmt, variant, nbits, seed, offset,
+                                          reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
+int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, int nbits, uint64_t seed,
+                    uint64_t step, uint64_t offset, void* stream) {
+  const int c = check_common(variant, nbits, n, offset);
+  if (c != FBSR_OK) return c;
+  if (n == 0) return FBSR_OK;
+  if (w == nullptr || g == nullptr) return FBSR_EINVAL;
+  if (misaligned(g, 4) || misaligned(w, 2)) return FBSR_EALIGN;
+  const hipError_t e = fbsr::launch_sgd(w, g, n, lr, variant, nbits, seed, step, offset,
+                                        reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
+uint64_t fbsr_bias_stats_workspace_bytes(uint64_t n, uint32_t nbins) {
+  (void)nbins;
+  // one record per 1024-element tile at most (tiles are 1024 elements or larger)
+  return (n / 1024 + 1) * fbsr::kStatsRecordDoubles * sizeof(double);
+}
+
+int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
+                    uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
+                    void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (!valid_fmt(fmt)) return FBSR_EINVAL;
+  const int c = check_common(variant, nbits, n, offset);
+  if (c != FBSR_OK) return c;
+  if (group == 0 || group > ((uint64_t)1 << 62)) return FBSR_EINVAL;
+  if (n == 0) return FBSR_OK;
+  if (x == nullptr || stats == nullptr || workspace == nullptr) return FBSR_EINVAL;
+  if (misaligned(x, 4) || misaligned(stats, 8) || misaligned(workspace, 8)) return FBSR_EALIGN;
+  if (out != nullptr && misaligned(out, code_bytes(fmt))) return FBSR_EALIGN;
+  const uint64_t bin_lo = offset / group, bin_hi = (offset + n - 1) / group;
+  if (bin_lo < first_bin || bin_hi - first_bin >= nbins) return FBSR_ERANGE;
+  if (workspace_bytes < fbsr_bias_stats_workspace_bytes(n, nbins)) return FBSR_ERANGE;
+  const hipError_t e =
+      fbsr::launch_stats(x, out, n, fmt, variant, nbits, seed, offset, group, first_bin, nbins, stats,
+                         reinterpret_cast<double*>(workspace), reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
+const char* fbsr_strerror(int status) {
+  switch (status) {
+    case FBSR_OK: return "ok";
+    case FBSR_EINVAL: return "invalid argument";
+    case FBSR_EALIGN: return "pointer not aligned to its element type";
+    case FBSR_ERANGE: return "element outside the bins, or workspace too small";
+    case FBSR_EDEVICE: return "HIP runtime error at launch";
+  }
+  return "unknown status";
+}
+
+int fbsr_version(void) { return 100; }
+
+}  // extern "C"

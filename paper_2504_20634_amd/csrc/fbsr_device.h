@@ -1,0 +1,265 @@
+// fbsr_device.h -- device-side building blocks for few-bit stochastic rounding on gfx950.
+//
+// Everything here works on the fp32 BIT PATTERN in a fixed-point "code space":
+// a 32-bit word whose top bits are the target format's magnitude code and whose low FRAC
+// bits are the fraction of one target ulp (the paper's delta, Sec. II-A Eq. (5), scaled by
+// 2^FRAC).  In that space every rounding predicate of the paper is one integer addition
+// followed by dropping the low FRAC bits (the "addition" implementation the paper mentions
+// at the end of Sec. II-A):
+//     SRFF  delta + n 2^-N >= 1            ->  + (n << (FRAC - N))
+//     SRF   delta + (n + 1/2) 2^-N >= 1    ->  + (n << (FRAC - N)) + (1 << (FRAC - N - 1))
+//     SRC   SRFF(RN_even(delta 2^N) 2^-N)  ->  + (2^(FRAC-N-1) - 1) + bit_(FRAC-N)  + (n << (FRAC - N))
+//     RNE   ties to even                   ->  SRC with N = 0, n = 0
+// A carry out of the fraction increments the significand and, when that overflows, the
+// exponent (Sec. II-A: "incrementing the exponent if sigma = 2^P") with no extra work.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fbsr {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Streaming 16-byte load of four consecutive floats (16-byte aligned), read once.
+__device__ __forceinline__ f32x4 load_stream4(const float* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+}
+
+enum : int { kBF16 = 0, kE4M3 = 1, kE5M2 = 2 };
+enum : int { kRNE = 0, kSRFF = 1, kSRF = 2, kSRC = 3 };
+
+// ------------------------------------------------------------------------------ Philox ---
+// Philox4x32-10 (Salmon et al., SC'11).  Counter (c0..c3), key (k0,k1); the key and the two
+// high counter words are wave-uniform, so their arithmetic lands on the scalar unit.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
+  constexpr uint32_t MUL_A = 0xD2511F53u, MUL_B = 0xCD9E8D57u;
+  constexpr uint32_t WEYL_A = 0x9E3779B9u, WEYL_B = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t pa = (uint64_t)MUL_A * c0;
+    const uint64_t pb = (uint64_t)MUL_B * c2;
+    const uint32_t t0 = (uint32_t)(pb >> 32) ^ c1 ^ (k0 + WEYL_A * (uint32_t)r);
+    const uint32_t t2 = (uint32_t)(pa >> 32) ^ c3 ^ (k1 + WEYL_B * (uint32_t)r);
+    c1 = (uint32_t)pb;
+    c3 = (uint32_t)pa;
+    c0 = t0;
+    c2 = t2;
+  }
+  o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
+}
+
+// The block with index `blk` of stream (seed, step).
+__device__ __forceinline__ void philox_block(uint64_t blk, uint64_t seed, uint64_t step, uint32_t (&o)[4]) {
+  philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step, (uint32_t)(step >> 32),
+                (uint32_t)seed, (uint32_t)(seed >> 32), o);
+}
+
+// ------------------------------------------------------------------------- code spaces ---
+// FRAC      fraction bits below the code's last place
+// U_MAXFIN  fp32 pattern of M, the largest finite value (Sec. II)
+// NAN_FX    canonical quiet NaN, already shifted into code space
+template <int FMT> struct Fx;
+
+template <> struct Fx<kBF16> {
+  static constexpr int FRAC = 16;
+  static constexpr int P = 8, B = 127;
+  static constexpr uint32_t U_MAXFIN = 0x7F7F0000u;
+  static constexpr uint32_t NAN_FX = 0x7FC00000u;
+  static constexpr bool kIsFp8 = false;
+  typedef uint16_t code_t;
+};
+
+// fp8: FRAC = 24.  A target-normal |x| maps to ((u - (Q << 23)) << S) with Q = 127 - B the
+// exponent re-bias and S = FRAC - (24 - P); a target-subnormal |x| (u < U_SUB) maps to
+// trunc(|x| * SUB_SCALE), its position on the fixed subnormal grid (Eq. (2) clamps the
+// exponent at 1 - B).  Patterns above U_CLAMP are clamped to it first.
+template <> struct Fx<kE4M3> {
+  static constexpr int FRAC = 24;
+  static constexpr int P = 4, B = 7;
+  static constexpr uint32_t Q = 120, S = 4;
+  static constexpr uint32_t U_MAXFIN = 0x43E00000u;   // 448
+  static constexpr uint32_t U_CLAMP = 0x43E00000u;    // saturating: everything above acts as M
+  static constexpr uint32_t U_SUB = 121u << 23;       // 2^-6, smallest normal
+  static constexpr float SUB_SCALE = 0x1p33f;         // 1 / (2^-9 subnormal spacing) * 2^FRAC
+  static constexpr bool kDetRegion = false;
+  static constexpr uint32_t NAN_FX = 0x7F000000u;
+  static constexpr uint32_t INF_CODE = 0x100u;        // none
+  static constexpr bool kIsFp8 = true;
+  typedef uint8_t code_t;
+};
+
+template <> struct Fx<kE5M2> {
+  static constexpr int FRAC = 24;
+  static constexpr int P = 3, B = 15;
+  static constexpr uint32_t Q = 112, S = 3;
+  static constexpr uint32_t U_MAXFIN = 0x47600000u;   // 57344
+  static constexpr uint32_t U_CLAMP = 0x47700000u;    // 61440 = M + ulp(M)/2: maps to code 123.5
+  static constexpr uint32_t U_SUB = 113u << 23;       // 2^-14
+  static constexpr float SUB_SCALE = 0x1p40f;         // 1 / 2^-16 * 2^FRAC
+  static constexpr bool kDetRegion = true;            // (M, 61440): nearest is M; >= 61440: inf
+  static constexpr uint32_t NAN_FX = 0x7E000000u;
+  static constexpr uint32_t INF_CODE = 0x7Cu;
+  static constexpr bool kIsFp8 = true;
+  typedef uint8_t code_t;
+};
+
+// Wave-uniform shift amounts and constants derived from N once per kernel.
+struct Addends {
+  uint32_t nbits;      // N (0 for RNE)
+  uint32_t shift;      // FRAC - N: position of n's last place
+  uint32_t fixed;      // SRF: half of n's last place; SRC/RNE: half of it minus one; SRFF: 0
+  uint32_t tie_mask;   // SRC/RNE: 1 when the inner rounding really drops bits, else 0
+};
+
+template <int FMT, int VAR>
+__device__ __forceinline__ Addends make_addends(int nbits) {
+  constexpr int FRAC = Fx<FMT>::FRAC;
+  Addends a;
+  a.nbits = VAR == kRNE ? 0u : (uint32_t)nbits;
+  a.shift = (uint32_t)FRAC - a.nbits;
+  a.fixed = 0;
+  a.tie_mask = 0;
+  if (VAR == kSRF) a.fixed = a.shift >= 1 ? (1u << (a.shift - 1)) : 0u;
+  if (VAR == kSRC || VAR == kRNE) {
+    // Round(delta 2^N) drops `shift` bits; with shift == 0 it is the identity.
+    a.fixed = a.shift >= 1 ? (1u << (a.shift - 1)) - 1u : 0u;
+    a.tie_mask = a.shift >= 1 ? 1u : 0u;
+  }
+  return a;
+}
+
+// Rounds one fp32 pattern.  Returns the signed code in the top (32 - FRAC) bits; the low FRAC
+// bits are garbage.  n < 2^N is the element's random integer (0 for RNE).
+// CHECKED = false may be used only when the caller has established that the pattern is not a
+// NaN and, for bf16, not above M (those cases take a few extra selects).
+template <int FMT, int VAR, bool CHECKED>
+__device__ __forceinline__ uint32_t round_pattern(uint32_t bits, uint32_t n, const Addends& a) {
+  typedef Fx<FMT> F;
+  const uint32_t u = bits & 0x7FFFFFFFu;
+  uint32_t r0;
+  if constexpr (!F::kIsFp8) {
+    r0 = u;   // bf16 shares fp32's exponent range: the pattern already is the code space
+  } else {
+    const uint32_t uc = u < F::U_CLAMP ? u : F::U_CLAMP;
+    const uint32_t normal = (uc << F::S) - (F::Q << (23 + F::S));   // wraps consistently mod 2^32
+    const float scaled = fabsf(__uint_as_float(bits)) * F::SUB_SCALE;  // exact: power-of-two scale
+    const uint32_t sub = (uint32_t)scaled;                            // truncation toward zero
+    const bool is_sub = u < F::U_SUB;
+    r0 = is_sub ? sub : normal;
+    if constexpr (VAR == kSRC || VAR == kRNE) {
+      // bits lost by the truncation only matter for the tie test of the inner rounding:
+      // fold them into the last fraction bit (a sticky bit), which lies below the tie position
+      const bool lost = is_sub && ((float)sub != scaled);
+      r0 |= lost ? 1u : 0u;
+    }
+  }
+  uint32_t add = n << a.shift;
+  if constexpr (VAR == kSRF) add += a.fixed;
+  if constexpr (VAR == kSRC || VAR == kRNE) add += a.fixed + ((r0 >> a.shift) & a.tie_mask);
+  // |x| > M: no randomness, round to nearest on the unbounded grid (Sec. II).  M's significand
+  // is odd in both formats that have this region, so the tie goes up, i.e. "add one half".
+  if constexpr (F::kIsFp8) {
+    if constexpr (F::kDetRegion) add = u > F::U_MAXFIN ? (1u << (F::FRAC - 1)) : add;
+  } else if constexpr (CHECKED) {
+    add = u > F::U_MAXFIN ? (1u << (F::FRAC - 1)) : add;
+  }
+  uint32_t r = r0 + add;
+  if constexpr (CHECKED) r = u > 0x7F800000u ? F::NAN_FX : r;
+  return r | (bits & 0x80000000u);
+}
+
+// True when round_pattern<.., CHECKED = false> is not allowed for this pattern.
+template <int FMT>
+__device__ __forceinline__ bool needs_checked(uint32_t u_max) {
+  return u_max > (Fx<FMT>::kIsFp8 ? 0x7F800000u : Fx<FMT>::U_MAXFIN);
+}
+
+// ------------------------------------------------------------------- tile geometry -------
+// A wave handles one tile: 64 lanes x BL Philox blocks = the random bits of
+// 64 * BL * (128 / W) consecutive elements, i.e. GROUPS groups of 1024 elements.  Inside a
+// group, row k (256 consecutive elements) is read fully coalesced: lane l owns elements
+// 256 k + 4 l .. + 3 (one 16-byte load).  The lane that COMPUTES a block is not the lane that
+// CONSUMES its bits, so the blocks go through a per-wave LDS strip laid out as the tile's
+// linear bit string (element e at bit e * W) and every lane reads back its 4 W bits per row.
+template <int W> struct Tile {
+  static constexpr int BL = W >= 8 ? W / 8 : 1;
+  static constexpr int GROUPS = W >= 8 ? 1 : 8 / W;
+  static constexpr int ELEMS = GROUPS * 1024;
+  static constexpr int BLOCKS = 64 * BL;           // Philox blocks per tile
+  static constexpr int PER_BLOCK = 128 / W;        // elements per Philox block
+};
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kThreads = 64 * kWavesPerBlock;
+
+// Computes this lane's BL blocks of the tile and writes them to the wave's LDS strip.
+template <int W>
+__device__ __forceinline__ void fill_tile_bits(uint4* strip, int lane, uint64_t tile_blk0,
+                                               uint64_t seed, uint64_t step) {
+  constexpr int BL = Tile<W>::BL;
+#pragma unroll
+  for (int b = 0; b < BL; ++b) {
+    uint32_t o[4];
+    philox_block(tile_blk0 + (uint64_t)(lane * BL + b), seed, step, o);
+    strip[lane * BL + b] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+// The 4 W random bits of this lane's four elements in (group g, row k), right-aligned in a
+// 64-bit word (element j at bits j * W).
+template <int W>
+__device__ __forceinline__ uint64_t read_row_bits(const uint4* strip, int lane, int g, int k) {
+  const unsigned char* base = reinterpret_cast<const unsigned char*>(strip);
+  const int e0 = g * 1024 + k * 256 + 4 * lane;   // first element, tile-relative
+  if constexpr (W == 16) {
+    return *reinterpret_cast<const uint64_t*>(base + e0 * 2);
+  } else if constexpr (W == 8) {
+    return *reinterpret_cast<const uint32_t*>(base + e0);
+  } else if constexpr (W == 4) {
+    return *reinterpret_cast<const uint16_t*>(base + e0 / 2);
+  } else if constexpr (W == 2) {
+    return base[e0 / 4];
+  } else {
+    return (uint32_t)(base[e0 / 8] >> ((lane & 1) * 4)) & 0xFu;
+  }
+}
+
+template <int W>
+__device__ __forceinline__ uint32_t slot_bits(uint64_t row_bits, int j, uint32_t nbits) {
+  if constexpr (W == 16) {
+    const uint32_t w = (uint32_t)(row_bits >> (32 * (j >> 1)));
+    return __builtin_amdgcn_ubfe(w, (uint32_t)(16 * (j & 1)), nbits);
+  } else {
+    return __builtin_amdgcn_ubfe((uint32_t)row_bits, (uint32_t)(j * W), nbits);
+  }
+}
+
+// Random integer of ONE element with global index i (the per-element kernels).
+__device__ __forceinline__ uint32_t element_bits(uint64_t i, int log2_per_block, int W, uint32_t nbits,
+                                                 uint64_t seed, uint64_t step) {
+  const uint64_t blk = i >> log2_per_block;
+  const uint32_t slot = (uint32_t)i & ((1u << log2_per_block) - 1u);
+  uint32_t o[4];
+  philox_block(blk, seed, step, o);
+  const uint32_t bit = slot * (uint32_t)W;
+  const uint32_t wi = bit >> 5;
+  const uint32_t word = wi == 0 ? o[0] : wi == 1 ? o[1] : wi == 2 ? o[2] : o[3];
+  return __builtin_amdgcn_ubfe(word, bit & 31u, nbits);
+}
+
+// Packs the codes of four rounded patterns (element 0 in the low bits).
+template <int FMT>
+__device__ __forceinline__ uint32_t pack4_fp8(uint32_t r0, uint32_t r1, uint32_t r2, uint32_t r3) {
+  // byte 3 of each word is the signed 8-bit code
+  const uint32_t lo = __builtin_amdgcn_perm(r1, r0, 0x0c0c0703u);   // [r0.b3, r1.b3, 0, 0]
+  const uint32_t hi = __builtin_amdgcn_perm(r3, r2, 0x07030c0cu);   // [0, 0, r2.b3, r3.b3]
+  return lo | hi;
+}
+
+__device__ __forceinline__ uint32_t pack2_bf16(uint32_t r0, uint32_t r1) {
+  return __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // [r0.hi16, r1.hi16]
+}
+
+}  // namespace fbsr

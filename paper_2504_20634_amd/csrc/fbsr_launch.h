@@ -1,0 +1,73 @@
+// fbsr_launch.h -- host-side planning shared by the kernel translation units and the C ABI.
+#pragma once
+
+#include "fbsr_device.h"
+
+namespace fbsr {
+
+// Slot width: the smallest power of two >= nbits.
+inline int slot_width(int nbits) {
+  int w = 1;
+  while (w < nbits) w *= 2;
+  return w;
+}
+
+inline int log2_of(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return l;
+}
+
+inline int tile_elems(int W) { return W >= 8 ? 1024 : (8 / W) * 1024; }
+
+// How a call over [0, n) is cut: `head` elements for the per-element kernel (up to the first
+// global index that starts a Philox block), `ntiles` whole tiles for the vector kernel, and
+// the rest for the per-element kernel again.  The vector kernel is used only when both
+// buffers are suitably aligned at the first tile.
+struct Split {
+  uint64_t head;
+  uint64_t ntiles;
+  uint64_t tile_elems;
+};
+
+// in_addr / out_addr: addresses of element 0; *_esize: bytes per element; *_align: alignment
+// the vector kernel needs at a tile start.  out_addr may be 0 (no output buffer).
+inline Split split_range(uint64_t n, uint64_t offset, int W, bool no_bits, uintptr_t in_addr, uint64_t in_esize,
+                         uint64_t in_align, uintptr_t out_addr, uint64_t out_esize, uint64_t out_align,
+                         uintptr_t in2_addr = 0, uint64_t in2_esize = 0, uint64_t in2_align = 1) {
+  Split s;
+  s.tile_elems = (uint64_t)tile_elems(W);
+  const uint64_t per_block = no_bits ? 1 : (uint64_t)(128 / W);
+  uint64_t head = (per_block - offset % per_block) % per_block;
+  if (head > n) head = n;
+  s.head = head;
+  s.ntiles = (n - head) / s.tile_elems;
+  const bool aligned = (in_addr + head * in_esize) % in_align == 0 &&
+                       (out_addr == 0 || (out_addr + head * out_esize) % out_align == 0) &&
+                       (in2_addr == 0 || (in2_addr + head * in2_esize) % in2_align == 0);
+  if (!aligned || s.ntiles == 0) {
+    s.head = 0;   // everything goes through the per-element kernel in one piece
+    s.ntiles = 0;
+  }
+  return s;
+}
+
+// Largest element count one per-element launch may cover (keeps gridDim.x below 2^31).
+constexpr uint64_t kMaxElemsPerLaunch = (uint64_t)1 << 38;
+// Largest n the library accepts.
+constexpr uint64_t kMaxElems = (uint64_t)1 << 40;
+
+hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
+                        uint64_t offset, hipStream_t stream);
+
+hipError_t launch_sgd(void* w, const float* g, uint64_t n, float lr, int variant, int nbits, uint64_t seed,
+                      uint64_t step, uint64_t offset, hipStream_t stream);
+
+// The tile kernel of the statistics path leaves one record per tile in the workspace.
+constexpr uint64_t kStatsRecordDoubles = 6;   // {sum y, sum e, sum e^2} for the tile's first and second bin
+
+hipError_t launch_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
+                        uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
+                        double* workspace, hipStream_t stream);
+
+}  // namespace fbsr

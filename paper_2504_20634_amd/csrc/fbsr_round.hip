@@ -1,0 +1,163 @@
+// fbsr_round.hip -- kernels behind fbsr_round: fp32 -> {bf16, E4M3, E5M2} few-bit stochastic
+// rounding (Sec. II-B SRFF / SRF, Eq. (7) SRC, Sec. II-A RNE).
+#include "fbsr_launch.h"
+
+namespace fbsr {
+
+// One wave per tile.  Streaming: every input byte is read once (16-byte loads, fully
+// coalesced: a row of 256 floats per load instruction) and every output byte written once
+// (4 bytes per lane for fp8, 8 for bf16).
+template <int FMT, int VAR, int W>
+__global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict__ x, void* __restrict__ out,
+                                                        uint64_t ntiles, int nbits, uint64_t seed,
+                                                        uint64_t blk0) {
+  typedef Tile<W> T;
+  __shared__ uint4 strips[kWavesPerBlock][T::BLOCKS];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + (uint64_t)wave;
+  if constexpr (VAR != kRNE) {
+    fill_tile_bits<W>(strips[wave], lane, blk0 + tile * T::BLOCKS, seed, 0);
+    __syncthreads();
+  }
+  if (tile >= ntiles) return;
+
+  const Addends a = make_addends<FMT, VAR>(nbits);
+  const float* xt = x + tile * T::ELEMS;
+#pragma unroll 1
+  for (int g = 0; g < T::GROUPS; ++g) {
+    f32x4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = load_stream4(xt + 4 * (g * 256 + k * 64 + lane));
+    uint32_t umax = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      umax = max(umax, max(max(__float_as_uint(v[k].x) & 0x7FFFFFFFu, __float_as_uint(v[k].y) & 0x7FFFFFFFu),
+                           max(__float_as_uint(v[k].z) & 0x7FFFFFFFu, __float_as_uint(v[k].w) & 0x7FFFFFFFu)));
+    }
+    const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: NaN (bf16: also |x| > M) is rare
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      uint64_t rb = 0;
+      if constexpr (VAR != kRNE) rb = read_row_bits<W>(strips[wave], lane, g, k);
+      const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
+                             __float_as_uint(v[k].w)};
+      uint32_t r[4];
+      if (checked) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          r[j] = round_pattern<FMT, VAR, true>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          r[j] = round_pattern<FMT, VAR, false>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
+      }
+      const uint64_t row = tile * (T::ELEMS / 4) + (uint64_t)(g * 256 + k * 64 + lane);   // in units of 4 elements
+      if constexpr (Fx<FMT>::kIsFp8) {
+        __builtin_nontemporal_store(pack4_fp8<FMT>(r[0], r[1], r[2], r[3]), reinterpret_cast<uint32_t*>(out) + row);
+      } else {
+        uint2 p = make_uint2(pack2_bf16(r[0], r[1]), pack2_bf16(r[2], r[3]));
+        uint64_t pv = (uint64_t)p.x | ((uint64_t)p.y << 32);
+        __builtin_nontemporal_store(pv, reinterpret_cast<uint64_t*>(out) + row);
+      }
+    }
+  }
+}
+
+// One thread per element: any alignment, any offset, ragged heads and tails.  Each thread
+// computes the whole Philox block its element lives in.
+template <int FMT, int VAR>
+__global__ __launch_bounds__(kThreads) void round_elems(const float* __restrict__ x, void* __restrict__ out,
+                                                        uint64_t n, int nbits, int W, int log2_per_block,
+                                                        uint64_t seed, uint64_t offset) {
+  const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= n) return;
+  const Addends a = make_addends<FMT, VAR>(nbits);
+  uint32_t rnd = 0;
+  if constexpr (VAR != kRNE) rnd = element_bits(offset + j, log2_per_block, W, a.nbits, seed, 0);
+  const uint32_t r = round_pattern<FMT, VAR, true>(__float_as_uint(x[j]), rnd, a);
+  typedef typename Fx<FMT>::code_t code_t;
+  reinterpret_cast<code_t*>(out)[j] = (code_t)(r >> Fx<FMT>::FRAC);
+}
+
+namespace {
+
+template <int FMT, int VAR, int W>
+hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
+                        hipStream_t stream) {
+  const uint64_t blocks = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
+  hipLaunchKernelGGL((round_tiles<FMT, VAR, W>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, out, ntiles,
+                     nbits, seed, blk0);
+  return hipGetLastError();
+}
+
+template <int FMT, int VAR>
+hipError_t launch_tiles_w(int W, const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed,
+                          uint64_t blk0, hipStream_t stream) {
+  if constexpr (VAR == kRNE) return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, stream);
+  switch (W) {
+    case 1: return launch_tiles<FMT, VAR, 1>(x, out, ntiles, nbits, seed, blk0, stream);
+    case 2: return launch_tiles<FMT, VAR, 2>(x, out, ntiles, nbits, seed, blk0, stream);
+    case 4: return launch_tiles<FMT, VAR, 4>(x, out, ntiles, nbits, seed, blk0, stream);
+    case 8: return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, stream);
+    default: return launch_tiles<FMT, VAR, 16>(x, out, ntiles, nbits, seed, blk0, stream);
+  }
+}
+
+template <int FMT, int VAR>
+hipError_t launch_elems(const float* x, void* out, uint64_t n, int nbits, int W, uint64_t seed, uint64_t offset,
+                        hipStream_t stream) {
+  const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
+  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
+    const uint64_t m = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
+    const uint64_t blocks = (m + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL((round_elems<FMT, VAR>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x + at,
+                       reinterpret_cast<char*>(out) + at * osize, m, nbits, W, log2_of(128 / W), seed, offset + at);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <int FMT, int VAR>
+hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, uint64_t offset,
+               hipStream_t stream) {
+  const int W = VAR == kRNE ? 8 : slot_width(nbits);
+  const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
+  const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
+                              reinterpret_cast<uintptr_t>(out), osize, 4 * osize);
+  char* o = reinterpret_cast<char*>(out);
+  hipError_t e = launch_elems<FMT, VAR>(x, out, s.head, nbits, W, seed, offset, stream);
+  if (e != hipSuccess) return e;
+  if (s.ntiles) {
+    e = launch_tiles_w<FMT, VAR>(W, x + s.head, o + s.head * osize, s.ntiles, nbits, seed,
+                                 (offset + s.head) / (uint64_t)(128 / W), stream);
+    if (e != hipSuccess) return e;
+  }
+  const uint64_t done = s.head + s.ntiles * s.tile_elems;
+  return launch_elems<FMT, VAR>(x + done, o + done * osize, n - done, nbits, W, seed, offset + done, stream);
+}
+
+template <int FMT>
+hipError_t run_v(int variant, const float* x, void* out, uint64_t n, int nbits, uint64_t seed, uint64_t offset,
+                 hipStream_t stream) {
+  switch (variant) {
+    case kRNE: return run<FMT, kRNE>(x, out, n, nbits, seed, offset, stream);
+    case kSRFF: return run<FMT, kSRFF>(x, out, n, nbits, seed, offset, stream);
+    case kSRF: return run<FMT, kSRF>(x, out, n, nbits, seed, offset, stream);
+    default: return run<FMT, kSRC>(x, out, n, nbits, seed, offset, stream);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
+                        uint64_t offset, hipStream_t stream) {
+  switch (fmt) {
+    case kBF16: return run_v<kBF16>(variant, x, out, n, nbits, seed, offset, stream);
+    case kE4M3: return run_v<kE4M3>(variant, x, out, n, nbits, seed, offset, stream);
+    default: return run_v<kE5M2>(variant, x, out, n, nbits, seed, offset, stream);
+  }
+}
+
+}  // namespace fbsr

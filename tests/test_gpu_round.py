@@ -1,0 +1,118 @@
+"""GPU parity: fbsr_round through the C ABI against the CPU oracle, byte for byte."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import dev, first_mismatch, host
+
+pytestmark = pytest.mark.gpu
+
+BF16, E4M3, E5M2 = 0, 1, 2
+RNE, SRFF, SRF, SRC = 0, 1, 2, 3
+FMT_TARGET = {BF16: "bf16", E4M3: "e4m3", E5M2: "e5m2"}
+
+
+def _mixed_inputs(n, fmt, seed):
+    """Full-range patterns with specials sprinkled in, plus a band of scaled normals."""
+    from paper_2504_20634_amd import workloads
+    x = workloads.full_range(n, FMT_TARGET[fmt], seed=seed, specials_every=97)
+    m = min(n // 3, 5000)
+    if m:
+        x[-m:] = workloads.scaled_normal(m, seed=seed + 1)
+    return x
+
+
+@pytest.mark.parametrize("fmt", [BF16, E4M3, E5M2])
+def test_all_variants_and_bit_counts(fbsr, oracle, fmt):
+    """Several tiles plus ragged head and tail, every variant, every N in 1..16."""
+    n = 3 * 8192 + 1024 + 333
+    x = _mixed_inputs(n, fmt, seed=40 + fmt)
+    xd = dev(x)
+    cases = [(RNE, 0)] + [(v, nb) for v in (SRFF, SRF, SRC) for nb in range(1, 17)]
+    for variant, nbits in cases:
+        for offset in (0, 5):
+            print("case fmt=%d variant=%d nbits=%d offset=%d n=%d" % (fmt, variant, nbits, offset, n), flush=True)
+            got = host(fbsr.fbsr_round(xd, fmt, variant, nbits, seed=17, offset=offset))
+            want = oracle.round_(x, fmt, variant, nbits, seed=17, offset=offset, nthreads=8)
+            assert first_mismatch(got, want) is None, (fmt, variant, nbits, offset, first_mismatch(got, want))
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 15, 16, 17, 127, 128, 1023, 1024, 1025, 4095, 4096, 8191, 8192, 8193, 20000])
+def test_sizes_and_offsets(fbsr, oracle, n):
+    """Empty, tiny and ragged sizes; offsets that do and do not start a Philox block."""
+    x = _mixed_inputs(max(n, 1), E4M3, seed=3)[:n]
+    xd = dev(x) if n else torch.empty(0, dtype=torch.float32, device="cuda")
+    for fmt, variant, nbits in ((E4M3, SRFF, 2), (E5M2, SRC, 8), (BF16, SRF, 1), (BF16, SRC, 16), (E4M3, RNE, 0)):
+        for offset in (0, 1, 64, 1000, (1 << 40) + 3):
+            print("case n=%d fmt=%d variant=%d nbits=%d offset=%d" % (n, fmt, variant, nbits, offset), flush=True)
+            got = host(fbsr.fbsr_round(xd, fmt, variant, nbits, seed=99, offset=offset))
+            want = oracle.round_(x, fmt, variant, nbits, seed=99, offset=offset)
+            assert got.shape == want.shape
+            assert first_mismatch(got, want) is None, (n, fmt, variant, nbits, offset, first_mismatch(got, want))
+
+
+def test_unaligned_buffers_take_the_element_path(fbsr, oracle):
+    """x or out not 16-byte aligned: same bytes as the aligned call."""
+    n = 2 * 8192 + 77
+    x = _mixed_inputs(n + 8, E5M2, seed=8)
+    xd = dev(x)
+    for shift in (1, 2, 3):
+        for fmt, variant, nbits in ((E5M2, SRF, 4), (BF16, SRFF, 2), (E4M3, SRC, 3)):
+            print("case shift=%d fmt=%d variant=%d nbits=%d" % (shift, fmt, variant, nbits), flush=True)
+            xs = xd[shift:shift + n]
+            want = oracle.round_(x[shift:shift + n], fmt, variant, nbits, seed=5, offset=11)
+            got = host(fbsr.fbsr_round(xs, fmt, variant, nbits, seed=5, offset=11))
+            assert first_mismatch(got, want) is None
+            # misaligned output, aligned input
+            big = torch.zeros(n + 8, dtype=fbsr.binding.code_dtype(fmt), device="cuda")
+            o = big[shift:shift + n]
+            fbsr.fbsr_round(xd[:n], fmt, variant, nbits, seed=5, offset=11, out=o)
+            want2 = oracle.round_(x[:n], fmt, variant, nbits, seed=5, offset=11)
+            assert first_mismatch(host(o), want2) is None
+            rest = host(big)
+            assert not rest[:shift].any() and not rest[shift + n:].any(), "wrote outside the output range"
+
+
+def test_chunked_calls_and_repeats_are_identical(fbsr):
+    """Pure function of the arguments: a repeat gives the same bytes, and cutting the call into
+    chunks whose offset continues the index gives the same bytes as the whole call."""
+    n = 5 * 8192 + 100
+    x = _mixed_inputs(n, E4M3, seed=12)
+    xd = dev(x)
+    for fmt, variant, nbits in ((E4M3, SRFF, 2), (E5M2, SRF, 6), (BF16, SRC, 12)):
+        whole = fbsr.fbsr_round(xd, fmt, variant, nbits, seed=31, offset=256)
+        again = fbsr.fbsr_round(xd, fmt, variant, nbits, seed=31, offset=256)
+        assert torch.equal(whole.view(torch.uint8), again.view(torch.uint8))
+        cuts = [0, 100, 100 + 8192, 100 + 8192 + 4096 + 64, 30000, n]
+        parts = [fbsr.fbsr_round(xd[a:b], fmt, variant, nbits, seed=31, offset=256 + a)
+                 for a, b in zip(cuts[:-1], cuts[1:])]
+        assert torch.equal(whole.view(torch.uint8), torch.cat(parts).view(torch.uint8))
+        other = fbsr.fbsr_round(xd, fmt, variant, nbits, seed=32, offset=256)
+        assert not torch.equal(whole.view(torch.uint8), other.view(torch.uint8))
+
+
+def test_output_canaries(fbsr):
+    """Nothing is written outside [out, out + n)."""
+    for fmt in (BF16, E4M3):
+        for n in (1024, 8192 * 2, 8192 * 2 + 5):
+            x = dev(_mixed_inputs(n, fmt, seed=2))
+            dt = fbsr.binding.code_dtype(fmt)
+            pad = 64
+            big = torch.full((n + 2 * pad,), 0x5A, dtype=torch.uint8, device="cuda") if fmt != BF16 else \
+                torch.full((n + 2 * pad,), 0x5A5A, dtype=torch.int16, device="cuda").view(dt)
+            fbsr.fbsr_round(x, fmt, SRF, 4, seed=1, offset=0, out=big[pad:pad + n])
+            b = host(big)
+            canary = 0x5A if fmt != BF16 else 0x5A5A
+            assert (b[:pad] == canary).all() and (b[pad + n:] == canary).all()
+
+
+def test_runs_on_a_side_stream(fbsr, oracle):
+    n = 8192 * 3
+    x = _mixed_inputs(n, E5M2, seed=6)
+    xd = dev(x)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        out = fbsr.fbsr_round(xd, E5M2, SRC, 5, seed=4, offset=0, stream=s)
+    s.synchronize()
+    assert first_mismatch(host(out), oracle.round_(x, E5M2, SRC, 5, seed=4)) is None

@@ -1,0 +1,120 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+Where the oracle cannot cover the whole array in seconds it checks sampled windows: legal
+because every element's bits depend only on its global index."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import assert_stats_close, dev, first_mismatch, host
+
+pytestmark = pytest.mark.gpu
+BF16, E4M3, E5M2 = 0, 1, 2
+RNE, SRFF, SRF, SRC = 0, 1, 2, 3
+THREADS = 16
+
+
+def _windows(n, count, width, seed):
+    rng = np.random.default_rng(seed)
+    starts = [0, n - width] + [int(s) for s in rng.integers(0, n - width, count)]
+    # some windows deliberately start off a tile boundary
+    return sorted(set(starts))
+
+
+def test_workload2_e4m3_scaled_normal_full(fbsr, oracle):
+    """2^24 scaled-normal values -> E4M3, N in {1,2,3,4,6,8}, all variants, seed 1: every byte."""
+    from paper_2504_20634_amd import workloads
+    n = 1 << 24
+    x = workloads.scaled_normal(n, seed=1)
+    xd = dev(x)
+    frac_sub = np.mean(np.abs(x) < 2.0 ** -6)
+    assert 0.1 < frac_sub < 0.5 and np.any(np.abs(x) > 448)      # the recipe exercises subnormals and saturation
+    for nbits in (1, 2, 3, 4, 6, 8):
+        for variant in (SRFF, SRF, SRC):
+            print("case nbits=%d variant=%d" % (nbits, variant), flush=True)
+            got = host(fbsr.fbsr_round(xd, E4M3, variant, nbits, seed=1))
+            want = oracle.round_(x, E4M3, variant, nbits, seed=1, nthreads=THREADS)
+            assert first_mismatch(got, want) is None, (nbits, variant, first_mismatch(got, want))
+
+
+@pytest.mark.parametrize("fmt,target", [(E5M2, "e5m2"), (BF16, "bf16"), (E4M3, "e4m3")])
+def test_workload3_full_range_2_28(fbsr, oracle, fmt, target):
+    """2^28 full-range values, N in {4,8,16} (and 2 for the headline), all variants, seed 2:
+    one combination compared over the whole array, the rest on 40 sampled windows of 2^16."""
+    from paper_2504_20634_amd import workloads
+    n = 1 << 28
+    x = workloads.full_range(n, target, seed=2, specials_every=(100003 if fmt == BF16 else 0))
+    xd = dev(x)
+    print("case fmt=%d full array SRF N=8" % fmt, flush=True)
+    got = host(fbsr.fbsr_round(xd, fmt, SRF, 8, seed=2))
+    want = oracle.round_(x, fmt, SRF, 8, seed=2, nthreads=THREADS)
+    assert first_mismatch(got, want) is None, first_mismatch(got, want)
+    del got, want
+    width = 1 << 16
+    wins = _windows(n, 40, width, seed=fmt)
+    for nbits in (2, 4, 8, 16):
+        for variant in (SRFF, SRF, SRC):
+            print("case fmt=%d nbits=%d variant=%d windows" % (fmt, nbits, variant), flush=True)
+            out = fbsr.fbsr_round(xd, fmt, variant, nbits, seed=2)
+            for s in wins:
+                got = host(out[s:s + width])
+                want = oracle.round_(x[s:s + width], fmt, variant, nbits, seed=2, offset=s)
+                assert first_mismatch(got, want) is None, (nbits, variant, s, first_mismatch(got, want))
+            del out
+
+
+def test_workload4_sgd_2_27_two_steps(fbsr, oracle):
+    """2^27 bf16 weights, fp32 gradients of std 1e-3, lr 1e-3: two full-size steps, every weight."""
+    from paper_2504_20634_amd import workloads
+    n = 1 << 27
+    w = workloads.sgd_weights(n, seed=3)
+    wd = dev(w)
+    for t in range(2):
+        g = workloads.sgd_grads(n, t, seed=3)
+        fbsr.fbsr_sgd_update(wd, dev(g), 1e-3, SRF, 4, seed=4, step=t)
+        with ThreadPoolExecutor(THREADS) as pool:
+            cuts = np.linspace(0, n, THREADS + 1).astype(np.int64)
+            parts = list(pool.map(lambda ab: oracle.sgd_update(w[ab[0]:ab[1]], g[ab[0]:ab[1]], 1e-3, SRF, 4, 4, t, int(ab[0])),
+                                  zip(cuts[:-1], cuts[1:])))
+        w = np.concatenate(parts)
+        print("case step=%d" % t, flush=True)
+        assert first_mismatch(host(wd), w) is None, t
+
+
+def test_workload5_log_bins_2_30(fbsr, oracle):
+    """2^30 inputs in 4096 log-spaced bins of 2^18 over [2^-10, 2^10): statistics only
+    (out = NULL).  The oracle checks every 128th bin in full; the remaining bins are checked
+    through properties: count = 2^18, |mean error| < 1 ulp in range, SRFF's bias near
+    -2^-(N+1) and SRF / SRC near 0 away from E4M3's saturation."""
+    from paper_2504_20634_amd import workloads
+    nbins, group = 4096, 1 << 18
+    xd = torch.empty(nbins * group, dtype=torch.float32, device="cuda")
+    keep = {}
+    slab = 64
+    for b0 in range(0, nbins, slab):
+        xs, edges = workloads.log_bins(nbins, group, seed=5, bins=range(b0, b0 + slab))
+        xd[b0 * group:(b0 + slab) * group] = torch.from_numpy(xs).cuda()
+        for b in range(b0, b0 + slab, 128):
+            keep[b] = xs[(b - b0) * group:(b - b0 + 1) * group].copy()
+        if b0 % 1024 == 0:
+            print("generated bins up to %d" % (b0 + slab), flush=True)
+    ws = torch.empty(fbsr.bias_stats_workspace_bytes(nbins * group, nbins) // 8 + 1, dtype=torch.float64, device="cuda")
+    for fmt, variant, nbits in ((E4M3, SRFF, 3), (E4M3, SRC, 3), (BF16, SRF, 2), (BF16, SRFF, 12), (E4M3, SRF, 8)):
+        print("case fmt=%d variant=%d nbits=%d" % (fmt, variant, nbits), flush=True)
+        stats, _ = fbsr.fbsr_bias_stats(xd, fmt, variant, nbits, 5, 0, group, 0, nbins, workspace=ws)
+        s = stats.cpu().numpy()
+
+        def one(b):
+            st, _ = oracle.bias_stats(keep[b], fmt, variant, nbits, 5, b * group, group, b, 1)
+            return st[0]
+        with ThreadPoolExecutor(THREADS) as pool:
+            want = np.array(list(pool.map(one, sorted(keep))))
+        assert_stats_close(s[sorted(keep)], want)
+        assert np.all(s[:, 0] == group)
+        mean_e = s[:, 2] / s[:, 0]
+        in_range = edges[1:] <= (448.0 if fmt == E4M3 else 3e38)
+        assert np.all(np.abs(mean_e[in_range]) < 1.0)
+        expect = -2.0 ** -(nbits + 1) if variant == SRFF else 0.0
+        # per-bin sampling noise ~ 0.5 / sqrt(2^18) ~ 1e-3
+        assert np.all(np.abs(mean_e[in_range] - expect) < 6e-3), np.max(np.abs(mean_e[in_range] - expect))
