@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--elems-log2", type=int, default=28, help="log2 of the batch size (default 28)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-paths", action="store_true", help="skip the secondary paths (profiling runs)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run two plain device copies of the 1 GiB input (a kernel of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -57,9 +60,9 @@ def timed_launches(torch, fn, reps, warm=2):
 
 def cpu_baseline(x_host, fmts, variants, threads):
     """The oracle as it stands, timed on the host cores over a bounded sample of the same
-    workload: the first 2^24 elements, every (format, N, variant) of the headline sweep."""
+    workload: the first 2^25 elements, every (format, N, variant) of the headline sweep."""
     from oracle import fbsr_oracle as oracle
-    sample = 1 << 24
+    sample = 1 << 25
     done = 0
     t0 = time.perf_counter()
     for fmt in fmts:
@@ -70,7 +73,7 @@ def cpu_baseline(x_host, fmts, variants, threads):
                 done += xs.size
     dt = time.perf_counter() - t0
     return {"value": done / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
-            "sample": "first 2^24 elements of the same inputs x 18 (format, N, variant) launches, "
+            "sample": "first 2^25 elements of the same inputs x 18 (format, N, variant) launches, "
                       "oracle_round_threads with %d threads, %.1f s wall" % (threads, dt)}
 
 
@@ -95,11 +98,25 @@ def main():
 
     x_host = {f: workloads.full_range(n, target[f], seed=2) for f in fmts}
     x_dev = {f: torch.from_numpy(x_host[f]).cuda() for f in fmts}
-    out8 = torch.empty(n, dtype=torch.uint8, device="cuda")
+    # Consecutive launches rotate through several input and output buffers (3 GiB of inputs per
+    # format, 1 GiB of outputs) so the 256 MB last-level cache cannot serve any of the traffic.
+    x_rot = {f: [x_dev[f]] + [torch.from_numpy(workloads.full_range(n, target[f], seed=20 + k)).cuda() for k in (1, 2)]
+             for f in fmts}
+    out_rot = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    out8 = out_rot[0]
     sweep = [(f, nb, v) for f in fmts for nb in HEADLINE_NBITS for v in variants]
+    turn = [0]
 
     def launch(f, nb, v):
-        fbsr.fbsr_round(x_dev[f], f, v, nb, seed=2, offset=0, out=out8)
+        turn[0] += 1
+        fbsr.fbsr_round(x_rot[f][turn[0] % 3], f, v, nb, seed=2, offset=0, out=out_rot[turn[0] % 4])
+
+    if args.copy_probe:
+        probe = torch.empty_like(x_dev[fbsr.FMT_E4M3])
+        for _ in range(2):
+            probe.copy_(x_dev[fbsr.FMT_E4M3])
+        torch.cuda.synchronize()
+        del probe
 
     def step():
         for f, nb, v in sweep:
