@@ -24,6 +24,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per fp8 round_tiles launch of 2^28 elements, from two rocprofv3 --pmc runs of this file
+# (FETCH_SIZE, then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy);
+# the summary is committed under profiles/.  Algorithmic bytes: 5 * 2^28 = 1342177280.
+MEASURED_TRAFFIC_BYTES_2P28 = 1342215899
 N_ELEMS = 1 << 28
 SGD_ELEMS = 1 << 27
 HEADLINE_NBITS = (2, 4, 8)
@@ -200,7 +204,8 @@ def main():
                                "step = {e4m3,e5m2} x N{2,4,8} x {srff,srf,src} = 18 launches" % args.elems_log2,
                    "elements": n, "launches_per_step": len(sweep)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES_2P28 if args.elems_log2 == 28 else None,
                      "kernel": "round_tiles<fmt,variant,W> (average over the 18 launches of a step)",
                      "bytes_per_launch": 5 * n, "avg_launch_ms": avg_ms, "gb_s_by_nbits": by_n},
         "per_launch": per,
