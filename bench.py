@@ -165,17 +165,19 @@ def main():
             paths["round_bf16_N%d_srf" % nb] = {"ms": round(ms, 4), "gb_s": round(6.0 * n / ms / 1e6, 1)}
         del out16
         ns = min(SGD_ELEMS, n)
-        w = torch.from_numpy(workloads.sgd_weights(ns, seed=3).view(np.int16)).cuda()
-        g = torch.from_numpy(workloads.sgd_grads(ns, 0, seed=3)).cuda()
+        # rotate through 3 weight and 3 gradient buffers (2.25 GiB) so the last-level cache cannot help
+        ws_ = [torch.from_numpy(workloads.sgd_weights(ns, seed=3 + k).view(np.int16)).cuda() for k in range(3)]
+        gs_ = [torch.from_numpy(workloads.sgd_grads(ns, k, seed=3)).cuda() for k in range(3)]
         step_no = [0]
 
         def sgd(nb):
-            fbsr.fbsr_sgd_update(w, g, 1e-3, fbsr.SRF, nb, seed=4, step=step_no[0])
+            k = step_no[0] % 3
+            fbsr.fbsr_sgd_update(ws_[k], gs_[k], 1e-3, fbsr.SRF, nb, seed=4, step=step_no[0])
             step_no[0] += 1
         for nb in (2, 4, 8):
-            ms = timed_launches(torch, lambda: sgd(nb), 10)
+            ms = timed_launches(torch, lambda: sgd(nb), 12)
             paths["sgd_update_bf16_N%d_srf" % nb] = {"ms": round(ms, 4), "gb_s": round(8.0 * ns / ms / 1e6, 1)}
-        del w, g
+        del ws_, gs_
         group = 1 << 18
         nbins = n // group
         ws = torch.empty(fbsr.bias_stats_workspace_bytes(n, nbins) // 8 + 1, dtype=torch.float64, device="cuda")

@@ -49,8 +49,8 @@ int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, 
 
 uint64_t fbsr_bias_stats_workspace_bytes(uint64_t n, uint32_t nbins) {
   (void)nbins;
-  // one record per 1024-element tile at most (tiles are 1024 elements or larger)
-  return (n / 1024 + 1) * fbsr::kStatsRecordDoubles * sizeof(double);
+  // one record per workgroup tile
+  return (n / fbsr::kTileElems + 1) * fbsr::kStatsRecordDoubles * sizeof(double);
 }
 
 int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,

@@ -18,7 +18,7 @@ inline int log2_of(int v) {
   return l;
 }
 
-inline int tile_elems(int W) { return W >= 8 ? 1024 : (8 / W) * 1024; }
+inline int tile_elems(int W) { (void)W; return kTileElems; }   // one workgroup tile
 
 // How a call over [0, n) is cut: `head` elements for the per-element kernel (up to the first
 // global index that starts a Philox block), `ntiles` whole tiles for the vector kernel, and

@@ -4,62 +4,55 @@
 
 namespace fbsr {
 
-// One wave per tile.  Streaming: every input byte is read once (16-byte loads, fully
-// coalesced: a row of 256 floats per load instruction) and every output byte written once
-// (4 bytes per lane for fp8, 8 for bf16).
+// One workgroup per 2048-element tile, one wave per 512 elements.  Streaming: every input byte
+// is read once (16-byte loads, fully coalesced: a row of 256 floats per load instruction) and
+// every output byte written once (4 bytes per lane for fp8, 8 for bf16).  The loads are issued
+// first so that their latency overlaps the Philox rounds.
 template <int FMT, int VAR, int W>
 __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict__ x, void* __restrict__ out,
-                                                        uint64_t ntiles, int nbits, uint64_t seed,
-                                                        uint64_t blk0) {
-  typedef Tile<W> T;
-  __shared__ uint4 strips[kWavesPerBlock][T::BLOCKS];
+                                                        int nbits, uint64_t seed, uint64_t blk0) {
+  typedef WgTile<W> T;
+  __shared__ uint4 strip[T::BLOCKS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + (uint64_t)wave;
+  const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+  f32x4 v[kRows];
+#pragma unroll
+  for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
   if constexpr (VAR != kRNE) {
-    fill_tile_bits<W>(strips[wave], lane, blk0 + tile * T::BLOCKS, seed, 0);
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
     __syncthreads();
   }
-  if (tile >= ntiles) return;
-
   const Addends a = make_addends<FMT, VAR>(nbits);
-  const float* xt = x + tile * T::ELEMS;
-#pragma unroll 1
-  for (int g = 0; g < T::GROUPS; ++g) {
-    f32x4 v[4];
+  uint32_t umax = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) v[k] = load_stream4(xt + 4 * (g * 256 + k * 64 + lane));
-    uint32_t umax = 0;
+  for (int k = 0; k < kRows; ++k) {
+    umax = max(umax, max(max(__float_as_uint(v[k].x) & 0x7FFFFFFFu, __float_as_uint(v[k].y) & 0x7FFFFFFFu),
+                         max(__float_as_uint(v[k].z) & 0x7FFFFFFFu, __float_as_uint(v[k].w) & 0x7FFFFFFFu)));
+  }
+  const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: NaN (bf16: also |x| > M) is rare
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      umax = max(umax, max(max(__float_as_uint(v[k].x) & 0x7FFFFFFFu, __float_as_uint(v[k].y) & 0x7FFFFFFFu),
-                           max(__float_as_uint(v[k].z) & 0x7FFFFFFFu, __float_as_uint(v[k].w) & 0x7FFFFFFFu)));
+  for (int k = 0; k < kRows; ++k) {
+    uint64_t rb = 0;
+    if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip, wave, lane, k);
+    const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
+                           __float_as_uint(v[k].w)};
+    uint32_t r[4];
+    if (checked) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        r[j] = round_pattern<FMT, VAR, true>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        r[j] = round_pattern<FMT, VAR, false>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
     }
-    const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: NaN (bf16: also |x| > M) is rare
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      uint64_t rb = 0;
-      if constexpr (VAR != kRNE) rb = read_row_bits<W>(strips[wave], lane, g, k);
-      const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
-                             __float_as_uint(v[k].w)};
-      uint32_t r[4];
-      if (checked) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          r[j] = round_pattern<FMT, VAR, true>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          r[j] = round_pattern<FMT, VAR, false>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
-      }
-      const uint64_t row = tile * (T::ELEMS / 4) + (uint64_t)(g * 256 + k * 64 + lane);   // in units of 4 elements
-      if constexpr (Fx<FMT>::kIsFp8) {
-        __builtin_nontemporal_store(pack4_fp8<FMT>(r[0], r[1], r[2], r[3]), reinterpret_cast<uint32_t*>(out) + row);
-      } else {
-        uint2 p = make_uint2(pack2_bf16(r[0], r[1]), pack2_bf16(r[2], r[3]));
-        uint64_t pv = (uint64_t)p.x | ((uint64_t)p.y << 32);
-        __builtin_nontemporal_store(pv, reinterpret_cast<uint64_t*>(out) + row);
-      }
+    const uint64_t row = row0 + (uint64_t)(k * 64);
+    if constexpr (Fx<FMT>::kIsFp8) {
+      __builtin_nontemporal_store(pack4_fp8<FMT>(r[0], r[1], r[2], r[3]), reinterpret_cast<uint32_t*>(out) + row);
+    } else {
+      const uint64_t pv = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
+      __builtin_nontemporal_store(pv, reinterpret_cast<uint64_t*>(out) + row);
     }
   }
 }
@@ -85,9 +78,8 @@ namespace {
 template <int FMT, int VAR, int W>
 hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
                         hipStream_t stream) {
-  const uint64_t blocks = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL((round_tiles<FMT, VAR, W>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, out, ntiles,
-                     nbits, seed, blk0);
+  hipLaunchKernelGGL((round_tiles<FMT, VAR, W>), dim3((unsigned)ntiles), dim3(kThreads), 0, stream, x, out, nbits,
+                     seed, blk0);
   return hipGetLastError();
 }
 

@@ -5,66 +5,60 @@
 
 namespace fbsr {
 
-// Same tile geometry as the rounding kernel: per row a lane reads 4 weights (8 bytes) and
+// Same workgroup tile as the rounding kernel: per row a lane reads 4 weights (8 bytes) and
 // 4 gradients (16 bytes) and writes 4 weights back in place.
 template <int VAR, int W>
 __global__ __launch_bounds__(kThreads) void sgd_tiles(uint16_t* __restrict__ w, const float* __restrict__ g,
-                                                      uint64_t ntiles, float neg_lr, int nbits, uint64_t seed,
-                                                      uint64_t step, uint64_t blk0) {
-  typedef Tile<W> T;
-  __shared__ uint4 strips[kWavesPerBlock][T::BLOCKS];
+                                                      float neg_lr, int nbits, uint64_t seed, uint64_t step,
+                                                      uint64_t blk0) {
+  typedef WgTile<W> T;
+  __shared__ uint4 strip[T::BLOCKS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + (uint64_t)wave;
+  const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+  uint64_t* wt = reinterpret_cast<uint64_t*>(w);
+  f32x4 gv[kRows];
+  uint64_t wv[kRows];
+#pragma unroll
+  for (int k = 0; k < kRows; ++k) {
+    gv[k] = load_stream4(g + 4 * (row0 + (uint64_t)(k * 64)));
+    wv[k] = wt[row0 + (uint64_t)(k * 64)];   // read-modify-write: keep the line in L2 for the store
+  }
   if constexpr (VAR != kRNE) {
-    fill_tile_bits<W>(strips[wave], lane, blk0 + tile * T::BLOCKS, seed, step);
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, step);
     __syncthreads();
   }
-  if (tile >= ntiles) return;
-
   const Addends a = make_addends<kBF16, VAR>(nbits);
-  const float* gt = g + tile * T::ELEMS;
-  uint64_t* wt = reinterpret_cast<uint64_t*>(w + tile * T::ELEMS);
-#pragma unroll 1
-  for (int grp = 0; grp < T::GROUPS; ++grp) {
-    f32x4 gv[4];
-    uint64_t wv[4];
+  uint32_t b[kRows][4];
+  uint32_t umax = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      gv[k] = load_stream4(gt + 4 * (grp * 256 + k * 64 + lane));
-      wv[k] = wt[grp * 256 + k * 64 + lane];
+  for (int k = 0; k < kRows; ++k) {
+    const uint32_t lo = (uint32_t)wv[k], hi = (uint32_t)(wv[k] >> 32);
+    const float wf[4] = {__uint_as_float(lo << 16), __uint_as_float(lo & 0xFFFF0000u), __uint_as_float(hi << 16),
+                         __uint_as_float(hi & 0xFFFF0000u)};
+    const float gf[4] = {gv[k].x, gv[k].y, gv[k].z, gv[k].w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      b[k][j] = __float_as_uint(__fmaf_rn(neg_lr, gf[j], wf[j]));
+      umax = max(umax, b[k][j] & 0x7FFFFFFFu);
     }
-    uint32_t b[4][4];
-    uint32_t umax = 0;
+  }
+  const bool checked = __any(needs_checked<kBF16>(umax));
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const uint32_t lo = (uint32_t)wv[k], hi = (uint32_t)(wv[k] >> 32);
-      const float wf[4] = {__uint_as_float(lo << 16), __uint_as_float(lo & 0xFFFF0000u), __uint_as_float(hi << 16),
-                           __uint_as_float(hi & 0xFFFF0000u)};
-      const float gf[4] = {gv[k].x, gv[k].y, gv[k].z, gv[k].w};
+  for (int k = 0; k < kRows; ++k) {
+    uint64_t rb = 0;
+    if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip, wave, lane, k);
+    uint32_t r[4];
+    if (checked) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        b[k][j] = __float_as_uint(__fmaf_rn(neg_lr, gf[j], wf[j]));
-        umax = max(umax, b[k][j] & 0x7FFFFFFFu);
-      }
+      for (int j = 0; j < 4; ++j)
+        r[j] = round_pattern<kBF16, VAR, true>(b[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        r[j] = round_pattern<kBF16, VAR, false>(b[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
     }
-    const bool checked = __any(needs_checked<kBF16>(umax));
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      uint64_t rb = 0;
-      if constexpr (VAR != kRNE) rb = read_row_bits<W>(strips[wave], lane, grp, k);
-      uint32_t r[4];
-      if (checked) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          r[j] = round_pattern<kBF16, VAR, true>(b[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          r[j] = round_pattern<kBF16, VAR, false>(b[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
-      }
-      wt[grp * 256 + k * 64 + lane] = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
-    }
+    wt[row0 + (uint64_t)(k * 64)] = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
   }
 }
 
@@ -86,9 +80,8 @@ namespace {
 template <int VAR, int W>
 hipError_t launch_tiles(uint16_t* w, const float* g, uint64_t ntiles, float neg_lr, int nbits, uint64_t seed,
                         uint64_t step, uint64_t blk0, hipStream_t stream) {
-  const uint64_t blocks = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL((sgd_tiles<VAR, W>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, w, g, ntiles, neg_lr,
-                     nbits, seed, step, blk0);
+  hipLaunchKernelGGL((sgd_tiles<VAR, W>), dim3((unsigned)ntiles), dim3(kThreads), 0, stream, w, g, neg_lr, nbits, seed,
+                     step, blk0);
   return hipGetLastError();
 }
 

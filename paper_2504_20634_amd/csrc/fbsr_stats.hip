@@ -63,81 +63,85 @@ __device__ __forceinline__ void accumulate(Acc& acc, uint32_t bits, uint32_t r) 
   acc.see = fma(e, e, acc.see);
 }
 
-// One wave per tile.  A tile touches at most two bins (the host guarantees group >= tile
-// elements): record = {A.sy, A.se, A.see, B.sy, B.se, B.see}.
+// Same workgroup tile as the rounding kernel.  A tile touches at most two bins (the host
+// guarantees group >= tile): lane-local fp64 sums for the first (A) and second (B) bin, an
+// xor-butterfly across each wave, the four waves' sums staged in LDS and added in wave order,
+// one record per tile = {A.sy, A.se, A.see, B.sy, B.se, B.see}.
 template <int FMT, int VAR, int W>
-__global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict__ x, void* __restrict__ out,
-                                                        uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
-                                                        uint64_t i0, uint64_t group, double* __restrict__ records) {
-  typedef Tile<W> T;
-  __shared__ uint4 strips[kWavesPerBlock][T::BLOCKS];
+__global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict__ x, void* __restrict__ out, int nbits,
+                                                        uint64_t seed, uint64_t blk0, uint64_t i0, uint64_t group,
+                                                        double* __restrict__ records) {
+  typedef WgTile<W> T;
+  __shared__ uint4 strip[T::BLOCKS];
+  __shared__ double staged[kWavesPerBlock][kStatsRecordDoubles];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + (uint64_t)wave;
+  const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+  f32x4 v[kRows];
+#pragma unroll
+  for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
   if constexpr (VAR != kRNE) {
-    fill_tile_bits<W>(strips[wave], lane, blk0 + tile * T::BLOCKS, seed, 0);
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
     __syncthreads();
   }
-  if (tile >= ntiles) return;
-
   const Addends a = make_addends<FMT, VAR>(nbits);
-  const uint64_t gi0 = i0 + tile * T::ELEMS;
-  const uint64_t to_boundary = group - gi0 % group;      // tile-relative index where the second bin starts
+  const uint64_t gi0 = i0 + (uint64_t)blockIdx.x * T::ELEMS;   // global index of the tile's first element
+  const uint64_t to_boundary = group - gi0 % group;           // tile-relative index where the second bin starts
   const int boundary = to_boundary > (uint64_t)T::ELEMS ? T::ELEMS : (int)to_boundary;
   Acc accA = {0.0, 0.0, 0.0}, accB = {0.0, 0.0, 0.0};
-  const float* xt = x + tile * T::ELEMS;
-#pragma unroll 1
-  for (int g = 0; g < T::GROUPS; ++g) {
-    f32x4 v[4];
+  uint32_t r[kRows][4], b[kRows][4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) v[k] = load_stream4(xt + 4 * (g * 256 + k * 64 + lane));
-    uint32_t r[4][4], b[4][4];
+  for (int k = 0; k < kRows; ++k) {
+    uint64_t rb = 0;
+    if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip, wave, lane, k);
+    b[k][0] = __float_as_uint(v[k].x); b[k][1] = __float_as_uint(v[k].y);
+    b[k][2] = __float_as_uint(v[k].z); b[k][3] = __float_as_uint(v[k].w);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      uint64_t rb = 0;
-      if constexpr (VAR != kRNE) rb = read_row_bits<W>(strips[wave], lane, g, k);
-      b[k][0] = __float_as_uint(v[k].x); b[k][1] = __float_as_uint(v[k].y);
-      b[k][2] = __float_as_uint(v[k].z); b[k][3] = __float_as_uint(v[k].w);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        r[k][j] = round_pattern<FMT, VAR, true>(b[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
-      if (out != nullptr) {
-        const uint64_t row = tile * (T::ELEMS / 4) + (uint64_t)(g * 256 + k * 64 + lane);
-        if constexpr (Fx<FMT>::kIsFp8) {
-          reinterpret_cast<uint32_t*>(out)[row] = pack4_fp8<FMT>(r[k][0], r[k][1], r[k][2], r[k][3]);
-        } else {
-          reinterpret_cast<uint64_t*>(out)[row] =
-              (uint64_t)pack2_bf16(r[k][0], r[k][1]) | ((uint64_t)pack2_bf16(r[k][2], r[k][3]) << 32);
-        }
+    for (int j = 0; j < 4; ++j)
+      r[k][j] = round_pattern<FMT, VAR, true>(b[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
+    if (out != nullptr) {
+      const uint64_t row = row0 + (uint64_t)(k * 64);
+      if constexpr (Fx<FMT>::kIsFp8) {
+        reinterpret_cast<uint32_t*>(out)[row] = pack4_fp8<FMT>(r[k][0], r[k][1], r[k][2], r[k][3]);
+      } else {
+        reinterpret_cast<uint64_t*>(out)[row] =
+            (uint64_t)pack2_bf16(r[k][0], r[k][1]) | ((uint64_t)pack2_bf16(r[k][2], r[k][3]) << 32);
       }
     }
-    const int g_lo = g * 1024, g_hi = g_lo + 1024;
-    if (boundary >= g_hi) {            // whole group in the first bin (wave-uniform)
+  }
+  const int w_lo = wave * kWaveElems, w_hi = w_lo + kWaveElems;   // this wave's tile-relative range
+  if (boundary >= w_hi) {            // the whole wave lies in the first bin (wave-uniform, the common case)
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+    for (int k = 0; k < kRows; ++k)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) accumulate<FMT>(accA, b[k][j], r[k][j]);
-    } else if (boundary <= g_lo) {     // whole group in the second bin
+      for (int j = 0; j < 4; ++j) accumulate<FMT>(accA, b[k][j], r[k][j]);
+  } else if (boundary <= w_lo) {     // the whole wave lies in the second bin
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+    for (int k = 0; k < kRows; ++k)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) accumulate<FMT>(accB, b[k][j], r[k][j]);
-    } else {                           // the one group that straddles the boundary
+      for (int j = 0; j < 4; ++j) accumulate<FMT>(accB, b[k][j], r[k][j]);
+  } else {                           // the bin boundary falls inside this wave's elements
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+    for (int k = 0; k < kRows; ++k)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int e = g_lo + k * 256 + 4 * lane + j;
-          if (e < boundary) accumulate<FMT>(accA, b[k][j], r[k][j]);
-          else accumulate<FMT>(accB, b[k][j], r[k][j]);
-        }
-    }
+      for (int j = 0; j < 4; ++j) {
+        const int e = w_lo + k * 256 + 4 * lane + j;
+        if (e < boundary) accumulate<FMT>(accA, b[k][j], r[k][j]);
+        else accumulate<FMT>(accB, b[k][j], r[k][j]);
+      }
   }
   const double s0 = wave_sum(accA.sy), s1 = wave_sum(accA.se), s2 = wave_sum(accA.see);
   const double s3 = wave_sum(accB.sy), s4 = wave_sum(accB.se), s5 = wave_sum(accB.see);
   if (lane == 0) {
-    double* rec = records + tile * kStatsRecordDoubles;
-    rec[0] = s0; rec[1] = s1; rec[2] = s2; rec[3] = s3; rec[4] = s4; rec[5] = s5;
+    staged[wave][0] = s0; staged[wave][1] = s1; staged[wave][2] = s2;
+    staged[wave][3] = s3; staged[wave][4] = s4; staged[wave][5] = s5;
+  }
+  __syncthreads();
+  if (threadIdx.x < kStatsRecordDoubles) {
+    double t = staged[0][threadIdx.x];
+#pragma unroll
+    for (int wv = 1; wv < kWavesPerBlock; ++wv) t += staged[wv][threadIdx.x];
+    records[(uint64_t)blockIdx.x * kStatsRecordDoubles + threadIdx.x] = t;
   }
 }
 
@@ -209,9 +213,8 @@ namespace {
 template <int FMT, int VAR, int W>
 hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
                         uint64_t i0, uint64_t group, double* records, hipStream_t stream) {
-  const uint64_t blocks = (ntiles + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL((stats_tiles<FMT, VAR, W>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, out, ntiles,
-                     nbits, seed, blk0, i0, group, records);
+  hipLaunchKernelGGL((stats_tiles<FMT, VAR, W>), dim3((unsigned)ntiles), dim3(kThreads), 0, stream, x, out, nbits, seed,
+                     blk0, i0, group, records);
   return hipGetLastError();
 }
 
