@@ -49,8 +49,9 @@ int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, 
 
 uint64_t fbsr_bias_stats_workspace_bytes(uint64_t n, uint32_t nbins) {
   (void)nbins;
-  // one record per workgroup tile
-  return (n / fbsr::kTileElems + 1) * fbsr::kStatsRecordDoubles * sizeof(double);
+  // one record per (chunk, bin it touches), sized for the smallest group the chunked kernel takes
+  const uint64_t chunk = (uint64_t)fbsr::kStatsChunkTiles * fbsr::kTileElems;
+  return (n / chunk + 1) * fbsr::kStatsMaxSlots * fbsr::kStatsRecordDoubles * sizeof(double);
 }
 
 int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,

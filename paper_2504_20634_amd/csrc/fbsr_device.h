@@ -67,6 +67,7 @@ template <> struct Fx<kBF16> {
   static constexpr int P = 8, B = 127;
   static constexpr uint32_t U_MAXFIN = 0x7F7F0000u;
   static constexpr uint32_t NAN_FX = 0x7FC00000u;
+  static constexpr uint32_t U_EXACT = 0u;             // the code space is the pattern: always exact
   static constexpr bool kIsFp8 = false;
   typedef uint16_t code_t;
 };
@@ -82,6 +83,7 @@ template <> struct Fx<kE4M3> {
   static constexpr uint32_t U_MAXFIN = 0x43E00000u;   // 448
   static constexpr uint32_t U_CLAMP = 0x43E00000u;    // saturating: everything above acts as M
   static constexpr uint32_t U_SUB = 121u << 23;       // 2^-6, smallest normal
+  static constexpr uint32_t U_EXACT = 117u << 23;     // from 2^-10 up no input bit lies below 2^-FRAC of the subnormal spacing
   static constexpr float SUB_SCALE = 0x1p33f;         // 1 / (2^-9 subnormal spacing) * 2^FRAC
   static constexpr bool kDetRegion = false;
   static constexpr uint32_t NAN_FX = 0x7F000000u;
@@ -97,6 +99,7 @@ template <> struct Fx<kE5M2> {
   static constexpr uint32_t U_MAXFIN = 0x47600000u;   // 57344
   static constexpr uint32_t U_CLAMP = 0x47700000u;    // 61440 = M + ulp(M)/2: maps to code 123.5
   static constexpr uint32_t U_SUB = 113u << 23;       // 2^-14
+  static constexpr uint32_t U_EXACT = 110u << 23;     // 2^-17, as above for the 2^-16 spacing
   static constexpr float SUB_SCALE = 0x1p40f;         // 1 / 2^-16 * 2^FRAC
   static constexpr bool kDetRegion = true;            // (M, 61440): nearest is M; >= 61440: inf
   static constexpr uint32_t NAN_FX = 0x7E000000u;
@@ -130,31 +133,38 @@ __device__ __forceinline__ Addends make_addends(int nbits) {
   return a;
 }
 
-// Rounds one fp32 pattern.  Returns the signed code in the top (32 - FRAC) bits; the low FRAC
-// bits are garbage.  n < 2^N is the element's random integer (0 for RNE).
-// CHECKED = false may be used only when the caller has established that the pattern is not a
-// NaN and, for bf16, not above M (those cases take a few extra selects).
-template <int FMT, int VAR, bool CHECKED>
-__device__ __forceinline__ uint32_t round_pattern(uint32_t bits, uint32_t n, const Addends& a) {
+// |x| in code space (see the file header): the magnitude code in the top bits, delta 2^FRAC in
+// the low FRAC bits.  For SRC / RNE the bits a target-subnormal input loses to the truncation are
+// folded into bit 0 (a sticky bit: it lies below the tie position of the inner rounding).
+template <int FMT, int VAR>
+__device__ __forceinline__ uint32_t to_code_space(uint32_t bits) {
   typedef Fx<FMT> F;
   const uint32_t u = bits & 0x7FFFFFFFu;
-  uint32_t r0;
   if constexpr (!F::kIsFp8) {
-    r0 = u;   // bf16 shares fp32's exponent range: the pattern already is the code space
+    return u;   // bf16 shares fp32's exponent range: the pattern already is the code space
   } else {
     const uint32_t uc = u < F::U_CLAMP ? u : F::U_CLAMP;
     const uint32_t normal = (uc << F::S) - (F::Q << (23 + F::S));   // wraps consistently mod 2^32
     const float scaled = fabsf(__uint_as_float(bits)) * F::SUB_SCALE;  // exact: power-of-two scale
     const uint32_t sub = (uint32_t)scaled;                            // truncation toward zero
     const bool is_sub = u < F::U_SUB;
-    r0 = is_sub ? sub : normal;
+    uint32_t r0 = is_sub ? sub : normal;
     if constexpr (VAR == kSRC || VAR == kRNE) {
-      // bits lost by the truncation only matter for the tie test of the inner rounding:
-      // fold them into the last fraction bit (a sticky bit), which lies below the tie position
       const bool lost = is_sub && ((float)sub != scaled);
       r0 |= lost ? 1u : 0u;
     }
+    return r0;
   }
+}
+
+// The rounding add in code space.  Returns the rounded MAGNITUDE (code in the top bits, garbage
+// below); n < 2^N is the element's random integer (0 for RNE).
+// CHECKED = false may be used only when the caller has established that the pattern is not a
+// NaN and, for bf16, not above M (those cases take a few extra selects).
+template <int FMT, int VAR, bool CHECKED>
+__device__ __forceinline__ uint32_t round_magnitude(uint32_t bits, uint32_t r0, uint32_t n, const Addends& a) {
+  typedef Fx<FMT> F;
+  const uint32_t u = bits & 0x7FFFFFFFu;
   uint32_t add = n << a.shift;
   if constexpr (VAR == kSRF) add += a.fixed;
   if constexpr (VAR == kSRC || VAR == kRNE) add += a.fixed + ((r0 >> a.shift) & a.tie_mask);
@@ -167,7 +177,14 @@ __device__ __forceinline__ uint32_t round_pattern(uint32_t bits, uint32_t n, con
   }
   uint32_t r = r0 + add;
   if constexpr (CHECKED) r = u > 0x7F800000u ? F::NAN_FX : r;
-  return r | (bits & 0x80000000u);
+  return r;
+}
+
+// Rounds one fp32 pattern.  Returns the signed code in the top (32 - FRAC) bits; the low FRAC
+// bits are garbage.
+template <int FMT, int VAR, bool CHECKED>
+__device__ __forceinline__ uint32_t round_pattern(uint32_t bits, uint32_t n, const Addends& a) {
+  return round_magnitude<FMT, VAR, CHECKED>(bits, to_code_space<FMT, VAR>(bits), n, a) | (bits & 0x80000000u);
 }
 
 // True when round_pattern<.., CHECKED = false> is not allowed for this pattern.

@@ -63,8 +63,13 @@ hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int vari
 hipError_t launch_sgd(void* w, const float* g, uint64_t n, float lr, int variant, int nbits, uint64_t seed,
                       uint64_t step, uint64_t offset, hipStream_t stream);
 
-// The tile kernel of the statistics path leaves one record per tile in the workspace.
-constexpr uint64_t kStatsRecordDoubles = 6;   // {sum y, sum e, sum e^2} for the tile's first and second bin
+// The tile kernel of the statistics path works in chunks of kStatsChunkTiles tiles per workgroup
+// and leaves one record {sum y, sum e, sum e^2} per (chunk, bin the chunk touches) in the
+// workspace; a chunk touches at most chunk / group + 2 bins, and group >= one tile on this path.
+constexpr int kStatsChunkTiles = 8;
+constexpr uint64_t kStatsRecordDoubles = 3;
+inline uint64_t stats_slots(uint64_t group) { return (uint64_t)(kStatsChunkTiles * kTileElems) / group + 2; }
+constexpr uint64_t kStatsMaxSlots = kStatsChunkTiles + 2;
 
 hipError_t launch_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                         uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,

@@ -3,9 +3,12 @@
 // in fp64 -- the measurement behind Figs. 1 and 2 (mean rounded value per input, bias in
 // target ulps, Sec. III).  Bins are runs of `group` consecutive global indices.
 //
-// Reduction order is fixed (lane-local sums -> xor-butterfly across the wave -> one record
-// per tile in the workspace -> per-bin sums over its tiles, lane-strided then butterfly), so
-// results are bit-reproducible; no floating-point atomics are used.
+// Reduction order is fixed (lane-local sums -> xor-butterfly across the wave -> the four waves'
+// sums staged in LDS and added in wave order -> one record per (chunk, bin) in the workspace ->
+// per-bin sums over its chunks, lane-strided then butterfly), so results are bit-reproducible;
+// no floating-point atomics are used.
+#include <type_traits>
+
 #include "fbsr_launch.h"
 
 namespace fbsr {
@@ -54,6 +57,8 @@ __device__ __forceinline__ double inv_ulp(uint32_t bits) {
   return __hiloint2double((int)hi, 0);
 }
 
+// The definition, in fp64, for any value (overflow, saturation, NaN, inputs with bits below the
+// code space's resolution).
 template <int FMT>
 __device__ __forceinline__ void accumulate(Acc& acc, uint32_t bits, uint32_t r) {
   const double y = (double)decode_top<FMT>(r);
@@ -63,104 +68,190 @@ __device__ __forceinline__ void accumulate(Acc& acc, uint32_t bits, uint32_t r) 
   acc.see = fma(e, e, acc.see);
 }
 
-// Same workgroup tile as the rounding kernel.  A tile touches at most two bins (the host
-// guarantees group >= tile): lane-local fp64 sums for the first (A) and second (B) bin, an
-// xor-butterfly across each wave, the four waves' sums staged in LDS and added in wave order,
-// one record per tile = {A.sy, A.se, A.see, B.sy, B.se, B.see}.
+// Per-thread partial sums of one bin.  In the common case (|x| <= M, and no input bit below the
+// code space's resolution) e 2^FRAC is the integer (rounded code << FRAC) - r0, so sum e and
+// sum e^2 are accumulated exactly in integers and only y takes an fp64 add per element; all
+// other values go through `accumulate` into `wide`.
+struct BinSums {
+  double sy;
+  int64_t se_fix;      // sum of e 2^FRAC
+  uint64_t see_fix;    // sum of (e 2^FRAC)^2
+  Acc wide;
+  __device__ __forceinline__ void clear() {
+    sy = 0.0; se_fix = 0; see_fix = 0; wide = {0.0, 0.0, 0.0};
+  }
+};
+
+// One workgroup per chunk of kStatsChunkTiles tiles.  Sums run in registers across the chunk's
+// tiles and are flushed (wave butterfly -> LDS -> record) when a bin ends and at the chunk's end:
+// record (chunk c, slot s) holds the chunk's part of bin floor(start(c) / group) + s.
 template <int FMT, int VAR, int W>
-__global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict__ x, void* __restrict__ out, int nbits,
-                                                        uint64_t seed, uint64_t blk0, uint64_t i0, uint64_t group,
+__global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict__ x, void* __restrict__ out,
+                                                        uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
+                                                        uint64_t i0, uint64_t group, uint64_t slots,
                                                         double* __restrict__ records) {
   typedef WgTile<W> T;
-  __shared__ uint4 strip[T::BLOCKS];
+  typedef Fx<FMT> F;
+  __shared__ uint4 strip[2][T::BLOCKS];
   __shared__ double staged[kWavesPerBlock][kStatsRecordDoubles];
+  __shared__ float lut[256];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
-  f32x4 v[kRows];
-#pragma unroll
-  for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
-  if constexpr (VAR != kRNE) {
-    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
-    __syncthreads();
-  }
+  constexpr uint32_t kFracMask = (1u << F::FRAC) - 1u;
+  if constexpr (F::kIsFp8) lut[threadIdx.x] = decode_top<FMT>((uint32_t)threadIdx.x << 24);   // all 256 signed codes
+
   const Addends a = make_addends<FMT, VAR>(nbits);
-  const uint64_t gi0 = i0 + (uint64_t)blockIdx.x * T::ELEMS;   // global index of the tile's first element
-  const uint64_t to_boundary = group - gi0 % group;           // tile-relative index where the second bin starts
-  const int boundary = to_boundary > (uint64_t)T::ELEMS ? T::ELEMS : (int)to_boundary;
-  Acc accA = {0.0, 0.0, 0.0}, accB = {0.0, 0.0, 0.0};
-  uint32_t r[kRows][4], b[kRows][4];
-#pragma unroll
-  for (int k = 0; k < kRows; ++k) {
-    uint64_t rb = 0;
-    if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip, wave, lane, k);
-    b[k][0] = __float_as_uint(v[k].x); b[k][1] = __float_as_uint(v[k].y);
-    b[k][2] = __float_as_uint(v[k].z); b[k][3] = __float_as_uint(v[k].w);
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      r[k][j] = round_pattern<FMT, VAR, true>(b[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
-    if (out != nullptr) {
-      const uint64_t row = row0 + (uint64_t)(k * 64);
-      if constexpr (Fx<FMT>::kIsFp8) {
-        reinterpret_cast<uint32_t*>(out)[row] = pack4_fp8<FMT>(r[k][0], r[k][1], r[k][2], r[k][3]);
-      } else {
-        reinterpret_cast<uint64_t*>(out)[row] =
-            (uint64_t)pack2_bf16(r[k][0], r[k][1]) | ((uint64_t)pack2_bf16(r[k][2], r[k][3]) << 32);
-      }
+  const uint64_t tile0 = (uint64_t)blockIdx.x * kStatsChunkTiles;
+  const uint64_t chunk_start = i0 + tile0 * T::ELEMS;
+  uint64_t next_bin = group - chunk_start % group;   // chunk-relative index at which the next bin starts
+  uint64_t slot = 0;
+  BinSums cur;
+  cur.clear();
+
+  auto flush = [&]() {
+    const double se = (double)cur.se_fix * (1.0 / (double)(1u << F::FRAC)) + cur.wide.se;
+    const double see = (double)cur.see_fix * (1.0 / ((double)(1u << F::FRAC) * (double)(1u << F::FRAC))) + cur.wide.see;
+    const double t0 = wave_sum(cur.sy + cur.wide.sy), t1 = wave_sum(se), t2 = wave_sum(see);
+    if (lane == 0) {
+      staged[wave][0] = t0; staged[wave][1] = t1; staged[wave][2] = t2;
     }
-  }
-  const int w_lo = wave * kWaveElems, w_hi = w_lo + kWaveElems;   // this wave's tile-relative range
-  if (boundary >= w_hi) {            // the whole wave lies in the first bin (wave-uniform, the common case)
+    __syncthreads();
+    if (threadIdx.x < kStatsRecordDoubles) {
+      double t = staged[0][threadIdx.x];
 #pragma unroll
-    for (int k = 0; k < kRows; ++k)
+      for (int wv = 1; wv < kWavesPerBlock; ++wv) t += staged[wv][threadIdx.x];
+      records[((uint64_t)blockIdx.x * slots + slot) * kStatsRecordDoubles + threadIdx.x] = t;
+    }
+    __syncthreads();
+    slot += 1;
+    cur.clear();
+  };
+
+#pragma unroll 1
+  for (int it = 0; it < kStatsChunkTiles; ++it) {
+    const uint64_t tile = tile0 + (uint64_t)it;
+    if (tile >= ntiles) break;   // uniform over the workgroup
+    const uint64_t row0 = tile * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+    f32x4 v[kRows];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) accumulate<FMT>(accA, b[k][j], r[k][j]);
-  } else if (boundary <= w_lo) {     // the whole wave lies in the second bin
+    for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
+    if constexpr (VAR != kRNE) fill_wg_bits<W>(strip[it & 1], threadIdx.x, blk0 + tile * T::BLOCKS, seed, 0);
+    // one barrier per tile: it also orders this fill after every wave's reads of two tiles ago
+    // (they precede that wave's arrival at the previous barrier) and publishes the decode table
+    __syncthreads();
+
+    uint32_t r0[kRows][4], rm[kRows][4], b[kRows][4];
+    uint64_t rb[kRows];
+    uint32_t bad = 0;
 #pragma unroll
-    for (int k = 0; k < kRows; ++k)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) accumulate<FMT>(accB, b[k][j], r[k][j]);
-  } else {                           // the bin boundary falls inside this wave's elements
-#pragma unroll
-    for (int k = 0; k < kRows; ++k)
+    for (int k = 0; k < kRows; ++k) {
+      rb[k] = 0;
+      if constexpr (VAR != kRNE) rb[k] = read_wg_row_bits<W>(strip[it & 1], wave, lane, k);
+      b[k][0] = __float_as_uint(v[k].x); b[k][1] = __float_as_uint(v[k].y);
+      b[k][2] = __float_as_uint(v[k].z); b[k][3] = __float_as_uint(v[k].w);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int e = w_lo + k * 256 + 4 * lane + j;
-        if (e < boundary) accumulate<FMT>(accA, b[k][j], r[k][j]);
-        else accumulate<FMT>(accB, b[k][j], r[k][j]);
+        const uint32_t u = b[k][j] & 0x7FFFFFFFu;
+        bad |= (u > F::U_MAXFIN) ? 1u : 0u;
+        if constexpr (F::U_EXACT != 0) bad |= (u - 1u < F::U_EXACT - 1u) ? 1u : 0u;   // 0 < u < U_EXACT
       }
-  }
-  const double s0 = wave_sum(accA.sy), s1 = wave_sum(accA.se), s2 = wave_sum(accA.see);
-  const double s3 = wave_sum(accB.sy), s4 = wave_sum(accB.se), s5 = wave_sum(accB.see);
-  if (lane == 0) {
-    staged[wave][0] = s0; staged[wave][1] = s1; staged[wave][2] = s2;
-    staged[wave][3] = s3; staged[wave][4] = s4; staged[wave][5] = s5;
-  }
-  __syncthreads();
-  if (threadIdx.x < kStatsRecordDoubles) {
-    double t = staged[0][threadIdx.x];
+    }
+    // wave-uniform: does any element need the fp64 definition (|x| > M, NaN, bits below the code
+    // space's resolution)?  If not, the unchecked rounding add is allowed as well.
+    const bool wide_path = __any(bad);
 #pragma unroll
-    for (int wv = 1; wv < kWavesPerBlock; ++wv) t += staged[wv][threadIdx.x];
-    records[(uint64_t)blockIdx.x * kStatsRecordDoubles + threadIdx.x] = t;
+    for (int k = 0; k < kRows; ++k)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) r0[k][j] = to_code_space<FMT, VAR>(b[k][j]);
+    if (wide_path) {
+#pragma unroll
+      for (int k = 0; k < kRows; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          rm[k][j] = round_magnitude<FMT, VAR, true>(b[k][j], r0[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb[k], j, a.nbits), a);
+    } else {
+#pragma unroll
+      for (int k = 0; k < kRows; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          rm[k][j] = round_magnitude<FMT, VAR, false>(b[k][j], r0[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb[k], j, a.nbits), a);
+    }
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) {
+      if (out != nullptr) {
+        const uint64_t row = row0 + (uint64_t)(k * 64);
+        uint32_t s[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s[j] = rm[k][j] | (b[k][j] & 0x80000000u);
+        if constexpr (F::kIsFp8) {
+          reinterpret_cast<uint32_t*>(out)[row] = pack4_fp8<FMT>(s[0], s[1], s[2], s[3]);
+        } else {
+          reinterpret_cast<uint64_t*>(out)[row] = (uint64_t)pack2_bf16(s[0], s[1]) | ((uint64_t)pack2_bf16(s[2], s[3]) << 32);
+        }
+      }
+    }
+
+    // adds the elements whose tile-relative index lies in [lo, hi) to `cur`; ALL = the whole tile
+    auto add_range = [&](auto all_tag, int lo, int hi) {
+      constexpr bool ALL = decltype(all_tag)::value;
+      const int w_lo = wave * kWaveElems;
+      int32_t se32 = 0;   // at most 8 terms below 2^FRAC in magnitude
+#pragma unroll
+      for (int k = 0; k < kRows; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int e = w_lo + k * 256 + 4 * lane + j;
+          const bool in = ALL || (e >= lo && e < hi);
+          const uint32_t signed_r = rm[k][j] | (b[k][j] & 0x80000000u);
+          if (wide_path) {
+            if (in) accumulate<FMT>(cur.wide, b[k][j], signed_r);
+          } else {
+            float y;
+            if constexpr (F::kIsFp8) y = lut[signed_r >> 24];
+            else y = __uint_as_float(signed_r & 0xFFFF0000u);
+            int32_t d = (int32_t)((rm[k][j] & ~kFracMask) - r0[k][j]);   // (|y| - |x|) / ulp_t, times 2^FRAC
+            const int32_t sgn = (int32_t)b[k][j] >> 31;                  // y - x = -(|y| - |x|) for negative x
+            if constexpr (!ALL) {
+              d = in ? d : 0;
+              y = in ? y : 0.0f;
+            }
+            cur.sy += (double)y;
+            se32 += (d ^ sgn) - sgn;
+            cur.see_fix += (uint64_t)((int64_t)d * (int64_t)d);
+          }
+        }
+      cur.se_fix += (int64_t)se32;
+    };
+
+    const uint64_t t_lo = (uint64_t)it * T::ELEMS, t_hi = t_lo + T::ELEMS;   // chunk-relative range of this tile
+    if (next_bin >= t_hi) {
+      add_range(std::true_type{}, 0, T::ELEMS);
+    } else {                       // a bin ends inside this tile (at most once: group >= tile)
+      const int cut = (int)(next_bin - t_lo);
+      add_range(std::false_type{}, 0, cut);
+      flush();
+      add_range(std::false_type{}, cut, T::ELEMS);
+      next_bin += group;
+    }
   }
+  flush();
 }
 
-// One wave per bin: sums the records of the tiles that overlap the bin and adds the bin's
-// totals to the caller's statistics.  Tiles cover global indices [i0, i0 + ntiles * tile_elems).
-__global__ __launch_bounds__(64) void stats_finalize(const double* __restrict__ records, uint64_t ntiles,
-                                                     uint64_t tile_elems, uint64_t i0, uint64_t group,
+// One wave per bin: sums the records of the chunks that overlap the bin and adds the bin's totals
+// to the caller's statistics.  Chunks cover global indices [i0, i_end).
+__global__ __launch_bounds__(64) void stats_finalize(const double* __restrict__ records, uint64_t i0, uint64_t i_end,
+                                                     uint64_t chunk_elems, uint64_t slots, uint64_t group,
                                                      uint64_t bin_lo, uint64_t first_bin, double* __restrict__ stats) {
   const int lane = threadIdx.x;
   const uint64_t bin = bin_lo + blockIdx.x;
-  const uint64_t i_end = i0 + ntiles * tile_elems;
   const uint64_t lo = bin * group > i0 ? bin * group : i0;
   const uint64_t hi = (bin + 1) * group < i_end ? (bin + 1) * group : i_end;
   if (lo >= hi) return;
-  const uint64_t t_lo = (lo - i0) / tile_elems, t_hi = (hi - 1 - i0) / tile_elems;
+  const uint64_t c_lo = (lo - i0) / chunk_elems, c_hi = (hi - 1 - i0) / chunk_elems;
   double sy = 0.0, se = 0.0, see = 0.0;
-  for (uint64_t t = t_lo + (uint64_t)lane; t <= t_hi; t += 64) {
-    // the tile's first bin is this bin iff the tile starts inside it
-    const double* rec = records + t * kStatsRecordDoubles + ((i0 + t * tile_elems >= bin * group) ? 0 : 3);
+  for (uint64_t c = c_lo + (uint64_t)lane; c <= c_hi; c += 64) {
+    const uint64_t first = (i0 + c * chunk_elems) / group;   // the bin of the chunk's slot 0
+    const double* rec = records + (c * slots + (bin - first)) * kStatsRecordDoubles;
     sy += rec[0];
     se += rec[1];
     see += rec[2];
@@ -213,8 +304,9 @@ namespace {
 template <int FMT, int VAR, int W>
 hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
                         uint64_t i0, uint64_t group, double* records, hipStream_t stream) {
-  hipLaunchKernelGGL((stats_tiles<FMT, VAR, W>), dim3((unsigned)ntiles), dim3(kThreads), 0, stream, x, out, nbits, seed,
-                     blk0, i0, group, records);
+  const uint64_t chunks = (ntiles + kStatsChunkTiles - 1) / kStatsChunkTiles;
+  hipLaunchKernelGGL((stats_tiles<FMT, VAR, W>), dim3((unsigned)chunks), dim3(kThreads), 0, stream, x, out, ntiles,
+                     nbits, seed, blk0, i0, group, stats_slots(group), records);
   return hipGetLastError();
 }
 
@@ -269,8 +361,9 @@ hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, 
                                  i0 / (uint64_t)(128 / W), i0, group, workspace, stream);
     if (e != hipSuccess) return e;
     const uint64_t bin_lo = i0 / group, bin_hi = (i0 + s.ntiles * s.tile_elems - 1) / group;
-    hipLaunchKernelGGL(stats_finalize, dim3((unsigned)(bin_hi - bin_lo + 1)), dim3(64), 0, stream, workspace, s.ntiles,
-                       s.tile_elems, i0, group, bin_lo, first_bin, stats);
+    hipLaunchKernelGGL(stats_finalize, dim3((unsigned)(bin_hi - bin_lo + 1)), dim3(64), 0, stream, workspace, i0,
+                       i0 + s.ntiles * s.tile_elems, (uint64_t)kStatsChunkTiles * s.tile_elems, stats_slots(group), group,
+                       bin_lo, first_bin, stats);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
