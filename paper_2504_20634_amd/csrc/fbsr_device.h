@@ -259,6 +259,75 @@ __device__ __forceinline__ uint32_t slot_bits(uint64_t row_bits, int j, uint32_t
   }
 }
 
+// ------------------------------------------------- hardware stochastic-rounding converts ---
+// gfx950 has v_cvt_sr_fp8_f32 / v_cvt_sr_bf8_f32 (OCP E4M3 / E5M2): they add the TOP bits of a
+// 32-bit random operand to the bits the conversion drops (however many those are: target
+// subnormals included) and truncate.  Feeding  n << (32 - N)  therefore is SRFF, and
+// (n << (32 - N)) | (1 << (31 - N))  is SRF; SRC first rounds |x| to P + N significant bits
+// (nearest-even, on the clamped-exponent grid of Eq. (2)) with a magic-constant float add.
+// Verified against the CPU oracle on every fp32 pattern; what the instructions do OUTSIDE the
+// finite range differs from this library's readings and is steered here:
+//   E4M3: above 448 they return NaN  -> the input is clamped to +-448 first (saturation);
+//   E5M2: in (M, 65536) they round stochastically between M and inf -> the random operand is
+//         replaced by one half, which gives M below 61440 and inf from there on;
+//   NaN comes back with the sign bit set -> NaN inputs never reach this path (the caller's
+//         wave-uniform check sends them to the integer path).
+struct HwAddends {
+  uint32_t nbits;     // N
+  uint32_t shift;     // 32 - N
+  uint32_t half;      // SRF: 1 << (31 - N), else 0
+  uint32_t grid_exp;  // SRC: (24 - P - N) << 23, the exponent offset of the magic constant
+};
+
+template <int FMT, int VAR>
+__device__ __forceinline__ HwAddends make_hw_addends(int nbits) {
+  HwAddends h;
+  h.nbits = (uint32_t)nbits;
+  h.shift = 32u - h.nbits;
+  h.half = VAR == kSRF ? (1u << (31u - h.nbits)) : 0u;
+  h.grid_exp = (uint32_t)(24 - Fx<FMT>::P - nbits) << 23;
+  return h;
+}
+
+// Four fp32 patterns -> four packed fp8 codes (element 0 in the low byte).  None may be a NaN.
+template <int FMT, int VAR, int W>
+__device__ __forceinline__ uint32_t round4_fp8_hw(const uint32_t (&bits)[4], uint64_t row_bits, const HwAddends& h) {
+  typedef Fx<FMT> F;
+  static_assert(F::kIsFp8 && VAR != kRNE, "hardware path: fp8 targets, stochastic variants");
+  int packed = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float x = __uint_as_float(bits[j]);
+    uint32_t rnd = (slot_bits<W>(row_bits, j, h.nbits) << h.shift) | h.half;
+    if constexpr (FMT == kE4M3) x = __builtin_amdgcn_fmed3f(x, -448.0f, 448.0f);
+    bool over = false;
+    if constexpr (FMT == kE5M2) over = fabsf(x) > 57344.0f;
+    if constexpr (VAR == kSRC) {
+      // C = 2^(e~ + 24 - P - N): adding and subtracting it rounds |x| to a multiple of
+      // 2^(e~ - (P - 1) - N), nearest-even (the inner Round of Eq. (7))
+      const uint32_t ef = __float_as_uint(x) & 0x7F800000u;   // after the clamp
+      const uint32_t c_bits = (ef > F::U_SUB ? ef : F::U_SUB) + h.grid_exp;
+      const float c = __uint_as_float(c_bits);
+      const float t = (fabsf(x) + c) - c;
+      const float pre = __uint_as_float((__float_as_uint(t) & 0x7FFFFFFFu) | (bits[j] & 0x80000000u));
+      x = over ? x : pre;
+    }
+    if constexpr (FMT == kE5M2) rnd = over ? 0x80000000u : rnd;
+    if constexpr (FMT == kE4M3) {
+      if (j == 0) packed = __builtin_amdgcn_cvt_sr_fp8_f32(x, (int)rnd, packed, 0);
+      if (j == 1) packed = __builtin_amdgcn_cvt_sr_fp8_f32(x, (int)rnd, packed, 1);
+      if (j == 2) packed = __builtin_amdgcn_cvt_sr_fp8_f32(x, (int)rnd, packed, 2);
+      if (j == 3) packed = __builtin_amdgcn_cvt_sr_fp8_f32(x, (int)rnd, packed, 3);
+    } else {
+      if (j == 0) packed = __builtin_amdgcn_cvt_sr_bf8_f32(x, (int)rnd, packed, 0);
+      if (j == 1) packed = __builtin_amdgcn_cvt_sr_bf8_f32(x, (int)rnd, packed, 1);
+      if (j == 2) packed = __builtin_amdgcn_cvt_sr_bf8_f32(x, (int)rnd, packed, 2);
+      if (j == 3) packed = __builtin_amdgcn_cvt_sr_bf8_f32(x, (int)rnd, packed, 3);
+    }
+  }
+  return (uint32_t)packed;
+}
+
 // Random integer of ONE element with global index i (the per-element kernels).
 __device__ __forceinline__ uint32_t element_bits(uint64_t i, int log2_per_block, int W, uint32_t nbits,
                                                  uint64_t seed, uint64_t step) {

@@ -24,6 +24,8 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
     __syncthreads();
   }
   const Addends a = make_addends<FMT, VAR>(nbits);
+  HwAddends hw = {0, 0, 0, 0};
+  if constexpr (Fx<FMT>::kIsFp8 && VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
   uint32_t umax = 0;
 #pragma unroll
   for (int k = 0; k < kRows; ++k) {
@@ -37,6 +39,13 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
     if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip, wave, lane, k);
     const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
                            __float_as_uint(v[k].w)};
+    const uint64_t row = row0 + (uint64_t)(k * 64);
+    if constexpr (Fx<FMT>::kIsFp8 && VAR != kRNE) {
+      if (!checked) {   // no NaN among the wave's elements: the hardware converts apply
+        __builtin_nontemporal_store(round4_fp8_hw<FMT, VAR, W>(b, rb, hw), reinterpret_cast<uint32_t*>(out) + row);
+        continue;
+      }
+    }
     uint32_t r[4];
     if (checked) {
 #pragma unroll
@@ -47,7 +56,6 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
       for (int j = 0; j < 4; ++j)
         r[j] = round_pattern<FMT, VAR, false>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
     }
-    const uint64_t row = row0 + (uint64_t)(k * 64);
     if constexpr (Fx<FMT>::kIsFp8) {
       __builtin_nontemporal_store(pack4_fp8<FMT>(r[0], r[1], r[2], r[3]), reinterpret_cast<uint32_t*>(out) + row);
     } else {

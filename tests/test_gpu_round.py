@@ -116,3 +116,37 @@ def test_runs_on_a_side_stream(fbsr, oracle):
         out = fbsr.fbsr_round(xd, E5M2, SRC, 5, seed=4, offset=0, stream=s)
     s.synchronize()
     assert first_mismatch(host(out), oracle.round_(x, E5M2, SRC, 5, seed=4)) is None
+
+
+@pytest.mark.parametrize("fmt,variant,nbits", [(E4M3, SRFF, 8), (E5M2, SRF, 4), (E4M3, SRC, 3), (E5M2, SRC, 8),
+                                               (E5M2, SRFF, 2), (E4M3, SRF, 16)])
+def test_every_fp32_pattern(fbsr, oracle, fmt, variant, nbits):
+    """All 2^32 input patterns (every normal, subnormal, zero, infinity and NaN of both signs), in
+    16 slabs of 2^28 consecutive patterns, through the tile kernel: byte-identical to the oracle.
+    This is what licenses the hardware stochastic-rounding converts inside the fp8 tile kernel."""
+    slab = 1 << 28
+    for s_no in range(16):
+        base = s_no * slab
+        bits = np.arange(base, base + slab, dtype=np.uint32)
+        x = bits.view(np.float32)
+        xd = torch.arange(base - (1 << 32) if base >= (1 << 31) else base,
+                          (base - (1 << 32) if base >= (1 << 31) else base) + slab,
+                          dtype=torch.int64, device="cuda").to(torch.int32).view(torch.float32)
+        got = host(fbsr.fbsr_round(xd, fmt, variant, nbits, seed=77, offset=base))
+        del xd
+        want = oracle.round_(x, fmt, variant, nbits, seed=77, offset=base, nthreads=16)
+        print("case fmt=%d variant=%d nbits=%d slab=%d" % (fmt, variant, nbits, s_no), flush=True)
+        assert first_mismatch(got, want) is None, (s_no, first_mismatch(got, want))
+
+
+def test_fp32_subnormal_inputs_to_fp8(fbsr, oracle):
+    """fp32 subnormals and the smallest normals are ordinary (tiny) values for the fp8 targets."""
+    rng = np.random.default_rng(5)
+    n = 3 * 2048 + 40
+    bits = rng.integers(0, 1 << 25, n, dtype=np.uint32) | (rng.integers(0, 2, n, dtype=np.uint32) << np.uint32(31))
+    x = bits.view(np.float32)
+    xd = dev(x)
+    for fmt in (E4M3, E5M2):
+        for variant, nbits in ((SRFF, 4), (SRF, 8), (SRC, 2), (RNE, 0)):
+            got = host(fbsr.fbsr_round(xd, fmt, variant, nbits, seed=1))
+            assert first_mismatch(got, oracle.round_(x, fmt, variant, nbits, seed=1)) is None
