@@ -164,6 +164,18 @@ def main():
             ms = timed_launches(torch, lambda: fbsr.fbsr_round(x_dev[fbsr.FMT_E5M2], fbsr.FMT_BF16, fbsr.SRF, nb, 2, 0, out=out16), 10)
             paths["round_bf16_N%d_srf" % nb] = {"ms": round(ms, 4), "gb_s": round(6.0 * n / ms / 1e6, 1)}
         del out16
+        # narrow-source rounding (bf16 -> fp8, 3 B/element), N = 3 as in the paper's experiments
+        x16 = [torch.from_numpy(workloads.sgd_weights(n, seed=30 + k).view(np.int16)).cuda() for k in range(3)]
+        rot16 = [0]
+
+        def from16(f, v, nb):
+            rot16[0] += 1
+            fbsr.fbsr_round_from16(x16[rot16[0] % 3], fbsr.SRC_BF16, f, v, nb, seed=2, offset=0, out=out_rot[rot16[0] % 4])
+        for f, v, nb in ((fbsr.FMT_E4M3, fbsr.SRC, 3), (fbsr.FMT_E5M2, fbsr.SRF, 3), (fbsr.FMT_E4M3, fbsr.SRFF, 8)):
+            ms = timed_launches(torch, lambda: from16(f, v, nb), 12)
+            paths["round_from_bf16_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
+                "ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
+        del x16
         ns = min(SGD_ELEMS, n)
         # rotate through 3 weight and 3 gradient buffers (2.25 GiB) so the last-level cache cannot help
         ws_ = [torch.from_numpy(workloads.sgd_weights(ns, seed=3 + k).view(np.int16)).cuda() for k in range(3)]

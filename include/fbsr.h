@@ -61,6 +61,12 @@ typedef enum {
 
 #define FBSR_MAX_NBITS 16
 
+/* 16-bit source formats of fbsr_round_from16. */
+typedef enum {
+  FBSR_SRC_BF16 = 0, /* K=16 P=8  B=127 */
+  FBSR_SRC_FP16 = 1  /* IEEE binary16: K=16 P=11 B=15 */
+} fbsr_src16;
+
 /* Rounds n fp32 values to `fmt`:  out[j] = FBSR(x[j]; bits of global element offset + j,
  * stream (seed, step = 0)).
  *   Sign-magnitude: |x| is rounded and the sign re-applied (the paper rounds positive values),
@@ -74,6 +80,16 @@ typedef enum {
  * FBSR_EDEVICE. */
 int fbsr_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits,
                uint64_t seed, uint64_t offset, void* stream);
+
+/* Narrow-source rounding, the paper's own setting (Sec. III-E: inputs of precision Q = P + D with
+ * few excess bits D; Fig. 2: bf16 -> a precision-3 target, D = 5; Sec. IV: bf16 updates -> an 8-bit
+ * format): out[j] = FBSR(value of x[j]) exactly as fbsr_round, with the 16-bit source value taken
+ * exactly (bf16 -> E4M3 has D = 4, bf16 -> E5M2 D = 5, binary16 -> E4M3 D = 7, binary16 -> E5M2
+ * D = 8).  nbits may exceed D; all variants then coincide with exact SR (App. A-C).
+ * x: n 16-bit codes of src_fmt (device, read, 2-byte aligned).  out: n fp8 codes (device, written).
+ * fmt must be FBSR_FMT_E4M3 or FBSR_FMT_E5M2 (else FBSR_EINVAL).  Other errors as fbsr_round. */
+int fbsr_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt, int variant, int nbits,
+                      uint64_t seed, uint64_t offset, void* stream);
 
 /* The weight update of Alg. 1 ("w <- RoundTo(w + u), SR applied here") fused into one pass,
  * in SGD form:  w[j] <- FBSR_bf16( fma(-lr, g[j], float(w[j])) )  with the bits of

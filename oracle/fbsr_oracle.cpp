@@ -61,7 +61,8 @@ struct Format {
   uint32_t inf_code;  // +inf (unused when !has_inf)
 };
 
-enum { FMT_BF16 = 0, FMT_E4M3 = 1, FMT_E5M2 = 2 };
+enum { FMT_BF16 = 0, FMT_E4M3 = 1, FMT_E5M2 = 2, FMT_FP16 = 3 };   // FP16: IEEE binary16, used as a SOURCE format
+enum { SRC_BF16 = 0, SRC_FP16 = 1 };
 enum { VAR_RNE = 0, VAR_SRFF = 1, VAR_SRF = 2, VAR_SRC = 3 };
 
 bool get_format(int fmt, Format* f) {
@@ -74,6 +75,9 @@ bool get_format(int fmt, Format* f) {
       return true;
     case FMT_E5M2:  // OCP E5M2: IEEE-like, max 1.75 * 2^15
       *f = Format{8, 3, 15, 57344.0, true, 0x7Eu, 0x7Cu};
+      return true;
+    case FMT_FP16:  // IEEE binary16: (2 - 2^-10) * 2^15
+      *f = Format{16, 11, 15, 65504.0, true, 0x7E00u, 0x7C00u};
       return true;
   }
   return false;
@@ -214,6 +218,17 @@ uint64_t random_bits(uint64_t seed, uint64_t step, uint64_t i, int N) {
   return (word >> (bit % 32)) & mask;
 }
 
+// The exact fp32 value of a 16-bit source code (bf16 or IEEE binary16) by Eq. (1); every such
+// value is representable in fp32.  The sign of zeros, infinities and NaNs is kept.
+float widen16(uint16_t code, int src_fmt) {
+  Format f;
+  get_format(src_fmt == SRC_BF16 ? FMT_BF16 : FMT_FP16, &f);
+  const double v = decode(code, f);
+  const bool neg = (code >> 15) & 1u;
+  if (std::isnan(v)) return std::copysign(std::numeric_limits<float>::quiet_NaN(), neg ? -1.0f : 1.0f);
+  return (float)v;   // exact (at most 11 significant bits, exponent within fp32's range); -0.0 stays -0.0
+}
+
 float bf16_to_float(uint16_t w) {
   const uint32_t bits = (uint32_t)w << 16;
   float f;
@@ -320,6 +335,29 @@ int oracle_round_threads(const float* x, void* out, uint64_t n, int fmt, int var
   }
   for (auto& th : pool) th.join();
   return 0;
+}
+
+// Narrow-source rounding (Sec. III-E: inputs of precision Q = P + D with few excess bits D, e.g.
+// bf16 -> E5M2 has D = 5; Fig. 2): the 16-bit source value is taken exactly and rounded as in
+// oracle_round.  x: n codes of src_fmt (0 = bf16, 1 = IEEE binary16); fmt: E4M3 or E5M2.
+int oracle_round_from16(const uint16_t* x, void* out, uint64_t n, int src_fmt, int fmt, int variant,
+                        int nbits, uint64_t seed, uint64_t offset) {
+  Format f;
+  if (!args_ok(fmt, variant, nbits, &f)) return 1;
+  if ((src_fmt != SRC_BF16 && src_fmt != SRC_FP16) || (fmt != FMT_E4M3 && fmt != FMT_E5M2)) return 1;
+  for (uint64_t j = 0; j < n; ++j) {
+    const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, 0, offset + j, nbits);
+    store_code(out, j, round_one(widen16(x[j], src_fmt), f, variant, nbits, r), f);
+  }
+  return 0;
+}
+
+// The fp32 bit pattern of widen16 (for pinning the widening against a library view).
+uint32_t oracle_widen16(uint16_t code, int src_fmt) {
+  const float v = widen16(code, src_fmt);
+  uint32_t bits;
+  std::memcpy(&bits, &v, 4);
+  return bits;
 }
 
 // Alg. 1's "w <- RoundTo(w + u)" in the SGD form u = -lr * g: the bf16 weight is

@@ -14,6 +14,7 @@ SOURCE = os.path.join(_HERE, "fbsr_oracle.cpp")
 LIB = os.path.join(_HERE, "liboracle_fbsr.so")
 
 FMT_BF16, FMT_E4M3, FMT_E5M2 = 0, 1, 2
+SRC_BF16, SRC_FP16 = 0, 1
 RNE, SRFF, SRF, SRC = 0, 1, 2, 3
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
@@ -55,6 +56,10 @@ def lib():
         L.oracle_round.restype = i32
         L.oracle_round_threads.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, i32]
         L.oracle_round_threads.restype = i32
+        L.oracle_round_from16.argtypes = [vp, vp, u64, i32, i32, i32, i32, u64, u64]
+        L.oracle_round_from16.restype = i32
+        L.oracle_widen16.argtypes = [ctypes.c_uint16, i32]
+        L.oracle_widen16.restype = u32
         L.oracle_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64]
         L.oracle_sgd_update.restype = i32
         L.oracle_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp]
@@ -119,6 +124,21 @@ def round_(x, fmt, variant, nbits, seed, offset=0, nthreads=1):
     if rc != 0:
         raise ValueError("oracle_round: status %d" % rc)
     return out
+
+
+def round_from16(x, src_fmt, fmt, variant, nbits, seed, offset=0):
+    """x: uint16 codes of the source format (0 = bf16, 1 = IEEE binary16) -> fp8 codes."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    out = np.empty(x.size, dtype=np.uint8)
+    rc = lib().oracle_round_from16(_ptr(x), _ptr(out), x.size, src_fmt, fmt, variant, nbits, seed, offset)
+    if rc != 0:
+        raise ValueError("oracle_round_from16: status %d" % rc)
+    return out
+
+
+def widen16(code, src_fmt):
+    """fp32 bit pattern of the exact value of a 16-bit source code."""
+    return int(lib().oracle_widen16(int(code), src_fmt))
 
 
 def sgd_update(w, g, lr, variant, nbits, seed, step, offset=0):

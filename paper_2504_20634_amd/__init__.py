@@ -1,8 +1,9 @@
 """Few-bit stochastic rounding (arXiv 2504.20634) for AMD MI355X: a C-ABI HIP library
 (include/fbsr.h, built into paper_2504_20634_amd/libfbsr.so) and this thin ctypes binding."""
 from . import binding
-from .binding import (FMT_BF16, FMT_E4M3, FMT_E5M2, RNE, SRFF, SRF, SRC, FbsrError,
-                      bias_stats_workspace_bytes, fbsr_bias_stats, fbsr_round, fbsr_sgd_update)
+from .binding import (FMT_BF16, FMT_E4M3, FMT_E5M2, RNE, SRFF, SRF, SRC, SRC_BF16, SRC_FP16, FbsrError,
+                      bias_stats_workspace_bytes, fbsr_bias_stats, fbsr_round, fbsr_round_from16,
+                      fbsr_sgd_update)
 
-__all__ = ["binding", "FMT_BF16", "FMT_E4M3", "FMT_E5M2", "RNE", "SRFF", "SRF", "SRC", "FbsrError",
-           "bias_stats_workspace_bytes", "fbsr_bias_stats", "fbsr_round", "fbsr_sgd_update"]
+__all__ = ["binding", "FMT_BF16", "FMT_E4M3", "FMT_E5M2", "RNE", "SRFF", "SRF", "SRC", "SRC_BF16", "SRC_FP16", "FbsrError",
+           "bias_stats_workspace_bytes", "fbsr_bias_stats", "fbsr_round", "fbsr_round_from16", "fbsr_sgd_update"]

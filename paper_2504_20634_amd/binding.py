@@ -12,11 +12,12 @@ LIB_PATH = os.path.join(_HERE, "libfbsr.so")
 
 FMT_BF16, FMT_E4M3, FMT_E5M2 = 0, 1, 2
 RNE, SRFF, SRF, SRC = 0, 1, 2, 3
+SRC_BF16, SRC_FP16 = 0, 1
 OK, EINVAL, EALIGN, ERANGE, EDEVICE = 0, 1, 2, 3, 4
 MAX_NBITS = 16
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
-EXPORTS = ("fbsr_round", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
+EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
            "fbsr_strerror", "fbsr_version")
 
 
@@ -41,6 +42,8 @@ def lib():
                                   ctypes.c_void_p)
         L.fbsr_round.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, vp]
         L.fbsr_round.restype = i32
+        L.fbsr_round_from16.argtypes = [vp, vp, u64, i32, i32, i32, i32, u64, u64, vp]
+        L.fbsr_round_from16.restype = i32
         L.fbsr_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64, vp]
         L.fbsr_sgd_update.restype = i32
         L.fbsr_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp, vp, u64, vp]
@@ -88,6 +91,20 @@ def fbsr_round(x, fmt, variant, nbits, seed, offset=0, out=None, stream=None):
     assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.dtype == code_dtype(fmt)
     _check(lib().fbsr_round(x.data_ptr(), out.data_ptr(), n, fmt, variant, nbits, seed, offset,
                             _stream_handle(stream)), "fbsr_round")
+    return out
+
+
+def fbsr_round_from16(x, src_fmt, fmt, variant, nbits, seed, offset=0, out=None, stream=None):
+    """Narrow-source rounding: x holds 16-bit codes of src_fmt (SRC_BF16 / SRC_FP16) as a uint16 /
+    int16 / bfloat16 / float16 CUDA tensor; returns the fp8 code tensor (uint8)."""
+    import torch
+    assert x.is_cuda and x.element_size() == 2 and x.is_contiguous()
+    n = x.numel()
+    if out is None:
+        out = torch.empty(n, dtype=torch.uint8, device=x.device)
+    assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.dtype == torch.uint8
+    _check(lib().fbsr_round_from16(x.data_ptr(), out.data_ptr(), n, src_fmt, fmt, variant, nbits, seed,
+                                   offset, _stream_handle(stream)), "fbsr_round_from16")
     return out
 
 

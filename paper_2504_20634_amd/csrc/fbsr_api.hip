@@ -35,6 +35,20 @@ int fbsr_round(const float* x, void* out, uint64_t n, int fmt, int variant, int 
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 
+int fbsr_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt, int variant, int nbits,
+                      uint64_t seed, uint64_t offset, void* stream) {
+  if (fmt != FBSR_FMT_E4M3 && fmt != FBSR_FMT_E5M2) return FBSR_EINVAL;
+  if (src_fmt != FBSR_SRC_BF16 && src_fmt != FBSR_SRC_FP16) return FBSR_EINVAL;
+  const int c = check_common(variant, nbits, n, offset);
+  if (c != FBSR_OK) return c;
+  if (n == 0) return FBSR_OK;
+  if (x == nullptr || out == nullptr) return FBSR_EINVAL;
+  if (misaligned(x, 2)) return FBSR_EALIGN;
+  const hipError_t e = fbsr::launch_round_from16(x, out, n, src_fmt, fmt, variant, nbits, seed, offset,
+                                                 reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
 int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, int nbits, uint64_t seed,
                     uint64_t step, uint64_t offset, void* stream) {
   const int c = check_common(variant, nbits, n, offset);

@@ -249,6 +249,31 @@ __device__ __forceinline__ uint64_t read_wg_row_bits(const uint4* strip, int wav
   }
 }
 
+// The random integers of EIGHT consecutive elements starting at tile-relative element e0 (a
+// multiple of 8): the 16-bit-source kernels give every lane one 16-byte load of 8 elements.
+template <int W>
+__device__ __forceinline__ void read_wg_bits8(const uint4* strip, int e0, uint32_t nbits, uint32_t (&n)[8]) {
+  const unsigned char* base = reinterpret_cast<const unsigned char*>(strip);
+  if constexpr (W == 16) {
+    const uint4 q = *reinterpret_cast<const uint4*>(base + e0 * 2);
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) n[j] = __builtin_amdgcn_ubfe(w[j >> 1], (uint32_t)(16 * (j & 1)), nbits);
+  } else if constexpr (W == 8) {
+    const uint2 q = *reinterpret_cast<const uint2*>(base + e0);
+    const uint32_t w[2] = {q.x, q.y};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) n[j] = __builtin_amdgcn_ubfe(w[j >> 2], (uint32_t)(8 * (j & 3)), nbits);
+  } else {
+    uint32_t w;
+    if constexpr (W == 4) w = *reinterpret_cast<const uint32_t*>(base + e0 / 2);
+    else if constexpr (W == 2) w = *reinterpret_cast<const uint16_t*>(base + e0 / 4);
+    else w = base[e0 / 8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) n[j] = __builtin_amdgcn_ubfe(w, (uint32_t)(j * W), nbits);
+  }
+}
+
 template <int W>
 __device__ __forceinline__ uint32_t slot_bits(uint64_t row_bits, int j, uint32_t nbits) {
   if constexpr (W == 16) {
@@ -289,16 +314,17 @@ __device__ __forceinline__ HwAddends make_hw_addends(int nbits) {
   return h;
 }
 
-// Four fp32 patterns -> four packed fp8 codes (element 0 in the low byte).  None may be a NaN.
-template <int FMT, int VAR, int W>
-__device__ __forceinline__ uint32_t round4_fp8_hw(const uint32_t (&bits)[4], uint64_t row_bits, const HwAddends& h) {
+// Four fp32 patterns and their random integers -> four packed fp8 codes (element 0 in the low
+// byte).  None of the patterns may be a NaN.
+template <int FMT, int VAR>
+__device__ __forceinline__ uint32_t round4_fp8_hw(const uint32_t (&bits)[4], const uint32_t (&n)[4], const HwAddends& h) {
   typedef Fx<FMT> F;
   static_assert(F::kIsFp8 && VAR != kRNE, "hardware path: fp8 targets, stochastic variants");
   int packed = 0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     float x = __uint_as_float(bits[j]);
-    uint32_t rnd = (slot_bits<W>(row_bits, j, h.nbits) << h.shift) | h.half;
+    uint32_t rnd = (n[j] << h.shift) | h.half;
     if constexpr (FMT == kE4M3) x = __builtin_amdgcn_fmed3f(x, -448.0f, 448.0f);
     bool over = false;
     if constexpr (FMT == kE5M2) over = fabsf(x) > 57344.0f;

@@ -60,6 +60,9 @@ constexpr uint64_t kMaxElems = (uint64_t)1 << 40;
 hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                         uint64_t offset, hipStream_t stream);
 
+hipError_t launch_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt, int variant, int nbits,
+                               uint64_t seed, uint64_t offset, hipStream_t stream);
+
 hipError_t launch_sgd(void* w, const float* g, uint64_t n, float lr, int variant, int nbits, uint64_t seed,
                       uint64_t step, uint64_t offset, hipStream_t stream);
 

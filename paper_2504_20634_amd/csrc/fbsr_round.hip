@@ -42,7 +42,9 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
     const uint64_t row = row0 + (uint64_t)(k * 64);
     if constexpr (Fx<FMT>::kIsFp8 && VAR != kRNE) {
       if (!checked) {   // no NaN among the wave's elements: the hardware converts apply
-        __builtin_nontemporal_store(round4_fp8_hw<FMT, VAR, W>(b, rb, hw), reinterpret_cast<uint32_t*>(out) + row);
+        const uint32_t n4[4] = {slot_bits<W>(rb, 0, a.nbits), slot_bits<W>(rb, 1, a.nbits), slot_bits<W>(rb, 2, a.nbits),
+                                slot_bits<W>(rb, 3, a.nbits)};
+        __builtin_nontemporal_store(round4_fp8_hw<FMT, VAR>(b, n4, hw), reinterpret_cast<uint32_t*>(out) + row);
         continue;
       }
     }

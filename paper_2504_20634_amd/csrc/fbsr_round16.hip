@@ -1,0 +1,168 @@
+// fbsr_round16.hip -- kernels behind fbsr_round_from16: bf16 / IEEE binary16 -> {E4M3, E5M2} few-bit
+// stochastic rounding, the narrow-source setting of Sec. III-E and Fig. 2 (few excess bits D).
+// The source value is widened exactly to an fp32 pattern and then takes the same rounding core as
+// fbsr_round.
+#include <hip/hip_fp16.h>
+
+#include "fbsr_launch.h"
+
+namespace fbsr {
+
+enum : int { kSrcBF16 = 0, kSrcFP16 = 1 };
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Exact fp32 pattern of a 16-bit source code.
+template <int SRC>
+__device__ __forceinline__ uint32_t widen16(uint32_t code16) {
+  if constexpr (SRC == kSrcBF16) {
+    return code16 << 16;
+  } else {
+    return __float_as_uint(__half2float(__ushort_as_half((unsigned short)code16)));   // v_cvt_f32_f16: exact
+  }
+}
+
+// One workgroup per 2048-element tile, one wave per 512 elements, one 16-byte load of 8 source
+// codes and one 8-byte store of 8 fp8 codes per lane: 3 bytes of traffic per element.
+template <int SRC, int FMT, int VAR, int W>
+__global__ __launch_bounds__(kThreads) void round16_tiles(const uint16_t* __restrict__ x, uint8_t* __restrict__ out,
+                                                          int nbits, uint64_t seed, uint64_t blk0) {
+  typedef WgTile<W> T;
+  __shared__ uint4 strip[T::BLOCKS];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int e0 = wave * kWaveElems + 8 * lane;                                  // tile-relative first element
+  const uint64_t g0 = (uint64_t)blockIdx.x * T::ELEMS + (uint64_t)e0;           // call-relative first element
+  const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + g0));
+  if constexpr (VAR != kRNE) {
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
+    __syncthreads();
+  }
+  const Addends a = make_addends<FMT, VAR>(nbits);
+  HwAddends hw = {0, 0, 0, 0};
+  if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
+  const uint32_t words[4] = {q.x, q.y, q.z, q.w};
+  uint32_t b[8];
+  uint32_t umax = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    b[j] = widen16<SRC>((words[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
+    umax = max(umax, b[j] & 0x7FFFFFFFu);
+  }
+  const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: a NaN among the wave's elements
+  uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if constexpr (VAR != kRNE) read_wg_bits8<W>(strip, e0, a.nbits, n);
+  uint32_t packed[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t b4[4] = {b[4 * h], b[4 * h + 1], b[4 * h + 2], b[4 * h + 3]};
+    const uint32_t n4[4] = {n[4 * h], n[4 * h + 1], n[4 * h + 2], n[4 * h + 3]};
+    bool done = false;
+    if constexpr (VAR != kRNE) {
+      if (!checked) {
+        packed[h] = round4_fp8_hw<FMT, VAR>(b4, n4, hw);
+        done = true;
+      }
+    }
+    if (!done) {
+      uint32_t r[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, true>(b4[j], n4[j], a);
+      packed[h] = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
+    }
+  }
+  __builtin_nontemporal_store((uint64_t)packed[0] | ((uint64_t)packed[1] << 32), reinterpret_cast<uint64_t*>(out + g0));
+}
+
+template <int SRC, int FMT, int VAR>
+__global__ __launch_bounds__(kThreads) void round16_elems(const uint16_t* __restrict__ x, uint8_t* __restrict__ out,
+                                                          uint64_t n, int nbits, int W, int log2_per_block,
+                                                          uint64_t seed, uint64_t offset) {
+  const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= n) return;
+  const Addends a = make_addends<FMT, VAR>(nbits);
+  uint32_t rnd = 0;
+  if constexpr (VAR != kRNE) rnd = element_bits(offset + j, log2_per_block, W, a.nbits, seed, 0);
+  out[j] = (uint8_t)(round_pattern<FMT, VAR, true>(widen16<SRC>(x[j]), rnd, a) >> Fx<FMT>::FRAC);
+}
+
+namespace {
+
+template <int SRC, int FMT, int VAR>
+hipError_t launch_tiles_w(int W, const uint16_t* x, uint8_t* out, uint64_t ntiles, int nbits, uint64_t seed,
+                          uint64_t blk0, hipStream_t stream) {
+  const dim3 grid((unsigned)ntiles), block(kThreads);
+  if constexpr (VAR == kRNE) {
+    hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, nbits, seed, blk0);
+  } else {
+    switch (W) {
+      case 1: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 1>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
+      case 2: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 2>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
+      case 4: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 4>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
+      case 8: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
+      default: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 16>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
+    }
+  }
+  return hipGetLastError();
+}
+
+template <int SRC, int FMT, int VAR>
+hipError_t launch_elems(const uint16_t* x, uint8_t* out, uint64_t n, int nbits, int W, uint64_t seed, uint64_t offset,
+                        hipStream_t stream) {
+  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
+    const uint64_t m = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
+    const uint64_t blocks = (m + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL((round16_elems<SRC, FMT, VAR>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x + at, out + at,
+                       m, nbits, W, log2_of(128 / W), seed, offset + at);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <int SRC, int FMT, int VAR>
+hipError_t run(const uint16_t* x, uint8_t* out, uint64_t n, int nbits, uint64_t seed, uint64_t offset,
+               hipStream_t stream) {
+  const int W = VAR == kRNE ? 8 : slot_width(nbits);
+  const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 2, 16,
+                              reinterpret_cast<uintptr_t>(out), 1, 8);
+  hipError_t e = launch_elems<SRC, FMT, VAR>(x, out, s.head, nbits, W, seed, offset, stream);
+  if (e != hipSuccess) return e;
+  if (s.ntiles) {
+    e = launch_tiles_w<SRC, FMT, VAR>(W, x + s.head, out + s.head, s.ntiles, nbits, seed,
+                                      (offset + s.head) / (uint64_t)(128 / W), stream);
+    if (e != hipSuccess) return e;
+  }
+  const uint64_t done = s.head + s.ntiles * s.tile_elems;
+  return launch_elems<SRC, FMT, VAR>(x + done, out + done, n - done, nbits, W, seed, offset + done, stream);
+}
+
+template <int SRC, int FMT>
+hipError_t run_v(int variant, const uint16_t* x, uint8_t* out, uint64_t n, int nbits, uint64_t seed, uint64_t offset,
+                 hipStream_t stream) {
+  switch (variant) {
+    case kRNE: return run<SRC, FMT, kRNE>(x, out, n, nbits, seed, offset, stream);
+    case kSRFF: return run<SRC, FMT, kSRFF>(x, out, n, nbits, seed, offset, stream);
+    case kSRF: return run<SRC, FMT, kSRF>(x, out, n, nbits, seed, offset, stream);
+    default: return run<SRC, FMT, kSRC>(x, out, n, nbits, seed, offset, stream);
+  }
+}
+
+template <int SRC>
+hipError_t run_f(int fmt, int variant, const uint16_t* x, uint8_t* out, uint64_t n, int nbits, uint64_t seed,
+                 uint64_t offset, hipStream_t stream) {
+  if (fmt == kE4M3) return run_v<SRC, kE4M3>(variant, x, out, n, nbits, seed, offset, stream);
+  return run_v<SRC, kE5M2>(variant, x, out, n, nbits, seed, offset, stream);
+}
+
+}  // namespace
+
+hipError_t launch_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt, int variant, int nbits,
+                               uint64_t seed, uint64_t offset, hipStream_t stream) {
+  const uint16_t* xp = reinterpret_cast<const uint16_t*>(x);
+  uint8_t* op = reinterpret_cast<uint8_t*>(out);
+  if (src_fmt == kSrcBF16) return run_f<kSrcBF16>(fmt, variant, xp, op, n, nbits, seed, offset, stream);
+  return run_f<kSrcFP16>(fmt, variant, xp, op, n, nbits, seed, offset, stream);
+}
+
+}  // namespace fbsr

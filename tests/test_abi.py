@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
-    assert {"fbsr_round", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
+    assert {"fbsr_round", "fbsr_round_from16", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
             "fbsr_strerror", "fbsr_version"} <= set(names)
     for name in names:
         assert hasattr(L, name), name
@@ -67,6 +67,11 @@ def test_argument_validation_happens_on_the_host(L):
         assert L.fbsr_bias_stats(p(good), None, 8, fmt, var, nb, 0, 0, 4, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
     assert L.fbsr_sgd_update(p(good), p(good), 8, 0.1, 5, 2, 0, 0, 0, None) == EINVAL
     assert L.fbsr_sgd_update(p(good), p(good), 8, 0.1, 1, 99, 0, 0, 0, None) == EINVAL
+    for src, fmt in ((2, 1), (0, 0), (1, 3), (-1, 2)):
+        assert L.fbsr_round_from16(p(good), p(good), 8, src, fmt, 1, 2, 0, 0, None) == EINVAL
+    assert L.fbsr_round_from16(None, None, 0, 0, 1, 1, 2, 0, 0, None) == OK
+    assert L.fbsr_round_from16(p(good + 1), p(good), 8, 0, 1, 1, 2, 0, 0, None) == EALIGN
+    assert L.fbsr_round_from16(p(good), None, 8, 0, 1, 1, 2, 0, 0, None) == EINVAL
     # RNE ignores nbits
     assert L.fbsr_round(None, p(good), 8, 0, 0, 99, 0, 0, None) == EINVAL      # (null x, not nbits)
     # null pointers with n > 0

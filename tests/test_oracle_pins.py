@@ -396,3 +396,57 @@ def test_sgd_is_one_fma_then_round(oracle):
                                              oracle.random_bits(2, 6, 10 + j, nbits) if variant else 0)
                          for j, xi in enumerate(x)], dtype=np.uint16)
         assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ narrow sources ---------
+SRC_BF16, SRC_FP16 = 0, 1
+
+
+@pytest.mark.parametrize("src,tdt", [(SRC_BF16, torch.bfloat16), (SRC_FP16, torch.float16)])
+def test_widening_matches_library(oracle, src, tdt):
+    """Eq. (1) on all 65536 source codes equals the library's widening to fp32 (NaNs: sign and
+    NaN-ness agree)."""
+    codes = np.arange(65536, dtype=np.uint16)
+    ref = torch.from_numpy(codes.view(np.int16)).view(tdt).to(torch.float32).numpy().view(np.uint32)
+    got = np.array([oracle.widen16(int(c), src) for c in codes], dtype=np.uint32)
+    nan = np.isnan(ref.view(np.float32))
+    assert np.array_equal(ref[~nan], got[~nan])
+    assert np.all(np.isnan(got[nan].view(np.float32))) and np.array_equal(ref[nan] >> 31, got[nan] >> 31)
+
+
+def test_narrow_source_is_widen_then_round(oracle):
+    rng = np.random.default_rng(4)
+    codes = rng.integers(0, 1 << 16, 20000, dtype=np.uint16)
+    for src, tdt in ((SRC_BF16, torch.bfloat16), (SRC_FP16, torch.float16)):
+        wide = torch.from_numpy(codes.view(np.int16)).view(tdt).to(torch.float32).numpy()
+        for fmt in (E4M3, E5M2):
+            for variant, nbits in ((RNE, 0), (SRFF, 2), (SRF, 3), (SRC, 4), (SRFF, 9)):
+                a = oracle.round_from16(codes, src, fmt, variant, nbits, seed=6, offset=123)
+                b = oracle.round_(wide, fmt, variant, nbits, seed=6, offset=123)
+                assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("src,fmt,D,start16", [(SRC_BF16, E4M3, 4, 0x3F80), (SRC_BF16, E5M2, 5, 0x4000),
+                                               (SRC_FP16, E4M3, 7, 0x3C00), (SRC_FP16, E5M2, 8, 0x4000)])
+def test_narrow_source_closed_forms(oracle, src, fmt, D, start16):
+    """Sec. III-E with the source formats the paper names: all 2^D source values of one target
+    interval, all 2^N draws.  SRFF (2^-D - 2^-N)/2 for N <= D (0 beyond), SRF 2^-(D+1) for N < D,
+    SRC 0.  bf16 -> E5M2 at N = 3 is Fig. 2's setting."""
+    codes = (start16 + np.arange(1 << D)).astype(np.uint16)
+    wide = np.array([oracle.widen16(int(c), src) for c in codes], dtype=np.uint32).view(np.float32)
+    for nbits in (1, 2, 3, 4, 6):
+        for variant in SR_VARIANTS:
+            ups = oracle.count_up(wide, fmt, variant, nbits)
+            total = Fraction(0)
+            for x, u in zip(wide, ups):
+                _, delta = delta_of(f32_fraction(x), fmt)
+                total += Fraction(int(u), 1 << nbits) - delta
+            got = total / (1 << D)
+            if variant == SRFF:
+                want = (pow2(-D) - pow2(-nbits)) / 2 if nbits <= D else 0
+            elif variant == SRF:
+                want = pow2(-(D + 1)) if nbits < D else None
+            else:
+                want = 0
+            if want is not None:
+                assert got == want, (src, fmt, variant, nbits, float(got))
