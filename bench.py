@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per fp8 round_tiles launch of 2^28 elements, from two rocprofv3 --pmc runs of this file
 # (FETCH_SIZE, then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy);
 # the summary is committed under profiles/.  Algorithmic bytes: 5 * 2^28 = 1342177280.
-MEASURED_TRAFFIC_BYTES_2P28 = 1342215899
+MEASURED_TRAFFIC_BYTES_2P28 = 1342193990
 N_ELEMS = 1 << 28
 SGD_ELEMS = 1 << 27
 HEADLINE_NBITS = (2, 4, 8)
