@@ -248,6 +248,28 @@ bool args_ok(int fmt, int variant, int nbits, Format* f) {
   return true;
 }
 
+// One fused step of Alg. 1 (quantization-aware training of an 8-bit model with 16-bit updates):
+//   w16 <- w8;  u16 <- AdamW update in 16-bit;  w8 <- RoundTo8(w16 + u16), SR applied to that rounding.
+// The paper gives no more than the listing and "gradient updates computed in BFloat16" (Sec. IV).
+// Reading taken here: the 16-bit format is bf16; every arithmetic operation below is ONE IEEE fp32
+// operation (round to nearest even) in the order written; every quantity the listing types as F16
+// (the moments, the update u, and the sum w16 + u16) is rounded to bf16 with ties-to-even, so the
+// value handed to the 8-bit rounding has bf16 precision (D = 4 excess bits for a precision-4 target,
+// the count Sec. IV reasons with).  AdamW as commonly defined (decoupled weight decay):
+//   m <- b1 m + (1 - b1) g;  v <- b2 v + (1 - b2) g^2;
+//   u = -lr ( (m / c1) / (sqrt(v / c2) + eps) + wd w ),  c1 = 1 - b1^t, c2 = 1 - b2^t supplied by the caller.
+// A NaN produced anywhere is stored as the positive canonical quiet NaN (NaN signs are not portable).
+struct AdamW {
+  float lr, beta1, beta2, eps, weight_decay, bias_corr1, bias_corr2;
+};
+
+uint16_t to_bf16_rne(float x) {
+  Format f;
+  get_format(FMT_BF16, &f);
+  if (std::isnan(x)) return 0x7FC0u;
+  return (uint16_t)round_one(x, f, VAR_RNE, 0, 0);
+}
+
 }  // namespace
 
 extern "C" {
@@ -371,6 +393,42 @@ int oracle_sgd_update(uint16_t* w, const float* g, uint64_t n, float lr, int var
     const float x = std::fmaf(-lr, g[j], bf16_to_float(w[j]));
     const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, step, offset + j, nbits);
     w[j] = (uint16_t)round_one(x, f, variant, nbits, r);
+  }
+  return 0;
+}
+
+// w8: n fp8 codes of fmt (E4M3 or E5M2), updated in place; g16: n bf16 gradients; m16, v16: n bf16
+// moments, updated in place; p: 7 floats {lr, beta1, beta2, eps, weight_decay, 1 - beta1^t, 1 - beta2^t}.
+// Random bits of element j: stream (seed, step), global index offset + j.
+int oracle_qat_adamw_step(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, int fmt,
+                          const float* p, int variant, int nbits, uint64_t seed, uint64_t step, uint64_t offset) {
+  Format f;
+  if (!args_ok(fmt, variant, nbits, &f) || (fmt != FMT_E4M3 && fmt != FMT_E5M2)) return 1;
+  const AdamW a = {p[0], p[1], p[2], p[3], p[4], p[5], p[6]};
+  const float omb1 = 1.0f - a.beta1, omb2 = 1.0f - a.beta2;
+  for (uint64_t j = 0; j < n; ++j) {
+    const float w = (float)decode(w8[j], f);            // w16 <- w8 (exact)
+    const float g = bf16_to_float(g16[j]);
+    const float m0 = bf16_to_float(m16[j]), v0 = bf16_to_float(v16[j]);
+    const float m1 = std::fmaf(a.beta1, m0, omb1 * g);
+    const float v1 = std::fmaf(a.beta2, v0, omb2 * (g * g));
+    const uint16_t mq = to_bf16_rne(m1), vq = to_bf16_rne(v1);
+    m16[j] = mq;
+    v16[j] = vq;
+    const float mh = bf16_to_float(mq) / a.bias_corr1;
+    const float vh = bf16_to_float(vq) / a.bias_corr2;
+    const float ratio = mh / (std::sqrt(vh) + a.eps);
+    const float u = -a.lr * std::fmaf(a.weight_decay, w, ratio);
+    const float u16 = bf16_to_float(to_bf16_rne(u));
+    const float s16 = bf16_to_float(to_bf16_rne(w + u16));   // the F16 sum handed to RoundTo8
+    uint32_t code;
+    if (std::isnan(s16)) {
+      code = f.nan_code;
+    } else {
+      const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, step, offset + j, nbits);
+      code = round_one(s16, f, variant, nbits, r);
+    }
+    w8[j] = (uint8_t)code;
   }
   return 0;
 }

@@ -60,6 +60,8 @@ def lib():
         L.oracle_round_from16.restype = i32
         L.oracle_widen16.argtypes = [ctypes.c_uint16, i32]
         L.oracle_widen16.restype = u32
+        L.oracle_qat_adamw_step.argtypes = [vp, vp, vp, vp, u64, i32, vp, i32, i32, u64, u64, u64]
+        L.oracle_qat_adamw_step.restype = i32
         L.oracle_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64]
         L.oracle_sgd_update.restype = i32
         L.oracle_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp]
@@ -151,6 +153,22 @@ def sgd_update(w, g, lr, variant, nbits, seed, step, offset=0):
     if rc != 0:
         raise ValueError("oracle_sgd_update: status %d" % rc)
     return w
+
+
+def qat_adamw_step(w8, g16, m16, v16, fmt, params, variant, nbits, seed, step, offset=0):
+    """One fused QAT step.  params = (lr, beta1, beta2, eps, weight_decay, 1 - beta1^t, 1 - beta2^t).
+    Returns new (w8, m16, v16); the inputs are not modified."""
+    w8 = np.array(w8, dtype=np.uint8, copy=True)
+    m16 = np.array(m16, dtype=np.uint16, copy=True)
+    v16 = np.array(v16, dtype=np.uint16, copy=True)
+    g16 = np.ascontiguousarray(g16, dtype=np.uint16)
+    p = np.asarray(params, dtype=np.float32)
+    assert p.size == 7 and w8.size == g16.size == m16.size == v16.size
+    rc = lib().oracle_qat_adamw_step(_ptr(w8), _ptr(g16), _ptr(m16), _ptr(v16), w8.size, fmt, _ptr(p), variant,
+                                     nbits, seed, step, offset)
+    if rc != 0:
+        raise ValueError("oracle_qat_adamw_step: status %d" % rc)
+    return w8, m16, v16
 
 
 def bias_stats(x, fmt, variant, nbits, seed, offset, group, first_bin, nbins, stats=None,

@@ -450,3 +450,110 @@ def test_narrow_source_closed_forms(oracle, src, fmt, D, start16):
                 want = 0
             if want is not None:
                 assert got == want, (src, fmt, variant, nbits, float(got))
+
+
+# ------------------------------------------------------------------ fused QAT step (Alg. 1) ----
+def _bf16_codes(a):
+    """fp32 array -> bf16 codes by the library's round-to-nearest-even cast."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def _bf16_values(c):
+    return (c.astype(np.uint32) << 16).view(np.float32)
+
+
+def _fp8_values(codes, fmt):
+    tdt = torch.float8_e4m3fn if fmt == E4M3 else torch.float8_e5m2
+    return torch.from_numpy(codes).view(tdt).to(torch.float32).numpy()
+
+
+@pytest.mark.parametrize("fmt", [E4M3, E5M2])
+def test_qat_step_tracks_library_adamw(oracle, fmt):
+    """Three steps of Alg. 1 with the oracle against torch.optim.AdamW in fp32 on the same gradients:
+    the bf16 moments stay within bf16 rounding of the fp32 moments, and each new 8-bit weight is within
+    one target ulp (plus the 16-bit roundings) of the fp32 update of the previous 8-bit weight.  A
+    dropped term, a wrong sign or a missing bias correction moves results by far more."""
+    rng = np.random.default_rng(17)
+    n = 4000
+    vals, codes = finite_table(fmt)
+    pick = rng.integers(8, len(codes) - 8, n)
+    w8 = (np.array(codes, dtype=np.uint8)[pick] | (rng.integers(0, 2, n).astype(np.uint8) << 7)).astype(np.uint8)
+    lr, b1, b2, eps, wd = 3e-2, 0.9, 0.95, 1e-8, 0.1
+    m16 = np.zeros(n, np.uint16)
+    v16 = np.zeros(n, np.uint16)
+    m_ref = np.zeros(n, np.float64)
+    v_ref = np.zeros(n, np.float64)
+    for t in (1, 2, 3):
+        g16 = _bf16_codes(rng.standard_normal(n) * 0.5)
+        g = _bf16_values(g16).astype(np.float64)
+        w_prev = _fp8_values(w8, fmt).astype(np.float64)
+        m_prev, v_prev = m_ref.copy(), v_ref.copy()
+        # library step on the current 8-bit weights with its own fp32 state replaced by the references
+        p = torch.nn.Parameter(torch.from_numpy(w_prev.astype(np.float32)))
+        opt = torch.optim.AdamW([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+        p.grad = torch.from_numpy(g.astype(np.float32))
+        opt.state[p] = {"step": torch.tensor(float(t - 1)), "exp_avg": torch.from_numpy(m_ref.astype(np.float32)),
+                        "exp_avg_sq": torch.from_numpy(v_ref.astype(np.float32))}
+        opt.step()
+        target = p.detach().numpy().astype(np.float64)
+        m_ref = opt.state[p]["exp_avg"].numpy().astype(np.float64)
+        v_ref = opt.state[p]["exp_avg_sq"].numpy().astype(np.float64)
+        params = (lr, b1, b2, eps, wd, 1 - b1 ** t, 1 - b2 ** t)
+        w8, m16, v16 = oracle.qat_adamw_step(w8, g16, m16, v16, fmt, params, SRC, 3, seed=5, step=t)
+        m_got, v_got = _bf16_values(m16).astype(np.float64), _bf16_values(v16).astype(np.float64)
+        # one bf16 rounding of the result, plus fp32 rounding noise relative to the terms that were added
+        m_tol = 2.0 ** -8 * np.abs(m_ref) + 2.0 ** -20 * (np.abs(m_prev) + np.abs(g)) + 1e-40
+        v_tol = 2.0 ** -8 * np.abs(v_ref) + 2.0 ** -20 * (np.abs(v_prev) + g * g) + 1e-40
+        assert np.all(np.abs(m_got - m_ref) <= m_tol), np.max(np.abs(m_got - m_ref) / m_tol)
+        assert np.all(np.abs(v_got - v_ref) <= v_tol), np.max(np.abs(v_got - v_ref) / v_tol)
+        w_new = _fp8_values(w8, fmt).astype(np.float64)
+        ulp8 = np.array([oracle.ulp(np.float32(x), fmt) for x in target])
+        slack = ulp8 + 2.0 ** -6 * np.abs(target) + 2.0 ** -5 * np.abs(target - w_prev)
+        assert np.all(np.abs(w_new - target) <= slack), np.max(np.abs(w_new - target) / slack)
+        # restart the reference moments from the 16-bit ones so rounding differences do not pile up
+        m_ref, v_ref = m_got, v_got
+
+
+def test_qat_step_structure(oracle):
+    """lr = 0 leaves every weight where it is (representable values are fixed points of all
+    variants); the 8-bit rounding is exactly the narrow-source FBSR of the bf16 sum with the bits of
+    (seed, step, index); nearest-even stagnates on tiny updates while the stochastic variants move
+    (Sec. IV: "further gradient updates make no change to the weights")."""
+    rng = np.random.default_rng(3)
+    n = 3000
+    for fmt in (E4M3, E5M2):
+        vals, codes = finite_table(fmt)
+        w8 = (np.array(codes, dtype=np.uint8)[rng.integers(4, len(codes) - 4, n)]
+              | (rng.integers(0, 2, n).astype(np.uint8) << 7)).astype(np.uint8)
+        g16 = _bf16_codes(rng.standard_normal(n))
+        m16 = _bf16_codes(rng.standard_normal(n) * 0.1)
+        v16 = _bf16_codes(rng.random(n) * 0.1)
+        for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 3), (SRC, 3)):
+            same, m_a, v_a = oracle.qat_adamw_step(w8, g16, m16, v16, fmt, (0.0, 0.9, 0.999, 1e-8, 0.01, 0.1, 0.001),
+                                                   variant, nbits, seed=1, step=4)
+            assert np.array_equal(same, w8)
+        # the moments do not depend on the variant, the seed or lr
+        _, m_b, v_b = oracle.qat_adamw_step(w8, g16, m16, v16, fmt, (0.5, 0.9, 0.999, 1e-8, 0.01, 0.1, 0.001), SRFF, 2, 9, 1)
+        assert np.array_equal(m_a, m_b) and np.array_equal(v_a, v_b)
+        # tiny updates: |u| far below the spacing of both the 8-bit and the 16-bit grid around w
+        params = (1e-6, 0.9, 0.999, 1e-8, 0.0, 0.1, 0.001)
+        big = (np.abs(_fp8_values(w8, fmt)) >= 2.0 ** -5)
+        stuck, _, _ = oracle.qat_adamw_step(w8, g16, m16, v16, fmt, params, RNE, 0, 1, 1)
+        assert np.array_equal(stuck[big], w8[big])
+    # the rounding handed to RoundTo8 is the narrow-source one: recompute the bf16 sum in numpy fp32
+    fmt, variant, nbits, seed, step, off = E4M3, SRF, 3, 11, 6, 40
+    lr, b1, b2, eps, wd, c1, c2 = (np.float32(v) for v in (0.05, 0.9, 0.99, 1e-8, 0.1, 0.3, 0.05))
+    w = _fp8_values(w8, fmt)
+    g, m0, v0 = _bf16_values(g16), _bf16_values(m16), _bf16_values(v16)
+    one = np.float32(1.0)
+    fma = lambda a, b, c: (a.astype(np.float64) * b.astype(np.float64) + c.astype(np.float64)).astype(np.float32)
+    m1 = fma(np.full(n, b1), m0, (one - b1) * g)
+    v1 = fma(np.full(n, b2), v0, (one - b2) * (g * g))
+    mq, vq = _bf16_values(_bf16_codes(m1)), _bf16_values(_bf16_codes(v1))
+    ratio = (mq / c1) / (np.sqrt(vq / c2) + eps)
+    u = -lr * fma(np.full(n, wd), w, ratio)
+    s16 = _bf16_codes(w + _bf16_values(_bf16_codes(u)))
+    got, _, _ = oracle.qat_adamw_step(w8, g16, m16, v16, fmt, (lr, b1, b2, eps, wd, c1, c2), variant, nbits, seed, step, off)
+    want = np.array([oracle.round_with_n(x, fmt, variant, nbits, oracle.random_bits(seed, step, off + j, nbits))
+                     for j, x in enumerate(_bf16_values(s16))], dtype=np.uint8)
+    assert np.array_equal(got, want)
