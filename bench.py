@@ -176,6 +176,25 @@ def main():
             paths["round_from_bf16_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
                 "ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
         del x16
+        # fused QAT step of Alg. 1 (7 B read + 5 B written per element), N = 3, 2^27 weights, rotated buffers
+        nq = min(SGD_ELEMS, n)
+        qs = [(torch.from_numpy((workloads.sgd_weights(nq, seed=40 + k) & 0x7777).view(np.uint8)[:nq].copy()).cuda(),
+               torch.from_numpy(workloads.sgd_weights(nq, seed=50 + k).view(np.int16)).cuda(),
+               torch.zeros(nq, dtype=torch.int16, device="cuda"), torch.zeros(nq, dtype=torch.int16, device="cuda"))
+              for k in range(3)]
+        tq = [0]
+
+        def qat(v):
+            tq[0] += 1
+            w8_, g_, m_, v_ = qs[tq[0] % 3]
+            t = 1 + tq[0] // 3
+            fbsr.fbsr_qat_adamw_step(w8_, g_, m_, v_, fbsr.FMT_E4M3, (1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9 ** t, 1 - 0.999 ** t),
+                                     v, 3, seed=6, step=t)
+        for v in (fbsr.SRC, fbsr.SRFF):
+            ms = timed_launches(torch, lambda: qat(v), 12)
+            paths["qat_adamw_e4m3_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
+                "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
+        del qs
         ns = min(SGD_ELEMS, n)
         # rotate through 3 weight and 3 gradient buffers (2.25 GiB) so the last-level cache cannot help
         ws_ = [torch.from_numpy(workloads.sgd_weights(ns, seed=3 + k).view(np.int16)).cuda() for k in range(3)]

@@ -100,6 +100,31 @@ int fbsr_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt
 int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, int nbits,
                     uint64_t seed, uint64_t step, uint64_t offset, void* stream);
 
+/* Scalars of one AdamW step (decoupled weight decay).  bias_corr1 = 1 - beta1^t and
+ * bias_corr2 = 1 - beta2^t for the step count t >= 1 are supplied by the caller. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay, bias_corr1, bias_corr2;
+} fbsr_adamw;
+
+/* One fused step of Alg. 1 (quantization-aware training of an 8-bit model with 16-bit updates):
+ *   w16 <- w8;  u16 <- AdamW update in 16-bit;  w8 <- RoundTo8(w16 + u16), SR applied to that rounding.
+ * The 16-bit format is bf16 (Sec. IV computes the updates in BFloat16).  Per element, every step is one
+ * IEEE fp32 operation (round to nearest even, subnormals kept) in this order, and every quantity the
+ * listing types as F16 is rounded to bf16 with ties to even:
+ *   m  <- bf16( fma(beta1, m, (1 - beta1) * g) )          v <- bf16( fma(beta2, v, (1 - beta2) * (g * g)) )
+ *   r  =  (m / bias_corr1) / (sqrt(v / bias_corr2) + eps)     (with the new bf16 m and v)
+ *   u  <- bf16( -lr * fma(weight_decay, w, r) )            s <- bf16( w + u )
+ *   w8 <- FBSR_fmt(s)  with the random bits of (seed, step, offset + j), as in fbsr_round_from16.
+ * So the value handed to the 8-bit rounding has bf16 precision: D = 4 excess bits for E4M3 (the count
+ * Sec. IV reasons with), 5 for E5M2.  A NaN produced anywhere is stored as the positive canonical NaN.
+ * w8: n codes of fmt (E4M3 or E5M2; device, updated in place).  g16: n bf16 gradients (device, read).
+ * m16, v16: n bf16 moments (device, updated in place).  p: HOST pointer, read during the call.
+ * Errors: FBSR_EINVAL (fmt not fp8, bad variant / nbits, null pointer), FBSR_EALIGN (16-bit arrays need
+ * 2-byte alignment), FBSR_EDEVICE. */
+int fbsr_qat_adamw_step(void* w8, const void* g16, void* m16, void* v16, uint64_t n, int fmt,
+                        const fbsr_adamw* p, int variant, int nbits, uint64_t seed, uint64_t step,
+                        uint64_t offset, void* stream);
+
 /* Rounds as fbsr_round and reduces the rounding error per bin -- the measurement behind
  * Figs. 1 and 2 (mean of the rounded samples per input value; bias = mean of rounded minus
  * input, Sec. III).  Element j has global index i = offset + j and bin

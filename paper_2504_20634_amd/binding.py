@@ -17,7 +17,7 @@ OK, EINVAL, EALIGN, ERANGE, EDEVICE = 0, 1, 2, 3, 4
 MAX_NBITS = 16
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
-EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
+EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
            "fbsr_strerror", "fbsr_version")
 
 
@@ -44,6 +44,8 @@ def lib():
         L.fbsr_round.restype = i32
         L.fbsr_round_from16.argtypes = [vp, vp, u64, i32, i32, i32, i32, u64, u64, vp]
         L.fbsr_round_from16.restype = i32
+        L.fbsr_qat_adamw_step.argtypes = [vp, vp, vp, vp, u64, i32, vp, i32, i32, u64, u64, u64, vp]
+        L.fbsr_qat_adamw_step.restype = i32
         L.fbsr_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64, vp]
         L.fbsr_sgd_update.restype = i32
         L.fbsr_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp, vp, u64, vp]
@@ -106,6 +108,27 @@ def fbsr_round_from16(x, src_fmt, fmt, variant, nbits, seed, offset=0, out=None,
     _check(lib().fbsr_round_from16(x.data_ptr(), out.data_ptr(), n, src_fmt, fmt, variant, nbits, seed,
                                    offset, _stream_handle(stream)), "fbsr_round_from16")
     return out
+
+
+class AdamW(ctypes.Structure):
+    """Mirror of the C struct fbsr_adamw."""
+    _fields_ = [(k, ctypes.c_float) for k in ("lr", "beta1", "beta2", "eps", "weight_decay", "bias_corr1", "bias_corr2")]
+
+
+def fbsr_qat_adamw_step(w8, g16, m16, v16, fmt, params, variant, nbits, seed, step, offset=0, stream=None):
+    """One fused step of Alg. 1, in place on w8 (uint8 fp8 codes), m16, v16 (bf16 codes); g16 is read.
+    params = (lr, beta1, beta2, eps, weight_decay, 1 - beta1^t, 1 - beta2^t)."""
+    import torch
+    for t in (w8, g16, m16, v16):
+        assert t.is_cuda and t.is_contiguous()
+    assert w8.dtype == torch.uint8 and g16.element_size() == m16.element_size() == v16.element_size() == 2
+    n = w8.numel()
+    assert g16.numel() == m16.numel() == v16.numel() == n
+    p = AdamW(*[float(x) for x in params])
+    _check(lib().fbsr_qat_adamw_step(w8.data_ptr(), g16.data_ptr(), m16.data_ptr(), v16.data_ptr(), n, fmt,
+                                     ctypes.byref(p), variant, nbits, seed, step, offset, _stream_handle(stream)),
+           "fbsr_qat_adamw_step")
+    return w8, m16, v16
 
 
 def fbsr_sgd_update(w, g, lr, variant, nbits, seed, step, offset=0, stream=None):

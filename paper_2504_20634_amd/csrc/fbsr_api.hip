@@ -61,6 +61,23 @@ int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, 
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 
+int fbsr_qat_adamw_step(void* w8, const void* g16, void* m16, void* v16, uint64_t n, int fmt, const fbsr_adamw* p,
+                        int variant, int nbits, uint64_t seed, uint64_t step, uint64_t offset, void* stream) {
+  if (fmt != FBSR_FMT_E4M3 && fmt != FBSR_FMT_E5M2) return FBSR_EINVAL;
+  const int c = check_common(variant, nbits, n, offset);
+  if (c != FBSR_OK) return c;
+  if (p == nullptr) return FBSR_EINVAL;
+  if (n == 0) return FBSR_OK;
+  if (w8 == nullptr || g16 == nullptr || m16 == nullptr || v16 == nullptr) return FBSR_EINVAL;
+  if (misaligned(g16, 2) || misaligned(m16, 2) || misaligned(v16, 2)) return FBSR_EALIGN;
+  const fbsr::AdamWScalars sc = {p->lr, p->beta1, p->beta2, p->eps, p->weight_decay, p->bias_corr1, p->bias_corr2};
+  const hipError_t e = fbsr::launch_qat_adamw(reinterpret_cast<uint8_t*>(w8), reinterpret_cast<const uint16_t*>(g16),
+                                              reinterpret_cast<uint16_t*>(m16), reinterpret_cast<uint16_t*>(v16), n, fmt,
+                                              sc, variant, nbits, seed, step, offset,
+                                              reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
 uint64_t fbsr_bias_stats_workspace_bytes(uint64_t n, uint32_t nbins) {
   (void)nbins;
   // one record per (chunk, bin it touches), sized for the smallest group the chunked kernel takes

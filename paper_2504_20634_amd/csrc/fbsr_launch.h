@@ -66,6 +66,14 @@ hipError_t launch_round_from16(const void* x, void* out, uint64_t n, int src_fmt
 hipError_t launch_sgd(void* w, const float* g, uint64_t n, float lr, int variant, int nbits, uint64_t seed,
                       uint64_t step, uint64_t offset, hipStream_t stream);
 
+struct AdamWScalars {
+  float lr, beta1, beta2, eps, weight_decay, bias_corr1, bias_corr2;
+};
+
+hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, int fmt,
+                            const AdamWScalars& p, int variant, int nbits, uint64_t seed, uint64_t step,
+                            uint64_t offset, hipStream_t stream);
+
 // The tile kernel of the statistics path works in chunks of kStatsChunkTiles tiles per workgroup
 // and leaves one record {sum y, sum e, sum e^2} per (chunk, bin the chunk touches) in the
 // workspace; a chunk touches at most chunk / group + 2 bins, and group >= one tile on this path.

@@ -1,0 +1,198 @@
+// fbsr_qat.hip -- kernels behind fbsr_qat_adamw_step: one fused step of Alg. 1
+// (w16 <- w8; AdamW update in bf16; w8 <- RoundTo8(w16 + u16) with few-bit stochastic rounding).
+// Per element 7 bytes are read (w8, g, m, v) and 5 written (w8, m, v); the arithmetic is a fixed
+// sequence of single IEEE fp32 operations (this file is compiled without contraction; the divisions
+// and the square root are the correctly rounded ones) so that it can be reproduced bit for bit.
+#include "fbsr_launch.h"
+
+namespace fbsr {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Exact value of an fp8 code (Eq. (1)); the hardware decode agrees with it on all 256 codes.
+template <int FMT>
+__device__ __forceinline__ float fp8_value(uint32_t code) {
+  if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
+  else return __builtin_amdgcn_cvt_f32_bf8((int)code, 0);
+}
+
+// bf16 code of x rounded to nearest even; any NaN becomes the positive canonical NaN.
+__device__ __forceinline__ uint32_t bf16_rne(float x, const Addends& a16) {
+  const uint32_t bits = __float_as_uint(x);
+  const uint32_t r = round_pattern<kBF16, kRNE, true>(bits, 0u, a16) >> 16;
+  return (bits & 0x7FFFFFFFu) > 0x7F800000u ? 0x7FC0u : r;
+}
+
+struct QatOut {
+  uint32_t w8, m16, v16;
+};
+
+template <int FMT, int VAR>
+__device__ __forceinline__ QatOut qat_one(uint32_t w8, uint32_t g16, uint32_t m16, uint32_t v16, uint32_t n,
+                                          const AdamWScalars& p, float omb1, float omb2, const Addends& a8,
+                                          const Addends& a16) {
+  const float w = fp8_value<FMT>(w8);
+  const float g = __uint_as_float(g16 << 16);
+  const float m0 = __uint_as_float(m16 << 16), v0 = __uint_as_float(v16 << 16);
+  const float m1 = __fmaf_rn(p.beta1, m0, omb1 * g);
+  const float v1 = __fmaf_rn(p.beta2, v0, omb2 * (g * g));
+  QatOut o;
+  o.m16 = bf16_rne(m1, a16);
+  o.v16 = bf16_rne(v1, a16);
+  const float mh = __uint_as_float(o.m16 << 16) / p.bias_corr1;
+  const float vh = __uint_as_float(o.v16 << 16) / p.bias_corr2;
+  const float ratio = mh / (sqrtf(vh) + p.eps);
+  const float u = -p.lr * __fmaf_rn(p.weight_decay, w, ratio);
+  const float u16 = __uint_as_float(bf16_rne(u, a16) << 16);
+  const uint32_t s16 = bf16_rne(w + u16, a16);
+  const uint32_t r = round_pattern<FMT, VAR, true>(s16 << 16, n, a8) >> Fx<FMT>::FRAC;
+  o.w8 = s16 == 0x7FC0u ? (Fx<FMT>::NAN_FX >> Fx<FMT>::FRAC) : r;
+  return o;
+}
+
+// One workgroup per 2048-element tile, 8 consecutive elements per lane: one 8-byte load of weights,
+// three 16-byte loads (gradient, both moments), the same back minus the gradient.
+template <int FMT, int VAR, int W>
+__global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, const uint16_t* __restrict__ g16,
+                                                      uint16_t* __restrict__ m16, uint16_t* __restrict__ v16,
+                                                      AdamWScalars p, int nbits, uint64_t seed, uint64_t step,
+                                                      uint64_t blk0) {
+  typedef WgTile<W> T;
+  __shared__ uint4 strip[T::BLOCKS];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int e0 = wave * kWaveElems + 8 * lane;
+  const uint64_t g0 = (uint64_t)blockIdx.x * T::ELEMS + (uint64_t)e0;
+  const uint64_t wq = *reinterpret_cast<const uint64_t*>(w8 + g0);
+  const u32x4 gq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g16 + g0));
+  const u32x4 mq = *reinterpret_cast<const u32x4*>(m16 + g0);
+  const u32x4 vq = *reinterpret_cast<const u32x4*>(v16 + g0);
+  if constexpr (VAR != kRNE) {
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, step);
+    __syncthreads();
+  }
+  const Addends a8 = make_addends<FMT, VAR>(nbits);
+  const Addends a16 = make_addends<kBF16, kRNE>(0);
+  const float omb1 = 1.0f - p.beta1, omb2 = 1.0f - p.beta2;
+  uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if constexpr (VAR != kRNE) read_wg_bits8<W>(strip, e0, a8.nbits, n);
+  const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w}, mw[4] = {mq.x, mq.y, mq.z, mq.w}, vw[4] = {vq.x, vq.y, vq.z, vq.w};
+  uint32_t mo[4] = {0, 0, 0, 0}, vo[4] = {0, 0, 0, 0};
+  uint64_t wo = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int sh = 16 * (j & 1);
+    const QatOut o = qat_one<FMT, VAR>((uint32_t)(wq >> (8 * j)) & 0xFFu, (gw[j >> 1] >> sh) & 0xFFFFu,
+                                       (mw[j >> 1] >> sh) & 0xFFFFu, (vw[j >> 1] >> sh) & 0xFFFFu, n[j], p, omb1, omb2,
+                                       a8, a16);
+    mo[j >> 1] |= o.m16 << sh;
+    vo[j >> 1] |= o.v16 << sh;
+    wo |= (uint64_t)o.w8 << (8 * j);
+  }
+  *reinterpret_cast<uint64_t*>(w8 + g0) = wo;
+  u32x4 t;
+  t.x = mo[0]; t.y = mo[1]; t.z = mo[2]; t.w = mo[3];
+  *reinterpret_cast<u32x4*>(m16 + g0) = t;
+  t.x = vo[0]; t.y = vo[1]; t.z = vo[2]; t.w = vo[3];
+  *reinterpret_cast<u32x4*>(v16 + g0) = t;
+}
+
+template <int FMT, int VAR>
+__global__ __launch_bounds__(kThreads) void qat_elems(uint8_t* __restrict__ w8, const uint16_t* __restrict__ g16,
+                                                      uint16_t* __restrict__ m16, uint16_t* __restrict__ v16, uint64_t n,
+                                                      AdamWScalars p, int nbits, int W, int log2_per_block, uint64_t seed,
+                                                      uint64_t step, uint64_t offset) {
+  const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= n) return;
+  const Addends a8 = make_addends<FMT, VAR>(nbits);
+  const Addends a16 = make_addends<kBF16, kRNE>(0);
+  uint32_t rnd = 0;
+  if constexpr (VAR != kRNE) rnd = element_bits(offset + j, log2_per_block, W, a8.nbits, seed, step);
+  const QatOut o = qat_one<FMT, VAR>(w8[j], g16[j], m16[j], v16[j], rnd, p, 1.0f - p.beta1, 1.0f - p.beta2, a8, a16);
+  w8[j] = (uint8_t)o.w8;
+  m16[j] = (uint16_t)o.m16;
+  v16[j] = (uint16_t)o.v16;
+}
+
+namespace {
+
+template <int FMT, int VAR>
+hipError_t launch_tiles_w(int W, uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t ntiles,
+                          const AdamWScalars& p, int nbits, uint64_t seed, uint64_t step, uint64_t blk0,
+                          hipStream_t stream) {
+  const dim3 grid((unsigned)ntiles), block(kThreads);
+#define FBSR_QAT_LAUNCH(WW) \
+  hipLaunchKernelGGL((qat_tiles<FMT, VAR, WW>), grid, block, 0, stream, w8, g16, m16, v16, p, nbits, seed, step, blk0)
+  if constexpr (VAR == kRNE) {
+    FBSR_QAT_LAUNCH(8);
+  } else {
+    switch (W) {
+      case 1: FBSR_QAT_LAUNCH(1); break;
+      case 2: FBSR_QAT_LAUNCH(2); break;
+      case 4: FBSR_QAT_LAUNCH(4); break;
+      case 8: FBSR_QAT_LAUNCH(8); break;
+      default: FBSR_QAT_LAUNCH(16); break;
+    }
+  }
+#undef FBSR_QAT_LAUNCH
+  return hipGetLastError();
+}
+
+template <int FMT, int VAR>
+hipError_t launch_elems(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,
+                        const AdamWScalars& p, int nbits, int W, uint64_t seed, uint64_t step, uint64_t offset,
+                        hipStream_t stream) {
+  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
+    const uint64_t m = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
+    const uint64_t blocks = (m + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL((qat_elems<FMT, VAR>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, w8 + at, g16 + at,
+                       m16 + at, v16 + at, m, p, nbits, W, log2_of(128 / W), seed, step, offset + at);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <int FMT, int VAR>
+hipError_t run(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, const AdamWScalars& p,
+               int nbits, uint64_t seed, uint64_t step, uint64_t offset, hipStream_t stream) {
+  const int W = VAR == kRNE ? 8 : slot_width(nbits);
+  Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(g16), 2, 16,
+                        reinterpret_cast<uintptr_t>(w8), 1, 8, reinterpret_cast<uintptr_t>(m16), 2, 16);
+  if ((reinterpret_cast<uintptr_t>(v16) + s.head * 2) % 16 != 0) {
+    s.head = 0;
+    s.ntiles = 0;
+  }
+  hipError_t e = launch_elems<FMT, VAR>(w8, g16, m16, v16, s.head, p, nbits, W, seed, step, offset, stream);
+  if (e != hipSuccess) return e;
+  if (s.ntiles) {
+    e = launch_tiles_w<FMT, VAR>(W, w8 + s.head, g16 + s.head, m16 + s.head, v16 + s.head, s.ntiles, p, nbits, seed,
+                                 step, (offset + s.head) / (uint64_t)(128 / W), stream);
+    if (e != hipSuccess) return e;
+  }
+  const uint64_t done = s.head + s.ntiles * s.tile_elems;
+  return launch_elems<FMT, VAR>(w8 + done, g16 + done, m16 + done, v16 + done, n - done, p, nbits, W, seed, step,
+                                offset + done, stream);
+}
+
+template <int FMT>
+hipError_t run_v(int variant, uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,
+                 const AdamWScalars& p, int nbits, uint64_t seed, uint64_t step, uint64_t offset, hipStream_t stream) {
+  switch (variant) {
+    case kRNE: return run<FMT, kRNE>(w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+    case kSRFF: return run<FMT, kSRFF>(w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+    case kSRF: return run<FMT, kSRF>(w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+    default: return run<FMT, kSRC>(w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, int fmt,
+                            const AdamWScalars& p, int variant, int nbits, uint64_t seed, uint64_t step,
+                            uint64_t offset, hipStream_t stream) {
+  if (fmt == kE4M3) return run_v<kE4M3>(variant, w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+  return run_v<kE5M2>(variant, w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+}
+
+}  // namespace fbsr

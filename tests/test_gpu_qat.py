@@ -1,0 +1,108 @@
+"""GPU parity: fbsr_qat_adamw_step (the fused step of Alg. 1) against the CPU oracle: new 8-bit
+weights and both bf16 moments byte-identical."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import dev, first_mismatch, host
+
+pytestmark = pytest.mark.gpu
+E4M3, E5M2 = 1, 2
+RNE, SRFF, SRF, SRC = 0, 1, 2, 3
+
+
+def _bf16(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def _state(n, seed, wild=False):
+    rng = np.random.default_rng(seed)
+    w8 = rng.integers(0, 256, n).astype(np.uint8)
+    g = _bf16(rng.standard_normal(n) * 0.3)
+    m = _bf16(rng.standard_normal(n) * 0.05)
+    v = _bf16(rng.random(n) * 0.02)
+    if wild:   # raw patterns: negative second moments, infinities, NaNs, subnormals, huge gradients
+        k = n // 4
+        g[:k] = rng.integers(0, 1 << 16, k).astype(np.uint16)
+        m[k:2 * k] = rng.integers(0, 1 << 16, k).astype(np.uint16)
+        v[2 * k:3 * k] = rng.integers(0, 1 << 16, k).astype(np.uint16)
+    return w8, g, m, v
+
+
+def _oracle_step(oracle, w8, g, m, v, fmt, params, variant, nbits, seed, step, offset, threads=16):
+    n = w8.size
+    if n < 4096:
+        return oracle.qat_adamw_step(w8, g, m, v, fmt, params, variant, nbits, seed, step, offset)
+    cuts = np.linspace(0, n, threads + 1).astype(np.int64)
+    with ThreadPoolExecutor(threads) as pool:
+        parts = list(pool.map(lambda ab: oracle.qat_adamw_step(w8[ab[0]:ab[1]], g[ab[0]:ab[1]], m[ab[0]:ab[1]], v[ab[0]:ab[1]],
+                                                               fmt, params, variant, nbits, seed, step, offset + int(ab[0])),
+                              zip(cuts[:-1], cuts[1:])))
+    return tuple(np.concatenate([p[i] for p in parts]) for i in range(3))
+
+
+PARAMS = [(1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9, 1 - 0.999),
+          (3e-2, 0.9, 0.95, 1e-8, 0.1, 1 - 0.9 ** 3, 1 - 0.95 ** 3),
+          (0.5, 0.0, 0.5, 1e-3, 0.0, 1.0, 0.5)]
+
+
+@pytest.mark.parametrize("fmt", [E4M3, E5M2])
+def test_single_step(fbsr, oracle, fmt):
+    for n in (0, 1, 7, 8, 2047, 2048, 5 * 2048 + 333):
+        for wild in (False, True):
+            w8, g, m, v = _state(max(n, 1), 100 + n, wild)
+            w8, g, m, v = w8[:n], g[:n], m[:n], v[:n]
+            for params in PARAMS:
+                for variant, nbits, offset, step in ((RNE, 0, 0, 1), (SRFF, 3, 0, 2), (SRF, 3, 16, 7), (SRC, 4, 5, 1 << 33),
+                                                     (SRC, 1, 0, 3), (SRF, 16, 128, 9)):
+                    print("case fmt=%d n=%d wild=%d lr=%g variant=%d nbits=%d offset=%d" % (fmt, n, wild, params[0], variant, nbits, offset), flush=True)
+                    if n:
+                        wd, gd, md, vd = dev(w8), dev(g), dev(m), dev(v)
+                    else:
+                        wd = torch.empty(0, dtype=torch.uint8, device="cuda")
+                        gd = md = vd = torch.empty(0, dtype=torch.int16, device="cuda")
+                        md, vd = md.clone(), vd.clone()
+                    fbsr.fbsr_qat_adamw_step(wd, gd, md, vd, fmt, params, variant, nbits, seed=31, step=step, offset=offset)
+                    ww, mm, vv = _oracle_step(oracle, w8, g, m, v, fmt, params, variant, nbits, 31, step, offset)
+                    assert first_mismatch(host(md), mm) is None, "first moment"
+                    assert first_mismatch(host(vd), vv) is None, "second moment"
+                    assert first_mismatch(host(wd), ww) is None, "weights"
+                    assert np.array_equal(host(gd), g), "gradient buffer was written"
+
+
+def test_unaligned_buffers(fbsr, oracle):
+    n = 3 * 2048 + 50
+    w8, g, m, v = _state(n + 8, 9)
+    for shift in (1, 3):
+        wd, gd, md, vd = dev(w8), dev(g), dev(m), dev(v)
+        sl = slice(shift, shift + n)
+        fbsr.fbsr_qat_adamw_step(wd[sl], gd[sl], md[sl], vd[sl], E4M3, PARAMS[1], SRC, 3, seed=1, step=1)
+        ww, mm, vv = _oracle_step(oracle, w8[sl], g[sl], m[sl], v[sl], E4M3, PARAMS[1], SRC, 3, 1, 1, 0)
+        for got, want, orig in ((wd, ww, w8), (md, mm, m), (vd, vv, v)):
+            full = host(got)
+            assert first_mismatch(full[sl], want) is None
+            assert np.array_equal(full[:shift], orig[:shift]) and np.array_equal(full[shift + n:], orig[shift + n:])
+
+
+def test_ten_steps_at_2_22(fbsr, oracle):
+    """A short training run: 2^22 weights, 10 steps with fresh gradients, N = 3 (the paper's setting),
+    every variant: the GPU trajectory stays identical to the oracle's."""
+    n = 1 << 22
+    lr, b1, b2, eps, wdecay = 2e-2, 0.9, 0.99, 1e-8, 0.01
+    for variant in (RNE, SRFF, SRF, SRC):
+        w8, _, m, v = _state(n, 77)
+        m[:] = 0
+        v[:] = 0
+        w8 &= 0x77          # moderate magnitudes, no NaN codes
+        wd, md, vd = dev(w8), dev(m), dev(v)
+        rng = np.random.default_rng(5)
+        for t in range(1, 11):
+            g = _bf16(rng.standard_normal(n) * 0.2)
+            params = (lr, b1, b2, eps, wdecay, 1 - b1 ** t, 1 - b2 ** t)
+            fbsr.fbsr_qat_adamw_step(wd, dev(g), md, vd, E4M3, params, variant, 3, seed=8, step=t)
+            w8, m, v = _oracle_step(oracle, w8, g, m, v, E4M3, params, variant, 3, 8, t, 0)
+        print("case variant=%d" % variant, flush=True)
+        assert first_mismatch(host(md), m) is None and first_mismatch(host(vd), v) is None
+        assert first_mismatch(host(wd), w8) is None
