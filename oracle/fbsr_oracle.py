@@ -12,6 +12,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCE = os.path.join(_HERE, "fbsr_oracle.cpp")
 LIB = os.path.join(_HERE, "liboracle_fbsr.so")
+# A test that plants a mistake in a COPY of the oracle points this at the mutated build.
+_OVERRIDE = os.environ.get("FBSR_ORACLE_LIB")
 
 FMT_BF16, FMT_E4M3, FMT_E5M2 = 0, 1, 2
 SRC_BF16, SRC_FP16 = 0, 1
@@ -23,6 +25,8 @@ VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
 def build(force=False):
     """Compile the oracle with the host compiler (no contraction: the SGD step's single
     fused multiply-add must stay the only fused operation)."""
+    if _OVERRIDE:
+        return _OVERRIDE
     if force or not os.path.exists(LIB) or os.path.getmtime(LIB) < os.path.getmtime(SOURCE):
         subprocess.check_call(
             ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fPIC", "-shared", "-pthread",

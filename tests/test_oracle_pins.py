@@ -467,8 +467,10 @@ def _fp8_values(codes, fmt):
     return torch.from_numpy(codes).view(tdt).to(torch.float32).numpy()
 
 
+@pytest.mark.parametrize("hyper", [(3e-2, 0.9, 0.95, 1e-8, 0.1), (0.1, 0.8, 0.9, 1e-6, 5.0)],
+                         ids=["small_decay", "large_decay"])
 @pytest.mark.parametrize("fmt", [E4M3, E5M2])
-def test_qat_step_tracks_library_adamw(oracle, fmt):
+def test_qat_step_tracks_library_adamw(oracle, fmt, hyper):
     """Three steps of Alg. 1 with the oracle against torch.optim.AdamW in fp32 on the same gradients:
     the bf16 moments stay within bf16 rounding of the fp32 moments, and each new 8-bit weight is within
     one target ulp (plus the 16-bit roundings) of the fp32 update of the previous 8-bit weight.  A
@@ -478,7 +480,7 @@ def test_qat_step_tracks_library_adamw(oracle, fmt):
     vals, codes = finite_table(fmt)
     pick = rng.integers(8, len(codes) - 8, n)
     w8 = (np.array(codes, dtype=np.uint8)[pick] | (rng.integers(0, 2, n).astype(np.uint8) << 7)).astype(np.uint8)
-    lr, b1, b2, eps, wd = 3e-2, 0.9, 0.95, 1e-8, 0.1
+    lr, b1, b2, eps, wd = hyper      # large_decay: lr * wd = 0.5, so the decay term alone moves weights by many ulps
     m16 = np.zeros(n, np.uint16)
     v16 = np.zeros(n, np.uint16)
     m_ref = np.zeros(n, np.float64)
