@@ -147,11 +147,12 @@ bool round_up(int variant, double fl, double delta, int N, uint64_t n) {
   return false;
 }
 
-// One element: fp32 value -> code of the target format, given the integer n < 2^N.
-uint32_t round_one(float xf, const Format& f, int variant, int N, uint64_t n) {
-  const uint32_t sign_code = (std::signbit(xf) ? 1u : 0u) << (f.K - 1);
-  if (std::isnan(xf)) return sign_code | f.nan_code;
-  const double a = std::fabs((double)xf);
+// One element: a value with at most 24 significant bits (an fp32 value, or one scaled exactly by a
+// power of two) -> code of the target format, given the integer n < 2^N.
+uint32_t round_one(double xv, const Format& f, int variant, int N, uint64_t n) {
+  const uint32_t sign_code = (std::signbit(xv) ? 1u : 0u) << (f.K - 1);
+  if (std::isnan(xv)) return sign_code | f.nan_code;
+  const double a = std::fabs(xv);
   if (a == 0.0) return sign_code;
   if (a > f.M) {  // outside the finite range: deterministic
     const int eM = std::ilogb(f.M);
@@ -380,6 +381,48 @@ uint32_t oracle_widen16(uint16_t code, int src_fmt) {
   uint32_t bits;
   std::memcpy(&bits, &v, 4);
   return bits;
+}
+
+// Block-scaled target (Sec. I-A: "blocks of low-precision values are accompanied by a scale factor,
+// which may be a power of two"; the paper fixes no rule for choosing it).  Reading taken: blocks of 32
+// consecutive elements of the call share the power-of-two scale 2^s with
+//   s = clamp(floor(log2 amax) - emax, -127, 127),  amax = max |x| over the block,
+//   emax = floor(log2 M) of the element format (8 for E4M3, 15 for E5M2),
+// stored as the byte s + 127 (a pure-exponent code; 0xFF marks a block that holds a NaN or an
+// infinity, all of whose elements become the positive canonical NaN), and every element is
+// FBSR(x 2^-s) -- an exact scaling -- with the random bits of global index offset + j as in
+// oracle_round.  The block's largest element lands in [2^emax, 2^(emax+1)); what exceeds M there is
+// rounded by the out-of-range rule.  A block of zeros takes s = -127.  The last block may be short.
+int oracle_round_block_scaled(const float* x, uint8_t* out, uint8_t* scales, uint64_t n, int fmt, int variant,
+                              int nbits, uint64_t seed, uint64_t offset) {
+  Format f;
+  if (!args_ok(fmt, variant, nbits, &f) || (fmt != FMT_E4M3 && fmt != FMT_E5M2)) return 1;
+  const int emax = std::ilogb(f.M);
+  const uint64_t B = 32;
+  for (uint64_t b0 = 0; b0 < n; b0 += B) {
+    const uint64_t len = n - b0 < B ? n - b0 : B;
+    double amax = 0.0;
+    bool special = false;
+    for (uint64_t k = 0; k < len; ++k) {
+      const double a = std::fabs((double)x[b0 + k]);
+      if (!std::isfinite(a)) special = true;
+      else if (a > amax) amax = a;
+    }
+    if (special) {
+      scales[b0 / B] = 0xFFu;
+      for (uint64_t k = 0; k < len; ++k) out[b0 + k] = (uint8_t)f.nan_code;
+      continue;
+    }
+    int s = amax == 0.0 ? -127 : std::ilogb(amax) - emax;
+    s = s < -127 ? -127 : (s > 127 ? 127 : s);
+    scales[b0 / B] = (uint8_t)(s + 127);
+    for (uint64_t k = 0; k < len; ++k) {
+      const uint64_t j = b0 + k;
+      const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, 0, offset + j, nbits);
+      out[j] = (uint8_t)round_one(std::ldexp((double)x[j], -s), f, variant, nbits, r);
+    }
+  }
+  return 0;
 }
 
 // Alg. 1's "w <- RoundTo(w + u)" in the SGD form u = -lr * g: the bf16 weight is

@@ -66,6 +66,8 @@ def lib():
         L.oracle_widen16.restype = u32
         L.oracle_qat_adamw_step.argtypes = [vp, vp, vp, vp, u64, i32, vp, i32, i32, u64, u64, u64]
         L.oracle_qat_adamw_step.restype = i32
+        L.oracle_round_block_scaled.argtypes = [vp, vp, vp, u64, i32, i32, i32, u64, u64]
+        L.oracle_round_block_scaled.restype = i32
         L.oracle_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64]
         L.oracle_sgd_update.restype = i32
         L.oracle_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp]
@@ -145,6 +147,17 @@ def round_from16(x, src_fmt, fmt, variant, nbits, seed, offset=0):
 def widen16(code, src_fmt):
     """fp32 bit pattern of the exact value of a 16-bit source code."""
     return int(lib().oracle_widen16(int(code), src_fmt))
+
+
+def round_block_scaled(x, fmt, variant, nbits, seed, offset=0):
+    """Blocks of 32 share a power-of-two scale.  Returns (codes uint8[n], scales uint8[ceil(n/32)])."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.size, dtype=np.uint8)
+    scales = np.empty((x.size + 31) // 32, dtype=np.uint8)
+    rc = lib().oracle_round_block_scaled(_ptr(x), _ptr(out), _ptr(scales), x.size, fmt, variant, nbits, seed, offset)
+    if rc != 0:
+        raise ValueError("oracle_round_block_scaled: status %d" % rc)
+    return out, scales
 
 
 def sgd_update(w, g, lr, variant, nbits, seed, step, offset=0):

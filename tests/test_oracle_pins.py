@@ -559,3 +559,62 @@ def test_qat_step_structure(oracle):
     want = np.array([oracle.round_with_n(x, fmt, variant, nbits, oracle.random_bits(seed, step, off + j, nbits))
                      for j, x in enumerate(_bf16_values(s16))], dtype=np.uint8)
     assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ block-scaled targets -------
+def test_block_scale_rule_and_composition(oracle):
+    """Sec. I-A's scaled tensors with a power-of-two scale per block of 32.  The scale exponent is
+    floor(log2 amax) - emax (library frexp), the elements are exactly the plain FBSR of the values
+    scaled by that power of two, the block maximum lands in [2^emax, 2^(emax+1)), and multiplying a
+    whole tensor by 2^k changes the scale bytes by k and no element code."""
+    rng = np.random.default_rng(8)
+    n = 32 * 200 + 13                                   # a short last block
+    x = (rng.standard_normal(n) * np.exp2(rng.integers(-20, 20, n))).astype(np.float32)
+    x[32 * 5:32 * 6] = 0.0                              # a block of zeros
+    x[32 * 7 + 3] = np.float32(3.0e38)
+    for fmt, emax in ((E4M3, 8), (E5M2, 15)):
+        for variant, nbits in ((RNE, 0), (SRFF, 2), (SRF, 3), (SRC, 4)):
+            codes, scales = oracle.round_block_scaled(x, fmt, variant, nbits, seed=3, offset=64)
+            assert scales.size == (n + 31) // 32
+            for b in range(scales.size):
+                blk = x[32 * b:32 * b + 32]
+                amax = float(np.max(np.abs(blk)))
+                if amax == 0.0:
+                    assert scales[b] == 0
+                    assert not (codes[32 * b:32 * b + 32] & 0x7F).any()
+                    continue
+                mant, ex = np.frexp(amax)              # amax = mant * 2^ex, mant in [0.5, 1)
+                s = max(-127, min(127, int(ex) - 1 - emax))
+                assert int(scales[b]) - 127 == s
+                scaled = np.ldexp(blk.astype(np.float64), -s)
+                assert 2.0 ** emax <= np.max(np.abs(scaled)) < 2.0 ** (emax + 1)
+                inexact = scaled.astype(np.float32).astype(np.float64) != scaled
+                assert np.all(np.abs(scaled[inexact]) < 2.0 ** -126)      # only fp32 underflow, far below any fp8 grid
+                want = oracle.round_(scaled.astype(np.float32), fmt, variant, nbits, seed=3, offset=64 + 32 * b)
+                assert np.array_equal(codes[32 * b:32 * b + 32], want)
+            for k in (-7, 11):
+                xk64 = np.ldexp(x.astype(np.float64), k)
+                xk = xk64.astype(np.float32)
+                c2, s2 = oracle.round_block_scaled(xk, fmt, variant, nbits, seed=3, offset=64)
+                for b in range(scales.size):
+                    sl = slice(32 * b, 32 * b + 32)
+                    if scales[b] == 0 or not np.array_equal(xk[sl].astype(np.float64), xk64[sl]):
+                        continue          # zeros, or the shifted block left fp32's exact range
+                    assert np.array_equal(c2[sl], codes[sl]) and int(s2[b]) == int(scales[b]) + k
+
+
+def test_block_scale_specials(oracle):
+    """A block that holds a NaN or an infinity is marked with the scale byte 0xFF and all its elements
+    become the positive canonical NaN; neighbouring blocks are untouched.  Scale exponents clamp at
+    -127 for blocks of fp32 subnormals."""
+    x = np.ones(32 * 4, dtype=np.float32)
+    x[40] = np.float32(np.nan)
+    x[70] = np.float32(-np.inf)
+    x[96:128] = _f32(np.arange(1, 33, dtype=np.uint32))          # fp32 subnormals
+    for fmt, nan_code in ((E4M3, 0x7F), (E5M2, 0x7E)):
+        codes, scales = oracle.round_block_scaled(x, fmt, SRF, 3, seed=1)
+        assert scales[1] == 0xFF and scales[2] == 0xFF
+        assert np.all(codes[32:96] == nan_code)
+        assert scales[0] == 127 - (8 if fmt == E4M3 else 15)
+        assert np.all(codes[:32] == oracle.round_with_n(np.float32(2.0 ** (8 if fmt == E4M3 else 15)), fmt, RNE, 1, 0))
+        assert scales[3] == 0
