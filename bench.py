@@ -176,6 +176,18 @@ def main():
             paths["round_from_bf16_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
                 "ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
         del x16
+        # block-scaled fp8 target (one scale byte per 32 elements: 4 B read + 1 + 1/32 B written per element)
+        sc = torch.empty(n // 32, dtype=torch.uint8, device="cuda")
+        rotb = [0]
+
+        def blockscaled(f, v, nb):
+            rotb[0] += 1
+            fbsr.fbsr_round_block_scaled(x_rot[f][rotb[0] % 3], f, v, nb, seed=2, offset=0, out=out_rot[rotb[0] % 4], scales=sc)
+        for f, v, nb in ((fbsr.FMT_E4M3, fbsr.SRC, 3), (fbsr.FMT_E5M2, fbsr.SRF, 8)):
+            ms = timed_launches(torch, lambda: blockscaled(f, v, nb), 12)
+            paths["round_block_scaled_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
+                "ms": round(ms, 4), "gb_s": round((5.0 + 1.0 / 32) * n / ms / 1e6, 1)}
+        del sc
         # fused QAT step of Alg. 1 (7 B read + 5 B written per element), N = 3, 2^27 weights, rotated buffers
         nq = min(SGD_ELEMS, n)
         qs = [(torch.from_numpy((workloads.sgd_weights(nq, seed=40 + k) & 0x7777).view(np.uint8)[:nq].copy()).cuda(),

@@ -100,6 +100,23 @@ int fbsr_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt
 int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, int nbits,
                     uint64_t seed, uint64_t step, uint64_t offset, void* stream);
 
+/* Elements per shared scale in fbsr_round_block_scaled. */
+#define FBSR_SCALE_BLOCK 32
+
+/* Block-scaled fp8 target (Sec. I-A: "blocks of low-precision values are accompanied by a scale factor,
+ * which may be a power of two"; the paper fixes no rule for it).  Blocks of FBSR_SCALE_BLOCK consecutive
+ * elements of the call (element j belongs to block j / 32; the last block may be short) share the scale
+ * 2^s,  s = clamp(floor(log2 amax) - emax, -127, 127),  amax = max |x| over the block,
+ * emax = floor(log2 M) of the element format (8 for E4M3, 15 for E5M2);  scales[b] = s + 127.
+ * Every element is out[j] = FBSR_fmt(x[j] * 2^-s) (an exact scaling) with the random bits of global index
+ * offset + j, as in fbsr_round; the block's largest element lands in [2^emax, 2^(emax+1)) and whatever
+ * exceeds M there follows fbsr_round's out-of-range rule.  A block of zeros has s = -127.  A block that
+ * holds a NaN or an infinity gets scales[b] = 0xFF and all its elements the positive canonical NaN.
+ * x: n floats (device, read).  out: n fp8 codes (device, written).  scales: ceil(n / 32) bytes (device,
+ * written).  fmt must be FBSR_FMT_E4M3 or FBSR_FMT_E5M2.  Errors as fbsr_round. */
+int fbsr_round_block_scaled(const float* x, void* out, void* scales, uint64_t n, int fmt, int variant,
+                            int nbits, uint64_t seed, uint64_t offset, void* stream);
+
 /* Scalars of one AdamW step (decoupled weight decay).  bias_corr1 = 1 - beta1^t and
  * bias_corr2 = 1 - beta2^t for the step count t >= 1 are supplied by the caller. */
 typedef struct {

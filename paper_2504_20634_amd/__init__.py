@@ -2,8 +2,8 @@
 (include/fbsr.h, built into paper_2504_20634_amd/libfbsr.so) and this thin ctypes binding."""
 from . import binding
 from .binding import (FMT_BF16, FMT_E4M3, FMT_E5M2, RNE, SRFF, SRF, SRC, SRC_BF16, SRC_FP16, FbsrError,
-                      bias_stats_workspace_bytes, fbsr_bias_stats, fbsr_qat_adamw_step, fbsr_round, fbsr_round_from16,
+                      bias_stats_workspace_bytes, fbsr_bias_stats, fbsr_qat_adamw_step, fbsr_round, fbsr_round_block_scaled, fbsr_round_from16,
                       fbsr_sgd_update)
 
 __all__ = ["binding", "FMT_BF16", "FMT_E4M3", "FMT_E5M2", "RNE", "SRFF", "SRF", "SRC", "SRC_BF16", "SRC_FP16", "FbsrError",
-           "bias_stats_workspace_bytes", "fbsr_bias_stats", "fbsr_qat_adamw_step", "fbsr_round", "fbsr_round_from16", "fbsr_sgd_update"]
+           "bias_stats_workspace_bytes", "fbsr_bias_stats", "fbsr_qat_adamw_step", "fbsr_round", "fbsr_round_block_scaled", "fbsr_round_from16", "fbsr_sgd_update"]

@@ -17,7 +17,7 @@ OK, EINVAL, EALIGN, ERANGE, EDEVICE = 0, 1, 2, 3, 4
 MAX_NBITS = 16
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
-EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
+EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
            "fbsr_strerror", "fbsr_version")
 
 
@@ -44,6 +44,8 @@ def lib():
         L.fbsr_round.restype = i32
         L.fbsr_round_from16.argtypes = [vp, vp, u64, i32, i32, i32, i32, u64, u64, vp]
         L.fbsr_round_from16.restype = i32
+        L.fbsr_round_block_scaled.argtypes = [vp, vp, vp, u64, i32, i32, i32, u64, u64, vp]
+        L.fbsr_round_block_scaled.restype = i32
         L.fbsr_qat_adamw_step.argtypes = [vp, vp, vp, vp, u64, i32, vp, i32, i32, u64, u64, u64, vp]
         L.fbsr_qat_adamw_step.restype = i32
         L.fbsr_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64, vp]
@@ -108,6 +110,27 @@ def fbsr_round_from16(x, src_fmt, fmt, variant, nbits, seed, offset=0, out=None,
     _check(lib().fbsr_round_from16(x.data_ptr(), out.data_ptr(), n, src_fmt, fmt, variant, nbits, seed,
                                    offset, _stream_handle(stream)), "fbsr_round_from16")
     return out
+
+
+SCALE_BLOCK = 32
+
+
+def fbsr_round_block_scaled(x, fmt, variant, nbits, seed, offset=0, out=None, scales=None, stream=None):
+    """Blocks of 32 share a power-of-two scale.  x: float32 CUDA tensor.  Returns (codes uint8[n],
+    scales uint8[ceil(n / 32)])."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    n = x.numel()
+    nb = (n + SCALE_BLOCK - 1) // SCALE_BLOCK
+    if out is None:
+        out = torch.empty(n, dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty(nb, dtype=torch.uint8, device=x.device)
+    assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.dtype == torch.uint8
+    assert scales.is_cuda and scales.is_contiguous() and scales.numel() == nb and scales.dtype == torch.uint8
+    _check(lib().fbsr_round_block_scaled(x.data_ptr(), out.data_ptr(), scales.data_ptr(), n, fmt, variant, nbits,
+                                         seed, offset, _stream_handle(stream)), "fbsr_round_block_scaled")
+    return out, scales
 
 
 class AdamW(ctypes.Structure):

@@ -61,6 +61,20 @@ int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, 
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 
+int fbsr_round_block_scaled(const float* x, void* out, void* scales, uint64_t n, int fmt, int variant, int nbits,
+                            uint64_t seed, uint64_t offset, void* stream) {
+  if (fmt != FBSR_FMT_E4M3 && fmt != FBSR_FMT_E5M2) return FBSR_EINVAL;
+  const int c = check_common(variant, nbits, n, offset);
+  if (c != FBSR_OK) return c;
+  if (n == 0) return FBSR_OK;
+  if (x == nullptr || out == nullptr || scales == nullptr) return FBSR_EINVAL;
+  if (misaligned(x, 4)) return FBSR_EALIGN;
+  const hipError_t e = fbsr::launch_round_block_scaled(x, reinterpret_cast<uint8_t*>(out), reinterpret_cast<uint8_t*>(scales),
+                                                       n, fmt, variant, nbits, seed, offset,
+                                                       reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
 int fbsr_qat_adamw_step(void* w8, const void* g16, void* m16, void* v16, uint64_t n, int fmt, const fbsr_adamw* p,
                         int variant, int nbits, uint64_t seed, uint64_t step, uint64_t offset, void* stream) {
   if (fmt != FBSR_FMT_E4M3 && fmt != FBSR_FMT_E5M2) return FBSR_EINVAL;

@@ -66,6 +66,9 @@ hipError_t launch_round_from16(const void* x, void* out, uint64_t n, int src_fmt
 hipError_t launch_sgd(void* w, const float* g, uint64_t n, float lr, int variant, int nbits, uint64_t seed,
                       uint64_t step, uint64_t offset, hipStream_t stream);
 
+hipError_t launch_round_block_scaled(const float* x, uint8_t* out, uint8_t* scales, uint64_t n, int fmt, int variant,
+                                    int nbits, uint64_t seed, uint64_t offset, hipStream_t stream);
+
 struct AdamWScalars {
   float lr, beta1, beta2, eps, weight_decay, bias_corr1, bias_corr2;
 };

@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
-    assert {"fbsr_round", "fbsr_round_from16", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
+    assert {"fbsr_round", "fbsr_round_from16", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
             "fbsr_strerror", "fbsr_version"} <= set(names)
     for name in names:
         assert hasattr(L, name), name
@@ -72,6 +72,10 @@ def test_argument_validation_happens_on_the_host(L):
     assert L.fbsr_round_from16(None, None, 0, 0, 1, 1, 2, 0, 0, None) == OK
     assert L.fbsr_round_from16(p(good + 1), p(good), 8, 0, 1, 1, 2, 0, 0, None) == EALIGN
     assert L.fbsr_round_from16(p(good), None, 8, 0, 1, 1, 2, 0, 0, None) == EINVAL
+    assert L.fbsr_round_block_scaled(None, None, None, 0, 1, 1, 2, 0, 0, None) == OK
+    assert L.fbsr_round_block_scaled(p(good), p(good), p(good), 8, 0, 1, 2, 0, 0, None) == EINVAL      # bf16 elements
+    assert L.fbsr_round_block_scaled(p(good), p(good), None, 8, 1, 1, 2, 0, 0, None) == EINVAL
+    assert L.fbsr_round_block_scaled(p(good + 2), p(good), p(good), 8, 1, 1, 2, 0, 0, None) == EALIGN
     hp = (ctypes.c_float * 7)(1e-3, 0.9, 0.999, 1e-8, 0.0, 0.1, 0.001)
     assert L.fbsr_qat_adamw_step(None, None, None, None, 0, 1, hp, 1, 3, 0, 0, 0, None) == OK
     assert L.fbsr_qat_adamw_step(p(good), p(good), p(good), p(good), 8, 0, hp, 1, 3, 0, 0, 0, None) == EINVAL   # bf16 target
