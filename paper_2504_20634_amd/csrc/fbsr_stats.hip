@@ -14,7 +14,7 @@
 namespace fbsr {
 
 struct Acc {
-  double sy, se, see;
+  double sy, se, see;   // sum y, sum e, sum e^2
 };
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -51,36 +51,41 @@ __device__ __forceinline__ float decode_top(uint32_t r) {
 template <int FMT>
 __device__ __forceinline__ double inv_ulp(uint32_t bits) {
   typedef Fx<FMT> F;
-  const int ef = (int)((bits >> 23) & 0xFFu) - 127;
-  const int et = ef > 1 - F::B ? ef : 1 - F::B;
-  const uint32_t hi = (uint32_t)(1023 + F::P - 1 - et) << 20;
+  constexpr uint32_t kMinField = (uint32_t)(1 - F::B + 127) << 23;          // exponent field of the clamp 1 - B
+  constexpr uint32_t kTop = (uint32_t)(1023 + F::P - 1 + 127) << 20;        // fp64 exponent of 2^(P-1) re-biased
+  const uint32_t ef = bits & 0x7F800000u;
+  const uint32_t hi = kTop - ((ef > kMinField ? ef : kMinField) >> 3);      // 2^(P - 1 - e~)
   return __hiloint2double((int)hi, 0);
 }
 
-// The definition, in fp64, for any value (overflow, saturation, NaN, inputs with bits below the
-// code space's resolution).
-template <int FMT>
-__device__ __forceinline__ void accumulate(Acc& acc, uint32_t bits, uint32_t r) {
-  const double y = (double)decode_top<FMT>(r);
-  const double e = (y - (double)__uint_as_float(bits)) * inv_ulp<FMT>(bits);
-  acc.sy += y;
+// Adds one element to a bin's sums.  WIDE = false: y - x is formed in fp32, where it is exact for
+// every finite |x| <= M (y is a neighbour of x on a coarser grid, so the difference is a multiple of
+// x's own last place and smaller than 2^24 of them); WIDE = true: the difference is formed in fp64
+// (overflow, saturation, NaN: values for which the fp32 difference would round or is not finite).
+// Either way e = (y - x) / ulp_t(x) is an exact scaling by a power of two in fp64.
+template <int FMT, bool WIDE>
+__device__ __forceinline__ void accumulate(Acc& acc, uint32_t bits, float y) {
+  const float x = __uint_as_float(bits);
+  double d;
+  if constexpr (WIDE) d = (double)y - (double)x;
+  else d = (double)(y - x);
+  const double e = d * inv_ulp<FMT>(bits);
+  acc.sy += (double)y;
   acc.se += e;
   acc.see = fma(e, e, acc.see);
 }
 
-// Per-thread partial sums of one bin.  In the common case (|x| <= M, and no input bit below the
-// code space's resolution) e 2^FRAC is the integer (rounded code << FRAC) - r0, so sum e and
-// sum e^2 are accumulated exactly in integers and only y takes an fp64 add per element; all
-// other values go through `accumulate` into `wide`.
-struct BinSums {
-  double sy;
-  int64_t se_fix;      // sum of e 2^FRAC
-  uint64_t see_fix;    // sum of (e 2^FRAC)^2
-  Acc wide;
-  __device__ __forceinline__ void clear() {
-    sy = 0.0; se_fix = 0; see_fix = 0; wide = {0.0, 0.0, 0.0};
+// The four decoded values of a packed fp8 word (the hardware decode equals Eq. (1) on all 256 codes).
+template <int FMT>
+__device__ __forceinline__ void decode4(uint32_t packed, float (&y)[4]) {
+  if constexpr (FMT == kE4M3) {
+    y[0] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 0); y[1] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 1);
+    y[2] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 2); y[3] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 3);
+  } else {
+    y[0] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 0); y[1] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 1);
+    y[2] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 2); y[3] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 3);
   }
-};
+}
 
 // One workgroup per chunk of kStatsChunkTiles tiles.  Sums run in registers across the chunk's
 // tiles and are flushed (wave butterfly -> LDS -> record) when a bin ends and at the chunk's end:
@@ -94,24 +99,20 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
   typedef Fx<FMT> F;
   __shared__ uint4 strip[2][T::BLOCKS];
   __shared__ double staged[kWavesPerBlock][kStatsRecordDoubles];
-  __shared__ float lut[256];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  constexpr uint32_t kFracMask = (1u << F::FRAC) - 1u;
-  if constexpr (F::kIsFp8) lut[threadIdx.x] = decode_top<FMT>((uint32_t)threadIdx.x << 24);   // all 256 signed codes
 
   const Addends a = make_addends<FMT, VAR>(nbits);
+  HwAddends hw = {0, 0, 0, 0};
+  if constexpr (F::kIsFp8 && VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
   const uint64_t tile0 = (uint64_t)blockIdx.x * kStatsChunkTiles;
   const uint64_t chunk_start = i0 + tile0 * T::ELEMS;
   uint64_t next_bin = group - chunk_start % group;   // chunk-relative index at which the next bin starts
   uint64_t slot = 0;
-  BinSums cur;
-  cur.clear();
+  Acc cur = {0.0, 0.0, 0.0};
 
   auto flush = [&]() {
-    const double se = (double)cur.se_fix * (1.0 / (double)(1u << F::FRAC)) + cur.wide.se;
-    const double see = (double)cur.see_fix * (1.0 / ((double)(1u << F::FRAC) * (double)(1u << F::FRAC))) + cur.wide.see;
-    const double t0 = wave_sum(cur.sy + cur.wide.sy), t1 = wave_sum(se), t2 = wave_sum(see);
+    const double t0 = wave_sum(cur.sy), t1 = wave_sum(cur.se), t2 = wave_sum(cur.see);
     if (lane == 0) {
       staged[wave][0] = t0; staged[wave][1] = t1; staged[wave][2] = t2;
     }
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
     }
     __syncthreads();
     slot += 1;
-    cur.clear();
+    cur = {0.0, 0.0, 0.0};
   };
 
 #pragma unroll 1
@@ -137,57 +138,58 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
     for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
     if constexpr (VAR != kRNE) fill_wg_bits<W>(strip[it & 1], threadIdx.x, blk0 + tile * T::BLOCKS, seed, 0);
     // one barrier per tile: it also orders this fill after every wave's reads of two tiles ago
-    // (they precede that wave's arrival at the previous barrier) and publishes the decode table
+    // (they precede that wave's arrival at the previous barrier)
     __syncthreads();
 
-    uint32_t r0[kRows][4], rm[kRows][4], b[kRows][4];
-    uint64_t rb[kRows];
-    uint32_t bad = 0;
+    uint32_t b[kRows][4];
+    float y[kRows][4];
+    uint32_t umax = 0;
 #pragma unroll
     for (int k = 0; k < kRows; ++k) {
-      rb[k] = 0;
-      if constexpr (VAR != kRNE) rb[k] = read_wg_row_bits<W>(strip[it & 1], wave, lane, k);
       b[k][0] = __float_as_uint(v[k].x); b[k][1] = __float_as_uint(v[k].y);
       b[k][2] = __float_as_uint(v[k].z); b[k][3] = __float_as_uint(v[k].w);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t u = b[k][j] & 0x7FFFFFFFu;
-        bad |= (u > F::U_MAXFIN) ? 1u : 0u;
-        if constexpr (F::U_EXACT != 0) bad |= (u - 1u < F::U_EXACT - 1u) ? 1u : 0u;   // 0 < u < U_EXACT
-      }
+      for (int j = 0; j < 4; ++j) umax = max(umax, b[k][j] & 0x7FFFFFFFu);
     }
-    // wave-uniform: does any element need the fp64 definition (|x| > M, NaN, bits below the code
-    // space's resolution)?  If not, the unchecked rounding add is allowed as well.
-    const bool wide_path = __any(bad);
-#pragma unroll
-    for (int k = 0; k < kRows; ++k)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) r0[k][j] = to_code_space<FMT, VAR>(b[k][j]);
-    if (wide_path) {
-#pragma unroll
-      for (int k = 0; k < kRows; ++k)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          rm[k][j] = round_magnitude<FMT, VAR, true>(b[k][j], r0[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb[k], j, a.nbits), a);
-    } else {
-#pragma unroll
-      for (int k = 0; k < kRows; ++k)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          rm[k][j] = round_magnitude<FMT, VAR, false>(b[k][j], r0[k][j], VAR == kRNE ? 0u : slot_bits<W>(rb[k], j, a.nbits), a);
-    }
+    // wave-uniform: |x| > M or NaN anywhere in the wave sends it down the checked integer rounding and
+    // the fp64 difference; otherwise the unchecked rounding (hardware converts for fp8) applies
+    const bool wide_path = __any(umax > F::U_MAXFIN);
 #pragma unroll
     for (int k = 0; k < kRows; ++k) {
-      if (out != nullptr) {
-        const uint64_t row = row0 + (uint64_t)(k * 64);
-        uint32_t s[4];
+      uint64_t rb = 0;
+      if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip[it & 1], wave, lane, k);
+      const uint32_t n4[4] = {VAR == kRNE ? 0u : slot_bits<W>(rb, 0, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 1, a.nbits),
+                              VAR == kRNE ? 0u : slot_bits<W>(rb, 2, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 3, a.nbits)};
+      uint32_t r[4];
+      uint32_t packed = 0;
+      bool have_packed = false;
+      if (wide_path) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s[j] = rm[k][j] | (b[k][j] & 0x80000000u);
-        if constexpr (F::kIsFp8) {
-          reinterpret_cast<uint32_t*>(out)[row] = pack4_fp8<FMT>(s[0], s[1], s[2], s[3]);
+        for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, true>(b[k][j], n4[j], a);
+      } else {
+        if constexpr (F::kIsFp8 && VAR != kRNE) {
+          packed = round4_fp8_hw<FMT, VAR>(b[k], n4, hw);
+          have_packed = true;
         } else {
-          reinterpret_cast<uint64_t*>(out)[row] = (uint64_t)pack2_bf16(s[0], s[1]) | ((uint64_t)pack2_bf16(s[2], s[3]) << 32);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, false>(b[k][j], n4[j], a);
         }
+      }
+      const uint64_t row = row0 + (uint64_t)(k * 64);
+      if constexpr (F::kIsFp8) {
+        if (!have_packed) packed = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
+        if (wide_path) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) y[k][j] = decode_top<FMT>(r[j]);   // keeps this library's NaN / sign conventions
+        } else {
+          decode4<FMT>(packed, y[k]);
+        }
+        if (out != nullptr) reinterpret_cast<uint32_t*>(out)[row] = packed;
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[k][j] = __uint_as_float(r[j] & 0xFFFF0000u);
+        if (out != nullptr)
+          reinterpret_cast<uint64_t*>(out)[row] = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
       }
     }
 
@@ -195,32 +197,21 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
     auto add_range = [&](auto all_tag, int lo, int hi) {
       constexpr bool ALL = decltype(all_tag)::value;
       const int w_lo = wave * kWaveElems;
-      int32_t se32 = 0;   // at most 8 terms below 2^FRAC in magnitude
 #pragma unroll
       for (int k = 0; k < kRows; ++k)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int e = w_lo + k * 256 + 4 * lane + j;
           const bool in = ALL || (e >= lo && e < hi);
-          const uint32_t signed_r = rm[k][j] | (b[k][j] & 0x80000000u);
           if (wide_path) {
-            if (in) accumulate<FMT>(cur.wide, b[k][j], signed_r);
+            if (in) accumulate<FMT, true>(cur, b[k][j], y[k][j]);
+          } else if (ALL) {
+            accumulate<FMT, false>(cur, b[k][j], y[k][j]);
           } else {
-            float y;
-            if constexpr (F::kIsFp8) y = lut[signed_r >> 24];
-            else y = __uint_as_float(signed_r & 0xFFFF0000u);
-            int32_t d = (int32_t)((rm[k][j] & ~kFracMask) - r0[k][j]);   // (|y| - |x|) / ulp_t, times 2^FRAC
-            const int32_t sgn = (int32_t)b[k][j] >> 31;                  // y - x = -(|y| - |x|) for negative x
-            if constexpr (!ALL) {
-              d = in ? d : 0;
-              y = in ? y : 0.0f;
-            }
-            cur.sy += (double)y;
-            se32 += (d ^ sgn) - sgn;
-            cur.see_fix += (uint64_t)((int64_t)d * (int64_t)d);
+            // outside the range: contribute y = 0 and x = 0, whose terms are exact zeros
+            accumulate<FMT, false>(cur, in ? b[k][j] : 0u, in ? y[k][j] : 0.0f);
           }
         }
-      cur.se_fix += (int64_t)se32;
     };
 
     const uint64_t t_lo = (uint64_t)it * T::ELEMS, t_hi = t_lo + T::ELEMS;   // chunk-relative range of this tile
@@ -290,7 +281,7 @@ __global__ __launch_bounds__(kThreads) void stats_bins(const float* __restrict__
     const uint32_t bits = __float_as_uint(x[i - a0]);
     const uint32_t r = round_pattern<FMT, VAR, true>(bits, rnd, a);
     if (out != nullptr) reinterpret_cast<code_t*>(out)[i - a0] = (code_t)(r >> Fx<FMT>::FRAC);
-    accumulate<FMT>(acc, bits, r);
+    accumulate<FMT, true>(acc, bits, decode_top<FMT>(r));
   }
   double* s = stats + (bin - first_bin) * 4;
   s[0] += (double)(hi - lo);
