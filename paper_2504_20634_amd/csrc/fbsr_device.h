@@ -67,7 +67,6 @@ template <> struct Fx<kBF16> {
   static constexpr int P = 8, B = 127;
   static constexpr uint32_t U_MAXFIN = 0x7F7F0000u;
   static constexpr uint32_t NAN_FX = 0x7FC00000u;
-  static constexpr uint32_t U_EXACT = 0u;             // the code space is the pattern: always exact
   static constexpr bool kIsFp8 = false;
   typedef uint16_t code_t;
 };
@@ -83,7 +82,6 @@ template <> struct Fx<kE4M3> {
   static constexpr uint32_t U_MAXFIN = 0x43E00000u;   // 448
   static constexpr uint32_t U_CLAMP = 0x43E00000u;    // saturating: everything above acts as M
   static constexpr uint32_t U_SUB = 121u << 23;       // 2^-6, smallest normal
-  static constexpr uint32_t U_EXACT = 117u << 23;     // from 2^-10 up no input bit lies below 2^-FRAC of the subnormal spacing
   static constexpr float SUB_SCALE = 0x1p33f;         // 1 / (2^-9 subnormal spacing) * 2^FRAC
   static constexpr bool kDetRegion = false;
   static constexpr uint32_t NAN_FX = 0x7F000000u;
@@ -99,7 +97,6 @@ template <> struct Fx<kE5M2> {
   static constexpr uint32_t U_MAXFIN = 0x47600000u;   // 57344
   static constexpr uint32_t U_CLAMP = 0x47700000u;    // 61440 = M + ulp(M)/2: maps to code 123.5
   static constexpr uint32_t U_SUB = 113u << 23;       // 2^-14
-  static constexpr uint32_t U_EXACT = 110u << 23;     // 2^-17, as above for the 2^-16 spacing
   static constexpr float SUB_SCALE = 0x1p40f;         // 1 / 2^-16 * 2^FRAC
   static constexpr bool kDetRegion = true;            // (M, 61440): nearest is M; >= 61440: inf
   static constexpr uint32_t NAN_FX = 0x7E000000u;
