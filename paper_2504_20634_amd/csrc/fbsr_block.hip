@@ -156,8 +156,11 @@ hipError_t run(const float* x, uint8_t* out, uint8_t* scales, uint64_t n, int nb
                               reinterpret_cast<uintptr_t>(out), 1, 4);
   // the tile kernel's blocks of 32 must be the call's blocks: it is used only when no head is cut off
   const uint64_t ntiles = s.head == 0 ? s.ntiles : 0;
-  if (ntiles) {
-    const hipError_t e = launch_tiles_w<FMT, VAR>(W, x, out, scales, ntiles, nbits, seed, offset / (uint64_t)(128 / W), stream);
+  for (uint64_t t0 = 0; t0 < ntiles; t0 += kMaxTilesPerLaunch) {
+    const uint64_t cnt = ntiles - t0 < kMaxTilesPerLaunch ? ntiles - t0 : kMaxTilesPerLaunch;
+    const uint64_t e0 = t0 * s.tile_elems;
+    const hipError_t e = launch_tiles_w<FMT, VAR>(W, x + e0, out + e0, scales + e0 / kScaleBlock, cnt, nbits, seed,
+                                                  (offset + e0) / (uint64_t)(128 / W), stream);
     if (e != hipSuccess) return e;
   }
   return launch_blocks<FMT, VAR>(x, out, scales, ntiles * s.tile_elems, n, nbits, W, seed, offset, stream);

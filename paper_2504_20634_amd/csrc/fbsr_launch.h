@@ -52,10 +52,13 @@ inline Split split_range(uint64_t n, uint64_t offset, int W, bool no_bits, uintp
   return s;
 }
 
-// Largest element count one per-element launch may cover (keeps gridDim.x below 2^31).
-constexpr uint64_t kMaxElemsPerLaunch = (uint64_t)1 << 38;
+// Largest element count one per-element launch may cover (keeps the total thread count of a launch
+// far below 2^32).
+constexpr uint64_t kMaxElemsPerLaunch = (uint64_t)1 << 30;
+// Largest tile count one tile-kernel launch may cover (2^30 threads per launch).
+constexpr uint64_t kMaxTilesPerLaunch = (uint64_t)1 << 22;
 // Largest n the library accepts.
-constexpr uint64_t kMaxElems = (uint64_t)1 << 40;
+constexpr uint64_t kMaxElems = (uint64_t)1 << 38;
 
 hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                         uint64_t offset, hipStream_t stream);

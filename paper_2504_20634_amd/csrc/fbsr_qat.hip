@@ -165,9 +165,11 @@ hipError_t run(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, u
   }
   hipError_t e = launch_elems<FMT, VAR>(w8, g16, m16, v16, s.head, p, nbits, W, seed, step, offset, stream);
   if (e != hipSuccess) return e;
-  if (s.ntiles) {
-    e = launch_tiles_w<FMT, VAR>(W, w8 + s.head, g16 + s.head, m16 + s.head, v16 + s.head, s.ntiles, p, nbits, seed,
-                                 step, (offset + s.head) / (uint64_t)(128 / W), stream);
+  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
+    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
+    const uint64_t e0 = s.head + t0 * s.tile_elems;
+    e = launch_tiles_w<FMT, VAR>(W, w8 + e0, g16 + e0, m16 + e0, v16 + e0, cnt, p, nbits, seed, step,
+                                 (offset + e0) / (uint64_t)(128 / W), stream);
     if (e != hipSuccess) return e;
   }
   const uint64_t done = s.head + s.ntiles * s.tile_elems;

@@ -128,9 +128,10 @@ hipError_t run(const uint16_t* x, uint8_t* out, uint64_t n, int nbits, uint64_t 
                               reinterpret_cast<uintptr_t>(out), 1, 8);
   hipError_t e = launch_elems<SRC, FMT, VAR>(x, out, s.head, nbits, W, seed, offset, stream);
   if (e != hipSuccess) return e;
-  if (s.ntiles) {
-    e = launch_tiles_w<SRC, FMT, VAR>(W, x + s.head, out + s.head, s.ntiles, nbits, seed,
-                                      (offset + s.head) / (uint64_t)(128 / W), stream);
+  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
+    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
+    const uint64_t e0 = s.head + t0 * s.tile_elems;
+    e = launch_tiles_w<SRC, FMT, VAR>(W, x + e0, out + e0, cnt, nbits, seed, (offset + e0) / (uint64_t)(128 / W), stream);
     if (e != hipSuccess) return e;
   }
   const uint64_t done = s.head + s.ntiles * s.tile_elems;

@@ -120,9 +120,10 @@ hipError_t run(uint16_t* w, const float* g, uint64_t n, float neg_lr, int nbits,
                               reinterpret_cast<uintptr_t>(w), 2, 8);
   hipError_t e = launch_elems<VAR>(w, g, s.head, neg_lr, nbits, W, seed, step, offset, stream);
   if (e != hipSuccess) return e;
-  if (s.ntiles) {
-    e = launch_tiles_w<VAR>(W, w + s.head, g + s.head, s.ntiles, neg_lr, nbits, seed, step,
-                            (offset + s.head) / (uint64_t)(128 / W), stream);
+  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
+    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
+    const uint64_t e0 = s.head + t0 * s.tile_elems;
+    e = launch_tiles_w<VAR>(W, w + e0, g + e0, cnt, neg_lr, nbits, seed, step, (offset + e0) / (uint64_t)(128 / W), stream);
     if (e != hipSuccess) return e;
   }
   const uint64_t done = s.head + s.ntiles * s.tile_elems;

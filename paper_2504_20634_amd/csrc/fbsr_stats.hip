@@ -296,9 +296,18 @@ template <int FMT, int VAR, int W>
 hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
                         uint64_t i0, uint64_t group, double* records, hipStream_t stream) {
   const uint64_t chunks = (ntiles + kStatsChunkTiles - 1) / kStatsChunkTiles;
-  hipLaunchKernelGGL((stats_tiles<FMT, VAR, W>), dim3((unsigned)chunks), dim3(kThreads), 0, stream, x, out, ntiles,
-                     nbits, seed, blk0, i0, group, stats_slots(group), records);
-  return hipGetLastError();
+  const uint64_t slots = stats_slots(group);
+  const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
+  for (uint64_t c0 = 0; c0 < chunks; c0 += kMaxTilesPerLaunch) {   // at most 2^30 threads per launch
+    const uint64_t cnt = chunks - c0 < kMaxTilesPerLaunch ? chunks - c0 : kMaxTilesPerLaunch;
+    const uint64_t t0 = c0 * kStatsChunkTiles, e0 = t0 * kTileElems;
+    hipLaunchKernelGGL((stats_tiles<FMT, VAR, W>), dim3((unsigned)cnt), dim3(kThreads), 0, stream, x + e0,
+                       out ? reinterpret_cast<char*>(out) + e0 * osize : nullptr, ntiles - t0, nbits, seed,
+                       blk0 + t0 * WgTile<W>::BLOCKS, i0 + e0, group, slots, records + c0 * slots * kStatsRecordDoubles);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 template <int FMT, int VAR>
