@@ -10,7 +10,8 @@
  *     the default stream) and returns without synchronising.
  *   - The return value is an fbsr_status; nothing throws or aborts.  Argument errors are
  *     detected on the host before anything is launched (so they can be tested without a GPU).
- *   - n == 0 is FBSR_OK and launches nothing.
+ *   - n == 0 is FBSR_OK and launches nothing.  n may be at most 2^38 elements and offset + n must
+ *     not overflow 64 bits (else FBSR_EINVAL); large calls are cut into several launches.
  *   - Results are a pure function of the arguments: the random bits of an element depend only
  *     on (seed, step, global element index), so repeating a call, or cutting it into chunks
  *     whose `offset` continues the index, gives identical bytes.
