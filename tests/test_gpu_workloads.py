@@ -160,3 +160,46 @@ def test_more_than_2_32_elements(fbsr, oracle):
     s = n - width
     want = oracle.round_from16(src[s:].cpu().numpy().view(np.uint16), 0, E5M2, SRF, 4, seed=3, offset=7 + s)
     assert first_mismatch(host(o2[s:]), want) is None
+
+
+def test_workload4_sgd_1000_steps_drift(fbsr):
+    """The fourth workload at full scale on the GPU: 2^27 bf16 weights ~ U(-1,1), lr = 1e-3, fresh
+    gradients N(0, (1e-3)^2) per step, 1000 steps, N in {2, 4, 8} against nearest-even.  Updates are far
+    below one ulp, so (Sec. IV) nearest-even stagnates -- and so do SRF and SRC, whose predicates never
+    fire for |update| << ulp -- while SRFF loses 2^-(N+1) ulp of |w| per step (App. A-A), i.e. the
+    weights drift toward zero.  Prints mean |w| every 250 steps."""
+    n, lr, steps = 1 << 27, 1e-3, 1000
+    from paper_2504_20634_amd import workloads
+    w0 = dev(workloads.sgd_weights(n, seed=3))
+    as_f = lambda w: (w.to(torch.int32) << 16).view(torch.float32)
+    a0 = as_f(w0).abs()
+    ulp0 = torch.exp2(torch.floor(torch.log2(a0.clamp_min(2.0 ** -120))) - 7)
+    m0 = a0.double().mean().item()
+    # the per-step rate is read on weights of at least 2^-6: relative to its own ulp a weight near zero moves
+    # by an unbounded amount, so a mean over all weights is set by the few smallest ones
+    big = a0 >= 2.0 ** -6
+    gen = torch.Generator(device="cuda")
+    g = torch.empty(n, dtype=torch.float32, device="cuda")
+    print("start   mean|w| = %.6f" % m0, flush=True)
+    for variant, nbits in ((RNE, 0), (SRF, 2), (SRC, 2), (SRFF, 8), (SRFF, 4), (SRFF, 2)):
+        w = w0.clone()
+        gen.manual_seed(1234)
+        track = []
+        for t in range(steps):
+            g.normal_(0.0, 1e-3, generator=gen)
+            fbsr.fbsr_sgd_update(w, g, lr, variant, nbits, seed=9, step=t)
+            if t + 1 == 20:
+                rate = (((as_f(w).abs() - a0) / ulp0)[big].double().mean().item()) / 20.0
+            if (t + 1) % 250 == 0:
+                track.append(as_f(w).abs().double().mean().item())
+        moved = (w != w0).double().mean().item()
+        print("variant=%d N=%d  ulp/step over the first 20 steps %+.5f  moved %.4f  mean|w| at 250..1000: %s"
+              % (variant, nbits, rate, moved, " ".join("%.6f" % v for v in track)), flush=True)
+        if variant == SRFF:
+            assert abs(rate + 2.0 ** -(nbits + 1)) < 0.1 * 2.0 ** -(nbits + 1), (nbits, rate)
+            # one ulp is between 2^-8 and 2^-7 of |w|, so |w| decays by a factor between these two per step
+            loss = steps * 2.0 ** -(nbits + 1)
+            assert m0 * np.exp(-loss / 128) < track[-1] < m0 * np.exp(-loss / 256), track
+        else:
+            # only weights so small that 1e-6 is not << their ulp (|w| < 2^-12: a few in a thousand) can move
+            assert moved < 1e-2 and abs(track[-1] - m0) < 1e-5 * m0, (variant, moved, track)
