@@ -14,7 +14,7 @@
 //   exponent  e~ = max(floor(log2 x~), 1-B) .................. Sec. II-A, Eq. (2)
 //   scaled significand  s~ = x~ * 2^-e~ * 2^(P-1) ............ Sec. II-A, Eq. (3)
 //   sigma = floor(s~) + 1[R(s~ - floor(s~))] ................. Sec. II-A, Eq. (5)
-//   R_TNE (ties to nearest even) ............................. Sec. II-A
+//   R_TNE (ties to nearest even), R_TNO (odd), R_TA (away) ... Sec. II-A, Eq. (4)
 //   R_SRFF(d,n) = d + n 2^-N >= 1 ............................ Sec. II-B
 //   R_SRF (d,n) = d + (n+1/2) 2^-N >= 1 ...................... Sec. II-B
 //   R_SRC (d,n) = R_SRFF(Round(d 2^N) 2^-N, n) ............... Sec. III-F, Eq. (7)
@@ -28,7 +28,10 @@
 //   * |x| > M: bf16 / E5M2 round to nearest on the unbounded-exponent grid
 //     (below M + ulp(M)/2 -> M, otherwise -> inf; the tie goes to inf because
 //     M's significand is odd); E4M3 has no infinity and saturates to +-M;
-//   * SRC's inner Round is round-to-nearest, ties to even;
+//   * SRC's inner Round is round-to-nearest, ties to even (ties to odd, which Sec. III-F also
+//     allows, is a separate variant of the generic-format entry points);
+//   * generic formats (any (K, P, B; M) of Sec. II with K <= 8): special encodings, the absence of
+//     -0 and the overflow policy are part of the caller's descriptor (see Format8);
 //   * the N random bits of element i are a slice of a Philox4x32-10 block
 //     (Salmon et al., SC'11) -- the paper leaves the generator open; the
 //     slicing convention is this build's and is restated in random_bits().
@@ -63,7 +66,8 @@ struct Format {
 
 enum { FMT_BF16 = 0, FMT_E4M3 = 1, FMT_E5M2 = 2, FMT_FP16 = 3 };   // FP16: IEEE binary16, used as a SOURCE format
 enum { SRC_BF16 = 0, SRC_FP16 = 1 };
-enum { VAR_RNE = 0, VAR_SRFF = 1, VAR_SRF = 2, VAR_SRC = 3 };
+enum { VAR_RNE = 0, VAR_SRFF = 1, VAR_SRF = 2, VAR_SRC = 3,
+       VAR_SRC_ODD = 4, VAR_TNO = 5, VAR_TA = 6 };   // 4..6: generic-format entry points only
 
 bool get_format(int fmt, Format* f) {
   switch (fmt) {
@@ -143,6 +147,18 @@ bool round_up(int variant, double fl, double delta, int N, uint64_t n) {
       const double h = std::nearbyint(std::ldexp(delta, N));  // default FE_TONEAREST
       return h + (double)n >= std::ldexp(1.0, N);
     }
+    case VAR_SRC_ODD: {  // the same with Round = RN ties-to-odd (Sec. III-F: "ties to even or odd")
+      const double s = std::ldexp(delta, N);
+      const double lo = std::floor(s);
+      const double r = s - lo;  // exact
+      double h = lo;
+      if (r > 0.5 || (r == 0.5 && std::fmod(lo, 2.0) == 0.0)) h = lo + 1.0;
+      return h + (double)n >= std::ldexp(1.0, N);
+    }
+    case VAR_TNO:  // R_TNO: a tie goes to the odd neighbour
+      return delta > 0.5 || (delta == 0.5 && std::fmod(fl, 2.0) == 0.0);
+    case VAR_TA:  // Eq. (4): R_TA(delta) = delta >= 1/2
+      return delta >= 0.5;
   }
   return false;
 }
@@ -167,6 +183,109 @@ uint32_t round_one(double xv, const Format& f, int variant, int N, uint64_t n) {
   const double delta = sig - fl;                            // exact
   const int64_t sigma = (int64_t)fl + (round_up(variant, fl, delta, N, n) ? 1 : 0);  // Eq. (5)
   return sign_code | encode_magnitude(sigma, et, f);
+}
+
+
+// ------------------------------------------------ generic formats, K <= 8 ---
+// Any (K, P, B; M) of Sec. II whose codes fit a byte.  The paper's format model says nothing about
+// special encodings, so they are data of the descriptor:
+//   max_code    magnitude code (e << (P-1) | t) of M; every magnitude code above it is not finite
+//   inf_code    magnitude code of infinity, or -1: the format has none and SATURATES (every
+//               |x| > M, infinities included, becomes +-M)
+//   nan_code    full code of the canonical NaN, or -1: no NaN (a NaN input then becomes +-M)
+//   nan_signed  the sign of a NaN input is OR-ed into nan_code
+//   neg_zero    the format has -0; without it a negative input that rounds to zero gives code 0
+// With an infinity, |x| > M rounds to nearest on the unbounded-exponent grid, ties to even
+// (Sec. II: "as in IEEE-754 round to nearest"): below M + ulp(M)/2 -> M, above -> inf, the tie
+// to whichever of the two has the even significand.
+struct Format8 {
+  Format f;   // K, P, B, M (the other fields of f are unused on this path)
+  int max_code, inf_code, nan_code;
+  bool nan_signed, neg_zero;
+};
+
+// desc: {K, P, B, max_code, inf_code, nan_code, nan_signed, neg_zero}.
+bool get_format8(const int32_t* d, Format8* g) {
+  const int K = d[0], P = d[1], B = d[2];
+  if (K < 2 || K > 8 || P < 1 || P > K - 1 || B < 0 || B > 96) return false;
+  const int mag_top = (1 << (K - 1)) - 1;
+  const int max_code = d[3], inf_code = d[4], nan_code = d[5];
+  if (max_code < (1 << (P - 1)) || max_code > mag_top) return false;        // M is a normal value
+  if (inf_code != -1 && (inf_code <= max_code || inf_code > mag_top)) return false;
+  const bool nan_signed = d[6] != 0, neg_zero = d[7] != 0;
+  if (nan_code != -1) {
+    if (nan_code < 0 || nan_code >= (1 << K)) return false;
+    const int mag = nan_code & mag_top, sgn = nan_code >> (K - 1);
+    const bool above = mag > max_code && mag != inf_code;                   // an unused magnitude
+    const bool minus_zero_slot = mag == 0 && sgn == 1 && !neg_zero && !nan_signed;
+    if (!above && !minus_zero_slot) return false;
+    if (nan_signed && sgn != 0) return false;
+  }
+  const int e_max = (max_code >> (P - 1)), t_max = max_code & ((1 << (P - 1)) - 1);
+  if (e_max - B > 126) return false;                                        // M + ulp(M) must be a finite fp32
+  const double M = (1.0 + std::ldexp((double)t_max, 1 - P)) * std::ldexp(1.0, e_max - B);   // Eq. (1), e > 0
+  g->f = Format{K, P, B, M, false, 0u, 0u};
+  g->max_code = max_code;
+  g->inf_code = inf_code;
+  g->nan_code = nan_code;
+  g->nan_signed = nan_signed;
+  g->neg_zero = neg_zero;
+  return true;
+}
+
+double decode8(uint32_t code, const Format8& g) {
+  const Format& f = g.f;
+  const uint32_t sign_bit = 1u << (f.K - 1);
+  code &= (sign_bit << 1) - 1u;
+  const uint32_t mag = code & (sign_bit - 1u);
+  const bool neg = (code & sign_bit) != 0;
+  const double qnan = std::numeric_limits<double>::quiet_NaN();
+  if (g.nan_code >= 0 && (g.nan_signed ? mag == (uint32_t)g.nan_code : code == (uint32_t)g.nan_code)) return qnan;
+  if (g.inf_code >= 0 && mag == (uint32_t)g.inf_code)
+    return neg ? -std::numeric_limits<double>::infinity() : std::numeric_limits<double>::infinity();
+  if (mag > (uint32_t)g.max_code) return qnan;          // an encoding the descriptor leaves unused
+  if (mag == 0 && neg && !g.neg_zero) return qnan;      // likewise
+  const uint32_t e = mag >> (f.P - 1), t = mag & ((1u << (f.P - 1)) - 1u);
+  const double sign = neg ? -1.0 : 1.0;
+  if (e == 0) return sign * std::ldexp((double)t, 1 - f.P) * std::ldexp(1.0, 1 - f.B);      // Eq. (1)
+  return sign * (1.0 + std::ldexp((double)t, 1 - f.P)) * std::ldexp(1.0, (int)e - f.B);
+}
+
+uint32_t round_one8(double xv, const Format8& g, int variant, int N, uint64_t n) {
+  const Format& f = g.f;
+  const uint32_t sign_code = (std::signbit(xv) ? 1u : 0u) << (f.K - 1);
+  if (std::isnan(xv)) {
+    if (g.nan_code < 0) return sign_code | (uint32_t)g.max_code;
+    return (uint32_t)g.nan_code | (g.nan_signed ? sign_code : 0u);
+  }
+  const double a = std::fabs(xv);
+  if (a == 0.0) return g.neg_zero ? sign_code : 0u;
+  if (a > f.M) {  // outside the finite range: deterministic
+    if (g.inf_code < 0) return sign_code | (uint32_t)g.max_code;
+    const double ulp_M = std::ldexp(1.0, std::ilogb(f.M) - f.P + 1);
+    const double tie = f.M + ulp_M / 2.0;
+    bool to_inf = a > tie;
+    if (a == tie) to_inf = std::fmod(f.M / ulp_M, 2.0) == 1.0;   // M's significand is odd: inf is the even side
+    return sign_code | (uint32_t)(to_inf ? g.inf_code : g.max_code);
+  }
+  const int et = rounding_exponent(a, f);                   // Eq. (2)
+  const double sig = std::ldexp(a, -et + f.P - 1);          // Eq. (3), exact
+  const double fl = std::floor(sig);
+  const double delta = sig - fl;                            // exact
+  const int64_t sigma = (int64_t)fl + (round_up(variant, fl, delta, N, n) ? 1 : 0);  // Eq. (5)
+  const uint32_t mag = encode_magnitude(sigma, et, f);
+  if (mag == 0 && !g.neg_zero) return 0u;
+  return sign_code | mag;
+}
+
+bool variant8_ok(int variant, int nbits) {
+  if (variant < VAR_RNE || variant > VAR_TA) return false;
+  const bool draws = variant == VAR_SRFF || variant == VAR_SRF || variant == VAR_SRC || variant == VAR_SRC_ODD;
+  return !draws || (nbits >= 1 && nbits <= 32);
+}
+
+bool variant_draws(int variant) {
+  return variant == VAR_SRFF || variant == VAR_SRF || variant == VAR_SRC || variant == VAR_SRC_ODD;
 }
 
 // ----------------------------------------------------------------- Philox ---
@@ -505,6 +624,46 @@ int oracle_bias_stats(const float* x, void* out, uint64_t n, int fmt, int varian
     s[1] += y;
     s[2] += e;
     s[3] += e * e;
+  }
+  return 0;
+}
+
+// ------------------------------------------------------------ generic formats ---
+// desc = {K, P, B, max_code, inf_code, nan_code, nan_signed, neg_zero} (see Format8).
+// variant: 0 RNE, 1 SRFF, 2 SRF, 3 SRC (inner ties-to-even), 4 SRC (inner ties-to-odd),
+// 5 nearest ties-to-odd, 6 nearest ties-away (0, 5 and 6 draw no bits).
+
+// 0 when the descriptor is acceptable.
+int oracle_format8_check(const int32_t* desc) {
+  Format8 g;
+  return get_format8(desc, &g) ? 0 : 1;
+}
+
+// Eq. (1) value of a code under the descriptor (NaN for NaN and unused encodings).
+double oracle_decode_format8(uint32_t code, const int32_t* desc) {
+  Format8 g;
+  if (!get_format8(desc, &g)) return std::numeric_limits<double>::quiet_NaN();
+  return decode8(code, g);
+}
+
+// One element with an explicit n.  Returns the code, or 0xFFFFFFFF on invalid arguments.
+uint32_t oracle_round_format8_with_n(float x, const int32_t* desc, int variant, int nbits, uint64_t n) {
+  Format8 g;
+  if (!get_format8(desc, &g) || !variant8_ok(variant, nbits)) return 0xFFFFFFFFu;
+  return round_one8(x, g, variant, nbits, n);
+}
+
+// x: n values of the source type src (0 = bf16 codes, 1 = IEEE binary16 codes, 2 = fp32); out: n
+// bytes, one code each (the bits above K are zero).  Random bits of element j: stream (seed, 0),
+// global index offset + j.  Returns 0, or 1 on invalid arguments.
+int oracle_round_format8(const void* x, int src, uint8_t* out, uint64_t n, const int32_t* desc, int variant,
+                         int nbits, uint64_t seed, uint64_t offset) {
+  Format8 g;
+  if (!get_format8(desc, &g) || !variant8_ok(variant, nbits) || src < 0 || src > 2) return 1;
+  for (uint64_t j = 0; j < n; ++j) {
+    const float v = src == 2 ? ((const float*)x)[j] : widen16(((const uint16_t*)x)[j], src);
+    const uint64_t r = variant_draws(variant) ? random_bits(seed, 0, offset + j, nbits) : 0;
+    out[j] = (uint8_t)round_one8(v, g, variant, nbits, r);
   }
   return 0;
 }

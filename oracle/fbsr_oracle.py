@@ -17,7 +17,9 @@ _OVERRIDE = os.environ.get("FBSR_ORACLE_LIB")
 
 FMT_BF16, FMT_E4M3, FMT_E5M2 = 0, 1, 2
 SRC_BF16, SRC_FP16 = 0, 1
+FROM_BF16, FROM_FP16, FROM_FP32 = 0, 1, 2  # source types of the generic-format entry points
 RNE, SRFF, SRF, SRC = 0, 1, 2, 3
+SRC_ODD, TNO, TA = 4, 5, 6                        # generic-format entry points only
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
 
@@ -68,6 +70,14 @@ def lib():
         L.oracle_qat_adamw_step.restype = i32
         L.oracle_round_block_scaled.argtypes = [vp, vp, vp, u64, i32, i32, i32, u64, u64]
         L.oracle_round_block_scaled.restype = i32
+        L.oracle_format8_check.argtypes = [vp]
+        L.oracle_format8_check.restype = i32
+        L.oracle_decode_format8.argtypes = [u32, vp]
+        L.oracle_decode_format8.restype = ctypes.c_double
+        L.oracle_round_format8_with_n.argtypes = [f32, vp, i32, i32, u64]
+        L.oracle_round_format8_with_n.restype = u32
+        L.oracle_round_format8.argtypes = [vp, i32, vp, u64, vp, i32, i32, u64, u64]
+        L.oracle_round_format8.restype = i32
         L.oracle_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64]
         L.oracle_sgd_update.restype = i32
         L.oracle_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp]
@@ -158,6 +168,38 @@ def round_block_scaled(x, fmt, variant, nbits, seed, offset=0):
     if rc != 0:
         raise ValueError("oracle_round_block_scaled: status %d" % rc)
     return out, scales
+
+
+def _desc(desc):
+    d = np.asarray(desc, dtype=np.int32)
+    assert d.shape == (8,), "descriptor = (K, P, B, max_code, inf_code, nan_code, nan_signed, neg_zero)"
+    return np.ascontiguousarray(d)
+
+
+def format8_check(desc):
+    return lib().oracle_format8_check(_ptr(_desc(desc))) == 0
+
+
+def decode_format8(code, desc):
+    return float(lib().oracle_decode_format8(int(code), _ptr(_desc(desc))))
+
+
+def round_format8_with_n(x, desc, variant, nbits, n):
+    code = lib().oracle_round_format8_with_n(float(np.float32(x)), _ptr(_desc(desc)), variant, nbits, n)
+    if code == 0xFFFFFFFF:
+        raise ValueError("oracle_round_format8_with_n: bad arguments")
+    return int(code)
+
+
+def round_format8(x, src, desc, variant, nbits, seed, offset=0):
+    """x: fp32 values (src = 2) or uint16 codes of bf16 (src = 0) / IEEE binary16 (src = 1); desc as in
+    _desc.  Returns one code per byte."""
+    x = np.ascontiguousarray(x, dtype=np.float32 if src == FROM_FP32 else np.uint16)
+    out = np.empty(x.size, dtype=np.uint8)
+    rc = lib().oracle_round_format8(_ptr(x), src, _ptr(out), x.size, _ptr(_desc(desc)), variant, nbits, seed, offset)
+    if rc != 0:
+        raise ValueError("oracle_round_format8: status %d" % rc)
+    return out
 
 
 def sgd_update(w, g, lr, variant, nbits, seed, step, offset=0):

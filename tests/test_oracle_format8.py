@@ -1,0 +1,313 @@
+"""Pins for the oracle's generic-format path (any (K, P, B; M) of Sec. II with K <= 8, the extra
+rounding modes of Sec. II-A / Sec. III-F): published value sets, the already pinned fixed-format
+path, library roundings, exact counting arguments and the closed-form biases of Sec. III.
+Nothing here touches the GPU library.  CPU only."""
+import bisect
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from exact_model import expected_ups, f32_fraction, floor_frac, pow2
+
+RNE, SRFF, SRF, SRC, SRC_ODD, TNO, TA = range(7)
+DRAWING = (SRFF, SRF, SRC, SRC_ODD)
+FROM_BF16, FROM_FP16, FROM_FP32 = 0, 1, 2
+
+
+# Descriptors (K, P, B, max_code, inf_code, nan_code, nan_signed, neg_zero), written here from the
+# formats' public definitions -- OCP 8-bit floating point (E4M3: S.1111.111 is NaN, no infinity;
+# E5M2: IEEE-like), OCP microscaling element types (E3M2, E2M3, E2M1: no NaN, no infinity), and the
+# IEEE WG P3109 interim report's binary8pP (bias 2^(7-P), 0x80 the only NaN, 0x7F / 0xFF the
+# infinities, no negative zero) whose binary8p4 is the format Sec. IV trains in.
+def p3109(P):
+    return (8, P, 1 << (7 - P), 0x7E, 0x7F, 0x80, 0, 0)
+
+
+E4M3 = (8, 4, 7, 0x7E, -1, 0x7F, 1, 1)
+E5M2 = (8, 3, 15, 0x7B, 0x7C, 0x7E, 1, 1)
+E3M2 = (6, 3, 3, 0x1F, -1, -1, 0, 1)
+E2M3 = (6, 4, 1, 0x1F, -1, -1, 0, 1)
+E2M1 = (4, 2, 1, 0x07, -1, -1, 0, 1)
+BINARY8P4 = p3109(4)
+ALL = {"e4m3": E4M3, "e5m2": E5M2, "e3m2": E3M2, "e2m3": E2M3, "e2m1": E2M1, "binary8p1": p3109(1),
+       "binary8p3": p3109(3), "binary8p4": BINARY8P4, "binary8p5": p3109(5), "binary8p7": p3109(7)}
+
+
+def value_of(code, d):
+    """Eq. (1) for a non-negative finite magnitude code, as a Fraction."""
+    K, P, B = d[0], d[1], d[2]
+    e, t = code >> (P - 1), code & ((1 << (P - 1)) - 1)
+    if e == 0:
+        return Fraction(t) * pow2(1 - P) * pow2(1 - B)
+    return (1 + Fraction(t) * pow2(1 - P)) * pow2(e - B)
+
+
+def table(d):
+    vals = [value_of(c, d) for c in range(d[3] + 1)]
+    assert vals == sorted(vals)
+    return vals
+
+
+def position(a, d):
+    """(lower magnitude code, delta in [0,1)) of the Fraction 0 <= a <= M."""
+    vals = table(d)
+    i = bisect.bisect_right(vals, a) - 1
+    if vals[i] == a:
+        return i, Fraction(0)
+    return i, (a - vals[i]) / (vals[i + 1] - vals[i])
+
+
+def rno_int(q):
+    f = floor_frac(q)
+    r = q - f
+    if r > Fraction(1, 2) or (r == Fraction(1, 2) and f % 2 == 0):
+        return f + 1
+    return f
+
+
+def ups(delta, variant, N):
+    if variant == SRC_ODD:
+        return min(rno_int(delta * 2 ** N), 2 ** N)
+    return expected_ups(delta, variant, N)
+
+
+def inputs_below_max(rng, d, count):
+    """fp32 values over the whole finite range of the format, sub-subnormal magnitudes included."""
+    K, P, B, max_code = d[:4]
+    lo = 127 + (1 - B) - (P - 1) - 3
+    hi = 127 + ((max_code >> (P - 1)) - B)
+    bits = rng.integers(0, 1 << 32, size=count, dtype=np.uint32)
+    field = rng.integers(max(lo, 1), hi + 1, size=count, dtype=np.uint32)
+    x = ((bits & np.uint32(0x807FFFFF)) | (field << np.uint32(23))).view(np.float32)
+    M = float(value_of(max_code, d))
+    return x[np.abs(x.astype(np.float64)) <= M]
+
+
+# ------------------------------------------------------------------ published value sets ----
+def test_published_value_sets(oracle):
+    dec = oracle.decode_format8
+    assert [dec(c, E2M1) for c in range(8)] == [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    assert [dec(c | 8, E2M1) for c in range(1, 8)] == [-0.5, -1.0, -1.5, -2.0, -3.0, -4.0, -6.0]
+    assert dec(0x1F, E2M3) == 7.5 and dec(0x01, E2M3) == 0.125 and dec(0x08, E2M3) == 1.0
+    assert dec(0x1F, E3M2) == 28.0 and dec(0x01, E3M2) == 0.0625 and dec(0x0C, E3M2) == 1.0
+    assert dec(0x7E, E4M3) == 448.0 and dec(0x01, E4M3) == 2.0 ** -9 and math.isnan(dec(0x7F, E4M3)) and math.isnan(dec(0xFF, E4M3))
+    assert dec(0x7B, E5M2) == 57344.0 and dec(0x01, E5M2) == 2.0 ** -16 and dec(0x7C, E5M2) == math.inf and dec(0xFC, E5M2) == -math.inf
+    assert all(math.isnan(dec(c, E5M2)) for c in (0x7D, 0x7E, 0x7F, 0xFD))
+    # binary8p4: 1.0 is 0x40, the largest finite value 224, the smallest subnormal 2^-10
+    assert dec(0x40, BINARY8P4) == 1.0 and dec(0x7E, BINARY8P4) == 224.0 and dec(0x01, BINARY8P4) == 2.0 ** -10
+    assert dec(0x08, BINARY8P4) == 2.0 ** -7 and dec(0xC0, BINARY8P4) == -1.0
+    assert dec(0x7F, BINARY8P4) == math.inf and dec(0xFF, BINARY8P4) == -math.inf and math.isnan(dec(0x80, BINARY8P4))
+    assert dec(0x00, BINARY8P4) == 0.0 and not math.copysign(1.0, dec(0x00, BINARY8P4)) < 0
+    assert dec(0x7E, p3109(3)) == 49152.0 and dec(0x7E, p3109(5)) == 15.0
+    assert dec(0x7E, p3109(1)) == 2.0 ** 62 and dec(0x01, p3109(1)) == 2.0 ** -63 and dec(0x40, p3109(1)) == 1.0
+    assert dec(0x7E, p3109(7)) == 1.0 + 62.0 / 64.0 and dec(0x01, p3109(7)) == 1.0 / 64.0
+
+
+@pytest.mark.parametrize("name", sorted(ALL))
+def test_decode_is_eq1_on_every_code(oracle, name):
+    d = ALL[name]
+    K = d[0]
+    for code in range(1 << K):
+        mag, neg = code & ((1 << (K - 1)) - 1), code >> (K - 1)
+        got = oracle.decode_format8(code, d)
+        special = (mag > d[3]) or (code == d[5]) or (d[6] and mag == d[5]) or (mag == 0 and neg and not d[7])
+        if special:
+            assert math.isnan(got) or (mag == d[4] and math.isinf(got) and (got < 0) == bool(neg)), (name, code)
+        else:
+            assert Fraction(got) == (-1 if neg else 1) * value_of(mag, d), (name, code)
+
+
+def test_descriptor_validation(oracle):
+    assert all(oracle.format8_check(d) for d in ALL.values())
+    bad = [(9, 4, 7, 0x7E, -1, 0x7F, 1, 1), (8, 8, 7, 0x7E, -1, 0x7F, 1, 1), (8, 0, 7, 0x7E, -1, 0x7F, 1, 1),
+           (8, 4, 7, 0x80, -1, -1, 0, 1),          # max_code outside the magnitude range
+           (8, 4, 7, 0x03, -1, -1, 0, 1),          # M would be subnormal
+           (8, 4, 7, 0x7E, 0x7E, -1, 0, 1),        # infinity not above M
+           (8, 4, 7, 0x7E, -1, 0x7E, 0, 1),        # NaN on a finite code
+           (8, 4, 7, 0x7E, -1, 0x80, 0, 1),        # 0x80 is -0 in a format with negative zero
+           (8, 4, 7, 0x7E, 0x7F, 0x7F, 0, 1),      # NaN on the infinity
+           (8, 4, 97, 0x7E, -1, 0x7F, 1, 1),       # bias out of range
+           (8, 1, 0, 0x7F, -1, -1, 0, 1)]          # M + ulp(M) beyond fp32
+    assert not any(oracle.format8_check(d) for d in bad)
+
+
+# ------------------------------------------------------ against the pinned fixed-format path ----
+@pytest.mark.parametrize("fmt,d", [(1, E4M3), (2, E5M2)])
+def test_descriptor_path_equals_fixed_path(oracle, fmt, d):
+    rng = np.random.default_rng(11 + fmt)
+    x = rng.integers(0, 1 << 32, size=4000, dtype=np.uint32).view(np.float32)
+    M = oracle.decode_format8(d[3], d)
+    ulp_M = M - oracle.decode_format8(d[3] - 1, d)
+    edge = np.array([0.0, -0.0, M, -M, M + ulp_M / 2, -(M + ulp_M / 2), np.nextafter(np.float32(M + ulp_M / 2), np.float32(0)),
+                     np.nextafter(np.float32(M + ulp_M / 2), np.float32(np.inf)), np.inf, -np.inf, np.nan, -np.nan,
+                     2.0 ** -149, -2.0 ** -149, 2.0 ** -126], dtype=np.float32)
+    edge[11] = np.array([0xFFC00001], dtype=np.uint32).view(np.float32)[0]   # a negative NaN with a payload
+    x = np.concatenate([x, edge, inputs_below_max(rng, d, 4000)])
+    for variant in (RNE, SRFF, SRF, SRC):
+        for nbits in (1, 3, 8, 16):
+            ns = rng.integers(0, 1 << nbits, size=x.size)
+            for xv, n in zip(x, ns):
+                assert oracle.round_format8_with_n(xv, d, variant, nbits, int(n)) == oracle.round_with_n(xv, fmt, variant, nbits, int(n)), (xv, variant, nbits, n)
+            if variant == RNE:
+                break
+    for code in range(256):
+        a, b = oracle.decode_format8(code, d), oracle.decode(code, fmt)
+        assert (math.isnan(a) and math.isnan(b)) or a == b
+
+
+# ----------------------------------------------------------- bracketing, identity, counting ----
+@pytest.mark.parametrize("name", sorted(ALL))
+def test_bracket_and_identity(oracle, name):
+    d = ALL[name]
+    rng = np.random.default_rng(5)
+    vals = table(d)
+    for xv in inputs_below_max(rng, d, 300):
+        a = abs(f32_fraction(xv))
+        lo, delta = position(a, d)
+        for variant in range(7):
+            nbits = int(rng.integers(1, 9))
+            n = int(rng.integers(0, 1 << nbits))
+            code = oracle.round_format8_with_n(xv, d, variant, nbits, n)
+            mag, neg = code & ((1 << (d[0] - 1)) - 1), code >> (d[0] - 1)
+            assert mag in ((lo,) if delta == 0 else (lo, lo + 1)), (name, xv, variant)
+            if mag != 0 or d[7]:
+                assert neg == int(np.signbit(xv))
+            else:
+                assert neg == 0          # no negative zero in this format
+    for code in range(d[3] + 1):         # representable values never move, whatever is drawn
+        xv = np.float32(float(vals[code]))
+        for variant in range(7):
+            for n in (0, 1, 7):
+                assert oracle.round_format8_with_n(xv, d, variant, 3, n) == code
+                neg = oracle.round_format8_with_n(-xv, d, variant, 3, n)
+                assert neg == (code | (1 << (d[0] - 1)) if (code or d[7]) else 0)
+
+
+@pytest.mark.parametrize("name", ["binary8p4", "binary8p3", "e2m3", "e2m1", "binary8p1", "binary8p7"])
+@pytest.mark.parametrize("variant", DRAWING)
+def test_exhaustive_round_up_counts(oracle, name, variant):
+    """For every draw n of N bits: the number that round away from zero equals the counting argument
+    over the exact delta (target subnormals and values below the smallest subnormal included)."""
+    d = ALL[name]
+    rng = np.random.default_rng(17)
+    for xv in inputs_below_max(rng, d, 60):
+        a = abs(f32_fraction(xv))
+        lo, delta = position(a, d)
+        for N in (1, 2, 3, 5):
+            got = sum((oracle.round_format8_with_n(xv, d, variant, N, n) & ((1 << (d[0] - 1)) - 1)) == lo + 1
+                      for n in range(1 << N))
+            want = ups(delta, variant, N) if delta != 0 else 0
+            assert got == want, (name, xv, variant, N, got, want)
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4])
+def test_src_with_ties_to_odd_is_unbiased_and_differs_only_at_ties(oracle, N):
+    """Sec. III-F allows ties-to-even or ties-to-odd for SRC's inner rounding: over a full grid of
+    D = 6 excess bits the mean of (P(up) - delta) is exactly zero for both, and the two variants
+    disagree only where delta 2^N lies exactly half-way."""
+    d = BINARY8P4                      # ulp 2^-3 in [1, 2): x = 1 + k 2^-9 gives D = 6
+    total = {SRC: Fraction(0), SRC_ODD: Fraction(0)}
+    for k in range(64):
+        xv = np.float32(1.0 + k * 2.0 ** -9)
+        delta = Fraction(k, 64)
+        cnt = {}
+        for variant in (SRC, SRC_ODD):
+            cnt[variant] = sum(oracle.round_format8_with_n(xv, d, variant, N, n) == 0x41 for n in range(1 << N))
+            total[variant] += Fraction(cnt[variant], 1 << N) - delta
+        tie = (delta * 2 ** N) % 1 == Fraction(1, 2)
+        assert (cnt[SRC] != cnt[SRC_ODD]) == tie, (k, cnt)
+    assert total[SRC] == 0 and total[SRC_ODD] == 0
+
+
+# ------------------------------------------------------------- deterministic modes vs library ----
+def test_deterministic_modes_on_an_integer_grid(oracle):
+    """In [8, 16) E4M3's ulp is 1, so rounding to the format is rounding to an integer: ties-to-even is
+    numpy's rint, ties-away (Eq. (4)) is floor(x + 1/2), ties-to-odd picks the odd neighbour of a tie."""
+    d = E4M3
+    for k in range(64, 128):
+        xv = np.float32(k / 8.0)
+        want_even = int(np.rint(np.float64(xv)))
+        want_away = int(np.floor(np.float64(xv) + 0.5))
+        is_tie = (k % 8) == 4
+        want_odd = want_even if not is_tie else (want_even + 1 if want_even == int(np.floor(xv)) else want_even - 1)
+        if is_tie:
+            assert want_odd % 2 == 1 and want_even % 2 == 0
+        for sign in (1.0, -1.0):     # sign-magnitude: "away" is away from zero
+            got = {v: sign * oracle.decode_format8(oracle.round_format8_with_n(sign * xv, d, v, 0, 0), d) for v in (RNE, TNO, TA)}
+            assert got[RNE] == want_even and got[TA] == want_away and got[TNO] == want_odd, (k, got)
+
+
+# ----------------------------------------------------------------- overflow and specials ----
+def test_overflow_and_specials(oracle):
+    r = lambda x, d, v=SRFF, N=3, n=0: oracle.round_format8_with_n(np.float32(x), d, v, N, n)
+    up = lambda v: np.nextafter(np.float32(v), np.float32(np.inf))
+    down = lambda v: np.nextafter(np.float32(v), np.float32(0))
+    for v in range(7):
+        for n in (0, 7):
+            # binary8p4: M = 224 = 14 * 16 has an even significand, so the tie 232 stays finite
+            assert r(232.0, BINARY8P4, v, 3, n) == 0x7E and r(-232.0, BINARY8P4, v, 3, n) == 0xFE
+            assert r(up(232.0), BINARY8P4, v, 3, n) == 0x7F and r(down(232.0), BINARY8P4, v, 3, n) == 0x7E
+            assert r(up(224.0), BINARY8P4, v, 3, n) == 0x7E          # above M: no draw can reach infinity
+            assert r(np.inf, BINARY8P4, v, 3, n) == 0x7F and r(-np.inf, BINARY8P4, v, 3, n) == 0xFF
+            assert r(np.nan, BINARY8P4, v, 3, n) == 0x80 and r(-np.nan, BINARY8P4, v, 3, n) == 0x80
+            assert r(0.0, BINARY8P4, v, 3, n) == 0x00 and r(-0.0, BINARY8P4, v, 3, n) == 0x00
+            # E5M2: M = 57344 = 7 * 8192 has an odd significand, the tie 61440 goes to infinity
+            assert r(61440.0, E5M2, v, 3, n) == 0x7C and r(down(61440.0), E5M2, v, 3, n) == 0x7B
+            # binary8p3: M = 49152 = 6 * 8192: even
+            assert r(49152.0 + 4096.0, p3109(3), v, 3, n) == 0x7E and r(up(49152.0 + 4096.0), p3109(3), v, 3, n) == 0x7F
+            # saturating formats
+            assert r(100.0, E2M1, v, 3, n) == 0x7 and r(-np.inf, E2M1, v, 3, n) == 0xF and r(np.inf, E4M3, v, 3, n) == 0x7E
+            assert r(1e30, E3M2, v, 3, n) == 0x1F and r(-7.75, E2M3, v, 3, n) == 0x3F
+            assert r(np.nan, E4M3, v, 3, n) == 0x7F and r(-np.nan, E4M3, v, 3, n) == 0xFF
+            assert r(np.nan, E2M1, v, 3, n) == 0x7 and r(-np.nan, E2M1, v, 3, n) == 0xF      # no NaN code: +-M
+            assert r(-0.0, E4M3, v, 3, n) == 0x80
+    # a small negative value that rounds to zero: -0 where the format has it, 0 where it has not
+    assert r(-2.0 ** -20, BINARY8P4, SRFF, 3, 0) == 0x00 and r(-2.0 ** -20, E4M3, SRFF, 3, 0) == 0x80
+    assert r(-2.0 ** -11, BINARY8P4, RNE) == 0x00 and r(-2.0 ** -11, BINARY8P4, TA) == 0x81 and r(-2.0 ** -11, BINARY8P4, TNO) == 0x81
+
+
+# ------------------------------------------------------- the narrow-source training setting ----
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5])
+def test_bf16_to_binary8p4_closed_form_biases(oracle, N):
+    """Sec. IV's setting: bf16 updates (precision 8) into binary8p4 (precision 4), D = 4 excess bits,
+    3 random bits used, 4 ideal.  Over all bf16 values of one binade and all draws, the mean error in
+    target ulps is (2^-D - 2^-N)/2 for SRFF, 2^-(D+1) for SRF (both 0 once N >= D) and 0 for SRC."""
+    d = BINARY8P4
+    D = 4
+    codes16 = np.arange(0x3F80, 0x4000, dtype=np.uint16)        # bf16 values in [1, 2)
+    x = (codes16.astype(np.uint32) << 16).view(np.float32)
+    want = {SRFF: (Fraction(1, 2 ** D) - Fraction(1, 2 ** N)) / 2 if N < D else Fraction(0),
+            SRF: Fraction(1, 2 ** (D + 1)) if N < D else Fraction(0), SRC: Fraction(0), SRC_ODD: Fraction(0)}
+    for variant in DRAWING:
+        err = Fraction(0)
+        for xv in x:
+            for n in range(1 << N):
+                y = oracle.decode_format8(oracle.round_format8_with_n(xv, d, variant, N, n), d)
+                err += (Fraction(y) - Fraction(float(xv))) / Fraction(1, 8)
+        assert err / (x.size << N) == want[variant], (variant, N)
+
+
+# --------------------------------------------------------------------------- array entry ----
+@pytest.mark.parametrize("src", [FROM_BF16, FROM_FP16, FROM_FP32])
+def test_array_call_is_the_per_element_rule(oracle, src):
+    rng = np.random.default_rng(23 + src)
+    n = 3000
+    if src == FROM_FP32:
+        x = rng.integers(0, 1 << 32, size=n, dtype=np.uint32).view(np.float32)
+        wide = x
+    else:
+        x = rng.integers(0, 1 << 16, size=n, dtype=np.uint16)
+        wide = np.array([oracle.widen16(int(c), src) for c in x], dtype=np.uint32).view(np.float32)
+    for name in ("binary8p4", "e2m3"):
+        d = ALL[name]
+        for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 2), (SRC, 5), (SRC_ODD, 3), (TNO, 0), (TA, 0)):
+            seed, offset = 77, 12345
+            got = oracle.round_format8(x, src, d, variant, nbits, seed, offset)
+            for j in range(0, n, 7):
+                r = oracle.random_bits(seed, 0, offset + j, nbits) if variant in DRAWING else 0
+                assert got[j] == oracle.round_format8_with_n(wide[j], d, variant, nbits, r), (name, variant, j)
+            # chunked == whole (the bits are a function of the global index)
+            part = oracle.round_format8(x[1000:], src, d, variant, nbits, seed, offset + 1000)
+            assert np.array_equal(part, got[1000:])

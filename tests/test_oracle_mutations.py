@@ -13,7 +13,11 @@ SOURCE = os.path.join(ROOT, "oracle", "fbsr_oracle.cpp")
 
 # name -> the pins (pytest -k expression) that are expected to notice it; running only those keeps the
 # suite quick.  The planted mistake must make at least one of them fail.
-WATCHERS = {'srf_half_term_dropped': 'exhaustive_round_up_counts and 2-0', 'srff_strict_compare': 'representables_are_fixed or exhaustive_round_up_counts and 2-0', 'rne_ties_to_odd': 'rne_matches_library_cast', 'src_inner_round_is_floor': 'src_ties or closed_form_bias_fp32_to_bf16', 'src_ties_away': 'src_ties', 'subnormal_clamp_dropped': 'rne_matches_library_cast', 'philox_multipliers_swapped': 'philox_known', 'philox_nine_rounds': 'philox_known', 'slot_uses_n_not_w': 'random_bits_are_slices', 'overflow_tie_goes_down': 'specials_and_out_of_range', 'e4m3_overflows_to_nan': 'specials_and_out_of_range', 'sign_lost': 'rne_matches_library_cast', 'exponent_carry_missing': 'rne_matches_library_cast', 'sgd_two_roundings': 'sgd_is_one_fma', 'sgd_step_not_in_key': 'sgd_is_one_fma', 'stats_error_sign': 'stats_sum_is_the_exact', 'stats_ulp_of_wrong_format': 'stats_sum_is_the_exact', 'qat_bias_correction_dropped': 'qat_step_tracks', 'qat_weight_decay_sign': 'qat_step_tracks', 'qat_sum_not_rounded_to_16_bits': 'qat_step_structure', 'widen_fp16_bias': 'widening_matches'}
+WATCHERS = {'srf_half_term_dropped': 'exhaustive_round_up_counts and 2-0', 'srff_strict_compare': 'representables_are_fixed or exhaustive_round_up_counts and 2-0', 'rne_ties_to_odd': 'rne_matches_library_cast', 'src_inner_round_is_floor': 'src_ties or closed_form_bias_fp32_to_bf16', 'src_ties_away': 'src_ties', 'subnormal_clamp_dropped': 'rne_matches_library_cast', 'philox_multipliers_swapped': 'philox_known', 'philox_nine_rounds': 'philox_known', 'slot_uses_n_not_w': 'random_bits_are_slices', 'overflow_tie_goes_down': 'specials_and_out_of_range', 'e4m3_overflows_to_nan': 'specials_and_out_of_range', 'sign_lost': 'rne_matches_library_cast', 'exponent_carry_missing': 'rne_matches_library_cast', 'sgd_two_roundings': 'sgd_is_one_fma', 'sgd_step_not_in_key': 'sgd_is_one_fma', 'stats_error_sign': 'stats_sum_is_the_exact', 'stats_ulp_of_wrong_format': 'stats_sum_is_the_exact', 'qat_bias_correction_dropped': 'qat_step_tracks', 'qat_weight_decay_sign': 'qat_step_tracks', 'qat_sum_not_rounded_to_16_bits': 'qat_step_structure', 'widen_fp16_bias': 'widening_matches',
+            'tno_is_tne': 'deterministic_modes', 'ta_is_strict': 'deterministic_modes',
+            'src_odd_parity': 'ties_to_odd', 'generic_overflow_tie_parity': 'overflow_and_specials',
+            'generic_negative_zero_kept': 'overflow_and_specials', 'generic_subnormal_scale': 'published_value_sets',
+            'generic_nan_sign_dropped': 'overflow_and_specials'}
 
 MUTATIONS = [
     ("srf_half_term_dropped", "std::ldexp((double)(2 * n + 1), -(N + 1))", "std::ldexp((double)(2 * n), -(N + 1))"),
@@ -37,6 +41,13 @@ MUTATIONS = [
     ("qat_weight_decay_sign", "std::fmaf(a.weight_decay, w, ratio)", "std::fmaf(-a.weight_decay, w, ratio)"),
     ("qat_sum_not_rounded_to_16_bits", "bf16_to_float(to_bf16_rne(w + u16));", "(w + u16);"),
     ("widen_fp16_bias", "Format{16, 11, 15, 65504.0", "Format{16, 11, 16, 65504.0"),
+    ("tno_is_tne", "delta == 0.5 && std::fmod(fl, 2.0) == 0.0", "delta == 0.5 && std::fmod(fl, 2.0) == 1.0"),
+    ("ta_is_strict", "return delta >= 0.5;", "return delta > 0.5;"),
+    ("src_odd_parity", "r == 0.5 && std::fmod(lo, 2.0) == 0.0", "r == 0.5 && std::fmod(lo, 2.0) == 1.0"),
+    ("generic_overflow_tie_parity", "std::fmod(f.M / ulp_M, 2.0) == 1.0", "std::fmod(f.M / ulp_M, 2.0) == 0.0"),
+    ("generic_negative_zero_kept", "if (mag == 0 && !g.neg_zero) return 0u;", ""),
+    ("generic_subnormal_scale", "std::ldexp(1.0, 1 - f.B);      // Eq. (1)", "std::ldexp(1.0, -f.B);      // Eq. (1)"),
+    ("generic_nan_sign_dropped", "(uint32_t)g.nan_code | (g.nan_signed ? sign_code : 0u)", "(uint32_t)g.nan_code"),
 ]
 
 
@@ -50,7 +61,8 @@ def test_a_planted_mistake_is_caught(tmp_path, name, old, new):
     subprocess.check_call(["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fPIC", "-shared", "-pthread",
                            "-o", str(lib), str(src)])
     env = dict(os.environ, FBSR_ORACLE_LIB=str(lib))
-    run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+    run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                          os.path.join(ROOT, "tests", "test_oracle_format8.py"), "-x", "-q",
                           "-p", "no:cacheprovider", "-k", WATCHERS[name]], env=env, cwd=ROOT, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
     assert run.returncode != 0, "no pin noticed the planted mistake '%s'" % name
     assert b"failed" in run.stdout or b"error" in run.stdout.lower()
