@@ -166,6 +166,62 @@ int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant,
  * today, kept in the signature for layouts that are not). */
 uint64_t fbsr_bias_stats_workspace_bytes(uint64_t n, uint32_t nbins);
 
+/* ---------------------------------------------------------------- generic 8-bit-or-narrower targets */
+
+/* Any format (K, P, B; M) of Sec. II, Eq. (1) whose codes fit a byte.  The paper's format model leaves
+ * special encodings open, so they are part of the descriptor.
+ *   width       K, 2..8: code = sign | exponent (K - P bits) | trailing significand (P - 1 bits)
+ *   precision   P, 1..K-1
+ *   bias        B, 0..96
+ *   max_code    magnitude code (exponent << (P-1) | trailing bits) of M, the largest finite value; M must
+ *               be a normal value and M + ulp(M) a finite fp32 value.  Magnitude codes above max_code
+ *               are never produced, except inf_code
+ *   inf_code    magnitude code of infinity (above max_code), or -1: the format has none and SATURATES,
+ *               every |x| > M (infinities included) becomes +-M
+ *   nan_code    full code of the canonical NaN, or -1: the format has none and a NaN input becomes +-M.
+ *               Its magnitude part must be an unused one (above max_code, not inf_code), or it is the
+ *               sign bit alone in a format without negative zero
+ *   nan_signed  nonzero: the sign of a NaN input is OR-ed into nan_code (whose own sign bit must be 0)
+ *   neg_zero    nonzero: the format has -0.  Otherwise a negative input that rounds to zero gives code 0
+ * With an infinity, |x| > M is rounded to nearest on the unbounded-exponent grid, ties to even, whatever
+ * the variant (Sec. II: out-of-range values are "rounded deterministically as in IEEE-754 round to
+ * nearest"): below M + ulp(M)/2 to M, above it to infinity, the tie to whichever of the two has the even
+ * significand. */
+typedef struct {
+  int32_t width, precision, bias, max_code, inf_code, nan_code, nan_signed, neg_zero;
+} fbsr_format8;
+
+/* Source types of fbsr_round_format8 (the first two as in fbsr_src16). */
+#define FBSR_FROM_BF16 0
+#define FBSR_FROM_FP16 1
+#define FBSR_FROM_FP32 2
+
+/* Further rounding predicates, accepted by fbsr_round_format8 only. */
+#define FBSR_SRC_TIES_ODD 4 /* Eq. (7) with Round = nearest, ties to odd (Sec. III-F allows either)      */
+#define FBSR_RNO 5          /* round to nearest, ties to odd (Sec. II-A, R_TNO); nbits ignored            */
+#define FBSR_RNA 6          /* round to nearest, ties away from zero (Eq. (4), R_TA); nbits ignored       */
+
+/* Fills *out with a published format.  Names: "ocp_e4m3", "ocp_e5m2" (OCP 8-bit floating point; the same
+ * formats as FBSR_FMT_E4M3 / FBSR_FMT_E5M2), "ocp_e3m2", "ocp_e2m3", "ocp_e2m1" (OCP microscaling element
+ * types: no NaN, no infinity), "p3109_binary8p1" .. "p3109_binary8p7" (IEEE WG P3109 interim report:
+ * bias 2^(7-P), 0x80 the only NaN, 0x7F / 0xFF the infinities, no negative zero; binary8p4 is the format
+ * Sec. IV trains in).  Host-only.  Returns FBSR_OK, or FBSR_EINVAL for an unknown name or a null pointer. */
+int fbsr_format8_named(const char* name, fbsr_format8* out);
+
+/* FBSR_OK when the descriptor satisfies the constraints above, else FBSR_EINVAL.  Host-only. */
+int fbsr_format8_check(const fbsr_format8* fmt);
+
+/* Rounds n values of source type src to the format *fmt, one code per output byte (bits above K zero):
+ * out[j] = FBSR(value of x[j]; bits of global element offset + j, stream (seed, step = 0)), with the
+ * conventions of fbsr_round (sign-magnitude, target subnormals on the clamped-exponent grid of Eq. (2))
+ * and the descriptor's treatment of specials.  For the two OCP fp8 descriptors the result equals
+ * fbsr_round / fbsr_round_from16 byte for byte.
+ * x: n floats (FBSR_FROM_FP32) or n 16-bit codes (device, read).  out: n bytes (device, written).
+ * fmt: HOST pointer, read during the call.  variant: FBSR_RNE .. FBSR_RNA.
+ * Errors: FBSR_EINVAL (bad descriptor / src / variant / nbits, null pointer), FBSR_EALIGN, FBSR_EDEVICE. */
+int fbsr_round_format8(const void* x, int src, void* out, uint64_t n, const fbsr_format8* fmt, int variant,
+                       int nbits, uint64_t seed, uint64_t offset, void* stream);
+
 /* Static description of a status code. */
 const char* fbsr_strerror(int status);
 

@@ -12,12 +12,14 @@ LIB_PATH = os.path.join(_HERE, "libfbsr.so")
 
 FMT_BF16, FMT_E4M3, FMT_E5M2 = 0, 1, 2
 RNE, SRFF, SRF, SRC = 0, 1, 2, 3
+SRC_TIES_ODD, RNO, RNA = 4, 5, 6          # fbsr_round_format8 only
 SRC_BF16, SRC_FP16 = 0, 1
+FROM_BF16, FROM_FP16, FROM_FP32 = 0, 1, 2  # source types of fbsr_round_format8
 OK, EINVAL, EALIGN, ERANGE, EDEVICE = 0, 1, 2, 3, 4
 MAX_NBITS = 16
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
-EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
+EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_format8_named", "fbsr_format8_check", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
            "fbsr_strerror", "fbsr_version")
 
 
@@ -54,6 +56,12 @@ def lib():
         L.fbsr_bias_stats.restype = i32
         L.fbsr_bias_stats_workspace_bytes.argtypes = [u64, u32]
         L.fbsr_bias_stats_workspace_bytes.restype = u64
+        L.fbsr_format8_named.argtypes = [ctypes.c_char_p, vp]
+        L.fbsr_format8_named.restype = i32
+        L.fbsr_format8_check.argtypes = [vp]
+        L.fbsr_format8_check.restype = i32
+        L.fbsr_round_format8.argtypes = [vp, i32, vp, u64, vp, i32, i32, u64, u64, vp]
+        L.fbsr_round_format8.restype = i32
         L.fbsr_strerror.argtypes = [i32]
         L.fbsr_strerror.restype = ctypes.c_char_p
         L.fbsr_version.argtypes = []
@@ -109,6 +117,48 @@ def fbsr_round_from16(x, src_fmt, fmt, variant, nbits, seed, offset=0, out=None,
     assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.dtype == torch.uint8
     _check(lib().fbsr_round_from16(x.data_ptr(), out.data_ptr(), n, src_fmt, fmt, variant, nbits, seed,
                                    offset, _stream_handle(stream)), "fbsr_round_from16")
+    return out
+
+
+class Format8(ctypes.Structure):
+    """Mirror of the C struct fbsr_format8: a format (K, P, B; M) with K <= 8 and its special codes."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("width", "precision", "bias", "max_code", "inf_code", "nan_code",
+                                             "nan_signed", "neg_zero")]
+
+    def astuple(self):
+        return tuple(getattr(self, k) for k, _ in self._fields_)
+
+
+def _format8(fmt):
+    return fmt if isinstance(fmt, Format8) else Format8(*[int(v) for v in fmt])
+
+
+def format8_named(name):
+    """The descriptor of a published format ("ocp_e4m3", "ocp_e2m1", "p3109_binary8p4", ...).  Host-only."""
+    f = Format8()
+    _check(lib().fbsr_format8_named(name.encode(), ctypes.byref(f)), "fbsr_format8_named(%r)" % name)
+    return f
+
+
+def format8_check(fmt):
+    """True when the descriptor (a Format8 or an 8-tuple) is acceptable.  Host-only."""
+    return lib().fbsr_format8_check(ctypes.byref(_format8(fmt))) == OK
+
+
+def fbsr_round_format8(x, src, fmt, variant, nbits, seed, offset=0, out=None, stream=None):
+    """Rounds to a generic format (a Format8 or an 8-tuple), one code per output byte.  x: float32 CUDA tensor
+    (src = FROM_FP32) or a tensor of 16-bit codes (FROM_BF16 / FROM_FP16)."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.element_size() == (4 if src == FROM_FP32 else 2)
+    if src == FROM_FP32:
+        assert x.dtype == torch.float32
+    n = x.numel()
+    if out is None:
+        out = torch.empty(n, dtype=torch.uint8, device=x.device)
+    assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.dtype == torch.uint8
+    f = _format8(fmt)
+    _check(lib().fbsr_round_format8(x.data_ptr(), src, out.data_ptr(), n, ctypes.byref(f), variant, nbits, seed, offset,
+                                    _stream_handle(stream)), "fbsr_round_format8")
     return out
 
 

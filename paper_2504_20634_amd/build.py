@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libfbsr.so")
-SOURCES = ["fbsr_api.hip", "fbsr_block.hip", "fbsr_round.hip", "fbsr_round16.hip", "fbsr_qat.hip", "fbsr_sgd.hip", "fbsr_stats.hip"]
+SOURCES = ["fbsr_api.hip", "fbsr_block.hip", "fbsr_format8.hip", "fbsr_round.hip", "fbsr_round16.hip", "fbsr_qat.hip", "fbsr_sgd.hip", "fbsr_stats.hip"]
 HEADERS = ["fbsr_device.h", "fbsr_launch.h"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -41,7 +41,7 @@ def build(force=True):
     """Compile every translation unit and link the shared library.  Returns its path."""
     if not force and not stale():
         return LIB
-    with ThreadPoolExecutor(max_workers=7) as pool:
+    with ThreadPoolExecutor(max_workers=8) as pool:
         objs = list(pool.map(_compile, SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
     return LIB

@@ -1,5 +1,8 @@
 // fbsr_api.hip -- the C ABI declared in include/fbsr.h: host-side argument checking and
 // dispatch.  Every check happens before anything is enqueued.
+#include <math.h>
+#include <string.h>
+
 #include "../../include/fbsr.h"
 #include "fbsr_launch.h"
 
@@ -17,6 +20,74 @@ int check_common(int variant, int nbits, uint64_t n, uint64_t offset) {
 bool misaligned(const void* p, uintptr_t a) { return reinterpret_cast<uintptr_t>(p) % a != 0; }
 
 uint64_t code_bytes(int fmt) { return fmt == FBSR_FMT_BF16 ? 2 : 1; }
+
+// Checks a generic-format descriptor and reduces it to the constants of the code-space arithmetic.
+bool derive_format8(const fbsr_format8& d, fbsr::Fmt8* f) {
+  const int K = d.width, P = d.precision, B = d.bias;
+  if (K < 2 || K > 8 || P < 1 || P >= K || B < 0 || B > 96) return false;
+  const int sign_bit = 1 << (K - 1), mag_top = sign_bit - 1;
+  if (d.max_code > mag_top || d.max_code < (1 << (P - 1))) return false;   // M must be a normal value
+  const bool has_inf = d.inf_code != -1;
+  if (has_inf && (d.inf_code <= d.max_code || d.inf_code > mag_top)) return false;
+  const bool has_nan = d.nan_code != -1;
+  if (has_nan) {
+    if (d.nan_code < 0 || d.nan_code > 2 * mag_top + 1) return false;
+    const int mag = d.nan_code & mag_top;
+    const bool negative = (d.nan_code & sign_bit) != 0;
+    const bool spare_magnitude = mag > d.max_code && !(has_inf && mag == d.inf_code);
+    const bool minus_zero_code = mag == 0 && negative && d.neg_zero == 0 && d.nan_signed == 0;
+    if (!spare_magnitude && !minus_zero_code) return false;
+    if (d.nan_signed != 0 && negative) return false;
+  }
+  const int e_max = d.max_code >> (P - 1), t_max = d.max_code & ((1 << (P - 1)) - 1);
+  if (e_max - B > 126) return false;   // M + ulp(M) has to be a finite fp32 value
+  const uint32_t ulp = 1u << (24 - P);   // one target ulp of a normal value, in fp32 pattern units
+  f->shift_p = (uint32_t)P;
+  f->rebias = (uint32_t)(127 - B) << 23;
+  f->u_max = ((uint32_t)(e_max + 127 - B) << 23) | ((uint32_t)t_max * ulp);
+  f->u_clamp = has_inf ? f->u_max + 3u * (ulp >> 2) : f->u_max;
+  f->u_sub = (uint32_t)(128 - B) << 23;
+  f->sub_scale = ldexpf(1.0f, 22 + B + P);
+  const uint32_t m_odd = P == 1 ? 1u : (uint32_t)(d.max_code & 1);   // parity of M's significand
+  f->det_add = (1u << 23) - 1u + m_odd;
+  f->max_code = (uint32_t)d.max_code;
+  f->over_code = (uint32_t)(has_inf ? d.inf_code : d.max_code);
+  f->nan_code = (uint32_t)(has_nan ? d.nan_code : d.max_code);
+  f->nan_sign = (!has_nan || d.nan_signed != 0) ? (uint32_t)sign_bit : 0u;
+  f->sign_bit = (uint32_t)sign_bit;
+  f->sign_shift = (uint32_t)(32 - K);
+  f->zero_sign = d.neg_zero != 0 ? (uint32_t)sign_bit : 0u;
+  f->unit_lsb = P == 1 ? (1u << 24) : 0u;
+  return true;
+}
+
+// The addend constants of a rounding mode in a code space with 24 fraction bits.
+bool derive_mode8(int variant, int nbits, fbsr::Mode8* m) {
+  const bool draws = variant == FBSR_SRFF || variant == FBSR_SRF || variant == FBSR_SRC || variant == FBSR_SRC_TIES_ODD;
+  if (variant < FBSR_RNE || variant > FBSR_RNA) return false;
+  if (draws && (nbits < 1 || nbits > FBSR_MAX_NBITS)) return false;
+  m->nbits = draws ? (uint32_t)nbits : 0u;
+  m->shift = 24u - m->nbits;
+  const uint32_t half = 1u << (m->shift - 1);   // half of the last kept place
+  m->tie_xor = (variant == FBSR_SRC_TIES_ODD || variant == FBSR_RNO) ? 1u : 0u;
+  m->ties = variant == FBSR_RNE || variant == FBSR_RNO || variant == FBSR_SRC || variant == FBSR_SRC_TIES_ODD;
+  m->fixed = m->ties ? half - 1u : (variant == FBSR_SRF || variant == FBSR_RNA) ? half : 0u;
+  return true;
+}
+
+struct NamedFormat8 {
+  const char* name;
+  fbsr_format8 f;
+};
+
+// Published formats: OCP 8-bit floating point, OCP microscaling element types.
+const NamedFormat8 kNamed[] = {
+    {"ocp_e4m3", {8, 4, 7, 0x7E, -1, 0x7F, 1, 1}},
+    {"ocp_e5m2", {8, 3, 15, 0x7B, 0x7C, 0x7E, 1, 1}},
+    {"ocp_e3m2", {6, 3, 3, 0x1F, -1, -1, 0, 1}},
+    {"ocp_e2m3", {6, 4, 1, 0x1F, -1, -1, 0, 1}},
+    {"ocp_e2m1", {4, 2, 1, 0x07, -1, -1, 0, 1}},
+};
 
 }  // namespace
 
@@ -89,6 +160,45 @@ int fbsr_qat_adamw_step(void* w8, const void* g16, void* m16, void* v16, uint64_
                                               reinterpret_cast<uint16_t*>(m16), reinterpret_cast<uint16_t*>(v16), n, fmt,
                                               sc, variant, nbits, seed, step, offset,
                                               reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
+int fbsr_format8_named(const char* name, fbsr_format8* out) {
+  if (name == nullptr || out == nullptr) return FBSR_EINVAL;
+  for (const NamedFormat8& k : kNamed) {
+    if (strcmp(name, k.name) == 0) {
+      *out = k.f;
+      return FBSR_OK;
+    }
+  }
+  // IEEE WG P3109 interim report, binary8pP: bias 2^(7-P), NaN 0x80, infinities 0x7F / 0xFF, no -0
+  const char* stem = "p3109_binary8p";
+  const size_t len = strlen(stem);
+  if (strncmp(name, stem, len) == 0 && name[len] >= '1' && name[len] <= '7' && name[len + 1] == '\0') {
+    const int P = name[len] - '0';
+    *out = fbsr_format8{8, P, 1 << (7 - P), 0x7E, 0x7F, 0x80, 0, 0};
+    return FBSR_OK;
+  }
+  return FBSR_EINVAL;
+}
+
+int fbsr_format8_check(const fbsr_format8* fmt) {
+  fbsr::Fmt8 f;
+  return fmt != nullptr && derive_format8(*fmt, &f) ? FBSR_OK : FBSR_EINVAL;
+}
+
+int fbsr_round_format8(const void* x, int src, void* out, uint64_t n, const fbsr_format8* fmt, int variant, int nbits,
+                       uint64_t seed, uint64_t offset, void* stream) {
+  fbsr::Fmt8 f;
+  fbsr::Mode8 m;
+  if (fmt == nullptr || !derive_format8(*fmt, &f) || !derive_mode8(variant, nbits, &m)) return FBSR_EINVAL;
+  if (src != FBSR_FROM_BF16 && src != FBSR_FROM_FP16 && src != FBSR_FROM_FP32) return FBSR_EINVAL;
+  if (n > fbsr::kMaxElems || offset > UINT64_MAX - n) return FBSR_EINVAL;
+  if (n == 0) return FBSR_OK;
+  if (x == nullptr || out == nullptr) return FBSR_EINVAL;
+  if (misaligned(x, src == FBSR_FROM_FP32 ? 4 : 2)) return FBSR_EALIGN;
+  const hipError_t e = fbsr::launch_round_format8(x, src, reinterpret_cast<uint8_t*>(out), n, f, m, seed, offset,
+                                                  reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 

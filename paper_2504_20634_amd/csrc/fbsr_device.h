@@ -14,6 +14,7 @@
 // exponent (Sec. II-A: "incrementing the exponent if sigma = 2^P") with no extra work.
 #pragma once
 
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,6 +29,19 @@ __device__ __forceinline__ f32x4 load_stream4(const float* p) {
 
 enum : int { kBF16 = 0, kE4M3 = 1, kE5M2 = 2 };
 enum : int { kRNE = 0, kSRFF = 1, kSRF = 2, kSRC = 3 };
+enum : int { kSrcBF16 = 0, kSrcFP16 = 1, kSrcFP32 = 2 };
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Exact fp32 pattern of a 16-bit source code.
+template <int SRC>
+__device__ __forceinline__ uint32_t widen16(uint32_t code16) {
+  if constexpr (SRC == kSrcBF16) {
+    return code16 << 16;
+  } else {
+    return __float_as_uint(__half2float(__ushort_as_half((unsigned short)code16)));   // v_cvt_f32_f16: exact
+  }
+}
 
 // ------------------------------------------------------------------------------ Philox ---
 // Philox4x32-10 (Salmon et al., SC'11).  Counter (c0..c3), key (k0,k1); the key and the two
@@ -349,6 +363,85 @@ __device__ __forceinline__ uint32_t round4_fp8_hw(const uint32_t (&bits)[4], con
     }
   }
   return (uint32_t)packed;
+}
+
+// ----------------------------------------------------------- generic formats, K <= 8 ---
+// A generic target format and a rounding mode, both reduced on the host to the constants the
+// code-space arithmetic needs (computed on the host from the caller's descriptor).
+struct Fmt8 {
+  uint32_t shift_p;     // P: a target-normal pattern maps to (u - rebias) << P
+  uint32_t rebias;      // (127 - B) << 23
+  uint32_t u_max;       // fp32 pattern of M
+  uint32_t u_clamp;     // |x| is clamped to this pattern: M when saturating, M + 3/4 ulp(M) with an infinity
+  uint32_t u_sub;       // fp32 pattern of 2^(1-B), the smallest normal
+  float sub_scale;      // 2^(22 + B + P): a target-subnormal |x| maps to trunc(|x| * sub_scale)
+  uint32_t det_add;     // the nearest-even addend that applies above M
+  uint32_t max_code;    // magnitude code of M
+  uint32_t over_code;   // magnitude code that replaces every code above max_code (infinity)
+  uint32_t nan_code;    // code of a NaN input before its sign is applied
+  uint32_t nan_sign;    // the sign bit if a NaN input keeps its sign, else 0
+  uint32_t sign_bit;    // 1 << (K - 1)
+  uint32_t sign_shift;  // 32 - K: (pattern >> sign_shift) & sign_bit is the code's sign
+  uint32_t zero_sign;   // the sign bit if the format has -0, else 0
+  uint32_t unit_lsb;    // 1 << 24 when P = 1 (the significand's last place is the implicit one), else 0
+};
+
+struct Mode8 {
+  uint32_t nbits;       // N; 0 for the deterministic modes
+  uint32_t shift;       // 24 - N
+  uint32_t fixed;       // the part of the addend that does not depend on the element
+  uint32_t tie_xor;     // inner rounding: 0 ties-to-even, 1 ties-to-odd
+  bool ties;            // the mode has an inner round-to-nearest (RNE, RNO, both SRC)
+};
+
+// One source pattern -> the output byte.  n < 2^N is the element's random integer (0 when the mode
+// draws none).  CHECKED = false may be used only when the pattern is known not to be a NaN.
+template <bool TIES, bool CHECKED>
+__device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m) {
+  const uint32_t u = bits & 0x7FFFFFFFu;
+  const uint32_t uc = u < f.u_clamp ? u : f.u_clamp;
+  const uint32_t normal = (uc - f.rebias) << f.shift_p;
+  const float scaled = __uint_as_float(uc) * f.sub_scale;   // exact: power-of-two scale (used below 2^(1-B) only)
+  const uint32_t sub = (uint32_t)scaled;                     // truncation toward zero
+  const bool is_sub = u < f.u_sub;
+  uint32_t r0 = is_sub ? sub : normal;
+  uint32_t add = (n << m.shift) + m.fixed;
+  if constexpr (TIES) {
+    // what a target-subnormal input loses to the truncation is folded into bit 0, below the tie position
+    const bool lost = is_sub && ((float)sub != scaled);
+    r0 |= lost ? 1u : 0u;
+    uint32_t parity_of = r0;
+    // P = 1 stores no significand bit: a normal value's significand is its implicit one (odd)
+    if (f.unit_lsb != 0u) parity_of |= is_sub ? 0u : f.unit_lsb;
+    add += ((parity_of >> m.shift) & 1u) ^ m.tie_xor;
+  }
+  add = u > f.u_max ? f.det_add : add;   // |x| > M: no randomness (Sec. II)
+  uint32_t mag = (r0 + add) >> 24;
+  mag = mag > f.max_code ? f.over_code : mag;
+  const uint32_t sgn = (bits >> f.sign_shift) & f.sign_bit;
+  uint32_t code = mag | (mag == 0u ? (sgn & f.zero_sign) : sgn);
+  if constexpr (CHECKED) code = u > 0x7F800000u ? (f.nan_code | (sgn & f.nan_sign)) : code;
+  return code;
+}
+
+__device__ __forceinline__ uint32_t pack4_bytes(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+  const uint32_t lo = __builtin_amdgcn_perm(c1, c0, 0x0c0c0400u);   // [c0.b0, c1.b0, 0, 0]
+  const uint32_t hi = __builtin_amdgcn_perm(c3, c2, 0x04000c0cu);   // [0, 0, c2.b0, c3.b0]
+  return lo | hi;
+}
+
+template <bool TIES>
+__device__ __forceinline__ uint32_t round4_bytes(const uint32_t (&b)[4], const uint32_t (&n)[4], bool checked,
+                                                 const Fmt8& f, const Mode8& m) {
+  uint32_t c[4];
+  if (checked) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c[j] = round8<TIES, true>(b[j], n[j], f, m);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c[j] = round8<TIES, false>(b[j], n[j], f, m);
+  }
+  return pack4_bytes(c[0], c[1], c[2], c[3]);
 }
 
 // Random integer of ONE element with global index i (the per-element kernels).

@@ -1,0 +1,174 @@
+// fbsr_format8.hip -- kernels behind fbsr_round_format8: few-bit stochastic rounding of fp32 / bf16 /
+// binary16 values to ANY format (K, P, B; M) of Sec. II, Eq. (1) with K <= 8, plus the deterministic
+// modes of Sec. II-A (nearest with ties to even, to odd, away from zero) and Eq. (7) with either tie
+// rule for its inner rounding (Sec. III-F).
+//
+// The arithmetic is the code-space addition of fbsr_device.h with the format's constants as
+// wave-uniform kernel arguments instead of template parameters: a 32-bit word whose top byte is the
+// magnitude code and whose low 24 bits are delta 2^24; every predicate is one integer addition.
+//     nearest-even   + 2^23 - 1 + (last kept bit)          ties-to-odd   + 2^23 - 1 + (last kept bit ^ 1)
+//     ties-away      + 2^23                                 SRFF / SRF / SRC as in fbsr_device.h
+// Above M a format with an infinity takes the nearest-even addend of M's own parity, which carries
+// into the code after max_code; that code is then replaced by the infinity's.
+#include "fbsr_launch.h"
+
+namespace fbsr {
+
+// One workgroup per 2048-element tile, one wave per 512 elements.  fp32 source: two rows of 256
+// elements per wave, a lane owns 4 consecutive floats per row (16-byte load, 4-byte store).  16-bit
+// sources: a lane owns 8 consecutive codes (16-byte load, 8-byte store).  W = 0: the mode draws no bits.
+template <int SRC, bool TIES, int W>
+__global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict__ xin, uint8_t* __restrict__ out, Fmt8 f,
+                                                          Mode8 m, uint64_t seed, uint64_t blk0) {
+  constexpr int WW = W == 0 ? 1 : W;
+  typedef WgTile<WW> T;
+  __shared__ uint4 strip[T::BLOCKS];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  if constexpr (SRC == kSrcFP32) {
+    const float* x = reinterpret_cast<const float*>(xin);
+    const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+    f32x4 v[kRows];
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
+    if constexpr (W != 0) {
+      fill_wg_bits<WW>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
+      __syncthreads();
+    }
+    uint32_t umax = 0;
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) {
+      umax = max(umax, max(max(__float_as_uint(v[k].x) & 0x7FFFFFFFu, __float_as_uint(v[k].y) & 0x7FFFFFFFu),
+                           max(__float_as_uint(v[k].z) & 0x7FFFFFFFu, __float_as_uint(v[k].w) & 0x7FFFFFFFu)));
+    }
+    const bool checked = __any(umax > 0x7F800000u);   // wave-uniform: a NaN among the wave's elements
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) {
+      uint64_t rb = 0;
+      if constexpr (W != 0) rb = read_wg_row_bits<WW>(strip, wave, lane, k);
+      const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
+                             __float_as_uint(v[k].w)};
+      const uint32_t n4[4] = {W == 0 ? 0u : slot_bits<WW>(rb, 0, m.nbits), W == 0 ? 0u : slot_bits<WW>(rb, 1, m.nbits),
+                              W == 0 ? 0u : slot_bits<WW>(rb, 2, m.nbits), W == 0 ? 0u : slot_bits<WW>(rb, 3, m.nbits)};
+      __builtin_nontemporal_store(round4_bytes<TIES>(b, n4, checked, f, m),
+                                  reinterpret_cast<uint32_t*>(out) + row0 + (uint64_t)(k * 64));
+    }
+  } else {
+    const uint16_t* x = reinterpret_cast<const uint16_t*>(xin);
+    const int e0 = wave * kWaveElems + 8 * lane;                                  // tile-relative first element
+    const uint64_t g0 = (uint64_t)blockIdx.x * T::ELEMS + (uint64_t)e0;           // call-relative first element
+    const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + g0));
+    if constexpr (W != 0) {
+      fill_wg_bits<WW>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
+      __syncthreads();
+    }
+    const uint32_t words[4] = {q.x, q.y, q.z, q.w};
+    uint32_t b[8];
+    uint32_t umax = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      b[j] = widen16<SRC>((words[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
+      umax = max(umax, b[j] & 0x7FFFFFFFu);
+    }
+    const bool checked = __any(umax > 0x7F800000u);
+    uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (W != 0) read_wg_bits8<WW>(strip, e0, m.nbits, n);
+    const uint32_t b_lo[4] = {b[0], b[1], b[2], b[3]}, b_hi[4] = {b[4], b[5], b[6], b[7]};
+    const uint32_t n_lo[4] = {n[0], n[1], n[2], n[3]}, n_hi[4] = {n[4], n[5], n[6], n[7]};
+    const uint32_t lo = round4_bytes<TIES>(b_lo, n_lo, checked, f, m);
+    const uint32_t hi = round4_bytes<TIES>(b_hi, n_hi, checked, f, m);
+    __builtin_nontemporal_store((uint64_t)lo | ((uint64_t)hi << 32), reinterpret_cast<uint64_t*>(out + g0));
+  }
+}
+
+// One thread per element: any alignment, any offset, ragged heads and tails.  W = 0: no bits.
+template <int SRC, bool TIES>
+__global__ __launch_bounds__(kThreads) void format8_elems(const void* __restrict__ xin, uint8_t* __restrict__ out, uint64_t n,
+                                                          Fmt8 f, Mode8 m, int W, int log2_per_block, uint64_t seed,
+                                                          uint64_t offset) {
+  const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (j >= n) return;
+  uint32_t bits;
+  if constexpr (SRC == kSrcFP32) bits = __float_as_uint(reinterpret_cast<const float*>(xin)[j]);
+  else bits = widen16<SRC>(reinterpret_cast<const uint16_t*>(xin)[j]);
+  uint32_t rnd = 0;
+  if (W != 0) rnd = element_bits(offset + j, log2_per_block, W, m.nbits, seed, 0);
+  out[j] = (uint8_t)round8<TIES, true>(bits, rnd, f, m);
+}
+
+namespace {
+
+template <int SRC, bool TIES>
+hipError_t launch_tiles_w(int W, const void* x, uint8_t* out, uint64_t ntiles, const Fmt8& f, const Mode8& m, uint64_t seed,
+                          uint64_t blk0, hipStream_t stream) {
+  const dim3 grid((unsigned)ntiles), block(kThreads);
+#define FBSR_F8_LAUNCH(WW) hipLaunchKernelGGL((format8_tiles<SRC, TIES, WW>), grid, block, 0, stream, x, out, f, m, seed, blk0)
+  switch (W) {
+    case 0: FBSR_F8_LAUNCH(0); break;
+    case 1: FBSR_F8_LAUNCH(1); break;
+    case 2: FBSR_F8_LAUNCH(2); break;
+    case 4: FBSR_F8_LAUNCH(4); break;
+    case 8: FBSR_F8_LAUNCH(8); break;
+    default: FBSR_F8_LAUNCH(16); break;
+  }
+#undef FBSR_F8_LAUNCH
+  return hipGetLastError();
+}
+
+template <int SRC, bool TIES>
+hipError_t launch_elems(const char* x, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m, int W, uint64_t seed,
+                        uint64_t offset, hipStream_t stream) {
+  constexpr uint64_t isize = SRC == kSrcFP32 ? 4 : 2;
+  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
+    const uint64_t cnt = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
+    const uint64_t blocks = (cnt + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL((format8_elems<SRC, TIES>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                       reinterpret_cast<const void*>(x + at * isize), out + at, cnt, f, m, W, W ? log2_of(128 / W) : 0, seed,
+                       offset + at);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <int SRC, bool TIES>
+hipError_t run(const void* xin, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
+               hipStream_t stream) {
+  constexpr uint64_t isize = SRC == kSrcFP32 ? 4 : 2;
+  constexpr uint64_t oalign = SRC == kSrcFP32 ? 4 : 8;
+  const char* x = reinterpret_cast<const char*>(xin);
+  const int W = m.nbits ? slot_width((int)m.nbits) : 0;
+  const Split s = split_range(n, offset, W ? W : 8, W == 0, reinterpret_cast<uintptr_t>(x), isize, 16,
+                              reinterpret_cast<uintptr_t>(out), 1, oalign);
+  hipError_t e = launch_elems<SRC, TIES>(x, out, s.head, f, m, W, seed, offset, stream);
+  if (e != hipSuccess) return e;
+  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
+    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
+    const uint64_t e0 = s.head + t0 * s.tile_elems;
+    e = launch_tiles_w<SRC, TIES>(W, x + e0 * isize, out + e0, cnt, f, m, seed, W ? (offset + e0) / (uint64_t)(128 / W) : 0,
+                                  stream);
+    if (e != hipSuccess) return e;
+  }
+  const uint64_t done = s.head + s.ntiles * s.tile_elems;
+  return launch_elems<SRC, TIES>(x + done * isize, out + done, n - done, f, m, W, seed, offset + done, stream);
+}
+
+template <int SRC>
+hipError_t run_t(const void* x, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
+                 hipStream_t stream) {
+  if (m.ties) return run<SRC, true>(x, out, n, f, m, seed, offset, stream);
+  return run<SRC, false>(x, out, n, f, m, seed, offset, stream);
+}
+
+}  // namespace
+
+hipError_t launch_round_format8(const void* x, int src, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m,
+                                uint64_t seed, uint64_t offset, hipStream_t stream) {
+  switch (src) {
+    case kSrcBF16: return run_t<kSrcBF16>(x, out, n, f, m, seed, offset, stream);
+    case kSrcFP16: return run_t<kSrcFP16>(x, out, n, f, m, seed, offset, stream);
+    default: return run_t<kSrcFP32>(x, out, n, f, m, seed, offset, stream);
+  }
+}
+
+}  // namespace fbsr

@@ -80,6 +80,9 @@ hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uin
                             const AdamWScalars& p, int variant, int nbits, uint64_t seed, uint64_t step,
                             uint64_t offset, hipStream_t stream);
 
+hipError_t launch_round_format8(const void* x, int src, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m,
+                                uint64_t seed, uint64_t offset, hipStream_t stream);
+
 // The tile kernel of the statistics path works in chunks of kStatsChunkTiles tiles per workgroup
 // and leaves one record {sum y, sum e, sum e^2} per (chunk, bin the chunk touches) in the
 // workspace; a chunk touches at most chunk / group + 2 bins, and group >= one tile on this path.

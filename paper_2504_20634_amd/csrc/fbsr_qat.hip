@@ -7,7 +7,6 @@
 
 namespace fbsr {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Exact value of an fp8 code (Eq. (1)); the hardware decode agrees with it on all 256 codes.
 template <int FMT>

@@ -2,25 +2,9 @@
 // stochastic rounding, the narrow-source setting of Sec. III-E and Fig. 2 (few excess bits D).
 // The source value is widened exactly to an fp32 pattern and then takes the same rounding core as
 // fbsr_round.
-#include <hip/hip_fp16.h>
-
 #include "fbsr_launch.h"
 
 namespace fbsr {
-
-enum : int { kSrcBF16 = 0, kSrcFP16 = 1 };
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// Exact fp32 pattern of a 16-bit source code.
-template <int SRC>
-__device__ __forceinline__ uint32_t widen16(uint32_t code16) {
-  if constexpr (SRC == kSrcBF16) {
-    return code16 << 16;
-  } else {
-    return __float_as_uint(__half2float(__ushort_as_half((unsigned short)code16)));   // v_cvt_f32_f16: exact
-  }
-}
 
 // One workgroup per 2048-element tile, one wave per 512 elements, one 16-byte load of 8 source
 // codes and one 8-byte store of 8 fp8 codes per lane: 3 bytes of traffic per element.

@@ -44,6 +44,9 @@ def test_enums_match_the_header():
                       ("FBSR_ERANGE", b.ERANGE), ("FBSR_EDEVICE", b.EDEVICE)):
         assert re.search(r"\b%s\s*=\s*%d\b" % (name, val), text), name
     assert re.search(r"#define\s+FBSR_MAX_NBITS\s+%d" % b.MAX_NBITS, text)
+    for name, val in (("FBSR_FROM_BF16", b.FROM_BF16), ("FBSR_FROM_FP16", b.FROM_FP16), ("FBSR_FROM_FP32", b.FROM_FP32),
+                      ("FBSR_SRC_TIES_ODD", b.SRC_TIES_ODD), ("FBSR_RNO", b.RNO), ("FBSR_RNA", b.RNA)):
+        assert re.search(r"#define\s+%s\s+%d\b" % (name, val), text), name
 
 
 def test_strerror_and_version(L):
@@ -106,6 +109,55 @@ def test_argument_validation_happens_on_the_host(L):
     need = L.fbsr_bias_stats_workspace_bytes(8, 2)
     assert need > 0
     assert L.fbsr_bias_stats(p(good), None, 8, 0, 1, 2, 0, 0, 4, 0, 2, p(good), p(good), need - 1, None) == ERANGE
+
+
+def test_named_formats_and_descriptor_checks(L):
+    """Host-only entry points: the named descriptors equal the ones the oracle's pins were written with
+    (tests/test_oracle_format8.py states them from the formats' public definitions), and both sides accept and
+    reject the same descriptors."""
+    import test_oracle_format8 as pins
+    from oracle import fbsr_oracle
+    from paper_2504_20634_amd import binding as b
+    names = {"ocp_e4m3": pins.E4M3, "ocp_e5m2": pins.E5M2, "ocp_e3m2": pins.E3M2, "ocp_e2m3": pins.E2M3, "ocp_e2m1": pins.E2M1}
+    names.update({"p3109_binary8p%d" % P: pins.p3109(P) for P in range(1, 8)})
+    for name, want in names.items():
+        assert b.format8_named(name).astuple() == tuple(want), name
+        assert b.format8_check(want)
+    for bad in ("", "ocp_e4m3 ", "p3109_binary8p0", "p3109_binary8p8", "p3109_binary8p44", "bf16"):
+        with pytest.raises(b.FbsrError):
+            b.format8_named(bad)
+    assert L.fbsr_format8_named(None, None) == 1 and L.fbsr_format8_check(None) == 1
+    # a sweep of descriptors, valid and not: the library and the oracle agree on every one
+    import itertools
+    checked = 0
+    for K, P, B, mx, inf, nan, ns, nz in itertools.product((1, 2, 4, 8, 9), (0, 1, 3, 7, 8), (-1, 0, 7, 96, 97),
+                                                           (0, 3, 7, 0x7B, 0x7E, 0x7F, 0x80), (-1, 0x7C, 0x7F),
+                                                           (-1, 0x7E, 0x7F, 0x80, 0xFF, 0x100), (0, 1), (0, 1)):
+        d = (K, P, B, mx, inf, nan, ns, nz)
+        assert b.format8_check(d) == fbsr_oracle.format8_check(d), d
+        checked += 1
+    assert checked > 10000
+
+
+def test_format8_argument_validation(L):
+    from paper_2504_20634_amd import binding as b
+    OK, EINVAL, EALIGN = 0, 1, 2
+    p = ctypes.c_void_p
+    good = 0x7F0000001000
+    f = b.format8_named("p3109_binary8p4")
+    ref = ctypes.byref(f)
+    assert L.fbsr_round_format8(None, 2, None, 0, ref, 1, 3, 0, 0, None) == OK
+    assert L.fbsr_round_format8(p(good), 2, p(good), 8, None, 1, 3, 0, 0, None) == EINVAL
+    for src, var, nb in ((3, 1, 3), (-1, 1, 3), (2, 7, 3), (2, -1, 3), (2, 1, 0), (2, 4, 17), (2, 3, -2)):
+        assert L.fbsr_round_format8(p(good), src, p(good), 8, ref, var, nb, 0, 0, None) == EINVAL
+    bad = b.Format8(8, 4, 8, 0x7E, 0x7E, 0x80, 0, 0)
+    assert L.fbsr_round_format8(p(good), 2, p(good), 8, ctypes.byref(bad), 1, 3, 0, 0, None) == EINVAL
+    assert L.fbsr_round_format8(None, 2, p(good), 8, ref, 1, 3, 0, 0, None) == EINVAL
+    assert L.fbsr_round_format8(p(good), 2, None, 8, ref, 1, 3, 0, 0, None) == EINVAL
+    assert L.fbsr_round_format8(p(good + 2), 2, p(good), 8, ref, 1, 3, 0, 0, None) == EALIGN
+    assert L.fbsr_round_format8(p(good + 1), 0, p(good), 8, ref, 1, 3, 0, 0, None) == EALIGN
+    assert L.fbsr_round_format8(p(good), 2, p(good), (1 << 38) + 1, ref, 1, 3, 0, 0, None) == EINVAL
+    assert L.fbsr_round_format8(p(good), 2, p(good), 8, ref, 1, 3, 0, (1 << 64) - 4, None) == EINVAL
 
 
 def test_workspace_size_grows_with_n(L):

@@ -1,0 +1,160 @@
+"""GPU parity: fbsr_round_format8 (generic (K, P, B; M) targets with K <= 8, the rounding modes of
+Sec. II-A and both tie rules of Eq. (7)) against the CPU oracle, byte for byte."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import dev, first_mismatch, host
+
+pytestmark = pytest.mark.gpu
+RNE, SRFF, SRF, SRC, SRC_ODD, RNO, RNA = range(7)
+FROM_BF16, FROM_FP16, FROM_FP32 = 0, 1, 2
+MODES = [(RNE, 0), (RNO, 0), (RNA, 0)] + [(v, nb) for v in (SRFF, SRF, SRC, SRC_ODD) for nb in (1, 3, 4, 8, 16)]
+
+
+def p3109(P):
+    return (8, P, 1 << (7 - P), 0x7E, 0x7F, 0x80, 0, 0)
+
+
+FORMATS = {"ocp_e4m3": (8, 4, 7, 0x7E, -1, 0x7F, 1, 1), "ocp_e5m2": (8, 3, 15, 0x7B, 0x7C, 0x7E, 1, 1),
+           "ocp_e3m2": (6, 3, 3, 0x1F, -1, -1, 0, 1), "ocp_e2m3": (6, 4, 1, 0x1F, -1, -1, 0, 1), "ocp_e2m1": (4, 2, 1, 0x07, -1, -1, 0, 1),
+           "binary8p1": p3109(1), "binary8p3": p3109(3), "binary8p4": p3109(4), "binary8p5": p3109(5), "binary8p7": p3109(7),
+           # not published anywhere: an infinity that is not the code after M (whose code is odd), a zero bias,
+           # the largest bias, the narrowest width
+           "inf_apart": (8, 4, 7, 0x77, 0x7A, 0x7F, 1, 1), "bias0": (5, 2, 0, 0x0E, 0x0F, -1, 0, 0),
+           "bias96": (8, 3, 96, 0x7B, 0x7C, 0x7E, 1, 1), "k2": (2, 1, 0, 1, -1, -1, 0, 1)}
+
+
+def _oracle(oracle, x, src, d, variant, nbits, seed, offset, threads=16):
+    cuts = np.linspace(0, x.size, threads + 1).astype(np.int64)
+    with ThreadPoolExecutor(threads) as pool:
+        parts = list(pool.map(lambda ab: oracle.round_format8(x[ab[0]:ab[1]], src, d, variant, nbits, seed, offset + int(ab[0])),
+                              zip(cuts[:-1], cuts[1:])))
+    return np.concatenate(parts)
+
+
+def _inputs(rng, d, count):
+    """fp32 patterns from far below the smallest subnormal to beyond M, with short mantissas (ties), the
+    neighbourhoods of M, of the overflow tie and of the smallest normal / subnormal, and specials."""
+    K, P, B, mx = d[:4]
+    e_top = (mx >> (P - 1)) - B
+    lo, hi = max(1, 127 + (1 - B) - (P - 1) - 30), min(254, 127 + e_top + 3)
+    bits = rng.integers(0, 1 << 32, count, dtype=np.uint32)
+    field = rng.integers(lo, hi + 1, count, dtype=np.uint32)
+    b = (bits & np.uint32(0x807FFFFF)) | (field << np.uint32(23))
+    b[::7] &= np.uint32(0xFFF00000)
+    b[::11] &= np.uint32(0xFFFF8000)
+    b[::13] &= np.uint32(0xFFFE0000)
+    t_max = mx & ((1 << (P - 1)) - 1)
+    M = (1.0 + t_max * 2.0 ** (1 - P)) * 2.0 ** e_top
+    ulp_M = 2.0 ** (e_top - P + 1)
+    pts = []
+    for v in (M, M + ulp_M / 2, M + ulp_M, M + 0.75 * ulp_M, 2.0 ** (1 - B), 2.0 ** (2 - B - P), 2.0 ** (1 - B - P), 3 * 2.0 ** (-B - P)):
+        u = int(np.float32(v).view(np.uint32))
+        pts += [u - 2, u - 1, u, u + 1, u + 2]
+    extra = np.array(pts + [0, 1, 0x007FFFFF, 0x00800000, 0x7F7FFFFF, 0x7F800000, 0x7F800001, 0x7FC00000, 0x7FFFFFFF], dtype=np.uint32)
+    return np.concatenate([b, extra, extra | np.uint32(0x80000000)]).view(np.float32)
+
+
+@pytest.mark.parametrize("name", sorted(FORMATS))
+def test_fp32_source_every_mode(fbsr, oracle, name):
+    d = FORMATS[name]
+    x = _inputs(np.random.default_rng(len(name)), d, 3 * 2048 * 37 + 11)
+    xd = dev(x)
+    for variant, nbits in MODES:
+        print("case fmt=%s variant=%d nbits=%d" % (name, variant, nbits), flush=True)
+        got = host(fbsr.fbsr_round_format8(xd, FROM_FP32, d, variant, nbits, seed=21, offset=0))
+        want = _oracle(oracle, x, FROM_FP32, d, variant, nbits, 21, 0)
+        assert first_mismatch(got, want) is None, (name, variant, nbits, first_mismatch(got, want))
+
+
+@pytest.mark.parametrize("src", [FROM_BF16, FROM_FP16])
+@pytest.mark.parametrize("name", ["binary8p4", "binary8p3", "ocp_e2m3", "ocp_e2m1", "binary8p1", "inf_apart"])
+def test_every_16_bit_source_code(fbsr, oracle, src, name):
+    """All 65536 source codes, each at 32 different global indices."""
+    d = FORMATS[name]
+    codes = np.tile(np.arange(65536, dtype=np.uint16), 32)
+    xd = dev(codes)
+    for variant, nbits in [(RNE, 0), (RNO, 0), (RNA, 0), (SRFF, 3), (SRF, 3), (SRC, 3), (SRC_ODD, 3), (SRFF, 4), (SRC, 8), (SRC_ODD, 11), (SRF, 16)]:
+        print("case src=%d fmt=%s variant=%d nbits=%d" % (src, name, variant, nbits), flush=True)
+        got = host(fbsr.fbsr_round_format8(xd, src, d, variant, nbits, seed=5, offset=0))
+        want = _oracle(oracle, codes, src, d, variant, nbits, 5, 0)
+        assert first_mismatch(got, want) is None, (src, name, variant, nbits, first_mismatch(got, want))
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 31, 127, 2047, 2048, 2049, 3 * 2048 + 100])
+def test_sizes_offsets_alignment(fbsr, oracle, n):
+    rng = np.random.default_rng(n + 1)
+    d = FORMATS["binary8p4"]
+    x32 = rng.integers(0, 1 << 32, n + 8, dtype=np.uint32).view(np.float32)
+    x16 = rng.integers(0, 1 << 16, n + 8, dtype=np.uint16)
+    for src, host_x in ((FROM_FP32, x32), (FROM_BF16, x16), (FROM_FP16, x16)):
+        xd = dev(host_x)
+        for variant, nbits in ((SRFF, 3), (SRC_ODD, 6), (RNA, 0), (SRF, 1), (SRC, 16)):
+            for offset in (0, 3, 128, (1 << 36) + 5):
+                for shift in (0, 1, 3):
+                    print("case n=%d src=%d variant=%d nbits=%d offset=%d shift=%d" % (n, src, variant, nbits, offset, shift), flush=True)
+                    xs = xd[shift:shift + n] if n else xd[:0]
+                    got = host(fbsr.fbsr_round_format8(xs, src, d, variant, nbits, seed=2, offset=offset))
+                    want = oracle.round_format8(host_x[shift:shift + n], src, d, variant, nbits, seed=2, offset=offset)
+                    assert first_mismatch(got, want) is None, first_mismatch(got, want)
+
+
+def test_ocp_descriptors_equal_the_fixed_format_entry_points(fbsr):
+    """fbsr_round / fbsr_round_from16 (hardware converts) and the generic integer path give the same bytes."""
+    rng = np.random.default_rng(9)
+    n = 1 << 22
+    x = torch.from_numpy(rng.integers(0, 1 << 32, n, dtype=np.uint32).view(np.int32)).cuda().view(torch.float32)
+    x16 = torch.from_numpy(rng.integers(0, 1 << 16, n, dtype=np.uint16).view(np.int16)).cuda()
+    for fmt, name in ((1, "ocp_e4m3"), (2, "ocp_e5m2")):
+        d = fbsr.format8_named(name)
+        for variant, nbits in ((RNE, 0), (SRFF, 2), (SRF, 4), (SRC, 8), (SRFF, 16), (SRC, 3)):
+            print("case fmt=%s variant=%d nbits=%d" % (name, variant, nbits), flush=True)
+            assert torch.equal(fbsr.fbsr_round(x, fmt, variant, nbits, seed=3, offset=77),
+                               fbsr.fbsr_round_format8(x, FROM_FP32, d, variant, nbits, seed=3, offset=77))
+            for src in (FROM_BF16, FROM_FP16):
+                assert torch.equal(fbsr.fbsr_round_from16(x16, src, fmt, variant, nbits, seed=3, offset=77),
+                                   fbsr.fbsr_round_format8(x16, src, d, variant, nbits, seed=3, offset=77))
+
+
+def test_chunked_equals_whole_and_repeatable(fbsr):
+    d = fbsr.format8_named("p3109_binary8p4")
+    n = 5 * 2048 + 333
+    x = torch.randn(n, device="cuda")
+    whole = fbsr.fbsr_round_format8(x, FROM_FP32, d, SRC, 3, seed=11, offset=1000)
+    assert torch.equal(whole, fbsr.fbsr_round_format8(x, FROM_FP32, d, SRC, 3, seed=11, offset=1000))
+    cut = 2048 + 77
+    a = fbsr.fbsr_round_format8(x[:cut], FROM_FP32, d, SRC, 3, seed=11, offset=1000)
+    b = fbsr.fbsr_round_format8(x[cut:], FROM_FP32, d, SRC, 3, seed=11, offset=1000 + cut)
+    assert torch.equal(whole, torch.cat([a, b]))
+
+
+def test_sec4_training_cast_bias_on_the_gpu(fbsr, oracle):
+    """Sec. IV's cast, bf16 updates -> binary8p4 with 3 random bits (D = 4 excess bits), at scale: every
+    bf16 value of [1, 2), 2^15 draws each.  Mean error in target ulps: SRFF (2^-4 - 2^-3)/2 = -0.03125,
+    SRF +2^-5 = +0.03125, SRC (either tie rule) 0, within the noise of the draws (0.3 / sqrt(4.2e6))."""
+    d = FORMATS["binary8p4"]
+    draws = 1 << 15
+    codes = np.repeat(np.arange(0x3F80, 0x4000, dtype=np.uint16), draws)
+    xd = dev(codes)
+    xv = (codes.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    table = np.array([oracle.decode_format8(c, d) for c in range(256)])
+    for variant, want in ((SRFF, -0.03125), (SRF, 0.03125), (SRC, 0.0), (SRC_ODD, 0.0)):
+        got = host(fbsr.fbsr_round_format8(xd, FROM_BF16, d, variant, 3, seed=31, offset=0))
+        bias = np.mean((table[got] - xv) / 0.125)
+        print("variant=%d bias=%+.6f ulp (closed form %+.6f)" % (variant, bias, want), flush=True)
+        assert abs(bias - want) < 1e-3
+    sample = slice(0, codes.size, 257)
+    want_codes = oracle.round_format8(codes, FROM_BF16, d, SRFF, 3, 31, 0)
+    got = host(fbsr.fbsr_round_format8(xd, FROM_BF16, d, SRFF, 3, seed=31, offset=0))
+    assert np.array_equal(got[sample], want_codes[sample])
+
+
+def test_rejects_bad_arguments(fbsr):
+    x = torch.zeros(16, device="cuda")
+    good = FORMATS["binary8p4"]
+    for d, variant, nbits in (((8, 4, 8, 0x7E, 0x7E, 0x80, 0, 0), SRFF, 3), (good, 7, 3), (good, SRC_ODD, 17), (good, SRF, 0)):
+        with pytest.raises(fbsr.FbsrError):
+            fbsr.fbsr_round_format8(x, FROM_FP32, d, variant, nbits, seed=0)
