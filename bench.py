@@ -175,6 +175,21 @@ def main():
             ms = timed_launches(torch, lambda: from16(f, v, nb), 12)
             paths["round_from_bf16_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
                 "ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
+        # generic-format path: the format Sec. IV trains in (P3109 binary8p4), from fp32 and from bf16 (N = 3)
+        p4 = fbsr.format8_named("p3109_binary8p4")
+        rotg = [0]
+
+        def generic(src, v, nb):
+            rotg[0] += 1
+            xin = x_rot[fbsr.FMT_E4M3][rotg[0] % 3] if src == fbsr.FROM_FP32 else x16[rotg[0] % 3]
+            fbsr.fbsr_round_format8(xin, src, p4, v, nb, seed=2, offset=0, out=out_rot[rotg[0] % 4])
+        for src, v, nb, tag in ((fbsr.FROM_FP32, fbsr.SRC, 3, "src"), (fbsr.FROM_FP32, fbsr.SRF, 8, "srf"),
+                                (fbsr.FROM_FP32, fbsr.SRC_TIES_ODD, 3, "src_ties_odd"), (fbsr.FROM_BF16, fbsr.SRC, 3, "src"),
+                                (fbsr.FROM_BF16, fbsr.SRFF, 3, "srff")):
+            ms = timed_launches(torch, lambda: generic(src, v, nb), 12)
+            bpe = 5.0 if src == fbsr.FROM_FP32 else 3.0
+            paths["round_format8_binary8p4_from_%s_N%d_%s" % ("fp32" if src == fbsr.FROM_FP32 else "bf16", nb, tag)] = {
+                "ms": round(ms, 4), "gb_s": round(bpe * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
         del x16
         # block-scaled fp8 target (one scale byte per 32 elements: 4 B read + 1 + 1/32 B written per element)
         sc = torch.empty(n // 32, dtype=torch.uint8, device="cuda")
