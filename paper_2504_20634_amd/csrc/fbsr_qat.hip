@@ -3,6 +3,8 @@
 // Per element 7 bytes are read (w8, g, m, v) and 5 written (w8, m, v); the arithmetic is a fixed
 // sequence of single IEEE fp32 operations (this file is compiled without contraction; the divisions
 // and the square root are the correctly rounded ones) so that it can be reproduced bit for bit.
+#include <type_traits>
+
 #include "fbsr_launch.h"
 
 namespace fbsr {
@@ -49,8 +51,43 @@ __device__ __forceinline__ QatOut qat_one(uint32_t w8, uint32_t g16, uint32_t m1
   return o;
 }
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 values -> two bf16 codes (a in the low half), round to nearest even, as one v_cvt_pk_bf16_f32.
+// On every non-NaN pattern the instruction equals the integer rounding of bf16_rne (overflow to infinity
+// and fp32 subnormals included; checked on all 2^32 patterns); a NaN comes back quieted in place, which is
+// not this library's canonical NaN, so callers keep NaNs away from results they store.
+__device__ __forceinline__ uint32_t bf16_pair_hw(float a, float b) {
+  const f32x2 v = {a, b};
+  const bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
+
+// Value of element J (0..7) of eight packed fp8 codes held in two words (hardware decode, byte select J & 3).
+template <int FMT, int J>
+__device__ __forceinline__ float w8_value(int lo, int hi) {
+  const int word = J < 4 ? lo : hi;
+  if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8(word, J & 3);
+  else return __builtin_amdgcn_cvt_f32_bf8(word, J & 3);
+}
+
+// The arithmetic of qat_one up to the bf16 sum s = bf16(w + u), for one element, on values.
+__device__ __forceinline__ float qat_update(float w, float mq, float vq, const AdamWScalars& p) {
+  const float mh = mq / p.bias_corr1;
+  const float vh = vq / p.bias_corr2;
+  const float ratio = mh / (sqrtf(vh) + p.eps);
+  return -p.lr * __fmaf_rn(p.weight_decay, w, ratio);
+}
+
 // One workgroup per 2048-element tile, 8 consecutive elements per lane: one 8-byte load of weights,
-// three 16-byte loads (gradient, both moments), the same back minus the gradient.
+// three 16-byte loads (gradient, both moments), the same back minus the gradient.  Elements are worked
+// on in pairs so that every bf16 rounding is half a packed hardware convert and the moments leave in
+// their storage layout; the 8-bit rounding of the stochastic variants uses the hardware SR converts.  A
+// NaN anywhere in the wave's sums sends the wave through qat_one instead (canonical NaNs).
 template <int FMT, int VAR, int W>
 __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, const uint16_t* __restrict__ g16,
                                                       uint16_t* __restrict__ m16, uint16_t* __restrict__ v16,
@@ -72,21 +109,63 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
   }
   const Addends a8 = make_addends<FMT, VAR>(nbits);
   const Addends a16 = make_addends<kBF16, kRNE>(0);
+  HwAddends hw = {0, 0, 0, 0};
+  if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
   const float omb1 = 1.0f - p.beta1, omb2 = 1.0f - p.beta2;
   uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if constexpr (VAR != kRNE) read_wg_bits8<W>(strip, e0, a8.nbits, n);
   const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w}, mw[4] = {mq.x, mq.y, mq.z, mq.w}, vw[4] = {vq.x, vq.y, vq.z, vq.w};
-  uint32_t mo[4] = {0, 0, 0, 0}, vo[4] = {0, 0, 0, 0};
+  const int wlo = (int)(uint32_t)wq, whi = (int)(uint32_t)(wq >> 32);
+  uint32_t mo[4], vo[4], so[4];
+  bool nan_seen = false;
+  auto do_pair = [&](auto hc) {   // elements 2h (low halves) and 2h + 1 (high halves)
+    constexpr int h = decltype(hc)::value;
+    const float wa = w8_value<FMT, 2 * h>(wlo, whi), wb = w8_value<FMT, 2 * h + 1>(wlo, whi);
+    const float ga = bf16_lo(gw[h]), gb = bf16_hi(gw[h]);
+    const float m1a = __fmaf_rn(p.beta1, bf16_lo(mw[h]), omb1 * ga), m1b = __fmaf_rn(p.beta1, bf16_hi(mw[h]), omb1 * gb);
+    const float v1a = __fmaf_rn(p.beta2, bf16_lo(vw[h]), omb2 * (ga * ga)), v1b = __fmaf_rn(p.beta2, bf16_hi(vw[h]), omb2 * (gb * gb));
+    mo[h] = bf16_pair_hw(m1a, m1b);
+    vo[h] = bf16_pair_hw(v1a, v1b);
+    const uint32_t uo = bf16_pair_hw(qat_update(wa, bf16_lo(mo[h]), bf16_lo(vo[h]), p), qat_update(wb, bf16_hi(mo[h]), bf16_hi(vo[h]), p));
+    const float sa = wa + bf16_lo(uo), sb = wb + bf16_hi(uo);
+    nan_seen = nan_seen || __builtin_isunordered(sa, sb);   // a NaN moment or update always reaches the sum
+    so[h] = bf16_pair_hw(sa, sb);
+  };
+  do_pair(std::integral_constant<int, 0>{});
+  do_pair(std::integral_constant<int, 1>{});
+  do_pair(std::integral_constant<int, 2>{});
+  do_pair(std::integral_constant<int, 3>{});
   uint64_t wo = 0;
+  if (__any(nan_seen)) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int sh = 16 * (j & 1);
-    const QatOut o = qat_one<FMT, VAR>((uint32_t)(wq >> (8 * j)) & 0xFFu, (gw[j >> 1] >> sh) & 0xFFFFu,
-                                       (mw[j >> 1] >> sh) & 0xFFFFu, (vw[j >> 1] >> sh) & 0xFFFFu, n[j], p, omb1, omb2,
-                                       a8, a16);
-    mo[j >> 1] |= o.m16 << sh;
-    vo[j >> 1] |= o.v16 << sh;
-    wo |= (uint64_t)o.w8 << (8 * j);
+    for (int h = 0; h < 4; ++h) {
+      mo[h] = 0;
+      vo[h] = 0;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int sh = 16 * (j & 1);
+      const QatOut o = qat_one<FMT, VAR>((uint32_t)(wq >> (8 * j)) & 0xFFu, (gw[j >> 1] >> sh) & 0xFFFFu,
+                                         (mw[j >> 1] >> sh) & 0xFFFFu, (vw[j >> 1] >> sh) & 0xFFFFu, n[j], p, omb1, omb2,
+                                         a8, a16);
+      mo[j >> 1] |= o.m16 << sh;
+      vo[j >> 1] |= o.v16 << sh;
+      wo |= (uint64_t)o.w8 << (8 * j);
+    }
+  } else {
+    uint32_t packed[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const uint32_t b4[4] = {so[2 * q] << 16, so[2 * q] & 0xFFFF0000u, so[2 * q + 1] << 16, so[2 * q + 1] & 0xFFFF0000u};
+      if constexpr (VAR != kRNE) {
+        const uint32_t n4[4] = {n[4 * q], n[4 * q + 1], n[4 * q + 2], n[4 * q + 3]};
+        packed[q] = round4_fp8_hw<FMT, VAR>(b4, n4, hw);
+      } else {
+        packed[q] = pack4_fp8<FMT>(round_pattern<FMT, kRNE, false>(b4[0], 0u, a8), round_pattern<FMT, kRNE, false>(b4[1], 0u, a8),
+                                   round_pattern<FMT, kRNE, false>(b4[2], 0u, a8), round_pattern<FMT, kRNE, false>(b4[3], 0u, a8));
+      }
+    }
+    wo = (uint64_t)packed[0] | ((uint64_t)packed[1] << 32);
   }
   *reinterpret_cast<uint64_t*>(w8 + g0) = wo;
   u32x4 t;

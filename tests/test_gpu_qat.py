@@ -72,6 +72,34 @@ def test_single_step(fbsr, oracle, fmt):
                     assert np.array_equal(host(gd), g), "gradient buffer was written"
 
 
+@pytest.mark.parametrize("fmt", [E4M3, E5M2])
+def test_extreme_finite_values_without_nan(fbsr, oracle, fmt):
+    """Raw bit patterns for the gradient and both moments -- zeros, subnormals, magnitudes up to 2^73, squares that
+    overflow to infinity -- but no input that can produce a NaN, so that every wave stays on the kernel's main path
+    (hardware bf16 and fp8 converts); a wave that meets a NaN takes another path, covered by test_single_step."""
+    n = 64 * 2048 + 77
+    rng = np.random.default_rng(41 + fmt)
+    finite8 = np.array([c for c in range(256) if np.isfinite(oracle.decode(c, fmt))], dtype=np.uint8)
+    w8 = finite8[rng.integers(0, finite8.size, n)]
+
+    def raw(signed):
+        field = rng.integers(0, 201, n).astype(np.uint16)
+        code = (field << 7) | rng.integers(0, 128, n).astype(np.uint16)
+        return code | (rng.integers(0, 2, n).astype(np.uint16) << 15) if signed else code
+    g, m, v = raw(True), raw(True), raw(False)
+    for params in PARAMS:
+        for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 2), (SRC, 4), (SRC, 16)):
+            print("case fmt=%d lr=%g variant=%d nbits=%d" % (fmt, params[0], variant, nbits), flush=True)
+            wd, gd, md, vd = dev(w8), dev(g), dev(m), dev(v)
+            fbsr.fbsr_qat_adamw_step(wd, gd, md, vd, fmt, params, variant, nbits, seed=19, step=4, offset=0)
+            ww, mm, vv = _oracle_step(oracle, w8, g, m, v, fmt, params, variant, nbits, 19, 4, 0)
+            assert np.all((mm & 0x7FFF) <= 0x7F80) and np.all((vv & 0x7FFF) <= 0x7F80), "the recipe produced a NaN moment"
+            assert not np.isnan([oracle.decode(int(c), fmt) for c in np.unique(ww)]).any(), "the recipe produced a NaN weight"
+            assert first_mismatch(host(md), mm) is None, "first moment"
+            assert first_mismatch(host(vd), vv) is None, "second moment"
+            assert first_mismatch(host(wd), ww) is None, "weights"
+
+
 def test_unaligned_buffers(fbsr, oracle):
     n = 3 * 2048 + 50
     w8, g, m, v = _state(n + 8, 9)
