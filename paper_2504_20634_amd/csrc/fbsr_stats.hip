@@ -154,76 +154,77 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
     // wave-uniform: |x| > M or NaN anywhere in the wave sends it down the checked integer rounding and
     // the fp64 difference; otherwise the unchecked rounding (hardware converts for fp8) applies
     const bool wide_path = __any(umax > F::U_MAXFIN);
-#pragma unroll
-    for (int k = 0; k < kRows; ++k) {
-      uint64_t rb = 0;
-      if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip[it & 1], wave, lane, k);
-      const uint32_t n4[4] = {VAR == kRNE ? 0u : slot_bits<W>(rb, 0, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 1, a.nbits),
-                              VAR == kRNE ? 0u : slot_bits<W>(rb, 2, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 3, a.nbits)};
-      uint32_t r[4];
-      uint32_t packed = 0;
-      bool have_packed = false;
-      if (wide_path) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, true>(b[k][j], n4[j], a);
-      } else {
-        if constexpr (F::kIsFp8 && VAR != kRNE) {
-          packed = round4_fp8_hw<FMT, VAR>(b[k], n4, hw);
-          have_packed = true;
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, false>(b[k][j], n4[j], a);
-        }
-      }
-      const uint64_t row = row0 + (uint64_t)(k * 64);
-      if constexpr (F::kIsFp8) {
-        if (!have_packed) packed = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
-        if (wide_path) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) y[k][j] = decode_top<FMT>(r[j]);   // keeps this library's NaN / sign conventions
-        } else {
-          decode4<FMT>(packed, y[k]);
-        }
-        if (out != nullptr) reinterpret_cast<uint32_t*>(out)[row] = packed;
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) y[k][j] = __uint_as_float(r[j] & 0xFFFF0000u);
-        if (out != nullptr)
-          reinterpret_cast<uint64_t*>(out)[row] = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
-      }
-    }
-
-    // adds the elements whose tile-relative index lies in [lo, hi) to `cur`; ALL = the whole tile
-    auto add_range = [&](auto all_tag, int lo, int hi) {
-      constexpr bool ALL = decltype(all_tag)::value;
-      const int w_lo = wave * kWaveElems;
-#pragma unroll
-      for (int k = 0; k < kRows; ++k)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int e = w_lo + k * 256 + 4 * lane + j;
-          const bool in = ALL || (e >= lo && e < hi);
-          if (wide_path) {
-            if (in) accumulate<FMT, true>(cur, b[k][j], y[k][j]);
-          } else if (ALL) {
-            accumulate<FMT, false>(cur, b[k][j], y[k][j]);
-          } else {
-            // outside the range: contribute y = 0 and x = 0, whose terms are exact zeros
-            accumulate<FMT, false>(cur, in ? b[k][j] : 0u, in ? y[k][j] : 0.0f);
-          }
-        }
-    };
-
     const uint64_t t_lo = (uint64_t)it * T::ELEMS, t_hi = t_lo + T::ELEMS;   // chunk-relative range of this tile
-    if (next_bin >= t_hi) {
-      add_range(std::true_type{}, 0, T::ELEMS);
-    } else {                       // a bin ends inside this tile (at most once: group >= tile)
-      const int cut = (int)(next_bin - t_lo);
-      add_range(std::false_type{}, 0, cut);
-      flush();
-      add_range(std::false_type{}, cut, T::ELEMS);
-      next_bin += group;
-    }
+
+    // the rest of the tile, instantiated once per flavour so that each is straight-line code
+    auto finish_tile = [&](auto wide_tag) {
+      constexpr bool WIDE = decltype(wide_tag)::value;
+#pragma unroll
+      for (int k = 0; k < kRows; ++k) {
+        uint64_t rb = 0;
+        if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip[it & 1], wave, lane, k);
+        const uint32_t n4[4] = {VAR == kRNE ? 0u : slot_bits<W>(rb, 0, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 1, a.nbits),
+                                VAR == kRNE ? 0u : slot_bits<W>(rb, 2, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 3, a.nbits)};
+        constexpr bool HW = !WIDE && F::kIsFp8 && VAR != kRNE;
+        uint32_t r[4] = {0, 0, 0, 0};
+        uint32_t packed = 0;
+        if constexpr (HW) {
+          packed = round4_fp8_hw<FMT, VAR>(b[k], n4, hw);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, WIDE>(b[k][j], n4[j], a);
+        }
+        const uint64_t row = row0 + (uint64_t)(k * 64);
+        if constexpr (F::kIsFp8) {
+          if constexpr (!HW) packed = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
+          if constexpr (WIDE) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) y[k][j] = decode_top<FMT>(r[j]);   // keeps this library's NaN / sign conventions
+          } else {
+            decode4<FMT>(packed, y[k]);
+          }
+          if (out != nullptr) reinterpret_cast<uint32_t*>(out)[row] = packed;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) y[k][j] = __uint_as_float(r[j] & 0xFFFF0000u);
+          if (out != nullptr)
+            reinterpret_cast<uint64_t*>(out)[row] = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
+        }
+      }
+
+      // adds the elements whose tile-relative index lies in [lo, hi) to `cur`; ALL = the whole tile
+      auto add_range = [&](auto all_tag, int lo, int hi) {
+        constexpr bool ALL = decltype(all_tag)::value;
+        const int w_lo = wave * kWaveElems;
+#pragma unroll
+        for (int k = 0; k < kRows; ++k)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int e = w_lo + k * 256 + 4 * lane + j;
+            const bool in = ALL || (e >= lo && e < hi);
+            if constexpr (ALL) {
+              accumulate<FMT, WIDE>(cur, b[k][j], y[k][j]);
+            } else if constexpr (WIDE) {
+              if (in) accumulate<FMT, true>(cur, b[k][j], y[k][j]);
+            } else {
+              // outside the range: contribute y = 0 and x = 0, whose terms are exact zeros
+              accumulate<FMT, false>(cur, in ? b[k][j] : 0u, in ? y[k][j] : 0.0f);
+            }
+          }
+      };
+
+      if (next_bin >= t_hi) {
+        add_range(std::true_type{}, 0, T::ELEMS);
+      } else {                       // a bin ends inside this tile (at most once: group >= tile)
+        const int cut = (int)(next_bin - t_lo);
+        add_range(std::false_type{}, 0, cut);
+        flush();
+        add_range(std::false_type{}, cut, T::ELEMS);
+        next_bin += group;
+      }
+    };
+    if (wide_path) finish_tile(std::true_type{});
+    else finish_tile(std::false_type{});
   }
   flush();
 }
