@@ -390,6 +390,25 @@ uint16_t to_bf16_rne(float x) {
   return (uint16_t)round_one(x, f, VAR_RNE, 0, 0);
 }
 
+// The 16-bit part of one step for one element: updates both moments in place and returns the bf16
+// sum w16 + u16 that is handed to RoundTo8 (as a float).
+float adamw_sum16(float w, uint16_t g16, uint16_t* m16, uint16_t* v16, const AdamW& a) {
+  const float omb1 = 1.0f - a.beta1, omb2 = 1.0f - a.beta2;
+  const float g = bf16_to_float(g16);
+  const float m0 = bf16_to_float(*m16), v0 = bf16_to_float(*v16);
+  const float m1 = std::fmaf(a.beta1, m0, omb1 * g);
+  const float v1 = std::fmaf(a.beta2, v0, omb2 * (g * g));
+  const uint16_t mq = to_bf16_rne(m1), vq = to_bf16_rne(v1);
+  *m16 = mq;
+  *v16 = vq;
+  const float mh = bf16_to_float(mq) / a.bias_corr1;
+  const float vh = bf16_to_float(vq) / a.bias_corr2;
+  const float ratio = mh / (std::sqrt(vh) + a.eps);
+  const float u = -a.lr * std::fmaf(a.weight_decay, w, ratio);
+  const float u16 = bf16_to_float(to_bf16_rne(u));
+  return bf16_to_float(to_bf16_rne(w + u16));   // the F16 sum handed to RoundTo8
+}
+
 }  // namespace
 
 extern "C" {
@@ -567,28 +586,40 @@ int oracle_qat_adamw_step(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint1
   Format f;
   if (!args_ok(fmt, variant, nbits, &f) || (fmt != FMT_E4M3 && fmt != FMT_E5M2)) return 1;
   const AdamW a = {p[0], p[1], p[2], p[3], p[4], p[5], p[6]};
-  const float omb1 = 1.0f - a.beta1, omb2 = 1.0f - a.beta2;
   for (uint64_t j = 0; j < n; ++j) {
     const float w = (float)decode(w8[j], f);            // w16 <- w8 (exact)
-    const float g = bf16_to_float(g16[j]);
-    const float m0 = bf16_to_float(m16[j]), v0 = bf16_to_float(v16[j]);
-    const float m1 = std::fmaf(a.beta1, m0, omb1 * g);
-    const float v1 = std::fmaf(a.beta2, v0, omb2 * (g * g));
-    const uint16_t mq = to_bf16_rne(m1), vq = to_bf16_rne(v1);
-    m16[j] = mq;
-    v16[j] = vq;
-    const float mh = bf16_to_float(mq) / a.bias_corr1;
-    const float vh = bf16_to_float(vq) / a.bias_corr2;
-    const float ratio = mh / (std::sqrt(vh) + a.eps);
-    const float u = -a.lr * std::fmaf(a.weight_decay, w, ratio);
-    const float u16 = bf16_to_float(to_bf16_rne(u));
-    const float s16 = bf16_to_float(to_bf16_rne(w + u16));   // the F16 sum handed to RoundTo8
+    const float s16 = adamw_sum16(w, g16[j], &m16[j], &v16[j], a);
     uint32_t code;
     if (std::isnan(s16)) {
       code = f.nan_code;
     } else {
       const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, step, offset + j, nbits);
       code = round_one(s16, f, variant, nbits, r);
+    }
+    w8[j] = (uint8_t)code;
+  }
+  return 0;
+}
+
+// The same step with the 8-bit weights in a generic format (desc as in oracle_round_format8; Sec. IV
+// trains in P3109 binary8p4) and any of the seven variants.  A weight code that decodes to NaN (or to
+// an unused encoding) enters the arithmetic as NaN.  A NaN sum is stored as the descriptor's NaN code
+// without a sign, or as +M when the format has none.
+int oracle_qat_adamw_step_format8(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,
+                                  const int32_t* desc, const float* p, int variant, int nbits, uint64_t seed,
+                                  uint64_t step, uint64_t offset) {
+  Format8 g;
+  if (!get_format8(desc, &g) || !variant8_ok(variant, nbits)) return 1;
+  const AdamW a = {p[0], p[1], p[2], p[3], p[4], p[5], p[6]};
+  for (uint64_t j = 0; j < n; ++j) {
+    const float w = (float)decode8(w8[j], g);           // w16 <- w8 (exact: at most 7 significant bits)
+    const float s16 = adamw_sum16(w, g16[j], &m16[j], &v16[j], a);
+    uint32_t code;
+    if (std::isnan(s16)) {
+      code = g.nan_code >= 0 ? (uint32_t)g.nan_code : (uint32_t)g.max_code;
+    } else {
+      const uint64_t r = variant_draws(variant) ? random_bits(seed, step, offset + j, nbits) : 0;
+      code = round_one8(s16, g, variant, nbits, r);
     }
     w8[j] = (uint8_t)code;
   }

@@ -68,6 +68,8 @@ def lib():
         L.oracle_widen16.restype = u32
         L.oracle_qat_adamw_step.argtypes = [vp, vp, vp, vp, u64, i32, vp, i32, i32, u64, u64, u64]
         L.oracle_qat_adamw_step.restype = i32
+        L.oracle_qat_adamw_step_format8.argtypes = [vp, vp, vp, vp, u64, vp, vp, i32, i32, u64, u64, u64]
+        L.oracle_qat_adamw_step_format8.restype = i32
         L.oracle_round_block_scaled.argtypes = [vp, vp, vp, u64, i32, i32, i32, u64, u64]
         L.oracle_round_block_scaled.restype = i32
         L.oracle_format8_check.argtypes = [vp]
@@ -227,6 +229,21 @@ def qat_adamw_step(w8, g16, m16, v16, fmt, params, variant, nbits, seed, step, o
                                      nbits, seed, step, offset)
     if rc != 0:
         raise ValueError("oracle_qat_adamw_step: status %d" % rc)
+    return w8, m16, v16
+
+
+def qat_adamw_step_format8(w8, g16, m16, v16, desc, params, variant, nbits, seed, step, offset=0):
+    """qat_adamw_step with the 8-bit weights in a generic format (descriptor as in round_format8)."""
+    w8 = np.array(w8, dtype=np.uint8, copy=True)
+    m16 = np.array(m16, dtype=np.uint16, copy=True)
+    v16 = np.array(v16, dtype=np.uint16, copy=True)
+    g16 = np.ascontiguousarray(g16, dtype=np.uint16)
+    p = np.asarray(params, dtype=np.float32)
+    assert p.size == 7 and w8.size == g16.size == m16.size == v16.size
+    rc = lib().oracle_qat_adamw_step_format8(_ptr(w8), _ptr(g16), _ptr(m16), _ptr(v16), w8.size, _ptr(_desc(desc)), _ptr(p),
+                                             variant, nbits, seed, step, offset)
+    if rc != 0:
+        raise ValueError("oracle_qat_adamw_step_format8: status %d" % rc)
     return w8, m16, v16
 
 

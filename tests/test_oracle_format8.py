@@ -311,3 +311,84 @@ def test_array_call_is_the_per_element_rule(oracle, src):
             # chunked == whole (the bits are a function of the global index)
             part = oracle.round_format8(x[1000:], src, d, variant, nbits, seed, offset + 1000)
             assert np.array_equal(part, got[1000:])
+
+
+# ------------------------------------------------------------------ fused QAT step, generic ----
+def _bf16_codes(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def _bf16_values(c):
+    return (np.asarray(c, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+@pytest.mark.parametrize("fmt,d", [(1, E4M3), (2, E5M2)])
+def test_qat_step_with_ocp_descriptor_equals_the_fixed_path(oracle, fmt, d):
+    """The generic-format step only swaps the 8-bit decode and the 8-bit rounding; with the descriptor of
+    an OCP fp8 format it must reproduce the fixed-format step (pinned against a library AdamW) on every
+    input, NaN codes and wild moments included."""
+    rng = np.random.default_rng(3 + fmt)
+    n = 6000
+    w8 = rng.integers(0, 256, n).astype(np.uint8)
+    g16 = _bf16_codes(rng.standard_normal(n) * 0.3)
+    m16 = _bf16_codes(rng.standard_normal(n) * 0.05)
+    v16 = _bf16_codes(rng.random(n) * 0.02)
+    k = n // 4
+    g16[:k] = rng.integers(0, 1 << 16, k)
+    m16[k:2 * k] = rng.integers(0, 1 << 16, k)
+    v16[2 * k:3 * k] = rng.integers(0, 1 << 16, k)
+    for params in ((1e-3, 0.9, 0.999, 1e-8, 0.01, 0.1, 0.001), (0.5, 0.0, 0.5, 1e-3, 0.0, 1.0, 0.5)):
+        for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 3), (SRC, 4)):
+            a = oracle.qat_adamw_step(w8, g16, m16, v16, fmt, params, variant, nbits, seed=7, step=5, offset=9)
+            b = oracle.qat_adamw_step_format8(w8, g16, m16, v16, d, params, variant, nbits, seed=7, step=5, offset=9)
+            for x, y in zip(a, b):
+                assert np.array_equal(x, y)
+
+
+def test_qat_step_structure_in_binary8p4(oracle):
+    """Sec. IV's configuration (binary8p4 weights, bf16 updates).  lr = 0 leaves every finite weight where
+    it is; the stored weight is the generic narrow-source rounding of the bf16 sum, recomputed here in
+    numpy fp32, with the bits of (seed, step, index); a NaN sum is stored as 0x80; the format's missing
+    negative zero shows when a small negative weight is pulled to zero."""
+    d = BINARY8P4
+    rng = np.random.default_rng(4)
+    n = 3000
+    w8 = rng.integers(0, 256, n).astype(np.uint8)
+    w8[w8 == 0x80] = 0x00                      # NaN
+    w8[(w8 & 0x7F) == 0x7F] ^= 0x01            # infinities -> the largest finite value
+    g16 = _bf16_codes(rng.standard_normal(n))
+    m16 = _bf16_codes(rng.standard_normal(n) * 0.1)
+    v16 = _bf16_codes(rng.random(n) * 0.1)
+    for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 3), (SRC, 3), (SRC_ODD, 3), (TNO, 0), (TA, 0)):
+        same, _, _ = oracle.qat_adamw_step_format8(w8, g16, m16, v16, d, (0.0, 0.9, 0.999, 1e-8, 0.01, 0.1, 0.001), variant, nbits, 1, 4)
+        assert np.array_equal(same, w8)
+    w = np.array([oracle.decode_format8(int(c), d) for c in w8], dtype=np.float32)
+    for variant, nbits in ((SRF, 3), (SRC_ODD, 3), (TA, 0)):
+        seed, step, off = 11, 6, 40
+        lr, b1, b2, eps, wd, c1, c2 = (np.float32(v) for v in (0.05, 0.9, 0.99, 1e-8, 0.1, 0.3, 0.05))
+        g, m0, v0 = _bf16_values(g16), _bf16_values(m16), _bf16_values(v16)
+        one = np.float32(1.0)
+        fma = lambda a, b, c: (a.astype(np.float64) * b.astype(np.float64) + c.astype(np.float64)).astype(np.float32)
+        m1 = fma(np.full(n, b1), m0, (one - b1) * g)
+        v1 = fma(np.full(n, b2), v0, (one - b2) * (g * g))
+        mq, vq = _bf16_values(_bf16_codes(m1)), _bf16_values(_bf16_codes(v1))
+        ratio = (mq / c1) / (np.sqrt(vq / c2) + eps)
+        u = -lr * fma(np.full(n, wd), w, ratio)
+        s16 = _bf16_values(_bf16_codes(w + _bf16_values(_bf16_codes(u))))
+        got, _, _ = oracle.qat_adamw_step_format8(w8, g16, m16, v16, d, (lr, b1, b2, eps, wd, c1, c2), variant, nbits, seed, step, off)
+        want = np.array([oracle.round_format8_with_n(x, d, variant, nbits, oracle.random_bits(seed, step, off + j, nbits) if variant in DRAWING else 0)
+                         for j, x in enumerate(s16)], dtype=np.uint8)
+        assert np.array_equal(got, want)
+    # specials: a NaN weight or gradient gives the NaN code; a huge update reaches the infinity code
+    w_nan = np.array([0x80, 0x40, 0x40, 0x89], dtype=np.uint8)
+    g_sp = np.array([0x3F80, 0x7FC0, 0x3F80, 0xBF80], dtype=np.uint16)       # 1.0, NaN, 1.0, -1.0
+    z = np.zeros(4, np.uint16)
+    out, _, _ = oracle.qat_adamw_step_format8(w_nan, g_sp, z, z, d, (1e30, 0.9, 0.999, 1e-8, 0.0, 0.1, 0.001), RNE, 0, 0, 1)
+    assert list(out) == [0x80, 0x80, 0xFF, 0x7F]
+    # the smallest negative subnormal (0x81 = -2^-10) pulled three quarters of the way to zero by weight decay alone:
+    # the sum -2^-12 rounds to a zero that keeps its sign only where the format has a negative zero
+    out, _, _ = oracle.qat_adamw_step_format8(np.array([0x81], np.uint8), z[:1], z[:1], z[:1], d, (0.75, 0.9, 0.999, 1e-8, 1.0, 0.1, 0.001), RNE, 0, 0, 1)
+    assert list(out) == [0x00]
+    out, _, _ = oracle.qat_adamw_step_format8(np.array([0x81], np.uint8), z[:1], z[:1], z[:1], E4M3, (0.75, 0.9, 0.999, 1e-8, 1.0, 0.1, 0.001), RNE, 0, 0, 1)
+    assert list(out) == [0x80]

@@ -17,7 +17,8 @@ WATCHERS = {'srf_half_term_dropped': 'exhaustive_round_up_counts and 2-0', 'srff
             'tno_is_tne': 'deterministic_modes', 'ta_is_strict': 'deterministic_modes',
             'src_odd_parity': 'ties_to_odd', 'generic_overflow_tie_parity': 'overflow_and_specials',
             'generic_negative_zero_kept': 'overflow_and_specials', 'generic_subnormal_scale': 'published_value_sets',
-            'generic_nan_sign_dropped': 'overflow_and_specials'}
+            'generic_nan_sign_dropped': 'overflow_and_specials',
+            'qat8_step_not_in_key': 'qat_step_structure_in_binary8p4', 'qat8_nan_becomes_max': 'qat_step_structure_in_binary8p4'}
 
 MUTATIONS = [
     ("srf_half_term_dropped", "std::ldexp((double)(2 * n + 1), -(N + 1))", "std::ldexp((double)(2 * n), -(N + 1))"),
@@ -47,6 +48,8 @@ MUTATIONS = [
     ("generic_overflow_tie_parity", "std::fmod(f.M / ulp_M, 2.0) == 1.0", "std::fmod(f.M / ulp_M, 2.0) == 0.0"),
     ("generic_negative_zero_kept", "if (mag == 0 && !g.neg_zero) return 0u;", ""),
     ("generic_subnormal_scale", "std::ldexp(1.0, 1 - f.B);      // Eq. (1)", "std::ldexp(1.0, -f.B);      // Eq. (1)"),
+    ("qat8_step_not_in_key", "random_bits(seed, step, offset + j, nbits) : 0;\n      code = round_one8", "random_bits(seed, 0, offset + j, nbits) : 0;\n      code = round_one8"),
+    ("qat8_nan_becomes_max", "code = g.nan_code >= 0 ? (uint32_t)g.nan_code : (uint32_t)g.max_code;", "code = (uint32_t)g.max_code;"),
     ("generic_nan_sign_dropped", "(uint32_t)g.nan_code | (g.nan_signed ? sign_code : 0u)", "(uint32_t)g.nan_code"),
 ]
 
