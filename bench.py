@@ -221,6 +221,19 @@ def main():
             ms = timed_launches(torch, lambda: qat(v), 12)
             paths["qat_adamw_e4m3_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
                 "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
+        # the same step with the weights in P3109 binary8p4 (the format Sec. IV trains in), decoded through a table
+        p4q = fbsr.format8_named("p3109_binary8p4")
+
+        def qat8(v):
+            tq[0] += 1
+            w8_, g_, m_, v_ = qs[tq[0] % 3]
+            t = 1 + tq[0] // 3
+            fbsr.fbsr_qat_adamw_step_format8(w8_, g_, m_, v_, p4q, (1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9 ** t, 1 - 0.999 ** t),
+                                             v, 3, seed=6, step=t)
+        for v in (fbsr.SRC, fbsr.SRFF):
+            ms = timed_launches(torch, lambda: qat8(v), 12)
+            paths["qat_adamw_binary8p4_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
+                "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
         del qs
         ns = min(SGD_ELEMS, n)
         # rotate through 3 weight and 3 gradient buffers (2.25 GiB) so the last-level cache cannot help

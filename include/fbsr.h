@@ -222,6 +222,17 @@ int fbsr_format8_check(const fbsr_format8* fmt);
 int fbsr_round_format8(const void* x, int src, void* out, uint64_t n, const fbsr_format8* fmt, int variant,
                        int nbits, uint64_t seed, uint64_t offset, void* stream);
 
+/* fbsr_qat_adamw_step with the 8-bit weights in a generic format (Sec. IV trains in P3109 binary8p4 with bf16
+ * updates and 3 random bits) and any variant FBSR_RNE .. FBSR_RNA.  The arithmetic is that of
+ * fbsr_qat_adamw_step; a weight byte is decoded by Eq. (1) under the descriptor (bits above K ignored; the NaN
+ * code and encodings the format leaves unused enter as NaN, the infinity codes as infinities), and
+ * w8 <- FBSR_fmt(s) as in fbsr_round_format8.  A NaN sum is stored as the descriptor's NaN code without a
+ * sign, or as +M in a format without NaN.  With an OCP fp8 descriptor the results equal fbsr_qat_adamw_step's.
+ * fmt and p are HOST pointers, read during the call.  Errors as fbsr_qat_adamw_step / fbsr_round_format8. */
+int fbsr_qat_adamw_step_format8(void* w8, const void* g16, void* m16, void* v16, uint64_t n, const fbsr_format8* fmt,
+                                const fbsr_adamw* p, int variant, int nbits, uint64_t seed, uint64_t step,
+                                uint64_t offset, void* stream);
+
 /* Static description of a status code. */
 const char* fbsr_strerror(int status);
 

@@ -19,7 +19,7 @@ OK, EINVAL, EALIGN, ERANGE, EDEVICE = 0, 1, 2, 3, 4
 MAX_NBITS = 16
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
-EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_format8_named", "fbsr_format8_check", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
+EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
            "fbsr_strerror", "fbsr_version")
 
 
@@ -62,6 +62,8 @@ def lib():
         L.fbsr_format8_check.restype = i32
         L.fbsr_round_format8.argtypes = [vp, i32, vp, u64, vp, i32, i32, u64, u64, vp]
         L.fbsr_round_format8.restype = i32
+        L.fbsr_qat_adamw_step_format8.argtypes = [vp, vp, vp, vp, u64, vp, vp, i32, i32, u64, u64, u64, vp]
+        L.fbsr_qat_adamw_step_format8.restype = i32
         L.fbsr_strerror.argtypes = [i32]
         L.fbsr_strerror.restype = ctypes.c_char_p
         L.fbsr_version.argtypes = []
@@ -201,6 +203,22 @@ def fbsr_qat_adamw_step(w8, g16, m16, v16, fmt, params, variant, nbits, seed, st
     _check(lib().fbsr_qat_adamw_step(w8.data_ptr(), g16.data_ptr(), m16.data_ptr(), v16.data_ptr(), n, fmt,
                                      ctypes.byref(p), variant, nbits, seed, step, offset, _stream_handle(stream)),
            "fbsr_qat_adamw_step")
+    return w8, m16, v16
+
+
+def fbsr_qat_adamw_step_format8(w8, g16, m16, v16, fmt, params, variant, nbits, seed, step, offset=0, stream=None):
+    """fbsr_qat_adamw_step with the 8-bit weights in a generic format (a Format8 or an 8-tuple)."""
+    import torch
+    for t in (w8, g16, m16, v16):
+        assert t.is_cuda and t.is_contiguous()
+    assert w8.dtype == torch.uint8 and g16.element_size() == m16.element_size() == v16.element_size() == 2
+    n = w8.numel()
+    assert g16.numel() == m16.numel() == v16.numel() == n
+    p = AdamW(*[float(x) for x in params])
+    f = _format8(fmt)
+    _check(lib().fbsr_qat_adamw_step_format8(w8.data_ptr(), g16.data_ptr(), m16.data_ptr(), v16.data_ptr(), n, ctypes.byref(f),
+                                             ctypes.byref(p), variant, nbits, seed, step, offset, _stream_handle(stream)),
+           "fbsr_qat_adamw_step_format8")
     return w8, m16, v16
 
 

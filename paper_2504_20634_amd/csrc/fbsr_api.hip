@@ -61,6 +61,29 @@ bool derive_format8(const fbsr_format8& d, fbsr::Fmt8* f) {
   return true;
 }
 
+// Value of every byte taken as a code of the (checked) format: Eq. (1), with the descriptor's specials.
+void decode_table8(const fbsr_format8& d, fbsr::Table8* t) {
+  const int K = d.width, P = d.precision, B = d.bias;
+  const int sign_bit = 1 << (K - 1), mag_top = sign_bit - 1;
+  for (int byte = 0; byte < 256; ++byte) {
+    const int code = byte & (2 * mag_top + 1);   // bits above K are ignored
+    const int mag = code & mag_top;
+    const bool negative = (code & sign_bit) != 0;
+    float v;
+    if (d.nan_code != -1 && (d.nan_signed != 0 ? mag == d.nan_code : code == d.nan_code)) {
+      v = NAN;
+    } else if (d.inf_code != -1 && mag == d.inf_code) {
+      v = INFINITY;
+    } else if (mag > d.max_code || (mag == 0 && negative && d.neg_zero == 0)) {
+      v = NAN;   // an encoding the format leaves unused
+    } else {
+      const int e = mag >> (P - 1), frac = mag & ((1 << (P - 1)) - 1);
+      v = e == 0 ? ldexpf((float)frac, 2 - P - B) : ldexpf((float)(frac + (1 << (P - 1))), e - B - (P - 1));
+    }
+    t->v[byte] = negative ? -v : v;
+  }
+}
+
 // The addend constants of a rounding mode in a code space with 24 fraction bits.
 bool derive_mode8(int variant, int nbits, fbsr::Mode8* m) {
   const bool draws = variant == FBSR_SRFF || variant == FBSR_SRF || variant == FBSR_SRC || variant == FBSR_SRC_TIES_ODD;
@@ -199,6 +222,26 @@ int fbsr_round_format8(const void* x, int src, void* out, uint64_t n, const fbsr
   if (misaligned(x, src == FBSR_FROM_FP32 ? 4 : 2)) return FBSR_EALIGN;
   const hipError_t e = fbsr::launch_round_format8(x, src, reinterpret_cast<uint8_t*>(out), n, f, m, seed, offset,
                                                   reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
+int fbsr_qat_adamw_step_format8(void* w8, const void* g16, void* m16, void* v16, uint64_t n, const fbsr_format8* fmt,
+                                const fbsr_adamw* p, int variant, int nbits, uint64_t seed, uint64_t step, uint64_t offset,
+                                void* stream) {
+  fbsr::Fmt8 f;
+  fbsr::Mode8 m;
+  if (fmt == nullptr || !derive_format8(*fmt, &f) || !derive_mode8(variant, nbits, &m)) return FBSR_EINVAL;
+  if (n > fbsr::kMaxElems || offset > UINT64_MAX - n) return FBSR_EINVAL;
+  if (p == nullptr) return FBSR_EINVAL;
+  if (n == 0) return FBSR_OK;
+  if (w8 == nullptr || g16 == nullptr || m16 == nullptr || v16 == nullptr) return FBSR_EINVAL;
+  if (misaligned(g16, 2) || misaligned(m16, 2) || misaligned(v16, 2)) return FBSR_EALIGN;
+  fbsr::Table8 t;
+  decode_table8(*fmt, &t);
+  const fbsr::AdamWScalars sc = {p->lr, p->beta1, p->beta2, p->eps, p->weight_decay, p->bias_corr1, p->bias_corr2};
+  const hipError_t e = fbsr::launch_qat_adamw_format8(reinterpret_cast<uint8_t*>(w8), reinterpret_cast<const uint16_t*>(g16),
+                                                      reinterpret_cast<uint16_t*>(m16), reinterpret_cast<uint16_t*>(v16), n, f,
+                                                      m, t, sc, seed, step, offset, reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 

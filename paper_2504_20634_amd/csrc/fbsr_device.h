@@ -386,6 +386,12 @@ struct Fmt8 {
   uint32_t unit_lsb;    // 1 << 24 when P = 1 (the significand's last place is the implicit one), else 0
 };
 
+// The value of every byte as a code of the format (Eq. (1); infinities, and NaN for the NaN code and for
+// encodings the format leaves unused), computed on the host.
+struct Table8 {
+  float v[256];
+};
+
 struct Mode8 {
   uint32_t nbits;       // N; 0 for the deterministic modes
   uint32_t shift;       // 24 - N

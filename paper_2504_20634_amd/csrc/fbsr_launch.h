@@ -76,6 +76,10 @@ struct AdamWScalars {
   float lr, beta1, beta2, eps, weight_decay, bias_corr1, bias_corr2;
 };
 
+hipError_t launch_qat_adamw_format8(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,
+                                    const Fmt8& f, const Mode8& m, const Table8& t, const AdamWScalars& p, uint64_t seed,
+                                    uint64_t step, uint64_t offset, hipStream_t stream);
+
 hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, int fmt,
                             const AdamWScalars& p, int variant, int nbits, uint64_t seed, uint64_t step,
                             uint64_t offset, hipStream_t stream);

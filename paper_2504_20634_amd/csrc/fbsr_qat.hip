@@ -1,54 +1,24 @@
-// fbsr_qat.hip -- kernels behind fbsr_qat_adamw_step: one fused step of Alg. 1
-// (w16 <- w8; AdamW update in bf16; w8 <- RoundTo8(w16 + u16) with few-bit stochastic rounding).
-// Per element 7 bytes are read (w8, g, m, v) and 5 written (w8, m, v); the arithmetic is a fixed
-// sequence of single IEEE fp32 operations (this file is compiled without contraction; the divisions
-// and the square root are the correctly rounded ones) so that it can be reproduced bit for bit.
+// fbsr_qat.hip -- kernels behind fbsr_qat_adamw_step and fbsr_qat_adamw_step_format8: one fused step
+// of Alg. 1 (w16 <- w8; AdamW update in bf16; w8 <- RoundTo8(w16 + u16) with few-bit stochastic
+// rounding).  Per element 7 bytes are read (w8, g, m, v) and 5 written (w8, m, v); the arithmetic is a
+// fixed sequence of single IEEE fp32 operations (this file is compiled without contraction; the
+// divisions and the square root are the correctly rounded ones) so that it can be reproduced bit for bit.
+//
+// The 8-bit format enters through a codec: how a weight code becomes a value and how the bf16 sum is
+// rounded back.  FixedCodec is OCP E4M3 / E5M2 with the hardware decode and the hardware SR converts;
+// Codec8 is any (K, P, B; M) with K <= 8 (Sec. II), decoded through a 256-entry table in LDS and rounded
+// by the code-space addition of round8.
 #include <type_traits>
 
 #include "fbsr_launch.h"
 
 namespace fbsr {
 
-
-// Exact value of an fp8 code (Eq. (1)); the hardware decode agrees with it on all 256 codes.
-template <int FMT>
-__device__ __forceinline__ float fp8_value(uint32_t code) {
-  if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
-  else return __builtin_amdgcn_cvt_f32_bf8((int)code, 0);
-}
-
 // bf16 code of x rounded to nearest even; any NaN becomes the positive canonical NaN.
 __device__ __forceinline__ uint32_t bf16_rne(float x, const Addends& a16) {
   const uint32_t bits = __float_as_uint(x);
   const uint32_t r = round_pattern<kBF16, kRNE, true>(bits, 0u, a16) >> 16;
   return (bits & 0x7FFFFFFFu) > 0x7F800000u ? 0x7FC0u : r;
-}
-
-struct QatOut {
-  uint32_t w8, m16, v16;
-};
-
-template <int FMT, int VAR>
-__device__ __forceinline__ QatOut qat_one(uint32_t w8, uint32_t g16, uint32_t m16, uint32_t v16, uint32_t n,
-                                          const AdamWScalars& p, float omb1, float omb2, const Addends& a8,
-                                          const Addends& a16) {
-  const float w = fp8_value<FMT>(w8);
-  const float g = __uint_as_float(g16 << 16);
-  const float m0 = __uint_as_float(m16 << 16), v0 = __uint_as_float(v16 << 16);
-  const float m1 = __fmaf_rn(p.beta1, m0, omb1 * g);
-  const float v1 = __fmaf_rn(p.beta2, v0, omb2 * (g * g));
-  QatOut o;
-  o.m16 = bf16_rne(m1, a16);
-  o.v16 = bf16_rne(v1, a16);
-  const float mh = __uint_as_float(o.m16 << 16) / p.bias_corr1;
-  const float vh = __uint_as_float(o.v16 << 16) / p.bias_corr2;
-  const float ratio = mh / (sqrtf(vh) + p.eps);
-  const float u = -p.lr * __fmaf_rn(p.weight_decay, w, ratio);
-  const float u16 = __uint_as_float(bf16_rne(u, a16) << 16);
-  const uint32_t s16 = bf16_rne(w + u16, a16);
-  const uint32_t r = round_pattern<FMT, VAR, true>(s16 << 16, n, a8) >> Fx<FMT>::FRAC;
-  o.w8 = s16 == 0x7FC0u ? (Fx<FMT>::NAN_FX >> Fx<FMT>::FRAC) : r;
-  return o;
 }
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -67,15 +37,7 @@ __device__ __forceinline__ uint32_t bf16_pair_hw(float a, float b) {
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
 
-// Value of element J (0..7) of eight packed fp8 codes held in two words (hardware decode, byte select J & 3).
-template <int FMT, int J>
-__device__ __forceinline__ float w8_value(int lo, int hi) {
-  const int word = J < 4 ? lo : hi;
-  if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8(word, J & 3);
-  else return __builtin_amdgcn_cvt_f32_bf8(word, J & 3);
-}
-
-// The arithmetic of qat_one up to the bf16 sum s = bf16(w + u), for one element, on values.
+// The AdamW update u (before its rounding to bf16) from the weight and the new bf16 moments.
 __device__ __forceinline__ float qat_update(float w, float mq, float vq, const AdamWScalars& p) {
   const float mh = mq / p.bias_corr1;
   const float vh = vq / p.bias_corr2;
@@ -83,18 +45,118 @@ __device__ __forceinline__ float qat_update(float w, float mq, float vq, const A
   return -p.lr * __fmaf_rn(p.weight_decay, w, ratio);
 }
 
+// ------------------------------------------------------------------------------- codecs ---
+// A codec provides
+//   Args            what the host passes (a kernel argument)
+//   kDraws          the rounding consumes random bits
+//   kTable          the decode needs the 256-entry table staged in LDS
+//   nbits()         N
+//   value<J>(lo,hi) value of element J of eight packed codes (main path)
+//   value_of(code)  value of one code
+//   round4(b, n)    four bf16-valued fp32 patterns, none a NaN -> four packed codes
+//   round1(s16, n)  one bf16 code (a NaN is the canonical positive one) -> code
+template <int FMT, int VAR>
+struct FixedCodec {
+  struct Args {
+    int nbits;
+  };
+  static constexpr bool kDraws = VAR != kRNE;
+  static constexpr bool kTable = false;
+  Addends a8;
+  HwAddends hw;
+  __device__ FixedCodec(const Args& a, const float*) : a8(make_addends<FMT, VAR>(a.nbits)) {
+    hw = HwAddends{0, 0, 0, 0};
+    if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(a.nbits);
+  }
+  __device__ __forceinline__ uint32_t nbits() const { return a8.nbits; }
+  // the hardware decode agrees with Eq. (1) on all 256 codes
+  template <int J>
+  __device__ __forceinline__ float value(int lo, int hi) const {
+    const int word = J < 4 ? lo : hi;
+    if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8(word, J & 3);
+    else return __builtin_amdgcn_cvt_f32_bf8(word, J & 3);
+  }
+  __device__ __forceinline__ float value_of(uint32_t code) const {
+    if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
+    else return __builtin_amdgcn_cvt_f32_bf8((int)code, 0);
+  }
+  __device__ __forceinline__ uint32_t round4(const uint32_t (&b)[4], const uint32_t (&n)[4]) const {
+    if constexpr (VAR != kRNE) {
+      return round4_fp8_hw<FMT, VAR>(b, n, hw);
+    } else {
+      return pack4_fp8<FMT>(round_pattern<FMT, kRNE, false>(b[0], 0u, a8), round_pattern<FMT, kRNE, false>(b[1], 0u, a8),
+                            round_pattern<FMT, kRNE, false>(b[2], 0u, a8), round_pattern<FMT, kRNE, false>(b[3], 0u, a8));
+    }
+  }
+  __device__ __forceinline__ uint32_t round1(uint32_t s16, uint32_t n) const {
+    const uint32_t r = round_pattern<FMT, VAR, true>(s16 << 16, n, a8) >> Fx<FMT>::FRAC;
+    return s16 == 0x7FC0u ? (Fx<FMT>::NAN_FX >> Fx<FMT>::FRAC) : r;
+  }
+};
+
+template <bool TIES, bool DRAWS>
+struct Codec8 {
+  struct Args {
+    Fmt8 f;
+    Mode8 m;
+    Table8 t;
+  };
+  static constexpr bool kDraws = DRAWS;
+  static constexpr bool kTable = true;
+  Fmt8 f;
+  Mode8 m;
+  const float* table;   // LDS
+  __device__ Codec8(const Args& a, const float* lds_table) : f(a.f), m(a.m), table(lds_table) {}
+  __device__ __forceinline__ uint32_t nbits() const { return m.nbits; }
+  template <int J>
+  __device__ __forceinline__ float value(int lo, int hi) const {
+    const uint32_t word = (uint32_t)(J < 4 ? lo : hi);
+    return table[(word >> (8 * (J & 3))) & 0xFFu];
+  }
+  __device__ __forceinline__ float value_of(uint32_t code) const { return table[code & 0xFFu]; }
+  __device__ __forceinline__ uint32_t round4(const uint32_t (&b)[4], const uint32_t (&n)[4]) const {
+    return round4_bytes<TIES>(b, n, false, f, m);
+  }
+  // a NaN sum (the canonical positive NaN) becomes the NaN code without a sign, or +M in a format without NaN
+  __device__ __forceinline__ uint32_t round1(uint32_t s16, uint32_t n) const { return round8<TIES, true>(s16 << 16, n, f, m); }
+};
+
+struct QatOut {
+  uint32_t w8, m16, v16;
+};
+
+// One element, every rounding on the integer path (canonical NaNs): the per-element kernel and any wave
+// of the tile kernel that meets a NaN.
+template <class CODEC>
+__device__ __forceinline__ QatOut qat_one(const CODEC& c, uint32_t w8, uint32_t g16, uint32_t m16, uint32_t v16, uint32_t n,
+                                          const AdamWScalars& p, float omb1, float omb2, const Addends& a16) {
+  const float w = c.value_of(w8);
+  const float g = __uint_as_float(g16 << 16);
+  const float m0 = __uint_as_float(m16 << 16), v0 = __uint_as_float(v16 << 16);
+  const float m1 = __fmaf_rn(p.beta1, m0, omb1 * g);
+  const float v1 = __fmaf_rn(p.beta2, v0, omb2 * (g * g));
+  QatOut o;
+  o.m16 = bf16_rne(m1, a16);
+  o.v16 = bf16_rne(v1, a16);
+  const float u = qat_update(w, __uint_as_float(o.m16 << 16), __uint_as_float(o.v16 << 16), p);
+  const float u16 = __uint_as_float(bf16_rne(u, a16) << 16);
+  const uint32_t s16 = bf16_rne(w + u16, a16);
+  o.w8 = c.round1(s16, n);
+  return o;
+}
+
 // One workgroup per 2048-element tile, 8 consecutive elements per lane: one 8-byte load of weights,
 // three 16-byte loads (gradient, both moments), the same back minus the gradient.  Elements are worked
 // on in pairs so that every bf16 rounding is half a packed hardware convert and the moments leave in
-// their storage layout; the 8-bit rounding of the stochastic variants uses the hardware SR converts.  A
-// NaN anywhere in the wave's sums sends the wave through qat_one instead (canonical NaNs).
-template <int FMT, int VAR, int W>
+// their storage layout.  A NaN anywhere in the wave's sums sends the wave through qat_one instead.
+template <class CODEC, int W>
 __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, const uint16_t* __restrict__ g16,
                                                       uint16_t* __restrict__ m16, uint16_t* __restrict__ v16,
-                                                      AdamWScalars p, int nbits, uint64_t seed, uint64_t step,
+                                                      AdamWScalars p, typename CODEC::Args ca, uint64_t seed, uint64_t step,
                                                       uint64_t blk0) {
   typedef WgTile<W> T;
   __shared__ uint4 strip[T::BLOCKS];
+  __shared__ float table[CODEC::kTable ? 256 : 1];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int e0 = wave * kWaveElems + 8 * lane;
@@ -103,24 +165,21 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
   const u32x4 gq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g16 + g0));
   const u32x4 mq = *reinterpret_cast<const u32x4*>(m16 + g0);
   const u32x4 vq = *reinterpret_cast<const u32x4*>(v16 + g0);
-  if constexpr (VAR != kRNE) {
-    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, step);
-    __syncthreads();
-  }
-  const Addends a8 = make_addends<FMT, VAR>(nbits);
+  if constexpr (CODEC::kTable) table[threadIdx.x] = ca.t.v[threadIdx.x];
+  if constexpr (CODEC::kDraws) fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, step);
+  if constexpr (CODEC::kTable || CODEC::kDraws) __syncthreads();
+  const CODEC c(ca, table);
   const Addends a16 = make_addends<kBF16, kRNE>(0);
-  HwAddends hw = {0, 0, 0, 0};
-  if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
   const float omb1 = 1.0f - p.beta1, omb2 = 1.0f - p.beta2;
   uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if constexpr (VAR != kRNE) read_wg_bits8<W>(strip, e0, a8.nbits, n);
+  if constexpr (CODEC::kDraws) read_wg_bits8<W>(strip, e0, c.nbits(), n);
   const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w}, mw[4] = {mq.x, mq.y, mq.z, mq.w}, vw[4] = {vq.x, vq.y, vq.z, vq.w};
   const int wlo = (int)(uint32_t)wq, whi = (int)(uint32_t)(wq >> 32);
   uint32_t mo[4], vo[4], so[4];
   bool nan_seen = false;
   auto do_pair = [&](auto hc) {   // elements 2h (low halves) and 2h + 1 (high halves)
     constexpr int h = decltype(hc)::value;
-    const float wa = w8_value<FMT, 2 * h>(wlo, whi), wb = w8_value<FMT, 2 * h + 1>(wlo, whi);
+    const float wa = c.template value<2 * h>(wlo, whi), wb = c.template value<2 * h + 1>(wlo, whi);
     const float ga = bf16_lo(gw[h]), gb = bf16_hi(gw[h]);
     const float m1a = __fmaf_rn(p.beta1, bf16_lo(mw[h]), omb1 * ga), m1b = __fmaf_rn(p.beta1, bf16_hi(mw[h]), omb1 * gb);
     const float v1a = __fmaf_rn(p.beta2, bf16_lo(vw[h]), omb2 * (ga * ga)), v1b = __fmaf_rn(p.beta2, bf16_hi(vw[h]), omb2 * (gb * gb));
@@ -128,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
     vo[h] = bf16_pair_hw(v1a, v1b);
     const uint32_t uo = bf16_pair_hw(qat_update(wa, bf16_lo(mo[h]), bf16_lo(vo[h]), p), qat_update(wb, bf16_hi(mo[h]), bf16_hi(vo[h]), p));
     const float sa = wa + bf16_lo(uo), sb = wb + bf16_hi(uo);
-    nan_seen = nan_seen || __builtin_isunordered(sa, sb);   // a NaN moment or update always reaches the sum
+    nan_seen = nan_seen || __builtin_isunordered(sa, sb);   // a NaN weight, moment or update always reaches the sum
     so[h] = bf16_pair_hw(sa, sb);
   };
   do_pair(std::integral_constant<int, 0>{});
@@ -145,9 +204,8 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int sh = 16 * (j & 1);
-      const QatOut o = qat_one<FMT, VAR>((uint32_t)(wq >> (8 * j)) & 0xFFu, (gw[j >> 1] >> sh) & 0xFFFFu,
-                                         (mw[j >> 1] >> sh) & 0xFFFFu, (vw[j >> 1] >> sh) & 0xFFFFu, n[j], p, omb1, omb2,
-                                         a8, a16);
+      const QatOut o = qat_one(c, (uint32_t)(wq >> (8 * j)) & 0xFFu, (gw[j >> 1] >> sh) & 0xFFFFu, (mw[j >> 1] >> sh) & 0xFFFFu,
+                               (vw[j >> 1] >> sh) & 0xFFFFu, n[j], p, omb1, omb2, a16);
       mo[j >> 1] |= o.m16 << sh;
       vo[j >> 1] |= o.v16 << sh;
       wo |= (uint64_t)o.w8 << (8 * j);
@@ -157,13 +215,8 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const uint32_t b4[4] = {so[2 * q] << 16, so[2 * q] & 0xFFFF0000u, so[2 * q + 1] << 16, so[2 * q + 1] & 0xFFFF0000u};
-      if constexpr (VAR != kRNE) {
-        const uint32_t n4[4] = {n[4 * q], n[4 * q + 1], n[4 * q + 2], n[4 * q + 3]};
-        packed[q] = round4_fp8_hw<FMT, VAR>(b4, n4, hw);
-      } else {
-        packed[q] = pack4_fp8<FMT>(round_pattern<FMT, kRNE, false>(b4[0], 0u, a8), round_pattern<FMT, kRNE, false>(b4[1], 0u, a8),
-                                   round_pattern<FMT, kRNE, false>(b4[2], 0u, a8), round_pattern<FMT, kRNE, false>(b4[3], 0u, a8));
-      }
+      const uint32_t n4[4] = {n[4 * q], n[4 * q + 1], n[4 * q + 2], n[4 * q + 3]};
+      packed[q] = c.round4(b4, n4);
     }
     wo = (uint64_t)packed[0] | ((uint64_t)packed[1] << 32);
   }
@@ -175,18 +228,24 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
   *reinterpret_cast<u32x4*>(v16 + g0) = t;
 }
 
-template <int FMT, int VAR>
+// One thread per element: any alignment, any offset, ragged heads and tails.
+template <class CODEC>
 __global__ __launch_bounds__(kThreads) void qat_elems(uint8_t* __restrict__ w8, const uint16_t* __restrict__ g16,
                                                       uint16_t* __restrict__ m16, uint16_t* __restrict__ v16, uint64_t n,
-                                                      AdamWScalars p, int nbits, int W, int log2_per_block, uint64_t seed,
-                                                      uint64_t step, uint64_t offset) {
+                                                      AdamWScalars p, typename CODEC::Args ca, int W, int log2_per_block,
+                                                      uint64_t seed, uint64_t step, uint64_t offset) {
+  __shared__ float table[CODEC::kTable ? 256 : 1];
+  if constexpr (CODEC::kTable) {
+    table[threadIdx.x] = ca.t.v[threadIdx.x];
+    __syncthreads();
+  }
   const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
   if (j >= n) return;
-  const Addends a8 = make_addends<FMT, VAR>(nbits);
+  const CODEC c(ca, table);
   const Addends a16 = make_addends<kBF16, kRNE>(0);
   uint32_t rnd = 0;
-  if constexpr (VAR != kRNE) rnd = element_bits(offset + j, log2_per_block, W, a8.nbits, seed, step);
-  const QatOut o = qat_one<FMT, VAR>(w8[j], g16[j], m16[j], v16[j], rnd, p, 1.0f - p.beta1, 1.0f - p.beta2, a8, a16);
+  if constexpr (CODEC::kDraws) rnd = element_bits(offset + j, log2_per_block, W, c.nbits(), seed, step);
+  const QatOut o = qat_one(c, w8[j], g16[j], m16[j], v16[j], rnd, p, 1.0f - p.beta1, 1.0f - p.beta2, a16);
   w8[j] = (uint8_t)o.w8;
   m16[j] = (uint16_t)o.m16;
   v16[j] = (uint16_t)o.v16;
@@ -194,14 +253,14 @@ __global__ __launch_bounds__(kThreads) void qat_elems(uint8_t* __restrict__ w8, 
 
 namespace {
 
-template <int FMT, int VAR>
+template <class CODEC>
 hipError_t launch_tiles_w(int W, uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t ntiles,
-                          const AdamWScalars& p, int nbits, uint64_t seed, uint64_t step, uint64_t blk0,
+                          const AdamWScalars& p, const typename CODEC::Args& ca, uint64_t seed, uint64_t step, uint64_t blk0,
                           hipStream_t stream) {
   const dim3 grid((unsigned)ntiles), block(kThreads);
 #define FBSR_QAT_LAUNCH(WW) \
-  hipLaunchKernelGGL((qat_tiles<FMT, VAR, WW>), grid, block, 0, stream, w8, g16, m16, v16, p, nbits, seed, step, blk0)
-  if constexpr (VAR == kRNE) {
+  hipLaunchKernelGGL((qat_tiles<CODEC, WW>), grid, block, 0, stream, w8, g16, m16, v16, p, ca, seed, step, blk0)
+  if constexpr (!CODEC::kDraws) {
     FBSR_QAT_LAUNCH(8);
   } else {
     switch (W) {
@@ -216,53 +275,54 @@ hipError_t launch_tiles_w(int W, uint8_t* w8, const uint16_t* g16, uint16_t* m16
   return hipGetLastError();
 }
 
-template <int FMT, int VAR>
-hipError_t launch_elems(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,
-                        const AdamWScalars& p, int nbits, int W, uint64_t seed, uint64_t step, uint64_t offset,
+template <class CODEC>
+hipError_t launch_elems(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, const AdamWScalars& p,
+                        const typename CODEC::Args& ca, int W, uint64_t seed, uint64_t step, uint64_t offset,
                         hipStream_t stream) {
   for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
     const uint64_t m = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
     const uint64_t blocks = (m + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL((qat_elems<FMT, VAR>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, w8 + at, g16 + at,
-                       m16 + at, v16 + at, m, p, nbits, W, log2_of(128 / W), seed, step, offset + at);
+    hipLaunchKernelGGL((qat_elems<CODEC>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, w8 + at, g16 + at, m16 + at,
+                       v16 + at, m, p, ca, W, log2_of(128 / W), seed, step, offset + at);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
-template <int FMT, int VAR>
+// nbits: N of a mode that draws bits (unused otherwise).
+template <class CODEC>
 hipError_t run(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, const AdamWScalars& p,
-               int nbits, uint64_t seed, uint64_t step, uint64_t offset, hipStream_t stream) {
-  const int W = VAR == kRNE ? 8 : slot_width(nbits);
-  Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(g16), 2, 16,
+               const typename CODEC::Args& ca, int nbits, uint64_t seed, uint64_t step, uint64_t offset, hipStream_t stream) {
+  const int W = CODEC::kDraws ? slot_width(nbits) : 8;
+  Split s = split_range(n, offset, W, !CODEC::kDraws, reinterpret_cast<uintptr_t>(g16), 2, 16,
                         reinterpret_cast<uintptr_t>(w8), 1, 8, reinterpret_cast<uintptr_t>(m16), 2, 16);
   if ((reinterpret_cast<uintptr_t>(v16) + s.head * 2) % 16 != 0) {
     s.head = 0;
     s.ntiles = 0;
   }
-  hipError_t e = launch_elems<FMT, VAR>(w8, g16, m16, v16, s.head, p, nbits, W, seed, step, offset, stream);
+  hipError_t e = launch_elems<CODEC>(w8, g16, m16, v16, s.head, p, ca, W, seed, step, offset, stream);
   if (e != hipSuccess) return e;
   for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
     const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
     const uint64_t e0 = s.head + t0 * s.tile_elems;
-    e = launch_tiles_w<FMT, VAR>(W, w8 + e0, g16 + e0, m16 + e0, v16 + e0, cnt, p, nbits, seed, step,
-                                 (offset + e0) / (uint64_t)(128 / W), stream);
+    e = launch_tiles_w<CODEC>(W, w8 + e0, g16 + e0, m16 + e0, v16 + e0, cnt, p, ca, seed, step,
+                              (offset + e0) / (uint64_t)(128 / W), stream);
     if (e != hipSuccess) return e;
   }
   const uint64_t done = s.head + s.ntiles * s.tile_elems;
-  return launch_elems<FMT, VAR>(w8 + done, g16 + done, m16 + done, v16 + done, n - done, p, nbits, W, seed, step,
-                                offset + done, stream);
+  return launch_elems<CODEC>(w8 + done, g16 + done, m16 + done, v16 + done, n - done, p, ca, W, seed, step, offset + done,
+                             stream);
 }
 
 template <int FMT>
 hipError_t run_v(int variant, uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,
                  const AdamWScalars& p, int nbits, uint64_t seed, uint64_t step, uint64_t offset, hipStream_t stream) {
   switch (variant) {
-    case kRNE: return run<FMT, kRNE>(w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
-    case kSRFF: return run<FMT, kSRFF>(w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
-    case kSRF: return run<FMT, kSRF>(w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
-    default: return run<FMT, kSRC>(w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+    case kRNE: return run<FixedCodec<FMT, kRNE>>(w8, g16, m16, v16, n, p, {nbits}, nbits, seed, step, offset, stream);
+    case kSRFF: return run<FixedCodec<FMT, kSRFF>>(w8, g16, m16, v16, n, p, {nbits}, nbits, seed, step, offset, stream);
+    case kSRF: return run<FixedCodec<FMT, kSRF>>(w8, g16, m16, v16, n, p, {nbits}, nbits, seed, step, offset, stream);
+    default: return run<FixedCodec<FMT, kSRC>>(w8, g16, m16, v16, n, p, {nbits}, nbits, seed, step, offset, stream);
   }
 }
 
@@ -273,6 +333,18 @@ hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uin
                             uint64_t offset, hipStream_t stream) {
   if (fmt == kE4M3) return run_v<kE4M3>(variant, w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
   return run_v<kE5M2>(variant, w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+}
+
+hipError_t launch_qat_adamw_format8(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,
+                                    const Fmt8& f, const Mode8& m, const Table8& t, const AdamWScalars& p, uint64_t seed,
+                                    uint64_t step, uint64_t offset, hipStream_t stream) {
+  const int nbits = (int)m.nbits;
+  if (m.nbits != 0) {
+    if (m.ties) return run<Codec8<true, true>>(w8, g16, m16, v16, n, p, {f, m, t}, nbits, seed, step, offset, stream);
+    return run<Codec8<false, true>>(w8, g16, m16, v16, n, p, {f, m, t}, nbits, seed, step, offset, stream);
+  }
+  if (m.ties) return run<Codec8<true, false>>(w8, g16, m16, v16, n, p, {f, m, t}, nbits, seed, step, offset, stream);
+  return run<Codec8<false, false>>(w8, g16, m16, v16, n, p, {f, m, t}, nbits, seed, step, offset, stream);
 }
 
 }  // namespace fbsr

@@ -160,6 +160,25 @@ def test_format8_argument_validation(L):
     assert L.fbsr_round_format8(p(good), 2, p(good), 8, ref, 1, 3, 0, (1 << 64) - 4, None) == EINVAL
 
 
+def test_qat_format8_argument_validation(L):
+    from paper_2504_20634_amd import binding as b
+    OK, EINVAL, EALIGN = 0, 1, 2
+    p = ctypes.c_void_p
+    good = 0x7F0000001000
+    f = b.format8_named("p3109_binary8p4")
+    ref = ctypes.byref(f)
+    hp = (ctypes.c_float * 7)(1e-3, 0.9, 0.999, 1e-8, 0.0, 0.1, 0.001)
+    assert L.fbsr_qat_adamw_step_format8(None, None, None, None, 0, ref, hp, 1, 3, 0, 0, 0, None) == OK
+    assert L.fbsr_qat_adamw_step_format8(p(good), p(good), p(good), p(good), 8, None, hp, 1, 3, 0, 0, 0, None) == EINVAL
+    assert L.fbsr_qat_adamw_step_format8(p(good), p(good), p(good), p(good), 8, ref, None, 1, 3, 0, 0, 0, None) == EINVAL
+    assert L.fbsr_qat_adamw_step_format8(p(good), None, p(good), p(good), 8, ref, hp, 1, 3, 0, 0, 0, None) == EINVAL
+    assert L.fbsr_qat_adamw_step_format8(p(good), p(good), p(good), p(good + 1), 8, ref, hp, 1, 3, 0, 0, 0, None) == EALIGN
+    for var, nb in ((7, 3), (-1, 3), (4, 17), (2, 0)):
+        assert L.fbsr_qat_adamw_step_format8(p(good), p(good), p(good), p(good), 8, ref, hp, var, nb, 0, 0, 0, None) == EINVAL
+    bad = b.Format8(8, 4, 8, 0x7E, 0x7E, 0x80, 0, 0)
+    assert L.fbsr_qat_adamw_step_format8(p(good), p(good), p(good), p(good), 8, ctypes.byref(bad), hp, 1, 3, 0, 0, 0, None) == EINVAL
+
+
 def test_workspace_size_grows_with_n(L):
     a = L.fbsr_bias_stats_workspace_bytes(1 << 20, 16)
     b = L.fbsr_bias_stats_workspace_bytes(1 << 30, 4096)

@@ -134,3 +134,104 @@ def test_ten_steps_at_2_22(fbsr, oracle):
         print("case variant=%d" % variant, flush=True)
         assert first_mismatch(host(md), m) is None and first_mismatch(host(vd), v) is None
         assert first_mismatch(host(wd), w8) is None
+
+
+# ------------------------------------------------------------------ generic 8-bit formats ----
+def p3109(P):
+    return (8, P, 1 << (7 - P), 0x7E, 0x7F, 0x80, 0, 0)
+
+
+FORMATS8 = {"binary8p4": p3109(4), "binary8p3": p3109(3), "binary8p5": p3109(5), "ocp_e4m3": (8, 4, 7, 0x7E, -1, 0x7F, 1, 1),
+            "ocp_e5m2": (8, 3, 15, 0x7B, 0x7C, 0x7E, 1, 1), "ocp_e2m3": (6, 4, 1, 0x1F, -1, -1, 0, 1), "ocp_e2m1": (4, 2, 1, 0x07, -1, -1, 0, 1)}
+SRC_ODD, RNO, RNA = 4, 5, 6
+
+
+def _oracle_step8(oracle, w8, g, m, v, d, params, variant, nbits, seed, step, offset, threads=16):
+    n = w8.size
+    if n < 4096:
+        return oracle.qat_adamw_step_format8(w8, g, m, v, d, params, variant, nbits, seed, step, offset)
+    cuts = np.linspace(0, n, threads + 1).astype(np.int64)
+    with ThreadPoolExecutor(threads) as pool:
+        parts = list(pool.map(lambda ab: oracle.qat_adamw_step_format8(w8[ab[0]:ab[1]], g[ab[0]:ab[1]], m[ab[0]:ab[1]], v[ab[0]:ab[1]],
+                                                                       d, params, variant, nbits, seed, step, offset + int(ab[0])),
+                              zip(cuts[:-1], cuts[1:])))
+    return tuple(np.concatenate([p[i] for p in parts]) for i in range(3))
+
+
+@pytest.mark.parametrize("name", sorted(FORMATS8))
+def test_format8_single_step(fbsr, oracle, name):
+    """Every weight byte (NaN, infinity and unused encodings, bits above K included), tame and wild moments,
+    every variant, sizes around the tile, shifted offsets."""
+    d = FORMATS8[name]
+    for n in (0, 1, 9, 2048, 5 * 2048 + 333):
+        for wild in (False, True):
+            w8, g, m, v = _state(max(n, 1), 200 + n, wild)
+            w8, g, m, v = w8[:n], g[:n], m[:n], v[:n]
+            for params in PARAMS[:2]:
+                for variant, nbits, offset, step in ((RNE, 0, 0, 1), (SRFF, 3, 0, 2), (SRF, 3, 16, 7), (SRC, 4, 5, 1 << 33),
+                                                     (SRC_ODD, 3, 0, 3), (RNO, 0, 7, 1), (RNA, 0, 0, 9), (SRF, 16, 128, 9)):
+                    print("case fmt=%s n=%d wild=%d lr=%g variant=%d nbits=%d offset=%d" % (name, n, wild, params[0], variant, nbits, offset), flush=True)
+                    if n:
+                        wd, gd, md, vd = dev(w8), dev(g), dev(m), dev(v)
+                    else:
+                        wd = torch.empty(0, dtype=torch.uint8, device="cuda")
+                        gd = torch.empty(0, dtype=torch.int16, device="cuda")
+                        md, vd = gd.clone(), gd.clone()
+                    fbsr.fbsr_qat_adamw_step_format8(wd, gd, md, vd, d, params, variant, nbits, seed=31, step=step, offset=offset)
+                    ww, mm, vv = _oracle_step8(oracle, w8, g, m, v, d, params, variant, nbits, 31, step, offset)
+                    assert first_mismatch(host(md), mm) is None, "first moment"
+                    assert first_mismatch(host(vd), vv) is None, "second moment"
+                    assert first_mismatch(host(wd), ww) is None, "weights"
+
+
+def test_format8_main_path_without_nan(fbsr, oracle):
+    """Finite binary8p4 weights and finite raw moments: no wave leaves the kernel's main path."""
+    d = FORMATS8["binary8p4"]
+    n = 32 * 2048 + 5
+    rng = np.random.default_rng(61)
+    finite8 = np.array([c for c in range(256) if np.isfinite(oracle.decode_format8(c, d))], dtype=np.uint8)
+    w8 = finite8[rng.integers(0, finite8.size, n)]
+
+    def raw(signed):
+        code = (rng.integers(0, 201, n).astype(np.uint16) << 7) | rng.integers(0, 128, n).astype(np.uint16)
+        return code | (rng.integers(0, 2, n).astype(np.uint16) << 15) if signed else code
+    g, m, v = raw(True), raw(True), raw(False)
+    for params in PARAMS:
+        for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 2), (SRC, 4), (SRC_ODD, 16), (RNA, 0)):
+            print("case lr=%g variant=%d nbits=%d" % (params[0], variant, nbits), flush=True)
+            wd, gd, md, vd = dev(w8), dev(g), dev(m), dev(v)
+            fbsr.fbsr_qat_adamw_step_format8(wd, gd, md, vd, d, params, variant, nbits, seed=19, step=4, offset=0)
+            ww, mm, vv = _oracle_step8(oracle, w8, g, m, v, d, params, variant, nbits, 19, 4, 0)
+            assert np.all((mm & 0x7FFF) <= 0x7F80) and np.all((vv & 0x7FFF) <= 0x7F80) and not np.any(ww == 0x80), "the recipe produced a NaN"
+            assert first_mismatch(host(md), mm) is None and first_mismatch(host(vd), vv) is None
+            assert first_mismatch(host(wd), ww) is None, "weights"
+
+
+def test_sec4_setting_binary8p4_three_bits(fbsr, oracle):
+    """Sec. IV's configuration at small scale: binary8p4 weights, bf16 AdamW updates, 3 random bits, 10 steps
+    over 2^21 weights with fresh gradients; the GPU trajectory equals the oracle's for every variant, and
+    with an OCP E4M3 descriptor it equals fbsr_qat_adamw_step's."""
+    n = 1 << 21
+    lr, b1, b2, eps, wdecay = 2e-2, 0.9, 0.99, 1e-8, 0.01
+    d = FORMATS8["binary8p4"]
+    for variant in (RNE, SRFF, SRF, SRC):
+        w8, _, m, v = _state(n, 78)
+        m[:] = 0
+        v[:] = 0
+        w8 &= 0x77
+        wd, md, vd = dev(w8), dev(m), dev(v)
+        wd_a, md_a, vd_a = dev(w8), dev(m), dev(v)
+        wd_b, md_b, vd_b = dev(w8), dev(m), dev(v)
+        rng = np.random.default_rng(6)
+        for t in range(1, 11):
+            g = _bf16(rng.standard_normal(n) * 0.2)
+            gd = dev(g)
+            params = (lr, b1, b2, eps, wdecay, 1 - b1 ** t, 1 - b2 ** t)
+            fbsr.fbsr_qat_adamw_step_format8(wd, gd, md, vd, d, params, variant, 3, seed=8, step=t)
+            w8, m, v = _oracle_step8(oracle, w8, g, m, v, d, params, variant, 3, 8, t, 0)
+            fbsr.fbsr_qat_adamw_step(wd_a, gd, md_a, vd_a, E4M3, params, variant, 3, seed=8, step=t)
+            fbsr.fbsr_qat_adamw_step_format8(wd_b, gd, md_b, vd_b, FORMATS8["ocp_e4m3"], params, variant, 3, seed=8, step=t)
+        print("case variant=%d" % variant, flush=True)
+        assert first_mismatch(host(md), m) is None and first_mismatch(host(vd), v) is None
+        assert first_mismatch(host(wd), w8) is None
+        assert torch.equal(wd_a, wd_b) and torch.equal(md_a, md_b) and torch.equal(vd_a, vd_b)
