@@ -203,3 +203,54 @@ def test_workload4_sgd_1000_steps_drift(fbsr):
         else:
             # only weights so small that 1e-6 is not << their ulp (|w| < 2^-12: a few in a thousand) can move
             assert moved < 1e-2 and abs(track[-1] - m0) < 1e-5 * m0, (variant, moved, track)
+
+
+def test_other_entry_points_at_bench_sizes(fbsr, oracle):
+    """The paths bench.py times beside the headline, at its sizes (2^28 elements; 2^27 for the fused steps), each
+    compared with the oracle on 24 sampled windows of 2^14: narrow-source, block-scaled, generic-format rounding
+    (P3109 binary8p4 from fp32 and from bf16) and both fused QAT steps."""
+    from paper_2504_20634_amd import workloads
+    n = 1 << 28
+    width = 1 << 14
+    x = workloads.full_range(n, "e4m3", seed=2)
+    xd = dev(x)
+    x16 = workloads.sgd_weights(n, seed=30)
+    x16d = dev(x16)
+    p4 = (8, 4, 8, 0x7E, 0x7F, 0x80, 0, 0)
+    wins = [s - s % 32 for s in _windows(n, 24, width, seed=9)]      # block-scaled windows start on a block
+    print("case narrow source", flush=True)
+    out = fbsr.fbsr_round_from16(x16d, 0, E4M3, SRC, 3, seed=2)
+    for s in wins:
+        assert first_mismatch(host(out[s:s + width]), oracle.round_from16(x16[s:s + width], 0, E4M3, SRC, 3, seed=2, offset=s)) is None, s
+    print("case block scaled", flush=True)
+    out, sc = fbsr.fbsr_round_block_scaled(xd, E5M2, SRF, 8, seed=2)
+    for s in wins:
+        wc, wsc = oracle.round_block_scaled(x[s:s + width], E5M2, SRF, 8, seed=2, offset=s)
+        assert first_mismatch(host(out[s:s + width]), wc) is None and first_mismatch(host(sc[s // 32:(s + width) // 32]), wsc) is None, s
+    for src, data, datad, variant, nbits in ((2, x, xd, SRC, 3), (2, x, xd, 4, 3), (0, x16, x16d, SRFF, 3), (0, x16, x16d, SRC, 3)):
+        print("case generic src=%d variant=%d" % (src, variant), flush=True)
+        out = fbsr.fbsr_round_format8(datad, src, p4, variant, nbits, seed=2)
+        for s in wins:
+            assert first_mismatch(host(out[s:s + width]), oracle.round_format8(data[s:s + width], src, p4, variant, nbits, 2, s)) is None, s
+    del out, xd, x16d
+    nq = 1 << 27
+    w8 = (workloads.sgd_weights(nq, seed=40) & 0x7777).view(np.uint8)[:nq].copy()
+    g16 = workloads.sgd_weights(nq, seed=50)
+    m16 = workloads.sgd_weights(nq, seed=51) & 0x3FFF        # moments of modest size, second one non-negative
+    v16 = workloads.sgd_weights(nq, seed=52) & 0x3FFF
+    params = (1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9 ** 2, 1 - 0.999 ** 2)
+    qwins = _windows(nq, 24, width, seed=10)
+    for generic in (False, True):
+        print("case qat generic=%d" % generic, flush=True)
+        wd, gd, md, vd = dev(w8), dev(g16), dev(m16), dev(v16)
+        if generic:
+            fbsr.fbsr_qat_adamw_step_format8(wd, gd, md, vd, p4, params, SRC, 3, seed=6, step=2)
+        else:
+            fbsr.fbsr_qat_adamw_step(wd, gd, md, vd, E4M3, params, SRC, 3, seed=6, step=2)
+        for s in qwins:
+            sl = slice(s, s + width)
+            if generic:
+                ww, mm, vv = oracle.qat_adamw_step_format8(w8[sl], g16[sl], m16[sl], v16[sl], p4, params, SRC, 3, 6, 2, s)
+            else:
+                ww, mm, vv = oracle.qat_adamw_step(w8[sl], g16[sl], m16[sl], v16[sl], E4M3, params, SRC, 3, 6, 2, s)
+            assert first_mismatch(host(wd[sl]), ww) is None and first_mismatch(host(md[sl]), mm) is None and first_mismatch(host(vd[sl]), vv) is None, s
