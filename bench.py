@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--elems-log2", type=int, default=28, help="log2 of the batch size (default 28)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-paths", action="store_true", help="skip the secondary paths (profiling runs)")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the five-workload report")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run two plain device copies of the 1 GiB input (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -60,6 +61,91 @@ def timed_launches(torch, fn, reps, warm=2):
         b.record()
     torch.cuda.synchronize()
     return sum(a.elapsed_time(b) for a, b in evs) / reps
+
+
+def timed_sweep(torch, launches, reps=3):
+    """Average duration (ms) of one pass over `launches` (a list of callables), from events around whole passes."""
+    for fn in launches:
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        for fn in launches:
+            fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def five_workloads(torch, np, fbsr, workloads, x_e5m2):
+    """Throughput on the five synthetic workloads at their own sizes (elements/s and algorithmic GB/s per launch,
+    averaged over each workload's sweep).  x_e5m2: 2^28 full-range inputs already on the device."""
+    rep = {}
+
+    def entry(elements, launches, ms, bytes_per_elem, note):
+        per = ms / launches
+        return {"elements": elements, "launches": launches, "ms_per_launch": round(per, 4), "gelem_s": round(elements / per / 1e6, 1),
+                "gb_s": round(bytes_per_elem * elements / per / 1e6, 1), "bytes_per_elem": bytes_per_elem, "note": note}
+
+    # 1: Fig. 1 sweep, 1024 X values x 5000 samples -> bf16, N = 2, rounded values and per-X statistics in one pass
+    x1 = torch.from_numpy(workloads.fig1_grid()[0]).cuda()
+    n1 = x1.numel()
+    out1 = torch.empty(n1, dtype=torch.uint16, device="cuda")
+    st1 = torch.zeros((1024, 4), dtype=torch.float64, device="cuda")
+    ws1 = torch.empty(fbsr.bias_stats_workspace_bytes(n1, 1024) // 8 + 1, dtype=torch.float64, device="cuda")
+    ls = [lambda v=v: fbsr.fbsr_bias_stats(x1, fbsr.FMT_BF16, v, 2, 0, 0, 5000, 0, 1024, stats=st1, out=out1, workspace=ws1)
+          for v in (fbsr.SRFF, fbsr.SRF, fbsr.SRC)]
+    rep["1_fig1_sweep_bf16_N2"] = entry(n1, len(ls), timed_sweep(torch, ls, 10), 6.0,
+                                        "fbsr_bias_stats with codes written; 20 MB input, resident in the last-level cache")
+    del x1, out1
+    # 2: 2^24 scaled normals -> E4M3, N in {1,2,3,4,6,8} x 3 variants
+    x2 = torch.from_numpy(workloads.scaled_normal(1 << 24, seed=1)).cuda()
+    out2 = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+    ls = [lambda nb=nb, v=v: fbsr.fbsr_round(x2, fbsr.FMT_E4M3, v, nb, seed=1, out=out2)
+          for nb in (1, 2, 3, 4, 6, 8) for v in (fbsr.SRFF, fbsr.SRF, fbsr.SRC)]
+    rep["2_e4m3_scaled_normal_2p24"] = entry(1 << 24, len(ls), timed_sweep(torch, ls, 5), 5.0,
+                                             "64 MiB input, resident in the 256 MB last-level cache: not an HBM figure")
+    del x2, out2
+    # 3: 2^28 full-range -> E5M2 and bf16, N in {4,8,16} x 3 variants
+    n3 = x_e5m2.numel()
+    xb = torch.from_numpy(workloads.full_range(n3, "bf16", seed=2)).cuda()
+    o8 = [torch.empty(n3, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    o16 = [torch.empty(n3, dtype=torch.uint16, device="cuda") for _ in range(2)]
+    ls = [lambda nb=nb, v=v, k=k: fbsr.fbsr_round(x_e5m2, fbsr.FMT_E5M2, v, nb, seed=2, out=o8[k % 2])
+          for k, (nb, v) in enumerate((nb, v) for nb in (4, 8, 16) for v in (fbsr.SRFF, fbsr.SRF, fbsr.SRC))]
+    rep["3_e5m2_full_range_2p28"] = entry(n3, len(ls), timed_sweep(torch, ls, 3), 5.0, "N in {4,8,16} x {srff,srf,src}")
+    ls = [lambda nb=nb, v=v, k=k: fbsr.fbsr_round(xb, fbsr.FMT_BF16, v, nb, seed=2, out=o16[k % 2])
+          for k, (nb, v) in enumerate((nb, v) for nb in (4, 8, 16) for v in (fbsr.SRFF, fbsr.SRF, fbsr.SRC))]
+    rep["3_bf16_full_range_2p28"] = entry(n3, len(ls), timed_sweep(torch, ls, 3), 6.0, "N in {4,8,16} x {srff,srf,src}")
+    del xb, o8, o16
+    # 4: fused SGD update, 2^27 bf16 weights, fresh gradients, N in {2,4,8} x 3 variants and RNE
+    n4 = 1 << 27
+    w4 = [torch.from_numpy(workloads.sgd_weights(n4, seed=3 + k).view(np.int16)).cuda() for k in range(3)]
+    g4 = [torch.from_numpy(workloads.sgd_grads(n4, k, seed=3)).cuda() for k in range(3)]
+    cases = [(fbsr.RNE, 0)] + [(v, nb) for nb in (2, 4, 8) for v in (fbsr.SRFF, fbsr.SRF, fbsr.SRC)]
+    ls = [lambda v=v, nb=nb, k=k: fbsr.fbsr_sgd_update(w4[k % 3], g4[k % 3], 1e-3, v, nb, seed=4, step=k) for k, (v, nb) in enumerate(cases)]
+    rep["4_sgd_update_bf16_2p27"] = entry(n4, len(ls), timed_sweep(torch, ls, 5), 8.0, "RNE and N in {2,4,8} x {srff,srf,src}")
+    del w4, g4
+    # 5: 2^30 inputs in 4096 log-spaced bins of 2^18 over [2^-10, 2^10), statistics only, E4M3 and bf16 x 3 variants x N = 1..12
+    nb5, grp = 4096, 1 << 18
+    edges = torch.exp2(-10.0 + 20.0 * torch.arange(nb5 + 1, dtype=torch.float64, device="cuda") / nb5).float().double()
+    x5 = torch.empty(nb5 * grp, dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    for b0 in range(0, nb5, 256):
+        u = torch.rand((256, grp), dtype=torch.float64, device="cuda", generator=gen)
+        lo, hi = edges[b0:b0 + 256, None], edges[b0 + 1:b0 + 257, None]
+        x5[b0 * grp:(b0 + 256) * grp] = torch.minimum(lo + u * (hi - lo), torch.nextafter(hi.float(), lo.float()).double()).float().reshape(-1)
+        del u
+    st5 = torch.zeros((nb5, 4), dtype=torch.float64, device="cuda")
+    ws5 = torch.empty(fbsr.bias_stats_workspace_bytes(nb5 * grp, nb5) // 8 + 1, dtype=torch.float64, device="cuda")
+    for f, name in ((fbsr.FMT_E4M3, "e4m3"), (fbsr.FMT_BF16, "bf16")):
+        ls = [lambda v=v, nb=nb: fbsr.fbsr_bias_stats(x5, f, v, nb, 5, 0, grp, 0, nb5, stats=st5, workspace=ws5)
+              for v in (fbsr.SRFF, fbsr.SRF, fbsr.SRC) for nb in range(1, 13)]
+        rep["5_bias_stats_%s_2p30" % name] = entry(nb5 * grp, len(ls), timed_sweep(torch, ls, 1), 4.0,
+                                                   "statistics only (out = NULL), 3 variants x N = 1..12; inputs drawn on the device")
+    return rep
 
 
 def cpu_baseline(x_host, fmts, variants, threads):
@@ -266,6 +352,11 @@ def main():
             paths["bias_stats_%s_N%d_srf" % (target[f], nb)] = {"ms": round(ms, 4), "gb_s": round(4.0 * n / ms / 1e6, 1)}
         del xs_
 
+    workloads_report = None
+    if not args.no_paths and not args.no_workloads and args.elems_log2 == 28:
+        del x_rot, out_rot
+        workloads_report = five_workloads(torch, np, fbsr, workloads, x_dev[fbsr.FMT_E5M2])
+
     result = {
         "metric": "FBSR fp32->fp8 elements/s (achieved HBM GB/s and fraction of peak under roofline), N=2,4,8",
         "value": value,
@@ -291,6 +382,8 @@ def main():
         "per_launch": per,
         "paths": paths,
     }
+    if workloads_report is not None:
+        result["workloads"] = workloads_report
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
         result["cpu_baseline"] = cpu_baseline(x_host, fmts, variants, threads)
