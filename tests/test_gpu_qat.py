@@ -235,3 +235,46 @@ def test_sec4_setting_binary8p4_three_bits(fbsr, oracle):
         assert first_mismatch(host(md), m) is None and first_mismatch(host(vd), v) is None
         assert first_mismatch(host(wd), w8) is None
         assert torch.equal(wd_a, wd_b) and torch.equal(md_a, md_b) and torch.equal(vd_a, vd_b)
+
+
+def test_sec4_behaviour_on_a_noisy_quadratic(fbsr, oracle):
+    """Sec. IV in miniature, on the fused step itself: 2^20 binary8p4 weights pulled toward targets by the noisy
+    gradient of a quadratic, AdamW in bf16, updates of about an eighth of an 8-bit ulp.  Nearest-even stagnates (no
+    update crosses half an ulp).  With 3 random bits and D = 4 excess bits SRFF's bias (2^-4 - 2^-3)/2 = -1/32 ulp per
+    rounding pulls the weights toward zero and SRF's residual 2^-(D+1) = +1/32 ulp pushes them away by as much
+    (Sec. III-E), both ending near the starting error; SRC, with either tie rule, has no bias and ends well below.
+    With 4 bits (N = D, "the ideal number" of Sec. IV) all three are exact SR and agree."""
+    d = FORMATS8["binary8p4"]
+    n, steps, lr, sigma = 1 << 20, 1500, 5e-4, 0.05
+    lut = torch.tensor([oracle.decode_format8(c, d) for c in range(256)], dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    t = torch.randn(n, device="cuda", generator=gen) * 0.05
+    start = t + torch.randn(n, device="cuda", generator=gen) * 0.01
+    w0 = fbsr.fbsr_round_format8(start, 2, d, RNE, 0, seed=0)
+    mse0 = ((lut[w0.long()] - t) ** 2).mean().item()
+    print("start           mse %.3e" % mse0, flush=True)
+    result = {}
+    for variant, nbits, name in ((RNE, 0, "rne"), (SRFF, 3, "srff_3"), (SRF, 3, "srf_3"), (SRC, 3, "src_3"), (SRC_ODD, 3, "src_ties_odd_3"),
+                                 (SRFF, 4, "srff_4"), (SRF, 4, "srf_4"), (SRC, 4, "src_4")):
+        w = w0.clone()
+        m = torch.zeros(n, dtype=torch.int16, device="cuda")
+        v = torch.zeros(n, dtype=torch.int16, device="cuda")
+        gen.manual_seed(11)
+        track = []
+        for k in range(1, steps + 1):
+            g = (lut[w.long()] - t + sigma * torch.randn(n, device="cuda", generator=gen)).to(torch.bfloat16).view(torch.int16)
+            fbsr.fbsr_qat_adamw_step_format8(w, g, m, v, d, (lr, 0.9, 0.999, 1e-8, 0.0, 1 - 0.9 ** k, 1 - 0.999 ** k), variant, nbits, seed=5, step=k)
+            if k % 500 == 0:
+                track.append(((lut[w.long()] - t) ** 2).mean().item())
+        shrink = (lut[w.long()].abs() - t.abs()).mean().item()
+        moved = (w != w0).double().mean().item()
+        result[name] = (track[-1], shrink, moved)
+        print("%-15s mse at 500/1000/1500 %s  mean(|w| - |t|) %+.2e  weights moved %.3f" %
+              (name, " ".join("%.3e" % x for x in track), shrink, moved), flush=True)
+    assert result["rne"][0] > 0.9 * mse0 and result["rne"][2] < 0.25
+    assert result["srff_3"][1] < -3e-3 and result["srf_3"][1] > 3e-3
+    for name in ("src_3", "src_ties_odd_3", "srff_4", "srf_4", "src_4"):
+        assert result[name][0] < 0.6 * mse0 and abs(result[name][1]) < 1.5e-3, name
+    assert result["srff_3"][0] > 1.5 * result["src_3"][0] and result["srf_3"][0] > 1.5 * result["src_3"][0]
+    assert max(result[k][0] for k in ("srff_4", "srf_4", "src_4")) < 1.1 * min(result[k][0] for k in ("srff_4", "srf_4", "src_4"))
