@@ -62,9 +62,15 @@ struct Format {
   bool has_inf;  // e = all-ones, t = 0 is +-inf
   uint32_t nan_code;  // canonical quiet NaN, sign bit clear
   uint32_t inf_code;  // +inf (unused when !has_inf)
+  // A format whose specials do not follow the two patterns above (a NaN that is a sign bit alone,
+  // no negative zero, finite values in the top exponent) is rounded and decoded through its
+  // generic descriptor (see Format8); nan_code then holds the full NaN code.
+  bool by_descriptor = false;
+  int32_t desc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 };
 
-enum { FMT_BF16 = 0, FMT_E4M3 = 1, FMT_E5M2 = 2, FMT_FP16 = 3 };   // FP16: IEEE binary16, used as a SOURCE format
+enum { FMT_BF16 = 0, FMT_E4M3 = 1, FMT_E5M2 = 2, FMT_BINARY8P4 = 3,
+       FMT_FP16 = 16 };   // FP16: IEEE binary16, used as a SOURCE format only (never a caller's target id)
 enum { SRC_BF16 = 0, SRC_FP16 = 1 };
 enum { VAR_RNE = 0, VAR_SRFF = 1, VAR_SRF = 2, VAR_SRC = 3,
        VAR_SRC_ODD = 4, VAR_TNO = 5, VAR_TA = 6 };   // 4..6: generic-format entry points only
@@ -80,6 +86,14 @@ bool get_format(int fmt, Format* f) {
     case FMT_E5M2:  // OCP E5M2: IEEE-like, max 1.75 * 2^15
       *f = Format{8, 3, 15, 57344.0, true, 0x7Eu, 0x7Cu};
       return true;
+    case FMT_BINARY8P4: {  // IEEE WG P3109 binary8p4, the format Sec. IV trains in: bias 8, max 1.75 * 2^7,
+                           // 0x7F / 0xFF infinities, 0x80 the only NaN, no negative zero
+      *f = Format{8, 4, 8, 224.0, true, 0x80u, 0x7Fu};
+      f->by_descriptor = true;
+      const int32_t d[8] = {8, 4, 8, 0x7E, 0x7F, 0x80, 0, 0};
+      for (int k = 0; k < 8; ++k) f->desc[k] = d[k];
+      return true;
+    }
     case FMT_FP16:  // IEEE binary16: (2 - 2^-10) * 2^15
       *f = Format{16, 11, 15, 65504.0, true, 0x7E00u, 0x7C00u};
       return true;
@@ -87,8 +101,12 @@ bool get_format(int fmt, Format* f) {
   return false;
 }
 
+double decode_by_descriptor(uint32_t code, const Format& f);
+uint32_t round_by_descriptor(double xv, const Format& f, int variant, int N, uint64_t n);
+
 // Eq. (1): the real value of (s,e,t); specials per format.
 double decode(uint32_t code, const Format& f) {
+  if (f.by_descriptor) return decode_by_descriptor(code, f);
   const int tbits = f.P - 1;
   const uint32_t s = (code >> (f.K - 1)) & 1u;
   const uint32_t e = (code >> tbits) & ((1u << (f.K - 1 - tbits)) - 1u);
@@ -166,6 +184,7 @@ bool round_up(int variant, double fl, double delta, int N, uint64_t n) {
 // One element: a value with at most 24 significant bits (an fp32 value, or one scaled exactly by a
 // power of two) -> code of the target format, given the integer n < 2^N.
 uint32_t round_one(double xv, const Format& f, int variant, int N, uint64_t n) {
+  if (f.by_descriptor) return round_by_descriptor(xv, f, variant, N, n);
   const uint32_t sign_code = (std::signbit(xv) ? 1u : 0u) << (f.K - 1);
   if (std::isnan(xv)) return sign_code | f.nan_code;
   const double a = std::fabs(xv);
@@ -278,6 +297,18 @@ uint32_t round_one8(double xv, const Format8& g, int variant, int N, uint64_t n)
   return sign_code | mag;
 }
 
+double decode_by_descriptor(uint32_t code, const Format& f) {
+  Format8 g;
+  get_format8(f.desc, &g);
+  return decode8(code, g);
+}
+
+uint32_t round_by_descriptor(double xv, const Format& f, int variant, int N, uint64_t n) {
+  Format8 g;
+  get_format8(f.desc, &g);
+  return round_one8(xv, g, variant, N, n);
+}
+
 bool variant8_ok(int variant, int nbits) {
   if (variant < VAR_RNE || variant > VAR_TA) return false;
   const bool draws = variant == VAR_SRFF || variant == VAR_SRF || variant == VAR_SRC || variant == VAR_SRC_ODD;
@@ -360,6 +391,8 @@ void store_code(void* out, uint64_t j, uint32_t code, const Format& f) {
   if (f.K == 16) ((uint16_t*)out)[j] = (uint16_t)code;
   else ((uint8_t*)out)[j] = (uint8_t)code;
 }
+
+bool is_8bit_target(int fmt) { return fmt == FMT_E4M3 || fmt == FMT_E5M2 || fmt == FMT_BINARY8P4; }
 
 bool args_ok(int fmt, int variant, int nbits, Format* f) {
   if (!get_format(fmt, f)) return false;
@@ -505,7 +538,7 @@ int oracle_round_from16(const uint16_t* x, void* out, uint64_t n, int src_fmt, i
                         int nbits, uint64_t seed, uint64_t offset) {
   Format f;
   if (!args_ok(fmt, variant, nbits, &f)) return 1;
-  if ((src_fmt != SRC_BF16 && src_fmt != SRC_FP16) || (fmt != FMT_E4M3 && fmt != FMT_E5M2)) return 1;
+  if ((src_fmt != SRC_BF16 && src_fmt != SRC_FP16) || !is_8bit_target(fmt)) return 1;
   for (uint64_t j = 0; j < n; ++j) {
     const uint64_t r = variant == VAR_RNE ? 0 : random_bits(seed, 0, offset + j, nbits);
     store_code(out, j, round_one(widen16(x[j], src_fmt), f, variant, nbits, r), f);
@@ -525,7 +558,7 @@ uint32_t oracle_widen16(uint16_t code, int src_fmt) {
 // which may be a power of two"; the paper fixes no rule for choosing it).  Reading taken: blocks of 32
 // consecutive elements of the call share the power-of-two scale 2^s with
 //   s = clamp(floor(log2 amax) - emax, -127, 127),  amax = max |x| over the block,
-//   emax = floor(log2 M) of the element format (8 for E4M3, 15 for E5M2),
+//   emax = floor(log2 M) of the element format (8 for E4M3, 15 for E5M2, 7 for binary8p4),
 // stored as the byte s + 127 (a pure-exponent code; 0xFF marks a block that holds a NaN or an
 // infinity, all of whose elements become the positive canonical NaN), and every element is
 // FBSR(x 2^-s) -- an exact scaling -- with the random bits of global index offset + j as in
@@ -534,7 +567,7 @@ uint32_t oracle_widen16(uint16_t code, int src_fmt) {
 int oracle_round_block_scaled(const float* x, uint8_t* out, uint8_t* scales, uint64_t n, int fmt, int variant,
                               int nbits, uint64_t seed, uint64_t offset) {
   Format f;
-  if (!args_ok(fmt, variant, nbits, &f) || (fmt != FMT_E4M3 && fmt != FMT_E5M2)) return 1;
+  if (!args_ok(fmt, variant, nbits, &f) || !is_8bit_target(fmt)) return 1;
   const int emax = std::ilogb(f.M);
   const uint64_t B = 32;
   for (uint64_t b0 = 0; b0 < n; b0 += B) {
@@ -584,7 +617,7 @@ int oracle_sgd_update(uint16_t* w, const float* g, uint64_t n, float lr, int var
 int oracle_qat_adamw_step(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, int fmt,
                           const float* p, int variant, int nbits, uint64_t seed, uint64_t step, uint64_t offset) {
   Format f;
-  if (!args_ok(fmt, variant, nbits, &f) || (fmt != FMT_E4M3 && fmt != FMT_E5M2)) return 1;
+  if (!args_ok(fmt, variant, nbits, &f) || !is_8bit_target(fmt)) return 1;
   const AdamW a = {p[0], p[1], p[2], p[3], p[4], p[5], p[6]};
   for (uint64_t j = 0; j < n; ++j) {
     const float w = (float)decode(w8[j], f);            // w16 <- w8 (exact)

@@ -15,12 +15,12 @@ LIB = os.path.join(_HERE, "liboracle_fbsr.so")
 # A test that plants a mistake in a COPY of the oracle points this at the mutated build.
 _OVERRIDE = os.environ.get("FBSR_ORACLE_LIB")
 
-FMT_BF16, FMT_E4M3, FMT_E5M2 = 0, 1, 2
+FMT_BF16, FMT_E4M3, FMT_E5M2, FMT_BINARY8P4 = 0, 1, 2, 3
 SRC_BF16, SRC_FP16 = 0, 1
 FROM_BF16, FROM_FP16, FROM_FP32 = 0, 1, 2  # source types of the generic-format entry points
 RNE, SRFF, SRF, SRC = 0, 1, 2, 3
 SRC_ODD, TNO, TA = 4, 5, 6                        # generic-format entry points only
-FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2"}
+FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2", FMT_BINARY8P4: "binary8p4"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
 
 

@@ -392,3 +392,57 @@ def test_qat_step_structure_in_binary8p4(oracle):
     assert list(out) == [0x00]
     out, _, _ = oracle.qat_adamw_step_format8(np.array([0x81], np.uint8), z[:1], z[:1], z[:1], E4M3, (0.75, 0.9, 0.999, 1e-8, 1.0, 0.1, 0.001), RNE, 0, 0, 1)
     assert list(out) == [0x80]
+
+
+# --------------------------------------------- binary8p4 as a target id of the fixed-format entries ----
+P4 = 3
+
+
+def test_binary8p4_target_id_follows_its_descriptor(oracle):
+    """Target id 3 (P3109 binary8p4) of round / round_from16 / block-scaled / QAT / statistics is the generic rule
+    under the binary8p4 descriptor: same codes as the descriptor entry points, same decode, ulp from Eq. (2)."""
+    rng = np.random.default_rng(12)
+    x = np.concatenate([rng.integers(0, 1 << 32, 3000, dtype=np.uint32).view(np.float32), inputs_below_max(rng, BINARY8P4, 3000),
+                        np.array([224.0, 232.0, np.nextafter(np.float32(232.0), np.float32(np.inf)), np.inf, -np.inf, np.nan, -0.0, -2.0 ** -20], dtype=np.float32)])
+    for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 2), (SRC, 4), (SRC, 16)):
+        for xv in x[::3]:
+            n = int(rng.integers(0, 1 << max(nbits, 1)))
+            assert oracle.round_with_n(xv, P4, variant, max(nbits, 1), n) == oracle.round_format8_with_n(xv, BINARY8P4, variant, max(nbits, 1), n)
+        assert np.array_equal(oracle.round_(x, P4, variant, nbits, seed=4, offset=9), oracle.round_format8(x, FROM_FP32, BINARY8P4, variant, nbits, 4, 9))
+        x16 = rng.integers(0, 1 << 16, 4000, dtype=np.uint16)
+        for src in (FROM_BF16, FROM_FP16):
+            assert np.array_equal(oracle.round_from16(x16, src, P4, variant, nbits, seed=4, offset=9),
+                                  oracle.round_format8(x16, src, BINARY8P4, variant, nbits, 4, 9))
+    for code in range(256):
+        a, b = oracle.decode(code, P4), oracle.decode_format8(code, BINARY8P4)
+        assert (math.isnan(a) and math.isnan(b)) or a == b
+    assert oracle.ulp(1.0, P4) == 0.125 and oracle.ulp(2.0 ** -9, P4) == 2.0 ** -10 and oracle.ulp(200.0, P4) == 16.0
+    # QAT: the fixed-id step equals the descriptor step
+    n = 4000
+    w8 = rng.integers(0, 256, n).astype(np.uint8)
+    g16, m16, v16 = _bf16_codes(rng.standard_normal(n) * 0.3), _bf16_codes(rng.standard_normal(n) * 0.05), _bf16_codes(rng.random(n) * 0.02)
+    params = (1e-2, 0.9, 0.999, 1e-8, 0.01, 0.1, 0.001)
+    for variant, nbits in ((RNE, 0), (SRFF, 3), (SRC, 3)):
+        a = oracle.qat_adamw_step(w8, g16, m16, v16, P4, params, variant, nbits, seed=7, step=5, offset=9)
+        b = oracle.qat_adamw_step_format8(w8, g16, m16, v16, BINARY8P4, params, variant, nbits, seed=7, step=5, offset=9)
+        assert all(np.array_equal(p, q) for p, q in zip(a, b))
+    # block-scaled: emax = 7, elements are the plain rounding of the scaled values, a NaN block is all 0x80
+    xb = (rng.standard_normal(32 * 50) * np.exp2(rng.integers(-20, 20, 32 * 50))).astype(np.float32)
+    xb[40] = np.nan
+    codes, scales = oracle.round_block_scaled(xb, P4, SRC, 3, seed=3, offset=64)
+    for b in range(50):
+        blk = xb[32 * b:32 * b + 32]
+        if b == 1:
+            assert scales[b] == 0xFF and np.all(codes[32:64] == 0x80)
+            continue
+        s = int(scales[b]) - 127
+        assert s == math.frexp(float(np.max(np.abs(blk))))[1] - 1 - 7
+        want = oracle.round_format8(np.ldexp(blk.astype(np.float64), -s).astype(np.float32), FROM_FP32, BINARY8P4, SRC, 3, 3, 64 + 32 * b)
+        assert np.array_equal(codes[32 * b:32 * b + 32], want)
+    # statistics: e = (y - x) / ulp with y decoded under the descriptor
+    xs = np.abs(x[np.isfinite(x)][:2000])
+    xs = xs[xs <= 224.0]
+    st, out = oracle.bias_stats(xs, P4, SRF, 3, 5, 0, xs.size, 0, 1, want_out=True)
+    y = np.array([oracle.decode_format8(int(c), BINARY8P4) for c in out])
+    e = (y - xs.astype(np.float64)) / np.array([oracle.ulp(v, P4) for v in xs])
+    assert st[0, 0] == xs.size and abs(st[0, 1] - y.sum()) <= 1e-9 * abs(y.sum()) and abs(st[0, 2] - e.sum()) < 1e-9 and abs(st[0, 3] - (e * e).sum()) < 1e-9
