@@ -261,7 +261,20 @@ def main():
             ms = timed_launches(torch, lambda: from16(f, v, nb), 12)
             paths["round_from_bf16_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
                 "ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
-        # generic-format path: the format Sec. IV trains in (P3109 binary8p4), from fp32 and from bf16 (N = 3)
+        # the format Sec. IV trains in (P3109 binary8p4) as a target id: hardware converts on 2 x
+        def p4round(v, nb):
+            turn[0] += 1
+            fbsr.fbsr_round(x_rot[fbsr.FMT_E4M3][turn[0] % 3], fbsr.FMT_BINARY8P4, v, nb, seed=2, offset=0, out=out_rot[turn[0] % 4])
+        for v, nb in ((fbsr.SRC, 3), (fbsr.SRFF, 8)):
+            ms = timed_launches(torch, lambda: p4round(v, nb), 12)
+            paths["round_binary8p4_N%d_%s" % (nb, fbsr.binding.VARIANT_NAMES[v])] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1)}
+
+        def p4from16(v, nb):
+            rot16[0] += 1
+            fbsr.fbsr_round_from16(x16[rot16[0] % 3], fbsr.SRC_BF16, fbsr.FMT_BINARY8P4, v, nb, seed=2, offset=0, out=out_rot[rot16[0] % 4])
+        ms = timed_launches(torch, lambda: p4from16(fbsr.SRC, 3), 12)
+        paths["round_from_bf16_binary8p4_N3_src"] = {"ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
+        # generic-format path (descriptor given at run time): the same format, from fp32 and from bf16 (N = 3)
         p4 = fbsr.format8_named("p3109_binary8p4")
         rotg = [0]
 
@@ -307,7 +320,24 @@ def main():
             ms = timed_launches(torch, lambda: qat(v), 12)
             paths["qat_adamw_e4m3_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
                 "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
-        # the same step with the weights in P3109 binary8p4 (the format Sec. IV trains in), decoded through a table
+        # the same step with the weights in P3109 binary8p4 (the format Sec. IV trains in): as a target id ...
+        # (fresh weights: a byte 0x80, E4M3's -0 left behind by the runs above, is binary8p4's NaN)
+        for k in range(3):
+            qs[k][0].copy_(torch.from_numpy((workloads.sgd_weights(nq, seed=60 + k) & 0x7777).view(np.uint8)[:nq].copy()))
+
+        def qatp4(v):
+            tq[0] += 1
+            w8_, g_, m_, v_ = qs[tq[0] % 3]
+            t = 1 + tq[0] // 3
+            fbsr.fbsr_qat_adamw_step(w8_, g_, m_, v_, fbsr.FMT_BINARY8P4, (1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9 ** t, 1 - 0.999 ** t),
+                                     v, 3, seed=6, step=t)
+        for v in (fbsr.SRC, fbsr.SRFF):
+            ms = timed_launches(torch, lambda: qatp4(v), 12)
+            paths["qat_adamw_binary8p4_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
+                "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
+        # ... and through the generic entry point (descriptor at run time, weights decoded through a table)
+        for k in range(3):
+            qs[k][0].copy_(torch.from_numpy((workloads.sgd_weights(nq, seed=60 + k) & 0x7777).view(np.uint8)[:nq].copy()))
         p4q = fbsr.format8_named("p3109_binary8p4")
 
         def qat8(v):
@@ -318,7 +348,7 @@ def main():
                                              v, 3, seed=6, step=t)
         for v in (fbsr.SRC, fbsr.SRFF):
             ms = timed_launches(torch, lambda: qat8(v), 12)
-            paths["qat_adamw_binary8p4_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
+            paths["qat_adamw_format8_binary8p4_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
                 "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
         del qs
         ns = min(SGD_ELEMS, n)

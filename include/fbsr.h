@@ -36,11 +36,16 @@
 extern "C" {
 #endif
 
-/* Target formats (Sec. II).  Codes are uint16 for BF16, uint8 for the fp8 formats. */
+/* Target formats (Sec. II).  Codes are uint16 for BF16, uint8 for the 8-bit formats. */
 typedef enum {
-  FBSR_FMT_BF16 = 0, /* K=16 P=8 B=127, M=(2-2^-7)*2^127, has infinities               */
-  FBSR_FMT_E4M3 = 1, /* OCP E4M3: K=8 P=4 B=7, M=448, no infinities, S.1111.111 is NaN  */
-  FBSR_FMT_E5M2 = 2  /* OCP E5M2: K=8 P=3 B=15, M=57344, has infinities                 */
+  FBSR_FMT_BF16 = 0,     /* K=16 P=8 B=127, M=(2-2^-7)*2^127, has infinities               */
+  FBSR_FMT_E4M3 = 1,     /* OCP E4M3: K=8 P=4 B=7, M=448, no infinities, S.1111.111 is NaN  */
+  FBSR_FMT_E5M2 = 2,     /* OCP E5M2: K=8 P=3 B=15, M=57344, has infinities                 */
+  FBSR_FMT_BINARY8P4 = 3 /* IEEE WG P3109 (interim report) binary8p4, the format Sec. IV trains in: K=8 P=4 B=8,
+                            M=224, infinities 0x7F / 0xFF, 0x80 the only NaN, no negative zero.  Rounded by the
+                            rules of fbsr_round_format8 under the descriptor "p3109_binary8p4": above M nearest
+                            even (the tie 232 stays at M, anything above goes to infinity), NaN -> 0x80 whatever
+                            its sign, a negative input that rounds to zero -> 0x00                             */
 } fbsr_fmt;
 
 /* Rounding predicates (delta = fractional part of the scaled significand, Sec. II-A Eq. (5);
@@ -88,7 +93,7 @@ int fbsr_round(const float* x, void* out, uint64_t n, int fmt, int variant, int 
  * exactly (bf16 -> E4M3 has D = 4, bf16 -> E5M2 D = 5, binary16 -> E4M3 D = 7, binary16 -> E5M2
  * D = 8).  nbits may exceed D; all variants then coincide with exact SR (App. A-C).
  * x: n 16-bit codes of src_fmt (device, read, 2-byte aligned).  out: n fp8 codes (device, written).
- * fmt must be FBSR_FMT_E4M3 or FBSR_FMT_E5M2 (else FBSR_EINVAL).  Other errors as fbsr_round. */
+ * fmt must be one of the 8-bit formats (else FBSR_EINVAL).  Other errors as fbsr_round. */
 int fbsr_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt, int variant, int nbits,
                       uint64_t seed, uint64_t offset, void* stream);
 
@@ -114,7 +119,8 @@ int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, 
  * exceeds M there follows fbsr_round's out-of-range rule.  A block of zeros has s = -127.  A block that
  * holds a NaN or an infinity gets scales[b] = 0xFF and all its elements the positive canonical NaN.
  * x: n floats (device, read).  out: n fp8 codes (device, written).  scales: ceil(n / 32) bytes (device,
- * written).  fmt must be FBSR_FMT_E4M3 or FBSR_FMT_E5M2.  Errors as fbsr_round. */
+ * written).  fmt must be one of the 8-bit formats (emax = 7 for binary8p4, whose elements above M follow its own
+ * out-of-range rule).  Errors as fbsr_round. */
 int fbsr_round_block_scaled(const float* x, void* out, void* scales, uint64_t n, int fmt, int variant,
                             int nbits, uint64_t seed, uint64_t offset, void* stream);
 
@@ -135,7 +141,7 @@ typedef struct {
  *   w8 <- FBSR_fmt(s)  with the random bits of (seed, step, offset + j), as in fbsr_round_from16.
  * So the value handed to the 8-bit rounding has bf16 precision: D = 4 excess bits for E4M3 (the count
  * Sec. IV reasons with), 5 for E5M2.  A NaN produced anywhere is stored as the positive canonical NaN.
- * w8: n codes of fmt (E4M3 or E5M2; device, updated in place).  g16: n bf16 gradients (device, read).
+ * w8: n codes of fmt (an 8-bit format; device, updated in place).  g16: n bf16 gradients (device, read).
  * m16, v16: n bf16 moments (device, updated in place).  p: HOST pointer, read during the call.
  * Errors: FBSR_EINVAL (fmt not fp8, bad variant / nbits, null pointer), FBSR_EALIGN (16-bit arrays need
  * 2-byte alignment), FBSR_EDEVICE. */

@@ -8,7 +8,9 @@
 
 namespace {
 
-bool valid_fmt(int fmt) { return fmt == FBSR_FMT_BF16 || fmt == FBSR_FMT_E4M3 || fmt == FBSR_FMT_E5M2; }
+bool valid_fmt(int fmt) { return fmt >= FBSR_FMT_BF16 && fmt <= FBSR_FMT_BINARY8P4; }
+
+bool is_8bit_fmt(int fmt) { return fmt == FBSR_FMT_E4M3 || fmt == FBSR_FMT_E5M2 || fmt == FBSR_FMT_BINARY8P4; }
 
 int check_common(int variant, int nbits, uint64_t n, uint64_t offset) {
   if (variant < FBSR_RNE || variant > FBSR_SRC) return FBSR_EINVAL;
@@ -131,7 +133,7 @@ int fbsr_round(const float* x, void* out, uint64_t n, int fmt, int variant, int 
 
 int fbsr_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt, int variant, int nbits,
                       uint64_t seed, uint64_t offset, void* stream) {
-  if (fmt != FBSR_FMT_E4M3 && fmt != FBSR_FMT_E5M2) return FBSR_EINVAL;
+  if (!is_8bit_fmt(fmt)) return FBSR_EINVAL;
   if (src_fmt != FBSR_SRC_BF16 && src_fmt != FBSR_SRC_FP16) return FBSR_EINVAL;
   const int c = check_common(variant, nbits, n, offset);
   if (c != FBSR_OK) return c;
@@ -157,7 +159,7 @@ int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, 
 
 int fbsr_round_block_scaled(const float* x, void* out, void* scales, uint64_t n, int fmt, int variant, int nbits,
                             uint64_t seed, uint64_t offset, void* stream) {
-  if (fmt != FBSR_FMT_E4M3 && fmt != FBSR_FMT_E5M2) return FBSR_EINVAL;
+  if (!is_8bit_fmt(fmt)) return FBSR_EINVAL;
   const int c = check_common(variant, nbits, n, offset);
   if (c != FBSR_OK) return c;
   if (n == 0) return FBSR_OK;
@@ -171,7 +173,7 @@ int fbsr_round_block_scaled(const float* x, void* out, void* scales, uint64_t n,
 
 int fbsr_qat_adamw_step(void* w8, const void* g16, void* m16, void* v16, uint64_t n, int fmt, const fbsr_adamw* p,
                         int variant, int nbits, uint64_t seed, uint64_t step, uint64_t offset, void* stream) {
-  if (fmt != FBSR_FMT_E4M3 && fmt != FBSR_FMT_E5M2) return FBSR_EINVAL;
+  if (!is_8bit_fmt(fmt)) return FBSR_EINVAL;
   const int c = check_common(variant, nbits, n, offset);
   if (c != FBSR_OK) return c;
   if (p == nullptr) return FBSR_EINVAL;

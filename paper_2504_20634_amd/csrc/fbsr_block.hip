@@ -10,6 +10,7 @@ constexpr int kScaleBlock = 32;
 template <int FMT> struct Emax;
 template <> struct Emax<kE4M3> { static constexpr int value = 8; };
 template <> struct Emax<kE5M2> { static constexpr int value = 15; };
+template <> struct Emax<kP4> { static constexpr int value = 7; };
 
 // From the largest |x| pattern of a block: the scale exponent s (clamped to [-127, 127]) and whether
 // the block holds a NaN or an infinity.  A pattern's exponent field is floor(log2) + 127 for normal
@@ -182,7 +183,8 @@ hipError_t run_v(int variant, const float* x, uint8_t* out, uint8_t* scales, uin
 hipError_t launch_round_block_scaled(const float* x, uint8_t* out, uint8_t* scales, uint64_t n, int fmt, int variant,
                                      int nbits, uint64_t seed, uint64_t offset, hipStream_t stream) {
   if (fmt == kE4M3) return run_v<kE4M3>(variant, x, out, scales, n, nbits, seed, offset, stream);
-  return run_v<kE5M2>(variant, x, out, scales, n, nbits, seed, offset, stream);
+  if (fmt == kE5M2) return run_v<kE5M2>(variant, x, out, scales, n, nbits, seed, offset, stream);
+  return run_v<kP4>(variant, x, out, scales, n, nbits, seed, offset, stream);
 }
 
 }  // namespace fbsr

@@ -27,7 +27,7 @@ __device__ __forceinline__ f32x4 load_stream4(const float* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
 }
 
-enum : int { kBF16 = 0, kE4M3 = 1, kE5M2 = 2 };
+enum : int { kBF16 = 0, kE4M3 = 1, kE5M2 = 2, kP4 = 3 };   // kP4: IEEE WG P3109 binary8p4
 enum : int { kRNE = 0, kSRFF = 1, kSRF = 2, kSRC = 3 };
 enum : int { kSrcBF16 = 0, kSrcFP16 = 1, kSrcFP32 = 2 };
 
@@ -80,6 +80,7 @@ template <> struct Fx<kBF16> {
   static constexpr int FRAC = 16;
   static constexpr int P = 8, B = 127;
   static constexpr uint32_t U_MAXFIN = 0x7F7F0000u;
+  static constexpr uint32_t U_UNCHECKED = U_MAXFIN;   // the largest pattern the unchecked paths accept
   static constexpr uint32_t NAN_FX = 0x7FC00000u;
   static constexpr bool kIsFp8 = false;
   typedef uint16_t code_t;
@@ -98,6 +99,8 @@ template <> struct Fx<kE4M3> {
   static constexpr uint32_t U_SUB = 121u << 23;       // 2^-6, smallest normal
   static constexpr float SUB_SCALE = 0x1p33f;         // 1 / (2^-9 subnormal spacing) * 2^FRAC
   static constexpr bool kDetRegion = false;
+  static constexpr uint32_t DET_ADD = 0;
+  static constexpr uint32_t U_UNCHECKED = 0x7F800000u;   // every non-NaN pattern
   static constexpr uint32_t NAN_FX = 0x7F000000u;
   static constexpr uint32_t INF_CODE = 0x100u;        // none
   static constexpr bool kIsFp8 = true;
@@ -113,8 +116,32 @@ template <> struct Fx<kE5M2> {
   static constexpr uint32_t U_SUB = 113u << 23;       // 2^-14
   static constexpr float SUB_SCALE = 0x1p40f;         // 1 / 2^-16 * 2^FRAC
   static constexpr bool kDetRegion = true;            // (M, 61440): nearest is M; >= 61440: inf
+  static constexpr uint32_t DET_ADD = 1u << 23;       // one half: M's significand is odd, the tie goes up
+  static constexpr uint32_t U_UNCHECKED = 0x7F800000u;
   static constexpr uint32_t NAN_FX = 0x7E000000u;
   static constexpr uint32_t INF_CODE = 0x7Cu;
+  static constexpr bool kIsFp8 = true;
+  typedef uint8_t code_t;
+};
+
+// IEEE WG P3109 binary8p4 (the format Sec. IV trains in): the value set of OCP E4M3 scaled by one half
+// (bias 8 instead of 7, M = 224 at the same code 0x7E), but with infinities at 0x7F / 0xFF, one NaN at
+// 0x80 and no negative zero.  Above M the clamp is M + 3/4 ulp(M) and the addend the nearest-even one
+// for an even significand (224 = 14 * 16), so the tie 232 stays at M and everything above carries into
+// 0x7F.  The NaN code is the sign bit alone, which is what NAN_FX | sign gives for either sign.
+template <> struct Fx<kP4> {
+  static constexpr int FRAC = 24;
+  static constexpr int P = 4, B = 8;
+  static constexpr uint32_t Q = 119, S = 4;
+  static constexpr uint32_t U_MAXFIN = 0x43600000u;   // 224
+  static constexpr uint32_t U_CLAMP = 0x436C0000u;    // 236 = M + 3/4 ulp(M): maps to code 126.75
+  static constexpr uint32_t U_SUB = 120u << 23;       // 2^-7, smallest normal
+  static constexpr float SUB_SCALE = 0x1p34f;         // 1 / (2^-10 subnormal spacing) * 2^FRAC
+  static constexpr bool kDetRegion = true;
+  static constexpr uint32_t DET_ADD = (1u << 23) - 1u;
+  static constexpr uint32_t U_UNCHECKED = 0x7F800000u;
+  static constexpr uint32_t NAN_FX = 0x80000000u;
+  static constexpr uint32_t INF_CODE = 0x7Fu;
   static constexpr bool kIsFp8 = true;
   typedef uint8_t code_t;
 };
@@ -179,10 +206,10 @@ __device__ __forceinline__ uint32_t round_magnitude(uint32_t bits, uint32_t r0, 
   uint32_t add = n << a.shift;
   if constexpr (VAR == kSRF) add += a.fixed;
   if constexpr (VAR == kSRC || VAR == kRNE) add += a.fixed + ((r0 >> a.shift) & a.tie_mask);
-  // |x| > M: no randomness, round to nearest on the unbounded grid (Sec. II).  M's significand
-  // is odd in both formats that have this region, so the tie goes up, i.e. "add one half".
+  // |x| > M: no randomness, round to nearest even on the unbounded grid (Sec. II): the addend is
+  // one half where M's significand is odd (the tie goes up), one half minus one last place where it is even.
   if constexpr (F::kIsFp8) {
-    if constexpr (F::kDetRegion) add = u > F::U_MAXFIN ? (1u << (F::FRAC - 1)) : add;
+    if constexpr (F::kDetRegion) add = u > F::U_MAXFIN ? F::DET_ADD : add;
   } else if constexpr (CHECKED) {
     add = u > F::U_MAXFIN ? (1u << (F::FRAC - 1)) : add;
   }
@@ -195,13 +222,19 @@ __device__ __forceinline__ uint32_t round_magnitude(uint32_t bits, uint32_t r0, 
 // bits are garbage.
 template <int FMT, int VAR, bool CHECKED>
 __device__ __forceinline__ uint32_t round_pattern(uint32_t bits, uint32_t n, const Addends& a) {
-  return round_magnitude<FMT, VAR, CHECKED>(bits, to_code_space<FMT, VAR>(bits), n, a) | (bits & 0x80000000u);
+  const uint32_t mag = round_magnitude<FMT, VAR, CHECKED>(bits, to_code_space<FMT, VAR>(bits), n, a);
+  if constexpr (FMT == kP4) {
+    // no negative zero: a zero magnitude drops the sign (the NaN code, bit 31 alone, passes unchanged)
+    return (mag & 0x7F000000u) != 0u ? (mag | (bits & 0x80000000u)) : mag;
+  } else {
+    return mag | (bits & 0x80000000u);
+  }
 }
 
 // True when round_pattern<.., CHECKED = false> is not allowed for this pattern.
 template <int FMT>
 __device__ __forceinline__ bool needs_checked(uint32_t u_max) {
-  return u_max > (Fx<FMT>::kIsFp8 ? 0x7F800000u : Fx<FMT>::U_MAXFIN);
+  return u_max > Fx<FMT>::U_UNCHECKED;
 }
 
 constexpr int kWavesPerBlock = 4;
@@ -308,6 +341,10 @@ __device__ __forceinline__ uint32_t slot_bits(uint64_t row_bits, int j, uint32_t
 //         replaced by one half, which gives M below 61440 and inf from there on;
 //   NaN comes back with the sign bit set -> NaN inputs never reach this path (the caller's
 //         wave-uniform check sends them to the integer path).
+// binary8p4 uses the E4M3 convert on 2 x (an exact doubling: the two value sets differ by that factor and
+// share their codes up to M = 0x7E); the clamp to +-448 turns every |x| > M into 0x7E, whose last bit is
+// then set for |x| > 232 (the infinity 0x7F; the tie 232 itself stays at M, whose significand is even);
+// a negative zero result loses its sign.
 struct HwAddends {
   uint32_t nbits;     // N
   uint32_t shift;     // 32 - N
@@ -331,26 +368,32 @@ template <int FMT, int VAR>
 __device__ __forceinline__ uint32_t round4_fp8_hw(const uint32_t (&bits)[4], const uint32_t (&n)[4], const HwAddends& h) {
   typedef Fx<FMT> F;
   static_assert(F::kIsFp8 && VAR != kRNE, "hardware path: fp8 targets, stochastic variants");
+  constexpr uint32_t kSubField = FMT == kP4 ? Fx<kE4M3>::U_SUB : F::U_SUB;   // binary8p4 works on 2 x in E4M3 terms
   int packed = 0;
+  uint32_t to_inf = 0;   // binary8p4: the last bit of every byte whose |x| lies above the overflow tie
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     float x = __uint_as_float(bits[j]);
     uint32_t rnd = (n[j] << h.shift) | h.half;
-    if constexpr (FMT == kE4M3) x = __builtin_amdgcn_fmed3f(x, -448.0f, 448.0f);
+    if constexpr (FMT == kP4) {
+      to_inf |= fabsf(x) > 232.0f ? (1u << (8 * j)) : 0u;
+      x = x + x;
+    }
+    if constexpr (FMT == kE4M3 || FMT == kP4) x = __builtin_amdgcn_fmed3f(x, -448.0f, 448.0f);
     bool over = false;
     if constexpr (FMT == kE5M2) over = fabsf(x) > 57344.0f;
     if constexpr (VAR == kSRC) {
       // C = 2^(e~ + 24 - P - N): adding and subtracting it rounds |x| to a multiple of
       // 2^(e~ - (P - 1) - N), nearest-even (the inner Round of Eq. (7))
       const uint32_t ef = __float_as_uint(x) & 0x7F800000u;   // after the clamp
-      const uint32_t c_bits = (ef > F::U_SUB ? ef : F::U_SUB) + h.grid_exp;
+      const uint32_t c_bits = (ef > kSubField ? ef : kSubField) + h.grid_exp;
       const float c = __uint_as_float(c_bits);
       const float t = (fabsf(x) + c) - c;
       const float pre = __uint_as_float((__float_as_uint(t) & 0x7FFFFFFFu) | (bits[j] & 0x80000000u));
       x = over ? x : pre;
     }
     if constexpr (FMT == kE5M2) rnd = over ? 0x80000000u : rnd;
-    if constexpr (FMT == kE4M3) {
+    if constexpr (FMT == kE4M3 || FMT == kP4) {
       if (j == 0) packed = __builtin_amdgcn_cvt_sr_fp8_f32(x, (int)rnd, packed, 0);
       if (j == 1) packed = __builtin_amdgcn_cvt_sr_fp8_f32(x, (int)rnd, packed, 1);
       if (j == 2) packed = __builtin_amdgcn_cvt_sr_fp8_f32(x, (int)rnd, packed, 2);
@@ -362,7 +405,31 @@ __device__ __forceinline__ uint32_t round4_fp8_hw(const uint32_t (&bits)[4], con
       if (j == 3) packed = __builtin_amdgcn_cvt_sr_bf8_f32(x, (int)rnd, packed, 3);
     }
   }
+  if constexpr (FMT == kP4) {
+    packed |= (int)to_inf;
+    // bytes with a zero magnitude lose their sign bit
+    const uint32_t m = (uint32_t)packed & 0x7F7F7F7Fu;
+    const uint32_t nonzero = ((m + 0x7F7F7F7Fu) | m) & 0x80808080u;   // 0x80 in every byte whose magnitude is not zero
+    return (uint32_t)packed & (nonzero | 0x7F7F7F7Fu);
+  }
   return (uint32_t)packed;
+}
+
+// Exact value of an 8-bit code (Eq. (1)); the hardware decodes agree with it on all 256 OCP codes, and
+// binary8p4's finite values are one half of E4M3's at the same code.
+template <int FMT>
+__device__ __forceinline__ float fp8_code_value(uint32_t code) {
+  if constexpr (FMT == kE4M3) {
+    return __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
+  } else if constexpr (FMT == kE5M2) {
+    return __builtin_amdgcn_cvt_f32_bf8((int)code, 0);
+  } else {
+    const uint32_t c = code & 0xFFu;
+    const float finite = 0.5f * __builtin_amdgcn_cvt_f32_fp8((int)c, 0);
+    const float inf = __uint_as_float(0x7F800000u | ((c & 0x80u) << 24));
+    const float v = (c & 0x7Fu) == 0x7Fu ? inf : finite;
+    return c == 0x80u ? __uint_as_float(0x7FC00000u) : v;
+  }
 }
 
 // ----------------------------------------------------------- generic formats, K <= 8 ---

@@ -53,6 +53,8 @@ __device__ __forceinline__ float qat_update(float w, float mq, float vq, const A
 //   nbits()         N
 //   value<J>(lo,hi) value of element J of eight packed codes (main path)
 //   value_of(code)  value of one code
+//   suspicious(lo, hi)  the eight weight codes hold one that value<J> does not decode
+//   must_recompute(sa, sb)  the sums may not go through round4 (a NaN)
 //   round4(b, n)    four bf16-valued fp32 patterns, none a NaN -> four packed codes
 //   round1(s16, n)  one bf16 code (a NaN is the canonical positive one) -> code
 template <int FMT, int VAR>
@@ -69,17 +71,28 @@ struct FixedCodec {
     if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(a.nbits);
   }
   __device__ __forceinline__ uint32_t nbits() const { return a8.nbits; }
-  // the hardware decode agrees with Eq. (1) on all 256 codes
+  // the hardware decode agrees with Eq. (1) on all 256 OCP codes; binary8p4's finite values are one half of
+  // E4M3's at the same code (its infinities come back as NaN, which sends the wave to value_of, and its NaN
+  // 0x80 as -0: see suspicious)
   template <int J>
   __device__ __forceinline__ float value(int lo, int hi) const {
     const int word = J < 4 ? lo : hi;
     if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8(word, J & 3);
+    else if constexpr (FMT == kP4) return 0.5f * __builtin_amdgcn_cvt_f32_fp8(word, J & 3);
     else return __builtin_amdgcn_cvt_f32_bf8(word, J & 3);
   }
-  __device__ __forceinline__ float value_of(uint32_t code) const {
-    if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
-    else return __builtin_amdgcn_cvt_f32_bf8((int)code, 0);
+  __device__ __forceinline__ float value_of(uint32_t code) const { return fp8_code_value<FMT>(code); }
+  // true when the main path may not be used for these eight weight codes
+  __device__ __forceinline__ bool suspicious(uint32_t lo, uint32_t hi) const {
+    if constexpr (FMT == kP4) {   // a byte 0x80 (NaN) anywhere
+      const uint32_t a = lo ^ 0x80808080u, b = hi ^ 0x80808080u;
+      return (((a - 0x01010101u) & ~a) | ((b - 0x01010101u) & ~b)) & 0x80808080u;
+    } else {
+      return false;
+    }
   }
+  // true when the pair of sums may not go through round4: a NaN
+  __device__ __forceinline__ bool must_recompute(float sa, float sb) const { return __builtin_isunordered(sa, sb); }
   __device__ __forceinline__ uint32_t round4(const uint32_t (&b)[4], const uint32_t (&n)[4]) const {
     if constexpr (VAR != kRNE) {
       return round4_fp8_hw<FMT, VAR>(b, n, hw);
@@ -114,6 +127,8 @@ struct Codec8 {
     return table[(word >> (8 * (J & 3))) & 0xFFu];
   }
   __device__ __forceinline__ float value_of(uint32_t code) const { return table[code & 0xFFu]; }
+  __device__ __forceinline__ bool suspicious(uint32_t, uint32_t) const { return false; }
+  __device__ __forceinline__ bool must_recompute(float sa, float sb) const { return __builtin_isunordered(sa, sb); }
   __device__ __forceinline__ uint32_t round4(const uint32_t (&b)[4], const uint32_t (&n)[4]) const {
     return round4_bytes<TIES>(b, n, false, f, m);
   }
@@ -176,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
   const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w}, mw[4] = {mq.x, mq.y, mq.z, mq.w}, vw[4] = {vq.x, vq.y, vq.z, vq.w};
   const int wlo = (int)(uint32_t)wq, whi = (int)(uint32_t)(wq >> 32);
   uint32_t mo[4], vo[4], so[4];
-  bool nan_seen = false;
+  bool nan_seen = c.suspicious((uint32_t)wlo, (uint32_t)whi);
   auto do_pair = [&](auto hc) {   // elements 2h (low halves) and 2h + 1 (high halves)
     constexpr int h = decltype(hc)::value;
     const float wa = c.template value<2 * h>(wlo, whi), wb = c.template value<2 * h + 1>(wlo, whi);
@@ -187,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
     vo[h] = bf16_pair_hw(v1a, v1b);
     const uint32_t uo = bf16_pair_hw(qat_update(wa, bf16_lo(mo[h]), bf16_lo(vo[h]), p), qat_update(wb, bf16_hi(mo[h]), bf16_hi(vo[h]), p));
     const float sa = wa + bf16_lo(uo), sb = wb + bf16_hi(uo);
-    nan_seen = nan_seen || __builtin_isunordered(sa, sb);   // a NaN weight, moment or update always reaches the sum
+    nan_seen = nan_seen || c.must_recompute(sa, sb);   // a NaN weight, moment or update always reaches the sum
     so[h] = bf16_pair_hw(sa, sb);
   };
   do_pair(std::integral_constant<int, 0>{});
@@ -332,7 +347,8 @@ hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uin
                             const AdamWScalars& p, int variant, int nbits, uint64_t seed, uint64_t step,
                             uint64_t offset, hipStream_t stream) {
   if (fmt == kE4M3) return run_v<kE4M3>(variant, w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
-  return run_v<kE5M2>(variant, w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+  if (fmt == kE5M2) return run_v<kE5M2>(variant, w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
+  return run_v<kP4>(variant, w8, g16, m16, v16, n, p, nbits, seed, step, offset, stream);
 }
 
 hipError_t launch_qat_adamw_format8(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,

@@ -159,7 +159,8 @@ hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int vari
   switch (fmt) {
     case kBF16: return run_v<kBF16>(variant, x, out, n, nbits, seed, offset, stream);
     case kE4M3: return run_v<kE4M3>(variant, x, out, n, nbits, seed, offset, stream);
-    default: return run_v<kE5M2>(variant, x, out, n, nbits, seed, offset, stream);
+    case kE5M2: return run_v<kE5M2>(variant, x, out, n, nbits, seed, offset, stream);
+    default: return run_v<kP4>(variant, x, out, n, nbits, seed, offset, stream);
   }
 }
 

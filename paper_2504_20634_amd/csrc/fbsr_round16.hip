@@ -137,7 +137,8 @@ template <int SRC>
 hipError_t run_f(int fmt, int variant, const uint16_t* x, uint8_t* out, uint64_t n, int nbits, uint64_t seed,
                  uint64_t offset, hipStream_t stream) {
   if (fmt == kE4M3) return run_v<SRC, kE4M3>(variant, x, out, n, nbits, seed, offset, stream);
-  return run_v<SRC, kE5M2>(variant, x, out, n, nbits, seed, offset, stream);
+  if (fmt == kE5M2) return run_v<SRC, kE5M2>(variant, x, out, n, nbits, seed, offset, stream);
+  return run_v<SRC, kP4>(variant, x, out, n, nbits, seed, offset, stream);
 }
 
 }  // namespace

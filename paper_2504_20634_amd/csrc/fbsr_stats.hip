@@ -29,6 +29,8 @@ __device__ __forceinline__ float decode_top(uint32_t r) {
   typedef Fx<FMT> F;
   if constexpr (!F::kIsFp8) {
     return __uint_as_float(r & 0xFFFF0000u);
+  } else if constexpr (FMT == kP4) {
+    return fp8_code_value<kP4>(r >> 24);
   } else {
     const uint32_t c = (r >> 24) & 0x7Fu;
     const uint32_t e = c >> (F::P - 1);
@@ -78,9 +80,13 @@ __device__ __forceinline__ void accumulate(Acc& acc, uint32_t bits, float y) {
 // The four decoded values of a packed fp8 word (the hardware decode equals Eq. (1) on all 256 codes).
 template <int FMT>
 __device__ __forceinline__ void decode4(uint32_t packed, float (&y)[4]) {
-  if constexpr (FMT == kE4M3) {
+  if constexpr (FMT == kE4M3 || FMT == kP4) {
     y[0] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 0); y[1] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 1);
     y[2] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 2); y[3] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 3);
+    if constexpr (FMT == kP4) {   // finite binary8p4 values are one half of E4M3's at the same code
+#pragma unroll
+      for (int j = 0; j < 4; ++j) y[j] *= 0.5f;
+    }
   } else {
     y[0] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 0); y[1] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 1);
     y[2] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 2); y[3] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 3);
@@ -393,7 +399,8 @@ hipError_t launch_stats(const float* x, void* out, uint64_t n, int fmt, int vari
   switch (fmt) {
     case kBF16: return run_v<kBF16>(variant, x, out, n, nbits, seed, offset, group, first_bin, stats, workspace, stream);
     case kE4M3: return run_v<kE4M3>(variant, x, out, n, nbits, seed, offset, group, first_bin, stats, workspace, stream);
-    default: return run_v<kE5M2>(variant, x, out, n, nbits, seed, offset, group, first_bin, stats, workspace, stream);
+    case kE5M2: return run_v<kE5M2>(variant, x, out, n, nbits, seed, offset, group, first_bin, stats, workspace, stream);
+    default: return run_v<kP4>(variant, x, out, n, nbits, seed, offset, group, first_bin, stats, workspace, stream);
   }
 }
 

@@ -39,6 +39,7 @@ def test_enums_match_the_header():
     from paper_2504_20634_amd import binding as b
     text = open(HEADER).read()
     for name, val in (("FBSR_FMT_BF16", b.FMT_BF16), ("FBSR_FMT_E4M3", b.FMT_E4M3), ("FBSR_FMT_E5M2", b.FMT_E5M2),
+                      ("FBSR_FMT_BINARY8P4", b.FMT_BINARY8P4),
                       ("FBSR_RNE", b.RNE), ("FBSR_SRFF", b.SRFF), ("FBSR_SRF", b.SRF), ("FBSR_SRC", b.SRC),
                       ("FBSR_OK", b.OK), ("FBSR_EINVAL", b.EINVAL), ("FBSR_EALIGN", b.EALIGN),
                       ("FBSR_ERANGE", b.ERANGE), ("FBSR_EDEVICE", b.EDEVICE)):
@@ -65,12 +66,12 @@ def test_argument_validation_happens_on_the_host(L):
     assert L.fbsr_sgd_update(None, None, 0, 0.1, 1, 2, 0, 0, 0, None) == OK
     assert L.fbsr_bias_stats(None, None, 0, 0, 1, 2, 0, 0, 1, 0, 1, None, None, 0, None) == OK
     # bad enums / nbits
-    for fmt, var, nb in ((3, 1, 2), (-1, 1, 2), (0, 4, 2), (0, -1, 2), (0, 1, 0), (0, 2, 17), (1, 3, -5)):
+    for fmt, var, nb in ((4, 1, 2), (-1, 1, 2), (0, 4, 2), (0, -1, 2), (0, 1, 0), (0, 2, 17), (1, 3, -5)):
         assert L.fbsr_round(p(good), p(good), 8, fmt, var, nb, 0, 0, None) == EINVAL
         assert L.fbsr_bias_stats(p(good), None, 8, fmt, var, nb, 0, 0, 4, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
     assert L.fbsr_sgd_update(p(good), p(good), 8, 0.1, 5, 2, 0, 0, 0, None) == EINVAL
     assert L.fbsr_sgd_update(p(good), p(good), 8, 0.1, 1, 99, 0, 0, 0, None) == EINVAL
-    for src, fmt in ((2, 1), (0, 0), (1, 3), (-1, 2)):
+    for src, fmt in ((2, 1), (0, 0), (1, 4), (-1, 2)):
         assert L.fbsr_round_from16(p(good), p(good), 8, src, fmt, 1, 2, 0, 0, None) == EINVAL
     assert L.fbsr_round_from16(None, None, 0, 0, 1, 1, 2, 0, 0, None) == OK
     assert L.fbsr_round_from16(p(good + 1), p(good), 8, 0, 1, 1, 2, 0, 0, None) == EALIGN

@@ -38,7 +38,7 @@ def _oracle(oracle, x, fmt, variant, nbits, seed, offset, threads=16):
     return np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
 
 
-@pytest.mark.parametrize("fmt", [E4M3, E5M2])
+@pytest.mark.parametrize("fmt", [E4M3, E5M2, 3])
 def test_sizes_variants_offsets(fbsr, oracle, fmt):
     for n in (0, 1, 31, 32, 33, 2047, 2048, 2049, 5 * 2048 + 77):
         x = _inputs(max(n, 1), 7 + n)[:n]

@@ -102,13 +102,14 @@ def test_sizes_offsets_alignment(fbsr, oracle, n):
                     assert first_mismatch(got, want) is None, first_mismatch(got, want)
 
 
-def test_ocp_descriptors_equal_the_fixed_format_entry_points(fbsr):
-    """fbsr_round / fbsr_round_from16 (hardware converts) and the generic integer path give the same bytes."""
+def test_named_descriptors_equal_the_fixed_format_entry_points(fbsr):
+    """fbsr_round / fbsr_round_from16 (hardware converts) and the generic integer path give the same bytes for the
+    three formats that exist as target ids."""
     rng = np.random.default_rng(9)
     n = 1 << 22
     x = torch.from_numpy(rng.integers(0, 1 << 32, n, dtype=np.uint32).view(np.int32)).cuda().view(torch.float32)
     x16 = torch.from_numpy(rng.integers(0, 1 << 16, n, dtype=np.uint16).view(np.int16)).cuda()
-    for fmt, name in ((1, "ocp_e4m3"), (2, "ocp_e5m2")):
+    for fmt, name in ((1, "ocp_e4m3"), (2, "ocp_e5m2"), (3, "p3109_binary8p4")):
         d = fbsr.format8_named(name)
         for variant, nbits in ((RNE, 0), (SRFF, 2), (SRF, 4), (SRC, 8), (SRFF, 16), (SRC, 3)):
             print("case fmt=%s variant=%d nbits=%d" % (name, variant, nbits), flush=True)

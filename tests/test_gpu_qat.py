@@ -48,7 +48,7 @@ PARAMS = [(1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9, 1 - 0.999),
           (0.5, 0.0, 0.5, 1e-3, 0.0, 1.0, 0.5)]
 
 
-@pytest.mark.parametrize("fmt", [E4M3, E5M2])
+@pytest.mark.parametrize("fmt", [E4M3, E5M2, 3])
 def test_single_step(fbsr, oracle, fmt):
     for n in (0, 1, 7, 8, 2047, 2048, 5 * 2048 + 333):
         for wild in (False, True):
@@ -72,7 +72,7 @@ def test_single_step(fbsr, oracle, fmt):
                     assert np.array_equal(host(gd), g), "gradient buffer was written"
 
 
-@pytest.mark.parametrize("fmt", [E4M3, E5M2])
+@pytest.mark.parametrize("fmt", [E4M3, E5M2, 3])
 def test_extreme_finite_values_without_nan(fbsr, oracle, fmt):
     """Raw bit patterns for the gradient and both moments -- zeros, subnormals, magnitudes up to 2^73, squares that
     overflow to infinity -- but no input that can produce a NaN, so that every wave stays on the kernel's main path

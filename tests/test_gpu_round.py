@@ -7,9 +7,9 @@ from gpu_util import dev, first_mismatch, host
 
 pytestmark = pytest.mark.gpu
 
-BF16, E4M3, E5M2 = 0, 1, 2
+BF16, E4M3, E5M2, P4 = 0, 1, 2, 3        # P4: P3109 binary8p4
 RNE, SRFF, SRF, SRC = 0, 1, 2, 3
-FMT_TARGET = {BF16: "bf16", E4M3: "e4m3", E5M2: "e5m2"}
+FMT_TARGET = {BF16: "bf16", E4M3: "e4m3", E5M2: "e5m2", P4: "e4m3"}   # binary8p4 spans E4M3's range, one binade lower
 
 
 def _mixed_inputs(n, fmt, seed):
@@ -22,7 +22,7 @@ def _mixed_inputs(n, fmt, seed):
     return x
 
 
-@pytest.mark.parametrize("fmt", [BF16, E4M3, E5M2])
+@pytest.mark.parametrize("fmt", [BF16, E4M3, E5M2, P4])
 def test_all_variants_and_bit_counts(fbsr, oracle, fmt):
     """Several tiles plus ragged head and tail, every variant, every N in 1..16."""
     n = 3 * 8192 + 1024 + 333
@@ -119,7 +119,7 @@ def test_runs_on_a_side_stream(fbsr, oracle):
 
 
 @pytest.mark.parametrize("fmt,variant,nbits", [(E4M3, SRFF, 8), (E5M2, SRF, 4), (E4M3, SRC, 3), (E5M2, SRC, 8),
-                                               (E5M2, SRFF, 2), (E4M3, SRF, 16)])
+                                               (E5M2, SRFF, 2), (E4M3, SRF, 16), (P4, SRC, 3), (P4, SRFF, 8), (P4, SRF, 2)])
 def test_every_fp32_pattern(fbsr, oracle, fmt, variant, nbits):
     """All 2^32 input patterns (every normal, subnormal, zero, infinity and NaN of both signs), in
     16 slabs of 2^28 consecutive patterns, through the tile kernel: byte-identical to the oracle.
@@ -146,7 +146,7 @@ def test_fp32_subnormal_inputs_to_fp8(fbsr, oracle):
     bits = rng.integers(0, 1 << 25, n, dtype=np.uint32) | (rng.integers(0, 2, n, dtype=np.uint32) << np.uint32(31))
     x = bits.view(np.float32)
     xd = dev(x)
-    for fmt in (E4M3, E5M2):
+    for fmt in (E4M3, E5M2, P4):
         for variant, nbits in ((SRFF, 4), (SRF, 8), (SRC, 2), (RNE, 0)):
             got = host(fbsr.fbsr_round(xd, fmt, variant, nbits, seed=1))
             assert first_mismatch(got, oracle.round_(x, fmt, variant, nbits, seed=1)) is None

@@ -9,7 +9,7 @@ import torch
 from gpu_util import assert_stats_close, dev, first_mismatch, host
 
 pytestmark = pytest.mark.gpu
-E4M3, E5M2 = 1, 2
+E4M3, E5M2, P4 = 1, 2, 3
 RNE, SRFF, SRF, SRC = 0, 1, 2, 3
 SRC_BF16, SRC_FP16 = 0, 1
 
@@ -23,7 +23,7 @@ def _oracle_from16(oracle, x, src, fmt, variant, nbits, seed, offset, threads=16
 
 
 @pytest.mark.parametrize("src", [SRC_BF16, SRC_FP16])
-@pytest.mark.parametrize("fmt", [E4M3, E5M2])
+@pytest.mark.parametrize("fmt", [E4M3, E5M2, P4])
 def test_every_source_code_many_draws(fbsr, oracle, src, fmt):
     """All 65536 source codes (every normal, subnormal, zero, infinity, NaN), each drawn 64 times at
     different global indices, every variant, N below, at and above the number of excess bits."""
@@ -57,7 +57,7 @@ def test_matches_the_fp32_path_on_widened_values(fbsr):
     codes = np.tile(np.arange(65536, dtype=np.uint16), 4)
     xd = dev(codes)
     wide = (xd.view(torch.int16).to(torch.int32) << 16).view(torch.float32)
-    for fmt in (E4M3, E5M2):
+    for fmt in (E4M3, E5M2, P4):
         for variant, nbits in ((SRFF, 2), (SRF, 4), (SRC, 3), (RNE, 0)):
             a = fbsr.fbsr_round_from16(xd, SRC_BF16, fmt, variant, nbits, seed=8, offset=4096)
             b = fbsr.fbsr_round(wide, fmt, variant, nbits, seed=8, offset=4096)
@@ -66,7 +66,7 @@ def test_matches_the_fp32_path_on_widened_values(fbsr):
 
 def test_rejects_bad_arguments(fbsr):
     x = torch.zeros(16, dtype=torch.int16, device="cuda")
-    for src, fmt in ((2, E4M3), (-1, E5M2), (SRC_BF16, 0), (SRC_FP16, 3)):
+    for src, fmt in ((2, E4M3), (-1, E5M2), (SRC_BF16, 0), (SRC_FP16, 4)):
         with pytest.raises(fbsr.FbsrError):
             fbsr.fbsr_round_from16(x, src, fmt, SRFF, 2, seed=0)
 

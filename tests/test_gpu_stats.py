@@ -22,7 +22,7 @@ def _run_both(fbsr, oracle, x, fmt, variant, nbits, seed, offset, group, first_b
     return stats
 
 
-@pytest.mark.parametrize("fmt", [BF16, E4M3, E5M2])
+@pytest.mark.parametrize("fmt", [BF16, E4M3, E5M2, 3])
 def test_groups_of_every_size(fbsr, oracle, fmt):
     """Bins smaller than, equal to and larger than a tile; ragged ends; offsets; bins that the
     call only partly covers."""
@@ -63,8 +63,8 @@ def test_non_finite_values_propagate(fbsr, oracle):
     """Overflow to infinity, NaN inputs and saturation follow IEEE arithmetic in the sums."""
     from paper_2504_20634_amd import workloads
     n, group = 3 * 8192, 8192
-    for fmt in (BF16, E5M2, E4M3):
-        x = workloads.full_range(n, {BF16: "bf16", E5M2: "e5m2", E4M3: "e4m3"}[fmt], seed=77, specials_every=0)
+    for fmt in (BF16, E5M2, E4M3, 3):
+        x = workloads.full_range(n, {BF16: "bf16", E5M2: "e5m2", E4M3: "e4m3", 3: "e4m3"}[fmt], seed=77, specials_every=0)
         x[100] = np.float32(np.nan)
         x[8192 + 5] = np.float32(np.inf)
         x[2 * 8192 + 9] = np.float32(-3.0e38)
