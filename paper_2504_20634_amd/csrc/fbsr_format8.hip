@@ -116,22 +116,6 @@ hipError_t launch_tiles_w(int W, const void* x, uint8_t* out, uint64_t ntiles, c
 }
 
 template <int SRC, bool TIES>
-hipError_t launch_elems(const char* x, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m, int W, uint64_t seed,
-                        uint64_t offset, hipStream_t stream) {
-  constexpr uint64_t isize = SRC == kSrcFP32 ? 4 : 2;
-  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
-    const uint64_t cnt = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
-    const uint64_t blocks = (cnt + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL((format8_elems<SRC, TIES>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
-                       reinterpret_cast<const void*>(x + at * isize), out + at, cnt, f, m, W, W ? log2_of(128 / W) : 0, seed,
-                       offset + at);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
-}
-
-template <int SRC, bool TIES>
 hipError_t run(const void* xin, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
                hipStream_t stream) {
   constexpr uint64_t isize = SRC == kSrcFP32 ? 4 : 2;
@@ -140,17 +124,18 @@ hipError_t run(const void* xin, uint8_t* out, uint64_t n, const Fmt8& f, const M
   const int W = m.nbits ? slot_width((int)m.nbits) : 0;
   const Split s = split_range(n, offset, W ? W : 8, W == 0, reinterpret_cast<uintptr_t>(x), isize, 16,
                               reinterpret_cast<uintptr_t>(out), 1, oalign);
-  hipError_t e = launch_elems<SRC, TIES>(x, out, s.head, f, m, W, seed, offset, stream);
-  if (e != hipSuccess) return e;
-  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
-    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
-    const uint64_t e0 = s.head + t0 * s.tile_elems;
-    e = launch_tiles_w<SRC, TIES>(W, x + e0 * isize, out + e0, cnt, f, m, seed, W ? (offset + e0) / (uint64_t)(128 / W) : 0,
-                                  stream);
-    if (e != hipSuccess) return e;
-  }
-  const uint64_t done = s.head + s.ntiles * s.tile_elems;
-  return launch_elems<SRC, TIES>(x + done * isize, out + done, n - done, f, m, W, seed, offset + done, stream);
+  return run_split(
+      s, n,
+      [&](uint64_t first, uint64_t count) {
+        hipLaunchKernelGGL((format8_elems<SRC, TIES>), elems_grid(count), dim3(kThreads), 0, stream,
+                           reinterpret_cast<const void*>(x + first * isize), out + first, count, f, m, W, W ? log2_of(128 / W) : 0,
+                           seed, offset + first);
+        return hipGetLastError();
+      },
+      [&](uint64_t first, uint64_t count) {
+        return launch_tiles_w<SRC, TIES>(W, x + first * isize, out + first, count, f, m, seed,
+                                         W ? (offset + first) / (uint64_t)(128 / W) : 0, stream);
+      });
 }
 
 template <int SRC>

@@ -60,6 +60,33 @@ constexpr uint64_t kMaxTilesPerLaunch = (uint64_t)1 << 22;
 // Largest n the library accepts.
 constexpr uint64_t kMaxElems = (uint64_t)1 << 38;
 
+// Calls launch(first, count) over [0, n) in pieces of at most `piece`; stops at the first error.
+template <class Launch>
+hipError_t in_pieces(uint64_t n, uint64_t piece, Launch launch) {
+  for (uint64_t at = 0; at < n; at += piece) {
+    const uint64_t m = n - at < piece ? n - at : piece;
+    const hipError_t e = launch(at, m);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// Carries out the cut of split_range: elems(first, count) launches the per-element kernel over the
+// elements [first, first + count) of the call, tiles(first, count) the tile kernel over `count` whole
+// tiles of which the first starts at element `first`.
+template <class Elems, class Tiles>
+hipError_t run_split(const Split& s, uint64_t n, Elems elems, Tiles tiles) {
+  hipError_t e = in_pieces(s.head, kMaxElemsPerLaunch, elems);
+  if (e != hipSuccess) return e;
+  e = in_pieces(s.ntiles, kMaxTilesPerLaunch,
+                [&](uint64_t t0, uint64_t count) { return tiles(s.head + t0 * s.tile_elems, count); });
+  if (e != hipSuccess) return e;
+  const uint64_t done = s.head + s.ntiles * s.tile_elems;
+  return in_pieces(n - done, kMaxElemsPerLaunch, [&](uint64_t at, uint64_t count) { return elems(done + at, count); });
+}
+
+inline dim3 elems_grid(uint64_t count) { return dim3((unsigned)((count + kThreads - 1) / kThreads)); }
+
 hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                         uint64_t offset, hipStream_t stream);
 

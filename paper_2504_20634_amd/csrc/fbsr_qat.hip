@@ -290,21 +290,6 @@ hipError_t launch_tiles_w(int W, uint8_t* w8, const uint16_t* g16, uint16_t* m16
   return hipGetLastError();
 }
 
-template <class CODEC>
-hipError_t launch_elems(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, const AdamWScalars& p,
-                        const typename CODEC::Args& ca, int W, uint64_t seed, uint64_t step, uint64_t offset,
-                        hipStream_t stream) {
-  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
-    const uint64_t m = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
-    const uint64_t blocks = (m + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL((qat_elems<CODEC>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, w8 + at, g16 + at, m16 + at,
-                       v16 + at, m, p, ca, W, log2_of(128 / W), seed, step, offset + at);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
-}
-
 // nbits: N of a mode that draws bits (unused otherwise).
 template <class CODEC>
 hipError_t run(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, const AdamWScalars& p,
@@ -316,18 +301,17 @@ hipError_t run(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, u
     s.head = 0;
     s.ntiles = 0;
   }
-  hipError_t e = launch_elems<CODEC>(w8, g16, m16, v16, s.head, p, ca, W, seed, step, offset, stream);
-  if (e != hipSuccess) return e;
-  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
-    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
-    const uint64_t e0 = s.head + t0 * s.tile_elems;
-    e = launch_tiles_w<CODEC>(W, w8 + e0, g16 + e0, m16 + e0, v16 + e0, cnt, p, ca, seed, step,
-                              (offset + e0) / (uint64_t)(128 / W), stream);
-    if (e != hipSuccess) return e;
-  }
-  const uint64_t done = s.head + s.ntiles * s.tile_elems;
-  return launch_elems<CODEC>(w8 + done, g16 + done, m16 + done, v16 + done, n - done, p, ca, W, seed, step, offset + done,
-                             stream);
+  return run_split(
+      s, n,
+      [&](uint64_t first, uint64_t count) {
+        hipLaunchKernelGGL((qat_elems<CODEC>), elems_grid(count), dim3(kThreads), 0, stream, w8 + first, g16 + first, m16 + first,
+                           v16 + first, count, p, ca, W, log2_of(128 / W), seed, step, offset + first);
+        return hipGetLastError();
+      },
+      [&](uint64_t first, uint64_t count) {
+        return launch_tiles_w<CODEC>(W, w8 + first, g16 + first, m16 + first, v16 + first, count, p, ca, seed, step,
+                                     (offset + first) / (uint64_t)(128 / W), stream);
+      });
 }
 
 template <int FMT>

@@ -107,21 +107,6 @@ hipError_t launch_tiles_w(int W, const float* x, void* out, uint64_t ntiles, int
 }
 
 template <int FMT, int VAR>
-hipError_t launch_elems(const float* x, void* out, uint64_t n, int nbits, int W, uint64_t seed, uint64_t offset,
-                        hipStream_t stream) {
-  const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
-  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
-    const uint64_t m = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
-    const uint64_t blocks = (m + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL((round_elems<FMT, VAR>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x + at,
-                       reinterpret_cast<char*>(out) + at * osize, m, nbits, W, log2_of(128 / W), seed, offset + at);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
-}
-
-template <int FMT, int VAR>
 hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, uint64_t offset,
                hipStream_t stream) {
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
@@ -129,16 +114,17 @@ hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, 
   const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
                               reinterpret_cast<uintptr_t>(out), osize, 4 * osize);
   char* o = reinterpret_cast<char*>(out);
-  hipError_t e = launch_elems<FMT, VAR>(x, out, s.head, nbits, W, seed, offset, stream);
-  if (e != hipSuccess) return e;
-  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
-    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
-    const uint64_t e0 = s.head + t0 * s.tile_elems;
-    e = launch_tiles_w<FMT, VAR>(W, x + e0, o + e0 * osize, cnt, nbits, seed, (offset + e0) / (uint64_t)(128 / W), stream);
-    if (e != hipSuccess) return e;
-  }
-  const uint64_t done = s.head + s.ntiles * s.tile_elems;
-  return launch_elems<FMT, VAR>(x + done, o + done * osize, n - done, nbits, W, seed, offset + done, stream);
+  return run_split(
+      s, n,
+      [&](uint64_t first, uint64_t count) {
+        hipLaunchKernelGGL((round_elems<FMT, VAR>), elems_grid(count), dim3(kThreads), 0, stream, x + first,
+                           reinterpret_cast<void*>(o + first * osize), count, nbits, W, log2_of(128 / W), seed, offset + first);
+        return hipGetLastError();
+      },
+      [&](uint64_t first, uint64_t count) {
+        return launch_tiles_w<FMT, VAR>(W, x + first, o + first * osize, count, nbits, seed,
+                                        (offset + first) / (uint64_t)(128 / W), stream);
+      });
 }
 
 template <int FMT>

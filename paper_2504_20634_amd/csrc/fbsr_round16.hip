@@ -91,35 +91,22 @@ hipError_t launch_tiles_w(int W, const uint16_t* x, uint8_t* out, uint64_t ntile
 }
 
 template <int SRC, int FMT, int VAR>
-hipError_t launch_elems(const uint16_t* x, uint8_t* out, uint64_t n, int nbits, int W, uint64_t seed, uint64_t offset,
-                        hipStream_t stream) {
-  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
-    const uint64_t m = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
-    const uint64_t blocks = (m + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL((round16_elems<SRC, FMT, VAR>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x + at, out + at,
-                       m, nbits, W, log2_of(128 / W), seed, offset + at);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
-}
-
-template <int SRC, int FMT, int VAR>
 hipError_t run(const uint16_t* x, uint8_t* out, uint64_t n, int nbits, uint64_t seed, uint64_t offset,
                hipStream_t stream) {
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
   const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 2, 16,
                               reinterpret_cast<uintptr_t>(out), 1, 8);
-  hipError_t e = launch_elems<SRC, FMT, VAR>(x, out, s.head, nbits, W, seed, offset, stream);
-  if (e != hipSuccess) return e;
-  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
-    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
-    const uint64_t e0 = s.head + t0 * s.tile_elems;
-    e = launch_tiles_w<SRC, FMT, VAR>(W, x + e0, out + e0, cnt, nbits, seed, (offset + e0) / (uint64_t)(128 / W), stream);
-    if (e != hipSuccess) return e;
-  }
-  const uint64_t done = s.head + s.ntiles * s.tile_elems;
-  return launch_elems<SRC, FMT, VAR>(x + done, out + done, n - done, nbits, W, seed, offset + done, stream);
+  return run_split(
+      s, n,
+      [&](uint64_t first, uint64_t count) {
+        hipLaunchKernelGGL((round16_elems<SRC, FMT, VAR>), elems_grid(count), dim3(kThreads), 0, stream, x + first, out + first,
+                           count, nbits, W, log2_of(128 / W), seed, offset + first);
+        return hipGetLastError();
+      },
+      [&](uint64_t first, uint64_t count) {
+        return launch_tiles_w<SRC, FMT, VAR>(W, x + first, out + first, count, nbits, seed,
+                                             (offset + first) / (uint64_t)(128 / W), stream);
+      });
 }
 
 template <int SRC, int FMT>

@@ -99,35 +99,22 @@ hipError_t launch_tiles_w(int W, uint16_t* w, const float* g, uint64_t ntiles, f
 }
 
 template <int VAR>
-hipError_t launch_elems(uint16_t* w, const float* g, uint64_t n, float neg_lr, int nbits, int W, uint64_t seed,
-                        uint64_t step, uint64_t offset, hipStream_t stream) {
-  for (uint64_t at = 0; at < n; at += kMaxElemsPerLaunch) {
-    const uint64_t m = n - at < kMaxElemsPerLaunch ? n - at : kMaxElemsPerLaunch;
-    const uint64_t blocks = (m + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL((sgd_elems<VAR>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, w + at, g + at, m, neg_lr,
-                       nbits, W, log2_of(128 / W), seed, step, offset + at);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
-}
-
-template <int VAR>
 hipError_t run(uint16_t* w, const float* g, uint64_t n, float neg_lr, int nbits, uint64_t seed, uint64_t step,
                uint64_t offset, hipStream_t stream) {
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
   const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(g), 4, 16,
                               reinterpret_cast<uintptr_t>(w), 2, 8);
-  hipError_t e = launch_elems<VAR>(w, g, s.head, neg_lr, nbits, W, seed, step, offset, stream);
-  if (e != hipSuccess) return e;
-  for (uint64_t t0 = 0; t0 < s.ntiles; t0 += kMaxTilesPerLaunch) {
-    const uint64_t cnt = s.ntiles - t0 < kMaxTilesPerLaunch ? s.ntiles - t0 : kMaxTilesPerLaunch;
-    const uint64_t e0 = s.head + t0 * s.tile_elems;
-    e = launch_tiles_w<VAR>(W, w + e0, g + e0, cnt, neg_lr, nbits, seed, step, (offset + e0) / (uint64_t)(128 / W), stream);
-    if (e != hipSuccess) return e;
-  }
-  const uint64_t done = s.head + s.ntiles * s.tile_elems;
-  return launch_elems<VAR>(w + done, g + done, n - done, neg_lr, nbits, W, seed, step, offset + done, stream);
+  return run_split(
+      s, n,
+      [&](uint64_t first, uint64_t count) {
+        hipLaunchKernelGGL((sgd_elems<VAR>), elems_grid(count), dim3(kThreads), 0, stream, w + first, g + first, count, neg_lr,
+                           nbits, W, log2_of(128 / W), seed, step, offset + first);
+        return hipGetLastError();
+      },
+      [&](uint64_t first, uint64_t count) {
+        return launch_tiles_w<VAR>(W, w + first, g + first, count, neg_lr, nbits, seed, step,
+                                   (offset + first) / (uint64_t)(128 / W), stream);
+      });
 }
 
 }  // namespace
