@@ -18,8 +18,6 @@ inline int log2_of(int v) {
   return l;
 }
 
-inline int tile_elems(int W) { (void)W; return kTileElems; }   // one workgroup tile
-
 // How a call over [0, n) is cut: `head` elements for the per-element kernel (up to the first
 // global index that starts a Philox block), `ntiles` whole tiles for the vector kernel, and
 // the rest for the per-element kernel again.  The vector kernel is used only when both
@@ -36,7 +34,7 @@ inline Split split_range(uint64_t n, uint64_t offset, int W, bool no_bits, uintp
                          uint64_t in_align, uintptr_t out_addr, uint64_t out_esize, uint64_t out_align,
                          uintptr_t in2_addr = 0, uint64_t in2_esize = 0, uint64_t in2_align = 1) {
   Split s;
-  s.tile_elems = (uint64_t)tile_elems(W);
+  s.tile_elems = (uint64_t)kTileElems;   // one workgroup tile
   const uint64_t per_block = no_bits ? 1 : (uint64_t)(128 / W);
   uint64_t head = (per_block - offset % per_block) % per_block;
   if (head > n) head = n;
