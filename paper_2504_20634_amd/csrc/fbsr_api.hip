@@ -180,7 +180,8 @@ int fbsr_qat_adamw_step(void* w8, const void* g16, void* m16, void* v16, uint64_
   if (n == 0) return FBSR_OK;
   if (w8 == nullptr || g16 == nullptr || m16 == nullptr || v16 == nullptr) return FBSR_EINVAL;
   if (misaligned(g16, 2) || misaligned(m16, 2) || misaligned(v16, 2)) return FBSR_EALIGN;
-  const fbsr::AdamWScalars sc = {p->lr, p->beta1, p->beta2, p->eps, p->weight_decay, p->bias_corr1, p->bias_corr2};
+  fbsr::AdamWScalars sc = {p->lr, p->beta1, p->beta2, p->eps, p->weight_decay, p->bias_corr1, p->bias_corr2, 0.0f, 0.0f, 0};
+  fbsr::derive_adamw(&sc);
   const hipError_t e = fbsr::launch_qat_adamw(reinterpret_cast<uint8_t*>(w8), reinterpret_cast<const uint16_t*>(g16),
                                               reinterpret_cast<uint16_t*>(m16), reinterpret_cast<uint16_t*>(v16), n, fmt,
                                               sc, variant, nbits, seed, step, offset,
@@ -240,7 +241,8 @@ int fbsr_qat_adamw_step_format8(void* w8, const void* g16, void* m16, void* v16,
   if (misaligned(g16, 2) || misaligned(m16, 2) || misaligned(v16, 2)) return FBSR_EALIGN;
   fbsr::Table8 t;
   decode_table8(*fmt, &t);
-  const fbsr::AdamWScalars sc = {p->lr, p->beta1, p->beta2, p->eps, p->weight_decay, p->bias_corr1, p->bias_corr2};
+  fbsr::AdamWScalars sc = {p->lr, p->beta1, p->beta2, p->eps, p->weight_decay, p->bias_corr1, p->bias_corr2, 0.0f, 0.0f, 0};
+  fbsr::derive_adamw(&sc);
   const hipError_t e = fbsr::launch_qat_adamw_format8(reinterpret_cast<uint8_t*>(w8), reinterpret_cast<const uint16_t*>(g16),
                                                       reinterpret_cast<uint16_t*>(m16), reinterpret_cast<uint16_t*>(v16), n, f,
                                                       m, t, sc, seed, step, offset, reinterpret_cast<hipStream_t>(stream));

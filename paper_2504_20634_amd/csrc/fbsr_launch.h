@@ -99,7 +99,19 @@ hipError_t launch_round_block_scaled(const float* x, uint8_t* out, uint8_t* scal
 
 struct AdamWScalars {
   float lr, beta1, beta2, eps, weight_decay, bias_corr1, bias_corr2;
+  // 1 / bias_corr (correctly rounded, computed on the host) and whether the tile kernel may divide by the two
+  // corrections with div_by_uniform (both in [2^-20, 1]); the caller's struct ends at bias_corr2.
+  float rcp_corr1, rcp_corr2;
+  int fast_div;
 };
+
+// Fills the derived fields of AdamWScalars.
+inline void derive_adamw(AdamWScalars* p) {
+  const float lo = 0x1p-20f;
+  p->fast_div = p->bias_corr1 >= lo && p->bias_corr1 <= 1.0f && p->bias_corr2 >= lo && p->bias_corr2 <= 1.0f;
+  p->rcp_corr1 = p->fast_div ? 1.0f / p->bias_corr1 : 0.0f;
+  p->rcp_corr2 = p->fast_div ? 1.0f / p->bias_corr2 : 0.0f;
+}
 
 hipError_t launch_qat_adamw_format8(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n,
                                     const Fmt8& f, const Mode8& m, const Table8& t, const AdamWScalars& p, uint64_t seed,

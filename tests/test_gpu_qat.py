@@ -87,6 +87,17 @@ def test_extreme_finite_values_without_nan(fbsr, oracle, fmt):
         code = (field << 7) | rng.integers(0, 128, n).astype(np.uint16)
         return code | (rng.integers(0, 2, n).astype(np.uint16) << 15) if signed else code
     g, m, v = raw(True), raw(True), raw(False)
+    # signed zeros everywhere (the sign of a zero moment can reach the sign of a zero weight), and moments around
+    # 2^-103, where the kernel's short division by the bias corrections hands over to the full one
+    k = 512
+    g[:k] = rng.choice(np.array([0x0000, 0x8000], dtype=np.uint16), k)
+    m[:k] = rng.choice(np.array([0x0000, 0x8000], dtype=np.uint16), k)
+    v[:k] = 0
+    w8[:k] = rng.choice(np.array([0x00, 0x01, 0x81] + ([0x80] if fmt != 3 else []), dtype=np.uint8), k)
+    edge = ((127 - 103 + rng.integers(-6, 7, k)).astype(np.uint16) << 7) | rng.integers(0, 128, k).astype(np.uint16)
+    m[k:2 * k] = edge | (rng.integers(0, 2, k).astype(np.uint16) << 15)
+    v[2 * k:3 * k] = edge
+    g[k:3 * k] = 0
     for params in PARAMS:
         for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 2), (SRC, 4), (SRC, 16)):
             print("case fmt=%d lr=%g variant=%d nbits=%d" % (fmt, params[0], variant, nbits), flush=True)
