@@ -242,7 +242,13 @@ def main():
 
     paths = {}
     if not args.no_paths:
-        # streaming ceiling: the RNE launch draws no random bits (same 4:1 read:write byte mix)
+        # practical ceiling of the launch shape: the same tiles with no arithmetic (plain 4:1 read:write stream)
+        def probe():
+            turn[0] += 1
+            fbsr.binding.fbsr_probe_stream41(x_rot[fbsr.FMT_E4M3][turn[0] % 3], out_rot[turn[0] % 4])
+        ms = timed_launches(torch, probe, 12)
+        paths["stream_4to1_no_arithmetic_ceiling"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1)}
+        # the RNE launch draws no random bits (same 4:1 read:write byte mix)
         ms = timed_launches(torch, lambda: fbsr.fbsr_round(x_dev[fbsr.FMT_E4M3], fbsr.FMT_E4M3, fbsr.RNE, 0, 2, 0, out=out8), 10)
         paths["round_e4m3_rne_ceiling"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1)}
         out16 = torch.empty(n, dtype=torch.uint16, device="cuda")

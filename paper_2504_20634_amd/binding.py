@@ -20,7 +20,7 @@ MAX_NBITS = 16
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2", FMT_BINARY8P4: "binary8p4"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
 EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",
-           "fbsr_strerror", "fbsr_version")
+           "fbsr_probe_stream41", "fbsr_strerror", "fbsr_version")
 
 
 class FbsrError(RuntimeError):
@@ -64,6 +64,8 @@ def lib():
         L.fbsr_round_format8.restype = i32
         L.fbsr_qat_adamw_step_format8.argtypes = [vp, vp, vp, vp, u64, vp, vp, i32, i32, u64, u64, u64, vp]
         L.fbsr_qat_adamw_step_format8.restype = i32
+        L.fbsr_probe_stream41.argtypes = [vp, vp, u64, vp]
+        L.fbsr_probe_stream41.restype = i32
         L.fbsr_strerror.argtypes = [i32]
         L.fbsr_strerror.restype = ctypes.c_char_p
         L.fbsr_version.argtypes = []
@@ -161,6 +163,15 @@ def fbsr_round_format8(x, src, fmt, variant, nbits, seed, offset=0, out=None, st
     f = _format8(fmt)
     _check(lib().fbsr_round_format8(x.data_ptr(), src, out.data_ptr(), n, ctypes.byref(f), variant, nbits, seed, offset,
                                     _stream_handle(stream)), "fbsr_round_format8")
+    return out
+
+
+def fbsr_probe_stream41(x, out, stream=None):
+    """Measurement aid: out[j] = top byte of x[j]'s pattern, in the rounding kernels' launch shape."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and out.is_cuda and out.dtype == torch.uint8
+    assert out.numel() == x.numel()
+    _check(lib().fbsr_probe_stream41(x.data_ptr(), out.data_ptr(), x.numel(), _stream_handle(stream)), "fbsr_probe_stream41")
     return out
 
 

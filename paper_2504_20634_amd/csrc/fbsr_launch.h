@@ -88,6 +88,8 @@ inline dim3 elems_grid(uint64_t count) { return dim3((unsigned)((count + kThread
 hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                         uint64_t offset, hipStream_t stream);
 
+hipError_t launch_stream41(const float* x, uint8_t* out, uint64_t ntiles, hipStream_t stream);
+
 hipError_t launch_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt, int variant, int nbits,
                                uint64_t seed, uint64_t offset, hipStream_t stream);
 

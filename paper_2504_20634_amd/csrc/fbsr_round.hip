@@ -83,6 +83,31 @@ __global__ __launch_bounds__(kThreads) void round_elems(const float* __restrict_
   reinterpret_cast<code_t*>(out)[j] = (code_t)(r >> Fx<FMT>::FRAC);
 }
 
+// Measurement aid: the same tile geometry with no arithmetic -- every float is read once (16-byte loads) and
+// its top byte written (4-byte stores), a plain 4 : 1 read : write stream.  What this reaches is the practical
+// ceiling of the rounding kernels' launch shape on the part at hand.
+__global__ __launch_bounds__(kThreads) void stream41_tiles(const float* __restrict__ x, uint8_t* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const uint64_t row0 = (uint64_t)blockIdx.x * (kTileElems / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);
+  f32x4 v[kRows];
+#pragma unroll
+  for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
+#pragma unroll
+  for (int k = 0; k < kRows; ++k) {
+    const uint32_t packed = pack4_fp8<kE4M3>(__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
+                                             __float_as_uint(v[k].w));
+    __builtin_nontemporal_store(packed, reinterpret_cast<uint32_t*>(out) + row0 + (uint64_t)(k * 64));
+  }
+}
+
+hipError_t launch_stream41(const float* x, uint8_t* out, uint64_t ntiles, hipStream_t stream) {
+  return in_pieces(ntiles, kMaxTilesPerLaunch, [&](uint64_t t0, uint64_t count) {
+    hipLaunchKernelGGL(stream41_tiles, dim3((unsigned)count), dim3(kThreads), 0, stream, x + t0 * kTileElems, out + t0 * kTileElems);
+    return hipGetLastError();
+  });
+}
+
 namespace {
 
 template <int FMT, int VAR, int W>

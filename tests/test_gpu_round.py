@@ -150,3 +150,14 @@ def test_fp32_subnormal_inputs_to_fp8(fbsr, oracle):
         for variant, nbits in ((SRFF, 4), (SRF, 8), (SRC, 2), (RNE, 0)):
             got = host(fbsr.fbsr_round(xd, fmt, variant, nbits, seed=1))
             assert first_mismatch(got, oracle.round_(x, fmt, variant, nbits, seed=1)) is None
+
+
+def test_stream_probe_copies_top_bytes(fbsr):
+    """The measurement aid writes the top byte of every pattern and nothing else."""
+    n = 7 * 2048
+    bits = torch.randint(-2 ** 31, 2 ** 31 - 1, (n,), dtype=torch.int64, device="cuda").to(torch.int32)
+    out = torch.full((n + 16,), 0xA5, dtype=torch.uint8, device="cuda")
+    fbsr.binding.fbsr_probe_stream41(bits.view(torch.float32), out[:n])
+    assert torch.equal(out[:n], ((bits >> 24) & 0xFF).to(torch.uint8)) and bool((out[n:] == 0xA5).all())
+    with pytest.raises(fbsr.FbsrError):
+        fbsr.binding.fbsr_probe_stream41(bits.view(torch.float32)[:100], out[:100])
