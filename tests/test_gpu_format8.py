@@ -70,6 +70,28 @@ def test_fp32_source_every_mode(fbsr, oracle, name):
         assert first_mismatch(got, want) is None, (name, variant, nbits, first_mismatch(got, want))
 
 
+def test_random_descriptors(fbsr, oracle):
+    """Sixty descriptors drawn at random (every combination of special encodings the checks allow), fp32 and
+    16-bit sources, a random mode each: byte-identical to the oracle."""
+    from test_oracle_format8 import random_descriptors
+    rng = np.random.default_rng(77)
+    codes16 = np.tile(np.arange(65536, dtype=np.uint16), 2)
+    c16d = dev(codes16)
+    for d in random_descriptors(rng, 60, oracle.format8_check):
+        assert fbsr.format8_check(d)
+        x = _inputs(rng, d, 2 * 2048 * 11 + 5)
+        xd = dev(x)
+        for variant, nbits in (MODES[int(rng.integers(0, len(MODES)))], MODES[int(rng.integers(3, len(MODES)))]):
+            print("case d=%s variant=%d nbits=%d" % (d, variant, nbits), flush=True)
+            got = host(fbsr.fbsr_round_format8(xd, FROM_FP32, d, variant, nbits, seed=3, offset=11))
+            want = _oracle(oracle, x, FROM_FP32, d, variant, nbits, 3, 11)
+            assert first_mismatch(got, want) is None, (d, variant, nbits, first_mismatch(got, want))
+            src = int(rng.integers(0, 2))
+            got = host(fbsr.fbsr_round_format8(c16d, src, d, variant, nbits, seed=3, offset=11))
+            want = _oracle(oracle, codes16, src, d, variant, nbits, 3, 11)
+            assert first_mismatch(got, want) is None, (d, src, variant, nbits, first_mismatch(got, want))
+
+
 @pytest.mark.parametrize("src", [FROM_BF16, FROM_FP16])
 @pytest.mark.parametrize("name", ["binary8p4", "binary8p3", "ocp_e2m3", "ocp_e2m1", "binary8p1", "inf_apart"])
 def test_every_16_bit_source_code(fbsr, oracle, src, name):

@@ -133,6 +133,66 @@ def test_descriptor_validation(oracle):
     assert not any(oracle.format8_check(d) for d in bad)
 
 
+def random_descriptors(rng, count, check):
+    """Valid descriptors drawn at random (rejection against `check`), special encodings of every kind included."""
+    out = []
+    while len(out) < count:
+        K = int(rng.integers(2, 9))
+        P = int(rng.integers(1, K))
+        top = (1 << (K - 1)) - 1
+        mx = int(rng.integers(1 << (P - 1), top + 1))
+        B = int(rng.integers(0, 41))
+        inf = int(rng.integers(mx + 1, top + 1)) if mx < top and rng.random() < 0.5 else -1
+        neg_zero = int(rng.random() < 0.6)
+        kind = rng.random()
+        if kind < 0.3:
+            nan, signed = -1, 0
+        elif kind < 0.45 and not neg_zero:
+            nan, signed = 1 << (K - 1), 0
+        else:
+            spare = [m for m in range(mx + 1, top + 1) if m != inf]
+            if not spare:
+                continue
+            nan, signed = int(rng.choice(spare)), int(rng.random() < 0.5)
+            if not signed and rng.random() < 0.3:
+                nan |= 1 << (K - 1)
+        d = (K, P, B, mx, inf, nan, signed, neg_zero)
+        if check(d):
+            out.append(d)
+    return out
+
+
+def test_random_descriptors_bracket_count_and_fix(oracle):
+    """Forty descriptors drawn at random: every rounded magnitude is a bracketing neighbour from the exact table of
+    Eq. (1), the number of draws that round up is the counting argument, representable values stay, and out-of-range
+    and special inputs follow the descriptor."""
+    rng = np.random.default_rng(2024)
+    for d in random_descriptors(rng, 40, oracle.format8_check):
+        K, P, B, mx, inf, nan, signed, neg_zero = d
+        sign_bit = 1 << (K - 1)
+        vals = table(d)
+        for xv in inputs_below_max(rng, d, 40):
+            a = abs(f32_fraction(xv))
+            lo, delta = position(a, d)
+            for variant in DRAWING:
+                N = int(rng.integers(1, 6))
+                got = sum((oracle.round_format8_with_n(xv, d, variant, N, n) & (sign_bit - 1)) == lo + 1 for n in range(1 << N))
+                assert got == (ups(delta, variant, N) if delta != 0 else 0), (d, xv, variant, N)
+            for variant in (RNE, TNO, TA):
+                code = oracle.round_format8_with_n(xv, d, variant, 0, 0)
+                assert (code & (sign_bit - 1)) in ((lo,) if delta == 0 else (lo, lo + 1)), (d, xv, variant)
+                if (code & (sign_bit - 1)) == 0 and not neg_zero:
+                    assert code == 0
+        for code in range(0, mx + 1, max(1, mx // 16)):
+            assert oracle.round_format8_with_n(np.float32(float(vals[code])), d, SRFF, 3, 7) == code
+        M = float(vals[mx])
+        big = oracle.round_format8_with_n(np.float32(M * 4.0), d, SRC, 3, 5)
+        assert big == (inf if inf >= 0 else mx), d
+        neg_nan = np.array([0xFFC00000], dtype=np.uint32).view(np.float32)[0]
+        got = oracle.round_format8_with_n(neg_nan, d, SRF, 3, 1)
+        assert got == ((nan | (sign_bit if signed else 0)) if nan >= 0 else (mx | sign_bit)), d
+
+
 # ------------------------------------------------------ against the pinned fixed-format path ----
 @pytest.mark.parametrize("fmt,d", [(1, E4M3), (2, E5M2)])
 def test_descriptor_path_equals_fixed_path(oracle, fmt, d):
