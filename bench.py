@@ -28,6 +28,17 @@ HBM_PEAK_GBS = 8000.0
 # (FETCH_SIZE, then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy);
 # the summary is committed under profiles/.  Algorithmic bytes: 5 * 2^28 = 1342177280.
 MEASURED_TRAFFIC_BYTES_2P28 = 1342193990
+# Vector-ALU roofline for the paths that are not bound by HBM: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz
+# one-lane operations per second.  VALU instructions per element are SQ_INSTS_VALU / SQ_WAVES / elements per lane
+# from a rocprofv3 --pmc run of this file (profiles/kernels_2p28_valu_counters.md).
+ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+VALU_PER_ELEM = {"qat_adamw_e4m3_N3_src": 72.8, "qat_adamw_e4m3_N3_srff": 65.8, "qat_adamw_binary8p4_N3_src": 80.1,
+                 "qat_adamw_binary8p4_N3_srff": 73.1, "qat_adamw_format8_binary8p4_N3_src": 92.5,
+                 "qat_adamw_format8_binary8p4_N3_srff": 84.3, "bias_stats_e4m3_N3_srf": 24.8, "bias_stats_e4m3_N8_srf": 26.6,
+                 "bias_stats_bf16_N2_srf": 22.5, "bias_stats_bf16_N8_srf": 24.2,
+                 "round_format8_binary8p4_from_fp32_N3_src": 36.4, "round_format8_binary8p4_from_fp32_N8_srf": 29.6,
+                 "round_format8_binary8p4_from_bf16_N3_src": 36.6, "round_format8_binary8p4_from_bf16_N3_srff": 27.8,
+                 "round_from_bf16_binary8p4_N3_src": 22.1, "round_from_bf16_e4m3_N3_src": 16.8}
 N_ELEMS = 1 << 28
 SGD_ELEMS = 1 << 27
 HEADLINE_NBITS = (2, 4, 8)
@@ -388,6 +399,14 @@ def main():
             paths["bias_stats_%s_N%d_srf" % (target[f], nb)] = {"ms": round(ms, 4), "gb_s": round(4.0 * n / ms / 1e6, 1)}
         del xs_
 
+    # the paths the vector ALU bounds: instructions per element x elements per second against the ALU peak
+    for name, per_elem in VALU_PER_ELEM.items():
+        if name in paths:
+            ms = paths[name]["ms"]
+            elems = SGD_ELEMS if name.startswith("qat") else n
+            rate = per_elem * min(elems, n) / (ms * 1e-3)
+            paths[name]["alu_roofline"] = {"bound": "alu", "achieved": round(rate / 1e12, 2), "peak": round(ALU_PEAK_LANE_OPS / 1e12, 2),
+                                           "unit": "T lane-ops/s", "frac": round(rate / ALU_PEAK_LANE_OPS, 3), "valu_per_elem": per_elem}
     workloads_report = None
     if not args.no_paths and not args.no_workloads and args.elems_log2 == 28:
         del x_rot, out_rot
