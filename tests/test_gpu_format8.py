@@ -181,3 +181,20 @@ def test_rejects_bad_arguments(fbsr):
     for d, variant, nbits in (((8, 4, 8, 0x7E, 0x7E, 0x80, 0, 0), SRFF, 3), (good, 7, 3), (good, SRC_ODD, 17), (good, SRF, 0)):
         with pytest.raises(fbsr.FbsrError):
             fbsr.fbsr_round_format8(x, FROM_FP32, d, variant, nbits, seed=0)
+
+
+@pytest.mark.parametrize("name,variant,nbits", [("binary8p4", SRC_ODD, 3), ("ocp_e2m1", SRF, 2), ("binary8p3", RNA, 0)])
+def test_every_fp32_pattern_generic(fbsr, oracle, name, variant, nbits):
+    """All 2^32 input patterns through the generic tile kernel, in 16 slabs of 2^28: byte-identical to the oracle."""
+    d = FORMATS[name]
+    slab = 1 << 28
+    for s_no in range(16):
+        base = s_no * slab
+        x = np.arange(base, base + slab, dtype=np.uint32).view(np.float32)
+        lo = base - (1 << 32) if base >= (1 << 31) else base
+        xd = torch.arange(lo, lo + slab, dtype=torch.int64, device="cuda").to(torch.int32).view(torch.float32)
+        got = host(fbsr.fbsr_round_format8(xd, FROM_FP32, d, variant, nbits, seed=77, offset=base))
+        del xd
+        want = _oracle(oracle, x, FROM_FP32, d, variant, nbits, 77, base)
+        print("case fmt=%s variant=%d nbits=%d slab=%d" % (name, variant, nbits, s_no), flush=True)
+        assert first_mismatch(got, want) is None, (s_no, first_mismatch(got, want))
