@@ -30,18 +30,19 @@ __device__ __forceinline__ float inv_scale(int s) { return __uint_as_float((uint
 template <int FMT, int VAR, int W>
 __global__ __launch_bounds__(kThreads) void block_tiles(const float* __restrict__ x, uint8_t* __restrict__ out,
                                                         uint8_t* __restrict__ scales, int nbits, uint64_t seed,
-                                                        uint64_t blk0) {
+                                                        uint64_t blk0, uint32_t xcd_lg) {
   typedef WgTile<W> T;
   typedef Fx<FMT> F;
   __shared__ uint4 strip[T::BLOCKS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+  const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+  const uint64_t row0 = (uint64_t)tile * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
   f32x4 v[kRows];
 #pragma unroll
   for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
   if constexpr (VAR != kRNE) {
-    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
     __syncthreads();
   }
   const Addends a = make_addends<FMT, VAR>(nbits);
@@ -113,7 +114,7 @@ hipError_t launch_tiles_w(int W, const float* x, uint8_t* out, uint8_t* scales, 
                           uint64_t seed, uint64_t blk0, hipStream_t stream) {
   const dim3 grid((unsigned)ntiles), block(kThreads);
 #define FBSR_BLOCK_LAUNCH(WW) \
-  hipLaunchKernelGGL((block_tiles<FMT, VAR, WW>), grid, block, 0, stream, x, out, scales, nbits, seed, blk0)
+  hipLaunchKernelGGL((block_tiles<FMT, VAR, WW>), grid, block, 0, stream, x, out, scales, nbits, seed, blk0, kXcdLgBlock)
   if constexpr (VAR == kRNE) {
     FBSR_BLOCK_LAUNCH(8);
   } else {

@@ -254,6 +254,20 @@ constexpr int kRows = 2;
 constexpr int kWaveElems = kRows * 256;
 constexpr int kTileElems = kWavesPerBlock * kWaveElems;
 
+// Which tile a workgroup takes.  Workgroups are handed to the part's 8 XCDs in turn (workgroup b runs on
+// XCD b mod 8), each XCD with an L2 and a share of the memory fabric of its own; with the identity map every
+// XCD walks the whole tensor with a stride of 8 tiles.  Here the launch is cut into chunks of 8 R tiles,
+// R = 2^log2_run, and within a chunk XCD j takes the j-th run of R consecutive tiles: each XCD then streams
+// through contiguous memory.  log2_run = 0 is the identity map.
+// A bijection of [0, ntiles): whole chunks are permuted within themselves, the tiles after the last whole
+// chunk keep their index.  What a tile computes depends on its index alone, so results do not change.
+__device__ __forceinline__ uint32_t xcd_tile(uint32_t wg, uint32_t ntiles, uint32_t log2_run) {
+  const uint32_t chunk_mask = (8u << log2_run) - 1u;
+  if (wg >= (ntiles & ~chunk_mask)) return wg;
+  const uint32_t r = wg & chunk_mask;
+  return (wg - r) + ((r & 7u) << log2_run) + (r >> 3);
+}
+
 template <int W> struct WgTile {
   static constexpr int ELEMS = kTileElems;
   static constexpr int BLOCKS = kTileElems * W / 128;

@@ -19,7 +19,7 @@ namespace fbsr {
 // sources: a lane owns 8 consecutive codes (16-byte load, 8-byte store).  W = 0: the mode draws no bits.
 template <int SRC, bool TIES, int W>
 __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict__ xin, uint8_t* __restrict__ out, Fmt8 f,
-                                                          Mode8 m, uint64_t seed, uint64_t blk0) {
+                                                          Mode8 m, uint64_t seed, uint64_t blk0, uint32_t xcd_lg) {
   constexpr int WW = W == 0 ? 1 : W;
   typedef WgTile<WW> T;
   __shared__ uint4 strip[T::BLOCKS];
@@ -27,12 +27,13 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
   const int wave = threadIdx.x >> 6;
   if constexpr (SRC == kSrcFP32) {
     const float* x = reinterpret_cast<const float*>(xin);
-    const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+    const uint64_t row0 = (uint64_t)tile * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
     f32x4 v[kRows];
 #pragma unroll
     for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
     if constexpr (W != 0) {
-      fill_wg_bits<WW>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
+      fill_wg_bits<WW>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
       __syncthreads();
     }
     uint32_t umax = 0;
@@ -56,10 +57,11 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
   } else {
     const uint16_t* x = reinterpret_cast<const uint16_t*>(xin);
     const int e0 = wave * kWaveElems + 8 * lane;                                  // tile-relative first element
-    const uint64_t g0 = (uint64_t)blockIdx.x * T::ELEMS + (uint64_t)e0;           // call-relative first element
+    const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+    const uint64_t g0 = (uint64_t)tile * T::ELEMS + (uint64_t)e0;           // call-relative first element
     const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + g0));
     if constexpr (W != 0) {
-      fill_wg_bits<WW>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
+      fill_wg_bits<WW>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
       __syncthreads();
     }
     const uint32_t words[4] = {q.x, q.y, q.z, q.w};
@@ -102,7 +104,7 @@ template <int SRC, bool TIES>
 hipError_t launch_tiles_w(int W, const void* x, uint8_t* out, uint64_t ntiles, const Fmt8& f, const Mode8& m, uint64_t seed,
                           uint64_t blk0, hipStream_t stream) {
   const dim3 grid((unsigned)ntiles), block(kThreads);
-#define FBSR_F8_LAUNCH(WW) hipLaunchKernelGGL((format8_tiles<SRC, TIES, WW>), grid, block, 0, stream, x, out, f, m, seed, blk0)
+#define FBSR_F8_LAUNCH(WW) hipLaunchKernelGGL((format8_tiles<SRC, TIES, WW>), grid, block, 0, stream, x, out, f, m, seed, blk0, kXcdLgFormat8)
   switch (W) {
     case 0: FBSR_F8_LAUNCH(0); break;
     case 1: FBSR_F8_LAUNCH(1); break;

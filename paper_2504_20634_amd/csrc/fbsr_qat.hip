@@ -189,20 +189,21 @@ template <class CODEC, int W>
 __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, const uint16_t* __restrict__ g16,
                                                       uint16_t* __restrict__ m16, uint16_t* __restrict__ v16,
                                                       AdamWScalars p, typename CODEC::Args ca, uint64_t seed, uint64_t step,
-                                                      uint64_t blk0) {
+                                                      uint64_t blk0, uint32_t xcd_lg) {
   typedef WgTile<W> T;
   __shared__ uint4 strip[T::BLOCKS];
   __shared__ float table[CODEC::kTable ? 256 : 1];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int e0 = wave * kWaveElems + 8 * lane;
-  const uint64_t g0 = (uint64_t)blockIdx.x * T::ELEMS + (uint64_t)e0;
+  const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+  const uint64_t g0 = (uint64_t)tile * T::ELEMS + (uint64_t)e0;
   const uint64_t wq = *reinterpret_cast<const uint64_t*>(w8 + g0);
   const u32x4 gq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g16 + g0));
   const u32x4 mq = *reinterpret_cast<const u32x4*>(m16 + g0);
   const u32x4 vq = *reinterpret_cast<const u32x4*>(v16 + g0);
   if constexpr (CODEC::kTable) table[threadIdx.x] = ca.t.v[threadIdx.x];
-  if constexpr (CODEC::kDraws) fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, step);
+  if constexpr (CODEC::kDraws) fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, step);
   if constexpr (CODEC::kTable || CODEC::kDraws) __syncthreads();
   const CODEC c(ca, table);
   const Addends a16 = make_addends<kBF16, kRNE>(0);
@@ -309,7 +310,7 @@ hipError_t launch_tiles_w(int W, uint8_t* w8, const uint16_t* g16, uint16_t* m16
                           hipStream_t stream) {
   const dim3 grid((unsigned)ntiles), block(kThreads);
 #define FBSR_QAT_LAUNCH(WW) \
-  hipLaunchKernelGGL((qat_tiles<CODEC, WW>), grid, block, 0, stream, w8, g16, m16, v16, p, ca, seed, step, blk0)
+  hipLaunchKernelGGL((qat_tiles<CODEC, WW>), grid, block, 0, stream, w8, g16, m16, v16, p, ca, seed, step, blk0, kXcdLgQat)
   if constexpr (!CODEC::kDraws) {
     FBSR_QAT_LAUNCH(8);
   } else {

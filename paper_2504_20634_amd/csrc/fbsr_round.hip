@@ -10,17 +10,18 @@ namespace fbsr {
 // first so that their latency overlaps the Philox rounds.
 template <int FMT, int VAR, int W>
 __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict__ x, void* __restrict__ out,
-                                                        int nbits, uint64_t seed, uint64_t blk0) {
+                                                        int nbits, uint64_t seed, uint64_t blk0, uint32_t xcd_lg) {
   typedef WgTile<W> T;
   __shared__ uint4 strip[T::BLOCKS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+  const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+  const uint64_t row0 = (uint64_t)tile * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
   f32x4 v[kRows];
 #pragma unroll
   for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
   if constexpr (VAR != kRNE) {
-    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
     __syncthreads();
   }
   const Addends a = make_addends<FMT, VAR>(nbits);
@@ -86,10 +87,11 @@ __global__ __launch_bounds__(kThreads) void round_elems(const float* __restrict_
 // Measurement aid: the same tile geometry with no arithmetic -- every float is read once (16-byte loads) and
 // its top byte written (4-byte stores), a plain 4 : 1 read : write stream.  What this reaches is the practical
 // ceiling of the rounding kernels' launch shape on the part at hand.
-__global__ __launch_bounds__(kThreads) void stream41_tiles(const float* __restrict__ x, uint8_t* __restrict__ out) {
+__global__ __launch_bounds__(kThreads) void stream41_tiles(const float* __restrict__ x, uint8_t* __restrict__ out, uint32_t xcd_lg) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const uint64_t row0 = (uint64_t)blockIdx.x * (kTileElems / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);
+  const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+  const uint64_t row0 = (uint64_t)tile * (kTileElems / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);
   f32x4 v[kRows];
 #pragma unroll
   for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
@@ -103,7 +105,8 @@ __global__ __launch_bounds__(kThreads) void stream41_tiles(const float* __restri
 
 hipError_t launch_stream41(const float* x, uint8_t* out, uint64_t ntiles, hipStream_t stream) {
   return in_pieces(ntiles, kMaxTilesPerLaunch, [&](uint64_t t0, uint64_t count) {
-    hipLaunchKernelGGL(stream41_tiles, dim3((unsigned)count), dim3(kThreads), 0, stream, x + t0 * kTileElems, out + t0 * kTileElems);
+    hipLaunchKernelGGL(stream41_tiles, dim3((unsigned)count), dim3(kThreads), 0, stream, x + t0 * kTileElems, out + t0 * kTileElems,
+                       kXcdLgRound);
     return hipGetLastError();
   });
 }
@@ -114,7 +117,7 @@ template <int FMT, int VAR, int W>
 hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
                         hipStream_t stream) {
   hipLaunchKernelGGL((round_tiles<FMT, VAR, W>), dim3((unsigned)ntiles), dim3(kThreads), 0, stream, x, out, nbits,
-                     seed, blk0);
+                     seed, blk0, kXcdLgRound);
   return hipGetLastError();
 }
 

@@ -10,16 +10,17 @@ namespace fbsr {
 // codes and one 8-byte store of 8 fp8 codes per lane: 3 bytes of traffic per element.
 template <int SRC, int FMT, int VAR, int W>
 __global__ __launch_bounds__(kThreads) void round16_tiles(const uint16_t* __restrict__ x, uint8_t* __restrict__ out,
-                                                          int nbits, uint64_t seed, uint64_t blk0) {
+                                                          int nbits, uint64_t seed, uint64_t blk0, uint32_t xcd_lg) {
   typedef WgTile<W> T;
   __shared__ uint4 strip[T::BLOCKS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int e0 = wave * kWaveElems + 8 * lane;                                  // tile-relative first element
-  const uint64_t g0 = (uint64_t)blockIdx.x * T::ELEMS + (uint64_t)e0;           // call-relative first element
+  const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+  const uint64_t g0 = (uint64_t)tile * T::ELEMS + (uint64_t)e0;           // call-relative first element
   const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + g0));
   if constexpr (VAR != kRNE) {
-    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, 0);
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
     __syncthreads();
   }
   const Addends a = make_addends<FMT, VAR>(nbits);
@@ -77,14 +78,14 @@ hipError_t launch_tiles_w(int W, const uint16_t* x, uint8_t* out, uint64_t ntile
                           uint64_t blk0, hipStream_t stream) {
   const dim3 grid((unsigned)ntiles), block(kThreads);
   if constexpr (VAR == kRNE) {
-    hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, nbits, seed, blk0);
+    hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16);
   } else {
     switch (W) {
-      case 1: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 1>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
-      case 2: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 2>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
-      case 4: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 4>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
-      case 8: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
-      default: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 16>), grid, block, 0, stream, x, out, nbits, seed, blk0); break;
+      case 1: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 1>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
+      case 2: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 2>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
+      case 4: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 4>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
+      case 8: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
+      default: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 16>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
     }
   }
   return hipGetLastError();

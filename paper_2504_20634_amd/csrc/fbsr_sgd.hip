@@ -10,12 +10,13 @@ namespace fbsr {
 template <int VAR, int W>
 __global__ __launch_bounds__(kThreads) void sgd_tiles(uint16_t* __restrict__ w, const float* __restrict__ g,
                                                       float neg_lr, int nbits, uint64_t seed, uint64_t step,
-                                                      uint64_t blk0) {
+                                                      uint64_t blk0, uint32_t xcd_lg) {
   typedef WgTile<W> T;
   __shared__ uint4 strip[T::BLOCKS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const uint64_t row0 = (uint64_t)blockIdx.x * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+  const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+  const uint64_t row0 = (uint64_t)tile * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
   uint64_t* wt = reinterpret_cast<uint64_t*>(w);
   f32x4 gv[kRows];
   uint64_t wv[kRows];
@@ -25,7 +26,7 @@ __global__ __launch_bounds__(kThreads) void sgd_tiles(uint16_t* __restrict__ w, 
     wv[k] = wt[row0 + (uint64_t)(k * 64)];   // read-modify-write: keep the line in L2 for the store
   }
   if constexpr (VAR != kRNE) {
-    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)blockIdx.x * T::BLOCKS, seed, step);
+    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, step);
     __syncthreads();
   }
   const Addends a = make_addends<kBF16, VAR>(nbits);
@@ -81,7 +82,7 @@ template <int VAR, int W>
 hipError_t launch_tiles(uint16_t* w, const float* g, uint64_t ntiles, float neg_lr, int nbits, uint64_t seed,
                         uint64_t step, uint64_t blk0, hipStream_t stream) {
   hipLaunchKernelGGL((sgd_tiles<VAR, W>), dim3((unsigned)ntiles), dim3(kThreads), 0, stream, w, g, neg_lr, nbits, seed,
-                     step, blk0);
+                     step, blk0, kXcdLgSgd);
   return hipGetLastError();
 }
 
