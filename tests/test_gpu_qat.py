@@ -111,6 +111,43 @@ def test_extreme_finite_values_without_nan(fbsr, oracle, fmt):
             assert first_mismatch(host(wd), ww) is None, "weights"
 
 
+@pytest.mark.parametrize("fmt", [E4M3, 3])
+def test_moments_at_the_limits_of_the_short_paths(fbsr, oracle, fmt):
+    """Second moments around 2^-96 and first moments around 2^-101: the limits below which the tile kernel leaves its
+    short division and its square root without rescaling for the full sequences.  The first eight tiles stay at or
+    above both limits (every wave on the short paths, the limits themselves included), the other eight mix in
+    values just below (the waves that meet one hand over).  Zero gradient, eps = 0 or negligible, and first moments
+    of the size of sqrt(v), so that the square root decides the update."""
+    n = 16 * 2048
+    half = n // 2
+    rng = np.random.default_rng(97 + fmt)
+    finite8 = np.array([c for c in range(256) if np.isfinite(oracle.decode(c, fmt)) and abs(oracle.decode(c, fmt)) <= 4.0],
+                       dtype=np.uint8)
+    w8 = finite8[rng.integers(0, finite8.size, n)]
+    g = rng.choice(np.array([0x0000, 0x8000], dtype=np.uint16), n)
+
+    def bf16_codes(exp_lo, exp_hi, count):      # positive, exponent uniform in [exp_lo, exp_hi], any significand
+        return ((127 + rng.integers(exp_lo, exp_hi + 1, count)).astype(np.uint16) << 7) | rng.integers(0, 128, count).astype(np.uint16)
+    v = bf16_codes(-95, -88, n)                  # beta2 v >= 0.95 * 2^-95 > 2^-96
+    v[:64] = (127 - 95) << 7                     # 2^-95 itself
+    v[half:] = np.where(rng.random(half) < 0.02, bf16_codes(-99, -96, half), v[half:])
+    # first moments of the size of sqrt(v) ~ 2^-47 in one block, around their own limit in the other
+    m = bf16_codes(-49, -45, n)
+    m[2048:4096] = bf16_codes(-100, -96, 2048)   # beta1 m >= 0.9 * 2^-100 > 2^-101
+    m[half + 2048:half + 4096] = bf16_codes(-104, -98, 2048)
+    m |= rng.integers(0, 2, n).astype(np.uint16) << 15
+    for params in ((0.5, 0.9, 0.999, 0.0, 0.01, 1 - 0.9, 1 - 0.999), (0.25, 0.9, 0.95, 1e-30, 0.0, 1 - 0.9 ** 3, 1 - 0.95 ** 3)):
+        for variant, nbits in ((RNE, 0), (SRFF, 3), (SRC, 4)):
+            print("case fmt=%d lr=%g variant=%d nbits=%d" % (fmt, params[0], variant, nbits), flush=True)
+            wd, gd, md, vd = dev(w8), dev(g), dev(m), dev(v)
+            fbsr.fbsr_qat_adamw_step(wd, gd, md, vd, fmt, params, variant, nbits, seed=23, step=6, offset=0)
+            ww, mm, vv = _oracle_step(oracle, w8, g, m, v, fmt, params, variant, nbits, 23, 6, 0)
+            assert np.count_nonzero(ww != w8) > n // 4, "the recipe leaves the weights where they are"
+            assert first_mismatch(host(md), mm) is None, "first moment"
+            assert first_mismatch(host(vd), vv) is None, "second moment"
+            assert first_mismatch(host(wd), ww) is None, "weights"
+
+
 def test_unaligned_buffers(fbsr, oracle):
     n = 3 * 2048 + 50
     w8, g, m, v = _state(n + 8, 9)
