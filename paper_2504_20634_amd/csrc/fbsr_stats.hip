@@ -96,6 +96,9 @@ __device__ __forceinline__ void decode4(uint32_t packed, float (&y)[4]) {
 // One workgroup per chunk of kStatsChunkTiles tiles.  Sums run in registers across the chunk's
 // tiles and are flushed (wave butterfly -> LDS -> record) when a bin ends and at the chunk's end:
 // record (chunk c, slot s) holds the chunk's part of bin floor(start(c) / group) + s.
+// The random bits of the whole chunk are drawn first, its Philox blocks dealt round-robin to all 256
+// threads (a tile alone has work for 16 W of them, which would leave most waves waiting), and one barrier
+// publishes them; after that the four waves walk the chunk's tiles independently.
 template <int FMT, int VAR, int W>
 __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict__ x, void* __restrict__ out,
                                                         uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
@@ -103,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
                                                         double* __restrict__ records) {
   typedef WgTile<W> T;
   typedef Fx<FMT> F;
-  __shared__ uint4 strip[2][T::BLOCKS];
+  __shared__ uint4 strip[kStatsChunkTiles * T::BLOCKS];
   __shared__ double staged[kWavesPerBlock][kStatsRecordDoubles];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -116,6 +119,16 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
   uint64_t next_bin = group - chunk_start % group;   // chunk-relative index at which the next bin starts
   uint64_t slot = 0;
   Acc cur = {0.0, 0.0, 0.0};
+  if constexpr (VAR != kRNE) {
+    const uint64_t left = ntiles - tile0;   // the grid has one workgroup per started chunk: tile0 < ntiles
+    const int nblk = (int)(left < (uint64_t)kStatsChunkTiles ? left : (uint64_t)kStatsChunkTiles) * T::BLOCKS;
+    for (int bi = threadIdx.x; bi < nblk; bi += kThreads) {
+      uint32_t o[4];
+      philox_block(blk0 + tile0 * T::BLOCKS + (uint64_t)bi, seed, 0, o);
+      strip[bi] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+    __syncthreads();
+  }
 
   auto flush = [&]() {
     const double t0 = wave_sum(cur.sy), t1 = wave_sum(cur.se), t2 = wave_sum(cur.see);
@@ -142,10 +155,6 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
     f32x4 v[kRows];
 #pragma unroll
     for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
-    if constexpr (VAR != kRNE) fill_wg_bits<W>(strip[it & 1], threadIdx.x, blk0 + tile * T::BLOCKS, seed, 0);
-    // one barrier per tile: it also orders this fill after every wave's reads of two tiles ago
-    // (they precede that wave's arrival at the previous barrier)
-    __syncthreads();
 
     uint32_t b[kRows][4];
     float y[kRows][4];
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
 #pragma unroll
       for (int k = 0; k < kRows; ++k) {
         uint64_t rb = 0;
-        if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip[it & 1], wave, lane, k);
+        if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip + it * T::BLOCKS, wave, lane, k);
         const uint32_t n4[4] = {VAR == kRNE ? 0u : slot_bits<W>(rb, 0, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 1, a.nbits),
                                 VAR == kRNE ? 0u : slot_bits<W>(rb, 2, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 3, a.nbits)};
         constexpr bool HW = !WIDE && F::kIsFp8 && VAR != kRNE;
