@@ -32,13 +32,13 @@ MEASURED_TRAFFIC_BYTES_2P28 = 1342193990
 # one-lane operations per second.  VALU instructions per element are SQ_INSTS_VALU / SQ_WAVES / elements per lane
 # from a rocprofv3 --pmc run of this file (profiles/kernels_2p28_valu_counters.md).
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-VALU_PER_ELEM = {"qat_adamw_e4m3_N3_src": 72.8, "qat_adamw_e4m3_N3_srff": 65.8, "qat_adamw_binary8p4_N3_src": 80.1,
-                 "qat_adamw_binary8p4_N3_srff": 73.1, "qat_adamw_format8_binary8p4_N3_src": 92.5,
-                 "qat_adamw_format8_binary8p4_N3_srff": 84.3, "bias_stats_e4m3_N3_srf": 24.8, "bias_stats_e4m3_N8_srf": 26.6,
-                 "bias_stats_bf16_N2_srf": 22.5, "bias_stats_bf16_N8_srf": 24.2,
+VALU_PER_ELEM = {"qat_adamw_e4m3_N3_src": 65.9, "qat_adamw_e4m3_N3_srff": 58.9, "qat_adamw_binary8p4_N3_src": 72.8,
+                 "qat_adamw_binary8p4_N3_srff": 65.8, "qat_adamw_format8_binary8p4_N3_src": 85.6,
+                 "qat_adamw_format8_binary8p4_N3_srff": 77.4, "bias_stats_e4m3_N3_srf": 24.5, "bias_stats_e4m3_N8_srf": 26.5,
+                 "bias_stats_bf16_N2_srf": 21.3, "bias_stats_bf16_N8_srf": 24.1,
                  "round_format8_binary8p4_from_fp32_N3_src": 36.4, "round_format8_binary8p4_from_fp32_N8_srf": 29.6,
-                 "round_format8_binary8p4_from_bf16_N3_src": 36.6, "round_format8_binary8p4_from_bf16_N3_srff": 27.8,
-                 "round_from_bf16_binary8p4_N3_src": 22.1, "round_from_bf16_e4m3_N3_src": 16.8}
+                 "round_format8_binary8p4_from_bf16_N3_src": 36.5, "round_format8_binary8p4_from_bf16_N3_srff": 27.8,
+                 "round_from_bf16_binary8p4_N3_src": 22.0, "round_from_bf16_e4m3_N3_src": 16.8}
 N_ELEMS = 1 << 28
 SGD_ELEMS = 1 << 27
 HEADLINE_NBITS = (2, 4, 8)
