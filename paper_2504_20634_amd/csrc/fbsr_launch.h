@@ -60,7 +60,7 @@ constexpr uint64_t kMaxTilesPerLaunch = (uint64_t)1 << 22;
 // 128-256 tiles (fp32 -> fp8 6.25 -> 6.57 TB/s, fp32 -> bf16 6.40 -> 6.70, the SGD update 6.15 -> 6.38); for
 // those that read only 16-bit and 8-bit streams (narrow-source rounding, the QAT step), and for the block-scaled
 // and generic-format kernels, no run length differs from the identity by more than run-to-run noise.
-constexpr uint32_t kXcdLgRound = 8, kXcdLgSgd = 7, kXcdLgRound16 = 0, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 0;
+constexpr uint32_t kXcdLgRound = 8, kXcdLgSgd = 7, kXcdLgRound16 = 7, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 0;
 // Largest n the library accepts.
 constexpr uint64_t kMaxElems = (uint64_t)1 << 38;
 

@@ -6,57 +6,76 @@
 
 namespace fbsr {
 
-// One workgroup per 2048-element tile, one wave per 512 elements, one 16-byte load of 8 source
-// codes and one 8-byte store of 8 fp8 codes per lane: 3 bytes of traffic per element.
+// One workgroup per PAIR of consecutive 2048-element tiles; per tile one wave takes 512 elements, a lane one
+// 16-byte load of 8 source codes and one 8-byte store of 8 fp8 codes: 3 bytes of traffic per element.  At 3 bytes
+// per element a single tile is only 6 KiB of traffic per workgroup; measured on a plain 2 : 1 stream of 2^28
+// elements, 4096 elements per workgroup reach 6.65 TB/s (with runs of 128 workgroups per XCD) where 2048 reach
+// 6.05-6.35 and 8192 6.3-6.5.  Both tiles' loads are issued first, and the pair's Philox blocks are dealt to the
+// threads together.  `ntiles` is the number of tiles of the launch; an odd one leaves the last workgroup one tile.
+constexpr int kPair16 = 2;
+
 template <int SRC, int FMT, int VAR, int W>
 __global__ __launch_bounds__(kThreads) void round16_tiles(const uint16_t* __restrict__ x, uint8_t* __restrict__ out,
-                                                          int nbits, uint64_t seed, uint64_t blk0, uint32_t xcd_lg) {
+                                                          uint32_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
+                                                          uint32_t xcd_lg) {
   typedef WgTile<W> T;
-  __shared__ uint4 strip[T::BLOCKS];
+  __shared__ uint4 strip[kPair16 * T::BLOCKS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int e0 = wave * kWaveElems + 8 * lane;                                  // tile-relative first element
-  const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
-  const uint64_t g0 = (uint64_t)tile * T::ELEMS + (uint64_t)e0;           // call-relative first element
-  const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + g0));
+  const uint32_t tile0 = xcd_tile(blockIdx.x, gridDim.x, xcd_lg) * kPair16;     // < ntiles: one workgroup per started pair
+  const int here = ntiles - tile0 < (uint32_t)kPair16 ? (int)(ntiles - tile0) : kPair16;
+  u32x4 q[kPair16];
+#pragma unroll
+  for (int t = 0; t < kPair16; ++t)
+    if (t < here) q[t] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + ((uint64_t)(tile0 + t) * T::ELEMS + (uint64_t)e0)));
   if constexpr (VAR != kRNE) {
-    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
+    for (int bi = threadIdx.x; bi < here * T::BLOCKS; bi += kThreads) {
+      uint32_t o[4];
+      philox_block(blk0 + (uint64_t)tile0 * T::BLOCKS + (uint64_t)bi, seed, 0, o);
+      strip[bi] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
     __syncthreads();
   }
   const Addends a = make_addends<FMT, VAR>(nbits);
   HwAddends hw = {0, 0, 0, 0};
   if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
-  const uint32_t words[4] = {q.x, q.y, q.z, q.w};
-  uint32_t b[8];
-  uint32_t umax = 0;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    b[j] = widen16<SRC>((words[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
-    umax = max(umax, b[j] & 0x7FFFFFFFu);
-  }
-  const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: a NaN among the wave's elements
-  uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if constexpr (VAR != kRNE) read_wg_bits8<W>(strip, e0, a.nbits, n);
-  uint32_t packed[2];
+  for (int t = 0; t < kPair16; ++t) {
+    if (t >= here) break;   // uniform over the workgroup
+    const uint32_t words[4] = {q[t].x, q[t].y, q[t].z, q[t].w};
+    uint32_t b[8];
+    uint32_t umax = 0;
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint32_t b4[4] = {b[4 * h], b[4 * h + 1], b[4 * h + 2], b[4 * h + 3]};
-    const uint32_t n4[4] = {n[4 * h], n[4 * h + 1], n[4 * h + 2], n[4 * h + 3]};
-    bool done = false;
-    if constexpr (VAR != kRNE) {
-      if (!checked) {
-        packed[h] = round4_fp8_hw<FMT, VAR>(b4, n4, hw);
-        done = true;
+    for (int j = 0; j < 8; ++j) {
+      b[j] = widen16<SRC>((words[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
+      umax = max(umax, b[j] & 0x7FFFFFFFu);
+    }
+    const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: a NaN among the wave's elements
+    uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (VAR != kRNE) read_wg_bits8<W>(strip + t * T::BLOCKS, e0, a.nbits, n);
+    uint32_t packed[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t b4[4] = {b[4 * h], b[4 * h + 1], b[4 * h + 2], b[4 * h + 3]};
+      const uint32_t n4[4] = {n[4 * h], n[4 * h + 1], n[4 * h + 2], n[4 * h + 3]};
+      bool done = false;
+      if constexpr (VAR != kRNE) {
+        if (!checked) {
+          packed[h] = round4_fp8_hw<FMT, VAR>(b4, n4, hw);
+          done = true;
+        }
+      }
+      if (!done) {
+        uint32_t r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, true>(b4[j], n4[j], a);
+        packed[h] = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
       }
     }
-    if (!done) {
-      uint32_t r[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, true>(b4[j], n4[j], a);
-      packed[h] = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
-    }
+    __builtin_nontemporal_store((uint64_t)packed[0] | ((uint64_t)packed[1] << 32),
+                                reinterpret_cast<uint64_t*>(out + ((uint64_t)(tile0 + t) * T::ELEMS + (uint64_t)e0)));
   }
-  __builtin_nontemporal_store((uint64_t)packed[0] | ((uint64_t)packed[1] << 32), reinterpret_cast<uint64_t*>(out + g0));
 }
 
 template <int SRC, int FMT, int VAR>
@@ -76,16 +95,16 @@ namespace {
 template <int SRC, int FMT, int VAR>
 hipError_t launch_tiles_w(int W, const uint16_t* x, uint8_t* out, uint64_t ntiles, int nbits, uint64_t seed,
                           uint64_t blk0, hipStream_t stream) {
-  const dim3 grid((unsigned)ntiles), block(kThreads);
+  const dim3 grid((unsigned)((ntiles + kPair16 - 1) / kPair16)), block(kThreads);
   if constexpr (VAR == kRNE) {
-    hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16);
+    hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16);
   } else {
     switch (W) {
-      case 1: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 1>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
-      case 2: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 2>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
-      case 4: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 4>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
-      case 8: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
-      default: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 16>), grid, block, 0, stream, x, out, nbits, seed, blk0, kXcdLgRound16); break;
+      case 1: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 1>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
+      case 2: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 2>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
+      case 4: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 4>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
+      case 8: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
+      default: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 16>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
     }
   }
   return hipGetLastError();

@@ -36,7 +36,7 @@ def test_every_source_code_many_draws(fbsr, oracle, src, fmt):
         assert first_mismatch(got, want) is None, (src, fmt, variant, nbits, first_mismatch(got, want))
 
 
-@pytest.mark.parametrize("n", [0, 1, 7, 8, 9, 127, 2047, 2048, 2049, 3 * 2048 + 100])
+@pytest.mark.parametrize("n", [0, 1, 7, 8, 9, 127, 2047, 2048, 2049, 3 * 2048 + 100, 4 * 2048, 5 * 2048 + 9])
 def test_sizes_offsets_alignment(fbsr, oracle, n):
     rng = np.random.default_rng(n)
     codes = rng.integers(0, 1 << 16, n + 8, dtype=np.uint16)
