@@ -55,11 +55,12 @@ inline Split split_range(uint64_t n, uint64_t offset, int W, bool no_bits, uintp
 constexpr uint64_t kMaxElemsPerLaunch = (uint64_t)1 << 30;
 // Largest tile count one tile-kernel launch may cover (2^30 threads per launch).
 constexpr uint64_t kMaxTilesPerLaunch = (uint64_t)1 << 22;
-// log2 of the run of consecutive tiles an XCD takes within a launch (xcd_tile), per kernel family; 0 keeps the
-// identity order.  From sweeps over 0..12 on 2^28 elements: the kernels that read fp32 gain 4-5 % at runs of
-// 128-256 tiles (fp32 -> fp8 6.25 -> 6.57 TB/s, fp32 -> bf16 6.40 -> 6.70, the SGD update 6.15 -> 6.38); for
-// those that read only 16-bit and 8-bit streams (narrow-source rounding, the QAT step), and for the block-scaled
-// and generic-format kernels, no run length differs from the identity by more than run-to-run noise.
+// log2 of the run of consecutive tiles (for the narrow-source kernel: pairs of tiles) an XCD takes within a launch
+// (xcd_tile), per kernel family; 0 keeps the identity order.  From sweeps over 0..12 on 2^28 elements: the kernels that
+// read fp32 gain 4-5 % at runs of 128-256 tiles (fp32 -> fp8 6.25 -> 6.57 TB/s, fp32 -> bf16 6.40 -> 6.70, the SGD
+// update 6.15 -> 6.38), a plain 16-bit -> 8-bit stream with 4096 elements per workgroup 5 % at runs of 128 (6.35 ->
+// 6.65); for the QAT step, the block-scaled and the generic-format kernels no run length differs from the identity by
+// more than run-to-run noise.
 constexpr uint32_t kXcdLgRound = 8, kXcdLgSgd = 7, kXcdLgRound16 = 7, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 0;
 // Largest n the library accepts.
 constexpr uint64_t kMaxElems = (uint64_t)1 << 38;
