@@ -59,13 +59,19 @@ typedef enum {
 
 typedef enum {
   FBSR_OK = 0,
-  FBSR_EINVAL = 1,  /* bad enum, nbits outside [1, FBSR_MAX_NBITS], null pointer, group == 0, ... */
+  FBSR_EINVAL = 1,  /* bad enum, nbits outside [1, the entry point's maximum], null pointer, group == 0, ... */
   FBSR_EALIGN = 2,  /* a pointer is not aligned to its element type                              */
   FBSR_ERANGE = 3,  /* an element would fall outside the caller's bins / workspace too small     */
   FBSR_EDEVICE = 4  /* the HIP runtime reported an error at launch                               */
 } fbsr_status;
 
+/* Largest nbits.  The rounding entry points (fbsr_round, fbsr_round_from16, fbsr_round_format8) take up to
+ * FBSR_MAX_NBITS_ROUND, which covers every bit an fp32 source can drop towards an 8-bit target (D = 20 for E4M3 and
+ * binary8p4, 21 for E5M2), so that nbits >= D gives classical SR; calls with more than FBSR_MAX_NBITS bits run on a
+ * slower kernel (one Philox block computed per element).  The fused updates, the block-scaled rounding and the
+ * statistics take up to FBSR_MAX_NBITS. */
 #define FBSR_MAX_NBITS 16
+#define FBSR_MAX_NBITS_ROUND 24
 
 /* 16-bit source formats of fbsr_round_from16. */
 typedef enum {

@@ -12,9 +12,9 @@ bool valid_fmt(int fmt) { return fmt >= FBSR_FMT_BF16 && fmt <= FBSR_FMT_BINARY8
 
 bool is_8bit_fmt(int fmt) { return fmt == FBSR_FMT_E4M3 || fmt == FBSR_FMT_E5M2 || fmt == FBSR_FMT_BINARY8P4; }
 
-int check_common(int variant, int nbits, uint64_t n, uint64_t offset) {
+int check_common(int variant, int nbits, uint64_t n, uint64_t offset, int max_nbits = FBSR_MAX_NBITS) {
   if (variant < FBSR_RNE || variant > FBSR_SRC) return FBSR_EINVAL;
-  if (variant != FBSR_RNE && (nbits < 1 || nbits > FBSR_MAX_NBITS)) return FBSR_EINVAL;
+  if (variant != FBSR_RNE && (nbits < 1 || nbits > max_nbits)) return FBSR_EINVAL;
   if (n > fbsr::kMaxElems || offset > UINT64_MAX - n) return FBSR_EINVAL;
   return FBSR_OK;
 }
@@ -87,13 +87,14 @@ void decode_table8(const fbsr_format8& d, fbsr::Table8* t) {
 }
 
 // The addend constants of a rounding mode in a code space with 24 fraction bits.
-bool derive_mode8(int variant, int nbits, fbsr::Mode8* m) {
+bool derive_mode8(int variant, int nbits, int max_nbits, fbsr::Mode8* m) {
   const bool draws = variant == FBSR_SRFF || variant == FBSR_SRF || variant == FBSR_SRC || variant == FBSR_SRC_TIES_ODD;
   if (variant < FBSR_RNE || variant > FBSR_RNA) return false;
-  if (draws && (nbits < 1 || nbits > FBSR_MAX_NBITS)) return false;
+  if (draws && (nbits < 1 || nbits > max_nbits)) return false;
   m->nbits = draws ? (uint32_t)nbits : 0u;
   m->shift = 24u - m->nbits;
-  const uint32_t half = 1u << (m->shift - 1);   // half of the last kept place
+  m->srf = variant == FBSR_SRF;
+  const uint32_t half = m->shift >= 1u ? 1u << (m->shift - 1) : 0u;   // half of the last kept place
   m->tie_xor = (variant == FBSR_SRC_TIES_ODD || variant == FBSR_RNO) ? 1u : 0u;
   m->ties = variant == FBSR_RNE || variant == FBSR_RNO || variant == FBSR_SRC || variant == FBSR_SRC_TIES_ODD;
   m->fixed = m->ties ? half - 1u : (variant == FBSR_SRF || variant == FBSR_RNA) ? half : 0u;
@@ -121,7 +122,7 @@ extern "C" {
 int fbsr_round(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                uint64_t offset, void* stream) {
   if (!valid_fmt(fmt)) return FBSR_EINVAL;
-  const int c = check_common(variant, nbits, n, offset);
+  const int c = check_common(variant, nbits, n, offset, FBSR_MAX_NBITS_ROUND);
   if (c != FBSR_OK) return c;
   if (n == 0) return FBSR_OK;
   if (x == nullptr || out == nullptr) return FBSR_EINVAL;
@@ -135,7 +136,7 @@ int fbsr_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt
                       uint64_t seed, uint64_t offset, void* stream) {
   if (!is_8bit_fmt(fmt)) return FBSR_EINVAL;
   if (src_fmt != FBSR_SRC_BF16 && src_fmt != FBSR_SRC_FP16) return FBSR_EINVAL;
-  const int c = check_common(variant, nbits, n, offset);
+  const int c = check_common(variant, nbits, n, offset, FBSR_MAX_NBITS_ROUND);
   if (c != FBSR_OK) return c;
   if (n == 0) return FBSR_OK;
   if (x == nullptr || out == nullptr) return FBSR_EINVAL;
@@ -217,7 +218,7 @@ int fbsr_round_format8(const void* x, int src, void* out, uint64_t n, const fbsr
                        uint64_t seed, uint64_t offset, void* stream) {
   fbsr::Fmt8 f;
   fbsr::Mode8 m;
-  if (fmt == nullptr || !derive_format8(*fmt, &f) || !derive_mode8(variant, nbits, &m)) return FBSR_EINVAL;
+  if (fmt == nullptr || !derive_format8(*fmt, &f) || !derive_mode8(variant, nbits, FBSR_MAX_NBITS_ROUND, &m)) return FBSR_EINVAL;
   if (src != FBSR_FROM_BF16 && src != FBSR_FROM_FP16 && src != FBSR_FROM_FP32) return FBSR_EINVAL;
   if (n > fbsr::kMaxElems || offset > UINT64_MAX - n) return FBSR_EINVAL;
   if (n == 0) return FBSR_OK;
@@ -233,7 +234,7 @@ int fbsr_qat_adamw_step_format8(void* w8, const void* g16, void* m16, void* v16,
                                 void* stream) {
   fbsr::Fmt8 f;
   fbsr::Mode8 m;
-  if (fmt == nullptr || !derive_format8(*fmt, &f) || !derive_mode8(variant, nbits, &m)) return FBSR_EINVAL;
+  if (fmt == nullptr || !derive_format8(*fmt, &f) || !derive_mode8(variant, nbits, FBSR_MAX_NBITS, &m)) return FBSR_EINVAL;
   if (n > fbsr::kMaxElems || offset > UINT64_MAX - n) return FBSR_EINVAL;
   if (p == nullptr) return FBSR_EINVAL;
   if (n == 0) return FBSR_OK;

@@ -218,16 +218,91 @@ __device__ __forceinline__ uint32_t round_magnitude(uint32_t bits, uint32_t r0, 
   return r;
 }
 
-// Rounds one fp32 pattern.  Returns the signed code in the top (32 - FRAC) bits; the low FRAC
-// bits are garbage.
-template <int FMT, int VAR, bool CHECKED>
-__device__ __forceinline__ uint32_t round_pattern(uint32_t bits, uint32_t n, const Addends& a) {
-  const uint32_t mag = round_magnitude<FMT, VAR, CHECKED>(bits, to_code_space<FMT, VAR>(bits), n, a);
+// The rounded magnitude with the sign of the source pattern.
+template <int FMT>
+__device__ __forceinline__ uint32_t with_sign(uint32_t mag, uint32_t bits) {
   if constexpr (FMT == kP4) {
     // no negative zero: a zero magnitude drops the sign (the NaN code, bit 31 alone, passes unchanged)
     return (mag & 0x7F000000u) != 0u ? (mag | (bits & 0x80000000u)) : mag;
   } else {
     return mag | (bits & 0x80000000u);
+  }
+}
+
+// Rounds one fp32 pattern.  Returns the signed code in the top (32 - FRAC) bits; the low FRAC
+// bits are garbage.
+template <int FMT, int VAR, bool CHECKED>
+__device__ __forceinline__ uint32_t round_pattern(uint32_t bits, uint32_t n, const Addends& a) {
+  return with_sign<FMT>(round_magnitude<FMT, VAR, CHECKED>(bits, to_code_space<FMT, VAR>(bits), n, a), bits);
+}
+
+// ------------------------------------------------------------ more than 16 random bits ---
+// N = 17 .. 24.  |x| / (spacing of the target around x) as a whole part (the magnitude code) and 32 fraction bits,
+// plus a sticky bit for what lies below them.  A target-normal |x| drops at most 21 bits, so its fraction is exact;
+// a target-subnormal |x| sits on a fixed grid (Eq. (2) clamps the exponent) and may reach far below it, which is
+// where the 24-bit code space of the main path would be too short for an addend this fine.
+struct WideCode {
+  uint32_t whole, frac;
+  bool sticky;
+};
+
+// u = |pattern| of a finite value, rebias = (127 - B) << 23, p = P, u_sub = pattern of 2^(1-B), bp = B + P.
+__device__ __forceinline__ WideCode wide_code(uint32_t u, uint32_t rebias, uint32_t p, uint32_t u_sub, int bp) {
+  WideCode c;
+  c.sticky = false;
+  if (u >= u_sub) {
+    const uint32_t r0 = (u - rebias) << p;   // code in the top 8 bits, 24 fraction bits (wraps consistently mod 2^32)
+    c.whole = r0 >> 24;
+    c.frac = r0 << 8;
+  } else {
+    const uint32_t field = u >> 23;
+    const uint32_t m = field != 0u ? ((u & 0x007FFFFFu) | 0x00800000u) : u;   // fp32 subnormals carry no hidden one
+    const int sh = (int)(field != 0u ? field : 1u) + bp - 120;   // |x| / 2^(2-B-P) * 2^32 = m 2^sh; sh <= 7 + P here
+    uint64_t r = 0;
+    if (sh >= 0) {
+      r = (uint64_t)m << sh;
+    } else if (sh > -25) {
+      r = m >> (-sh);
+      c.sticky = (m & ((1u << (-sh)) - 1u)) != 0u;
+    } else {
+      c.sticky = m != 0u;
+    }
+    c.whole = (uint32_t)(r >> 32);
+    c.frac = (uint32_t)r;
+  }
+  return c;
+}
+
+// 1 when the variant rounds up.  srf: add the half of Eq. (SRF); src: the inner round-to-nearest of Eq. (7), its ties
+// to even (tie_xor = 0) or odd (1) in the last of the N kept fraction bits.  17 <= N <= 24, n < 2^N.
+__device__ __forceinline__ uint32_t wide_round_up(const WideCode& c, uint32_t n, uint32_t N, bool srf, bool src, uint32_t tie_xor) {
+  if (src) {
+    const uint32_t drop = 32u - N;   // 8 .. 15
+    const uint32_t h = c.frac >> drop, rem = c.frac & ((1u << drop) - 1u), half = 1u << (drop - 1u);
+    const bool inc = rem > half || (rem == half && (c.sticky || ((h & 1u) ^ tie_xor) != 0u));
+    return (h + (inc ? 1u : 0u) + n) >> N;   // Round(delta 2^N) + n >= 2^N
+  }
+  // below the lowest addend bit nothing can carry, so neither the low fraction bits nor the sticky bit matter
+  const uint64_t add = ((uint64_t)n << (32u - N)) + (srf ? (uint64_t)(1u << (31u - N)) : 0u);
+  return (uint32_t)(((uint64_t)c.frac + add) >> 32);
+}
+
+// round_pattern for N = 17 .. 24 (the per-element kernels; any pattern).
+template <int FMT, int VAR>
+__device__ __forceinline__ uint32_t round_pattern_wide(uint32_t bits, uint32_t n, uint32_t N) {
+  typedef Fx<FMT> F;
+  static_assert(VAR != kRNE, "nearest-even draws no bits");
+  if constexpr (!F::kIsFp8) {
+    // bf16 drops D = 16 bits, all of them within 16 fraction bits: with N >= D every variant is exact SR on the
+    // top D bits of n (App. A-C), which is what the addends of N = 16 compute
+    return round_pattern<FMT, VAR, true>(bits, n >> (N - 16u), make_addends<FMT, VAR>(16));
+  } else {
+    const uint32_t u = bits & 0x7FFFFFFFu;
+    // |x| > M or NaN: no randomness enters (Sec. II), any N gives the same code
+    if (u > F::U_MAXFIN) return round_pattern<FMT, VAR, true>(bits, 0u, make_addends<FMT, VAR>(1));
+    const WideCode c = wide_code(u, F::Q << 23, (uint32_t)F::S, F::U_SUB, F::B + F::P);
+    const uint32_t up = wide_round_up(c, n, N, VAR == kSRF, VAR == kSRC, 0u);
+    return with_sign<FMT>((c.whole + up) << 24, bits);
   }
 }
 
@@ -479,7 +554,19 @@ struct Mode8 {
   uint32_t fixed;       // the part of the addend that does not depend on the element
   uint32_t tie_xor;     // inner rounding: 0 ties-to-even, 1 ties-to-odd
   bool ties;            // the mode has an inner round-to-nearest (RNE, RNO, both SRC)
+  bool srf;             // the mode adds half a step of the random grid (SRF)
 };
+
+// From the rounded magnitude code to the output byte: codes above M become the infinity (or M, saturating),
+// the sign goes on (a zero keeps it only in formats with -0), a NaN input becomes the NaN code.
+template <bool CHECKED>
+__device__ __forceinline__ uint32_t finish8(uint32_t mag, uint32_t bits, const Fmt8& f) {
+  mag = mag > f.max_code ? f.over_code : mag;
+  const uint32_t sgn = (bits >> f.sign_shift) & f.sign_bit;
+  uint32_t code = mag | (mag == 0u ? (sgn & f.zero_sign) : sgn);
+  if constexpr (CHECKED) code = (bits & 0x7FFFFFFFu) > 0x7F800000u ? (f.nan_code | (sgn & f.nan_sign)) : code;
+  return code;
+}
 
 // One source pattern -> the output byte.  n < 2^N is the element's random integer (0 when the mode
 // draws none).  CHECKED = false may be used only when the pattern is known not to be a NaN.
@@ -503,12 +590,17 @@ __device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8
     add += ((parity_of >> m.shift) & 1u) ^ m.tie_xor;
   }
   add = u > f.u_max ? f.det_add : add;   // |x| > M: no randomness (Sec. II)
-  uint32_t mag = (r0 + add) >> 24;
-  mag = mag > f.max_code ? f.over_code : mag;
-  const uint32_t sgn = (bits >> f.sign_shift) & f.sign_bit;
-  uint32_t code = mag | (mag == 0u ? (sgn & f.zero_sign) : sgn);
-  if constexpr (CHECKED) code = u > 0x7F800000u ? (f.nan_code | (sgn & f.nan_sign)) : code;
-  return code;
+  return finish8<CHECKED>((r0 + add) >> 24, bits, f);
+}
+
+// round8 for N = 17 .. 24 (the per-element kernel; any pattern): see round_pattern_wide.
+__device__ __forceinline__ uint32_t round8_wide(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m) {
+  const uint32_t u = bits & 0x7FFFFFFFu;
+  if (u > f.u_max) return round8<false, true>(bits, 0u, f, m);   // |x| > M or NaN: the addend does not depend on the mode
+  const int bp = (int)(__float_as_uint(f.sub_scale) >> 23) - 127 - 22;   // B + P from sub_scale = 2^(22 + B + P)
+  const WideCode c = wide_code(u, f.rebias, f.shift_p, f.u_sub, bp);
+  const uint32_t up = wide_round_up(c, n, m.nbits, m.srf, m.ties, m.tie_xor);
+  return finish8<false>(c.whole + up, bits, f);
 }
 
 __device__ __forceinline__ uint32_t pack4_bytes(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {

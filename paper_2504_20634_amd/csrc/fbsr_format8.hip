@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void format8_elems(const void* __restrict
   else bits = widen16<SRC>(reinterpret_cast<const uint16_t*>(xin)[j]);
   uint32_t rnd = 0;
   if (W != 0) rnd = element_bits(offset + j, log2_per_block, W, m.nbits, seed, 0);
-  out[j] = (uint8_t)round8<TIES, true>(bits, rnd, f, m);
+  out[j] = (uint8_t)(m.nbits > (uint32_t)kMaxTileNbits ? round8_wide(bits, rnd, f, m) : round8<TIES, true>(bits, rnd, f, m));
 }
 
 namespace {
@@ -124,8 +124,9 @@ hipError_t run(const void* xin, uint8_t* out, uint64_t n, const Fmt8& f, const M
   constexpr uint64_t oalign = SRC == kSrcFP32 ? 4 : 8;
   const char* x = reinterpret_cast<const char*>(xin);
   const int W = m.nbits ? slot_width((int)m.nbits) : 0;
-  const Split s = split_range(n, offset, W ? W : 8, W == 0, reinterpret_cast<uintptr_t>(x), isize, 16,
-                              reinterpret_cast<uintptr_t>(out), 1, oalign);
+  Split s = split_range(n, offset, W ? W : 8, W == 0, reinterpret_cast<uintptr_t>(x), isize, 16,
+                        reinterpret_cast<uintptr_t>(out), 1, oalign);
+  if (m.nbits > (uint32_t)kMaxTileNbits) s.head = s.ntiles = 0;   // more than 16 bits: the per-element kernel throughout
   return run_split(
       s, n,
       [&](uint64_t first, uint64_t count) {

@@ -76,10 +76,14 @@ __global__ __launch_bounds__(kThreads) void round_elems(const float* __restrict_
                                                         uint64_t seed, uint64_t offset) {
   const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
   if (j >= n) return;
-  const Addends a = make_addends<FMT, VAR>(nbits);
-  uint32_t rnd = 0;
-  if constexpr (VAR != kRNE) rnd = element_bits(offset + j, log2_per_block, W, a.nbits, seed, 0);
-  const uint32_t r = round_pattern<FMT, VAR, true>(__float_as_uint(x[j]), rnd, a);
+  uint32_t r;
+  if constexpr (VAR != kRNE) {
+    const uint32_t rnd = element_bits(offset + j, log2_per_block, W, (uint32_t)nbits, seed, 0);
+    if (nbits > kMaxTileNbits) r = round_pattern_wide<FMT, VAR>(__float_as_uint(x[j]), rnd, (uint32_t)nbits);   // uniform over the launch
+    else r = round_pattern<FMT, VAR, true>(__float_as_uint(x[j]), rnd, make_addends<FMT, VAR>(nbits));
+  } else {
+    r = round_pattern<FMT, VAR, true>(__float_as_uint(x[j]), 0u, make_addends<FMT, VAR>(nbits));
+  }
   typedef typename Fx<FMT>::code_t code_t;
   reinterpret_cast<code_t*>(out)[j] = (code_t)(r >> Fx<FMT>::FRAC);
 }
@@ -139,8 +143,9 @@ hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, 
                hipStream_t stream) {
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
   const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
-  const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
-                              reinterpret_cast<uintptr_t>(out), osize, 4 * osize);
+  Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
+                        reinterpret_cast<uintptr_t>(out), osize, 4 * osize);
+  if (VAR != kRNE && nbits > kMaxTileNbits) s.head = s.ntiles = 0;   // more than 16 bits: the per-element kernel throughout
   char* o = reinterpret_cast<char*>(out);
   return run_split(
       s, n,

@@ -84,10 +84,15 @@ __global__ __launch_bounds__(kThreads) void round16_elems(const uint16_t* __rest
                                                           uint64_t seed, uint64_t offset) {
   const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
   if (j >= n) return;
-  const Addends a = make_addends<FMT, VAR>(nbits);
-  uint32_t rnd = 0;
-  if constexpr (VAR != kRNE) rnd = element_bits(offset + j, log2_per_block, W, a.nbits, seed, 0);
-  out[j] = (uint8_t)(round_pattern<FMT, VAR, true>(widen16<SRC>(x[j]), rnd, a) >> Fx<FMT>::FRAC);
+  uint32_t r;
+  if constexpr (VAR != kRNE) {
+    const uint32_t rnd = element_bits(offset + j, log2_per_block, W, (uint32_t)nbits, seed, 0);
+    if (nbits > kMaxTileNbits) r = round_pattern_wide<FMT, VAR>(widen16<SRC>(x[j]), rnd, (uint32_t)nbits);   // uniform over the launch
+    else r = round_pattern<FMT, VAR, true>(widen16<SRC>(x[j]), rnd, make_addends<FMT, VAR>(nbits));
+  } else {
+    r = round_pattern<FMT, VAR, true>(widen16<SRC>(x[j]), 0u, make_addends<FMT, VAR>(nbits));
+  }
+  out[j] = (uint8_t)(r >> Fx<FMT>::FRAC);
 }
 
 namespace {
@@ -114,8 +119,9 @@ template <int SRC, int FMT, int VAR>
 hipError_t run(const uint16_t* x, uint8_t* out, uint64_t n, int nbits, uint64_t seed, uint64_t offset,
                hipStream_t stream) {
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
-  const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 2, 16,
-                              reinterpret_cast<uintptr_t>(out), 1, 8);
+  Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 2, 16,
+                        reinterpret_cast<uintptr_t>(out), 1, 8);
+  if (VAR != kRNE && nbits > kMaxTileNbits) s.head = s.ntiles = 0;   // more than 16 bits: the per-element kernel throughout
   return run_split(
       s, n,
       [&](uint64_t first, uint64_t count) {

@@ -45,6 +45,7 @@ def test_enums_match_the_header():
                       ("FBSR_ERANGE", b.ERANGE), ("FBSR_EDEVICE", b.EDEVICE)):
         assert re.search(r"\b%s\s*=\s*%d\b" % (name, val), text), name
     assert re.search(r"#define\s+FBSR_MAX_NBITS\s+%d" % b.MAX_NBITS, text)
+    assert re.search(r"#define\s+FBSR_MAX_NBITS_ROUND\s+%d" % b.MAX_NBITS_ROUND, text)
     for name, val in (("FBSR_FROM_BF16", b.FROM_BF16), ("FBSR_FROM_FP16", b.FROM_FP16), ("FBSR_FROM_FP32", b.FROM_FP32),
                       ("FBSR_SRC_TIES_ODD", b.SRC_TIES_ODD), ("FBSR_RNO", b.RNO), ("FBSR_RNA", b.RNA)):
         assert re.search(r"#define\s+%s\s+%d\b" % (name, val), text), name
@@ -66,9 +67,16 @@ def test_argument_validation_happens_on_the_host(L):
     assert L.fbsr_sgd_update(None, None, 0, 0.1, 1, 2, 0, 0, 0, None) == OK
     assert L.fbsr_bias_stats(None, None, 0, 0, 1, 2, 0, 0, 1, 0, 1, None, None, 0, None) == OK
     # bad enums / nbits
-    for fmt, var, nb in ((4, 1, 2), (-1, 1, 2), (0, 4, 2), (0, -1, 2), (0, 1, 0), (0, 2, 17), (1, 3, -5)):
+    for fmt, var, nb in ((4, 1, 2), (-1, 1, 2), (0, 4, 2), (0, -1, 2), (0, 1, 0), (0, 2, 25), (1, 3, -5)):
         assert L.fbsr_round(p(good), p(good), 8, fmt, var, nb, 0, 0, None) == EINVAL
         assert L.fbsr_bias_stats(p(good), None, 8, fmt, var, nb, 0, 0, 4, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
+    # the rounding entry points take up to 24 bits, everything else up to 16
+    assert L.fbsr_bias_stats(p(good), None, 8, 1, 1, 17, 0, 0, 4, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
+    assert L.fbsr_round_block_scaled(p(good), p(good), p(good), 8, 1, 1, 17, 0, 0, None) == EINVAL
+    assert L.fbsr_sgd_update(p(good), p(good), 8, 0.1, 1, 17, 0, 0, 0, None) == EINVAL
+    assert L.fbsr_round_from16(p(good), p(good), 8, 0, 1, 1, 25, 0, 0, None) == EINVAL
+    assert L.fbsr_round(p(good + 2), p(good), 8, 1, 1, 24, 0, 0, None) == EALIGN      # 24 passes the nbits check
+    assert L.fbsr_round_from16(p(good + 1), p(good), 8, 0, 1, 1, 24, 0, 0, None) == EALIGN
     assert L.fbsr_sgd_update(p(good), p(good), 8, 0.1, 5, 2, 0, 0, 0, None) == EINVAL
     assert L.fbsr_sgd_update(p(good), p(good), 8, 0.1, 1, 99, 0, 0, 0, None) == EINVAL
     for src, fmt in ((2, 1), (0, 0), (1, 4), (-1, 2)):
@@ -149,13 +157,14 @@ def test_format8_argument_validation(L):
     ref = ctypes.byref(f)
     assert L.fbsr_round_format8(None, 2, None, 0, ref, 1, 3, 0, 0, None) == OK
     assert L.fbsr_round_format8(p(good), 2, p(good), 8, None, 1, 3, 0, 0, None) == EINVAL
-    for src, var, nb in ((3, 1, 3), (-1, 1, 3), (2, 7, 3), (2, -1, 3), (2, 1, 0), (2, 4, 17), (2, 3, -2)):
+    for src, var, nb in ((3, 1, 3), (-1, 1, 3), (2, 7, 3), (2, -1, 3), (2, 1, 0), (2, 4, 25), (2, 3, -2)):
         assert L.fbsr_round_format8(p(good), src, p(good), 8, ref, var, nb, 0, 0, None) == EINVAL
     bad = b.Format8(8, 4, 8, 0x7E, 0x7E, 0x80, 0, 0)
     assert L.fbsr_round_format8(p(good), 2, p(good), 8, ctypes.byref(bad), 1, 3, 0, 0, None) == EINVAL
     assert L.fbsr_round_format8(None, 2, p(good), 8, ref, 1, 3, 0, 0, None) == EINVAL
     assert L.fbsr_round_format8(p(good), 2, None, 8, ref, 1, 3, 0, 0, None) == EINVAL
     assert L.fbsr_round_format8(p(good + 2), 2, p(good), 8, ref, 1, 3, 0, 0, None) == EALIGN
+    assert L.fbsr_round_format8(p(good + 2), 2, p(good), 8, ref, 4, 24, 0, 0, None) == EALIGN      # 24 passes the nbits check
     assert L.fbsr_round_format8(p(good + 1), 0, p(good), 8, ref, 1, 3, 0, 0, None) == EALIGN
     assert L.fbsr_round_format8(p(good), 2, p(good), (1 << 38) + 1, ref, 1, 3, 0, 0, None) == EINVAL
     assert L.fbsr_round_format8(p(good), 2, p(good), 8, ref, 1, 3, 0, (1 << 64) - 4, None) == EINVAL

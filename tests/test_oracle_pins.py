@@ -193,6 +193,24 @@ def test_exhaustive_round_up_counts(oracle, fmt, nbits):
             assert int(u) == expected_ups(delta, variant, nbits), (float(x), variant, nbits)
 
 
+@pytest.mark.parametrize("fmt,nbits", [(E4M3, 19), (E4M3, 24), (E5M2, 23)])
+def test_exhaustive_round_up_counts_many_bits_below_the_smallest_normal(oracle, fmt, nbits):
+    """All 2^N draws for N up to 24 on inputs in and far below the target's subnormal range, where the fixed grid
+    (Eq. (2) clamps the exponent) drops more than 24 bits: the counts still equal those the predicates imply, in
+    exact rational arithmetic."""
+    rng = np.random.default_rng(5 * fmt + nbits)
+    lo_field = {E4M3: 127 - 9 - 30, E5M2: 127 - 16 - 30}[fmt]                 # down to 2^-30 of the subnormal spacing
+    hi_field = {E4M3: 127 - 6, E5M2: 127 - 14}[fmt]                           # the smallest normal binade
+    fields = rng.integers(lo_field, hi_field + 1, 5).astype(np.uint32)
+    xs = ((fields << np.uint32(23)) | rng.integers(0, 1 << 23, 5, dtype=np.uint32)).view(np.float32)
+    xs = np.concatenate([xs, np.array([2.0 ** -9 * 1.5, 2.0 ** -16 * 2.5 + 2.0 ** -39], dtype=np.float32)])   # a tie, a near tie
+    for variant in SR_VARIANTS:
+        ups = oracle.count_up(xs, fmt, variant, nbits)
+        for x, u in zip(xs, ups):
+            _, delta = delta_of(abs(f32_fraction(x)), fmt)
+            assert int(u) == expected_ups(delta, variant, nbits), (float(x), variant, nbits)
+
+
 @pytest.mark.parametrize("fmt,nbits", [(BF16, 16), (BF16, 18), (E4M3, 20), (E5M2, 21), (E5M2, 22)])
 def test_enough_bits_is_exact_sr(oracle, fmt, nbits):
     """N >= D: every variant rounds up with probability exactly delta (App. A-C: the floor
