@@ -67,8 +67,8 @@ typedef enum {
 
 /* Largest nbits.  The rounding entry points (fbsr_round, fbsr_round_from16, fbsr_round_format8) take up to
  * FBSR_MAX_NBITS_ROUND, which covers every bit an fp32 source can drop towards an 8-bit target (D = 20 for E4M3 and
- * binary8p4, 21 for E5M2), so that nbits >= D gives classical SR; calls with more than FBSR_MAX_NBITS bits run on a
- * slower kernel (one Philox block computed per element).  The fused updates, the block-scaled rounding and the
+ * binary8p4, 21 for E5M2), so that nbits >= D gives classical SR; calls with more than FBSR_MAX_NBITS bits use 32-bit
+ * slots (4 elements per Philox block) and a slower rounding that keeps 32 fraction bits.  The fused updates, the block-scaled rounding and the
  * statistics take up to FBSR_MAX_NBITS. */
 #define FBSR_MAX_NBITS 16
 #define FBSR_MAX_NBITS_ROUND 24

@@ -24,6 +24,27 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
     fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
     __syncthreads();
   }
+  if constexpr (W == 32 && VAR != kRNE) {
+    // more than 16 random bits: one 32-bit slot per element, every element on the wide path
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) {
+      const uint4 q = strip[(wave * kWaveElems + k * 256 + 4 * lane) / 4];   // the row's four slots: one Philox block
+      const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z), __float_as_uint(v[k].w)};
+      const uint32_t s4[4] = {q.x, q.y, q.z, q.w};
+      uint32_t r[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        r[j] = round_pattern_wide<FMT, VAR>(b[j], __builtin_amdgcn_ubfe(s4[j], 0u, (uint32_t)nbits), (uint32_t)nbits);
+      const uint64_t row = row0 + (uint64_t)(k * 64);
+      if constexpr (Fx<FMT>::kIsFp8) {
+        __builtin_nontemporal_store(pack4_fp8<FMT>(r[0], r[1], r[2], r[3]), reinterpret_cast<uint32_t*>(out) + row);
+      } else {
+        const uint64_t pv = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
+        __builtin_nontemporal_store(pv, reinterpret_cast<uint64_t*>(out) + row);
+      }
+    }
+    return;
+  }
   const Addends a = make_addends<FMT, VAR>(nbits);
   HwAddends hw = {0, 0, 0, 0};
   if constexpr (Fx<FMT>::kIsFp8 && VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
@@ -134,7 +155,8 @@ hipError_t launch_tiles_w(int W, const float* x, void* out, uint64_t ntiles, int
     case 2: return launch_tiles<FMT, VAR, 2>(x, out, ntiles, nbits, seed, blk0, stream);
     case 4: return launch_tiles<FMT, VAR, 4>(x, out, ntiles, nbits, seed, blk0, stream);
     case 8: return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, stream);
-    default: return launch_tiles<FMT, VAR, 16>(x, out, ntiles, nbits, seed, blk0, stream);
+    case 16: return launch_tiles<FMT, VAR, 16>(x, out, ntiles, nbits, seed, blk0, stream);
+    default: return launch_tiles<FMT, VAR, 32>(x, out, ntiles, nbits, seed, blk0, stream);
   }
 }
 
@@ -143,9 +165,8 @@ hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, 
                hipStream_t stream) {
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
   const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
-  Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
-                        reinterpret_cast<uintptr_t>(out), osize, 4 * osize);
-  if (VAR != kRNE && nbits > kMaxTileNbits) s.head = s.ntiles = 0;   // more than 16 bits: the per-element kernel throughout
+  const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
+                              reinterpret_cast<uintptr_t>(out), osize, 4 * osize);
   char* o = reinterpret_cast<char*>(out);
   return run_split(
       s, n,
