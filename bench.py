@@ -38,7 +38,7 @@ VALU_PER_ELEM = {"qat_adamw_e4m3_N3_src": 65.9, "qat_adamw_e4m3_N3_srff": 58.9, 
                  "bias_stats_bf16_N2_srf": 21.3, "bias_stats_bf16_N8_srf": 24.1,
                  "round_format8_binary8p4_from_fp32_N3_src": 36.4, "round_format8_binary8p4_from_fp32_N8_srf": 29.6,
                  "round_format8_binary8p4_from_bf16_N3_src": 36.5, "round_format8_binary8p4_from_bf16_N3_srff": 27.8,
-                 "round_from_bf16_binary8p4_N3_src": 22.0, "round_from_bf16_e4m3_N3_src": 16.8}
+                 "round_from_bf16_binary8p4_N3_src": 22.4, "round_from_bf16_e4m3_N3_src": 17.2}
 N_ELEMS = 1 << 28
 SGD_ELEMS = 1 << 27
 HEADLINE_NBITS = (2, 4, 8)
