@@ -16,8 +16,8 @@ SRC_TIES_ODD, RNO, RNA = 4, 5, 6          # fbsr_round_format8 only
 SRC_BF16, SRC_FP16 = 0, 1
 FROM_BF16, FROM_FP16, FROM_FP32 = 0, 1, 2  # source types of fbsr_round_format8
 OK, EINVAL, EALIGN, ERANGE, EDEVICE = 0, 1, 2, 3, 4
-MAX_NBITS = 16            # fused updates, block-scaled rounding, statistics
-MAX_NBITS_ROUND = 24      # fbsr_round, fbsr_round_from16, fbsr_round_format8
+MAX_NBITS = 16            # the fused updates (SGD, QAT steps)
+MAX_NBITS_ROUND = 24      # every other entry point
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2", FMT_BINARY8P4: "binary8p4"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
 EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_workspace_bytes",

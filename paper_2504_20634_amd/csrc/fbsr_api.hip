@@ -161,7 +161,7 @@ int fbsr_sgd_update(void* w, const float* g, uint64_t n, float lr, int variant, 
 int fbsr_round_block_scaled(const float* x, void* out, void* scales, uint64_t n, int fmt, int variant, int nbits,
                             uint64_t seed, uint64_t offset, void* stream) {
   if (!is_8bit_fmt(fmt)) return FBSR_EINVAL;
-  const int c = check_common(variant, nbits, n, offset);
+  const int c = check_common(variant, nbits, n, offset, FBSR_MAX_NBITS_ROUND);
   if (c != FBSR_OK) return c;
   if (n == 0) return FBSR_OK;
   if (x == nullptr || out == nullptr || scales == nullptr) return FBSR_EINVAL;
@@ -261,7 +261,7 @@ int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant,
                     uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
                     void* workspace, uint64_t workspace_bytes, void* stream) {
   if (!valid_fmt(fmt)) return FBSR_EINVAL;
-  const int c = check_common(variant, nbits, n, offset);
+  const int c = check_common(variant, nbits, n, offset, FBSR_MAX_NBITS_ROUND);
   if (c != FBSR_OK) return c;
   if (group == 0 || group > ((uint64_t)1 << 62)) return FBSR_EINVAL;
   if (n == 0) return FBSR_OK;

@@ -98,11 +98,17 @@ __global__ __launch_bounds__(kThreads) void block_blocks(const float* __restrict
   const int s = scale_exponent<FMT>(umax, &special);
   scales[blk] = special ? (uint8_t)0xFF : (uint8_t)(s + 127);
   const float mult = inv_scale(s);
-  const Addends a = make_addends<FMT, VAR>(nbits);
+  const bool many_bits = VAR != kRNE && nbits > kMaxTileNbits;   // uniform over the launch
+  const Addends a = make_addends<FMT, VAR>(many_bits ? kMaxTileNbits : nbits);
   for (int k = 0; k < len; ++k) {
-    uint32_t rnd = 0;
-    if constexpr (VAR != kRNE) rnd = element_bits(offset + j0 + k, log2_per_block, W, a.nbits, seed, 0);
-    const uint32_t r = round_pattern<FMT, VAR, true>(__float_as_uint(x[j0 + k] * mult), rnd, a);
+    const uint32_t bits = __float_as_uint(x[j0 + k] * mult);
+    uint32_t r;
+    if constexpr (VAR != kRNE) {
+      const uint32_t rnd = element_bits(offset + j0 + k, log2_per_block, W, (uint32_t)nbits, seed, 0);
+      r = many_bits ? round_pattern_wide<FMT, VAR>(bits, rnd, (uint32_t)nbits) : round_pattern<FMT, VAR, true>(bits, rnd, a);
+    } else {
+      r = round_pattern<FMT, VAR, true>(bits, 0u, a);
+    }
     out[j0 + k] = special ? (uint8_t)(Fx<FMT>::NAN_FX >> 24) : (uint8_t)(r >> 24);
   }
 }
@@ -156,8 +162,9 @@ hipError_t run(const float* x, uint8_t* out, uint8_t* scales, uint64_t n, int nb
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
   const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
                               reinterpret_cast<uintptr_t>(out), 1, 4);
-  // the tile kernel's blocks of 32 must be the call's blocks: it is used only when no head is cut off
-  const uint64_t ntiles = s.head == 0 ? s.ntiles : 0;
+  // the tile kernel's blocks of 32 must be the call's blocks: it is used only when no head is cut off -- and with at
+  // most 16 random bits per element (more go through the per-block kernel and its wide rounding)
+  const uint64_t ntiles = s.head == 0 && (VAR == kRNE || nbits <= kMaxTileNbits) ? s.ntiles : 0;
   for (uint64_t t0 = 0; t0 < ntiles; t0 += kMaxTilesPerLaunch) {
     const uint64_t cnt = ntiles - t0 < kMaxTilesPerLaunch ? ntiles - t0 : kMaxTilesPerLaunch;
     const uint64_t e0 = t0 * s.tile_elems;

@@ -24,7 +24,7 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
     fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
     __syncthreads();
   }
-  if constexpr (W == 32 && VAR != kRNE) {
+  if constexpr (W == 32) {
     // more than 16 random bits: one 32-bit slot per element, every element on the wide path
 #pragma unroll
     for (int k = 0; k < kRows; ++k) {
@@ -149,14 +149,17 @@ hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, u
 template <int FMT, int VAR>
 hipError_t launch_tiles_w(int W, const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed,
                           uint64_t blk0, hipStream_t stream) {
-  if constexpr (VAR == kRNE) return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, stream);
-  switch (W) {
-    case 1: return launch_tiles<FMT, VAR, 1>(x, out, ntiles, nbits, seed, blk0, stream);
-    case 2: return launch_tiles<FMT, VAR, 2>(x, out, ntiles, nbits, seed, blk0, stream);
-    case 4: return launch_tiles<FMT, VAR, 4>(x, out, ntiles, nbits, seed, blk0, stream);
-    case 8: return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, stream);
-    case 16: return launch_tiles<FMT, VAR, 16>(x, out, ntiles, nbits, seed, blk0, stream);
-    default: return launch_tiles<FMT, VAR, 32>(x, out, ntiles, nbits, seed, blk0, stream);
+  if constexpr (VAR == kRNE) {
+    return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, stream);
+  } else {
+    switch (W) {
+      case 1: return launch_tiles<FMT, VAR, 1>(x, out, ntiles, nbits, seed, blk0, stream);
+      case 2: return launch_tiles<FMT, VAR, 2>(x, out, ntiles, nbits, seed, blk0, stream);
+      case 4: return launch_tiles<FMT, VAR, 4>(x, out, ntiles, nbits, seed, blk0, stream);
+      case 8: return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, stream);
+      case 16: return launch_tiles<FMT, VAR, 16>(x, out, ntiles, nbits, seed, blk0, stream);
+      default: return launch_tiles<FMT, VAR, 32>(x, out, ntiles, nbits, seed, blk0, stream);
+    }
   }
 }
 

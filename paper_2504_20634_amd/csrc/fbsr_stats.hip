@@ -106,29 +106,35 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
                                                         double* __restrict__ records) {
   typedef WgTile<W> T;
   typedef Fx<FMT> F;
-  __shared__ uint4 strip[kStatsChunkTiles * T::BLOCKS];
+  // MANY: more than 16 random bits per element (32-bit slots, the wide rounding).  The strip then holds the bits of
+  // half a chunk at a time (32 KiB) and is refilled before the fifth tile.
+  constexpr bool MANY = W == 32 && VAR != kRNE;
+  constexpr int kStripTiles = MANY ? kStatsChunkTiles / 2 : kStatsChunkTiles;
+  __shared__ uint4 strip[kStripTiles * T::BLOCKS];
   __shared__ double staged[kWavesPerBlock][kStatsRecordDoubles];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
 
-  const Addends a = make_addends<FMT, VAR>(nbits);
+  const Addends a = make_addends<FMT, VAR>(MANY ? kMaxTileNbits : nbits);
   HwAddends hw = {0, 0, 0, 0};
-  if constexpr (F::kIsFp8 && VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
+  if constexpr (F::kIsFp8 && VAR != kRNE && !MANY) hw = make_hw_addends<FMT, VAR>(nbits);
   const uint64_t tile0 = (uint64_t)blockIdx.x * kStatsChunkTiles;
   const uint64_t chunk_start = i0 + tile0 * T::ELEMS;
   uint64_t next_bin = group - chunk_start % group;   // chunk-relative index at which the next bin starts
   uint64_t slot = 0;
   Acc cur = {0.0, 0.0, 0.0};
-  if constexpr (VAR != kRNE) {
-    const uint64_t left = ntiles - tile0;   // the grid has one workgroup per started chunk: tile0 < ntiles
-    const int nblk = (int)(left < (uint64_t)kStatsChunkTiles ? left : (uint64_t)kStatsChunkTiles) * T::BLOCKS;
+  // draws the bits of the tiles [first, first + kStripTiles) of the chunk (those that exist) into the strip
+  auto draw = [&](int first) {
+    const uint64_t left = ntiles - (tile0 + (uint64_t)first);   // > 0 at every call
+    const int nblk = (int)(left < (uint64_t)kStripTiles ? left : (uint64_t)kStripTiles) * T::BLOCKS;
     for (int bi = threadIdx.x; bi < nblk; bi += kThreads) {
       uint32_t o[4];
-      philox_block(blk0 + tile0 * T::BLOCKS + (uint64_t)bi, seed, 0, o);
+      philox_block(blk0 + (tile0 + (uint64_t)first) * T::BLOCKS + (uint64_t)bi, seed, 0, o);
       strip[bi] = make_uint4(o[0], o[1], o[2], o[3]);
     }
     __syncthreads();
-  }
+  };
+  if constexpr (VAR != kRNE) draw(0);   // the grid has one workgroup per started chunk: tile0 < ntiles
 
   auto flush = [&]() {
     const double t0 = wave_sum(cur.sy), t1 = wave_sum(cur.se), t2 = wave_sum(cur.see);
@@ -151,6 +157,12 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
   for (int it = 0; it < kStatsChunkTiles; ++it) {
     const uint64_t tile = tile0 + (uint64_t)it;
     if (tile >= ntiles) break;   // uniform over the workgroup
+    if constexpr (MANY) {
+      if (it == kStripTiles) {   // every wave is done with the first half's bits before they are replaced
+        __syncthreads();
+        draw(kStripTiles);
+      }
+    }
     const uint64_t row0 = tile * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
     f32x4 v[kRows];
 #pragma unroll
@@ -176,15 +188,25 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
       constexpr bool WIDE = decltype(wide_tag)::value;
 #pragma unroll
       for (int k = 0; k < kRows; ++k) {
-        uint64_t rb = 0;
-        if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip + it * T::BLOCKS, wave, lane, k);
-        const uint32_t n4[4] = {VAR == kRNE ? 0u : slot_bits<W>(rb, 0, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 1, a.nbits),
-                                VAR == kRNE ? 0u : slot_bits<W>(rb, 2, a.nbits), VAR == kRNE ? 0u : slot_bits<W>(rb, 3, a.nbits)};
-        constexpr bool HW = !WIDE && F::kIsFp8 && VAR != kRNE;
+        uint32_t n4[4] = {0, 0, 0, 0};
+        if constexpr (MANY) {
+          // the row's four 32-bit slots are one Philox block
+          const uint4 q = strip[(it % kStripTiles) * T::BLOCKS + (wave * kWaveElems + k * 256 + 4 * lane) / 4];
+          n4[0] = __builtin_amdgcn_ubfe(q.x, 0u, (uint32_t)nbits); n4[1] = __builtin_amdgcn_ubfe(q.y, 0u, (uint32_t)nbits);
+          n4[2] = __builtin_amdgcn_ubfe(q.z, 0u, (uint32_t)nbits); n4[3] = __builtin_amdgcn_ubfe(q.w, 0u, (uint32_t)nbits);
+        } else if constexpr (VAR != kRNE) {
+          const uint64_t rb = read_wg_row_bits<W>(strip + it * T::BLOCKS, wave, lane, k);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) n4[j] = slot_bits<W>(rb, j, a.nbits);
+        }
+        constexpr bool HW = !WIDE && F::kIsFp8 && VAR != kRNE && !MANY;
         uint32_t r[4] = {0, 0, 0, 0};
         uint32_t packed = 0;
         if constexpr (HW) {
           packed = round4_fp8_hw<FMT, VAR>(b[k], n4, hw);
+        } else if constexpr (MANY) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) r[j] = round_pattern_wide<FMT, VAR>(b[k][j], n4[j], (uint32_t)nbits);
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, WIDE>(b[k][j], n4[j], a);
@@ -288,14 +310,19 @@ __global__ __launch_bounds__(kThreads) void stats_bins(const float* __restrict__
   const uint64_t lo = bin * group > a0 ? bin * group : a0;
   const uint64_t hi = (bin + 1) * group < a0 + n ? (bin + 1) * group : a0 + n;
   if (lo >= hi) return;
-  const Addends a = make_addends<FMT, VAR>(nbits);
+  const bool many_bits = VAR != kRNE && nbits > kMaxTileNbits;   // uniform over the launch
+  const Addends a = make_addends<FMT, VAR>(many_bits ? kMaxTileNbits : nbits);
   Acc acc = {0.0, 0.0, 0.0};
   typedef typename Fx<FMT>::code_t code_t;
   for (uint64_t i = lo; i < hi; ++i) {
-    uint32_t rnd = 0;
-    if constexpr (VAR != kRNE) rnd = element_bits(i, log2_per_block, W, a.nbits, seed, 0);
     const uint32_t bits = __float_as_uint(x[i - a0]);
-    const uint32_t r = round_pattern<FMT, VAR, true>(bits, rnd, a);
+    uint32_t r;
+    if constexpr (VAR != kRNE) {
+      const uint32_t rnd = element_bits(i, log2_per_block, W, (uint32_t)nbits, seed, 0);
+      r = many_bits ? round_pattern_wide<FMT, VAR>(bits, rnd, (uint32_t)nbits) : round_pattern<FMT, VAR, true>(bits, rnd, a);
+    } else {
+      r = round_pattern<FMT, VAR, true>(bits, 0u, a);
+    }
     if (out != nullptr) reinterpret_cast<code_t*>(out)[i - a0] = (code_t)(r >> Fx<FMT>::FRAC);
     accumulate<FMT, true>(acc, bits, decode_top<FMT>(r));
   }
@@ -329,13 +356,17 @@ hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, u
 template <int FMT, int VAR>
 hipError_t launch_tiles_w(int W, const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed,
                           uint64_t blk0, uint64_t i0, uint64_t group, double* records, hipStream_t stream) {
-  if constexpr (VAR == kRNE) return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-  switch (W) {
-    case 1: return launch_tiles<FMT, VAR, 1>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-    case 2: return launch_tiles<FMT, VAR, 2>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-    case 4: return launch_tiles<FMT, VAR, 4>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-    case 8: return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-    default: return launch_tiles<FMT, VAR, 16>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+  if constexpr (VAR == kRNE) {
+    return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+  } else {
+    switch (W) {
+      case 1: return launch_tiles<FMT, VAR, 1>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+      case 2: return launch_tiles<FMT, VAR, 2>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+      case 4: return launch_tiles<FMT, VAR, 4>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+      case 8: return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+      case 16: return launch_tiles<FMT, VAR, 16>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+      default: return launch_tiles<FMT, VAR, 32>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+    }
   }
 }
 

@@ -70,9 +70,11 @@ def test_argument_validation_happens_on_the_host(L):
     for fmt, var, nb in ((4, 1, 2), (-1, 1, 2), (0, 4, 2), (0, -1, 2), (0, 1, 0), (0, 2, 25), (1, 3, -5)):
         assert L.fbsr_round(p(good), p(good), 8, fmt, var, nb, 0, 0, None) == EINVAL
         assert L.fbsr_bias_stats(p(good), None, 8, fmt, var, nb, 0, 0, 4, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
-    # the rounding entry points take up to 24 bits, everything else up to 16
-    assert L.fbsr_bias_stats(p(good), None, 8, 1, 1, 17, 0, 0, 4, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
-    assert L.fbsr_round_block_scaled(p(good), p(good), p(good), 8, 1, 1, 17, 0, 0, None) == EINVAL
+    # the fused updates take up to 16 bits, everything else up to 24
+    assert L.fbsr_bias_stats(p(good), None, 8, 1, 1, 25, 0, 0, 4, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
+    assert L.fbsr_bias_stats(p(good + 2), None, 8, 1, 1, 24, 0, 0, 4, 0, 2, p(good), p(good), 1 << 20, None) == EALIGN
+    assert L.fbsr_round_block_scaled(p(good), p(good), p(good), 8, 1, 1, 25, 0, 0, None) == EINVAL
+    assert L.fbsr_round_block_scaled(p(good + 2), p(good), p(good), 8, 1, 1, 24, 0, 0, None) == EALIGN
     assert L.fbsr_sgd_update(p(good), p(good), 8, 0.1, 1, 17, 0, 0, 0, None) == EINVAL
     assert L.fbsr_round_from16(p(good), p(good), 8, 0, 1, 1, 25, 0, 0, None) == EINVAL
     assert L.fbsr_round(p(good + 2), p(good), 8, 1, 1, 24, 0, 0, None) == EALIGN      # 24 passes the nbits check

@@ -1,11 +1,11 @@
-"""GPU parity for more than 16 random bits per element (17..24, the rounding entry points only): enough bits to
+"""GPU parity for more than 16 random bits per element (17..24; every entry point but the fused updates): enough bits to
 reach classical SR from fp32 (E4M3 and binary8p4 drop D = 20 bits, E5M2 21, bf16 16).  These calls run on the
 per-element kernel with 32 fraction bits; the oracle is the same one, which takes any N <= 32."""
 import numpy as np
 import pytest
 import torch
 
-from gpu_util import dev, first_mismatch, host
+from gpu_util import assert_stats_close, dev, first_mismatch, host
 
 pytestmark = pytest.mark.gpu
 
@@ -81,12 +81,43 @@ def test_narrow_source_and_generic_formats_with_many_bits(fbsr, oracle):
         assert first_mismatch(got, oracle.round_format8(codes, 0, d, SRC, 21, 9, 0)) is None, name
 
 
-def test_other_entry_points_keep_their_limit(fbsr):
+def test_block_scaled_with_many_bits(fbsr, oracle):
+    n = 3 * 2048 + 77
+    x = _inputs(n, E4M3, seed=81)
+    x[:64] = 0.0                                                # an all-zero block
+    xd = dev(x)
+    for fmt, variant, nbits, offset in ((E4M3, SRC, 17, 0), (E5M2, SRF, 24, 0), (P4, SRFF, 20, 32 * 5), (E4M3, SRC, 24, 64)):
+        print("case block-scaled fmt=%d variant=%d nbits=%d offset=%d" % (fmt, variant, nbits, offset), flush=True)
+        codes, scales = fbsr.fbsr_round_block_scaled(xd, fmt, variant, nbits, seed=12, offset=offset)
+        wc, ws = oracle.round_block_scaled(x, fmt, variant, nbits, seed=12, offset=offset)
+        assert first_mismatch(host(codes), wc) is None and first_mismatch(host(scales), ws) is None
+
+
+@pytest.mark.parametrize("fmt", [BF16, E4M3, E5M2, P4])
+def test_statistics_with_many_bits(fbsr, oracle, fmt):
+    """Bins larger than a tile (the chunked kernel, whose strip of random bits is refilled half-way through a chunk),
+    bins smaller than one (the per-bin kernel), ragged ends, an offset that starts inside a bin; codes written too."""
+    n = 21 * 2048 + 300                                         # two whole chunks of 8 tiles, a part of a third, a tail
+    x = _inputs(n, fmt, seed=90 + fmt)
+    x = np.where(np.isfinite(x), x, np.float32(1.5)).astype(np.float32)
+    xd = dev(x)
+    for variant, nbits, group, offset in ((SRFF, 20, 4096, 0), (SRC, 24, 5000, 1234), (SRF, 17, 1 << 14, 8), (SRC, 21, 100, 0)):
+        first_bin = offset // group
+        nbins = (offset + n - 1) // group - first_bin + 1
+        print("case stats fmt=%d variant=%d nbits=%d group=%d offset=%d" % (fmt, variant, nbits, group, offset), flush=True)
+        out = torch.empty(n, dtype=fbsr.binding.code_dtype(fmt), device="cuda")
+        stats, out = fbsr.fbsr_bias_stats(xd, fmt, variant, nbits, 6, offset, group, first_bin, nbins, out=out)
+        want, wout = oracle.bias_stats(x, fmt, variant, nbits, 6, offset, group, first_bin, nbins, want_out=True)
+        assert_stats_close(stats.cpu().numpy(), want)
+        assert first_mismatch(host(out), wout) is None
+
+
+def test_limits(fbsr):
     w = torch.zeros(64, dtype=torch.int16, device="cuda")
     g = torch.zeros(64, dtype=torch.float32, device="cuda")
     with pytest.raises(fbsr.FbsrError):
         fbsr.fbsr_sgd_update(w, g, 1e-3, SRC, 17, seed=1, step=0)
     with pytest.raises(fbsr.FbsrError):
-        fbsr.fbsr_round_block_scaled(g, E4M3, SRC, 17, seed=1)
+        fbsr.fbsr_round_block_scaled(g, E4M3, SRC, 25, seed=1)
     with pytest.raises(fbsr.FbsrError):
         fbsr.fbsr_round(g, E4M3, SRC, 25, seed=1)
