@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per fp8 round_tiles launch of 2^28 elements, from two rocprofv3 --pmc runs of this file
 # (FETCH_SIZE, then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy);
 # the summary is committed under profiles/.  Algorithmic bytes: 5 * 2^28 = 1342177280.
-MEASURED_TRAFFIC_BYTES_2P28 = 1342193990
+MEASURED_TRAFFIC_BYTES_2P28 = 1342194673
 # Vector-ALU roofline for the paths that are not bound by HBM: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz
 # one-lane operations per second.  VALU instructions per element are SQ_INSTS_VALU / SQ_WAVES / elements per lane
 # from a rocprofv3 --pmc run of this file (profiles/kernels_2p28_valu_counters.md).
