@@ -153,6 +153,12 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
     cur = {0.0, 0.0, 0.0};
   };
 
+  // the loads of a tile are issued one iteration ahead, so that their latency is covered by the arithmetic of
+  // the tile before (the waves of a workgroup run independently between the chunk's barriers)
+  const uint64_t lane_row = (uint64_t)(wave * (kWaveElems / 4) + lane);
+  f32x4 ahead[kRows];
+#pragma unroll
+  for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(x + 4 * (tile0 * (T::ELEMS / 4) + lane_row + (uint64_t)(k * 64)));   // tile0 < ntiles
 #pragma unroll 1
   for (int it = 0; it < kStatsChunkTiles; ++it) {
     const uint64_t tile = tile0 + (uint64_t)it;
@@ -163,10 +169,14 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
         draw(kStripTiles);
       }
     }
-    const uint64_t row0 = tile * (T::ELEMS / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);   // units of 4 elements
+    const uint64_t row0 = tile * (T::ELEMS / 4) + lane_row;   // units of 4 elements
     f32x4 v[kRows];
 #pragma unroll
-    for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
+    for (int k = 0; k < kRows; ++k) v[k] = ahead[k];
+    if (it + 1 < kStatsChunkTiles && tile + 1 < ntiles) {
+#pragma unroll
+      for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(x + 4 * (row0 + (uint64_t)(T::ELEMS / 4) + (uint64_t)(k * 64)));
+    }
 
     uint32_t b[kRows][4];
     float y[kRows][4];
