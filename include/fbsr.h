@@ -65,8 +65,8 @@ typedef enum {
   FBSR_EDEVICE = 4  /* the HIP runtime reported an error at launch                               */
 } fbsr_status;
 
-/* Largest nbits.  Every entry point that rounds fp32 values to a caller-chosen format (fbsr_round, fbsr_round_from16,
- * fbsr_round_format8, fbsr_round_block_scaled, fbsr_bias_stats) takes up to FBSR_MAX_NBITS_ROUND, which covers every
+/* Largest nbits.  Every entry point but the fused updates (fbsr_round, fbsr_round_from16, fbsr_round_format8,
+ * fbsr_round_block_scaled, fbsr_bias_stats) takes up to FBSR_MAX_NBITS_ROUND, which covers every
  * bit an fp32 source can drop towards an 8-bit target (D = 20 for E4M3 and binary8p4, 21 for E5M2), so that nbits >= D
  * gives classical SR; calls with more than FBSR_MAX_NBITS bits use 32-bit slots (4 elements per Philox block) and a
  * slower rounding that keeps 32 fraction bits.  The fused updates take up to FBSR_MAX_NBITS: their rounding drops at
