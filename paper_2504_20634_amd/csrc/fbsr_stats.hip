@@ -15,6 +15,7 @@ namespace fbsr {
 
 struct Acc {
   double sy, se, see;   // sum y, sum e, sum e^2
+  float sy32;           // the part of sum y kept in fp32 (formats whose sums over a chunk are exact there)
 };
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -60,19 +61,34 @@ __device__ __forceinline__ double inv_ulp(uint32_t bits) {
   return __hiloint2double((int)hi, 0);
 }
 
+// A lane's share of a chunk is 64 elements.  64 values of E4M3 (multiples of 2^-9 up to 448) or of binary8p4
+// (multiples of 2^-10 up to 224) sum to a multiple of that step below 2^24 steps: exact in fp32 in any order, so
+// the sum of y runs there and is widened once per record.
+template <int FMT> struct SumYInFp32 { static constexpr bool value = FMT == kE4M3 || FMT == kP4; };
+
 // Adds one element to a bin's sums.  WIDE = false: y - x is formed in fp32, where it is exact for
 // every finite |x| <= M (y is a neighbour of x on a coarser grid, so the difference is a multiple of
-// x's own last place and smaller than 2^24 of them); WIDE = true: the difference is formed in fp64
-// (overflow, saturation, NaN: values for which the fp32 difference would round or is not finite).
-// Either way e = (y - x) / ulp_t(x) is an exact scaling by a power of two in fp64.
+// x's own last place and smaller than 2^24 of them), and so is its scaling by 1 / ulp_t(x), a power of two
+// (the quotient keeps the difference's significand and stays below 2 in magnitude);
+// WIDE = true: the difference is formed in fp64 (overflow, saturation, NaN: values for which the fp32 difference
+// would round or is not finite).  Either way e = (y - x) / ulp_t(x) reaches the fp64 sums without a rounding.
 template <int FMT, bool WIDE>
 __device__ __forceinline__ void accumulate(Acc& acc, uint32_t bits, float y) {
+  typedef Fx<FMT> F;
   const float x = __uint_as_float(bits);
-  double d;
-  if constexpr (WIDE) d = (double)y - (double)x;
-  else d = (double)(y - x);
-  const double e = d * inv_ulp<FMT>(bits);
-  acc.sy += (double)y;
+  double e;
+  if constexpr (WIDE) {
+    e = ((double)y - (double)x) * inv_ulp<FMT>(bits);
+    acc.sy += (double)y;
+  } else {
+    // 1 / ulp_t(x) = 2^(P - 1 - e~), e~ = max(floor(log2|x|), 1 - B) (Eq. (2)); frexp's exponent is floor(log2|x|) + 1
+    // (0 for x = 0, where y - x = 0 makes the scale irrelevant)
+    const int fe = __builtin_amdgcn_frexp_expf(x);
+    const int k = F::P - (fe > 2 - F::B ? fe : 2 - F::B);
+    e = (double)__builtin_amdgcn_ldexpf(y - x, k);
+    if constexpr (SumYInFp32<FMT>::value) acc.sy32 += y;
+    else acc.sy += (double)y;
+  }
   acc.se += e;
   acc.see = fma(e, e, acc.see);
 }
@@ -122,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
   const uint64_t chunk_start = i0 + tile0 * T::ELEMS;
   uint64_t next_bin = group - chunk_start % group;   // chunk-relative index at which the next bin starts
   uint64_t slot = 0;
-  Acc cur = {0.0, 0.0, 0.0};
+  Acc cur = {0.0, 0.0, 0.0, 0.0f};
   // draws the bits of the tiles [first, first + kStripTiles) of the chunk (those that exist) into the strip
   auto draw = [&](int first) {
     const uint64_t left = ntiles - (tile0 + (uint64_t)first);   // > 0 at every call
@@ -137,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
   if constexpr (VAR != kRNE) draw(0);   // the grid has one workgroup per started chunk: tile0 < ntiles
 
   auto flush = [&]() {
-    const double t0 = wave_sum(cur.sy), t1 = wave_sum(cur.se), t2 = wave_sum(cur.see);
+    const double t0 = wave_sum(cur.sy + (double)cur.sy32), t1 = wave_sum(cur.se), t2 = wave_sum(cur.see);
     if (lane == 0) {
       staged[wave][0] = t0; staged[wave][1] = t1; staged[wave][2] = t2;
     }
@@ -150,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict_
     }
     __syncthreads();
     slot += 1;
-    cur = {0.0, 0.0, 0.0};
+    cur = {0.0, 0.0, 0.0, 0.0f};
   };
 
   // the loads of a tile are issued one iteration ahead, so that their latency is covered by the arithmetic of
@@ -322,7 +338,7 @@ __global__ __launch_bounds__(kThreads) void stats_bins(const float* __restrict__
   if (lo >= hi) return;
   const bool many_bits = VAR != kRNE && nbits > kMaxTileNbits;   // uniform over the launch
   const Addends a = make_addends<FMT, VAR>(many_bits ? kMaxTileNbits : nbits);
-  Acc acc = {0.0, 0.0, 0.0};
+  Acc acc = {0.0, 0.0, 0.0, 0.0f};
   typedef typename Fx<FMT>::code_t code_t;
   for (uint64_t i = lo; i < hi; ++i) {
     const uint32_t bits = __float_as_uint(x[i - a0]);
