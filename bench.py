@@ -34,8 +34,8 @@ MEASURED_TRAFFIC_BYTES_2P28 = 1342194673
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 VALU_PER_ELEM = {"qat_adamw_e4m3_N3_src": 65.9, "qat_adamw_e4m3_N3_srff": 58.9, "qat_adamw_binary8p4_N3_src": 72.8,
                  "qat_adamw_binary8p4_N3_srff": 65.8, "qat_adamw_format8_binary8p4_N3_src": 85.6,
-                 "qat_adamw_format8_binary8p4_N3_srff": 77.4, "bias_stats_e4m3_N3_srf": 26.7, "bias_stats_e4m3_N8_srf": 28.6,
-                 "bias_stats_bf16_N2_srf": 23.7, "bias_stats_bf16_N8_srf": 26.4,
+                 "qat_adamw_format8_binary8p4_N3_srff": 77.4, "bias_stats_e4m3_N3_srf": 25.1, "bias_stats_e4m3_N8_srf": 27.0,
+                 "bias_stats_bf16_N2_srf": 22.7, "bias_stats_bf16_N8_srf": 25.5,
                  "round_format8_binary8p4_from_fp32_N3_src": 36.4, "round_format8_binary8p4_from_fp32_N8_srf": 29.6,
                  "round_format8_binary8p4_from_bf16_N3_src": 36.5, "round_format8_binary8p4_from_bf16_N3_srff": 27.8,
                  "round_from_bf16_binary8p4_N3_src": 22.4, "round_from_bf16_e4m3_N3_src": 17.2}
