@@ -53,9 +53,11 @@ __global__ __launch_bounds__(kThreads) void block_tiles(const float* __restrict_
     const uint32_t raw[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
                              __float_as_uint(v[k].w)};
     uint32_t umax = max(max(raw[0] & 0x7FFFFFFFu, raw[1] & 0x7FFFFFFFu), max(raw[2] & 0x7FFFFFFFu, raw[3] & 0x7FFFFFFFu));
-    umax = max(umax, (uint32_t)__shfl_xor((int)umax, 1, 64));
-    umax = max(umax, (uint32_t)__shfl_xor((int)umax, 2, 64));
-    umax = max(umax, (uint32_t)__shfl_xor((int)umax, 4, 64));
+    // maximum over the 8 lanes of the block, by data-parallel-primitive moves (no LDS): neighbours within a quad,
+    // the other pair of the quad, then the mirror image within the group of 8 (lane i <-> 7 - i: the other quad)
+    umax = max(umax, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)umax, 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+    umax = max(umax, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)umax, 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+    umax = max(umax, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)umax, 0x141, 0xF, 0xF, false));   // row_half_mirror
     bool special;
     const int s = scale_exponent<FMT>(umax, &special);
     const float mult = inv_scale(s);
