@@ -173,9 +173,27 @@ def cpu_baseline(x_host, fmts, variants, threads):
                 oracle.round_(xs, fmt, variant, nbits, seed=2, offset=0, nthreads=threads)
                 done += xs.size
     dt = time.perf_counter() - t0
+    # the same sweep on one thread, over the first 2^22 elements
+    one = 1 << 22
+    done1 = 0
+    t1 = time.perf_counter()
+    for fmt in fmts:
+        for nbits in HEADLINE_NBITS:
+            for variant in variants:
+                oracle.round_(x_host[fmt][:one], fmt, variant, nbits, seed=2, offset=0, nthreads=1)
+                done1 += one
+    dt1 = time.perf_counter() - t1
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            model = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), "unknown")
+    except OSError:
+        pass
     return {"value": done / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
             "sample": "first 2^25 elements of the same inputs x 18 (format, N, variant) launches, "
-                      "oracle_round_threads with %d threads, %.1f s wall" % (threads, dt)}
+                      "oracle_round_threads with %d threads, %.1f s wall" % (threads, dt),
+            "single_thread_value": done1 / dt1, "single_thread_sample": "first 2^22 elements x the same 18 launches, %.1f s" % dt1,
+            "cpu_model": model}
 
 
 def main():
