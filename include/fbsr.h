@@ -61,7 +61,8 @@ typedef enum {
   FBSR_OK = 0,
   FBSR_EINVAL = 1,  /* bad enum, nbits outside [1, the entry point's maximum], null pointer, group == 0, ... */
   FBSR_EALIGN = 2,  /* a pointer is not aligned to its element type                              */
-  FBSR_ERANGE = 3,  /* an element would fall outside the caller's bins / workspace too small     */
+  FBSR_ERANGE = 3,  /* an element would fall outside the caller's bins / workspace too small / call too
+                       large for fbsr_bias_stats_static                                          */
   FBSR_EDEVICE = 4  /* the HIP runtime reported an error at launch                               */
 } fbsr_status;
 
@@ -175,6 +176,18 @@ int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant,
                     uint64_t seed, uint64_t offset, uint64_t group, uint64_t first_bin,
                     uint32_t nbins, double* stats, void* workspace, uint64_t workspace_bytes,
                     void* stream);
+
+/* fbsr_bias_stats for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc) and so have no workspace to pass: the same kernels, with the workspace
+ * in a fixed 4 MiB array inside the library's device image (each GPU the library runs on holds it until the
+ * process ends).  The call allocates and frees nothing.  n may be at most FBSR_BIAS_STATS_STATIC_MAX_ELEMS
+ * (else FBSR_ERANGE); everything else -- arguments, results bit for bit, errors -- as fbsr_bias_stats.
+ * All calls on one GPU share that array: two of them must not overlap in time (order them on one stream, or
+ * synchronise between them), or they race.  Nothing in it has to be cleared between calls. */
+#define FBSR_BIAS_STATS_STATIC_MAX_ELEMS ((uint64_t)1 << 28)
+int fbsr_bias_stats_static(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits,
+                           uint64_t seed, uint64_t offset, uint64_t group, uint64_t first_bin,
+                           uint32_t nbins, double* stats, void* stream);
 
 /* Bytes of workspace fbsr_bias_stats needs for n elements (never 0; independent of nbins
  * today, kept in the signature for layouts that are not). */

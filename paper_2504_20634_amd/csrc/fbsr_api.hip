@@ -257,23 +257,61 @@ uint64_t fbsr_bias_stats_workspace_bytes(uint64_t n, uint32_t nbins) {
   return (n / chunk + 1) * fbsr::kStatsMaxSlots * fbsr::kStatsRecordDoubles * sizeof(double);
 }
 
-int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
-                    uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
-                    void* workspace, uint64_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// The checks fbsr_bias_stats and fbsr_bias_stats_static share (everything but the workspace).
+int check_stats(const float* x, const void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t offset,
+                uint64_t group, uint64_t first_bin, uint32_t nbins, const double* stats, bool* nothing_to_do) {
+  *nothing_to_do = false;
   if (!valid_fmt(fmt)) return FBSR_EINVAL;
   const int c = check_common(variant, nbits, n, offset, FBSR_MAX_NBITS_ROUND);
   if (c != FBSR_OK) return c;
   if (group == 0 || group > ((uint64_t)1 << 62)) return FBSR_EINVAL;
-  if (n == 0) return FBSR_OK;
-  if (x == nullptr || stats == nullptr || workspace == nullptr) return FBSR_EINVAL;
-  if (misaligned(x, 4) || misaligned(stats, 8) || misaligned(workspace, 8)) return FBSR_EALIGN;
+  if (n == 0) {
+    *nothing_to_do = true;
+    return FBSR_OK;
+  }
+  if (x == nullptr || stats == nullptr) return FBSR_EINVAL;
+  if (misaligned(x, 4) || misaligned(stats, 8)) return FBSR_EALIGN;
   if (out != nullptr && misaligned(out, code_bytes(fmt))) return FBSR_EALIGN;
   const uint64_t bin_lo = offset / group, bin_hi = (offset + n - 1) / group;
   if (bin_lo < first_bin || bin_hi - first_bin >= nbins) return FBSR_ERANGE;
+  return FBSR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
+                    uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
+                    void* workspace, uint64_t workspace_bytes, void* stream) {
+  bool nothing = false;
+  const int c = check_stats(x, out, n, fmt, variant, nbits, offset, group, first_bin, nbins, stats, &nothing);
+  if (c != FBSR_OK || nothing) return c;
+  if (workspace == nullptr) return FBSR_EINVAL;
+  if (misaligned(workspace, 8)) return FBSR_EALIGN;
   if (workspace_bytes < fbsr_bias_stats_workspace_bytes(n, nbins)) return FBSR_ERANGE;
   const hipError_t e =
       fbsr::launch_stats(x, out, n, fmt, variant, nbits, seed, offset, group, first_bin, nbins, stats,
                          reinterpret_cast<double*>(workspace), reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
+int fbsr_bias_stats_static(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
+                           uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
+                           void* stream) {
+  bool nothing = false;
+  const int c = check_stats(x, out, n, fmt, variant, nbits, offset, group, first_bin, nbins, stats, &nothing);
+  if (c != FBSR_OK || nothing) return c;
+  if (n > fbsr::kStaticMaxElems || fbsr_bias_stats_workspace_bytes(n, nbins) > fbsr::kStaticScratchBytes) return FBSR_ERANGE;
+  double* ws = nullptr;
+  if (fbsr::static_scratch(&ws) != hipSuccess) return FBSR_EDEVICE;
+  // every record finalize reads is written by this call's own tile kernel first: nothing has to start at zero
+  const hipError_t e = fbsr::launch_stats(x, out, n, fmt, variant, nbits, seed, offset, group, first_bin, nbins, stats, ws,
+                                          reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 
@@ -292,12 +330,12 @@ const char* fbsr_strerror(int status) {
     case FBSR_OK: return "ok";
     case FBSR_EINVAL: return "invalid argument";
     case FBSR_EALIGN: return "pointer not aligned to its element type";
-    case FBSR_ERANGE: return "element outside the bins, or workspace too small";
+    case FBSR_ERANGE: return "element outside the bins, workspace too small, or call too large for the built-in workspace";
     case FBSR_EDEVICE: return "HIP runtime error at launch";
   }
   return "unknown status";
 }
 
-int fbsr_version(void) { return 100; }
+int fbsr_version(void) { return 101; }
 
 }  // extern "C"

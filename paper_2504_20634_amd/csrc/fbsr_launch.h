@@ -145,6 +145,14 @@ constexpr uint64_t kStatsRecordDoubles = 3;
 inline uint64_t stats_slots(uint64_t group) { return (uint64_t)(kStatsChunkTiles * kTileElems) / group + 2; }
 constexpr uint64_t kStatsMaxSlots = kStatsChunkTiles + 2;
 
+// fbsr_bias_stats_static: bytes of the workspace array that lives in the library's device image, and the largest
+// call it serves (its records need 240 bytes per 16384 elements: 3.75 MiB at 2^28).
+constexpr uint64_t kStaticScratchBytes = (uint64_t)4 << 20;
+constexpr uint64_t kStaticMaxElems = (uint64_t)1 << 28;
+
+// Address of that array on the current device (looked up once per device).
+hipError_t static_scratch(double** ptr);
+
 hipError_t launch_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                         uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
                         double* workspace, hipStream_t stream);

@@ -7,6 +7,7 @@
 // sums staged in LDS and added in wave order -> one record per (chunk, bin) in the workspace ->
 // per-bin sums over its chunks, lane-strided then butterfly), so results are bit-reproducible;
 // no floating-point atomics are used.
+#include <mutex>
 #include <type_traits>
 
 #include "fbsr_launch.h"
@@ -457,6 +458,34 @@ hipError_t run_v(int variant, const float* x, void* out, uint64_t n, int nbits, 
 }
 
 }  // namespace
+
+// Workspace for callers that cannot allocate one: a fixed array in the library's device image.  Every GPU the
+// library runs on holds its own copy at its own address for the life of the process.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_lock;
+void* scratch_of_device[kMaxDevices];   // the array's address on each device, looked up on that device's first call
+}  // namespace
+
+hipError_t static_scratch(double** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(scratch_lock);
+  if (scratch_of_device[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // of the current device
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    scratch_of_device[dev] = p;
+  }
+  *ptr = reinterpret_cast<double*>(scratch_of_device[dev]);
+  return hipSuccess;
+}
 
 hipError_t launch_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                         uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,

@@ -117,6 +117,12 @@ def test_argument_validation_happens_on_the_host(L):
     assert L.fbsr_bias_stats(p(good), None, 8, 0, 1, 2, 0, 0, 0, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
     assert L.fbsr_bias_stats(p(good), None, 8, 0, 1, 2, 0, 0, 4, 0, 1, p(good), p(good), 1 << 20, None) == ERANGE
     assert L.fbsr_bias_stats(p(good), None, 8, 0, 1, 2, 0, 0, 4, 1, 4, p(good), p(good), 1 << 20, None) == ERANGE
+    # the entry point with the built-in workspace: same checks, and a size limit of its own
+    assert L.fbsr_bias_stats_static(None, None, 0, 0, 1, 2, 0, 0, 1, 0, 1, None, None) == OK
+    assert L.fbsr_bias_stats_static(p(good), None, 8, 0, 1, 2, 0, 0, 0, 0, 2, p(good), None) == EINVAL
+    assert L.fbsr_bias_stats_static(p(good), None, 8, 0, 1, 2, 0, 0, 4, 0, 1, p(good), None) == ERANGE
+    assert L.fbsr_bias_stats_static(p(good), None, 8, 0, 1, 2, 0, 0, 4, 0, 2, p(good + 4), None) == EALIGN
+    assert L.fbsr_bias_stats_static(p(good), None, (1 << 28) + 1, 1, 1, 2, 0, 0, 1 << 20, 0, 1024, p(good), None) == ERANGE
     need = L.fbsr_bias_stats_workspace_bytes(8, 2)
     assert need > 0
     assert L.fbsr_bias_stats(p(good), None, 8, 0, 1, 2, 0, 0, 4, 0, 2, p(good), p(good), need - 1, None) == ERANGE
