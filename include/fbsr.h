@@ -179,7 +179,7 @@ int fbsr_bias_stats(const float* x, void* out, uint64_t n, int fmt, int variant,
 
 /* fbsr_bias_stats for callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc) and so have no workspace to pass: the same kernels, with the workspace
- * in a fixed 4 MiB array inside the library's device image (each GPU the library runs on holds it until the
+ * in a fixed 1 MiB array inside the library's device image (each GPU the library runs on holds it until the
  * process ends).  The call allocates and frees nothing.  n may be at most FBSR_BIAS_STATS_STATIC_MAX_ELEMS
  * (else FBSR_ERANGE); everything else -- arguments, results bit for bit, errors -- as fbsr_bias_stats.
  * All calls on one GPU share that array: two of them must not overlap in time (order them on one stream, or

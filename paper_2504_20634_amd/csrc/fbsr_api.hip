@@ -252,9 +252,7 @@ int fbsr_qat_adamw_step_format8(void* w8, const void* g16, void* m16, void* v16,
 
 uint64_t fbsr_bias_stats_workspace_bytes(uint64_t n, uint32_t nbins) {
   (void)nbins;
-  // one record per (chunk, bin it touches), sized for the smallest group the chunked kernel takes
-  const uint64_t chunk = (uint64_t)fbsr::kStatsChunkTiles * fbsr::kTileElems;
-  return (n / chunk + 1) * fbsr::kStatsMaxSlots * fbsr::kStatsRecordDoubles * sizeof(double);
+  return fbsr::stats_workspace_bytes(n);   // two records per chunk of the vector kernel
 }
 
 }  // extern "C"

@@ -521,6 +521,69 @@ __device__ __forceinline__ float fp8_code_value(uint32_t code) {
   }
 }
 
+// ------------------------------------------- rounding with the error in hand (statistics) ---
+// In code space the rounding error needs no second look at the value: with r0 = |x| there and r = r0 + addend,
+// the rounded magnitude is r with its fraction cleared, so  (r & ~fraction mask) - r0  is, as a plain integer, the
+// error (|y| - |x|) / ulp_t(x) of Sec. III in units of 2^-FRAC -- exact whenever r0 is exact, and valid across a
+// carry into the next binade (the first value up there continues this binade's grid).
+//   FastRound::rs     the signed code in the top (32 - FRAC) bits, zeros below
+//   FastRound::e_int  (|y| - |x|) / ulp_t(x) 2^FRAC, in (-2^FRAC, 2^FRAC): e 2^FRAC for x >= 0, its negative for x < 0
+// Preconditions (the caller checks them for a whole wave): no NaN and |x| <= M; fp8 with MIXED = false: every |x|
+// target-normal (|x| >= 2^(1-B)); fp8 with MIXED = true: additionally any |x| that is zero or >= 2^(2-B-P-FRAC+23),
+// the patterns whose position on the subnormal grid has no bits below 2^-FRAC (bf16 needs no such split: its code
+// space is the fp32 pattern itself).
+struct FastRound {
+  uint32_t rs;
+  int32_t e_int;
+};
+
+// Smallest |pattern| > 0 a MIXED fast path may see.
+template <int FMT> struct FastLimits {
+  static constexpr uint32_t U_DEEP = (uint32_t)(128 - Fx<FMT>::B - Fx<FMT>::P) << 23;
+};
+
+// POSITIVE: the caller knows that no pattern has its sign bit set (then nothing has to be carried over into rs).
+template <int FMT, int VAR, bool MIXED, bool POSITIVE = false>
+__device__ __forceinline__ FastRound round_fast(uint32_t bits, uint32_t n, const Addends& a) {
+  typedef Fx<FMT> F;
+  constexpr uint32_t kFracMask = (1u << F::FRAC) - 1u;
+  uint32_t r0;
+  if constexpr (!F::kIsFp8) {
+    r0 = bits;   // the sign rides along in bit 31: no carry reaches it while |x| <= M
+  } else {
+    constexpr uint32_t kRebias = 0u - (F::Q << (23 + F::S));
+    if constexpr (MIXED) {
+      // |x| is split at the smallest normal value 2^(1-B): what lies above it is placed by the re-biased pattern
+      // (of max(|x|, 2^(1-B))), what lies below it on the fixed subnormal grid (of min(|x|, 2^(1-B)), a product
+      // below 2^32); the position is the sum of the two less the one they both hold at the split point
+      const float ax = fabsf(__uint_as_float(bits)), split = __uint_as_float(F::U_SUB);
+      constexpr uint32_t kSplit = 1u << (F::FRAC + F::P - 1);
+      const uint32_t nrm = (__float_as_uint(fmaxf(ax, split)) << F::S) + (kRebias - kSplit);
+      r0 = nrm + (uint32_t)(fminf(ax, split) * F::SUB_SCALE);
+    } else {
+      r0 = (bits << F::S) + kRebias;
+    }
+  }
+  uint32_t add = n << a.shift;
+  if constexpr (VAR == kSRF) add += a.fixed;
+  if constexpr (VAR == kSRC || VAR == kRNE) add += a.fixed + ((r0 >> a.shift) & a.tie_mask);
+  const uint32_t t = (r0 + add) & ~kFracMask;
+  FastRound f;
+  f.e_int = (int32_t)(t - r0);
+  if constexpr (F::kIsFp8 && !POSITIVE) f.rs = t | (bits & 0x80000000u);
+  else f.rs = t;
+  return f;
+}
+
+// Value of the code FastRound::rs holds (Eq. (1); finite codes only).
+template <int FMT>
+__device__ __forceinline__ float fast_value(uint32_t rs) {
+  if constexpr (FMT == kBF16) return __uint_as_float(rs);
+  else if constexpr (FMT == kE5M2) return __builtin_amdgcn_cvt_f32_bf8((int)rs, 3);
+  else if constexpr (FMT == kE4M3) return __builtin_amdgcn_cvt_f32_fp8((int)rs, 3);
+  else return 0.5f * __builtin_amdgcn_cvt_f32_fp8((int)rs, 3);   // binary8p4: one half of E4M3's value at the same code
+}
+
 // ----------------------------------------------------------- generic formats, K <= 8 ---
 // A generic target format and a rounding mode, both reduced on the host to the constants the
 // code-space arithmetic needs (computed on the host from the caller's descriptor).

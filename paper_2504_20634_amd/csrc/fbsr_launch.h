@@ -32,9 +32,10 @@ struct Split {
 // the vector kernel needs at a tile start.  out_addr may be 0 (no output buffer).
 inline Split split_range(uint64_t n, uint64_t offset, int W, bool no_bits, uintptr_t in_addr, uint64_t in_esize,
                          uint64_t in_align, uintptr_t out_addr, uint64_t out_esize, uint64_t out_align,
-                         uintptr_t in2_addr = 0, uint64_t in2_esize = 0, uint64_t in2_align = 1) {
+                         uintptr_t in2_addr = 0, uint64_t in2_esize = 0, uint64_t in2_align = 1,
+                         uint64_t tile_elems = (uint64_t)kTileElems) {
   Split s;
-  s.tile_elems = (uint64_t)kTileElems;   // one workgroup tile
+  s.tile_elems = tile_elems;   // one workgroup tile, unless the kernel works in other units
   const uint64_t per_block = no_bits ? 1 : (uint64_t)(128 / W);
   uint64_t head = (per_block - offset % per_block) % per_block;
   if (head > n) head = n;
@@ -137,17 +138,25 @@ hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uin
 hipError_t launch_round_format8(const void* x, int src, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m,
                                 uint64_t seed, uint64_t offset, hipStream_t stream);
 
-// The tile kernel of the statistics path works in chunks of kStatsChunkTiles tiles per workgroup
-// and leaves one record {sum y, sum e, sum e^2} per (chunk, bin the chunk touches) in the
-// workspace; a chunk touches at most chunk / group + 2 bins, and group >= one tile on this path.
-constexpr int kStatsChunkTiles = 8;
+// Geometry of the statistics kernel: a workgroup takes a chunk of kStatsChunkElems consecutive elements, each of
+// its waves a span of kStatsSpanElems of them, walked in pairs of rows (kStatsPairElems = 512 elements: eight per
+// lane).  Bins must hold at least kStatsMinGroup elements on this path, so a chunk touches at most
+// kStatsMaxBinsPerChunk of them; the first and the last of those may continue in the neighbouring chunks and leave
+// one record {sum y, sum e, sum e^2} each in the workspace.
+constexpr int kStatsPairElems = kRows * 256;
+constexpr int kStatsSpanPairs = 8;
+constexpr int kStatsSpanElems = kStatsSpanPairs * kStatsPairElems;
+constexpr int kStatsChunkElems = kWavesPerBlock * kStatsSpanElems;
+constexpr uint64_t kStatsMinGroup = 512;
+constexpr int kStatsMaxBinsPerChunk = kStatsChunkElems / (int)kStatsMinGroup + 2;
 constexpr uint64_t kStatsRecordDoubles = 3;
-inline uint64_t stats_slots(uint64_t group) { return (uint64_t)(kStatsChunkTiles * kTileElems) / group + 2; }
-constexpr uint64_t kStatsMaxSlots = kStatsChunkTiles + 2;
+inline uint64_t stats_workspace_bytes(uint64_t n) {
+  return (n / (uint64_t)kStatsChunkElems + 2) * 2 * kStatsRecordDoubles * sizeof(double);
+}
 
 // fbsr_bias_stats_static: bytes of the workspace array that lives in the library's device image, and the largest
-// call it serves (its records need 240 bytes per 16384 elements: 3.75 MiB at 2^28).
-constexpr uint64_t kStaticScratchBytes = (uint64_t)4 << 20;
+// call it serves (its records need 48 bytes per 16384 elements: 768 KiB at 2^28).
+constexpr uint64_t kStaticScratchBytes = (uint64_t)1 << 20;
 constexpr uint64_t kStaticMaxElems = (uint64_t)1 << 28;
 
 // Address of that array on the current device (looked up once per device).

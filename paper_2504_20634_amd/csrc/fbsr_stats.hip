@@ -3,9 +3,9 @@
 // in fp64 -- the measurement behind Figs. 1 and 2 (mean rounded value per input, bias in
 // target ulps, Sec. III).  Bins are runs of `group` consecutive global indices.
 //
-// Reduction order is fixed (lane-local sums -> xor-butterfly across the wave -> the four waves'
-// sums staged in LDS and added in wave order -> one record per (chunk, bin) in the workspace ->
-// per-bin sums over its chunks, lane-strided then butterfly), so results are bit-reproducible;
+// Reduction order is fixed (lane-local sums -> a fixed tree across the wave -> the four waves' sums
+// added in wave order -> for a bin that continues in a neighbouring chunk one record per chunk in the
+// workspace, added per bin lane-strided and through the same tree), so results are bit-reproducible;
 // no floating-point atomics are used.
 #include <mutex>
 #include <type_traits>
@@ -14,40 +14,13 @@
 
 namespace fbsr {
 
-struct Acc {
-  double sy, se, see;   // sum y, sum e, sum e^2
-  float sy32;           // the part of sum y kept in fp32 (formats whose sums over a chunk are exact there)
-};
-
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-
-// Decoded value of the signed code held in the top bits of r (Eq. (1)).
+// Decoded value of the signed code held in the top bits of r (Eq. (1)).  The hardware decodes agree with Eq. (1) on
+// every finite fp8 code, give infinities for E5M2's and NaN for the NaN codes (whose sign and payload do not matter
+// to a sum).
 template <int FMT>
 __device__ __forceinline__ float decode_top(uint32_t r) {
-  typedef Fx<FMT> F;
-  if constexpr (!F::kIsFp8) {
-    return __uint_as_float(r & 0xFFFF0000u);
-  } else if constexpr (FMT == kP4) {
-    return fp8_code_value<kP4>(r >> 24);
-  } else {
-    const uint32_t c = (r >> 24) & 0x7Fu;
-    const uint32_t e = c >> (F::P - 1);
-    const uint32_t t = c & ((1u << (F::P - 1)) - 1u);
-    const uint32_t mant = e ? (t | (1u << (F::P - 1))) : t;       // subnormals have no hidden one
-    const int ex = (int)(e ? e : 1u) - (F::B + F::P - 1);
-    float y = ldexpf((float)mant, ex);
-    if constexpr (FMT == kE5M2) {
-      y = c == F::INF_CODE ? __uint_as_float(0x7F800000u) : y;
-      y = c > F::INF_CODE ? __uint_as_float(0x7FC00000u) : y;
-    } else {
-      y = c == 0x7Fu ? __uint_as_float(0x7FC00000u) : y;
-    }
-    return __uint_as_float(__float_as_uint(y) | (r & 0x80000000u));
-  }
+  if constexpr (!Fx<FMT>::kIsFp8) return __uint_as_float(r & 0xFFFF0000u);
+  else return fp8_code_value<FMT>(r >> 24);
 }
 
 // 1 / ulp_t(x) = 2^(P - 1 - e~), e~ = max(floor(log2|x|), 1 - B) (Eq. (2)), built from the
@@ -62,259 +35,438 @@ __device__ __forceinline__ double inv_ulp(uint32_t bits) {
   return __hiloint2double((int)hi, 0);
 }
 
-// A lane's share of a chunk is 64 elements.  64 values of E4M3 (multiples of 2^-9 up to 448) or of binary8p4
+// A lane's share of a span is 64 elements.  64 values of E4M3 (multiples of 2^-9 up to 448) or of binary8p4
 // (multiples of 2^-10 up to 224) sum to a multiple of that step below 2^24 steps: exact in fp32 in any order, so
-// the sum of y runs there and is widened once per record.
+// the sum of y runs there and is widened when the wave closes a bin.
 template <int FMT> struct SumYInFp32 { static constexpr bool value = FMT == kE4M3 || FMT == kP4; };
 
-// Adds one element to a bin's sums.  WIDE = false: y - x is formed in fp32, where it is exact for
-// every finite |x| <= M (y is a neighbour of x on a coarser grid, so the difference is a multiple of
-// x's own last place and smaller than 2^24 of them), and so is its scaling by 1 / ulp_t(x), a power of two
-// (the quotient keeps the difference's significand and stays below 2 in magnitude);
-// WIDE = true: the difference is formed in fp64 (overflow, saturation, NaN: values for which the fp32 difference
-// would round or is not finite).  Either way e = (y - x) / ulp_t(x) reaches the fp64 sums without a rounding.
-template <int FMT, bool WIDE>
-__device__ __forceinline__ void accumulate(Acc& acc, uint32_t bits, float y) {
-  typedef Fx<FMT> F;
-  const float x = __uint_as_float(bits);
-  double e;
-  if constexpr (WIDE) {
-    e = ((double)y - (double)x) * inv_ulp<FMT>(bits);
-    acc.sy += (double)y;
-  } else {
-    // 1 / ulp_t(x) = 2^(P - 1 - e~), e~ = max(floor(log2|x|), 1 - B) (Eq. (2)); frexp's exponent is floor(log2|x|) + 1
-    // (0 for x = 0, where y - x = 0 makes the scale irrelevant)
-    const int fe = __builtin_amdgcn_frexp_expf(x);
-    const int k = F::P - (fe > 2 - F::B ? fe : 2 - F::B);
-    e = (double)__builtin_amdgcn_ldexpf(y - x, k);
-    if constexpr (SumYInFp32<FMT>::value) acc.sy32 += y;
-    else acc.sy += (double)y;
-  }
-  acc.se += e;
-  acc.see = fma(e, e, acc.see);
+// End of a bin in global indices, saturating (group may be as large as 2^62, so (bin + 1) * group can pass 2^64).
+__device__ __forceinline__ uint64_t bin_end(uint64_t bin, uint64_t group) {
+  const uint64_t k = bin + 1;
+  return __umul64hi(k, group) != 0 ? ~(uint64_t)0 : k * group;
 }
 
-// The four decoded values of a packed fp8 word (the hardware decode equals Eq. (1) on all 256 codes).
-template <int FMT>
-__device__ __forceinline__ void decode4(uint32_t packed, float (&y)[4]) {
-  if constexpr (FMT == kE4M3 || FMT == kP4) {
-    y[0] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 0); y[1] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 1);
-    y[2] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 2); y[3] = __builtin_amdgcn_cvt_f32_fp8((int)packed, 3);
-    if constexpr (FMT == kP4) {   // finite binary8p4 values are one half of E4M3's at the same code
-#pragma unroll
-      for (int j = 0; j < 4; ++j) y[j] *= 0.5f;
-    }
+// Sum over the wave in a fixed tree: quads, eights and sixteens by DPP, the rows of 16 by two exchanges through LDS
+// hardware.  Every lane ends with the same bits.
+__device__ __forceinline__ double wave_total(double v) {
+  auto dpp = [](double a, auto ctrl) {
+    constexpr int C = decltype(ctrl)::value;
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(a), C, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(a), C, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+  };
+  v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+  v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+  v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+  v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+// The 4 W random bits of four consecutive elements whose first has index e0 (a multiple of 4) in the bit string
+// `strip` holds (element e at bit e W), right-aligned in a 64-bit word.
+template <int W>
+__device__ __forceinline__ uint64_t read_row_bits(const uint4* strip, int e0) {
+  const unsigned char* base = reinterpret_cast<const unsigned char*>(strip);
+  if constexpr (W == 16) {
+    return *reinterpret_cast<const uint64_t*>(base + e0 * 2);
+  } else if constexpr (W == 8) {
+    return *reinterpret_cast<const uint32_t*>(base + e0);
+  } else if constexpr (W == 4) {
+    return *reinterpret_cast<const uint16_t*>(base + e0 / 2);
+  } else if constexpr (W == 2) {
+    return base[e0 / 4];
   } else {
-    y[0] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 0); y[1] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 1);
-    y[2] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 2); y[3] = __builtin_amdgcn_cvt_f32_bf8((int)packed, 3);
+    return (uint32_t)(base[e0 / 8] >> (e0 & 4)) & 0xFu;
   }
 }
 
-// One workgroup per chunk of kStatsChunkTiles tiles.  Sums run in registers across the chunk's
-// tiles and are flushed (wave butterfly -> LDS -> record) when a bin ends and at the chunk's end:
-// record (chunk c, slot s) holds the chunk's part of bin floor(start(c) / group) + s.
-// The random bits of the whole chunk are drawn first, its Philox blocks dealt round-robin to all 256
-// threads (a tile alone has work for 16 W of them, which would leave most waves waiting), and one barrier
-// publishes them; after that the four waves walk the chunk's tiles independently.
+// A lane's running sums for the bin its wave is in.  The integer part serves the elements rounded by round_fast
+// (e as an integer multiple of 2^-FRAC: a lane adds at most 64 of them, each below 2^FRAC in magnitude, before its
+// wave closes the span, so 32 bits hold their sum and 64 bits the sum of their squares, both exactly); the fp64 part
+// serves the elements of the general path.
+struct LaneSums {
+  int32_t se_i, neg_i;   // sum of e_int ^ s and of s, s = -1 for a negative x and 0 otherwise: their difference is the signed sum
+  long long see_i;
+  float sy32;           // sum y in fp32 for the formats whose 64 values per lane add exactly there
+  double sy, se, see;
+};
+
+// One workgroup per chunk of kStatsChunkElems consecutive elements, one wave per span of kStatsSpanElems of them,
+// walked in pairs of rows of 256 (lane l owns elements 4 l .. 4 l + 3 of a row: one coalesced 16-byte load).  A wave
+// draws the random bits of its own span -- lane l computes block 64 k + l of the span in round k, so one round
+// serves 8192 / W elements, and the blocks pass through a strip of LDS that only this wave touches -- and keeps
+// its sums in registers; where a bin ends inside the span the sums are closed (wave_total) into the wave's row of
+// `part`, one entry per bin the chunk touches.  Nothing in the loop waits for another wave: the one barrier of the
+// kernel stands after it, in code every thread reaches.  Then the four rows are added in wave order; the chunk's
+// first and last bin go to the workspace (they may continue in the neighbouring chunks; stats_finalize adds them
+// up), the bins in between are complete and are added to the caller's statistics right here.
+//
+// Per pair of rows the wave picks, uniformly, the cheapest path the pair's 512 elements allow (see do_pair): one of
+// three integer flavours of round_fast with integer error sums, or the general path in fp64.
 template <int FMT, int VAR, int W>
-__global__ __launch_bounds__(kThreads) void stats_tiles(const float* __restrict__ x, void* __restrict__ out,
-                                                        uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
-                                                        uint64_t i0, uint64_t group, uint64_t slots,
-                                                        double* __restrict__ records) {
-  typedef WgTile<W> T;
+__global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict__ x, void* __restrict__ out,
+                                                        uint64_t npairs, int nbits, uint64_t seed, uint64_t blk0,
+                                                        uint64_t i0, uint64_t group, uint64_t first_bin,
+                                                        uint64_t chunk_base, double* __restrict__ records,
+                                                        double* __restrict__ stats) {
   typedef Fx<FMT> F;
-  // MANY: more than 16 random bits per element (32-bit slots, the wide rounding).  The strip then holds the bits of
-  // half a chunk at a time (32 KiB) and is refilled before the fifth tile.
-  constexpr bool MANY = W == 32 && VAR != kRNE;
-  constexpr int kStripTiles = MANY ? kStatsChunkTiles / 2 : kStatsChunkTiles;
-  __shared__ uint4 strip[kStripTiles * T::BLOCKS];
-  __shared__ double staged[kWavesPerBlock][kStatsRecordDoubles];
+  constexpr bool DRAWS = VAR != kRNE;
+  constexpr bool MANY = W == 32 && DRAWS;                         // more than 16 bits: a lane's row is one block of its own
+  constexpr int PPR = W >= 16 ? 1 : (W >= 2 ? 16 / W : 8);        // pairs of rows one round of 64 blocks serves
+  constexpr int SPAN_BLOCKS = kStatsSpanElems / 128 * (W > 16 ? 16 : W);   // blocks that hold the span's bits (W <= 16)
+  __shared__ uint4 strips[kWavesPerBlock][2][64];
+  __shared__ double part[kWavesPerBlock][kStatsMaxBinsPerChunk][kStatsRecordDoubles];
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // in a scalar register: what follows from it is uniform
+  const uint64_t chunk = chunk_base + blockIdx.x;
+  const uint64_t i_end = i0 + npairs * kStatsPairElems;
+  const uint64_t chunk_lo = i0 + chunk * kStatsChunkElems;        // < i_end: the grid has one workgroup per started chunk
+  const uint64_t chunk_hi = chunk_lo + kStatsChunkElems < i_end ? chunk_lo + kStatsChunkElems : i_end;
+  const uint64_t bin_first = chunk_lo / group;
+  const int nbins_here = (int)((chunk_hi - 1) / group - bin_first) + 1;   // <= kStatsMaxBinsPerChunk: group >= kStatsMinGroup
 
+  for (int t = lane; t < nbins_here * (int)kStatsRecordDoubles; t += 64) (&part[wave][0][0])[t] = 0.0;
+
+  const uint64_t span_lo = chunk_lo + (uint64_t)wave * kStatsSpanElems;
+  const uint64_t pair0 = chunk * (kStatsChunkElems / kStatsPairElems) + (uint64_t)(wave * kStatsSpanPairs);
+  const int my_pairs = pair0 >= npairs ? 0 : (npairs - pair0 < (uint64_t)kStatsSpanPairs ? (int)(npairs - pair0) : kStatsSpanPairs);
   const Addends a = make_addends<FMT, VAR>(MANY ? kMaxTileNbits : nbits);
-  HwAddends hw = {0, 0, 0, 0};
-  if constexpr (F::kIsFp8 && VAR != kRNE && !MANY) hw = make_hw_addends<FMT, VAR>(nbits);
-  const uint64_t tile0 = (uint64_t)blockIdx.x * kStatsChunkTiles;
-  const uint64_t chunk_start = i0 + tile0 * T::ELEMS;
-  uint64_t next_bin = group - chunk_start % group;   // chunk-relative index at which the next bin starts
-  uint64_t slot = 0;
-  Acc cur = {0.0, 0.0, 0.0, 0.0f};
-  // draws the bits of the tiles [first, first + kStripTiles) of the chunk (those that exist) into the strip
-  auto draw = [&](int first) {
-    const uint64_t left = ntiles - (tile0 + (uint64_t)first);   // > 0 at every call
-    const int nblk = (int)(left < (uint64_t)kStripTiles ? left : (uint64_t)kStripTiles) * T::BLOCKS;
-    for (int bi = threadIdx.x; bi < nblk; bi += kThreads) {
-      uint32_t o[4];
-      philox_block(blk0 + (tile0 + (uint64_t)first) * T::BLOCKS + (uint64_t)bi, seed, 0, o);
-      strip[bi] = make_uint4(o[0], o[1], o[2], o[3]);
-    }
-    __syncthreads();
-  };
-  if constexpr (VAR != kRNE) draw(0);   // the grid has one workgroup per started chunk: tile0 < ntiles
+  const uint64_t span_blk = blk0 + (chunk * (kStatsChunkElems / 128) + (uint64_t)wave * (kStatsSpanElems / 128)) * (uint64_t)W;
+  uint4* strip = &strips[wave][0][0];
 
-  auto flush = [&]() {
-    const double t0 = wave_sum(cur.sy + (double)cur.sy32), t1 = wave_sum(cur.se), t2 = wave_sum(cur.see);
-    if (lane == 0) {
-      staged[wave][0] = t0; staged[wave][1] = t1; staged[wave][2] = t2;
-    }
-    __syncthreads();
-    if (threadIdx.x < kStatsRecordDoubles) {
-      double t = staged[0][threadIdx.x];
-#pragma unroll
-      for (int wv = 1; wv < kWavesPerBlock; ++wv) t += staged[wv][threadIdx.x];
-      records[((uint64_t)blockIdx.x * slots + slot) * kStatsRecordDoubles + threadIdx.x] = t;
-    }
-    __syncthreads();
-    slot += 1;
-    cur = {0.0, 0.0, 0.0, 0.0f};
-  };
-
-  // the loads of a tile are issued one iteration ahead, so that their latency is covered by the arithmetic of
-  // the tile before (the waves of a workgroup run independently between the chunk's barriers)
-  const uint64_t lane_row = (uint64_t)(wave * (kWaveElems / 4) + lane);
-  f32x4 ahead[kRows];
-#pragma unroll
-  for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(x + 4 * (tile0 * (T::ELEMS / 4) + lane_row + (uint64_t)(k * 64)));   // tile0 < ntiles
-#pragma unroll 1
-  for (int it = 0; it < kStatsChunkTiles; ++it) {
-    const uint64_t tile = tile0 + (uint64_t)it;
-    if (tile >= ntiles) break;   // uniform over the workgroup
-    if constexpr (MANY) {
-      if (it == kStripTiles) {   // every wave is done with the first half's bits before they are replaced
-        __syncthreads();
-        draw(kStripTiles);
+  // round k of the span's bits into half k & 1 of the wave's strip
+  auto draw = [&](int k) {
+    if constexpr (DRAWS && !MANY) {
+      const int b = k * 64 + lane;
+      if (b < SPAN_BLOCKS) {
+        uint32_t o[4];
+        philox_block(span_blk + (uint64_t)b, seed, 0, o);
+        strip[(k & 1) * 64 + lane] = make_uint4(o[0], o[1], o[2], o[3]);
       }
-    }
-    const uint64_t row0 = tile * (T::ELEMS / 4) + lane_row;   // units of 4 elements
-    f32x4 v[kRows];
-#pragma unroll
-    for (int k = 0; k < kRows; ++k) v[k] = ahead[k];
-    if (it + 1 < kStatsChunkTiles && tile + 1 < ntiles) {
-#pragma unroll
-      for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(x + 4 * (row0 + (uint64_t)(T::ELEMS / 4) + (uint64_t)(k * 64)));
-    }
+      __builtin_amdgcn_wave_barrier();   // the wave's own LDS traffic keeps program order; this keeps the compiler to it
 
+    }
+  };
+
+  LaneSums cur = {0, 0, 0, 0.0f, 0.0, 0.0, 0.0};
+  int slot = my_pairs > 0 ? (int)(span_lo / group - bin_first) : 0;
+  uint64_t next_bin = my_pairs > 0 ? group - span_lo % group : 0;   // span-relative index at which the next bin starts
+
+  // closes the sums of the bin the wave is in
+  auto close_bin = [&]() {
+    constexpr double kUnit = 1.0 / (double)((uint64_t)1 << F::FRAC);
+    const double t0 = wave_total(cur.sy + (double)cur.sy32);
+    const double t1 = wave_total(cur.se + (double)(cur.se_i - cur.neg_i) * kUnit);
+    const double t2 = wave_total(cur.see + (double)cur.see_i * (kUnit * kUnit));
+    if (lane == 0) {
+      part[wave][slot][0] = t0; part[wave][slot][1] = t1; part[wave][slot][2] = t2;
+    }
+    slot += 1;
+    cur = {0, 0, 0, 0.0f, 0.0, 0.0, 0.0};
+  };
+
+  const float* xs = x + (span_lo - i0);
+  f32x4 va[kRows], vb[kRows];
+  auto load_pair = [&](f32x4 (&v)[kRows], int p) {
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) v[k] = load_stream4(xs + (p * kStatsPairElems + k * 256 + 4 * lane));
+  };
+
+  // Walks the bins of the elements [lo_e, lo_e + len) of the span: add_all() adds all of them to the running sums,
+  // add_some(first, last) those whose index relative to lo_e lies in [first, last).
+  auto over_bins = [&](int lo_e, int len, auto add_all, auto add_some) {
+    const int hi_e = lo_e + len;
+    if (next_bin >= (uint64_t)hi_e) {
+      add_all();
+      return;
+    }
+    int from = 0;
+    while (next_bin < (uint64_t)hi_e) {   // uniform over the wave
+      const int cut = (int)next_bin - lo_e;
+      add_some(from, cut);
+      close_bin();
+      from = cut;
+      next_bin += group;
+    }
+    add_some(from, len);
+  };
+
+  // The random integers of this lane's four elements in row k of pair p.
+  auto row_draws = [&](int p, int k, uint32_t (&n)[4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) n[j] = 0;
+    if constexpr (MANY) {
+      uint32_t o[4];
+      philox_block(span_blk + (uint64_t)((p * kRows + k) * 64 + lane), seed, 0, o);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) n[j] = __builtin_amdgcn_ubfe(o[j], 0u, (uint32_t)nbits);
+    } else if constexpr (DRAWS) {
+      const uint64_t rb = read_row_bits<W>(strip + ((p / PPR) & 1) * 64, (p % PPR) * kStatsPairElems + k * 256 + 4 * lane);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) n[j] = slot_bits<W>(rb, j, a.nbits);
+    }
+  };
+
+  // The general path for row k of pair p: the checked rounding, and e = (y - x) / ulp_t(x) with every step in fp64
+  // (Sec. III), so that non-finite values follow IEEE arithmetic.  It is rare, and it is kept small rather than
+  // fast: one row at a time, its elements read again (from the cache) so that the registers of the fast paths are
+  // not held across it.
+  auto general_row = [&](int p, int k) {
+    const int e0 = p * kStatsPairElems + k * 256;   // span-relative index of the row
+    const f32x4 v = *reinterpret_cast<const f32x4*>(xs + (e0 + 4 * lane));
+    const uint32_t b[4] = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+    uint32_t n[4], r[4];
+    row_draws(p, k, n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if constexpr (MANY) r[j] = round_pattern_wide<FMT, VAR>(b[j], n[j], (uint32_t)nbits);
+      else r[j] = round_pattern<FMT, VAR, true>(b[j], n[j], a);
+    }
+    if (out != nullptr) {
+      const uint64_t row = (span_lo - i0) / 4 + (uint64_t)(e0 / 4 + lane);   // units of 4 elements
+      if constexpr (F::kIsFp8)
+        reinterpret_cast<uint32_t*>(out)[row] = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
+      else
+        reinterpret_cast<uint64_t*>(out)[row] = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
+    }
+    auto add_one = [&](uint32_t bits, uint32_t rr) {
+      const double y = (double)decode_top<FMT>(rr);
+      const double e = (y - (double)__uint_as_float(bits)) * inv_ulp<FMT>(bits);
+      cur.sy += y;
+      cur.se += e;
+      cur.see = fma(e, e, cur.see);
+    };
+    over_bins(
+        e0, 256,
+        [&]() {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) add_one(b[j], r[j]);
+        },
+        [&](int first, int last) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int e = 4 * lane + j;
+            if (e >= first && e < last) add_one(b[j], r[j]);
+          }
+        });
+  };
+
+  // everything for pair p of the span, whose elements are in v
+  auto do_pair = [&](const f32x4 (&v)[kRows], int p) {
     uint32_t b[kRows][4];
-    float y[kRows][4];
-    uint32_t umax = 0;
 #pragma unroll
     for (int k = 0; k < kRows; ++k) {
       b[k][0] = __float_as_uint(v[k].x); b[k][1] = __float_as_uint(v[k].y);
       b[k][2] = __float_as_uint(v[k].z); b[k][3] = __float_as_uint(v[k].w);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) umax = max(umax, b[k][j] & 0x7FFFFFFFu);
     }
-    // wave-uniform: |x| > M or NaN anywhere in the wave sends it down the checked integer rounding and
-    // the fp64 difference; otherwise the unchecked rounding (hardware converts for fp8) applies
-    const bool wide_path = __any(umax > F::U_MAXFIN);
-    const uint64_t t_lo = (uint64_t)it * T::ELEMS, t_hi = t_lo + T::ELEMS;   // chunk-relative range of this tile
-
-    // the rest of the tile, instantiated once per flavour so that each is straight-line code
-    auto finish_tile = [&](auto wide_tag) {
-      constexpr bool WIDE = decltype(wide_tag)::value;
+    // Which path: a cascade of wave-uniform tests, the cheapest first.
+    //   kPositive  every pattern, taken as an unsigned integer, lies between those of 2^(1-B) (bf16: 0) and M: no sign
+    //              bit, no NaN, nothing out of range, (fp8) nothing below the normal range;
+    //   kSigned    the same for |x|, either sign;
+    //   kMixed     (fp8) as kSigned, with zeros and target-subnormal values that the 24-bit code space places exactly;
+    //   kPositiveMixed  (fp8) as kMixed when no pattern has its sign bit set;
+    //   kGeneral   everything else.
+    enum : int { kPositive, kSigned, kMixed, kPositiveMixed, kGeneral };
+    int path = kGeneral;
+    if constexpr (!MANY) {
+      uint32_t top = 0, bottom = 0xFFFFFFFFu;
 #pragma unroll
-      for (int k = 0; k < kRows; ++k) {
-        uint32_t n4[4] = {0, 0, 0, 0};
-        if constexpr (MANY) {
-          // the row's four 32-bit slots are one Philox block
-          const uint4 q = strip[(it % kStripTiles) * T::BLOCKS + (wave * kWaveElems + k * 256 + 4 * lane) / 4];
-          n4[0] = __builtin_amdgcn_ubfe(q.x, 0u, (uint32_t)nbits); n4[1] = __builtin_amdgcn_ubfe(q.y, 0u, (uint32_t)nbits);
-          n4[2] = __builtin_amdgcn_ubfe(q.z, 0u, (uint32_t)nbits); n4[3] = __builtin_amdgcn_ubfe(q.w, 0u, (uint32_t)nbits);
-        } else if constexpr (VAR != kRNE) {
-          const uint64_t rb = read_wg_row_bits<W>(strip + it * T::BLOCKS, wave, lane, k);
+      for (int k = 0; k < kRows; ++k)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) n4[j] = slot_bits<W>(rb, j, a.nbits);
+        for (int j = 0; j < 4; j += 2) {
+          top = max(top, max(b[k][j], b[k][j + 1]));
+          if constexpr (F::kIsFp8) bottom = min(bottom, min(b[k][j], b[k][j + 1]));
         }
-        constexpr bool HW = !WIDE && F::kIsFp8 && VAR != kRNE && !MANY;
-        uint32_t r[4] = {0, 0, 0, 0};
-        uint32_t packed = 0;
-        if constexpr (HW) {
-          packed = round4_fp8_hw<FMT, VAR>(b[k], n4, hw);
-        } else if constexpr (MANY) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) r[j] = round_pattern_wide<FMT, VAR>(b[k][j], n4[j], (uint32_t)nbits);
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, WIDE>(b[k][j], n4[j], a);
-        }
-        const uint64_t row = row0 + (uint64_t)(k * 64);
-        if constexpr (F::kIsFp8) {
-          if constexpr (!HW) packed = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
-          if constexpr (WIDE) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) y[k][j] = decode_top<FMT>(r[j]);   // keeps this library's NaN / sign conventions
-          } else {
-            decode4<FMT>(packed, y[k]);
-          }
-          if (out != nullptr) reinterpret_cast<uint32_t*>(out)[row] = packed;
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) y[k][j] = __uint_as_float(r[j] & 0xFFFF0000u);
-          if (out != nullptr)
-            reinterpret_cast<uint64_t*>(out)[row] = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
-        }
-      }
-
-      // adds the elements whose tile-relative index lies in [lo, hi) to `cur`; ALL = the whole tile
-      auto add_range = [&](auto all_tag, int lo, int hi) {
-        constexpr bool ALL = decltype(all_tag)::value;
-        const int w_lo = wave * kWaveElems;
+      bool ok;
+      if constexpr (F::kIsFp8) ok = !__any(top > F::U_MAXFIN || bottom < F::U_SUB);
+      else ok = !__any(top > F::U_MAXFIN);
+      bool ok_mixed = false;   // positive, <= M, nothing between zero and the smallest exactly placed pattern (zero itself excluded too)
+      if constexpr (F::kIsFp8) ok_mixed = !ok && !__any(top > F::U_MAXFIN || bottom < FastLimits<FMT>::U_DEEP);
+      if (ok) {
+        path = kPositive;
+      } else if (ok_mixed) {
+        path = kPositiveMixed;
+      } else if constexpr (F::kIsFp8) {
+        // (|x| pattern - pattern of 2^(1-B)) * 2 as an unsigned number: small for target-normal |x| <= M, huge otherwise
+        uint32_t m = 0;
 #pragma unroll
         for (int k = 0; k < kRows; ++k)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int e = w_lo + k * 256 + 4 * lane + j;
-            const bool in = ALL || (e >= lo && e < hi);
-            if constexpr (ALL) {
-              accumulate<FMT, WIDE>(cur, b[k][j], y[k][j]);
-            } else if constexpr (WIDE) {
-              if (in) accumulate<FMT, true>(cur, b[k][j], y[k][j]);
-            } else {
-              // outside the range: contribute y = 0 and x = 0, whose terms are exact zeros
-              accumulate<FMT, false>(cur, in ? b[k][j] : 0u, in ? y[k][j] : 0.0f);
+          for (int j = 0; j < 4; j += 2)
+            m = max(m, max((b[k][j] << 1) - 2u * F::U_SUB, (b[k][j + 1] << 1) - 2u * F::U_SUB));
+        if (!__any(m > 2u * (F::U_MAXFIN - F::U_SUB))) {
+          path = kSigned;
+        } else {
+          uint32_t hi = 0, lo = 0xFFFFFFFFu;   // largest |pattern|; smallest |pattern| - 1 (zero wraps to the top)
+#pragma unroll
+          for (int k = 0; k < kRows; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const uint32_t u = b[k][j] & 0x7FFFFFFFu;
+              hi = max(hi, u);
+              lo = min(lo, u - 1u);
             }
-          }
-      };
-
-      if (next_bin >= t_hi) {
-        add_range(std::true_type{}, 0, T::ELEMS);
-      } else {                       // a bin ends inside this tile (at most once: group >= tile)
-        const int cut = (int)(next_bin - t_lo);
-        add_range(std::false_type{}, 0, cut);
-        flush();
-        add_range(std::false_type{}, cut, T::ELEMS);
-        next_bin += group;
+          if (!__any(hi > F::U_MAXFIN || lo < FastLimits<FMT>::U_DEEP - 1u)) path = kMixed;
+        }
+      } else {
+        // largest |x|: among the negative patterns the unsigned maximum (top), among the others the signed one
+        int32_t mi = 0;
+#pragma unroll
+        for (int k = 0; k < kRows; ++k)
+#pragma unroll
+          for (int j = 0; j < 4; j += 2) mi = max(mi, max((int32_t)b[k][j], (int32_t)b[k][j + 1]));
+        if (!__any((top & 0x7FFFFFFFu) > F::U_MAXFIN || mi > (int32_t)F::U_MAXFIN)) path = kSigned;
       }
+    }
+    if (path == kGeneral) {
+#pragma unroll 1
+      for (int k = 0; k < kRows; ++k) general_row(p, k);
+      return;
+    }
+
+    // the three integer paths share everything but the flavour of round_fast and the handling of the sign
+    auto integer_pair = [&](auto mixed_tag, auto positive_tag) {
+      constexpr bool MIXED = decltype(mixed_tag)::value, POSITIVE = decltype(positive_tag)::value;
+      FastRound fr[kRows][4];
+#pragma unroll
+      for (int k = 0; k < kRows; ++k) {
+        uint32_t n[4];
+        row_draws(p, k, n);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fr[k][j] = round_fast<FMT, VAR, MIXED, POSITIVE>(b[k][j], n[j], a);
+      }
+      if (out != nullptr) {
+        const uint64_t orow = (span_lo - i0) / 4 + (uint64_t)(p * (kStatsPairElems / 4) + lane);   // units of 4 elements
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) {
+          if constexpr (F::kIsFp8) {
+            uint32_t packed = pack4_fp8<FMT>(fr[k][0].rs, fr[k][1].rs, fr[k][2].rs, fr[k][3].rs);
+            if constexpr (FMT == kP4 && MIXED) {   // no negative zero: a byte with a zero magnitude loses its sign
+              const uint32_t mg = packed & 0x7F7F7F7Fu;
+              packed &= (((mg + 0x7F7F7F7Fu) | mg) & 0x80808080u) | 0x7F7F7F7Fu;
+            }
+            reinterpret_cast<uint32_t*>(out)[orow + (uint64_t)(k * 64)] = packed;
+          } else {
+            reinterpret_cast<uint64_t*>(out)[orow + (uint64_t)(k * 64)] =
+                (uint64_t)pack2_bf16(fr[k][0].rs, fr[k][1].rs) | ((uint64_t)pack2_bf16(fr[k][2].rs, fr[k][3].rs) << 32);
+          }
+        }
+      }
+      // e_int is the error of the magnitude; e carries the sign of x: (e_int ^ s) - s with s = -1 for x < 0, else 0
+      auto add_one = [&](const FastRound& f, uint32_t bits) {
+        const float y = fast_value<FMT>(f.rs);
+        if constexpr (POSITIVE) {
+          cur.se_i += f.e_int;
+        } else {
+          const int32_t s = (int32_t)bits >> 31;
+          cur.se_i += f.e_int ^ s;
+          cur.neg_i += s;
+        }
+        cur.see_i += (long long)f.e_int * (long long)f.e_int;
+        if constexpr (SumYInFp32<FMT>::value) cur.sy32 += y;
+        else cur.sy += (double)y;
+      };
+      over_bins(
+          p * kStatsPairElems, kStatsPairElems,
+          [&]() {
+#pragma unroll
+            for (int k = 0; k < kRows; ++k)
+#pragma unroll
+              for (int j = 0; j < 4; ++j) add_one(fr[k][j], b[k][j]);
+          },
+          [&](int first, int last) {
+#pragma unroll
+            for (int k = 0; k < kRows; ++k)
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const int e = k * 256 + 4 * lane + j;
+                // outside the range: a zero code with a zero error adds exact zeros
+                const bool in = e >= first && e < last;
+                FastRound f = fr[k][j];
+                f.rs = in ? f.rs : 0u;
+                f.e_int = in ? f.e_int : 0;
+                add_one(f, b[k][j]);
+              }
+          });
     };
-    if (wide_path) finish_tile(std::true_type{});
-    else finish_tile(std::false_type{});
+    if (path == kPositive) integer_pair(std::false_type{}, std::true_type{});
+    else if (path == kSigned) integer_pair(std::false_type{}, std::false_type{});
+    else if (path == kPositiveMixed) integer_pair(std::integral_constant<bool, F::kIsFp8>{}, std::true_type{});
+    else integer_pair(std::integral_constant<bool, F::kIsFp8>{}, std::false_type{});
+  };
+
+  if (my_pairs > 0) {
+    load_pair(va, 0);
+    draw(0);
+    // Two pairs per trip, their loads in two register sets: the loads of a pair are in flight while the pair before
+    // it is worked on, and no register is copied.  Every trip issues its loads whether or not the pair exists (past
+    // the end the span's last pair is read again and dropped): with a load that may or may not have been issued
+    // the compiler would have to wait for all of them at the point where the two cases meet.
+    const int last = my_pairs - 1;
+#pragma unroll 1
+    for (int p = 0; p < kStatsSpanPairs; p += 2) {
+      load_pair(vb, p + 1 < last ? p + 1 : last);
+      if (p % PPR == 0 && p / PPR + 1 < (kStatsSpanPairs + PPR - 1) / PPR) draw(p / PPR + 1);
+      do_pair(va, p);
+      if (p + 1 > last) break;   // uniform over the wave
+      load_pair(va, p + 2 < last ? p + 2 : last);
+      if ((p + 1) % PPR == 0 && (p + 1) / PPR + 1 < (kStatsSpanPairs + PPR - 1) / PPR) draw((p + 1) / PPR + 1);
+      do_pair(vb, p + 1);
+      if (p + 2 > last) break;
+    }
+    close_bin();
   }
-  flush();
+  __syncthreads();
+  const int t = threadIdx.x;
+  if (t < nbins_here * (int)kStatsRecordDoubles) {
+    const int s = t / (int)kStatsRecordDoubles, k = t % (int)kStatsRecordDoubles;
+    double v = part[0][s][k];
+#pragma unroll
+    for (int wv = 1; wv < kWavesPerBlock; ++wv) v += part[wv][s][k];
+    if (s == 0) {
+      records[chunk * (2 * kStatsRecordDoubles) + k] = v;
+    } else if (s == nbins_here - 1) {
+      records[chunk * (2 * kStatsRecordDoubles) + kStatsRecordDoubles + k] = v;
+    } else {
+      double* st = stats + (bin_first + (uint64_t)s - first_bin) * 4;   // a bin that lies inside this chunk: no other writer
+      st[1 + k] += v;
+      if (k == 0) st[0] += (double)group;
+    }
+  }
 }
 
-// One wave per bin: sums the records of the chunks that overlap the bin and adds the bin's totals
-// to the caller's statistics.  Chunks cover global indices [i0, i_end).
+// One wave per bin: adds up the parts of the bin that stats_spans left in the workspace (the bin is the first or the
+// last one of every chunk it shares with a neighbour; a bin inside a single chunk was finished there) and adds the
+// totals to the caller's statistics.  Chunks cover global indices [i0, i_end).
 __global__ __launch_bounds__(64) void stats_finalize(const double* __restrict__ records, uint64_t i0, uint64_t i_end,
-                                                     uint64_t chunk_elems, uint64_t slots, uint64_t group,
-                                                     uint64_t bin_lo, uint64_t first_bin, double* __restrict__ stats) {
+                                                     uint64_t group, uint64_t bin_lo, uint64_t first_bin,
+                                                     double* __restrict__ stats) {
   const int lane = threadIdx.x;
   const uint64_t bin = bin_lo + blockIdx.x;
   const uint64_t lo = bin * group > i0 ? bin * group : i0;
-  const uint64_t hi = (bin + 1) * group < i_end ? (bin + 1) * group : i_end;
+  const uint64_t be = bin_end(bin, group);
+  const uint64_t hi = be < i_end ? be : i_end;
   if (lo >= hi) return;
-  const uint64_t c_lo = (lo - i0) / chunk_elems, c_hi = (hi - 1 - i0) / chunk_elems;
+  const uint64_t c_lo = (lo - i0) / kStatsChunkElems, c_hi = (hi - 1 - i0) / kStatsChunkElems;
   double sy = 0.0, se = 0.0, see = 0.0;
+  bool mine = false;
   for (uint64_t c = c_lo + (uint64_t)lane; c <= c_hi; c += 64) {
-    const uint64_t first = (i0 + c * chunk_elems) / group;   // the bin of the chunk's slot 0
-    const double* rec = records + (c * slots + (bin - first)) * kStatsRecordDoubles;
+    const uint64_t cs = i0 + c * kStatsChunkElems;
+    const uint64_t ce = cs + kStatsChunkElems < i_end ? cs + kStatsChunkElems : i_end;
+    const uint64_t fb = cs / group, lb = (ce - 1) / group;
+    if (bin != fb && bin != lb) continue;   // inside chunk c (then c_lo == c_hi): finished by stats_spans
+    const double* rec = records + c * (2 * kStatsRecordDoubles) + (bin == fb ? 0 : kStatsRecordDoubles);
     sy += rec[0];
     se += rec[1];
     see += rec[2];
+    mine = true;
   }
-  sy = wave_sum(sy);
-  se = wave_sum(se);
-  see = wave_sum(see);
+  if (!__any(mine)) return;
+  sy = wave_total(sy);
+  se = wave_total(se);
+  see = wave_total(see);
   if (lane == 0) {
     double* s = stats + (bin - first_bin) * 4;
     s[0] += (double)(hi - lo);
@@ -325,7 +477,7 @@ __global__ __launch_bounds__(64) void stats_finalize(const double* __restrict__ 
 }
 
 // One thread per bin, serial over the bin's elements inside [a, a + n): any alignment, any
-// group size; used for ragged heads and tails and whenever the tile kernel does not apply.
+// group size; used for ragged heads and tails and for bins shorter than kStatsMinGroup.
 template <int FMT, int VAR>
 __global__ __launch_bounds__(kThreads) void stats_bins(const float* __restrict__ x, void* __restrict__ out, uint64_t n,
                                                        int nbits, int W, int log2_per_block, uint64_t seed, uint64_t a0,
@@ -335,11 +487,12 @@ __global__ __launch_bounds__(kThreads) void stats_bins(const float* __restrict__
   if (k >= nb) return;
   const uint64_t bin = bin_lo + k;
   const uint64_t lo = bin * group > a0 ? bin * group : a0;
-  const uint64_t hi = (bin + 1) * group < a0 + n ? (bin + 1) * group : a0 + n;
+  const uint64_t be = bin_end(bin, group);
+  const uint64_t hi = be < a0 + n ? be : a0 + n;
   if (lo >= hi) return;
   const bool many_bits = VAR != kRNE && nbits > kMaxTileNbits;   // uniform over the launch
   const Addends a = make_addends<FMT, VAR>(many_bits ? kMaxTileNbits : nbits);
-  Acc acc = {0.0, 0.0, 0.0, 0.0f};
+  double sy = 0.0, se = 0.0, see = 0.0;
   typedef typename Fx<FMT>::code_t code_t;
   for (uint64_t i = lo; i < hi; ++i) {
     const uint32_t bits = __float_as_uint(x[i - a0]);
@@ -351,29 +504,31 @@ __global__ __launch_bounds__(kThreads) void stats_bins(const float* __restrict__
       r = round_pattern<FMT, VAR, true>(bits, 0u, a);
     }
     if (out != nullptr) reinterpret_cast<code_t*>(out)[i - a0] = (code_t)(r >> Fx<FMT>::FRAC);
-    accumulate<FMT, true>(acc, bits, decode_top<FMT>(r));
+    const double y = (double)decode_top<FMT>(r);
+    const double e = (y - (double)__uint_as_float(bits)) * inv_ulp<FMT>(bits);
+    sy += y;
+    se += e;
+    see = fma(e, e, see);
   }
   double* s = stats + (bin - first_bin) * 4;
   s[0] += (double)(hi - lo);
-  s[1] += acc.sy;
-  s[2] += acc.se;
-  s[3] += acc.see;
+  s[1] += sy;
+  s[2] += se;
+  s[3] += see;
 }
 
 namespace {
 
 template <int FMT, int VAR, int W>
-hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
-                        uint64_t i0, uint64_t group, double* records, hipStream_t stream) {
-  const uint64_t chunks = (ntiles + kStatsChunkTiles - 1) / kStatsChunkTiles;
-  const uint64_t slots = stats_slots(group);
-  const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
+hipError_t launch_spans(const float* x, void* out, uint64_t npairs, int nbits, uint64_t seed, uint64_t blk0,
+                        uint64_t i0, uint64_t group, uint64_t first_bin, double* records, double* stats,
+                        hipStream_t stream) {
+  const uint64_t per_chunk = kStatsChunkElems / kStatsPairElems;
+  const uint64_t chunks = (npairs + per_chunk - 1) / per_chunk;
   for (uint64_t c0 = 0; c0 < chunks; c0 += kMaxTilesPerLaunch) {   // at most 2^30 threads per launch
     const uint64_t cnt = chunks - c0 < kMaxTilesPerLaunch ? chunks - c0 : kMaxTilesPerLaunch;
-    const uint64_t t0 = c0 * kStatsChunkTiles, e0 = t0 * kTileElems;
-    hipLaunchKernelGGL((stats_tiles<FMT, VAR, W>), dim3((unsigned)cnt), dim3(kThreads), 0, stream, x + e0,
-                       out ? reinterpret_cast<char*>(out) + e0 * osize : nullptr, ntiles - t0, nbits, seed,
-                       blk0 + t0 * WgTile<W>::BLOCKS, i0 + e0, group, slots, records + c0 * slots * kStatsRecordDoubles);
+    hipLaunchKernelGGL((stats_spans<FMT, VAR, W>), dim3((unsigned)cnt), dim3(kThreads), 0, stream, x, out, npairs, nbits,
+                       seed, blk0, i0, group, first_bin, c0, records, stats);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -381,18 +536,19 @@ hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, u
 }
 
 template <int FMT, int VAR>
-hipError_t launch_tiles_w(int W, const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed,
-                          uint64_t blk0, uint64_t i0, uint64_t group, double* records, hipStream_t stream) {
+hipError_t launch_spans_w(int W, const float* x, void* out, uint64_t npairs, int nbits, uint64_t seed, uint64_t blk0,
+                          uint64_t i0, uint64_t group, uint64_t first_bin, double* records, double* stats,
+                          hipStream_t stream) {
   if constexpr (VAR == kRNE) {
-    return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+    return launch_spans<FMT, VAR, 8>(x, out, npairs, nbits, seed, blk0, i0, group, first_bin, records, stats, stream);
   } else {
     switch (W) {
-      case 1: return launch_tiles<FMT, VAR, 1>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-      case 2: return launch_tiles<FMT, VAR, 2>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-      case 4: return launch_tiles<FMT, VAR, 4>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-      case 8: return launch_tiles<FMT, VAR, 8>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-      case 16: return launch_tiles<FMT, VAR, 16>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
-      default: return launch_tiles<FMT, VAR, 32>(x, out, ntiles, nbits, seed, blk0, i0, group, records, stream);
+      case 1: return launch_spans<FMT, VAR, 1>(x, out, npairs, nbits, seed, blk0, i0, group, first_bin, records, stats, stream);
+      case 2: return launch_spans<FMT, VAR, 2>(x, out, npairs, nbits, seed, blk0, i0, group, first_bin, records, stats, stream);
+      case 4: return launch_spans<FMT, VAR, 4>(x, out, npairs, nbits, seed, blk0, i0, group, first_bin, records, stats, stream);
+      case 8: return launch_spans<FMT, VAR, 8>(x, out, npairs, nbits, seed, blk0, i0, group, first_bin, records, stats, stream);
+      case 16: return launch_spans<FMT, VAR, 16>(x, out, npairs, nbits, seed, blk0, i0, group, first_bin, records, stats, stream);
+      default: return launch_spans<FMT, VAR, 32>(x, out, npairs, nbits, seed, blk0, i0, group, first_bin, records, stats, stream);
     }
   }
 }
@@ -420,28 +576,30 @@ hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, 
                uint64_t first_bin, double* stats, double* workspace, hipStream_t stream) {
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
   const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
-  Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
-                        reinterpret_cast<uintptr_t>(out), osize, 4 * osize);
-  if (group < s.tile_elems) {   // a tile could touch more than two bins
-    s.head = 0;
-    s.ntiles = 0;
-  }
+  // the vector kernel takes whole pairs of rows, from the first element that starts a Philox block
+  const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
+                              reinterpret_cast<uintptr_t>(out), osize, 4 * osize, 0, 0, 1, kStatsPairElems);
+  const uint64_t head = group < kStatsMinGroup ? 0 : s.head;
+  const uint64_t npairs = group < kStatsMinGroup ? 0 : s.ntiles;
   char* o = reinterpret_cast<char*>(out);
-  hipError_t e = launch_bins<FMT, VAR>(x, out, s.head, nbits, W, seed, offset, group, first_bin, stats, stream);
+  hipError_t e = launch_bins<FMT, VAR>(x, out, head, nbits, W, seed, offset, group, first_bin, stats, stream);
   if (e != hipSuccess) return e;
-  if (s.ntiles) {
-    const uint64_t i0 = offset + s.head;
-    e = launch_tiles_w<FMT, VAR>(W, x + s.head, out ? o + s.head * osize : nullptr, s.ntiles, nbits, seed,
-                                 i0 / (uint64_t)(128 / W), i0, group, workspace, stream);
+  if (npairs) {
+    const uint64_t i0 = offset + head;
+    e = launch_spans_w<FMT, VAR>(W, x + head, out ? o + head * osize : nullptr, npairs, nbits, seed,
+                                 i0 / (uint64_t)(128 / W), i0, group, first_bin, workspace, stats, stream);
     if (e != hipSuccess) return e;
-    const uint64_t bin_lo = i0 / group, bin_hi = (i0 + s.ntiles * s.tile_elems - 1) / group;
-    hipLaunchKernelGGL(stats_finalize, dim3((unsigned)(bin_hi - bin_lo + 1)), dim3(64), 0, stream, workspace, i0,
-                       i0 + s.ntiles * s.tile_elems, (uint64_t)kStatsChunkTiles * s.tile_elems, stats_slots(group), group,
-                       bin_lo, first_bin, stats);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const uint64_t i_end = i0 + npairs * kStatsPairElems;
+    const uint64_t bin_lo = i0 / group, bin_hi = (i_end - 1) / group;
+    for (uint64_t at = 0; at <= bin_hi - bin_lo; at += kMaxElemsPerLaunch) {
+      const uint64_t m = bin_hi - bin_lo + 1 - at < kMaxElemsPerLaunch ? bin_hi - bin_lo + 1 - at : kMaxElemsPerLaunch;
+      hipLaunchKernelGGL(stats_finalize, dim3((unsigned)m), dim3(64), 0, stream, workspace, i0, i_end, group, bin_lo + at,
+                         first_bin, stats);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
   }
-  const uint64_t done = s.head + s.ntiles * s.tile_elems;
+  const uint64_t done = head + npairs * kStatsPairElems;
   return launch_bins<FMT, VAR>(x + done, out ? o + done * osize : nullptr, n - done, nbits, W, seed, offset + done,
                                group, first_bin, stats, stream);
 }

@@ -83,50 +83,59 @@ def test_workload4_sgd_2_27_two_steps(fbsr, oracle):
 
 
 def test_workload5_log_bins_2_30(fbsr, oracle):
-    """2^30 inputs in 4096 log-spaced bins of 2^18 over [2^-10, 2^10): statistics only
-    (out = NULL).  The oracle checks every 128th bin in full; the remaining bins are checked
-    through properties: count = 2^18, |mean error| < 1 ulp in range, SRFF's bias near
-    -2^-(N+1) and SRF / SRC near 0 away from E4M3's saturation."""
+    """2^30 inputs in 4096 log-spaced bins of 2^18 over [2^-10, 2^10): statistics only (out = NULL), the whole
+    sweep of the workload: {E4M3, bf16} x {SRFF, SRF, SRC} x N = 1..12 = 72 passes.  In every pass the oracle
+    checks 66 bins in full (every 64th bin, which takes in 13 bins of E4M3's subnormal range below 2^-6 and 3 of
+    its saturated range above 448, plus the two bins that straddle 2^-6 and 448); the remaining bins are checked
+    through properties: count = 2^18, |mean error| < 1 ulp in range, SRFF's bias near -2^-(N+1) and SRF / SRC
+    near 0 away from E4M3's saturation."""
     from paper_2504_20634_amd import workloads
     nbins, group = 4096, 1 << 18
+    straddle = [int(np.floor((np.log2(v) + 10.0) / 20.0 * nbins)) for v in (2.0 ** -6 * 1.0001, 448.0)]
+    kept = sorted(set(range(0, nbins, 64)) | set(straddle))
     xd = torch.empty(nbins * group, dtype=torch.float32, device="cuda")
     keep = {}
     slab = 64
     for b0 in range(0, nbins, slab):
         xs, edges = workloads.log_bins(nbins, group, seed=5, bins=range(b0, b0 + slab))
         xd[b0 * group:(b0 + slab) * group] = torch.from_numpy(xs).cuda()
-        for b in range(b0, b0 + slab, 128):
-            keep[b] = xs[(b - b0) * group:(b - b0 + 1) * group].copy()
+        for b in kept:
+            if b0 <= b < b0 + slab:
+                keep[b] = xs[(b - b0) * group:(b - b0 + 1) * group].copy()
         if b0 % 1024 == 0:
             print("generated bins up to %d" % (b0 + slab), flush=True)
+    assert edges[straddle[0]] <= 2.0 ** -6 < edges[straddle[0] + 1] and edges[straddle[1]] <= 448.0 < edges[straddle[1] + 1]
+    assert sum(1 for b in kept if edges[b + 1] <= 2.0 ** -6) >= 13 and sum(1 for b in kept if edges[b] > 448.0) >= 3
     ws = torch.empty(fbsr.bias_stats_workspace_bytes(nbins * group, nbins) // 8 + 1, dtype=torch.float64, device="cuda")
-    for fmt, variant, nbits in ((E4M3, SRFF, 3), (E4M3, SRC, 3), (BF16, SRF, 2), (BF16, SRFF, 12), (E4M3, SRF, 8)):
-        print("case fmt=%d variant=%d nbits=%d" % (fmt, variant, nbits), flush=True)
-        stats, _ = fbsr.fbsr_bias_stats(xd, fmt, variant, nbits, 5, 0, group, 0, nbins, workspace=ws)
-        s = stats.cpu().numpy()
+    for fmt in (E4M3, BF16):
+        for variant in (SRFF, SRF, SRC):
+            for nbits in range(1, 13):
+                print("case fmt=%d variant=%d nbits=%d" % (fmt, variant, nbits), flush=True)
+                stats, _ = fbsr.fbsr_bias_stats(xd, fmt, variant, nbits, 5, 0, group, 0, nbins, workspace=ws)
+                s = stats.cpu().numpy()
 
-        def one(b):
-            st, _ = oracle.bias_stats(keep[b], fmt, variant, nbits, 5, b * group, group, b, 1)
-            return st[0]
-        with ThreadPoolExecutor(THREADS) as pool:
-            want = np.array(list(pool.map(one, sorted(keep))))
-        assert_stats_close(s[sorted(keep)], want)
-        assert np.all(s[:, 0] == group)
-        mean_e = s[:, 2] / s[:, 0]
-        in_range = edges[1:] <= (448.0 if fmt == E4M3 else 3e38)
-        assert np.all(np.abs(mean_e[in_range]) < 1.0)
-        # A bin is far narrower than one E4M3 ulp, so a single bin sees only a slice of delta:
-        # its bias is a point on the sawtooth (SRFF in [-2^-N, 0], SRF / SRC within +-2^-(N+1)),
-        # plus sampling noise ~ 0.5 / sqrt(2^18) ~ 1e-3.  Averaged over all in-range bins the
-        # sawtooth integrates to the closed forms of Sec. III-D / III-E.
-        me = mean_e[in_range]
-        half = 2.0 ** -(nbits + 1)
-        if variant == SRFF:
-            assert np.all(me < 6e-3) and np.all(me > -2 * half - 6e-3), (me.min(), me.max())
-            assert abs(me.mean() + half) < 5e-3, me.mean()
-        else:
-            assert np.all(np.abs(me) < half + 6e-3), (me.min(), me.max())
-            assert abs(me.mean()) < 5e-3, me.mean()
+                def one(b):
+                    st, _ = oracle.bias_stats(keep[b], fmt, variant, nbits, 5, b * group, group, b, 1)
+                    return st[0]
+                with ThreadPoolExecutor(THREADS) as pool:
+                    want = np.array(list(pool.map(one, kept)))
+                assert_stats_close(s[kept], want)
+                assert np.all(s[:, 0] == group)
+                mean_e = s[:, 2] / s[:, 0]
+                in_range = edges[1:] <= (448.0 if fmt == E4M3 else 3e38)
+                assert np.all(np.abs(mean_e[in_range]) < 1.0)
+                # A bin is far narrower than one E4M3 ulp, so a single bin sees only a slice of delta:
+                # its bias is a point on the sawtooth (SRFF in [-2^-N, 0], SRF / SRC within +-2^-(N+1)),
+                # plus sampling noise ~ 0.5 / sqrt(2^18) ~ 1e-3.  Averaged over all in-range bins the
+                # sawtooth integrates to the closed forms of Sec. III-D / III-E.
+                me = mean_e[in_range]
+                half = 2.0 ** -(nbits + 1)
+                if variant == SRFF:
+                    assert np.all(me < 6e-3) and np.all(me > -2 * half - 6e-3), (me.min(), me.max())
+                    assert abs(me.mean() + half) < 5e-3, me.mean()
+                else:
+                    assert np.all(np.abs(me) < half + 6e-3), (me.min(), me.max())
+                    assert abs(me.mean()) < 5e-3, me.mean()
 
 
 def test_more_than_2_32_elements(fbsr, oracle):

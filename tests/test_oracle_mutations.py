@@ -18,7 +18,9 @@ WATCHERS = {'srf_half_term_dropped': 'exhaustive_round_up_counts and 2-0', 'srff
             'src_odd_parity': 'ties_to_odd', 'generic_overflow_tie_parity': 'overflow_and_specials',
             'generic_negative_zero_kept': 'overflow_and_specials', 'generic_subnormal_scale': 'published_value_sets',
             'generic_nan_sign_dropped': 'overflow_and_specials',
-            'qat8_step_not_in_key': 'qat_step_structure_in_binary8p4', 'qat8_nan_becomes_max': 'qat_step_structure_in_binary8p4'}
+            'qat8_step_not_in_key': 'qat_step_structure_in_binary8p4', 'qat8_nan_becomes_max': 'qat_step_structure_in_binary8p4',
+            'qat_eps_inside_the_root': 'eps_outside_the_root', 'stats_ulp_not_clamped_for_subnormals': 'exact_rational_sums',
+            'stats_sum_y_takes_the_input': 'exact_rational_sums'}
 
 MUTATIONS = [
     ("srf_half_term_dropped", "std::ldexp((double)(2 * n + 1), -(N + 1))", "std::ldexp((double)(2 * n), -(N + 1))"),
@@ -51,6 +53,10 @@ MUTATIONS = [
     ("qat8_step_not_in_key", "random_bits(seed, step, offset + j, nbits) : 0;\n      code = round_one8", "random_bits(seed, 0, offset + j, nbits) : 0;\n      code = round_one8"),
     ("qat8_nan_becomes_max", "code = g.nan_code >= 0 ? (uint32_t)g.nan_code : (uint32_t)g.max_code;", "code = (uint32_t)g.max_code;"),
     ("generic_nan_sign_dropped", "(uint32_t)g.nan_code | (g.nan_signed ? sign_code : 0u)", "(uint32_t)g.nan_code"),
+    ("qat_eps_inside_the_root", "mh / (std::sqrt(vh) + a.eps)", "mh / std::sqrt(vh + a.eps)"),
+    ("stats_ulp_not_clamped_for_subnormals", "return std::ldexp(1.0, rounding_exponent(a, f) - f.P + 1);",
+     "return std::ldexp(1.0, std::ilogb(a) - f.P + 1);"),
+    ("stats_sum_y_takes_the_input", "    s[1] += y;\n    s[2] += e;", "    s[1] += (double)x[j];\n    s[2] += e;"),
 ]
 
 

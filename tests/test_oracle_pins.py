@@ -373,6 +373,56 @@ def test_stats_sum_is_the_exact_integer_sum(oracle):
             assert abs(stats[b, 3] - np.sum((diff[bins == b] / 65536.0) ** 2)) <= 1e-9 * stats[b, 3]
 
 
+@pytest.mark.parametrize("fmt", [E4M3, E5M2])
+def test_stats_sums_are_the_exact_rational_sums(oracle, fmt):
+    """Per-bin {count, sum y, sum e, sum e^2} against sums of exact rationals: y from Eq. (1) on the
+    returned code, ulp_t(x) = 2^(max(floor(log2 |x|), 1 - B) - P + 1) from Eq. (2) with integer
+    arithmetic on x's own fraction, e = (y - x) / ulp_t(x).  Inputs cover the target's normal range,
+    its subnormal range, values far below the smallest subnormal, both signs, zero, and (E4M3) the
+    saturated range above M, where y = +-M.  sum e is a sum of multiples of one power of two that
+    fits fp64, so the oracle's fp64 accumulation must reproduce it exactly."""
+    _, K, P, B, has_inf = FORMATS[fmt]
+    rng = np.random.default_rng(40 + fmt)
+    group = 500
+    M = float(MAX_FINITE[fmt])
+    parts = [rng.uniform(2.0 ** (1 - B), M, group),                                        # normal range
+             rng.uniform(2.0 ** (2 - B - P), 2.0 ** (1 - B), group),                        # subnormal range
+             rng.uniform(2.0 ** (-B - P - 20), 2.0 ** (2 - B - P), group),                  # below the smallest subnormal
+             -np.exp(rng.uniform(np.log(2.0 ** (-B - P - 3)), np.log(M), group)),           # negative, every range
+             np.concatenate([np.zeros(5), -np.zeros(5), rng.uniform(2.0 ** -B, 2.0 ** (3 - B), group - 10)])]
+    if not has_inf:
+        parts.append(rng.uniform(M, 8 * M, group) * np.where(rng.integers(0, 2, group) == 1, -1.0, 1.0))   # saturates to +-M
+    x = np.concatenate(parts).astype(np.float32)
+    nbins = len(parts)
+    for variant, nbits in ((SRFF, 2), (SRF, 3), (SRC, 3), (RNE, 0), (SRC, 8)):
+        stats, out = oracle.bias_stats(x, fmt, variant, nbits, seed=6, offset=0, group=group, first_bin=0, nbins=nbins,
+                                       want_out=True)
+        for b in range(nbins):
+            sy = se = see = Fraction(0)
+            for j in range(b * group, (b + 1) * group):
+                xf = f32_fraction(x[j])
+                code = int(out[j])
+                mag = code_value(code & ((1 << (K - 1)) - 1), fmt)
+                assert mag is not None
+                y = -mag if code >> (K - 1) else mag
+                a = abs(xf)
+                lg = (a.numerator.bit_length() - a.denominator.bit_length()) if a else 1 - B
+                if a and Fraction(2) ** lg > a:
+                    lg -= 1
+                ulp = Fraction(2) ** (max(lg, 1 - B) - P + 1)
+                e = (y - xf) / ulp
+                sy += y
+                se += e
+                see += e * e
+            assert stats[b, 0] == group
+            assert stats[b, 1] == float(sy) or abs(stats[b, 1] - float(sy)) <= 1e-13 * abs(float(sy)), (fmt, variant, b)
+            if b < 2 or b >= 4:      # multiples of 2^-(24-P) (2^-24 in the saturated range) below 2^53 of them: exact
+                assert stats[b, 2] == float(se), (fmt, variant, nbits, b, stats[b, 2], float(se))
+            else:                    # deep inputs: single errors carry more than 53 bits, fp64 rounds each of them
+                assert abs(stats[b, 2] - float(se)) <= 1e-12 * max(abs(float(se)), 1.0), (fmt, variant, nbits, b)
+            assert abs(stats[b, 3] - float(see)) <= 1e-12 * float(see) + 1e-300, (fmt, variant, nbits, b)
+
+
 def test_sgd_small_updates(oracle):
     """Updates far below one ulp (Sec. IV: nearest-even stagnates, SRFF drifts): RNE, SRF and
     SRC leave the weights alone; SRFF loses 2^-(N+1) ulp of |w| per step on average, because the
@@ -532,6 +582,34 @@ def test_qat_step_tracks_library_adamw(oracle, fmt, hyper):
         assert np.all(np.abs(w_new - target) <= slack), np.max(np.abs(w_new - target) / slack)
         # restart the reference moments from the 16-bit ones so rounding differences do not pile up
         m_ref, v_ref = m_got, v_got
+
+
+def test_qat_step_adds_eps_outside_the_root(oracle):
+    """Where AdamW's eps sits: u = -lr (m / c1) / (sqrt(v / c2) + eps), not sqrt(v / c2 + eps).  With a zero gradient
+    and a zero second moment the denominator is eps itself, so the two placements differ by 1 / sqrt(eps); every
+    number below is a power of two, the library's fp32 step is exact and lands on E4M3 values, and the oracle must
+    return exactly those (a representable sum is a fixed point of every variant)."""
+    lr, b1, b2, eps, wd = 0.125, 0.5, 0.75, 2.0 ** -4, 0.0
+    w = np.array([1.0, -1.0, 2.0, 0.5, 4.0, -8.0], dtype=np.float32)
+    m = np.array([0.25, -0.25, 0.125, 0.5, -0.5, 0.5], dtype=np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(w.copy()))
+    opt = torch.optim.AdamW([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+    p.grad = torch.zeros(w.size)
+    opt.state[p] = {"step": torch.tensor(0.0), "exp_avg": torch.from_numpy(m.copy()), "exp_avg_sq": torch.zeros(w.size)}
+    opt.step()
+    target = p.detach().numpy()
+    # the library's own numbers: m <- m / 2, denominator eps, step lr / c1 * m' / eps = m * 2
+    assert np.array_equal(target, w - 2.0 * m)
+    vals, codes = finite_table(E4M3)
+    lookup = {float(v): c for v, c in zip(vals, codes)}
+    w8 = np.array([lookup[abs(float(v))] | (0x80 if v < 0 else 0) for v in w], dtype=np.uint8)
+    want8 = np.array([lookup[abs(float(v))] | (0x80 if v < 0 else 0) for v in target], dtype=np.uint8)
+    g16 = np.zeros(w.size, np.uint16)
+    for variant, nbits in ((RNE, 0), (SRFF, 3), (SRF, 3), (SRC, 3)):
+        got, m16, v16 = oracle.qat_adamw_step(w8, g16, _bf16_codes(m), np.zeros(w.size, np.uint16), E4M3,
+                                             (lr, b1, b2, eps, wd, 1 - b1, 1 - b2), variant, nbits, seed=3, step=1)
+        assert np.array_equal(got, want8), (variant, got, want8)
+        assert np.array_equal(_bf16_values(m16), m * np.float32(0.5)) and not v16.any()
 
 
 def test_qat_step_structure(oracle):
