@@ -260,12 +260,6 @@ int fbsr_qat_adamw_step_format8(void* w8, const void* g16, void* m16, void* v16,
                                 const fbsr_adamw* p, int variant, int nbits, uint64_t seed, uint64_t step,
                                 uint64_t offset, void* stream);
 
-/* Measurement aid, not part of the method: streams n floats through the rounding kernels' launch shape with no
- * arithmetic (out[j] = the top byte of x[j]'s pattern): every input byte read once, one byte written per element.
- * Its throughput is the practical ceiling for fbsr_round's 4 : 1 read : write traffic on the part at hand.
- * n must be a multiple of 2048, x 16-byte and out 4-byte aligned (else FBSR_EINVAL / FBSR_EALIGN). */
-int fbsr_probe_stream41(const float* x, void* out, uint64_t n, void* stream);
-
 /* Static description of a status code. */
 const char* fbsr_strerror(int status);
 

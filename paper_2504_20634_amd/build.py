@@ -33,7 +33,7 @@ def stale():
         return True
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS]
-    deps.append(os.path.join(os.path.dirname(_HERE), "include", "fbsr.h"))
+    deps += [os.path.join(os.path.dirname(_HERE), "include", h) for h in ("fbsr.h", "fbsr_measure.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include "../../include/fbsr.h"
+#include "../../include/fbsr_measure.h"
 #include "fbsr_launch.h"
 
 namespace {

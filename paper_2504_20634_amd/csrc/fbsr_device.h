@@ -543,7 +543,8 @@ template <int FMT> struct FastLimits {
 };
 
 // POSITIVE: the caller knows that no pattern has its sign bit set (then nothing has to be carried over into rs).
-template <int FMT, int VAR, bool MIXED, bool POSITIVE = false>
+// SUB_ONLY (fp8, with MIXED): the caller knows that every |x| lies below 2^(1-B), so the subnormal grid alone places it.
+template <int FMT, int VAR, bool MIXED, bool POSITIVE = false, bool SUB_ONLY = false>
 __device__ __forceinline__ FastRound round_fast(uint32_t bits, uint32_t n, const Addends& a) {
   typedef Fx<FMT> F;
   constexpr uint32_t kFracMask = (1u << F::FRAC) - 1u;
@@ -552,7 +553,9 @@ __device__ __forceinline__ FastRound round_fast(uint32_t bits, uint32_t n, const
     r0 = bits;   // the sign rides along in bit 31: no carry reaches it while |x| <= M
   } else {
     constexpr uint32_t kRebias = 0u - (F::Q << (23 + F::S));
-    if constexpr (MIXED) {
+    if constexpr (MIXED && SUB_ONLY) {
+      r0 = (uint32_t)(fabsf(__uint_as_float(bits)) * F::SUB_SCALE);   // below 2^(FRAC + P - 1): no conversion out of range
+    } else if constexpr (MIXED) {
       // |x| is split at the smallest normal value 2^(1-B): what lies above it is placed by the re-biased pattern
       // (of max(|x|, 2^(1-B))), what lies below it on the fixed subnormal grid (of min(|x|, 2^(1-B)), a product
       // below 2^32); the position is the sum of the two less the one they both hold at the split point

@@ -38,6 +38,12 @@ __device__ __forceinline__ double inv_ulp(uint32_t bits) {
 // A lane's share of a span is 64 elements.  64 values of E4M3 (multiples of 2^-9 up to 448) or of binary8p4
 // (multiples of 2^-10 up to 224) sum to a multiple of that step below 2^24 steps: exact in fp32 in any order, so
 // the sum of y runs there and is widened when the wave closes a bin.
+// E4M3 has no infinity: every |x| > M becomes +-M (the library's reading of Sec. II for a saturating format), and the
+// error of such an element is a plain integer too.  With |x| = m 2^(e - 23), m the 24-bit significand and e >= 8, and
+// ulp_t(x) = 2^(e - 3):  e 2^20 = (M - |x|) / ulp_t(x) 2^20 = (7 << (29 - e)) - m, for e <= 29.
+template <int FMT> struct kSaturates { static constexpr bool value = FMT == kE4M3; };
+constexpr uint32_t kSaturatedLimit = (uint32_t)(127 + 30) << 23;   // patterns below 2^30
+
 template <int FMT> struct SumYInFp32 { static constexpr bool value = FMT == kE4M3 || FMT == kP4; };
 
 // End of a bin in global indices, saturating (group may be as large as 2^62, so (bin + 1) * group can pass 2^64).
@@ -89,6 +95,8 @@ __device__ __forceinline__ uint64_t read_row_bits(const uint4* strip, int e0) {
 struct LaneSums {
   int32_t se_i, neg_i;   // sum of e_int ^ s and of s, s = -1 for a negative x and 0 otherwise: their difference is the signed sum
   long long see_i;
+  int32_t se20_i;        // the same two sums for the saturated path, whose errors come in units of 2^-20 (signed already)
+  long long see20_i;
   float sy32;           // sum y in fp32 for the formats whose 64 values per lane add exactly there
   double sy, se, see;
 };
@@ -150,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
     }
   };
 
-  LaneSums cur = {0, 0, 0, 0.0f, 0.0, 0.0, 0.0};
+  LaneSums cur = {0, 0, 0, 0, 0, 0.0f, 0.0, 0.0, 0.0};
   int slot = my_pairs > 0 ? (int)(span_lo / group - bin_first) : 0;
   uint64_t next_bin = my_pairs > 0 ? group - span_lo % group : 0;   // span-relative index at which the next bin starts
 
@@ -158,13 +166,19 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
   auto close_bin = [&]() {
     constexpr double kUnit = 1.0 / (double)((uint64_t)1 << F::FRAC);
     const double t0 = wave_total(cur.sy + (double)cur.sy32);
-    const double t1 = wave_total(cur.se + (double)(cur.se_i - cur.neg_i) * kUnit);
-    const double t2 = wave_total(cur.see + (double)cur.see_i * (kUnit * kUnit));
+    constexpr double kUnit20 = 1.0 / (double)(1 << 20);
+    double se = cur.se + (double)(cur.se_i - cur.neg_i) * kUnit, see = cur.see + (double)cur.see_i * (kUnit * kUnit);
+    if constexpr (kSaturates<FMT>::value) {
+      se += (double)cur.se20_i * kUnit20;
+      see += (double)cur.see20_i * (kUnit20 * kUnit20);
+    }
+    const double t1 = wave_total(se);
+    const double t2 = wave_total(see);
     if (lane == 0) {
       part[wave][slot][0] = t0; part[wave][slot][1] = t1; part[wave][slot][2] = t2;
     }
     slot += 1;
-    cur = {0, 0, 0, 0.0f, 0.0, 0.0, 0.0};
+    cur = {0, 0, 0, 0, 0, 0.0f, 0.0, 0.0, 0.0};
   };
 
   const float* xs = x + (span_lo - i0);
@@ -267,8 +281,10 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
     //   kSigned    the same for |x|, either sign;
     //   kMixed     (fp8) as kSigned, with zeros and target-subnormal values that the 24-bit code space places exactly;
     //   kPositiveMixed  (fp8) as kMixed when no pattern has its sign bit set;
+    //   kPositiveSubnormal  (fp8) as kPositiveMixed when every value lies below the normal range;
     //   kGeneral   everything else.
-    enum : int { kPositive, kSigned, kMixed, kPositiveMixed, kGeneral };
+    //   kSaturated / kPositiveSaturated  (E4M3) every |x| above M and below 2^30: y = +-M, the error an integer again.
+    enum : int { kPositive, kSigned, kMixed, kPositiveMixed, kPositiveSubnormal, kSaturated, kPositiveSaturated, kGeneral };
     int path = kGeneral;
     if constexpr (!MANY) {
       uint32_t top = 0, bottom = 0xFFFFFFFFu;
@@ -284,10 +300,17 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
       else ok = !__any(top > F::U_MAXFIN);
       bool ok_mixed = false;   // positive, <= M, nothing between zero and the smallest exactly placed pattern (zero itself excluded too)
       if constexpr (F::kIsFp8) ok_mixed = !ok && !__any(top > F::U_MAXFIN || bottom < FastLimits<FMT>::U_DEEP);
+      bool ok_saturated = false;
+      if constexpr (kSaturates<FMT>::value) ok_saturated = !ok && !ok_mixed && !__any(bottom <= F::U_MAXFIN || top >= kSaturatedLimit);
       if (ok) {
         path = kPositive;
       } else if (ok_mixed) {
         path = kPositiveMixed;
+        if constexpr (F::kIsFp8) {
+          if (!__any(top >= F::U_SUB)) path = kPositiveSubnormal;
+        }
+      } else if (ok_saturated) {
+        path = kPositiveSaturated;
       } else if constexpr (F::kIsFp8) {
         // (|x| pattern - pattern of 2^(1-B)) * 2 as an unsigned number: small for target-normal |x| <= M, huge otherwise
         uint32_t m = 0;
@@ -309,6 +332,9 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
               lo = min(lo, u - 1u);
             }
           if (!__any(hi > F::U_MAXFIN || lo < FastLimits<FMT>::U_DEEP - 1u)) path = kMixed;
+          if constexpr (kSaturates<FMT>::value) {
+            if (!__any(lo < F::U_MAXFIN || hi >= kSaturatedLimit)) path = kSaturated;   // lo = smallest |pattern| - 1
+          }
         }
       } else {
         // largest |x|: among the negative patterns the unsigned maximum (top), among the others the signed one
@@ -327,15 +353,15 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
     }
 
     // the three integer paths share everything but the flavour of round_fast and the handling of the sign
-    auto integer_pair = [&](auto mixed_tag, auto positive_tag) {
-      constexpr bool MIXED = decltype(mixed_tag)::value, POSITIVE = decltype(positive_tag)::value;
+    auto integer_pair = [&](auto mixed_tag, auto positive_tag, auto sub_only_tag) {
+      constexpr bool MIXED = decltype(mixed_tag)::value, POSITIVE = decltype(positive_tag)::value, SUB_ONLY = decltype(sub_only_tag)::value;
       FastRound fr[kRows][4];
 #pragma unroll
       for (int k = 0; k < kRows; ++k) {
         uint32_t n[4];
         row_draws(p, k, n);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fr[k][j] = round_fast<FMT, VAR, MIXED, POSITIVE>(b[k][j], n[j], a);
+        for (int j = 0; j < 4; ++j) fr[k][j] = round_fast<FMT, VAR, MIXED, POSITIVE, SUB_ONLY>(b[k][j], n[j], a);
       }
       if (out != nullptr) {
         const uint64_t orow = (span_lo - i0) / 4 + (uint64_t)(p * (kStatsPairElems / 4) + lane);   // units of 4 elements
@@ -391,10 +417,59 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
               }
           });
     };
-    if (path == kPositive) integer_pair(std::false_type{}, std::true_type{});
-    else if (path == kSigned) integer_pair(std::false_type{}, std::false_type{});
-    else if (path == kPositiveMixed) integer_pair(std::integral_constant<bool, F::kIsFp8>{}, std::true_type{});
-    else integer_pair(std::integral_constant<bool, F::kIsFp8>{}, std::false_type{});
+    if constexpr (kSaturates<FMT>::value) {
+      if (path == kSaturated || path == kPositiveSaturated) {
+        int32_t e20[kRows][4];
+#pragma unroll
+        for (int k = 0; k < kRows; ++k)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t u = b[k][j] & 0x7FFFFFFFu;
+            const uint32_t m24 = (u & 0x007FFFFFu) | 0x00800000u;
+            const int32_t mag = (int32_t)(7u << (156u - (u >> 23))) - (int32_t)m24;   // (M - |x|) / ulp_t(x) 2^20 <= 0
+            const int32_t sgn = (int32_t)b[k][j] >> 31;
+            e20[k][j] = (mag ^ sgn) - sgn;                                            // e carries the sign of x
+          }
+        if (out != nullptr) {
+          const uint64_t orow = (span_lo - i0) / 4 + (uint64_t)(p * (kStatsPairElems / 4) + lane);
+#pragma unroll
+          for (int k = 0; k < kRows; ++k) {
+            const uint32_t signs = pack4_fp8<FMT>(b[k][0], b[k][1], b[k][2], b[k][3]) & 0x80808080u;
+            reinterpret_cast<uint32_t*>(out)[orow + (uint64_t)(k * 64)] = signs | 0x7E7E7E7Eu;
+          }
+        }
+        auto add_one = [&](int32_t e, uint32_t bits, bool in) {
+          cur.se20_i += in ? e : 0;
+          cur.see20_i += (long long)(in ? e : 0) * (long long)(in ? e : 0);
+          const float y = __uint_as_float((bits & 0x80000000u) | F::U_MAXFIN);
+          cur.sy32 += in ? y : 0.0f;
+        };
+        over_bins(
+            p * kStatsPairElems, kStatsPairElems,
+            [&]() {
+#pragma unroll
+              for (int k = 0; k < kRows; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) add_one(e20[k][j], b[k][j], true);
+            },
+            [&](int first, int last) {
+#pragma unroll
+              for (int k = 0; k < kRows; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                  const int e = k * 256 + 4 * lane + j;
+                  add_one(e20[k][j], b[k][j], e >= first && e < last);
+                }
+            });
+        return;
+      }
+    }
+    typedef std::integral_constant<bool, F::kIsFp8> fp8_tag;
+    if (path == kPositive) integer_pair(std::false_type{}, std::true_type{}, std::false_type{});
+    else if (path == kSigned) integer_pair(std::false_type{}, std::false_type{}, std::false_type{});
+    else if (path == kPositiveMixed) integer_pair(fp8_tag{}, std::true_type{}, std::false_type{});
+    else if (path == kPositiveSubnormal) integer_pair(fp8_tag{}, std::true_type{}, fp8_tag{});
+    else integer_pair(fp8_tag{}, std::false_type{}, std::false_type{});
   };
 
   if (my_pairs > 0) {

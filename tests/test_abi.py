@@ -14,15 +14,22 @@ HEADER = os.path.join(ROOT, "include", "fbsr.h")
 @pytest.fixture(scope="module")
 def L():
     from paper_2504_20634_amd import binding, build
-    if not os.path.exists(binding.LIB_PATH):
+    if os.environ.get("FBSR_ABI_LIB"):      # a host-sanitized build of the argument checks (tests/test_sanitizers.py)
+        binding.LIB_PATH = os.environ["FBSR_ABI_LIB"]
+    elif not os.path.exists(binding.LIB_PATH):
         build.build()
     return binding.lib()
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(fbsr_[a-z_0-9]+)\s*\(", text)))
+    """Every function declared in any header under include/ (the product interface and the measurement aids)."""
+    names = set()
+    for header in sorted(os.listdir(os.path.dirname(HEADER))):
+        if header.endswith(".h"):
+            text = open(os.path.join(os.path.dirname(HEADER), header)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(fbsr_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(L):
