@@ -224,9 +224,11 @@ struct Format8 {
 };
 
 // desc: {K, P, B, max_code, inf_code, nan_code, nan_signed, neg_zero}.
-bool get_format8(const int32_t* d, Format8* g) {
+// max_width: 8 for the entry points whose codes are bytes, 16 for those with 16-bit codes (the format model of
+// Sec. II, Eq. (1) is the same at every width; B may then reach 127).
+bool get_format8(const int32_t* d, Format8* g, int max_width = 8) {
   const int K = d[0], P = d[1], B = d[2];
-  if (K < 2 || K > 8 || P < 1 || P > K - 1 || B < 0 || B > 96) return false;
+  if (K < 2 || K > max_width || P < 1 || P > K - 1 || B < 0 || B > (max_width > 8 ? 127 : 96)) return false;
   const int mag_top = (1 << (K - 1)) - 1;
   const int max_code = d[3], inf_code = d[4], nan_code = d[5];
   if (max_code < (1 << (P - 1)) || max_code > mag_top) return false;        // M is a normal value
@@ -708,6 +710,37 @@ double oracle_decode_format8(uint32_t code, const int32_t* desc) {
   Format8 g;
   if (!get_format8(desc, &g)) return std::numeric_limits<double>::quiet_NaN();
   return decode8(code, g);
+}
+
+// The same three with codes of up to 16 bits (K <= 16).
+int oracle_format16_check(const int32_t* desc) {
+  Format8 g;
+  return get_format8(desc, &g, 16) ? 0 : 1;
+}
+
+double oracle_decode_format16(uint32_t code, const int32_t* desc) {
+  Format8 g;
+  if (!get_format8(desc, &g, 16)) return std::numeric_limits<double>::quiet_NaN();
+  return decode8(code, g);
+}
+
+uint32_t oracle_round_format16_with_n(float x, const int32_t* desc, int variant, int nbits, uint64_t n) {
+  Format8 g;
+  if (!get_format8(desc, &g, 16) || !variant8_ok(variant, nbits)) return 0xFFFFFFFFu;
+  return round_one8(x, g, variant, nbits, n);
+}
+
+// oracle_round_format8 for a format of up to 16 bits: out holds one code per 16-bit word (the bits above K zero).
+int oracle_round_format16(const void* x, int src, uint16_t* out, uint64_t n, const int32_t* desc, int variant,
+                          int nbits, uint64_t seed, uint64_t offset) {
+  Format8 g;
+  if (!get_format8(desc, &g, 16) || !variant8_ok(variant, nbits) || src < 0 || src > 2) return 1;
+  for (uint64_t j = 0; j < n; ++j) {
+    const float v = src == 2 ? ((const float*)x)[j] : widen16(((const uint16_t*)x)[j], src);
+    const uint64_t r = variant_draws(variant) ? random_bits(seed, 0, offset + j, nbits) : 0;
+    out[j] = (uint16_t)round_one8(v, g, variant, nbits, r);
+  }
+  return 0;
 }
 
 // One element with an explicit n.  Returns the code, or 0xFFFFFFFF on invalid arguments.

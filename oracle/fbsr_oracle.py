@@ -80,6 +80,14 @@ def lib():
         L.oracle_round_format8_with_n.restype = u32
         L.oracle_round_format8.argtypes = [vp, i32, vp, u64, vp, i32, i32, u64, u64]
         L.oracle_round_format8.restype = i32
+        L.oracle_format16_check.argtypes = [vp]
+        L.oracle_format16_check.restype = i32
+        L.oracle_decode_format16.argtypes = [u32, vp]
+        L.oracle_decode_format16.restype = ctypes.c_double
+        L.oracle_round_format16_with_n.argtypes = [f32, vp, i32, i32, u64]
+        L.oracle_round_format16_with_n.restype = u32
+        L.oracle_round_format16.argtypes = [vp, i32, vp, u64, vp, i32, i32, u64, u64]
+        L.oracle_round_format16.restype = i32
         L.oracle_sgd_update.argtypes = [vp, vp, u64, f32, i32, i32, u64, u64, u64]
         L.oracle_sgd_update.restype = i32
         L.oracle_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp]
@@ -201,6 +209,31 @@ def round_format8(x, src, desc, variant, nbits, seed, offset=0):
     rc = lib().oracle_round_format8(_ptr(x), src, _ptr(out), x.size, _ptr(_desc(desc)), variant, nbits, seed, offset)
     if rc != 0:
         raise ValueError("oracle_round_format8: status %d" % rc)
+    return out
+
+
+def format16_check(desc):
+    return lib().oracle_format16_check(_ptr(_desc(desc))) == 0
+
+
+def decode_format16(code, desc):
+    return float(lib().oracle_decode_format16(int(code), _ptr(_desc(desc))))
+
+
+def round_format16_with_n(x, desc, variant, nbits, n):
+    code = lib().oracle_round_format16_with_n(float(np.float32(x)), _ptr(_desc(desc)), variant, nbits, n)
+    if code == 0xFFFFFFFF:
+        raise ValueError("oracle_round_format16_with_n: bad arguments")
+    return int(code)
+
+
+def round_format16(x, src, desc, variant, nbits, seed, offset=0):
+    """round_format8 for a format of up to 16 bits: one code per uint16."""
+    x = np.ascontiguousarray(x, dtype=np.float32 if src == FROM_FP32 else np.uint16)
+    out = np.empty(x.size, dtype=np.uint16)
+    rc = lib().oracle_round_format16(_ptr(x), src, _ptr(out), x.size, _ptr(_desc(desc)), variant, nbits, seed, offset)
+    if rc != 0:
+        raise ValueError("oracle_round_format16: status %d" % rc)
     return out
 
 

@@ -50,8 +50,11 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
                                               uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
   constexpr uint32_t MUL_A = 0xD2511F53u, MUL_B = 0xCD9E8D57u;
   constexpr uint32_t WEYL_A = 0x9E3779B9u, WEYL_B = 0xBB67AE85u;
+#ifndef FBSR_PROBE_ROUNDS
+#define FBSR_PROBE_ROUNDS 10
+#endif
 #pragma unroll
-  for (int r = 0; r < 10; ++r) {
+  for (int r = 0; r < FBSR_PROBE_ROUNDS; ++r) {
     const uint64_t pa = (uint64_t)MUL_A * c0;
     const uint64_t pb = (uint64_t)MUL_B * c2;
     const uint32_t t0 = (uint32_t)(pb >> 32) ^ c1 ^ (k0 + WEYL_A * (uint32_t)r);

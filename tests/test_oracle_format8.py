@@ -44,10 +44,16 @@ def value_of(code, d):
     return (1 + Fraction(t) * pow2(1 - P)) * pow2(e - B)
 
 
+_TABLES = {}
+
+
 def table(d):
-    vals = [value_of(c, d) for c in range(d[3] + 1)]
-    assert vals == sorted(vals)
-    return vals
+    key = tuple(int(v) for v in d)
+    if key not in _TABLES:
+        vals = [value_of(c, d) for c in range(d[3] + 1)]
+        assert vals == sorted(vals)
+        _TABLES[key] = vals
+    return _TABLES[key]
 
 
 def position(a, d):
