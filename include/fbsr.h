@@ -230,7 +230,8 @@ typedef struct {
 
 /* Fills *out with a published format.  Names: "ocp_e4m3", "ocp_e5m2" (OCP 8-bit floating point; the same
  * formats as FBSR_FMT_E4M3 / FBSR_FMT_E5M2), "ocp_e3m2", "ocp_e2m3", "ocp_e2m1" (OCP microscaling element
- * types: no NaN, no infinity), "p3109_binary8p1" .. "p3109_binary8p7" (IEEE WG P3109 interim report:
+ * types: no NaN, no infinity), "ieee_binary16" (IEEE 754 binary16, for fbsr_round_format16 only),
+ * "p3109_binary8p1" .. "p3109_binary8p7" (IEEE WG P3109 interim report:
  * bias 2^(7-P), 0x80 the only NaN, 0x7F / 0xFF the infinities, no negative zero; binary8p4 is the format
  * Sec. IV trains in).  Host-only.  Returns FBSR_OK, or FBSR_EINVAL for an unknown name or a null pointer. */
 int fbsr_format8_named(const char* name, fbsr_format8* out);
@@ -248,6 +249,18 @@ int fbsr_format8_check(const fbsr_format8* fmt);
  * Errors: FBSR_EINVAL (bad descriptor / src / variant / nbits, null pointer), FBSR_EALIGN, FBSR_EDEVICE. */
 int fbsr_round_format8(const void* x, int src, void* out, uint64_t n, const fbsr_format8* fmt, int variant,
                        int nbits, uint64_t seed, uint64_t offset, void* stream);
+
+/* The same for formats of up to 16 bits (IEEE binary16 and any other (K, P, B; M) with K <= 16): one code per
+ * 16-bit word of out (bits above K zero).  The descriptor is the struct above with width 2..16 and bias 0..127;
+ * because an fp32 source drops 24 - P bits and the kernels keep 32 - K fraction bits beside a code, the precision must be
+ * at least K - 8 (binary16: P = 11 >= 8).  bf16 itself (whose M + ulp(M) is not a finite fp32 value) is served by
+ * fbsr_round, not by a descriptor.  nbits at most min(FBSR_MAX_NBITS, 30 - K) (14 for a 16-bit format): with
+ * P >= K - 8 a target-normal fp32 input drops at most 32 - K bits, so every nbits from 24 - P on (13 for binary16)
+ * already is classical SR.  "ieee_binary16" is a name fbsr_format8_named knows.
+ * out: n 16-bit codes (device, written, 2-byte aligned).  Everything else as fbsr_round_format8. */
+int fbsr_format16_check(const fbsr_format8* fmt);
+int fbsr_round_format16(const void* x, int src, void* out, uint64_t n, const fbsr_format8* fmt, int variant,
+                        int nbits, uint64_t seed, uint64_t offset, void* stream);
 
 /* fbsr_qat_adamw_step with the 8-bit weights in a generic format (Sec. IV trains in P3109 binary8p4 with bf16
  * updates and 3 random bits) and any variant FBSR_RNE .. FBSR_RNA.  The arithmetic is that of

@@ -20,7 +20,7 @@ MAX_NBITS = 16            # the fused updates (SGD, QAT steps)
 MAX_NBITS_ROUND = 24      # every other entry point
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2", FMT_BINARY8P4: "binary8p4"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
-EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_static", "fbsr_bias_stats_workspace_bytes",
+EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_round_format16", "fbsr_format16_check", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_static", "fbsr_bias_stats_workspace_bytes",
            "fbsr_probe_stream41", "fbsr_strerror", "fbsr_version")
 
 
@@ -65,6 +65,10 @@ def lib():
         L.fbsr_format8_check.restype = i32
         L.fbsr_round_format8.argtypes = [vp, i32, vp, u64, vp, i32, i32, u64, u64, vp]
         L.fbsr_round_format8.restype = i32
+        L.fbsr_round_format16.argtypes = [vp, i32, vp, u64, vp, i32, i32, u64, u64, vp]
+        L.fbsr_round_format16.restype = i32
+        L.fbsr_format16_check.argtypes = [vp]
+        L.fbsr_format16_check.restype = i32
         L.fbsr_qat_adamw_step_format8.argtypes = [vp, vp, vp, vp, u64, vp, vp, i32, i32, u64, u64, u64, vp]
         L.fbsr_qat_adamw_step_format8.restype = i32
         L.fbsr_probe_stream41.argtypes = [vp, vp, u64, vp]
@@ -166,6 +170,27 @@ def fbsr_round_format8(x, src, fmt, variant, nbits, seed, offset=0, out=None, st
     f = _format8(fmt)
     _check(lib().fbsr_round_format8(x.data_ptr(), src, out.data_ptr(), n, ctypes.byref(f), variant, nbits, seed, offset,
                                     _stream_handle(stream)), "fbsr_round_format8")
+    return out
+
+
+def format16_check(fmt):
+    """True when the descriptor is acceptable to fbsr_round_format16 (K <= 16, P >= K - 8).  Host-only."""
+    return lib().fbsr_format16_check(ctypes.byref(_format8(fmt))) == OK
+
+
+def fbsr_round_format16(x, src, fmt, variant, nbits, seed, offset=0, out=None, stream=None):
+    """fbsr_round_format8 for formats of up to 16 bits: one code per uint16."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.element_size() == (4 if src == FROM_FP32 else 2)
+    if src == FROM_FP32:
+        assert x.dtype == torch.float32
+    n = x.numel()
+    if out is None:
+        out = torch.empty(n, dtype=torch.uint16, device=x.device)
+    assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.element_size() == 2
+    f = _format8(fmt)
+    _check(lib().fbsr_round_format16(x.data_ptr(), src, out.data_ptr(), n, ctypes.byref(f), variant, nbits, seed, offset,
+                                     _stream_handle(stream)), "fbsr_round_format16")
     return out
 
 

@@ -25,9 +25,13 @@ bool misaligned(const void* p, uintptr_t a) { return reinterpret_cast<uintptr_t>
 uint64_t code_bytes(int fmt) { return fmt == FBSR_FMT_BF16 ? 2 : 1; }
 
 // Checks a generic-format descriptor and reduces it to the constants of the code-space arithmetic.
-bool derive_format8(const fbsr_format8& d, fbsr::Fmt8* f) {
+// max_width 8: codes are bytes and the code space has 24 fraction bits.  max_width 16: codes are 16-bit words and the
+// code space has 32 - K fraction bits, which must hold every bit an fp32 value drops (24 - P), so P >= K - 8.
+bool derive_format8(const fbsr_format8& d, fbsr::Fmt8* f, int max_width = 8) {
   const int K = d.width, P = d.precision, B = d.bias;
-  if (K < 2 || K > 8 || P < 1 || P >= K || B < 0 || B > 96) return false;
+  if (K < 2 || K > max_width || P < 1 || P >= K || B < 0 || B > (max_width > 8 ? 127 : 96)) return false;
+  const int frac = max_width > 8 ? 32 - K : 24;
+  if (frac < 24 - P) return false;
   const int sign_bit = 1 << (K - 1), mag_top = sign_bit - 1;
   if (d.max_code > mag_top || d.max_code < (1 << (P - 1))) return false;   // M must be a normal value
   const bool has_inf = d.inf_code != -1;
@@ -45,14 +49,16 @@ bool derive_format8(const fbsr_format8& d, fbsr::Fmt8* f) {
   const int e_max = d.max_code >> (P - 1), t_max = d.max_code & ((1 << (P - 1)) - 1);
   if (e_max - B > 126) return false;   // M + ulp(M) has to be a finite fp32 value
   const uint32_t ulp = 1u << (24 - P);   // one target ulp of a normal value, in fp32 pattern units
-  f->shift_p = (uint32_t)P;
+  f->frac = (uint32_t)frac;
+  f->shift_p = (uint32_t)(frac - (24 - P));
+  f->sub_exp = frac - 2 + B + P;
   f->rebias = (uint32_t)(127 - B) << 23;
   f->u_max = ((uint32_t)(e_max + 127 - B) << 23) | ((uint32_t)t_max * ulp);
   f->u_clamp = has_inf ? f->u_max + 3u * (ulp >> 2) : f->u_max;
   f->u_sub = (uint32_t)(128 - B) << 23;
-  f->sub_scale = ldexpf(1.0f, 22 + B + P);
+  f->sub_scale = frac == 24 ? ldexpf(1.0f, 22 + B + P) : 0.0f;   // the 16-bit path scales by sub_exp instead
   const uint32_t m_odd = P == 1 ? 1u : (uint32_t)(d.max_code & 1);   // parity of M's significand
-  f->det_add = (1u << 23) - 1u + m_odd;
+  f->det_add = (1u << (frac - 1)) - 1u + m_odd;
   f->max_code = (uint32_t)d.max_code;
   f->over_code = (uint32_t)(has_inf ? d.inf_code : d.max_code);
   f->nan_code = (uint32_t)(has_nan ? d.nan_code : d.max_code);
@@ -60,7 +66,7 @@ bool derive_format8(const fbsr_format8& d, fbsr::Fmt8* f) {
   f->sign_bit = (uint32_t)sign_bit;
   f->sign_shift = (uint32_t)(32 - K);
   f->zero_sign = d.neg_zero != 0 ? (uint32_t)sign_bit : 0u;
-  f->unit_lsb = P == 1 ? (1u << 24) : 0u;
+  f->unit_lsb = P == 1 ? (1u << frac) : 0u;
   return true;
 }
 
@@ -87,13 +93,13 @@ void decode_table8(const fbsr_format8& d, fbsr::Table8* t) {
   }
 }
 
-// The addend constants of a rounding mode in a code space with 24 fraction bits.
-bool derive_mode8(int variant, int nbits, int max_nbits, fbsr::Mode8* m) {
+// The addend constants of a rounding mode in a code space with `frac` fraction bits.
+bool derive_mode8(int variant, int nbits, int max_nbits, fbsr::Mode8* m, uint32_t frac = 24) {
   const bool draws = variant == FBSR_SRFF || variant == FBSR_SRF || variant == FBSR_SRC || variant == FBSR_SRC_TIES_ODD;
   if (variant < FBSR_RNE || variant > FBSR_RNA) return false;
   if (draws && (nbits < 1 || nbits > max_nbits)) return false;
   m->nbits = draws ? (uint32_t)nbits : 0u;
-  m->shift = 24u - m->nbits;
+  m->shift = frac - m->nbits;
   m->srf = variant == FBSR_SRF;
   const uint32_t half = m->shift >= 1u ? 1u << (m->shift - 1) : 0u;   // half of the last kept place
   m->tie_xor = (variant == FBSR_SRC_TIES_ODD || variant == FBSR_RNO) ? 1u : 0u;
@@ -114,6 +120,7 @@ const NamedFormat8 kNamed[] = {
     {"ocp_e3m2", {6, 3, 3, 0x1F, -1, -1, 0, 1}},
     {"ocp_e2m3", {6, 4, 1, 0x1F, -1, -1, 0, 1}},
     {"ocp_e2m1", {4, 2, 1, 0x07, -1, -1, 0, 1}},
+    {"ieee_binary16", {16, 11, 15, 0x7BFF, 0x7C00, 0x7E00, 1, 1}},
 };
 
 }  // namespace
@@ -227,6 +234,30 @@ int fbsr_round_format8(const void* x, int src, void* out, uint64_t n, const fbsr
   if (misaligned(x, src == FBSR_FROM_FP32 ? 4 : 2)) return FBSR_EALIGN;
   const hipError_t e = fbsr::launch_round_format8(x, src, reinterpret_cast<uint8_t*>(out), n, f, m, seed, offset,
                                                   reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
+int fbsr_format16_check(const fbsr_format8* fmt) {
+  fbsr::Fmt8 f;
+  return fmt != nullptr && derive_format8(*fmt, &f, 16) ? FBSR_OK : FBSR_EINVAL;
+}
+
+int fbsr_round_format16(const void* x, int src, void* out, uint64_t n, const fbsr_format8* fmt, int variant, int nbits,
+                        uint64_t seed, uint64_t offset, void* stream) {
+  fbsr::Fmt8 f;
+  fbsr::Mode8 m;
+  if (fmt == nullptr || !derive_format8(*fmt, &f, 16)) return FBSR_EINVAL;
+  // the last place of n must stay two bits above the end of the code space: one for the half step / the tie position of
+  // the inner rounding, one for the sticky bit of a truncated target-subnormal input
+  const int max_nbits = (int)f.frac - 2 < FBSR_MAX_NBITS ? (int)f.frac - 2 : FBSR_MAX_NBITS;
+  if (!derive_mode8(variant, nbits, max_nbits, &m, f.frac)) return FBSR_EINVAL;
+  if (src != FBSR_FROM_BF16 && src != FBSR_FROM_FP16 && src != FBSR_FROM_FP32) return FBSR_EINVAL;
+  if (n > fbsr::kMaxElems || offset > UINT64_MAX - n) return FBSR_EINVAL;
+  if (n == 0) return FBSR_OK;
+  if (x == nullptr || out == nullptr) return FBSR_EINVAL;
+  if (misaligned(x, src == FBSR_FROM_FP32 ? 4 : 2) || misaligned(out, 2)) return FBSR_EALIGN;
+  const hipError_t e = fbsr::launch_round_format16(x, src, reinterpret_cast<uint16_t*>(out), n, f, m, seed, offset,
+                                                   reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 

@@ -594,7 +594,7 @@ __device__ __forceinline__ float fast_value(uint32_t rs) {
 // A generic target format and a rounding mode, both reduced on the host to the constants the
 // code-space arithmetic needs (computed on the host from the caller's descriptor).
 struct Fmt8 {
-  uint32_t shift_p;     // P: a target-normal pattern maps to (u - rebias) << P
+  uint32_t shift_p;     // frac - (24 - P): a target-normal pattern maps to (u - rebias) << shift_p (P when frac = 24)
   uint32_t rebias;      // (127 - B) << 23
   uint32_t u_max;       // fp32 pattern of M
   uint32_t u_clamp;     // |x| is clamped to this pattern: M when saturating, M + 3/4 ulp(M) with an infinity
@@ -609,6 +609,8 @@ struct Fmt8 {
   uint32_t sign_shift;  // 32 - K: (pattern >> sign_shift) & sign_bit is the code's sign
   uint32_t zero_sign;   // the sign bit if the format has -0, else 0
   uint32_t unit_lsb;    // 1 << 24 when P = 1 (the significand's last place is the implicit one), else 0
+  uint32_t frac;        // fraction bits of the code space: 24 for K <= 8; 32 - K for the 16-bit-code entry point
+  int32_t sub_exp;      // frac - 2 + B + P: a target-subnormal |x| maps to trunc(|x| * 2^sub_exp)
 };
 
 // The value of every byte as a code of the format (Eq. (1); infinities, and NaN for the NaN code and for
@@ -619,7 +621,7 @@ struct Table8 {
 
 struct Mode8 {
   uint32_t nbits;       // N; 0 for the deterministic modes
-  uint32_t shift;       // 24 - N
+  uint32_t shift;       // frac - N
   uint32_t fixed;       // the part of the addend that does not depend on the element
   uint32_t tie_xor;     // inner rounding: 0 ties-to-even, 1 ties-to-odd
   bool ties;            // the mode has an inner round-to-nearest (RNE, RNO, both SRC)
@@ -639,12 +641,16 @@ __device__ __forceinline__ uint32_t finish8(uint32_t mag, uint32_t bits, const F
 
 // One source pattern -> the output byte.  n < 2^N is the element's random integer (0 when the mode
 // draws none).  CHECKED = false may be used only when the pattern is known not to be a NaN.
-template <bool TIES, bool CHECKED>
+// WIDE = false: the code space has 24 fraction bits (K <= 8).  WIDE = true: f.frac of them (32 - K, for codes of up to
+// 16 bits), and the subnormal scale, which may pass fp32's range as a factor, is applied to the exponent.
+template <bool TIES, bool CHECKED, bool WIDE = false>
 __device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m) {
   const uint32_t u = bits & 0x7FFFFFFFu;
   const uint32_t uc = u < f.u_clamp ? u : f.u_clamp;
   const uint32_t normal = (uc - f.rebias) << f.shift_p;
-  const float scaled = __uint_as_float(uc) * f.sub_scale;   // exact: power-of-two scale (used below 2^(1-B) only)
+  float scaled;   // exact: power-of-two scale (used below 2^(1-B) only)
+  if constexpr (WIDE) scaled = __builtin_amdgcn_ldexpf(__uint_as_float(uc), f.sub_exp);
+  else scaled = __uint_as_float(uc) * f.sub_scale;
   const uint32_t sub = (uint32_t)scaled;                     // truncation toward zero
   const bool is_sub = u < f.u_sub;
   uint32_t r0 = is_sub ? sub : normal;
@@ -659,7 +665,8 @@ __device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8
     add += ((parity_of >> m.shift) & 1u) ^ m.tie_xor;
   }
   add = u > f.u_max ? f.det_add : add;   // |x| > M: no randomness (Sec. II)
-  return finish8<CHECKED>((r0 + add) >> 24, bits, f);
+  if constexpr (WIDE) return finish8<CHECKED>((r0 + add) >> f.frac, bits, f);
+  else return finish8<CHECKED>((r0 + add) >> 24, bits, f);
 }
 
 // round8 for N = 17 .. 24 (the per-element kernel; any pattern): see round_pattern_wide.
@@ -670,6 +677,21 @@ __device__ __forceinline__ uint32_t round8_wide(uint32_t bits, uint32_t n, const
   const WideCode c = wide_code(u, f.rebias, f.shift_p, f.u_sub, bp);
   const uint32_t up = wide_round_up(c, n, m.nbits, m.srf, m.ties, m.tie_xor);
   return finish8<false>(c.whole + up, bits, f);
+}
+
+// Four 16-bit codes of a generic format as two words (element 0 in the low half of the first).
+template <bool TIES>
+__device__ __forceinline__ uint2 round4_codes16(const uint32_t (&b)[4], const uint32_t (&n)[4], bool checked, const Fmt8& f,
+                                                const Mode8& m) {
+  uint32_t c[4];
+  if (checked) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c[j] = round8<TIES, true, true>(b[j], n[j], f, m);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c[j] = round8<TIES, false, true>(b[j], n[j], f, m);
+  }
+  return make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
 }
 
 __device__ __forceinline__ uint32_t pack4_bytes(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {

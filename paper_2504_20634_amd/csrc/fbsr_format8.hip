@@ -1,5 +1,6 @@
-// fbsr_format8.hip -- kernels behind fbsr_round_format8: few-bit stochastic rounding of fp32 / bf16 /
-// binary16 values to ANY format (K, P, B; M) of Sec. II, Eq. (1) with K <= 8, plus the deterministic
+// fbsr_format8.hip -- kernels behind fbsr_round_format8 and fbsr_round_format16: few-bit stochastic rounding of
+// fp32 / bf16 / binary16 values to ANY format (K, P, B; M) of Sec. II, Eq. (1) with K <= 8 (one code per byte) or
+// K <= 16 (one code per 16-bit word; the code space then has 32 - K fraction bits), plus the deterministic
 // modes of Sec. II-A (nearest with ties to even, to odd, away from zero) and Eq. (7) with either tie
 // rule for its inner rounding (Sec. III-F).
 //
@@ -17,8 +18,9 @@ namespace fbsr {
 // One workgroup per 2048-element tile, one wave per 512 elements.  fp32 source: two rows of 256
 // elements per wave, a lane owns 4 consecutive floats per row (16-byte load, 4-byte store).  16-bit
 // sources: a lane owns 8 consecutive codes (16-byte load, 8-byte store).  W = 0: the mode draws no bits.
-template <int SRC, bool TIES, int W>
-__global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict__ xin, uint8_t* __restrict__ out, Fmt8 f,
+// WIDE: 16-bit codes (a lane then stores 8 bytes per row of an fp32 source, 16 bytes from a 16-bit source).
+template <int SRC, bool TIES, int W, bool WIDE>
+__global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict__ xin, void* __restrict__ out, Fmt8 f,
                                                           Mode8 m, uint64_t seed, uint64_t blk0, uint32_t xcd_lg) {
   constexpr int WW = W == 0 ? 1 : W;
   typedef WgTile<WW> T;
@@ -51,8 +53,13 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
                              __float_as_uint(v[k].w)};
       const uint32_t n4[4] = {W == 0 ? 0u : slot_bits<WW>(rb, 0, m.nbits), W == 0 ? 0u : slot_bits<WW>(rb, 1, m.nbits),
                               W == 0 ? 0u : slot_bits<WW>(rb, 2, m.nbits), W == 0 ? 0u : slot_bits<WW>(rb, 3, m.nbits)};
-      __builtin_nontemporal_store(round4_bytes<TIES>(b, n4, checked, f, m),
-                                  reinterpret_cast<uint32_t*>(out) + row0 + (uint64_t)(k * 64));
+      if constexpr (WIDE) {
+        const uint2 c = round4_codes16<TIES>(b, n4, checked, f, m);
+        __builtin_nontemporal_store((uint64_t)c.x | ((uint64_t)c.y << 32), reinterpret_cast<uint64_t*>(out) + row0 + (uint64_t)(k * 64));
+      } else {
+        __builtin_nontemporal_store(round4_bytes<TIES>(b, n4, checked, f, m),
+                                    reinterpret_cast<uint32_t*>(out) + row0 + (uint64_t)(k * 64));
+      }
     }
   } else {
     const uint16_t* x = reinterpret_cast<const uint16_t*>(xin);
@@ -77,15 +84,22 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
     if constexpr (W != 0) read_wg_bits8<WW>(strip, e0, m.nbits, n);
     const uint32_t b_lo[4] = {b[0], b[1], b[2], b[3]}, b_hi[4] = {b[4], b[5], b[6], b[7]};
     const uint32_t n_lo[4] = {n[0], n[1], n[2], n[3]}, n_hi[4] = {n[4], n[5], n[6], n[7]};
-    const uint32_t lo = round4_bytes<TIES>(b_lo, n_lo, checked, f, m);
-    const uint32_t hi = round4_bytes<TIES>(b_hi, n_hi, checked, f, m);
-    __builtin_nontemporal_store((uint64_t)lo | ((uint64_t)hi << 32), reinterpret_cast<uint64_t*>(out + g0));
+    if constexpr (WIDE) {
+      const uint2 lo = round4_codes16<TIES>(b_lo, n_lo, checked, f, m), hi = round4_codes16<TIES>(b_hi, n_hi, checked, f, m);
+      u32x4 c;
+      c.x = lo.x; c.y = lo.y; c.z = hi.x; c.w = hi.y;
+      __builtin_nontemporal_store(c, reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + g0));
+    } else {
+      const uint32_t lo = round4_bytes<TIES>(b_lo, n_lo, checked, f, m);
+      const uint32_t hi = round4_bytes<TIES>(b_hi, n_hi, checked, f, m);
+      __builtin_nontemporal_store((uint64_t)lo | ((uint64_t)hi << 32), reinterpret_cast<uint64_t*>(reinterpret_cast<uint8_t*>(out) + g0));
+    }
   }
 }
 
 // One thread per element: any alignment, any offset, ragged heads and tails.  W = 0: no bits.
-template <int SRC, bool TIES>
-__global__ __launch_bounds__(kThreads) void format8_elems(const void* __restrict__ xin, uint8_t* __restrict__ out, uint64_t n,
+template <int SRC, bool TIES, bool WIDE>
+__global__ __launch_bounds__(kThreads) void format8_elems(const void* __restrict__ xin, void* __restrict__ out, uint64_t n,
                                                           Fmt8 f, Mode8 m, int W, int log2_per_block, uint64_t seed,
                                                           uint64_t offset) {
   const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -95,16 +109,21 @@ __global__ __launch_bounds__(kThreads) void format8_elems(const void* __restrict
   else bits = widen16<SRC>(reinterpret_cast<const uint16_t*>(xin)[j]);
   uint32_t rnd = 0;
   if (W != 0) rnd = element_bits(offset + j, log2_per_block, W, m.nbits, seed, 0);
-  out[j] = (uint8_t)(m.nbits > (uint32_t)kMaxTileNbits ? round8_wide(bits, rnd, f, m) : round8<TIES, true>(bits, rnd, f, m));
+  if constexpr (WIDE) {   // at most 16 random bits here
+    reinterpret_cast<uint16_t*>(out)[j] = (uint16_t)round8<TIES, true, true>(bits, rnd, f, m);
+  } else {
+    reinterpret_cast<uint8_t*>(out)[j] =
+        (uint8_t)(m.nbits > (uint32_t)kMaxTileNbits ? round8_wide(bits, rnd, f, m) : round8<TIES, true>(bits, rnd, f, m));
+  }
 }
 
 namespace {
 
-template <int SRC, bool TIES>
-hipError_t launch_tiles_w(int W, const void* x, uint8_t* out, uint64_t ntiles, const Fmt8& f, const Mode8& m, uint64_t seed,
+template <int SRC, bool TIES, bool WIDE>
+hipError_t launch_tiles_w(int W, const void* x, void* out, uint64_t ntiles, const Fmt8& f, const Mode8& m, uint64_t seed,
                           uint64_t blk0, hipStream_t stream) {
   const dim3 grid((unsigned)ntiles), block(kThreads);
-#define FBSR_F8_LAUNCH(WW) hipLaunchKernelGGL((format8_tiles<SRC, TIES, WW>), grid, block, 0, stream, x, out, f, m, seed, blk0, kXcdLgFormat8)
+#define FBSR_F8_LAUNCH(WW) hipLaunchKernelGGL((format8_tiles<SRC, TIES, WW, WIDE>), grid, block, 0, stream, x, out, f, m, seed, blk0, kXcdLgFormat8)
   switch (W) {
     case 0: FBSR_F8_LAUNCH(0); break;
     case 1: FBSR_F8_LAUNCH(1); break;
@@ -117,46 +136,59 @@ hipError_t launch_tiles_w(int W, const void* x, uint8_t* out, uint64_t ntiles, c
   return hipGetLastError();
 }
 
-template <int SRC, bool TIES>
-hipError_t run(const void* xin, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
+template <int SRC, bool TIES, bool WIDE>
+hipError_t run(const void* xin, void* outv, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
                hipStream_t stream) {
   constexpr uint64_t isize = SRC == kSrcFP32 ? 4 : 2;
-  constexpr uint64_t oalign = SRC == kSrcFP32 ? 4 : 8;
+  constexpr uint64_t osize = WIDE ? 2 : 1;
+  constexpr uint64_t oalign = (SRC == kSrcFP32 ? 4 : 8) * osize;
   const char* x = reinterpret_cast<const char*>(xin);
+  char* out = reinterpret_cast<char*>(outv);
   const int W = m.nbits ? slot_width((int)m.nbits) : 0;
   Split s = split_range(n, offset, W ? W : 8, W == 0, reinterpret_cast<uintptr_t>(x), isize, 16,
-                        reinterpret_cast<uintptr_t>(out), 1, oalign);
+                        reinterpret_cast<uintptr_t>(out), osize, oalign);
   if (m.nbits > (uint32_t)kMaxTileNbits) s.head = s.ntiles = 0;   // more than 16 bits: the per-element kernel throughout
   return run_split(
       s, n,
       [&](uint64_t first, uint64_t count) {
-        hipLaunchKernelGGL((format8_elems<SRC, TIES>), elems_grid(count), dim3(kThreads), 0, stream,
-                           reinterpret_cast<const void*>(x + first * isize), out + first, count, f, m, W, W ? log2_of(128 / W) : 0,
-                           seed, offset + first);
+        hipLaunchKernelGGL((format8_elems<SRC, TIES, WIDE>), elems_grid(count), dim3(kThreads), 0, stream,
+                           reinterpret_cast<const void*>(x + first * isize), reinterpret_cast<void*>(out + first * osize), count, f, m,
+                           W, W ? log2_of(128 / W) : 0, seed, offset + first);
         return hipGetLastError();
       },
       [&](uint64_t first, uint64_t count) {
-        return launch_tiles_w<SRC, TIES>(W, x + first * isize, out + first, count, f, m, seed,
-                                         W ? (offset + first) / (uint64_t)(128 / W) : 0, stream);
+        return launch_tiles_w<SRC, TIES, WIDE>(W, x + first * isize, out + first * osize, count, f, m, seed,
+                                               W ? (offset + first) / (uint64_t)(128 / W) : 0, stream);
       });
 }
 
-template <int SRC>
-hipError_t run_t(const void* x, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
+template <int SRC, bool WIDE>
+hipError_t run_t(const void* x, void* out, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
                  hipStream_t stream) {
-  if (m.ties) return run<SRC, true>(x, out, n, f, m, seed, offset, stream);
-  return run<SRC, false>(x, out, n, f, m, seed, offset, stream);
+  if (m.ties) return run<SRC, true, WIDE>(x, out, n, f, m, seed, offset, stream);
+  return run<SRC, false, WIDE>(x, out, n, f, m, seed, offset, stream);
+}
+
+template <bool WIDE>
+hipError_t run_s(const void* x, int src, void* out, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
+                 hipStream_t stream) {
+  switch (src) {
+    case kSrcBF16: return run_t<kSrcBF16, WIDE>(x, out, n, f, m, seed, offset, stream);
+    case kSrcFP16: return run_t<kSrcFP16, WIDE>(x, out, n, f, m, seed, offset, stream);
+    default: return run_t<kSrcFP32, WIDE>(x, out, n, f, m, seed, offset, stream);
+  }
 }
 
 }  // namespace
 
 hipError_t launch_round_format8(const void* x, int src, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m,
                                 uint64_t seed, uint64_t offset, hipStream_t stream) {
-  switch (src) {
-    case kSrcBF16: return run_t<kSrcBF16>(x, out, n, f, m, seed, offset, stream);
-    case kSrcFP16: return run_t<kSrcFP16>(x, out, n, f, m, seed, offset, stream);
-    default: return run_t<kSrcFP32>(x, out, n, f, m, seed, offset, stream);
-  }
+  return run_s<false>(x, src, out, n, f, m, seed, offset, stream);
+}
+
+hipError_t launch_round_format16(const void* x, int src, uint16_t* out, uint64_t n, const Fmt8& f, const Mode8& m,
+                                 uint64_t seed, uint64_t offset, hipStream_t stream) {
+  return run_s<true>(x, src, out, n, f, m, seed, offset, stream);
 }
 
 }  // namespace fbsr

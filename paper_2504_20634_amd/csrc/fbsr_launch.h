@@ -138,6 +138,9 @@ hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uin
 hipError_t launch_round_format8(const void* x, int src, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m,
                                 uint64_t seed, uint64_t offset, hipStream_t stream);
 
+hipError_t launch_round_format16(const void* x, int src, uint16_t* out, uint64_t n, const Fmt8& f, const Mode8& m,
+                                 uint64_t seed, uint64_t offset, hipStream_t stream);
+
 // Geometry of the statistics kernel: a workgroup takes a chunk of kStatsChunkElems consecutive elements, each of
 // its waves a span of kStatsSpanElems of them, walked in pairs of rows (kStatsPairElems = 512 elements: eight per
 // lane).  Bins must hold at least kStatsMinGroup elements on this path, so a chunk touches at most

@@ -124,6 +124,19 @@ def test_argument_validation_happens_on_the_host(L):
     assert L.fbsr_bias_stats(p(good), None, 8, 0, 1, 2, 0, 0, 0, 0, 2, p(good), p(good), 1 << 20, None) == EINVAL
     assert L.fbsr_bias_stats(p(good), None, 8, 0, 1, 2, 0, 0, 4, 0, 1, p(good), p(good), 1 << 20, None) == ERANGE
     assert L.fbsr_bias_stats(p(good), None, 8, 0, 1, 2, 0, 0, 4, 1, 4, p(good), p(good), 1 << 20, None) == ERANGE
+    # generic formats of up to 16 bits
+    b16 = (ctypes.c_int32 * 8)(16, 11, 15, 0x7BFF, 0x7C00, 0x7E00, 1, 1)
+    assert L.fbsr_format16_check(b16) == OK and L.fbsr_format8_check(b16) == EINVAL
+    assert L.fbsr_format16_check((ctypes.c_int32 * 8)(16, 7, 15, 0x7BFF, -1, -1, 0, 1)) == EINVAL      # P < K - 8
+    assert L.fbsr_format16_check((ctypes.c_int32 * 8)(17, 11, 15, 0x7BFF, -1, -1, 0, 1)) == EINVAL
+    assert L.fbsr_format16_check(None) == EINVAL
+    assert L.fbsr_round_format16(None, 2, None, 0, b16, 1, 3, 0, 0, None) == OK
+    assert L.fbsr_round_format16(p(good), 2, p(good), 8, b16, 1, 15, 0, 0, None) == EINVAL      # nbits <= 30 - K
+    assert L.fbsr_round_format16(p(good), 3, p(good), 8, b16, 1, 3, 0, 0, None) == EINVAL
+    assert L.fbsr_round_format16(p(good), 2, p(good + 1), 8, b16, 1, 3, 0, 0, None) == EALIGN
+    assert L.fbsr_round_format16(p(good + 2), 2, p(good), 8, b16, 1, 3, 0, 0, None) == EALIGN
+    assert L.fbsr_round_format16(p(good), 2, None, 8, b16, 1, 3, 0, 0, None) == EINVAL
+    assert L.fbsr_round_format8(p(good), 2, p(good), 8, b16, 1, 3, 0, 0, None) == EINVAL
     # the entry point with the built-in workspace: same checks, and a size limit of its own
     assert L.fbsr_bias_stats_static(None, None, 0, 0, 1, 2, 0, 0, 1, 0, 1, None, None) == OK
     assert L.fbsr_bias_stats_static(p(good), None, 8, 0, 1, 2, 0, 0, 0, 0, 2, p(good), None) == EINVAL
