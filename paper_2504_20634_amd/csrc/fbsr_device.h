@@ -456,7 +456,10 @@ __device__ __forceinline__ HwAddends make_hw_addends(int nbits) {
 
 // Four fp32 patterns and their random integers -> four packed fp8 codes (element 0 in the low
 // byte).  None of the patterns may be a NaN.
-template <int FMT, int VAR>
+// MANY: nbits may exceed 24 - P, the number of bits a target-normal input drops.  The grid of SRC's inner rounding is
+// then finer than some inputs' own last place; those inputs (|x| >= C) already lie on it and must be left alone, because
+// the sum |x| + C would round them in a higher binade.
+template <int FMT, int VAR, bool MANY = false>
 __device__ __forceinline__ uint32_t round4_fp8_hw(const uint32_t (&bits)[4], const uint32_t (&n)[4], const HwAddends& h) {
   typedef Fx<FMT> F;
   static_assert(F::kIsFp8 && VAR != kRNE, "hardware path: fp8 targets, stochastic variants");
@@ -480,7 +483,8 @@ __device__ __forceinline__ uint32_t round4_fp8_hw(const uint32_t (&bits)[4], con
       const uint32_t ef = __float_as_uint(x) & 0x7F800000u;   // after the clamp
       const uint32_t c_bits = (ef > kSubField ? ef : kSubField) + h.grid_exp;
       const float c = __uint_as_float(c_bits);
-      const float t = (fabsf(x) + c) - c;
+      float t = (fabsf(x) + c) - c;
+      if constexpr (MANY) t = fabsf(x) < c ? t : fabsf(x);
       const float pre = __uint_as_float((__float_as_uint(t) & 0x7FFFFFFFu) | (bits[j] & 0x80000000u));
       x = over ? x : pre;
     }

@@ -24,28 +24,11 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
     fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
     __syncthreads();
   }
-  if constexpr (W == 32) {
-    // more than 16 random bits: one 32-bit slot per element, every element on the wide path
-#pragma unroll
-    for (int k = 0; k < kRows; ++k) {
-      const uint4 q = strip[(wave * kWaveElems + k * 256 + 4 * lane) / 4];   // the row's four slots: one Philox block
-      const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z), __float_as_uint(v[k].w)};
-      const uint32_t s4[4] = {q.x, q.y, q.z, q.w};
-      uint32_t r[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        r[j] = round_pattern_wide<FMT, VAR>(b[j], __builtin_amdgcn_ubfe(s4[j], 0u, (uint32_t)nbits), (uint32_t)nbits);
-      const uint64_t row = row0 + (uint64_t)(k * 64);
-      if constexpr (Fx<FMT>::kIsFp8) {
-        __builtin_nontemporal_store(pack4_fp8<FMT>(r[0], r[1], r[2], r[3]), reinterpret_cast<uint32_t*>(out) + row);
-      } else {
-        const uint64_t pv = (uint64_t)pack2_bf16(r[0], r[1]) | ((uint64_t)pack2_bf16(r[2], r[3]) << 32);
-        __builtin_nontemporal_store(pv, reinterpret_cast<uint64_t*>(out) + row);
-      }
-    }
-    return;
-  }
-  const Addends a = make_addends<FMT, VAR>(nbits);
+  // W = 32: more than 16 random bits, one 32-bit slot per element (a row's four slots are one Philox block).  The fp8
+  // targets still go through the hardware converts, which take a random operand of 32 bits; only a wave that holds a
+  // NaN, and bf16, take the integer arithmetic, in its flavour for many bits.
+  constexpr bool MANY = W == 32;
+  const Addends a = make_addends<FMT, VAR>(MANY ? kMaxTileNbits : nbits);
   HwAddends hw = {0, 0, 0, 0};
   if constexpr (Fx<FMT>::kIsFp8 && VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
   uint32_t umax = 0;
@@ -55,30 +38,53 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
                          max(__float_as_uint(v[k].z) & 0x7FFFFFFFu, __float_as_uint(v[k].w) & 0x7FFFFFFFu)));
   }
   const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: NaN (bf16: also |x| > M) is rare
+  // The hardware converts add the top D = 24 - P bits of the random operand to the first D bits below the kept ones and
+  // drop whatever lies further down.  That is the exact rule for up to D random bits (D - 1 with SRF's half step) on any
+  // input, and for any number of bits on a target-normal input, which has no bits further down.  With more bits a
+  // wave that holds a non-zero value below the normal range takes the integer arithmetic.
+  bool hw_ok = true;
+  if constexpr (MANY && Fx<FMT>::kIsFp8) {
+    if (nbits > 24 - Fx<FMT>::P - (VAR == kSRF ? 1 : 0)) {   // uniform over the launch
+      uint32_t lowest = 0xFFFFFFFFu;                          // smallest |pattern| - 1 (zero wraps to the top)
+#pragma unroll
+      for (int k = 0; k < kRows; ++k) {
+        lowest = min(lowest, min(min((__float_as_uint(v[k].x) & 0x7FFFFFFFu) - 1u, (__float_as_uint(v[k].y) & 0x7FFFFFFFu) - 1u),
+                                 min((__float_as_uint(v[k].z) & 0x7FFFFFFFu) - 1u, (__float_as_uint(v[k].w) & 0x7FFFFFFFu) - 1u)));
+      }
+      hw_ok = !__any(lowest < Fx<FMT>::U_SUB - 1u);
+    }
+  }
 #pragma unroll
   for (int k = 0; k < kRows; ++k) {
-    uint64_t rb = 0;
-    if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip, wave, lane, k);
+    uint32_t n4[4] = {0, 0, 0, 0};
+    if constexpr (MANY) {
+      const uint4 q = strip[(wave * kWaveElems + k * 256 + 4 * lane) / 4];   // the row's four slots
+      n4[0] = __builtin_amdgcn_ubfe(q.x, 0u, (uint32_t)nbits); n4[1] = __builtin_amdgcn_ubfe(q.y, 0u, (uint32_t)nbits);
+      n4[2] = __builtin_amdgcn_ubfe(q.z, 0u, (uint32_t)nbits); n4[3] = __builtin_amdgcn_ubfe(q.w, 0u, (uint32_t)nbits);
+    } else if constexpr (VAR != kRNE) {
+      const uint64_t rb = read_wg_row_bits<W>(strip, wave, lane, k);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) n4[j] = slot_bits<W>(rb, j, a.nbits);
+    }
     const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
                            __float_as_uint(v[k].w)};
     const uint64_t row = row0 + (uint64_t)(k * 64);
     if constexpr (Fx<FMT>::kIsFp8 && VAR != kRNE) {
-      if (!checked) {   // no NaN among the wave's elements: the hardware converts apply
-        const uint32_t n4[4] = {slot_bits<W>(rb, 0, a.nbits), slot_bits<W>(rb, 1, a.nbits), slot_bits<W>(rb, 2, a.nbits),
-                                slot_bits<W>(rb, 3, a.nbits)};
-        __builtin_nontemporal_store(round4_fp8_hw<FMT, VAR>(b, n4, hw), reinterpret_cast<uint32_t*>(out) + row);
+      if (!checked && hw_ok) {   // no NaN among the wave's elements: the hardware converts apply
+        __builtin_nontemporal_store(round4_fp8_hw<FMT, VAR, MANY>(b, n4, hw), reinterpret_cast<uint32_t*>(out) + row);
         continue;
       }
     }
     uint32_t r[4];
-    if (checked) {
+    if constexpr (MANY) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        r[j] = round_pattern<FMT, VAR, true>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
+      for (int j = 0; j < 4; ++j) r[j] = round_pattern_wide<FMT, VAR>(b[j], n4[j], (uint32_t)nbits);
+    } else if (checked) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, true>(b[j], n4[j], a);
     } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        r[j] = round_pattern<FMT, VAR, false>(b[j], VAR == kRNE ? 0u : slot_bits<W>(rb, j, a.nbits), a);
+      for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, false>(b[j], n4[j], a);
     }
     if constexpr (Fx<FMT>::kIsFp8) {
       __builtin_nontemporal_store(pack4_fp8<FMT>(r[0], r[1], r[2], r[3]), reinterpret_cast<uint32_t*>(out) + row);
