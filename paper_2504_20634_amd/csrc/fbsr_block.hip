@@ -45,7 +45,8 @@ __global__ __launch_bounds__(kThreads) void block_tiles(const float* __restrict_
     fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
     __syncthreads();
   }
-  const Addends a = make_addends<FMT, VAR>(nbits);
+  constexpr bool MANY = W == 32;   // more than 16 random bits: 32-bit slots
+  const Addends a = make_addends<FMT, VAR>(MANY ? kMaxTileNbits : nbits);
   HwAddends hw = {0, 0, 0, 0};
   if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
 #pragma unroll
@@ -64,13 +65,28 @@ __global__ __launch_bounds__(kThreads) void block_tiles(const float* __restrict_
     uint32_t b[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) b[j] = special ? 0u : __float_as_uint(__uint_as_float(raw[j]) * mult);
-    uint64_t rb = 0;
-    if constexpr (VAR != kRNE) rb = read_wg_row_bits<W>(strip, wave, lane, k);
     uint32_t packed;
-    if constexpr (VAR != kRNE) {   // no NaN can reach the rounding: the hardware converts always apply
-      const uint32_t n4[4] = {slot_bits<W>(rb, 0, a.nbits), slot_bits<W>(rb, 1, a.nbits), slot_bits<W>(rb, 2, a.nbits),
-                              slot_bits<W>(rb, 3, a.nbits)};
-      packed = round4_fp8_hw<FMT, VAR>(b, n4, hw);
+    if constexpr (VAR != kRNE) {   // no NaN can reach the rounding: the hardware converts apply ...
+      uint32_t n4[4];
+      row_draws4<W>(strip, wave, lane, k, (uint32_t)nbits, n4);
+      bool hw_ok = true;           // ... unless there are more random bits than they take on a value below the normal range
+      if constexpr (MANY) {
+        if (hw_needs_normal_inputs<FMT, VAR>(nbits)) {
+          const uint32_t lowest = min(min(magnitude_less_one(b[0]), magnitude_less_one(b[1])),
+                                      min(magnitude_less_one(b[2]), magnitude_less_one(b[3])));
+          hw_ok = !__any(lowest < F::U_SUB - 1u);
+        }
+      }
+      if (hw_ok) {
+        packed = round4_fp8_hw<FMT, VAR, MANY>(b, n4, hw);
+      } else {
+        uint32_t r[4] = {0, 0, 0, 0};
+        if constexpr (MANY) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) r[j] = round_pattern_wide<FMT, VAR>(b[j], n4[j], (uint32_t)nbits);
+        }
+        packed = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
+      }
     } else {
       uint32_t r[4];
 #pragma unroll
@@ -131,7 +147,8 @@ hipError_t launch_tiles_w(int W, const float* x, uint8_t* out, uint8_t* scales, 
       case 2: FBSR_BLOCK_LAUNCH(2); break;
       case 4: FBSR_BLOCK_LAUNCH(4); break;
       case 8: FBSR_BLOCK_LAUNCH(8); break;
-      default: FBSR_BLOCK_LAUNCH(16); break;
+      case 16: FBSR_BLOCK_LAUNCH(16); break;
+      default: FBSR_BLOCK_LAUNCH(32); break;
     }
   }
 #undef FBSR_BLOCK_LAUNCH
@@ -164,9 +181,8 @@ hipError_t run(const float* x, uint8_t* out, uint8_t* scales, uint64_t n, int nb
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
   const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
                               reinterpret_cast<uintptr_t>(out), 1, 4);
-  // the tile kernel's blocks of 32 must be the call's blocks: it is used only when no head is cut off -- and with at
-  // most 16 random bits per element (more go through the per-block kernel and its wide rounding)
-  const uint64_t ntiles = s.head == 0 && (VAR == kRNE || nbits <= kMaxTileNbits) ? s.ntiles : 0;
+  // the tile kernel's blocks of 32 must be the call's blocks: it is used only when no head is cut off
+  const uint64_t ntiles = s.head == 0 ? s.ntiles : 0;
   for (uint64_t t0 = 0; t0 < ntiles; t0 += kMaxTilesPerLaunch) {
     const uint64_t cnt = ntiles - t0 < kMaxTilesPerLaunch ? ntiles - t0 : kMaxTilesPerLaunch;
     const uint64_t e0 = t0 * s.tile_elems;

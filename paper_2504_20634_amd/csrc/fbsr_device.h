@@ -390,7 +390,12 @@ __device__ __forceinline__ uint64_t read_wg_row_bits(const uint4* strip, int wav
 template <int W>
 __device__ __forceinline__ void read_wg_bits8(const uint4* strip, int e0, uint32_t nbits, uint32_t (&n)[8]) {
   const unsigned char* base = reinterpret_cast<const unsigned char*>(strip);
-  if constexpr (W == 16) {
+  if constexpr (W == 32) {   // more than 16 random bits: two Philox blocks
+    const uint4 q0 = strip[e0 / 4], q1 = strip[e0 / 4 + 1];
+    const uint32_t w[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) n[j] = __builtin_amdgcn_ubfe(w[j], 0u, nbits);
+  } else if constexpr (W == 16) {
     const uint4 q = *reinterpret_cast<const uint4*>(base + e0 * 2);
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
@@ -410,6 +415,24 @@ __device__ __forceinline__ void read_wg_bits8(const uint4* strip, int e0, uint32
   }
 }
 
+// The random integers of this lane's four elements in row k of its wave, for every slot width: with 32-bit slots
+// (more than 16 random bits) the row's four slots are one Philox block.
+template <int W>
+__device__ __forceinline__ void row_draws4(const uint4* strip, int wave, int lane, int k, uint32_t nbits, uint32_t (&n)[4]);
+
+// With more than 16 random bits: true when the bit count passes what the hardware converts apply exactly to every input
+// (they add the top D = 24 - P bits of the random operand to the first D bits below the kept ones and drop what lies
+// further down: exact for up to D random bits, D - 1 with SRF's half step, on any input; exact for any count on a
+// target-normal input, which has no bits further down).  Then a wave may use them only if it holds no non-zero value
+// below the target's normal range.
+template <int FMT, int VAR>
+__device__ __forceinline__ bool hw_needs_normal_inputs(int nbits) {
+  return nbits > 24 - Fx<FMT>::P - (VAR == kSRF ? 1 : 0);
+}
+
+// For that test: |pattern| - 1, which sends zero to the top of the range.
+__device__ __forceinline__ uint32_t magnitude_less_one(uint32_t bits) { return (bits & 0x7FFFFFFFu) - 1u; }
+
 template <int W>
 __device__ __forceinline__ uint32_t slot_bits(uint64_t row_bits, int j, uint32_t nbits) {
   if constexpr (W == 16) {
@@ -417,6 +440,19 @@ __device__ __forceinline__ uint32_t slot_bits(uint64_t row_bits, int j, uint32_t
     return __builtin_amdgcn_ubfe(w, (uint32_t)(16 * (j & 1)), nbits);
   } else {
     return __builtin_amdgcn_ubfe((uint32_t)row_bits, (uint32_t)(j * W), nbits);
+  }
+}
+
+template <int W>
+__device__ __forceinline__ void row_draws4(const uint4* strip, int wave, int lane, int k, uint32_t nbits, uint32_t (&n)[4]) {
+  if constexpr (W == 32) {
+    const uint4 q = strip[(wave * kWaveElems + k * 256 + 4 * lane) / 4];
+    n[0] = __builtin_amdgcn_ubfe(q.x, 0u, nbits); n[1] = __builtin_amdgcn_ubfe(q.y, 0u, nbits);
+    n[2] = __builtin_amdgcn_ubfe(q.z, 0u, nbits); n[3] = __builtin_amdgcn_ubfe(q.w, 0u, nbits);
+  } else {
+    const uint64_t rb = read_wg_row_bits<W>(strip, wave, lane, k);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) n[j] = slot_bits<W>(rb, j, nbits);
   }
 }
 
@@ -704,11 +740,15 @@ __device__ __forceinline__ uint32_t pack4_bytes(uint32_t c0, uint32_t c1, uint32
   return lo | hi;
 }
 
-template <bool TIES>
+// MANY: more than 16 random bits, the rounding that keeps 32 fraction bits (any pattern).
+template <bool TIES, bool MANY = false>
 __device__ __forceinline__ uint32_t round4_bytes(const uint32_t (&b)[4], const uint32_t (&n)[4], bool checked,
                                                  const Fmt8& f, const Mode8& m) {
   uint32_t c[4];
-  if (checked) {
+  if constexpr (MANY) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c[j] = round8_wide(b[j], n[j], f, m);
+  } else if (checked) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) c[j] = round8<TIES, true>(b[j], n[j], f, m);
   } else {

@@ -47,17 +47,15 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
     const bool checked = __any(umax > 0x7F800000u);   // wave-uniform: a NaN among the wave's elements
 #pragma unroll
     for (int k = 0; k < kRows; ++k) {
-      uint64_t rb = 0;
-      if constexpr (W != 0) rb = read_wg_row_bits<WW>(strip, wave, lane, k);
       const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
                              __float_as_uint(v[k].w)};
-      const uint32_t n4[4] = {W == 0 ? 0u : slot_bits<WW>(rb, 0, m.nbits), W == 0 ? 0u : slot_bits<WW>(rb, 1, m.nbits),
-                              W == 0 ? 0u : slot_bits<WW>(rb, 2, m.nbits), W == 0 ? 0u : slot_bits<WW>(rb, 3, m.nbits)};
+      uint32_t n4[4] = {0, 0, 0, 0};
+      if constexpr (W != 0) row_draws4<WW>(strip, wave, lane, k, m.nbits, n4);
       if constexpr (WIDE) {
         const uint2 c = round4_codes16<TIES>(b, n4, checked, f, m);
         __builtin_nontemporal_store((uint64_t)c.x | ((uint64_t)c.y << 32), reinterpret_cast<uint64_t*>(out) + row0 + (uint64_t)(k * 64));
       } else {
-        __builtin_nontemporal_store(round4_bytes<TIES>(b, n4, checked, f, m),
+        __builtin_nontemporal_store(round4_bytes<TIES, W == 32>(b, n4, checked, f, m),
                                     reinterpret_cast<uint32_t*>(out) + row0 + (uint64_t)(k * 64));
       }
     }
@@ -90,8 +88,8 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
       c.x = lo.x; c.y = lo.y; c.z = hi.x; c.w = hi.y;
       __builtin_nontemporal_store(c, reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + g0));
     } else {
-      const uint32_t lo = round4_bytes<TIES>(b_lo, n_lo, checked, f, m);
-      const uint32_t hi = round4_bytes<TIES>(b_hi, n_hi, checked, f, m);
+      const uint32_t lo = round4_bytes<TIES, W == 32>(b_lo, n_lo, checked, f, m);
+      const uint32_t hi = round4_bytes<TIES, W == 32>(b_hi, n_hi, checked, f, m);
       __builtin_nontemporal_store((uint64_t)lo | ((uint64_t)hi << 32), reinterpret_cast<uint64_t*>(reinterpret_cast<uint8_t*>(out) + g0));
     }
   }
@@ -130,7 +128,11 @@ hipError_t launch_tiles_w(int W, const void* x, void* out, uint64_t ntiles, cons
     case 2: FBSR_F8_LAUNCH(2); break;
     case 4: FBSR_F8_LAUNCH(4); break;
     case 8: FBSR_F8_LAUNCH(8); break;
-    default: FBSR_F8_LAUNCH(16); break;
+    case 16: FBSR_F8_LAUNCH(16); break;
+    default:
+      if constexpr (WIDE) return hipErrorInvalidValue;   // 16-bit codes take at most 16 random bits (checked by the caller)
+      else FBSR_F8_LAUNCH(32);
+      break;
   }
 #undef FBSR_F8_LAUNCH
   return hipGetLastError();
@@ -147,7 +149,6 @@ hipError_t run(const void* xin, void* outv, uint64_t n, const Fmt8& f, const Mod
   const int W = m.nbits ? slot_width((int)m.nbits) : 0;
   Split s = split_range(n, offset, W ? W : 8, W == 0, reinterpret_cast<uintptr_t>(x), isize, 16,
                         reinterpret_cast<uintptr_t>(out), osize, oalign);
-  if (m.nbits > (uint32_t)kMaxTileNbits) s.head = s.ntiles = 0;   // more than 16 bits: the per-element kernel throughout
   return run_split(
       s, n,
       [&](uint64_t first, uint64_t count) {

@@ -63,9 +63,10 @@ constexpr uint64_t kMaxTilesPerLaunch = (uint64_t)1 << 22;
 // 6.65); for the QAT step, the block-scaled and the generic-format kernels no run length differs from the identity by
 // more than run-to-run noise.
 constexpr uint32_t kXcdLgRound = 8, kXcdLgSgd = 7, kXcdLgRound16 = 7, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 0;
-// Up to 16 random bits per element the tile kernels apply (slots of at most 16 bits, 24 fraction bits).  With more
-// (the rounding entry points take up to 24) fbsr_round has a tile kernel with 32-bit slots and the wide rounding
-// (32 fraction bits); the narrow-source and generic-format entry points go through their per-element kernels.
+// Up to 16 random bits per element use slots of at most 16 bits and a code space with 24 fraction bits.  With more (the
+// rounding entry points take up to 24) every tile kernel has a flavour with 32-bit slots: the fp8 targets through the
+// hardware converts where those are exact and otherwise, like bf16 and the generic formats, through a rounding that
+// keeps 32 fraction bits.
 constexpr int kMaxTileNbits = 16;
 // Largest n the library accepts.
 constexpr uint64_t kMaxElems = (uint64_t)1 << 38;

@@ -38,34 +38,23 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
                          max(__float_as_uint(v[k].z) & 0x7FFFFFFFu, __float_as_uint(v[k].w) & 0x7FFFFFFFu)));
   }
   const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: NaN (bf16: also |x| > M) is rare
-  // The hardware converts add the top D = 24 - P bits of the random operand to the first D bits below the kept ones and
-  // drop whatever lies further down.  That is the exact rule for up to D random bits (D - 1 with SRF's half step) on any
-  // input, and for any number of bits on a target-normal input, which has no bits further down.  With more bits a
-  // wave that holds a non-zero value below the normal range takes the integer arithmetic.
+  // with more random bits than the hardware converts apply exactly to every input, a wave that holds a non-zero value
+  // below the target's normal range takes the integer arithmetic
   bool hw_ok = true;
   if constexpr (MANY && Fx<FMT>::kIsFp8) {
-    if (nbits > 24 - Fx<FMT>::P - (VAR == kSRF ? 1 : 0)) {   // uniform over the launch
-      uint32_t lowest = 0xFFFFFFFFu;                          // smallest |pattern| - 1 (zero wraps to the top)
+    if (hw_needs_normal_inputs<FMT, VAR>(nbits)) {   // uniform over the launch
+      uint32_t lowest = 0xFFFFFFFFu;
 #pragma unroll
-      for (int k = 0; k < kRows; ++k) {
-        lowest = min(lowest, min(min((__float_as_uint(v[k].x) & 0x7FFFFFFFu) - 1u, (__float_as_uint(v[k].y) & 0x7FFFFFFFu) - 1u),
-                                 min((__float_as_uint(v[k].z) & 0x7FFFFFFFu) - 1u, (__float_as_uint(v[k].w) & 0x7FFFFFFFu) - 1u)));
-      }
+      for (int k = 0; k < kRows; ++k)
+        lowest = min(lowest, min(min(magnitude_less_one(__float_as_uint(v[k].x)), magnitude_less_one(__float_as_uint(v[k].y))),
+                                 min(magnitude_less_one(__float_as_uint(v[k].z)), magnitude_less_one(__float_as_uint(v[k].w)))));
       hw_ok = !__any(lowest < Fx<FMT>::U_SUB - 1u);
     }
   }
 #pragma unroll
   for (int k = 0; k < kRows; ++k) {
     uint32_t n4[4] = {0, 0, 0, 0};
-    if constexpr (MANY) {
-      const uint4 q = strip[(wave * kWaveElems + k * 256 + 4 * lane) / 4];   // the row's four slots
-      n4[0] = __builtin_amdgcn_ubfe(q.x, 0u, (uint32_t)nbits); n4[1] = __builtin_amdgcn_ubfe(q.y, 0u, (uint32_t)nbits);
-      n4[2] = __builtin_amdgcn_ubfe(q.z, 0u, (uint32_t)nbits); n4[3] = __builtin_amdgcn_ubfe(q.w, 0u, (uint32_t)nbits);
-    } else if constexpr (VAR != kRNE) {
-      const uint64_t rb = read_wg_row_bits<W>(strip, wave, lane, k);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) n4[j] = slot_bits<W>(rb, j, a.nbits);
-    }
+    if constexpr (VAR != kRNE) row_draws4<W>(strip, wave, lane, k, (uint32_t)nbits, n4);
     const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
                            __float_as_uint(v[k].w)};
     const uint64_t row = row0 + (uint64_t)(k * 64);

@@ -37,7 +37,8 @@ __global__ __launch_bounds__(kThreads) void round16_tiles(const uint16_t* __rest
     }
     __syncthreads();
   }
-  const Addends a = make_addends<FMT, VAR>(nbits);
+  constexpr bool MANY = W == 32;   // more than 16 random bits: 32-bit slots
+  const Addends a = make_addends<FMT, VAR>(MANY ? kMaxTileNbits : nbits);
   HwAddends hw = {0, 0, 0, 0};
   if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
 #pragma unroll
@@ -51,9 +52,19 @@ __global__ __launch_bounds__(kThreads) void round16_tiles(const uint16_t* __rest
       b[j] = widen16<SRC>((words[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
       umax = max(umax, b[j] & 0x7FFFFFFFu);
     }
-    const bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: a NaN among the wave's elements
+    bool checked = __any(needs_checked<FMT>(umax));   // wave-uniform: a NaN among the wave's elements
+    if constexpr (MANY) {
+      // more random bits than the hardware converts apply exactly to every input: they serve a wave only if it holds no
+      // non-zero value below the target's normal range
+      if (hw_needs_normal_inputs<FMT, VAR>(nbits)) {
+        uint32_t lowest = 0xFFFFFFFFu;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) lowest = min(lowest, magnitude_less_one(b[j]));
+        checked = checked || __any(lowest < Fx<FMT>::U_SUB - 1u);
+      }
+    }
     uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if constexpr (VAR != kRNE) read_wg_bits8<W>(strip + t * T::BLOCKS, e0, a.nbits, n);
+    if constexpr (VAR != kRNE) read_wg_bits8<W>(strip + t * T::BLOCKS, e0, (uint32_t)nbits, n);
     uint32_t packed[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -62,14 +73,17 @@ __global__ __launch_bounds__(kThreads) void round16_tiles(const uint16_t* __rest
       bool done = false;
       if constexpr (VAR != kRNE) {
         if (!checked) {
-          packed[h] = round4_fp8_hw<FMT, VAR>(b4, n4, hw);
+          packed[h] = round4_fp8_hw<FMT, VAR, MANY>(b4, n4, hw);
           done = true;
         }
       }
       if (!done) {
         uint32_t r[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, true>(b4[j], n4[j], a);
+        for (int j = 0; j < 4; ++j) {
+          if constexpr (MANY) r[j] = round_pattern_wide<FMT, VAR>(b4[j], n4[j], (uint32_t)nbits);
+          else r[j] = round_pattern<FMT, VAR, true>(b4[j], n4[j], a);
+        }
         packed[h] = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
       }
     }
@@ -109,7 +123,8 @@ hipError_t launch_tiles_w(int W, const uint16_t* x, uint8_t* out, uint64_t ntile
       case 2: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 2>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
       case 4: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 4>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
       case 8: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 8>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
-      default: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 16>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
+      case 16: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 16>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
+      default: hipLaunchKernelGGL((round16_tiles<SRC, FMT, VAR, 32>), grid, block, 0, stream, x, out, (uint32_t)ntiles, nbits, seed, blk0, kXcdLgRound16); break;
     }
   }
   return hipGetLastError();
@@ -119,9 +134,8 @@ template <int SRC, int FMT, int VAR>
 hipError_t run(const uint16_t* x, uint8_t* out, uint64_t n, int nbits, uint64_t seed, uint64_t offset,
                hipStream_t stream) {
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
-  Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 2, 16,
-                        reinterpret_cast<uintptr_t>(out), 1, 8);
-  if (VAR != kRNE && nbits > kMaxTileNbits) s.head = s.ntiles = 0;   // more than 16 bits: the per-element kernel throughout
+  const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 2, 16,
+                              reinterpret_cast<uintptr_t>(out), 1, 8);
   return run_split(
       s, n,
       [&](uint64_t first, uint64_t count) {
