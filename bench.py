@@ -24,21 +24,48 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per fp8 round_tiles launch of 2^28 elements, from two rocprofv3 --pmc runs of this file
-# (FETCH_SIZE, then WRITE_SIZE, each scaled by what the counter reads for a plain 1 GiB device copy);
-# the summary is committed under profiles/.  Algorithmic bytes: 5 * 2^28 = 1342177280.
-MEASURED_TRAFFIC_BYTES_2P28 = 1342194673
-# Vector-ALU roofline for the paths that are not bound by HBM: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz
-# one-lane operations per second.  VALU instructions per element are SQ_INSTS_VALU / SQ_WAVES / elements per lane
-# from a rocprofv3 --pmc run of this file (profiles/kernels_2p28_valu_counters.md).
-ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-VALU_PER_ELEM = {"qat_adamw_e4m3_N3_src": 65.9, "qat_adamw_e4m3_N3_srff": 58.9, "qat_adamw_binary8p4_N3_src": 72.8,
-                 "qat_adamw_binary8p4_N3_srff": 65.8, "qat_adamw_format8_binary8p4_N3_src": 85.6,
-                 "qat_adamw_format8_binary8p4_N3_srff": 77.4, "bias_stats_e4m3_N3_srf": 25.1, "bias_stats_e4m3_N8_srf": 27.0,
-                 "bias_stats_bf16_N2_srf": 22.7, "bias_stats_bf16_N8_srf": 25.5,
-                 "round_format8_binary8p4_from_fp32_N3_src": 36.4, "round_format8_binary8p4_from_fp32_N8_srf": 29.6,
-                 "round_format8_binary8p4_from_bf16_N3_src": 36.5, "round_format8_binary8p4_from_bf16_N3_srff": 27.8,
-                 "round_from_bf16_binary8p4_N3_src": 22.4, "round_from_bf16_e4m3_N3_src": 17.2}
+# Vector-ALU ceiling for the paths that HBM does not bound: the part's published fp32 vector peak of 157.3 TFLOP/s is
+# 78.6 x 10^12 fused multiply-adds a second, i.e. one-lane operations a second at the widest issue the vector ALUs have
+# (256 compute units x 128 lanes x 2.4 GHz).  No instruction mix can pass it; the integer / conversion / fp64 instructions
+# these kernels are made of run at about half that rate, so read the fraction as an upper-bound-normalised figure.
+ALU_PEAK_LANE_OPS = 157.3e12 / 2
+# Counter-derived figures (VALU instructions per element per path, HBM traffic of the headline launch) come from
+# profiles/kernel_counters.json, which `python -m paper_2504_20634_amd.profile_summary` writes from rocprofv3 --pmc runs
+# of this file together with a hash of the kernel sources.  When the sources have changed since, the figures are
+# stale and are left out.
+COUNTERS_JSON = os.path.join(ROOT, "profiles", "kernel_counters.json")
+# The kernel each secondary path launches, as rocprofv3 names it (template arguments: round_tiles<fmt, variant, W>,
+# round16_tiles<src, fmt, variant, W>, format8_tiles<src, ties, W, 16-bit codes>, block_tiles<fmt, variant, W>,
+# format8_lut_tiles<src, W>, sgd_tiles<variant, W>, stats_spans<fmt, variant, W>, qat_tiles<codec, W>; fmt 0 bf16, 1 E4M3, 2 E5M2, 3 binary8p4;
+# variant 0 RNE, 1 SRFF, 2 SRF, 3 SRC; W the slot width).  The profile summary joins counters to paths through these.
+PATH_KERNELS = {
+    "stream_4to1_no_arithmetic_ceiling": "fbsr::stream41_tiles", "stream_7to5_no_arithmetic_ceiling": "fbsr::stream75_tiles",
+    "round_e4m3_rne_ceiling": "fbsr::round_tiles<1, 0, 8>",
+    "round_bf16_N4_srf": "fbsr::round_tiles<0, 2, 4>", "round_bf16_N8_srf": "fbsr::round_tiles<0, 2, 8>",
+    "round_bf16_N16_srf": "fbsr::round_tiles<0, 2, 16>",
+    "round_from_bf16_e4m3_N3_src": "fbsr::round16_tiles<0, 1, 3, 4>", "round_from_bf16_e5m2_N3_srf": "fbsr::round16_tiles<0, 2, 2, 4>",
+    "round_from_bf16_e4m3_N8_srff": "fbsr::round16_tiles<0, 1, 1, 8>", "round_from_bf16_e4m3_N20_srff": "fbsr::round16_tiles<0, 1, 1, 32>",
+    "round_binary8p4_N3_src": "fbsr::round_tiles<3, 3, 4>", "round_binary8p4_N8_srff": "fbsr::round_tiles<3, 1, 8>",
+    "round_e4m3_N20_classical_sr": "fbsr::round_tiles<1, 1, 32>", "round_e4m3_N24_src": "fbsr::round_tiles<1, 3, 32>",
+    "round_from_bf16_binary8p4_N3_src": "fbsr::round16_tiles<0, 3, 3, 4>",
+    "round_format8_binary8p4_from_fp32_N3_src": "fbsr::format8_tiles<2, true, 4, false>",
+    "round_format8_binary8p4_from_fp32_N8_srf": "fbsr::format8_tiles<2, false, 8, false>",
+    "round_format8_binary8p4_from_fp32_N3_src_ties_odd": "fbsr::format8_tiles<2, true, 4, false>",
+    "round_format8_binary8p4_from_fp32_N20_srff": "fbsr::format8_tiles<2, false, 32, false>",
+    "round_format8_binary8p4_from_bf16_N3_src": "fbsr::format8_lut_tiles<0, 4>",
+    "round_format8_binary8p4_from_bf16_N3_srff": "fbsr::format8_lut_tiles<0, 4>",
+    "round_format16_binary16_from_fp32_N3_src": "fbsr::format8_tiles<2, true, 4, true>",
+    "round_format16_binary16_from_fp32_N8_srf": "fbsr::format8_tiles<2, false, 8, true>",
+    "round_block_scaled_e4m3_N3_src": "fbsr::block_tiles<1, 3, 4>", "round_block_scaled_e5m2_N8_srf": "fbsr::block_tiles<2, 2, 8>",
+    "round_block_scaled_e4m3_N20_srff": "fbsr::block_tiles<1, 1, 32>",
+    "qat_adamw_e4m3_N3_src": "fbsr::qat_tiles<fbsr::FixedCodec<1, 3>, 4>", "qat_adamw_e4m3_N3_srff": "fbsr::qat_tiles<fbsr::FixedCodec<1, 1>, 4>",
+    "qat_adamw_binary8p4_N3_src": "fbsr::qat_tiles<fbsr::FixedCodec<3, 3>, 4>", "qat_adamw_binary8p4_N3_srff": "fbsr::qat_tiles<fbsr::FixedCodec<3, 1>, 4>",
+    "qat_adamw_format8_binary8p4_N3_src": "fbsr::qat_tiles<fbsr::Codec8<true, true>, 4>",
+    "qat_adamw_format8_binary8p4_N3_srff": "fbsr::qat_tiles<fbsr::Codec8<false, true>, 4>",
+    "sgd_update_bf16_N2_srf": "fbsr::sgd_tiles<2, 2>", "sgd_update_bf16_N4_srf": "fbsr::sgd_tiles<2, 4>", "sgd_update_bf16_N8_srf": "fbsr::sgd_tiles<2, 8>",
+    "bias_stats_e4m3_N3_srf": "fbsr::stats_spans<1, 2, 4>", "bias_stats_e4m3_N8_srf": "fbsr::stats_spans<1, 2, 8>",
+    "bias_stats_bf16_N2_srf": "fbsr::stats_spans<0, 2, 2>", "bias_stats_bf16_N8_srf": "fbsr::stats_spans<0, 2, 8>",
+}
 N_ELEMS = 1 << 28
 SGD_ELEMS = 1 << 27
 HEADLINE_NBITS = (2, 4, 8)
@@ -57,6 +84,31 @@ def parse():
                     help="also run two plain device copies of the 1 GiB input (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
+
+
+def kernel_sources_hash():
+    """sha256 over the kernel sources and headers, in a fixed order (what the counter figures belong to)."""
+    import hashlib
+    h = hashlib.sha256()
+    for folder in (os.path.join(ROOT, "paper_2504_20634_amd", "csrc"), os.path.join(ROOT, "include")):
+        for name in sorted(os.listdir(folder)):
+            if name.endswith((".hip", ".h")):
+                h.update(name.encode())
+                with open(os.path.join(folder, name), "rb") as fh:
+                    h.update(fh.read())
+    return h.hexdigest()
+
+
+def load_counters():
+    """(figures, note): the counter-derived figures if they belong to the sources at hand, else ({}, why not)."""
+    try:
+        with open(COUNTERS_JSON) as fh:
+            c = json.load(fh)
+    except (OSError, ValueError):
+        return {}, "no profiles/kernel_counters.json"
+    if c.get("sources_sha256") != kernel_sources_hash():
+        return {}, "profiles/kernel_counters.json belongs to other kernel sources (stale): counter-derived figures left out"
+    return c, "profiles/kernel_counters.json"
 
 
 def timed_launches(torch, fn, reps, warm=2):
@@ -189,7 +241,7 @@ def cpu_baseline(x_host, fmts, variants, threads):
             model = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), "unknown")
     except OSError:
         pass
-    return {"value": done / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+    return {"value": done / dt, "unit": "elements/s", "cores": threads, "host_cpus": os.cpu_count(), "kind": "oracle",
             "sample": "first 2^25 elements of the same inputs x 18 (format, N, variant) launches, "
                       "oracle_round_threads with %d threads, %.1f s wall" % (threads, dt),
             "single_thread_value": done1 / dt1, "single_thread_sample": "first 2^22 elements x the same 18 launches, %.1f s" % dt1,
@@ -263,7 +315,8 @@ def main():
     for i, (f, nb, v) in enumerate(sweep):
         ms = sum(evs[k][i][0].elapsed_time(evs[k][i][1]) for k in range(args.steps)) / args.steps
         per["%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
-            "ms": round(ms, 4), "gelem_s": round(n / ms / 1e6, 2), "gb_s": round(5.0 * n / ms / 1e6, 1)}
+            "ms": round(ms, 4), "gelem_s": round(n / ms / 1e6, 2), "gb_s": round(5.0 * n / ms / 1e6, 1),
+            "kernel": "fbsr::round_tiles<%d, %d, %d>" % (f, v, 1 << (nb - 1).bit_length()), "elements": n}
     avg_ms = sum(p["ms"] for p in per.values()) / len(per)
     achieved = 5.0 * n / (avg_ms * 1e-3) / 1e9
     by_n = {"N%d" % nb: round(sum(5.0 * n / p["ms"] / 1e6 for k, p in per.items() if "_N%d_" % nb in k) /
@@ -296,6 +349,8 @@ def main():
             ms = timed_launches(torch, lambda: from16(f, v, nb), 12)
             paths["round_from_bf16_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
                 "ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
+        ms = timed_launches(torch, lambda: from16(fbsr.FMT_E4M3, fbsr.SRFF, 20), 8)       # more than 16 random bits: 32-bit slots
+        paths["round_from_bf16_e4m3_N20_srff"] = {"ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
         # the format Sec. IV trains in (P3109 binary8p4) as a target id: hardware converts on 2 x
         def p4round(v, nb):
             turn[0] += 1
@@ -312,6 +367,14 @@ def main():
         paths["round_e4m3_N20_classical_sr"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1),
                                                                    "gelem_s": round(n / ms / 1e6, 1)}
 
+        # 24 bits with the corrected variant: past what the hardware converts apply to every input, so waves that hold
+        # values below the normal range (most waves of this full-range input) take the integer rounding
+        def most_bits():
+            turn[0] += 1
+            fbsr.fbsr_round(x_rot[fbsr.FMT_E4M3][turn[0] % 3], fbsr.FMT_E4M3, fbsr.SRC, 24, seed=2, offset=0, out=out_rot[turn[0] % 4])
+        ms = timed_launches(torch, most_bits, 6)
+        paths["round_e4m3_N24_src"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
+
         def p4from16(v, nb):
             rot16[0] += 1
             fbsr.fbsr_round_from16(x16[rot16[0] % 3], fbsr.SRC_BF16, fbsr.FMT_BINARY8P4, v, nb, seed=2, offset=0, out=out_rot[rot16[0] % 4])
@@ -326,13 +389,25 @@ def main():
             xin = x_rot[fbsr.FMT_E4M3][rotg[0] % 3] if src == fbsr.FROM_FP32 else x16[rotg[0] % 3]
             fbsr.fbsr_round_format8(xin, src, p4, v, nb, seed=2, offset=0, out=out_rot[rotg[0] % 4])
         for src, v, nb, tag in ((fbsr.FROM_FP32, fbsr.SRC, 3, "src"), (fbsr.FROM_FP32, fbsr.SRF, 8, "srf"),
-                                (fbsr.FROM_FP32, fbsr.SRC_TIES_ODD, 3, "src_ties_odd"), (fbsr.FROM_BF16, fbsr.SRC, 3, "src"),
-                                (fbsr.FROM_BF16, fbsr.SRFF, 3, "srff")):
+                                (fbsr.FROM_FP32, fbsr.SRC_TIES_ODD, 3, "src_ties_odd"), (fbsr.FROM_FP32, fbsr.SRFF, 20, "srff"),
+                                (fbsr.FROM_BF16, fbsr.SRC, 3, "src"), (fbsr.FROM_BF16, fbsr.SRFF, 3, "srff")):
             ms = timed_launches(torch, lambda: generic(src, v, nb), 12)
             bpe = 5.0 if src == fbsr.FROM_FP32 else 3.0
             paths["round_format8_binary8p4_from_%s_N%d_%s" % ("fp32" if src == fbsr.FROM_FP32 else "bf16", nb, tag)] = {
                 "ms": round(ms, 4), "gb_s": round(bpe * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
         del x16
+        # IEEE binary16 as a generic 16-bit target (4 B read, 2 B written per element)
+        b16 = fbsr.format8_named("ieee_binary16")
+        o16 = [torch.empty(n, dtype=torch.uint16, device="cuda") for _ in range(2)]
+
+        def wide16(v, nb):
+            rotg[0] += 1
+            fbsr.fbsr_round_format16(x_rot[fbsr.FMT_E4M3][rotg[0] % 3], fbsr.FROM_FP32, b16, v, nb, seed=2, offset=0, out=o16[rotg[0] % 2])
+        for v, nb, tag in ((fbsr.SRC, 3, "src"), (fbsr.SRF, 8, "srf")):
+            ms = timed_launches(torch, lambda: wide16(v, nb), 10)
+            paths["round_format16_binary16_from_fp32_N%d_%s" % (nb, tag)] = {"ms": round(ms, 4), "gb_s": round(6.0 * n / ms / 1e6, 1),
+                                                                              "gelem_s": round(n / ms / 1e6, 1)}
+        del o16
         # block-scaled fp8 target (one scale byte per 32 elements: 4 B read + 1 + 1/32 B written per element)
         sc = torch.empty(n // 32, dtype=torch.uint8, device="cuda")
         rotb = [0]
@@ -340,7 +415,7 @@ def main():
         def blockscaled(f, v, nb):
             rotb[0] += 1
             fbsr.fbsr_round_block_scaled(x_rot[f][rotb[0] % 3], f, v, nb, seed=2, offset=0, out=out_rot[rotb[0] % 4], scales=sc)
-        for f, v, nb in ((fbsr.FMT_E4M3, fbsr.SRC, 3), (fbsr.FMT_E5M2, fbsr.SRF, 8)):
+        for f, v, nb in ((fbsr.FMT_E4M3, fbsr.SRC, 3), (fbsr.FMT_E5M2, fbsr.SRF, 8), (fbsr.FMT_E4M3, fbsr.SRFF, 20)):
             ms = timed_launches(torch, lambda: blockscaled(f, v, nb), 12)
             paths["round_block_scaled_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
                 "ms": round(ms, 4), "gb_s": round((5.0 + 1.0 / 32) * n / ms / 1e6, 1)}
@@ -352,6 +427,15 @@ def main():
                torch.zeros(nq, dtype=torch.int16, device="cuda"), torch.zeros(nq, dtype=torch.int16, device="cuda"))
               for k in range(3)]
         tq = [0]
+
+        # the step's loads and stores with the arithmetic taken out: the ceiling of its 7 : 5 read : write stream
+        def stream75_twice():                        # two launches on two buffer sets; each set gets an even count in all,
+            for k in range(2):                       # so the buffers end as they began
+                w8_, g_, m_, v_ = qs[k]
+                fbsr.binding.fbsr_probe_stream75(w8_, g_, m_, v_)
+        ms = timed_launches(torch, stream75_twice, 6) / 2
+        paths["stream_7to5_no_arithmetic_ceiling"] = {"ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1),
+                                                      "gelem_s": round(nq / ms / 1e6, 1)}
 
         def qat(v):
             tq[0] += 1
@@ -425,14 +509,20 @@ def main():
             paths["bias_stats_%s_N%d_srf" % (target[f], nb)] = {"ms": round(ms, 4), "gb_s": round(4.0 * n / ms / 1e6, 1)}
         del xs_
 
-    # the paths the vector ALU bounds: instructions per element x elements per second against the ALU peak
-    for name, per_elem in VALU_PER_ELEM.items():
-        if name in paths:
-            ms = paths[name]["ms"]
-            elems = SGD_ELEMS if name.startswith("qat") else n
-            rate = per_elem * min(elems, n) / (ms * 1e-3)
-            paths[name]["alu_roofline"] = {"bound": "alu", "achieved": round(rate / 1e12, 2), "peak": round(ALU_PEAK_LANE_OPS / 1e12, 2),
-                                           "unit": "T lane-ops/s", "frac": round(rate / ALU_PEAK_LANE_OPS, 3), "valu_per_elem": per_elem}
+    # every path names its kernel and its elements per launch; where the committed counter figures belong to the kernel
+    # sources at hand, a path also carries its vector-ALU figures: instructions per element x elements per second against
+    # the ALU ceiling, and the share of the kernel's time with vector-ALU work in flight (rocprofv3's VALUBusy)
+    counters, counters_note = load_counters()
+    for name, entry in paths.items():
+        elems = min(SGD_ELEMS, n) if name.startswith(("qat", "sgd", "stream_7to5")) else n
+        entry["kernel"] = PATH_KERNELS.get(name)
+        entry["elements"] = elems
+        per_elem = counters.get("valu_per_elem", {}).get(name)
+        if per_elem is not None:
+            rate = per_elem * elems / (entry["ms"] * 1e-3)
+            entry["alu_roofline"] = {"bound": "alu", "achieved": round(rate / 1e12, 2), "peak": round(ALU_PEAK_LANE_OPS / 1e12, 2),
+                                     "unit": "T lane-ops/s", "frac": round(rate / ALU_PEAK_LANE_OPS, 3), "valu_per_elem": per_elem,
+                                     "valu_busy_pct": counters.get("valu_busy_pct", {}).get(name)}
     workloads_report = None
     if not args.no_paths and not args.no_workloads and args.elems_log2 == 28:
         del x_rot, out_rot
@@ -457,7 +547,8 @@ def main():
                    "elements": n, "launches_per_step": len(sweep)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES_2P28 if args.elems_log2 == 28 else None,
+                     "traffic": counters.get("headline_traffic_bytes_2p28") if args.elems_log2 == 28 else None,
+                     "traffic_source": counters_note,
                      "kernel": "round_tiles<fmt,variant,W> (average over the 18 launches of a step)",
                      "bytes_per_launch": 5 * n, "avg_launch_ms": avg_ms, "gb_s_by_nbits": by_n},
         "per_launch": per,

@@ -21,7 +21,7 @@ MAX_NBITS_ROUND = 24      # every other entry point
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2", FMT_BINARY8P4: "binary8p4"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
 EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_round_format16", "fbsr_format16_check", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_static", "fbsr_bias_stats_workspace_bytes",
-           "fbsr_probe_stream41", "fbsr_strerror", "fbsr_version")
+           "fbsr_probe_stream41", "fbsr_probe_stream75", "fbsr_strerror", "fbsr_version")
 
 
 class FbsrError(RuntimeError):
@@ -73,6 +73,8 @@ def lib():
         L.fbsr_qat_adamw_step_format8.restype = i32
         L.fbsr_probe_stream41.argtypes = [vp, vp, u64, vp]
         L.fbsr_probe_stream41.restype = i32
+        L.fbsr_probe_stream75.argtypes = [vp, vp, vp, vp, u64, vp]
+        L.fbsr_probe_stream75.restype = i32
         L.fbsr_strerror.argtypes = [i32]
         L.fbsr_strerror.restype = ctypes.c_char_p
         L.fbsr_version.argtypes = []
@@ -201,6 +203,15 @@ def fbsr_probe_stream41(x, out, stream=None):
     assert out.numel() == x.numel()
     _check(lib().fbsr_probe_stream41(x.data_ptr(), out.data_ptr(), x.numel(), _stream_handle(stream)), "fbsr_probe_stream41")
     return out
+
+
+def fbsr_probe_stream75(w8, g16, m16, v16, stream=None):
+    """Measurement aid: the fused training step's loads and stores with no arithmetic (buffers updated in place)."""
+    n = w8.numel()
+    assert all(t.is_cuda and t.is_contiguous() for t in (w8, g16, m16, v16)) and w8.element_size() == 1
+    assert all(t.numel() == n and t.element_size() == 2 for t in (g16, m16, v16))
+    _check(lib().fbsr_probe_stream75(w8.data_ptr(), g16.data_ptr(), m16.data_ptr(), v16.data_ptr(), n, _stream_handle(stream)),
+           "fbsr_probe_stream75")
 
 
 SCALE_BLOCK = 32

@@ -355,6 +355,17 @@ int fbsr_probe_stream41(const float* x, void* out, uint64_t n, void* stream) {
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 
+int fbsr_probe_stream75(void* w8, const void* g16, void* m16, void* v16, uint64_t n, void* stream) {
+  if (n > fbsr::kMaxElems || n % fbsr::kTileElems != 0) return FBSR_EINVAL;
+  if (n == 0) return FBSR_OK;
+  if (w8 == nullptr || g16 == nullptr || m16 == nullptr || v16 == nullptr) return FBSR_EINVAL;
+  if (misaligned(w8, 8) || misaligned(g16, 16) || misaligned(m16, 16) || misaligned(v16, 16)) return FBSR_EALIGN;
+  const hipError_t e = fbsr::launch_stream75(reinterpret_cast<uint8_t*>(w8), reinterpret_cast<const uint16_t*>(g16),
+                                             reinterpret_cast<uint16_t*>(m16), reinterpret_cast<uint16_t*>(v16),
+                                             n / fbsr::kTileElems, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
 const char* fbsr_strerror(int status) {
   switch (status) {
     case FBSR_OK: return "ok";

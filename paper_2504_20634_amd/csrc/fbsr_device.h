@@ -50,11 +50,8 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
                                               uint32_t k0, uint32_t k1, uint32_t (&o)[4]) {
   constexpr uint32_t MUL_A = 0xD2511F53u, MUL_B = 0xCD9E8D57u;
   constexpr uint32_t WEYL_A = 0x9E3779B9u, WEYL_B = 0xBB67AE85u;
-#ifndef FBSR_PROBE_ROUNDS
-#define FBSR_PROBE_ROUNDS 10
-#endif
 #pragma unroll
-  for (int r = 0; r < FBSR_PROBE_ROUNDS; ++r) {
+  for (int r = 0; r < 10; ++r) {
     const uint64_t pa = (uint64_t)MUL_A * c0;
     const uint64_t pb = (uint64_t)MUL_B * c2;
     const uint32_t t0 = (uint32_t)(pb >> 32) ^ c1 ^ (k0 + WEYL_A * (uint32_t)r);
@@ -679,12 +676,11 @@ __device__ __forceinline__ uint32_t finish8(uint32_t mag, uint32_t bits, const F
   return code;
 }
 
-// One source pattern -> the output byte.  n < 2^N is the element's random integer (0 when the mode
-// draws none).  CHECKED = false may be used only when the pattern is known not to be a NaN.
-// WIDE = false: the code space has 24 fraction bits (K <= 8).  WIDE = true: f.frac of them (32 - K, for codes of up to
-// 16 bits), and the subnormal scale, which may pass fp32's range as a factor, is applied to the exponent.
-template <bool TIES, bool CHECKED, bool WIDE = false>
-__device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m) {
+// The part of round8's sum that the element's random integer does not enter: the code-space pattern of |x| plus the
+// mode's fixed addend and tie bit, or, above M (*above set; no randomness there, Sec. II), plus the nearest-even addend
+// alone.  The sum stays below 2^32: the pattern is below (max_code + 2) 2^frac and an addend below 2^frac.
+template <bool TIES, bool WIDE>
+__device__ __forceinline__ uint32_t round8_fixed_part(uint32_t bits, const Fmt8& f, const Mode8& m, bool* above) {
   const uint32_t u = bits & 0x7FFFFFFFu;
   const uint32_t uc = u < f.u_clamp ? u : f.u_clamp;
   const uint32_t normal = (uc - f.rebias) << f.shift_p;
@@ -694,7 +690,7 @@ __device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8
   const uint32_t sub = (uint32_t)scaled;                     // truncation toward zero
   const bool is_sub = u < f.u_sub;
   uint32_t r0 = is_sub ? sub : normal;
-  uint32_t add = (n << m.shift) + m.fixed;
+  uint32_t add = m.fixed;
   if constexpr (TIES) {
     // what a target-subnormal input loses to the truncation is folded into bit 0, below the tie position
     const bool lost = is_sub && ((float)sub != scaled);
@@ -704,9 +700,21 @@ __device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8
     if (f.unit_lsb != 0u) parity_of |= is_sub ? 0u : f.unit_lsb;
     add += ((parity_of >> m.shift) & 1u) ^ m.tie_xor;
   }
-  add = u > f.u_max ? f.det_add : add;   // |x| > M: no randomness (Sec. II)
-  if constexpr (WIDE) return finish8<CHECKED>((r0 + add) >> f.frac, bits, f);
-  else return finish8<CHECKED>((r0 + add) >> 24, bits, f);
+  *above = u > f.u_max;
+  return r0 + (*above ? f.det_add : add);
+}
+
+// One source pattern -> the output byte.  n < 2^N is the element's random integer (0 when the mode
+// draws none).  CHECKED = false may be used only when the pattern is known not to be a NaN.
+// WIDE = false: the code space has 24 fraction bits (K <= 8).  WIDE = true: f.frac of them (32 - K, for codes of up to
+// 16 bits), and the subnormal scale, which may pass fp32's range as a factor, is applied to the exponent.
+template <bool TIES, bool CHECKED, bool WIDE = false>
+__device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m) {
+  bool above;
+  const uint32_t fixed_part = round8_fixed_part<TIES, WIDE>(bits, f, m, &above);
+  const uint32_t sum = fixed_part + (above ? 0u : n << m.shift);
+  if constexpr (WIDE) return finish8<CHECKED>(sum >> f.frac, bits, f);
+  else return finish8<CHECKED>(sum >> 24, bits, f);
 }
 
 // round8 for N = 17 .. 24 (the per-element kernel; any pattern): see round_pattern_wide.

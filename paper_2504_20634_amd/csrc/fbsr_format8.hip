@@ -11,6 +11,8 @@
 //     ties-away      + 2^23                                 SRFF / SRF / SRC as in fbsr_device.h
 // Above M a format with an infinity takes the nearest-even addend of M's own parity, which carries
 // into the code after max_code; that code is then replaced by the infinity's.
+#include <mutex>
+
 #include "fbsr_launch.h"
 
 namespace fbsr {
@@ -95,6 +97,136 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
   }
 }
 
+// ------------------------------------------------- 16-bit sources through a table over their magnitudes ---
+// A 16-bit source has 2^15 magnitudes, and everything round8 computes before the element's random integer enters
+// depends on the magnitude alone.  One workgroup per compute unit tabulates that part once (128 KiB of LDS) and then
+// streams tiles through it: per element one table read, t = entry + (n << shift), the magnitude code min(t >> 24, cap)
+// and the sign.  An entry is round8_fixed_part's sum; above M, where no random bits apply, it is the finished
+// magnitude code in the top byte over zero fraction bits, which the n << shift of any n leaves where it is.  cap is
+// over_code, which the host has checked to be max_code (saturating) or max_code + 1 (the infinity follows M's code),
+// so that one minimum replaces the comparison with max_code.  A wave whose tile holds a NaN rounds that tile with
+// round8 itself.
+//
+// Geometry: 1024 threads in four groups of 256; a pass of the loop takes 16 consecutive tiles, group g the tiles
+// 4 q + g, q = 0 .. 3, a lane 8 consecutive codes of each (16-byte loads, issued one pass ahead; 8-byte stores).
+// Every wave draws the Philox blocks of its own 4 x 512 elements into a strip of its own (64 blocks, one per lane;
+// with 8-bit slots in two halves), so the loop has no workgroup barrier.
+constexpr int kLutThreads = 1024;
+constexpr int kLutPassTiles = 16;
+constexpr int kLutEntries = 1 << 15;
+
+template <int SRC, bool TIES>
+__device__ __forceinline__ uint32_t lut_entry(uint32_t magnitude16, const Fmt8& f, const Mode8& m) {
+  const uint32_t bits = widen16<SRC>(magnitude16);
+  if (bits > 0x7F800000u) return f.nan_code << 24;   // a NaN: never read on the table path
+  bool above;
+  const uint32_t sum = round8_fixed_part<TIES, false>(bits, f, m, &above);
+  if (!above) return sum;
+  const uint32_t mag = sum >> 24;
+  return (mag > f.max_code ? f.over_code : mag) << 24;
+}
+
+template <int SRC, int W>
+__global__ __launch_bounds__(kLutThreads) void format8_lut_tiles(const uint16_t* __restrict__ x, uint8_t* __restrict__ out, Fmt8 f,
+                                                                 Mode8 m, uint64_t seed, uint64_t blk0, uint32_t ntiles) {
+  constexpr int WW = W == 0 ? 1 : W;
+  constexpr int BLOCKS = WgTile<WW>::BLOCKS;                  // Philox blocks per tile
+  constexpr int WAVE_BLOCKS = BLOCKS / kWavesPerBlock;        // ... per wave's 512 elements of a tile: 4 W
+  constexpr int Q_PER_DRAW = 64 / WAVE_BLOCKS >= 4 ? 4 : 64 / WAVE_BLOCKS;                    // tiles of a wave one draw covers
+  constexpr uint32_t NAN_ABOVE = (SRC == kSrcBF16 ? 0x7F80u : 0x7C00u) << 2;                  // as a byte offset into the table
+  static_assert(W == 0 || (Q_PER_DRAW >= 1 && Q_PER_DRAW * WAVE_BLOCKS <= 64), "a draw is at most one block per lane");
+  __shared__ uint32_t lut[kLutEntries];
+  __shared__ uint4 strips[W == 0 ? 1 : kLutThreads / 64][W == 0 ? 1 : 64];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // 0 .. 15
+  const int group = wave >> 2;
+  const int e0 = 8 * (tid & 255);                             // tile-relative first element
+  {
+    // 1024 consecutive magnitudes per step.  A step that lies wholly above M and at or above the clamp (every entry is
+    // the one of the clamp itself; NaN entries are never read) or wholly below one unit of the code space (the pattern is 0, plus
+    // the sticky bit of a non-zero value) is filled with these constants; most of a bf16 source's range is such.
+    const auto entry = [&](uint32_t mag16) { return m.ties ? lut_entry<SRC, true>(mag16, f, m) : lut_entry<SRC, false>(mag16, f, m); };
+    const uint32_t at_clamp = entry(SRC == kSrcBF16 ? 0x7F80u : 0x7C00u), at_zero = entry(0u), below_one = entry(1u);
+    for (int i0 = 0; i0 < kLutEntries; i0 += kLutThreads) {
+      const uint32_t first = widen16<SRC>((uint32_t)i0), last = widen16<SRC>((uint32_t)(i0 + kLutThreads - 1));
+      const int i = i0 + tid;
+      if (first >= f.u_clamp && first > f.u_max) lut[i] = at_clamp;
+      else if (__uint_as_float(last) * f.sub_scale < 1.0f && last < f.u_sub) lut[i] = i == 0 ? at_zero : below_one;
+      else lut[i] = entry((uint32_t)i);
+    }
+  }
+  __syncthreads();
+  const uint32_t cap = f.over_code;
+  const uint32_t sign_lo = f.sign_shift - 16u;
+  const uint32_t passes = (ntiles + (uint32_t)kLutPassTiles - 1u) / (uint32_t)kLutPassTiles;
+  uint4* const strip = strips[W == 0 ? 0 : wave];
+  // a tile past the end reads the last one again and stores nothing; the loads of a pass are issued one pass ahead
+  const auto load_pass = [&](uint32_t pass, u32x4 (&v)[4]) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t tile = min(pass * (uint32_t)kLutPassTiles + (uint32_t)(4 * q + group), ntiles - 1u);
+      v[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + (uint64_t)tile * kTileElems + (uint64_t)e0));
+    }
+  };
+  u32x4 ahead[4];
+  load_pass(blockIdx.x, ahead);
+  for (uint32_t pass = blockIdx.x; pass < passes; pass += gridDim.x) {
+    const uint32_t tile0 = pass * (uint32_t)kLutPassTiles;
+    u32x4 v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] = ahead[q];
+    load_pass(min(pass + gridDim.x, passes - 1u), ahead);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if constexpr (W != 0) {
+        if (q % Q_PER_DRAW == 0) {   // the blocks of this wave's elements in tiles 4 (q + qq) + group, qq < Q_PER_DRAW
+          __builtin_amdgcn_wave_barrier();   // the wave's own LDS traffic keeps program order; this keeps the compiler to it
+          if (lane < Q_PER_DRAW * WAVE_BLOCKS) {
+            const uint32_t tile = tile0 + (uint32_t)(4 * (q + lane / WAVE_BLOCKS) + group);
+            uint32_t o[4];
+            philox_block(blk0 + (uint64_t)tile * BLOCKS + (uint64_t)((wave & 3) * WAVE_BLOCKS + lane % WAVE_BLOCKS), seed, 0, o);
+            strip[lane] = make_uint4(o[0], o[1], o[2], o[3]);
+          }
+          __builtin_amdgcn_wave_barrier();
+        }
+      }
+      const uint32_t tile = tile0 + (uint32_t)(4 * q + group);
+      const uint32_t words[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+      uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      if constexpr (W != 0) read_wg_bits8<WW>(strip + (q % Q_PER_DRAW) * WAVE_BLOCKS, 8 * lane, m.nbits, n);
+      uint32_t at[8], at_max = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        at[j] = (j & 1) ? (words[j >> 1] >> 14) & 0x1FFFCu : (words[j >> 1] << 2) & 0x1FFFCu;
+        at_max = max(at_max, at[j]);
+      }
+      uint32_t c[8];
+      if (__any(at_max > NAN_ABOVE)) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t bits = widen16<SRC>((words[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
+          c[j] = m.ties ? round8<true, true>(bits, n[j], f, m) : round8<false, true>(bits, n[j], f, m);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t entry = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(lut) + at[j]);
+          const uint32_t t = entry + (n[j] << m.shift);
+          const uint32_t mag = min(t >> 24, cap);
+          const uint32_t sgn = (words[j >> 1] >> ((j & 1) ? f.sign_shift : sign_lo)) & f.sign_bit;
+          c[j] = mag | (mag == 0u ? (sgn & f.zero_sign) : sgn);
+        }
+      }
+      if (tile < ntiles) {
+        const uint32_t lo = pack4_bytes(c[0], c[1], c[2], c[3]), hi = pack4_bytes(c[4], c[5], c[6], c[7]);
+        __builtin_nontemporal_store((uint64_t)lo | ((uint64_t)hi << 32),
+                                    reinterpret_cast<uint64_t*>(out + (uint64_t)tile * kTileElems + (uint64_t)e0));
+      }
+    }
+  }
+}
+
 // One thread per element: any alignment, any offset, ragged heads and tails.  W = 0: no bits.
 template <int SRC, bool TIES, bool WIDE>
 __global__ __launch_bounds__(kThreads) void format8_elems(const void* __restrict__ xin, void* __restrict__ out, uint64_t n,
@@ -138,6 +270,47 @@ hipError_t launch_tiles_w(int W, const void* x, void* out, uint64_t ntiles, cons
   return hipGetLastError();
 }
 
+// The table kernel pays for its table (2^15 entries per workgroup) from 2^26 elements on; it needs the
+// device to grant a workgroup its 144 KiB of LDS, at most 8 random bits, and an over_code that is max_code or the code after.
+constexpr uint64_t kLutMinTiles = (uint64_t)1 << 15;
+
+struct LutDevice {
+  int checked = 0, units = 0, lds = 0;
+};
+
+inline bool lut_device(int* units) {
+  static LutDevice known[64];
+  static std::mutex guard;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  std::lock_guard<std::mutex> lock(guard);
+  LutDevice& d = known[dev];
+  if (!d.checked) {
+    if (hipDeviceGetAttribute(&d.units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) d.units = 0;
+    if (hipDeviceGetAttribute(&d.lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) d.lds = 0;
+    d.checked = 1;
+  }
+  *units = d.units;
+  return d.units > 0 && d.lds >= (int)(kLutEntries * 4 + kLutThreads * 16);
+}
+
+template <int SRC>
+hipError_t launch_lut_tiles(int W, const uint16_t* x, uint8_t* out, uint64_t ntiles, const Fmt8& f, const Mode8& m, uint64_t seed,
+                            uint64_t blk0, int units, hipStream_t stream) {
+  const uint64_t passes = (ntiles + kLutPassTiles - 1) / kLutPassTiles;
+  const dim3 grid((unsigned)(passes < (uint64_t)units ? passes : (uint64_t)units)), block(kLutThreads);
+#define FBSR_LUT_LAUNCH(WW) hipLaunchKernelGGL((format8_lut_tiles<SRC, WW>), grid, block, 0, stream, x, out, f, m, seed, blk0, (uint32_t)ntiles)
+  switch (W) {
+    case 0: FBSR_LUT_LAUNCH(0); break;
+    case 1: FBSR_LUT_LAUNCH(1); break;
+    case 2: FBSR_LUT_LAUNCH(2); break;
+    case 4: FBSR_LUT_LAUNCH(4); break;
+    default: FBSR_LUT_LAUNCH(8); break;
+  }
+#undef FBSR_LUT_LAUNCH
+  return hipGetLastError();
+}
+
 template <int SRC, bool TIES, bool WIDE>
 hipError_t run(const void* xin, void* outv, uint64_t n, const Fmt8& f, const Mode8& m, uint64_t seed, uint64_t offset,
                hipStream_t stream) {
@@ -158,8 +331,16 @@ hipError_t run(const void* xin, void* outv, uint64_t n, const Fmt8& f, const Mod
         return hipGetLastError();
       },
       [&](uint64_t first, uint64_t count) {
-        return launch_tiles_w<SRC, TIES, WIDE>(W, x + first * isize, out + first * osize, count, f, m, seed,
-                                               W ? (offset + first) / (uint64_t)(128 / W) : 0, stream);
+        const uint64_t blk0 = W ? (offset + first) / (uint64_t)(128 / W) : 0;
+        if constexpr (SRC != kSrcFP32 && !WIDE) {
+          int units = 0;
+          if (count >= kLutMinTiles && W <= 8 && (f.over_code == f.max_code || f.over_code == f.max_code + 1u) &&
+              lut_device(&units)) {
+            return launch_lut_tiles<SRC>(W, reinterpret_cast<const uint16_t*>(x + first * isize),
+                                         reinterpret_cast<uint8_t*>(out + first * osize), count, f, m, seed, blk0, units, stream);
+          }
+        }
+        return launch_tiles_w<SRC, TIES, WIDE>(W, x + first * isize, out + first * osize, count, f, m, seed, blk0, stream);
       });
 }
 

@@ -60,9 +60,9 @@ constexpr uint64_t kMaxTilesPerLaunch = (uint64_t)1 << 22;
 // (xcd_tile), per kernel family; 0 keeps the identity order.  From sweeps over 0..12 on 2^28 elements: the kernels that
 // read fp32 gain 4-5 % at runs of 128-256 tiles (fp32 -> fp8 6.25 -> 6.57 TB/s, fp32 -> bf16 6.40 -> 6.70, the SGD
 // update 6.15 -> 6.38), a plain 16-bit -> 8-bit stream with 4096 elements per workgroup 5 % at runs of 128 (6.35 ->
-// 6.65); for the QAT step, the block-scaled and the generic-format kernels no run length differs from the identity by
-// more than run-to-run noise.
-constexpr uint32_t kXcdLgRound = 8, kXcdLgSgd = 7, kXcdLgRound16 = 7, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 0;
+// 6.65), the QAT step's 7 : 5 in-place stream 3 % at runs of 128 (its no-arithmetic probe 5.64 -> 5.83); for the
+// block-scaled and the generic-format kernels no run length differs from the identity by more than run-to-run noise.
+constexpr uint32_t kXcdLgRound = 8, kXcdLgSgd = 7, kXcdLgRound16 = 7, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 7;
 // Up to 16 random bits per element use slots of at most 16 bits and a code space with 24 fraction bits.  With more (the
 // rounding entry points take up to 24) every tile kernel has a flavour with 32-bit slots: the fp8 targets through the
 // hardware converts where those are exact and otherwise, like bf16 and the generic formats, through a rounding that
@@ -102,6 +102,7 @@ hipError_t launch_round(const float* x, void* out, uint64_t n, int fmt, int vari
                         uint64_t offset, hipStream_t stream);
 
 hipError_t launch_stream41(const float* x, uint8_t* out, uint64_t ntiles, hipStream_t stream);
+hipError_t launch_stream75(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t ntiles, hipStream_t stream);
 
 hipError_t launch_round_from16(const void* x, void* out, uint64_t n, int src_fmt, int fmt, int variant, int nbits,
                                uint64_t seed, uint64_t offset, hipStream_t stream);
@@ -114,8 +115,9 @@ hipError_t launch_round_block_scaled(const float* x, uint8_t* out, uint8_t* scal
 
 struct AdamWScalars {
   float lr, beta1, beta2, eps, weight_decay, bias_corr1, bias_corr2;
-  // 1 / bias_corr (correctly rounded, computed on the host) and whether the tile kernel may divide by the two
-  // corrections with div_by_uniform (both in [2^-20, 1]); the caller's struct ends at bias_corr2.
+  // 1 / bias_corr (correctly rounded, computed on the host) and whether the tile kernel may take its shortened
+  // divisions and the tabulated square root (both corrections in [2^-20, 1], eps in [2^-28, 2^30]); the caller's
+  // struct ends at bias_corr2.
   float rcp_corr1, rcp_corr2;
   int fast_div;
 };
@@ -123,7 +125,8 @@ struct AdamWScalars {
 // Fills the derived fields of AdamWScalars.
 inline void derive_adamw(AdamWScalars* p) {
   const float lo = 0x1p-20f;
-  p->fast_div = p->bias_corr1 >= lo && p->bias_corr1 <= 1.0f && p->bias_corr2 >= lo && p->bias_corr2 <= 1.0f;
+  p->fast_div = p->bias_corr1 >= lo && p->bias_corr1 <= 1.0f && p->bias_corr2 >= lo && p->bias_corr2 <= 1.0f &&
+                p->eps >= 0x1p-28f && p->eps <= 0x1p30f;
   p->rcp_corr1 = p->fast_div ? 1.0f / p->bias_corr1 : 0.0f;
   p->rcp_corr2 = p->fast_div ? 1.0f / p->bias_corr2 : 0.0f;
 }

@@ -73,12 +73,68 @@ __device__ __forceinline__ float qat_update(float w, float mq, float vq, const A
   return -p.lr * __fmaf_rn(p.weight_decay, w, ratio);
 }
 
-// The same value with the two divisions by the bias corrections taken by div_by_uniform and the square root by
-// sqrt_not_tiny.
-__device__ __forceinline__ float qat_update_fast(float w, float mq, float vq, const AdamWScalars& p, bool* tiny) {
-  const float mh = div_by_uniform<-100>(mq, p.bias_corr1, p.rcp_corr1, tiny);
-  const float vh = div_by_uniform<-95>(vq, p.bias_corr2, p.rcp_corr2, tiny);   // vq is 0 or >= 2^-96, and vh >= vq
-  const float ratio = mh / (sqrt_not_tiny(vh) + p.eps);
+// n / d, correctly rounded, for a d in [2^-28, 2^65) and an n that is zero, infinite, a NaN or of magnitude at least
+// 2^-40: the reciprocal approximation, one Newton step on it, the quotient and two residual corrections of it, then
+// v_div_fixup_f32 for the sign of a zero quotient and for an infinite or NaN operand.  These are the operations of the
+// full division sequence without its pre-scaling of the operands (v_div_scale_f32, and the rescaling inside
+// v_div_fmas_f32), which exists to keep the intermediates of extreme operands in range and changes nothing when they
+// are: on this domain no reciprocal, quotient or residual leaves the normal range unless the quotient itself
+// overflows, and then the result is an infinity or a NaN as in the full sequence or a NaN that sends the wave to the
+// exact path.  A NaN d gives a NaN.  (On a CPU, with every reciprocal start within one ulp: equal to the division on
+// 8 x 10^8 operand pairs of this domain drawn to favour all-ones and all-zeros significands.)
+__device__ __forceinline__ float div_in_range(float n, float d) {
+  const float r0 = __builtin_amdgcn_rcpf(d);
+  const float e = __fmaf_rn(-d, r0, 1.0f);
+  const float r = __fmaf_rn(e, r0, r0);
+  float q = n * r;
+  float rem = __fmaf_rn(-d, q, n);
+  q = __fmaf_rn(rem, r, q);
+  rem = __fmaf_rn(-d, q, n);
+  q = __fmaf_rn(rem, r, q);
+  return __builtin_amdgcn_div_fixupf(q, d, n);
+}
+
+// sqrt(v / bias_corr2) for a bf16 second moment v by two table reads.  With E the exponent field of v, H = E >> 1 and
+// p = E & 1, v = (1.f x 2^(p + 1)) x (2^(H - 64))^2, and both the correctly rounded division by a constant and the
+// correctly rounded square root commute with such a scaling while every value stays normal.  So the root is
+// roots[p, f] x scales[sign, H] with
+//   roots[p, f]   = sqrt((1.f x 2^(p + 1)) / bias_corr2), 256 entries, filled by each workgroup with the two routines above;
+//   scales[0, H]  = 2^(H - 64) for 1 <= H <= 116 (v in [2^-125, 2^107): the quotient stays normal for bias_corr2 in [2^-20, 1]);
+//   scales[0, 0]  = 0: a v below 2^-125, zero included, has a root below 2^-52, which the sum with an eps of at least
+//                   2^-28 (the host checks it) drops entirely, so a zero root gives the same denominator;
+//   every other entry (an overflowing quotient, infinity, NaN, any set sign bit) = NaN, which reaches the sum of
+//                   weight and update and sends the wave to the exact path.
+struct RootTables {
+  float roots[256];
+  float scales[256];
+};
+
+__device__ __forceinline__ void fill_root_tables(RootTables* t, int tid, const AdamWScalars& p) {
+  bool unused = false;
+  const float x = __uint_as_float(((128u + ((uint32_t)tid >> 7)) << 23) | (((uint32_t)tid & 127u) << 16));
+  t->roots[tid] = sqrt_not_tiny(div_by_uniform<-100>(x, p.bias_corr2, p.rcp_corr2, &unused));
+  const uint32_t H = (uint32_t)tid;
+  t->scales[tid] = __uint_as_float(H == 0u ? 0u : (H <= 116u ? (H + 63u) << 23 : 0x7FC00000u));
+}
+
+// HALF 0: the second moment in the low half of `pair`, 1: in the high half.
+template <int HALF>
+__device__ __forceinline__ float root_of_corrected(const RootTables* t, uint32_t pair) {
+  const uint32_t at_root = HALF ? (pair >> 14) & 0x3FCu : (pair << 2) & 0x3FCu;     // byte offsets: (p, f) and (sign, H)
+  const uint32_t at_scale = HALF ? (pair >> 22) & 0x3FCu : (pair >> 6) & 0x3FCu;
+  const float root = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(t->roots) + at_root);
+  const float scale = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(t->scales) + at_scale);
+  return root * scale;
+}
+
+// The same value as qat_update with the division by bias_corr1 taken by div_by_uniform, the corrected second moment's
+// root by root_of_corrected and the last division by div_in_range (the host has checked the scalars' ranges, and
+// *tiny sends a first moment below 2^-40 to the exact path).
+template <int HALF>
+__device__ __forceinline__ float qat_update_fast(float w, float mq, uint32_t v_pair, const AdamWScalars& p, const RootTables* t,
+                                                 bool* tiny) {
+  const float mh = div_by_uniform<-39>(mq, p.bias_corr1, p.rcp_corr1, tiny);
+  const float ratio = div_in_range(mh, root_of_corrected<HALF>(t, v_pair) + p.eps);
   return -p.lr * __fmaf_rn(p.weight_decay, w, ratio);
 }
 
@@ -209,6 +265,7 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
   typedef WgTile<W> T;
   __shared__ uint4 strip[T::BLOCKS];
   __shared__ float table[CODEC::kTable ? 256 : 1];
+  __shared__ RootTables roots;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int e0 = wave * kWaveElems + 8 * lane;
@@ -220,7 +277,8 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
   const u32x4 vq = *reinterpret_cast<const u32x4*>(v16 + g0);
   if constexpr (CODEC::kTable) table[threadIdx.x] = ca.t.v[threadIdx.x];
   if constexpr (CODEC::kDraws) fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, step);
-  if constexpr (CODEC::kTable || CODEC::kDraws) __syncthreads();
+  if (p.fast_div != 0) fill_root_tables(&roots, threadIdx.x, p);   // uniform over the launch
+  __syncthreads();
   const CODEC c(ca, table);
   const Addends a16 = make_addends<kBF16, kRNE>(0);
   const float omb1 = 1.0f - p.beta1, omb2 = 1.0f - p.beta2;
@@ -241,8 +299,8 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
     vo[h] = bf16_pair_hw(v1a, v1b);
     uint32_t uo;
     if constexpr (FAST) {
-      uo = bf16_pair_hw(qat_update_fast(wa, bf16_lo(mo[h]), bf16_lo(vo[h]), p, &nan_seen),
-                        qat_update_fast(wb, bf16_hi(mo[h]), bf16_hi(vo[h]), p, &nan_seen));
+      uo = bf16_pair_hw(qat_update_fast<0>(wa, bf16_lo(mo[h]), vo[h], p, &roots, &nan_seen),
+                        qat_update_fast<1>(wb, bf16_hi(mo[h]), vo[h], p, &roots, &nan_seen));
     } else {
       uo = bf16_pair_hw(qat_update(wa, bf16_lo(mo[h]), bf16_lo(vo[h]), p), qat_update(wb, bf16_hi(mo[h]), bf16_hi(vo[h]), p));
     }
@@ -293,6 +351,26 @@ __global__ __launch_bounds__(kThreads) void qat_tiles(uint8_t* __restrict__ w8, 
   *reinterpret_cast<u32x4*>(m16 + g0) = t;
   t.x = vo[0]; t.y = vo[1]; t.z = vo[2]; t.w = vo[3];
   *reinterpret_cast<u32x4*>(v16 + g0) = t;
+}
+
+// Measurement aid: the tile kernel's loads and stores with the arithmetic taken out (each output word is the input
+// word combined with the gradient's by one exclusive or): 7 bytes read and 5 written per element in the same
+// launch shape.  What this reaches is the practical ceiling of the fused step's traffic on the part at hand.
+__global__ __launch_bounds__(kThreads) void stream75_tiles(uint8_t* __restrict__ w8, const uint16_t* __restrict__ g16,
+                                                           uint16_t* __restrict__ m16, uint16_t* __restrict__ v16, uint32_t xcd_lg) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
+  const uint64_t g0 = (uint64_t)tile * kTileElems + (uint64_t)(wave * kWaveElems + 8 * lane);
+  const uint64_t wq = *reinterpret_cast<const uint64_t*>(w8 + g0);
+  const u32x4 gq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g16 + g0));
+  u32x4 mq = *reinterpret_cast<const u32x4*>(m16 + g0);
+  u32x4 vq = *reinterpret_cast<const u32x4*>(v16 + g0);
+  mq.x ^= gq.x; mq.y ^= gq.y; mq.z ^= gq.z; mq.w ^= gq.w;
+  vq.x ^= gq.w; vq.y ^= gq.z; vq.z ^= gq.y; vq.w ^= gq.x;
+  *reinterpret_cast<uint64_t*>(w8 + g0) = wq ^ (uint64_t)(gq.x & 0x01010101u);
+  *reinterpret_cast<u32x4*>(m16 + g0) = mq;
+  *reinterpret_cast<u32x4*>(v16 + g0) = vq;
 }
 
 // One thread per element: any alignment, any offset, ragged heads and tails.
@@ -378,6 +456,15 @@ hipError_t run_v(int variant, uint8_t* w8, const uint16_t* g16, uint16_t* m16, u
 }
 
 }  // namespace
+
+hipError_t launch_stream75(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t ntiles, hipStream_t stream) {
+  return in_pieces(ntiles, kMaxTilesPerLaunch, [&](uint64_t t0, uint64_t count) {
+    const uint64_t e0 = t0 * kTileElems;
+    hipLaunchKernelGGL(stream75_tiles, dim3((unsigned)count), dim3(kThreads), 0, stream, w8 + e0, g16 + e0, m16 + e0, v16 + e0,
+                       kXcdLgQat);
+    return hipGetLastError();
+  });
+}
 
 hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, int fmt,
                             const AdamWScalars& p, int variant, int nbits, uint64_t seed, uint64_t step,

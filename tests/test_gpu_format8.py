@@ -106,6 +106,33 @@ def test_every_16_bit_source_code(fbsr, oracle, src, name):
         assert first_mismatch(got, want) is None, (src, name, variant, nbits, first_mismatch(got, want))
 
 
+@pytest.mark.parametrize("src", [FROM_BF16, FROM_FP16])
+@pytest.mark.parametrize("name", ["binary8p4", "ocp_e4m3", "ocp_e5m2", "ocp_e2m1", "binary8p1", "inf_apart"])
+def test_16_bit_sources_at_the_size_of_the_table_kernel(fbsr, oracle, src, name):
+    """From 2^26 elements on, 16-bit sources with at most 8 random bits go through the kernel that tabulates the 2^15
+    source magnitudes per workgroup.  All 65536 source codes (NaNs, infinities and both zeros among them) about 1024
+    times each at different global indices, a tile count that leaves the last pass of 16 tiles ragged, an offset that
+    leaves a head for the per-element kernel, a second input without a single NaN (every wave on the table path);
+    formats with and without -0, saturating and with an infinity, one whose infinity is not the code after M (which
+    stays on the other kernel, as 11 random bits do)."""
+    d = FORMATS[name]
+    n = (1 << 26) + 21 * 2048 + 77
+    rng = np.random.default_rng(7 + src)
+    codes = np.tile(np.arange(65536, dtype=np.uint16), n // 65536 + 1)[:n]
+    rng.shuffle(codes[: 1 << 20])
+    nan_from = 0x7F81 if src == FROM_BF16 else 0x7C01
+    clean = np.where((codes & 0x7FFF) >= nan_from, codes & 0x83FF, codes).astype(np.uint16)
+    for host_x, tag in ((codes, "all codes"), (clean, "no NaN")):
+        xd = dev(host_x)
+        modes = [(RNE, 0), (RNA, 0), (SRFF, 3), (SRF, 1), (SRC, 3), (SRC_ODD, 4), (SRF, 8), (SRC, 2), (SRFF, 11)]
+        for variant, nbits in (modes if tag == "all codes" else modes[2:6]):
+            for offset in ((0, 8) if (variant, nbits) in ((SRFF, 3), (SRC, 3)) else (0,)):
+                print("case src=%d fmt=%s %s variant=%d nbits=%d offset=%d" % (src, name, tag, variant, nbits, offset), flush=True)
+                got = host(fbsr.fbsr_round_format8(xd, src, d, variant, nbits, seed=5, offset=offset))
+                want = _oracle(oracle, host_x, src, d, variant, nbits, 5, offset)
+                assert first_mismatch(got, want) is None, (src, name, tag, variant, nbits, offset, first_mismatch(got, want))
+
+
 @pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 31, 127, 2047, 2048, 2049, 3 * 2048 + 100])
 def test_sizes_offsets_alignment(fbsr, oracle, n):
     rng = np.random.default_rng(n + 1)

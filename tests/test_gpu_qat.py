@@ -113,39 +113,83 @@ def test_extreme_finite_values_without_nan(fbsr, oracle, fmt):
 
 @pytest.mark.parametrize("fmt", [E4M3, 3])
 def test_moments_at_the_limits_of_the_short_paths(fbsr, oracle, fmt):
-    """Second moments around 2^-96 and first moments around 2^-101: the limits below which the tile kernel leaves its
-    short division and its square root without rescaling for the full sequences.  The first eight tiles stay at or
-    above both limits (every wave on the short paths, the limits themselves included), the other eight mix in
-    values just below (the waves that meet one hand over).  Zero gradient, eps = 0 or negligible, and first moments
-    of the size of sqrt(v), so that the square root decides the update."""
-    n = 16 * 2048
-    half = n // 2
+    """The limits of the tile kernel's short paths.  Second moments: exponent fields 0 and 1 (zero, bf16 subnormals,
+    2^-126: the tabulated root reads zero, which an eps of 2^-28 or more must make exact), 2 and 3 (the smallest the
+    tables scale), around 233 (above it the corrected moment may overflow and the wave hands over).  First moments
+    around 2^-40, below which the wave hands over too.  Scalars: eps at its limit 2^-28 and at 1e-8, bias corrections
+    at both ends of [2^-20, 1], and an eps below the limit (the whole launch on the full sequences).  Zero gradient,
+    and first moments of the size of the denominator so that the quotient decides the update.  Tiles alternate
+    between staying inside every limit (each wave on the short paths) and mixing in values just outside."""
+    tiles = 24
+    n = tiles * 2048
     rng = np.random.default_rng(97 + fmt)
     finite8 = np.array([c for c in range(256) if np.isfinite(oracle.decode(c, fmt)) and abs(oracle.decode(c, fmt)) <= 4.0],
                        dtype=np.uint8)
     w8 = finite8[rng.integers(0, finite8.size, n)]
     g = rng.choice(np.array([0x0000, 0x8000], dtype=np.uint16), n)
 
-    def bf16_codes(exp_lo, exp_hi, count):      # positive, exponent uniform in [exp_lo, exp_hi], any significand
-        return ((127 + rng.integers(exp_lo, exp_hi + 1, count)).astype(np.uint16) << 7) | rng.integers(0, 128, count).astype(np.uint16)
-    v = bf16_codes(-95, -88, n)                  # beta2 v >= 0.95 * 2^-95 > 2^-96
-    v[:64] = (127 - 95) << 7                     # 2^-95 itself
-    v[half:] = np.where(rng.random(half) < 0.02, bf16_codes(-99, -96, half), v[half:])
-    # first moments of the size of sqrt(v) ~ 2^-47 in one block, around their own limit in the other
-    m = bf16_codes(-49, -45, n)
-    m[2048:4096] = bf16_codes(-100, -96, 2048)   # beta1 m >= 0.9 * 2^-100 > 2^-101
-    m[half + 2048:half + 4096] = bf16_codes(-104, -98, 2048)
+    def fields(lo, hi, count):      # positive bf16 codes, exponent field uniform in [lo, hi], any significand
+        return (rng.integers(lo, hi + 1, count).astype(np.uint16) << 7) | rng.integers(0, 128, count).astype(np.uint16)
+    v = np.empty(n, dtype=np.uint16)
+    m = np.empty(n, dtype=np.uint16)
+    for t in range(tiles):
+        a, b = t * 2048, (t + 1) * 2048
+        kind = t % 6
+        if kind == 0:      # fields 0..3: zero, subnormal, the smallest scaled values; the denominator is eps or near it
+            v[a:b] = fields(0, 3, 2048)
+            v[a:a + 256] = 0
+            m[a:b] = fields(127 - 32, 127 - 26, 2048)
+        elif kind == 1:    # the top of the tabulated range, inside
+            v[a:b] = fields(226, 233, 2048)
+            m[a:b] = fields(127 + 50, 127 + 62, 2048)
+        elif kind == 2:    # ... and across it (fields 234 and up overflow for the smallest correction, 255 is infinity)
+            v[a:b] = np.where(rng.random(2048) < 0.05, fields(234, 255, 2048) & 0xFF80, fields(226, 233, 2048))
+            m[a:b] = fields(127 + 50, 127 + 62, 2048)
+        elif kind == 3:    # first moments at and above 2^-40 with a denominator of eps
+            v[a:b] = 0
+            m[a:b] = fields(127 - 40, 127 - 34, 2048)
+            m[a:a + 64] = (127 - 40) << 7
+        elif kind == 4:    # ... and across it
+            v[a:b] = fields(0, 1, 2048)
+            m[a:b] = fields(127 - 44, 127 - 36, 2048)
+        else:              # the middle of everything
+            v[a:b] = fields(60, 140, 2048)
+            m[a:b] = fields(90, 130, 2048)
     m |= rng.integers(0, 2, n).astype(np.uint16) << 15
-    for params in ((0.5, 0.9, 0.999, 0.0, 0.01, 1 - 0.9, 1 - 0.999), (0.25, 0.9, 0.95, 1e-30, 0.0, 1 - 0.9 ** 3, 1 - 0.95 ** 3)):
+    lo = 2.0 ** -20
+    scalars = ((0.5, 0.9, 0.999, 2.0 ** -28, 0.01, 1 - 0.9, 1 - 0.999), (0.25, 0.9, 0.95, 1e-8, 0.0, 1 - 0.9 ** 3, 1 - 0.95 ** 3),
+               (0.125, 0.9, 0.999, 1e-6, 0.0, lo, lo), (0.5, 0.5, 0.75, 2.0 ** -28, 0.0, 1.0, 1.0),
+               (0.5, 0.9, 0.999, 2.0 ** -29, 0.01, 1 - 0.9, 1 - 0.999))
+    for params in scalars:
         for variant, nbits in ((RNE, 0), (SRFF, 3), (SRC, 4)):
-            print("case fmt=%d lr=%g variant=%d nbits=%d" % (fmt, params[0], variant, nbits), flush=True)
+            print("case fmt=%d lr=%g eps=%g corr=%g variant=%d nbits=%d" % (fmt, params[0], params[3], params[6], variant, nbits), flush=True)
             wd, gd, md, vd = dev(w8), dev(g), dev(m), dev(v)
             fbsr.fbsr_qat_adamw_step(wd, gd, md, vd, fmt, params, variant, nbits, seed=23, step=6, offset=0)
             ww, mm, vv = _oracle_step(oracle, w8, g, m, v, fmt, params, variant, nbits, 23, 6, 0)
-            assert np.count_nonzero(ww != w8) > n // 4, "the recipe leaves the weights where they are"
+            assert np.count_nonzero(ww != w8) > n // 8, "the recipe leaves the weights where they are"
             assert first_mismatch(host(md), mm) is None, "first moment"
             assert first_mismatch(host(vd), vv) is None, "second moment"
             assert first_mismatch(host(wd), ww) is None, "weights"
+
+
+def test_stream_probe_of_the_step_is_a_plain_exclusive_or(fbsr):
+    """The measurement aid in the step's launch shape: every word combined with the gradient's, nothing else touched,
+    and a second call restores the buffers."""
+    n = 5 * 2048
+    g = torch.randint(0, 1 << 16, (n,), dtype=torch.int32, device="cuda").to(torch.int16)
+    w = torch.randint(0, 256, (n + 16,), dtype=torch.int32, device="cuda").to(torch.uint8)
+    m = torch.randint(0, 1 << 16, (n + 16,), dtype=torch.int32, device="cuda").to(torch.int16)
+    v = torch.randint(0, 1 << 16, (n + 16,), dtype=torch.int32, device="cuda").to(torch.int16)
+    w0, m0, v0, g0 = w.clone(), m.clone(), v.clone(), g.clone()
+    fbsr.binding.fbsr_probe_stream75(w[:n], g, m[:n], v[:n])
+    assert torch.equal(g, g0) and torch.equal(w[n:], w0[n:]) and torch.equal(m[n:], m0[n:]) and torch.equal(v[n:], v0[n:])
+    assert torch.equal(m[:n], m0[:n] ^ g)
+    assert torch.equal(v[:n].view(-1, 8), v0[:n].view(-1, 8) ^ g.view(-1, 4, 2).flip(1).reshape(-1, 8))
+    assert not torch.equal(w[:n], w0[:n]) and bool((((w[:n] ^ w0[:n]) & 0xFE) == 0).all())
+    fbsr.binding.fbsr_probe_stream75(w[:n], g, m[:n], v[:n])
+    assert torch.equal(w, w0) and torch.equal(m, m0) and torch.equal(v, v0)
+    with pytest.raises(fbsr.FbsrError):
+        fbsr.binding.fbsr_probe_stream75(w[:100], g[:100], m[:100], v[:100])
 
 
 def test_unaligned_buffers(fbsr, oracle):
