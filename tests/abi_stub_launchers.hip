@@ -24,6 +24,9 @@ hipError_t launch_qat_adamw(uint8_t*, const uint16_t*, uint16_t*, uint16_t*, uin
 hipError_t launch_round_format8(const void*, int, uint8_t*, uint64_t, const Fmt8&, const Mode8&, uint64_t, uint64_t, hipStream_t) {
   return hipSuccess;
 }
+hipError_t launch_round_format16(const void*, int, uint16_t*, uint64_t, const Fmt8&, const Mode8&, uint64_t, uint64_t, hipStream_t) {
+  return hipSuccess;
+}
 hipError_t launch_stats(const float*, void*, uint64_t, int, int, int, uint64_t, uint64_t, uint64_t, uint64_t, uint32_t, double*,
                         double*, hipStream_t) {
   return hipSuccess;
