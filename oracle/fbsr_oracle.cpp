@@ -765,4 +765,37 @@ int oracle_round_format8(const void* x, int src, uint8_t* out, uint64_t n, const
   return 0;
 }
 
+// The statistics of oracle_bias_stats for a format given by its descriptor (fp32 inputs): per bin
+// {count, sum y, sum e, sum e^2} with y the Eq. (1) value of the rounded code under the descriptor and
+// e = (y - x) / ulp_t(x), ulp_t(x) = 2^(e~ - P + 1), e~ of Eq. (2) with the descriptor's B and no upper clamp;
+// ulp_t of a non-finite x is 1, as there.  out (one code per byte) may be null.
+// Returns 0 ok, 1 bad arguments, 3 an element falls outside [0, nbins).
+int oracle_bias_stats_format8(const float* x, uint8_t* out, uint64_t n, const int32_t* desc, int variant, int nbits,
+                              uint64_t seed, uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins,
+                              double* stats) {
+  Format8 g;
+  if (!get_format8(desc, &g) || !variant8_ok(variant, nbits) || group == 0) return 1;
+  if (n > 0) {
+    const uint64_t lo = offset / group, hi = (offset + n - 1) / group;
+    if (lo < first_bin || hi - first_bin >= nbins) return 3;
+  }
+  for (uint64_t j = 0; j < n; ++j) {
+    const uint64_t i = offset + j;
+    const uint64_t bin = i / group - first_bin;
+    const uint64_t r = variant_draws(variant) ? random_bits(seed, 0, i, nbits) : 0;
+    const uint32_t code = round_one8(x[j], g, variant, nbits, r);
+    if (out) out[j] = (uint8_t)code;
+    const double y = decode8(code, g);
+    const double a = std::fabs((double)x[j]);
+    const double ulp = std::isfinite(a) ? std::ldexp(1.0, rounding_exponent(a, g.f) - g.f.P + 1) : 1.0;
+    const double e = (y - (double)x[j]) / ulp;
+    double* s = stats + 4 * bin;
+    s[0] += 1.0;
+    s[1] += y;
+    s[2] += e;
+    s[3] += e * e;
+  }
+  return 0;
+}
+
 }  // extern "C"

@@ -92,6 +92,8 @@ def lib():
         L.oracle_sgd_update.restype = i32
         L.oracle_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp]
         L.oracle_bias_stats.restype = i32
+        L.oracle_bias_stats_format8.argtypes = [vp, vp, u64, vp, i32, i32, u64, u64, u64, u64, u32, vp]
+        L.oracle_bias_stats_format8.restype = i32
         _lib = L
     return _lib
 
@@ -210,6 +212,20 @@ def round_format8(x, src, desc, variant, nbits, seed, offset=0):
     if rc != 0:
         raise ValueError("oracle_round_format8: status %d" % rc)
     return out
+
+
+def bias_stats_format8(x, desc, variant, nbits, seed, offset, group, first_bin, nbins, stats=None, want_out=False):
+    """bias_stats for a format given by its descriptor: (stats[nbins,4], byte codes or None)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if stats is None:
+        stats = np.zeros((nbins, 4), dtype=np.float64)
+    assert stats.dtype == np.float64 and stats.shape == (nbins, 4) and stats.flags.c_contiguous
+    out = np.empty(x.size, dtype=np.uint8) if want_out else None
+    rc = lib().oracle_bias_stats_format8(_ptr(x), _ptr(out) if want_out else None, x.size, _ptr(_desc(desc)), variant, nbits,
+                                         seed, offset, group, first_bin, nbins, _ptr(stats))
+    if rc != 0:
+        raise ValueError("oracle_bias_stats_format8: status %d" % rc)
+    return stats, out
 
 
 def format16_check(desc):

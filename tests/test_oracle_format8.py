@@ -355,6 +355,89 @@ def test_bf16_to_binary8p4_closed_form_biases(oracle, N):
         assert err / (x.size << N) == want[variant], (variant, N)
 
 
+# ------------------------------------------------------------ per-bin statistics (Figs. 1-2) ----
+@pytest.mark.parametrize("fmt,d", [(1, E4M3), (2, E5M2)])
+def test_stats_under_an_ocp_descriptor_equal_the_fixed_format_statistics(oracle, fmt, d):
+    """The descriptor form of the per-bin statistics against the fixed-format one (pinned on its own): same codes,
+    same four sums bit for bit, on inputs from below the smallest subnormal to beyond M with NaN and infinities."""
+    rng = np.random.default_rng(61 + fmt)
+    x = np.concatenate([inputs_below_max(rng, d, 6000), rng.integers(0, 1 << 32, size=1500, dtype=np.uint32).view(np.float32),
+                        np.array([np.inf, -np.inf, np.nan, 0.0, -0.0], dtype=np.float32)])
+    for variant, nbits in ((RNE, 0), (SRFF, 2), (SRF, 3), (SRC, 3), (SRC, 11), (SRFF, 20)):
+        for group, offset in ((500, 0), (1 << 20, 12345), (7, 3), (500, 5000)):
+            first = offset // group
+            nbins = (offset + x.size - 1) // group - first + 1
+            a, ca = oracle.bias_stats_format8(x, d, variant, nbits, 9, offset, group, first, nbins, want_out=True)
+            b, cb = oracle.bias_stats(x, fmt, variant, nbits, 9, offset, group, first, nbins, want_out=True)
+            assert np.array_equal(ca, cb)
+            assert np.array_equal(a, b, equal_nan=True), (variant, nbits, group)
+
+
+@pytest.mark.parametrize("name", ["binary8p3", "binary8p4", "e2m3", "e2m1", "binary8p1", "binary8p7"])
+def test_stats_sums_are_the_exact_rational_sums(oracle, name):
+    """{count, sum y, sum e, sum e^2} per bin against sums of exact rationals: y from Eq. (1) on the returned code
+    (value_of above), ulp_t(x) = 2^(max(floor(log2 |x|), 1 - B) - P + 1) from Eq. (2) by integer arithmetic on x's
+    own fraction, e = (y - x) / ulp_t(x); normal and subnormal range, far below the smallest subnormal, both signs,
+    zeros, and the range above M of the formats that saturate (y = +-M)."""
+    d = ALL[name]
+    K, P, B, max_code, inf_code = d[:5]
+    M = value_of(max_code, d)
+    rng = np.random.default_rng(abs(hash(name)) % 1000)
+    group = 300
+    fM = float(M)
+    parts = [rng.uniform(2.0 ** (1 - B), fM, group), rng.uniform(2.0 ** (-B - P - 20), 2.0 ** (1 - B), group),
+             -np.exp(rng.uniform(np.log(2.0 ** (-B - P - 3)), np.log(fM), group)),
+             np.concatenate([np.zeros(5), -np.zeros(5), rng.uniform(2.0 ** -B, min(2.0 ** (3 - B), fM), group - 10)])]
+    if inf_code < 0:
+        parts.append(rng.uniform(fM, 8 * fM, group) * np.where(rng.integers(0, 2, group) == 1, -1.0, 1.0))
+    x = np.concatenate(parts).astype(np.float32)
+    nbins = len(parts)
+    for variant, nbits in ((SRFF, 2), (SRF, 3), (SRC, 3), (RNE, 0), (SRC_ODD, 4), (TA, 0)):
+        stats, out = oracle.bias_stats_format8(x, d, variant, nbits, 6, 0, group, 0, nbins, want_out=True)
+        for b in range(nbins):
+            sy = se = see = Fraction(0)
+            for j in range(b * group, (b + 1) * group):
+                xf = f32_fraction(x[j])
+                code = int(out[j])
+                mag = code & ((1 << (K - 1)) - 1)
+                assert mag <= max_code
+                y = value_of(mag, d) * (-1 if code >> (K - 1) else 1)
+                a = abs(xf)
+                lg = (a.numerator.bit_length() - a.denominator.bit_length()) if a else 1 - B
+                if a and Fraction(2) ** lg > a:
+                    lg -= 1
+                e = (y - xf) / Fraction(2) ** (max(lg, 1 - B) - P + 1)
+                sy, se, see = sy + y, se + e, see + e * e
+            assert stats[b, 0] == group
+            assert abs(stats[b, 1] - float(sy)) <= 1e-13 * abs(float(sy)), (name, variant, b)
+            assert abs(stats[b, 2] - float(se)) <= 1e-12 * max(abs(float(se)), 1.0), (name, variant, nbits, b)
+            assert abs(stats[b, 3] - float(see)) <= 1e-12 * float(see), (name, variant, nbits, b)
+
+
+def test_stats_of_bf16_values_into_binary8p4_give_the_closed_form_biases(oracle):
+    """Sec. III-E through the statistics entry: all bf16 values of [1, 2) (D = 4 excess bits for binary8p4) repeated
+    over many draws; the per-bin mean of e tends to (2^-D - 2^-N)/2 for SRFF, 2^-(D+1) for SRF and 0 for SRC."""
+    d, D, N = BINARY8P4, 4, 3
+    x = np.tile((np.arange(0x3F80, 0x4000, dtype=np.uint32) << 16).view(np.float32), 4096)
+    want = {SRFF: (2.0 ** -D - 2.0 ** -N) / 2, SRF: 2.0 ** -(D + 1), SRC: 0.0, SRC_ODD: 0.0}
+    for variant in DRAWING:
+        stats, _ = oracle.bias_stats_format8(x, d, variant, N, 3, 0, x.size, 0, 1)
+        assert stats[0, 0] == x.size
+        assert abs(stats[0, 2] / x.size - want[variant]) < 2e-3, (variant, stats[0, 2] / x.size)   # five standard errors
+        assert abs(stats[0, 1] / x.size - (1.5 - 2.0 ** -8 + want[variant] / 8)) < 2.5e-4
+
+
+def test_stats_reject_bad_arguments_and_elements_outside_the_bins(oracle):
+    x = np.ones(10, dtype=np.float32)
+    for bad in (lambda: oracle.bias_stats_format8(x, (9, 4, 7, 0x7E, -1, 0x7F, 1, 1), SRFF, 2, 1, 0, 5, 0, 2),
+                lambda: oracle.bias_stats_format8(x, BINARY8P4, SRFF, 0, 1, 0, 5, 0, 2),
+                lambda: oracle.bias_stats_format8(x, BINARY8P4, SRFF, 2, 1, 0, 0, 0, 2),
+                lambda: oracle.bias_stats_format8(x, BINARY8P4, SRFF, 2, 1, 0, 5, 0, 1),
+                lambda: oracle.bias_stats_format8(x, BINARY8P4, SRFF, 2, 1, 0, 5, 1, 2)):
+        with pytest.raises(ValueError):
+            bad()
+
+
 # --------------------------------------------------------------------------- array entry ----
 @pytest.mark.parametrize("src", [FROM_BF16, FROM_FP16, FROM_FP32])
 def test_array_call_is_the_per_element_rule(oracle, src):
