@@ -36,7 +36,7 @@ ALU_PEAK_LANE_OPS = 157.3e12 / 2
 COUNTERS_JSON = os.path.join(ROOT, "profiles", "kernel_counters.json")
 # The kernel each secondary path launches, as rocprofv3 names it (template arguments: round_tiles<fmt, variant, W>,
 # round16_tiles<src, fmt, variant, W>, format8_tiles<src, ties, W, 16-bit codes>, block_tiles<fmt, variant, W>,
-# format8_lut_tiles<src, W>, sgd_tiles<variant, W>, stats_spans<fmt, variant, W>, qat_tiles<codec, W>; fmt 0 bf16, 1 E4M3, 2 E5M2, 3 binary8p4;
+# format8_lut_tiles<src, W>, sgd_tiles<variant, W>, stats_spans<fmt, variant, W>, stats8_spans<W>, qat_tiles<codec, W>; fmt 0 bf16, 1 E4M3, 2 E5M2, 3 binary8p4;
 # variant 0 RNE, 1 SRFF, 2 SRF, 3 SRC; W the slot width).  The profile summary joins counters to paths through these.
 PATH_KERNELS = {
     "stream_4to1_no_arithmetic_ceiling": "fbsr::stream41_tiles", "stream_7to5_no_arithmetic_ceiling": "fbsr::stream75_tiles",
@@ -65,6 +65,7 @@ PATH_KERNELS = {
     "sgd_update_bf16_N2_srf": "fbsr::sgd_tiles<2, 2>", "sgd_update_bf16_N4_srf": "fbsr::sgd_tiles<2, 4>", "sgd_update_bf16_N8_srf": "fbsr::sgd_tiles<2, 8>",
     "bias_stats_e4m3_N3_srf": "fbsr::stats_spans<1, 2, 4>", "bias_stats_e4m3_N8_srf": "fbsr::stats_spans<1, 2, 8>",
     "bias_stats_bf16_N2_srf": "fbsr::stats_spans<0, 2, 2>", "bias_stats_bf16_N8_srf": "fbsr::stats_spans<0, 2, 8>",
+    "bias_stats_format8_binary8p4_N3_srf": "fbsr::stats8_spans<4>", "bias_stats_format8_binary8p4_N3_src": "fbsr::stats8_spans<4>",
 }
 N_ELEMS = 1 << 28
 SGD_ELEMS = 1 << 27
@@ -507,6 +508,14 @@ def main():
         for f, nb in ((fbsr.FMT_E4M3, 3), (fbsr.FMT_E4M3, 8), (fbsr.FMT_BF16, 2), (fbsr.FMT_BF16, 8)):
             ms = timed_launches(torch, lambda: stat(f, nb), 6)
             paths["bias_stats_%s_N%d_srf" % (target[f], nb)] = {"ms": round(ms, 4), "gb_s": round(4.0 * n / ms / 1e6, 1)}
+
+        # the same statistics with the target given by its descriptor (P3109 binary8p4, the format Sec. IV trains in)
+        def stat8(v, nb):
+            rot[0] += 1
+            fbsr.fbsr_bias_stats_format8(xs_[rot[0] % 2], p4, v, nb, 5, 0, group, 0, nbins, stats=stats, workspace=ws)
+        for v, nb, tag in ((fbsr.SRF, 3, "srf"), (fbsr.SRC, 3, "src")):
+            ms = timed_launches(torch, lambda: stat8(v, nb), 6)
+            paths["bias_stats_format8_binary8p4_N%d_%s" % (nb, tag)] = {"ms": round(ms, 4), "gb_s": round(4.0 * n / ms / 1e6, 1)}
         del xs_
 
     # every path names its kernel and its elements per launch; where the committed counter figures belong to the kernel

@@ -250,6 +250,17 @@ int fbsr_format8_check(const fbsr_format8* fmt);
 int fbsr_round_format8(const void* x, int src, void* out, uint64_t n, const fbsr_format8* fmt, int variant,
                        int nbits, uint64_t seed, uint64_t offset, void* stream);
 
+/* fbsr_bias_stats (the measurement behind Figs. 1 and 2, Sec. III) for a target format given by its descriptor and
+ * any rounding mode of fbsr_round_format8: per bin {count, sum y, sum e, sum e^2} with y the Eq. (1) value of the
+ * rounded code under the descriptor (infinity for the infinity code, NaN for a NaN code) and e = (y - x) / ulp_t(x),
+ * ulp_t(x) = 2^(e~ - P + 1), e~ = max(floor(log2 |x|), 1 - B) (Eq. (2)) with the descriptor's P and B.
+ * x: n fp32 values (device).  out: n codes, one per byte (device), or NULL.  fmt: HOST pointer, read during the call.
+ * nbits up to FBSR_MAX_NBITS_ROUND.  Bins, stats, workspace (fbsr_bias_stats_workspace_bytes), accumulation, the
+ * fixed summation order and the errors are those of fbsr_bias_stats; a bad descriptor or mode gives FBSR_EINVAL. */
+int fbsr_bias_stats_format8(const float* x, void* out, uint64_t n, const fbsr_format8* fmt, int variant, int nbits,
+                            uint64_t seed, uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins,
+                            double* stats, void* workspace, uint64_t workspace_bytes, void* stream);
+
 /* The same for formats of up to 16 bits (IEEE binary16 and any other (K, P, B; M) with K <= 16): one code per
  * 16-bit word of out (bits above K zero).  The descriptor is the struct above with width 2..16 and bias 0..127;
  * because an fp32 source drops 24 - P bits and the kernels keep 32 - K fraction bits beside a code, the precision must be

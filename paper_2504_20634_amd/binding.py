@@ -20,7 +20,7 @@ MAX_NBITS = 16            # the fused updates (SGD, QAT steps)
 MAX_NBITS_ROUND = 24      # every other entry point
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2", FMT_BINARY8P4: "binary8p4"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
-EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_round_format16", "fbsr_format16_check", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_static", "fbsr_bias_stats_workspace_bytes",
+EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_round_format16", "fbsr_format16_check", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_format8", "fbsr_bias_stats_static", "fbsr_bias_stats_workspace_bytes",
            "fbsr_probe_stream41", "fbsr_probe_stream75", "fbsr_strerror", "fbsr_version")
 
 
@@ -55,6 +55,8 @@ def lib():
         L.fbsr_sgd_update.restype = i32
         L.fbsr_bias_stats.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp, vp, u64, vp]
         L.fbsr_bias_stats.restype = i32
+        L.fbsr_bias_stats_format8.argtypes = [vp, vp, u64, vp, i32, i32, u64, u64, u64, u64, u32, vp, vp, u64, vp]
+        L.fbsr_bias_stats_format8.restype = i32
         L.fbsr_bias_stats_static.argtypes = [vp, vp, u64, i32, i32, i32, u64, u64, u64, u64, u32, vp, vp]
         L.fbsr_bias_stats_static.restype = i32
         L.fbsr_bias_stats_workspace_bytes.argtypes = [u64, u32]
@@ -308,6 +310,28 @@ def fbsr_bias_stats(x, fmt, variant, nbits, seed, offset, group, first_bin, nbin
                                  variant, nbits, seed, offset, group, first_bin, nbins,
                                  stats.data_ptr(), workspace.data_ptr(), wbytes,
                                  _stream_handle(stream)), "fbsr_bias_stats")
+    return stats, out
+
+
+def fbsr_bias_stats_format8(x, fmt, variant, nbits, seed, offset, group, first_bin, nbins, stats=None, out=None,
+                            workspace=None, stream=None):
+    """fbsr_bias_stats for a format given by its descriptor (a tuple as for fbsr_round_format8 or an fbsr_format8);
+    out: uint8 codes or None.  Returns (stats, out)."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    n = x.numel()
+    if stats is None:
+        stats = torch.zeros((nbins, 4), dtype=torch.float64, device=x.device)
+    assert stats.is_cuda and stats.dtype == torch.float64 and stats.is_contiguous() and stats.numel() == 4 * nbins
+    if workspace is None:
+        workspace = torch.empty((bias_stats_workspace_bytes(n, nbins) + 7) // 8, dtype=torch.float64, device=x.device)
+    if out is not None:
+        assert out.is_cuda and out.is_contiguous() and out.numel() == n and out.dtype == torch.uint8
+    f = _format8(fmt)
+    _check(lib().fbsr_bias_stats_format8(x.data_ptr(), out.data_ptr() if out is not None else None, n, ctypes.byref(f), variant,
+                                         nbits, seed, offset, group, first_bin, nbins, stats.data_ptr(), workspace.data_ptr(),
+                                         workspace.numel() * workspace.element_size(), _stream_handle(stream)),
+           "fbsr_bias_stats_format8")
     return stats, out
 
 

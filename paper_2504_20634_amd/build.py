@@ -10,8 +10,8 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libfbsr.so")
-SOURCES = ["fbsr_api.hip", "fbsr_block.hip", "fbsr_format8.hip", "fbsr_round.hip", "fbsr_round16.hip", "fbsr_qat.hip", "fbsr_sgd.hip", "fbsr_stats.hip"]
-HEADERS = ["fbsr_device.h", "fbsr_launch.h"]
+SOURCES = ["fbsr_api.hip", "fbsr_block.hip", "fbsr_format8.hip", "fbsr_round.hip", "fbsr_round16.hip", "fbsr_qat.hip", "fbsr_sgd.hip", "fbsr_stats.hip", "fbsr_stats8.hip"]
+HEADERS = ["fbsr_device.h", "fbsr_launch.h", "fbsr_stats_common.h"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # keep hipcc from forming packed-fp32 instructions out of scalar float code

@@ -345,6 +345,28 @@ int fbsr_bias_stats_static(const float* x, void* out, uint64_t n, int fmt, int v
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 
+int fbsr_bias_stats_format8(const float* x, void* out, uint64_t n, const fbsr_format8* fmt, int variant, int nbits,
+                            uint64_t seed, uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
+                            void* workspace, uint64_t workspace_bytes, void* stream) {
+  fbsr::Fmt8 f;
+  fbsr::Mode8 m;
+  if (fmt == nullptr || !derive_format8(*fmt, &f) || !derive_mode8(variant, nbits, FBSR_MAX_NBITS_ROUND, &m)) return FBSR_EINVAL;
+  if (n > fbsr::kMaxElems || offset > UINT64_MAX - n) return FBSR_EINVAL;
+  if (group == 0 || group > ((uint64_t)1 << 62)) return FBSR_EINVAL;
+  if (n == 0) return FBSR_OK;
+  if (x == nullptr || stats == nullptr || workspace == nullptr) return FBSR_EINVAL;
+  if (misaligned(x, 4) || misaligned(stats, 8) || misaligned(workspace, 8)) return FBSR_EALIGN;
+  const uint64_t bin_lo = offset / group, bin_hi = (offset + n - 1) / group;
+  if (bin_lo < first_bin || bin_hi - first_bin >= nbins) return FBSR_ERANGE;
+  if (workspace_bytes < fbsr_bias_stats_workspace_bytes(n, nbins)) return FBSR_ERANGE;
+  fbsr::Table8 t;
+  decode_table8(*fmt, &t);
+  const hipError_t e = fbsr::launch_stats_format8(x, reinterpret_cast<uint8_t*>(out), n, f, m, t, fmt->precision, fmt->bias, seed, offset, group,
+                                                  first_bin, stats, reinterpret_cast<double*>(workspace),
+                                                  reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
 int fbsr_probe_stream41(const float* x, void* out, uint64_t n, void* stream) {
   if (n > fbsr::kMaxElems || n % fbsr::kTileElems != 0) return FBSR_EINVAL;
   if (n == 0) return FBSR_OK;

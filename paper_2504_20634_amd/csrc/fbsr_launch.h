@@ -169,6 +169,16 @@ constexpr uint64_t kStaticMaxElems = (uint64_t)1 << 28;
 // Address of that array on the current device (looked up once per device).
 hipError_t static_scratch(double** ptr);
 
+// Adds the workspace records of the chunks that cover global indices [i0, i_end) to the caller's statistics (the
+// kernel that closes both statistics paths).
+hipError_t launch_stats_finalize(const double* records, uint64_t i0, uint64_t i_end, uint64_t group, uint64_t first_bin,
+                                 double* stats, hipStream_t stream);
+
+// The statistics for a format given by its descriptor; P and B are the descriptor's (for ulp_t).
+hipError_t launch_stats_format8(const float* x, uint8_t* out, uint64_t n, const Fmt8& f, const Mode8& m, const Table8& t,
+                                int P, int B, uint64_t seed, uint64_t offset, uint64_t group, uint64_t first_bin,
+                                double* stats, double* workspace, hipStream_t stream);
+
 hipError_t launch_stats(const float* x, void* out, uint64_t n, int fmt, int variant, int nbits, uint64_t seed,
                         uint64_t offset, uint64_t group, uint64_t first_bin, uint32_t nbins, double* stats,
                         double* workspace, hipStream_t stream);

@@ -11,6 +11,7 @@
 #include <type_traits>
 
 #include "fbsr_launch.h"
+#include "fbsr_stats_common.h"
 
 namespace fbsr {
 
@@ -45,48 +46,6 @@ template <int FMT> struct kSaturates { static constexpr bool value = FMT == kE4M
 constexpr uint32_t kSaturatedLimit = (uint32_t)(127 + 30) << 23;   // patterns below 2^30
 
 template <int FMT> struct SumYInFp32 { static constexpr bool value = FMT == kE4M3 || FMT == kP4; };
-
-// End of a bin in global indices, saturating (group may be as large as 2^62, so (bin + 1) * group can pass 2^64).
-__device__ __forceinline__ uint64_t bin_end(uint64_t bin, uint64_t group) {
-  const uint64_t k = bin + 1;
-  return __umul64hi(k, group) != 0 ? ~(uint64_t)0 : k * group;
-}
-
-// Sum over the wave in a fixed tree: quads, eights and sixteens by DPP, the rows of 16 by two exchanges through LDS
-// hardware.  Every lane ends with the same bits.
-__device__ __forceinline__ double wave_total(double v) {
-  auto dpp = [](double a, auto ctrl) {
-    constexpr int C = decltype(ctrl)::value;
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(a), C, 0xF, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(a), C, 0xF, 0xF, false);
-    return __hiloint2double(hi, lo);
-  };
-  v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
-  v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
-  v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
-  v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
-}
-
-// The 4 W random bits of four consecutive elements whose first has index e0 (a multiple of 4) in the bit string
-// `strip` holds (element e at bit e W), right-aligned in a 64-bit word.
-template <int W>
-__device__ __forceinline__ uint64_t read_row_bits(const uint4* strip, int e0) {
-  const unsigned char* base = reinterpret_cast<const unsigned char*>(strip);
-  if constexpr (W == 16) {
-    return *reinterpret_cast<const uint64_t*>(base + e0 * 2);
-  } else if constexpr (W == 8) {
-    return *reinterpret_cast<const uint32_t*>(base + e0);
-  } else if constexpr (W == 4) {
-    return *reinterpret_cast<const uint16_t*>(base + e0 / 2);
-  } else if constexpr (W == 2) {
-    return base[e0 / 4];
-  } else {
-    return (uint32_t)(base[e0 / 8] >> (e0 & 4)) & 0xFu;
-  }
-}
 
 // A lane's running sums for the bin its wave is in.  The integer part serves the elements rounded by round_fast
 // (e as an integer multiple of 2^-FRAC: a lane adds at most 64 of them, each below 2^FRAC in magnitude, before its
@@ -664,15 +623,8 @@ hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, 
     e = launch_spans_w<FMT, VAR>(W, x + head, out ? o + head * osize : nullptr, npairs, nbits, seed,
                                  i0 / (uint64_t)(128 / W), i0, group, first_bin, workspace, stats, stream);
     if (e != hipSuccess) return e;
-    const uint64_t i_end = i0 + npairs * kStatsPairElems;
-    const uint64_t bin_lo = i0 / group, bin_hi = (i_end - 1) / group;
-    for (uint64_t at = 0; at <= bin_hi - bin_lo; at += kMaxElemsPerLaunch) {
-      const uint64_t m = bin_hi - bin_lo + 1 - at < kMaxElemsPerLaunch ? bin_hi - bin_lo + 1 - at : kMaxElemsPerLaunch;
-      hipLaunchKernelGGL(stats_finalize, dim3((unsigned)m), dim3(64), 0, stream, workspace, i0, i_end, group, bin_lo + at,
-                         first_bin, stats);
-      e = hipGetLastError();
-      if (e != hipSuccess) return e;
-    }
+    e = launch_stats_finalize(workspace, i0, i0 + npairs * kStatsPairElems, group, first_bin, stats, stream);
+    if (e != hipSuccess) return e;
   }
   const uint64_t done = head + npairs * kStatsPairElems;
   return launch_bins<FMT, VAR>(x + done, out ? o + done * osize : nullptr, n - done, nbits, W, seed, offset + done,
@@ -691,6 +643,19 @@ hipError_t run_v(int variant, const float* x, void* out, uint64_t n, int nbits, 
 }
 
 }  // namespace
+
+hipError_t launch_stats_finalize(const double* records, uint64_t i0, uint64_t i_end, uint64_t group, uint64_t first_bin,
+                                 double* stats, hipStream_t stream) {
+  const uint64_t bin_lo = i0 / group, bin_hi = (i_end - 1) / group;
+  for (uint64_t at = 0; at <= bin_hi - bin_lo; at += kMaxElemsPerLaunch) {
+    const uint64_t m = bin_hi - bin_lo + 1 - at < kMaxElemsPerLaunch ? bin_hi - bin_lo + 1 - at : kMaxElemsPerLaunch;
+    hipLaunchKernelGGL(stats_finalize, dim3((unsigned)m), dim3(64), 0, stream, records, i0, i_end, group, bin_lo + at, first_bin,
+                       stats);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
 
 // Workspace for callers that cannot allocate one: a fixed array in the library's device image.  Every GPU the
 // library runs on holds its own copy at its own address for the life of the process.  In host code the array's

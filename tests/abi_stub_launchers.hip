@@ -31,6 +31,10 @@ hipError_t launch_stats(const float*, void*, uint64_t, int, int, int, uint64_t, 
                         double*, hipStream_t) {
   return hipSuccess;
 }
+hipError_t launch_stats_format8(const float*, uint8_t*, uint64_t, const Fmt8&, const Mode8&, const Table8&, int, int, uint64_t,
+                                uint64_t, uint64_t, uint64_t, double*, double*, hipStream_t) {
+  return hipSuccess;
+}
 hipError_t static_scratch(double** ptr) {
   static double none[1];
   *ptr = none;
