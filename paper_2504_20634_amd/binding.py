@@ -21,7 +21,7 @@ MAX_NBITS_ROUND = 24      # every other entry point
 FMT_NAMES = {FMT_BF16: "bf16", FMT_E4M3: "e4m3", FMT_E5M2: "e5m2", FMT_BINARY8P4: "binary8p4"}
 VARIANT_NAMES = {RNE: "rne", SRFF: "srff", SRF: "srf", SRC: "src"}
 EXPORTS = ("fbsr_round", "fbsr_round_from16", "fbsr_round_format8", "fbsr_round_format16", "fbsr_format16_check", "fbsr_format8_named", "fbsr_format8_check", "fbsr_qat_adamw_step_format8", "fbsr_round_block_scaled", "fbsr_qat_adamw_step", "fbsr_sgd_update", "fbsr_bias_stats", "fbsr_bias_stats_format8", "fbsr_bias_stats_static", "fbsr_bias_stats_workspace_bytes",
-           "fbsr_probe_stream41", "fbsr_probe_stream75", "fbsr_strerror", "fbsr_version")
+           "fbsr_probe_stream41", "fbsr_probe_stream75", "fbsr_check_qat_division", "fbsr_check_qat_root", "fbsr_strerror", "fbsr_version")
 
 
 class FbsrError(RuntimeError):
@@ -77,6 +77,10 @@ def lib():
         L.fbsr_probe_stream41.restype = i32
         L.fbsr_probe_stream75.argtypes = [vp, vp, vp, vp, u64, vp]
         L.fbsr_probe_stream75.restype = i32
+        L.fbsr_check_qat_division.argtypes = [vp, vp, u64, vp, vp]
+        L.fbsr_check_qat_division.restype = i32
+        L.fbsr_check_qat_root.argtypes = [ctypes.c_float, vp, vp]
+        L.fbsr_check_qat_root.restype = i32
         L.fbsr_strerror.argtypes = [i32]
         L.fbsr_strerror.restype = ctypes.c_char_p
         L.fbsr_version.argtypes = []
@@ -214,6 +218,22 @@ def fbsr_probe_stream75(w8, g16, m16, v16, stream=None):
     assert all(t.numel() == n and t.element_size() == 2 for t in (g16, m16, v16))
     _check(lib().fbsr_probe_stream75(w8.data_ptr(), g16.data_ptr(), m16.data_ptr(), v16.data_ptr(), n, _stream_handle(stream)),
            "fbsr_probe_stream75")
+
+
+def fbsr_check_qat_division(num, den, counts, stream=None):
+    """Device self-check: counts[0] += pairs where the fused step's short division differs from num / den."""
+    import torch
+    assert num.is_cuda and den.is_cuda and num.dtype == torch.float32 and den.dtype == torch.float32 and num.numel() == den.numel()
+    assert num.is_contiguous() and den.is_contiguous() and counts.is_cuda and counts.dtype == torch.int64 and counts.numel() == 2
+    _check(lib().fbsr_check_qat_division(num.data_ptr(), den.data_ptr(), num.numel(), counts.data_ptr(), _stream_handle(stream)),
+           "fbsr_check_qat_division")
+
+
+def fbsr_check_qat_root(bias_corr2, counts, stream=None):
+    """Device self-check: counts[1] += second-moment codes whose tabulated root differs from sqrt(v / bias_corr2)."""
+    import torch
+    assert counts.is_cuda and counts.dtype == torch.int64 and counts.numel() == 2
+    _check(lib().fbsr_check_qat_root(float(bias_corr2), counts.data_ptr(), _stream_handle(stream)), "fbsr_check_qat_root")
 
 
 SCALE_BLOCK = 32

@@ -388,6 +388,29 @@ int fbsr_probe_stream75(void* w8, const void* g16, void* m16, void* v16, uint64_
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }
 
+int fbsr_check_qat_division(const float* num, const float* den, uint64_t count, uint64_t* counts, void* stream) {
+  if (count > fbsr::kMaxElems) return FBSR_EINVAL;
+  if (count == 0) return FBSR_OK;
+  if (num == nullptr || den == nullptr || counts == nullptr) return FBSR_EINVAL;
+  if (misaligned(num, 4) || misaligned(den, 4) || misaligned(counts, 8)) return FBSR_EALIGN;
+  const hipError_t e = fbsr::launch_check_division(num, den, count, reinterpret_cast<unsigned long long*>(counts),
+                                                   reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
+int fbsr_check_qat_root(float bias_corr2, uint64_t* counts, void* stream) {
+  if (counts == nullptr || !(bias_corr2 >= 0x1p-20f && bias_corr2 <= 1.0f)) return FBSR_EINVAL;
+  if (misaligned(counts, 8)) return FBSR_EALIGN;
+  fbsr::AdamWScalars sc = {};
+  sc.bias_corr1 = 1.0f;
+  sc.bias_corr2 = bias_corr2;
+  sc.eps = 1e-8f;
+  fbsr::derive_adamw(&sc);
+  const hipError_t e = fbsr::launch_check_corrected_root(sc, reinterpret_cast<unsigned long long*>(counts),
+                                                         reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
+}
+
 const char* fbsr_strerror(int status) {
   switch (status) {
     case FBSR_OK: return "ok";

@@ -135,6 +135,10 @@ hipError_t launch_qat_adamw_format8(uint8_t* w8, const uint16_t* g16, uint16_t* 
                                     const Fmt8& f, const Mode8& m, const Table8& t, const AdamWScalars& p, uint64_t seed,
                                     uint64_t step, uint64_t offset, hipStream_t stream);
 
+// Device self-checks of the fused step's short arithmetic (fbsr_measure.h).
+hipError_t launch_check_division(const float* num, const float* den, uint64_t count, unsigned long long* counts, hipStream_t stream);
+hipError_t launch_check_corrected_root(const AdamWScalars& p, unsigned long long* counts, hipStream_t stream);
+
 hipError_t launch_qat_adamw(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t n, int fmt,
                             const AdamWScalars& p, int variant, int nbits, uint64_t seed, uint64_t step,
                             uint64_t offset, hipStream_t stream);

@@ -77,11 +77,12 @@ __device__ __forceinline__ float qat_update(float w, float mq, float vq, const A
 // 2^-40: the reciprocal approximation, one Newton step on it, the quotient and two residual corrections of it, then
 // v_div_fixup_f32 for the sign of a zero quotient and for an infinite or NaN operand.  These are the operations of the
 // full division sequence without its pre-scaling of the operands (v_div_scale_f32, and the rescaling inside
-// v_div_fmas_f32), which exists to keep the intermediates of extreme operands in range and changes nothing when they
+// v_div_fmas_f32), which exists to keep the intermediates of extreme operands in range and changes no bit when they
 // are: on this domain no reciprocal, quotient or residual leaves the normal range unless the quotient itself
-// overflows, and then the result is an infinity or a NaN as in the full sequence or a NaN that sends the wave to the
-// exact path.  A NaN d gives a NaN.  (On a CPU, with every reciprocal start within one ulp: equal to the division on
-// 8 x 10^8 operand pairs of this domain drawn to favour all-ones and all-zeros significands.)
+// overflows, and then the result is the same infinity, or a NaN that sends the wave to the exact path.  A NaN d gives
+// a NaN.  Checked on a CPU from every reciprocal start within one ulp (tests/unscaled_division_check.c; the one start
+// no such sequence survives -- an all-ones divisor significand with the start below the rounded reciprocal -- is not
+// what v_rcp_f32 returns), and on the device against the division itself (fbsr_check_qat_division).
 __device__ __forceinline__ float div_in_range(float n, float d) {
   const float r0 = __builtin_amdgcn_rcpf(d);
   const float e = __fmaf_rn(-d, r0, 1.0f);
@@ -373,6 +374,33 @@ __global__ __launch_bounds__(kThreads) void stream75_tiles(uint8_t* __restrict__
   *reinterpret_cast<u32x4*>(v16 + g0) = vq;
 }
 
+// Device self-checks of the two identities the tile kernel's update arithmetic rests on (the same device functions,
+// run on the part at hand): counts[0] counts the operand pairs for which div_in_range differs from the division
+// (a NaN from div_in_range counts as agreement: the tile kernel then recomputes), counts[1] the second-moment codes
+// for which the tabulated root differs from sqrtf(v / bias_corr2) (a NaN from the table likewise).
+__global__ __launch_bounds__(kThreads) void check_division(const float* __restrict__ num, const float* __restrict__ den, uint64_t count,
+                                                           unsigned long long* __restrict__ counts) {
+  const uint64_t k = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (k >= count) return;
+  const float n = num[k], d = den[k];
+  const float got = div_in_range(n, d), want = n / d;
+  if (got == got && __float_as_uint(got) != __float_as_uint(want)) atomicAdd(counts, 1ull);
+}
+
+__global__ __launch_bounds__(kThreads) void check_corrected_root(AdamWScalars p, unsigned long long* __restrict__ counts) {
+  __shared__ RootTables roots;
+  fill_root_tables(&roots, threadIdx.x, p);
+  __syncthreads();
+  const uint32_t pair = ((uint32_t)blockIdx.x << 8 | threadIdx.x) * 0x00010001u;   // the same code in both halves
+  const float v = bf16_hi(pair);
+  const float want = sqrtf(v / p.bias_corr2);
+  const float lo = root_of_corrected<0>(&roots, pair), hi = root_of_corrected<1>(&roots, pair);
+  const bool tiny = (pair & 0x7F800000u) < 0x01000000u;   // exponent field 0 or 1: the table reads zero, the root is below 2^-52
+  const bool ok_lo = lo != lo || (tiny ? (lo == 0.0f && want < 0x1p-52f) : __float_as_uint(lo) == __float_as_uint(want));
+  const bool ok_hi = hi != hi || (tiny ? (hi == 0.0f && want < 0x1p-52f) : __float_as_uint(hi) == __float_as_uint(want));
+  if (!ok_lo || !ok_hi) atomicAdd(counts + 1, 1ull);
+}
+
 // One thread per element: any alignment, any offset, ragged heads and tails.
 template <class CODEC>
 __global__ __launch_bounds__(kThreads) void qat_elems(uint8_t* __restrict__ w8, const uint16_t* __restrict__ g16,
@@ -456,6 +484,18 @@ hipError_t run_v(int variant, uint8_t* w8, const uint16_t* g16, uint16_t* m16, u
 }
 
 }  // namespace
+
+hipError_t launch_check_division(const float* num, const float* den, uint64_t count, unsigned long long* counts, hipStream_t stream) {
+  return in_pieces(count, kMaxElemsPerLaunch, [&](uint64_t at, uint64_t m) {
+    hipLaunchKernelGGL(check_division, elems_grid(m), dim3(kThreads), 0, stream, num + at, den + at, m, counts);
+    return hipGetLastError();
+  });
+}
+
+hipError_t launch_check_corrected_root(const AdamWScalars& p, unsigned long long* counts, hipStream_t stream) {
+  hipLaunchKernelGGL(check_corrected_root, dim3(256), dim3(kThreads), 0, stream, p, counts);
+  return hipGetLastError();
+}
 
 hipError_t launch_stream75(uint8_t* w8, const uint16_t* g16, uint16_t* m16, uint16_t* v16, uint64_t ntiles, hipStream_t stream) {
   return in_pieces(ntiles, kMaxTilesPerLaunch, [&](uint64_t t0, uint64_t count) {

@@ -7,6 +7,8 @@ namespace fbsr {
 
 hipError_t launch_round(const float*, void*, uint64_t, int, int, int, uint64_t, uint64_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_stream41(const float*, uint8_t*, uint64_t, hipStream_t) { return hipSuccess; }
+hipError_t launch_check_division(const float*, const float*, uint64_t, unsigned long long*, hipStream_t) { return hipSuccess; }
+hipError_t launch_check_corrected_root(const AdamWScalars&, unsigned long long*, hipStream_t) { return hipSuccess; }
 hipError_t launch_stream75(uint8_t*, const uint16_t*, uint16_t*, uint16_t*, uint64_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_round_from16(const void*, void*, uint64_t, int, int, int, int, uint64_t, uint64_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_sgd(void*, const float*, uint64_t, float, int, int, uint64_t, uint64_t, uint64_t, hipStream_t) { return hipSuccess; }

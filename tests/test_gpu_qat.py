@@ -172,6 +172,43 @@ def test_moments_at_the_limits_of_the_short_paths(fbsr, oracle, fmt):
             assert first_mismatch(host(wd), ww) is None, "weights"
 
 
+def test_short_division_and_tabulated_root_on_the_device(fbsr):
+    """The tile kernel's own device functions against the plain operations, on the GPU at hand: its division without
+    operand scaling on 2^26 operand pairs drawn to favour all-ones and all-zeros significands plus every pairing of an
+    all-ones divisor significand with a power-of-two numerator (the operands on which a reciprocal one ulp low would
+    show), and its two-table root of the corrected second moment on all 65536 codes for 300 correction values."""
+    rng = np.random.default_rng(5)
+    n = 1 << 26
+    md = rng.integers(0, 1 << 23, n, dtype=np.uint32)
+    mn = rng.integers(0, 1 << 23, n, dtype=np.uint32)
+    kind = rng.integers(0, 8, n)
+    md = np.where(kind == 0, 0x7FFFFF - rng.integers(0, 4, n, dtype=np.uint32), md)
+    md = np.where(kind == 1, rng.integers(0, 4, n, dtype=np.uint32), md)
+    mn = np.where(kind == 2, mn & 0x7F0000, mn)
+    mn = np.where(kind == 3, 0, mn)
+    ed = rng.integers(-28, 65, n)
+    en = np.minimum(rng.integers(-40, 101, n), ed + 126)        # the quotient stays finite
+    den = (((ed + 127).astype(np.uint32) << 23) | md.astype(np.uint32)).view(np.float32)
+    num = (((en + 127).astype(np.uint32) << 23) | mn.astype(np.uint32) | (rng.integers(0, 2, n).astype(np.uint32) << 31)).view(np.float32)
+    num[::1001] = 0.0
+    num[1::1001] = -0.0
+    dd, nn = np.meshgrid(np.arange(-28, 65), np.arange(-40, 101), indexing="ij")
+    ok = (nn - dd) <= 126
+    grid_d = ((dd[ok] + 127).astype(np.uint32) << 23)[:, None] | (0x7FFFFF - np.arange(8, dtype=np.uint32))[None, :]
+    grid_n = np.broadcast_to(((nn[ok] + 127).astype(np.uint32) << 23)[:, None], grid_d.shape)
+    den = np.concatenate([den, grid_d.reshape(-1).view(np.float32), grid_d.reshape(-1).view(np.float32)])
+    num = np.concatenate([num, grid_n.reshape(-1).view(np.float32), -grid_n.reshape(-1).view(np.float32)])
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    fbsr.binding.fbsr_check_qat_division(dev(num), dev(den), counts)
+    corrections = [1.0, 2.0 ** -20, 1 - 0.999, 1 - 0.95 ** 3, float(np.float32(0.1))]
+    corrections += [float(c) for c in np.exp(rng.uniform(np.log(2.0 ** -20), 0.0, 295)).astype(np.float32)]
+    for c in corrections:
+        fbsr.binding.fbsr_check_qat_root(c, counts)
+    assert counts.tolist() == [0, 0], counts.tolist()
+    with pytest.raises(fbsr.FbsrError):
+        fbsr.binding.fbsr_check_qat_root(2.0, counts)
+
+
 def test_stream_probe_of_the_step_is_a_plain_exclusive_or(fbsr):
     """The measurement aid in the step's launch shape: every word combined with the gradient's, nothing else touched,
     and a second call restores the buffers."""
