@@ -117,7 +117,8 @@ def main():
     n = bench["config"]["elements"]
     tag = "2p%d" % (n.bit_length() - 1)
     prog = "python3 bench.py " + args.bench_args
-    pre = "cd /tmp && export TMPDIR=/tmp && cd $GRAFT_REPO_ROOT && "
+    pre = "TMPDIR=/tmp "          # the commands are run from the repository root
+    out_dir = {k: os.path.relpath(getattr(args, k), ROOT) if getattr(args, k) else "<dir>" for k in ("kt", "fetch", "write", "sq", "busy")}
     os.makedirs(args.out, exist_ok=True)
     figures = {"sources_sha256": bench_module.kernel_sources_hash(), "program": prog, "elements": n}
 
@@ -136,7 +137,7 @@ def main():
     head_avg = sum(stats[k]["avg_us"] for k in head if k in stats) / max(1, sum(1 for k in head if k in stats))
     with open(os.path.join(args.out, "bench_%s_kernel_trace.md" % tag), "w") as fh:
         fh.write("# rocprofv3 --kernel-trace --stats of bench.py, 2^%d elements (MI355X, gfx950)\n\nCommand:\n\n" % (n.bit_length() - 1))
-        fh.write("    %srocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof_kt -o kt \\\n        -- %s\n\n" % (pre, prog))
+        fh.write("    %srocprofv3 --kernel-trace --stats --output-format csv -d %s -o kt \\\n        -- %s\n\n" % (pre, out_dir["kt"], prog))
         fh.write("Durations in microseconds.  `bench us` is bench.py's own HIP-event timing of the same launches in the same run\n"
                  "(events include the gap between launches, so they read a few us above the trace); GB/s = algorithmic bytes\n"
                  "per launch / the trace's mean duration.  Kernels with no bench line are warm-up or helper launches.\n\n")
@@ -168,8 +169,8 @@ def main():
         figures["traffic_bytes"] = {l: int(round(traffic[k])) for k in traffic for l in entries[k]["labels"] if l in bench.get("paths", {})}
         with open(os.path.join(args.out, "kernels_%s_hbm_traffic.md" % tag), "w") as fh:
             fh.write("# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: every kernel bench.py times, 2^%d elements (2^27 for the fused updates)\n\n" % (n.bit_length() - 1))
-            fh.write("Commands (one counter per run):\n\n    %srocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/prof_fetch -o f \\\n        -- %s --copy-probe\n" % (pre, prog))
-            fh.write("    ... the same with --pmc WRITE_SIZE -d gpurun_out/prof_write -o w\n\n")
+            fh.write("Commands (one counter per run):\n\n    %srocprofv3 --pmc FETCH_SIZE --output-format csv -d %s -o f \\\n        -- %s --copy-probe\n" % (pre, out_dir["fetch"], prog))
+            fh.write("    ... the same with --pmc WRITE_SIZE -d %s -o w\n\n" % out_dir["write"])
             fh.write("Counters (KiB per dispatch) scaled by what they read for the plain 1 GiB device copy of the same run\n"
                      "(FETCH_SIZE x %.5f, WRITE_SIZE x %.5f), mean per launch.  Algorithmic KiB: inputs once, outputs once\n"
                      "(what bench.py's GB/s figures count).\n\n" % (f_scale, w_scale))
@@ -203,8 +204,8 @@ def main():
                         figures["valu_busy_pct"][l] = round(b, 1)
         with open(os.path.join(args.out, "kernels_%s_valu_counters.md" % tag), "w") as fh:
             fh.write("# rocprofv3 --pmc SQ instruction counters per kernel: bench.py, 2^%d elements (MI355X, gfx950)\n\nCommands:\n\n" % (n.bit_length() - 1))
-            fh.write("    %srocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_LDS SQ_WAVES --output-format csv -d gpurun_out/prof_sq -o sq \\\n        -- %s\n" % (pre, prog))
-            fh.write("    ... and, in a run of its own, --pmc VALUBusy -d gpurun_out/prof_busy -o b\n\n")
+            fh.write("    %srocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_LDS SQ_WAVES --output-format csv -d %s -o sq \\\n        -- %s\n" % (pre, out_dir["sq"], prog))
+            fh.write("    ... and, in a run of its own, --pmc VALUBusy -d %s -o b\n\n" % out_dir["busy"])
             fh.write("VALU/elem = SQ_INSTS_VALU x 64 lanes / elements per launch: one-lane vector operations per element, idle lanes of\n"
                      "an issued instruction included.  T lane-ops/s = VALU/elem x elements / the kernel-trace mean duration; the\n"
                      "ceiling bench.py prices it against is 78.6 T/s (the chip's 157.3 TFLOP/s of fp32 FMA at two flops each); plain\n"
