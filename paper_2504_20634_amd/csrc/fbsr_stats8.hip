@@ -9,7 +9,13 @@
 // a fixed tree over the wave when a bin ends -> the four waves in order -> one record per chunk for a bin that
 // continues next door, added up by the same finalizing kernel).  What differs is the element: round8 with the
 // descriptor's constants as kernel arguments, the code's value from a 256-entry table in LDS, and the error in fp64
-// for every element (no integer shortcuts).
+// for every element -- except on "plain" rows, which are most rows of ordinary data: when a wave's row lies in one
+// bin and holds only values with |x| <= M that are zero or at least 2^(1 - B - P) (no NaN, nothing above M, no bits
+// lost below the code space), the code-space word is exact and is formed without selects: the normal map of
+// max(|x|, 2^(1 - B)) plus the truncated subnormal map of min(|x|, 2^(1 - B)) minus the word both give at the split.
+// The error is then the integer (r & ~mask) - r0 in units of 2^-24 ulp, in magnitude space (its sign flipped for a
+// negative x by an exclusive or with the sign mask and one correction sum); a lane adds at most 64 of them before
+// its wave closes the span, so 32 bits hold their sum and 64 bits the sum of their squares exactly.
 #include "fbsr_launch.h"
 #include "fbsr_stats_common.h"
 
@@ -28,6 +34,11 @@ struct Stats8Args {
   Fmt8 f;
   Mode8 m;
   uint32_t min_field, top;   // of inv_ulp8
+  // the plain rows' integer path (see stats8_spans): the pattern of 2^(1 - B - P), below which a target-subnormal value
+  // loses bits to the truncation; -(rebias << shift_p) - 2^(23 + P); 2^(23 + P), the code-space word of 2^(1 - B)
+  uint32_t u_exact, map_add;
+  float split;
+  uint32_t plain_ok;         // 0: the format or the mode rules the integer path out (P = 1, more than 16 random bits)
 };
 
 // The code of one element: any pattern, any bit count the entry point accepts.
@@ -70,26 +81,28 @@ __global__ __launch_bounds__(kThreads) void stats8_spans(const float* __restrict
   uint4* strip = strips[wave];
 
   double sy = 0.0, se = 0.0, see = 0.0;
+  int32_t se_i = 0, neg_i = 0;   // plain rows: sum of e_int ^ s and of s, s = -1 for a negative x and 0 otherwise
+  long long see_i = 0;
   int slot = my_rows > 0 ? (int)(span_lo / group - bin_first) : 0;
   uint64_t next_bin = my_rows > 0 ? group - span_lo % group : 0;   // span-relative index at which the next bin starts
 
   auto close_bin = [&]() {
-    const double t0 = wave_total(sy), t1 = wave_total(se), t2 = wave_total(see);
+    constexpr double kUnit = 1.0 / (double)(1 << 24);
+    const double t0 = wave_total(sy), t1 = wave_total(se + (double)(se_i - neg_i) * kUnit);
+    const double t2 = wave_total(see + (double)see_i * (kUnit * kUnit));
     if (lane == 0) {
       part[wave][slot][0] = t0; part[wave][slot][1] = t1; part[wave][slot][2] = t2;
     }
     slot += 1;
     sy = se = see = 0.0;
+    se_i = neg_i = 0;
+    see_i = 0;
   };
 
   const float* xs = x + (span_lo - i0);
   if (my_rows > 0) {
-    f32x4 ahead = load_stream4(xs + 4 * lane);
-#pragma unroll 1
-    for (int r = 0; r < my_rows; ++r) {
-      const f32x4 v = ahead;
-      const int nr = r + 1 < my_rows ? r + 1 : r;   // past the end the last row is read again and dropped
-      ahead = load_stream4(xs + (nr * 256 + 4 * lane));
+    // one row of the span: its random integers, then the plain or the general way
+    auto do_row = [&](int r, const f32x4& v) {
       uint32_t n[4] = {0, 0, 0, 0};
       if constexpr (MANY) {
         uint32_t o[4];
@@ -112,6 +125,38 @@ __global__ __launch_bounds__(kThreads) void stats8_spans(const float* __restrict
         for (int j = 0; j < 4; ++j) n[j] = slot_bits<WW>(rb, j, a.m.nbits);
       }
       const uint32_t b[4] = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+      const int lo_e = r * 256, hi_e = lo_e + 256;   // the row's elements in the span
+      if (a.plain_ok != 0u && next_bin >= (uint64_t)hi_e) {
+        const uint32_t u0 = b[0] & 0x7FFFFFFFu, u1 = b[1] & 0x7FFFFFFFu, u2 = b[2] & 0x7FFFFFFFu, u3 = b[3] & 0x7FFFFFFFu;
+        const uint32_t top = max(max(u0, u1), max(u2, u3));
+        const uint32_t low = min(min(u0 - 1u, u1 - 1u), min(u2 - 1u, u3 - 1u));   // a zero wraps to the largest value
+        if (!__any(top > a.f.u_max || low < a.u_exact - 1u)) {
+          uint32_t mag[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t u = b[j] & 0x7FFFFFFFu;
+            const uint32_t normal_part = (max(u, a.f.u_sub) << a.f.shift_p) + a.map_add;
+            const uint32_t sub_part = (uint32_t)fminf(__uint_as_float(u) * a.f.sub_scale, a.split);
+            const uint32_t r0 = normal_part + sub_part;
+            uint32_t add = (n[j] << a.m.shift) + a.m.fixed;
+            if (a.m.ties) add += ((r0 >> a.m.shift) & 1u) ^ a.m.tie_xor;
+            const uint32_t sum = r0 + add;
+            mag[j] = sum >> 24;
+            const int32_t e_int = (int32_t)((sum & 0xFF000000u) - r0);
+            const int32_t sgn = (int32_t)b[j] >> 31;
+            se_i += e_int ^ sgn;
+            neg_i += sgn;
+            see_i += (long long)e_int * (long long)e_int;
+            sy += (double)__uint_as_float(__float_as_uint(value_of[mag[j]]) | (b[j] & 0x80000000u));
+          }
+          if (out != nullptr) {
+            reinterpret_cast<uint32_t*>(out)[(span_lo - i0) / 4 + (uint64_t)(r * 64 + lane)] =
+                pack4_bytes(finish8<false>(mag[0], b[0], a.f), finish8<false>(mag[1], b[1], a.f), finish8<false>(mag[2], b[2], a.f),
+                            finish8<false>(mag[3], b[3], a.f));
+          }
+          return;
+        }
+      }
       uint32_t c[4];
       double y[4], e[4];
 #pragma unroll
@@ -124,7 +169,6 @@ __global__ __launch_bounds__(kThreads) void stats8_spans(const float* __restrict
         reinterpret_cast<uint32_t*>(out)[(span_lo - i0) / 4 + (uint64_t)(r * 64 + lane)] = pack4_bytes(c[0], c[1], c[2], c[3]);
       }
       // the bins of this row's elements [lo_e, lo_e + 256) of the span
-      const int lo_e = r * 256, hi_e = lo_e + 256;
       auto add_some = [&](int first, int last) {   // the row's elements whose index in the row lies in [first, last)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -144,6 +188,22 @@ __global__ __launch_bounds__(kThreads) void stats8_spans(const float* __restrict
         next_bin += group;
       }
       add_some(from, 256);
+    };
+    // two rows per trip, the next two loaded before these are worked on (past the end the last pair is read again
+    // and dropped: a load that may or may not have been issued would make the compiler wait for all of them)
+    f32x4 ahead[kRows];
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(xs + (k * 256 + 4 * lane));
+#pragma unroll 1
+    for (int r = 0; r < my_rows; r += kRows) {
+      f32x4 v[kRows];
+#pragma unroll
+      for (int k = 0; k < kRows; ++k) v[k] = ahead[k];
+      const int nr = r + kRows < my_rows ? r + kRows : r;
+#pragma unroll
+      for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(xs + ((nr + k) * 256 + 4 * lane));
+#pragma unroll
+      for (int k = 0; k < kRows; ++k) do_row(r + k, v[k]);
     }
     close_bin();
   }
@@ -245,6 +305,10 @@ hipError_t launch_stats_format8(const float* x, uint8_t* out, uint64_t n, const 
   a.m = m;
   a.min_field = (uint32_t)(1 - B + 127) << 23;
   a.top = (uint32_t)(1023 + P - 1 + 127) << 20;
+  a.u_exact = (uint32_t)(1 - B - P + 127) << 23;
+  a.map_add = 0u - (f.rebias << f.shift_p) - ((uint32_t)1 << (23 + P));
+  a.split = (float)((uint32_t)1 << (23 + P));
+  a.plain_ok = f.unit_lsb == 0u && m.nbits <= (uint32_t)kMaxTileNbits && 1 - B - P + 127 >= 1 ? 1u : 0u;
   const int W = m.nbits ? slot_width((int)m.nbits) : 0;
   const Split s = split_range(n, offset, W ? W : 8, W == 0, reinterpret_cast<uintptr_t>(x), 4, 16, reinterpret_cast<uintptr_t>(out),
                               1, 4, 0, 0, 1, kStatsPairElems);

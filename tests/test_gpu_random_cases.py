@@ -111,7 +111,7 @@ def test_random_calls(fbsr, oracle, run_seed):
             P = int(rng.integers(1, 8)); d = (8, P, 1 << (7 - P), 0x7E, 0x7F, 0x80, 0, 0)
             if rng.random() < 0.3: d = (8, 4, 7, 0x7E, -1, 0x7F, 1, 1)
             variant = int(rng.integers(0, 7))
-            x = workloads.full_range(n + 8, "e4m3", seed=c, specials_every=int(rng.choice([0, 997])))
+            x = workloads.full_range(n + 8, "e4m3", seed=c, specials_every=int(rng.choice([0, 997]))) if rng.random() < 0.5 else workloads.scaled_normal(n + 8, seed=c)
             group = int(rng.choice([1, 7, 100, 512, 2048, 5000, 1 << 14, 1 << 20]))
             if n == 0: continue
             first_bin = offset // group; nbins = (offset + n - 1) // group - first_bin + 1

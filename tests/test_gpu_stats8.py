@@ -43,6 +43,35 @@ def test_groups_of_every_size(fbsr, oracle, name):
             _run_both(fbsr, oracle, x, d, variant, nbits, 6, offset, group, first_bin, nbins, with_out=(group in (7, 5000, 513)))
 
 
+@pytest.mark.parametrize("name", ["binary8p4", "binary8p3", "ocp_e4m3", "ocp_e5m2", "ocp_e2m3", "ocp_e2m1", "binary8p7", "bias96", "k2"])
+def test_rows_of_ordinary_values_take_the_integer_path(fbsr, oracle, name):
+    """Every row holds only values with |x| <= M that are zero or at least 2^(1 - B - P) -- normal and subnormal
+    targets mixed, both signs, zeros, M itself, the smallest value without lost bits -- so the kernel's integer path
+    serves them (a row that a bin boundary cuts, and the rows of the last block, which hold values one step outside
+    either limit, go the general way)."""
+    d = FORMATS[name]
+    K, P, B, mx = d[:4]
+    t_max = mx & ((1 << (P - 1)) - 1)
+    M = np.float32((1.0 + t_max * 2.0 ** (1 - P)) * 2.0 ** ((mx >> (P - 1)) - B)) if (mx >> (P - 1)) else np.float32(t_max * 2.0 ** (2 - P - B))
+    lo = np.float32(2.0 ** (1 - B - P))
+    rng = np.random.default_rng(K * 100 + P)
+    n = 6 * 16384
+    mag = np.exp(rng.uniform(np.log(float(lo)), np.log(float(M)), n)).astype(np.float32)
+    mag = np.clip(mag, lo, M)
+    mag[::97] = 0.0
+    mag[1::97] = M
+    mag[2::97] = lo
+    x = (mag * np.where(rng.integers(0, 2, n) == 1, np.float32(-1), np.float32(1))).astype(np.float32)
+    x[5 * 16384::64] = np.nextafter(M, np.float32(np.inf))
+    x[5 * 16384 + 1::64] = np.nextafter(lo, np.float32(0))
+    for variant, nbits in ((SRFF, 2), (SRF, 3), (SRC, 3), (SRC_ODD, 4), (RNE, 0), (RNO, 0), (RNA, 0), (SRC, 16), (SRFF, 9)):
+        for group, offset in ((1 << 14, 0), (5000, 0), (20000, 64)):
+            first_bin = offset // group
+            nbins = (offset + n - 1) // group - first_bin + 1
+            print("case fmt=%s variant=%d nbits=%d group=%d offset=%d" % (name, variant, nbits, group, offset), flush=True)
+            _run_both(fbsr, oracle, x, d, variant, nbits, 4, offset, group, first_bin, nbins, with_out=(group == 5000))
+
+
 def test_under_ocp_descriptors_the_fixed_format_statistics_come_back(fbsr):
     """E4M3 and E5M2 by descriptor against fbsr_bias_stats with the format ids: same codes, sums equal to the last
     few bits (two kernels, two summation orders)."""
