@@ -21,7 +21,7 @@ WATCHERS = {'srf_half_term_dropped': 'exhaustive_round_up_counts and 2-0', 'srff
             'qat8_step_not_in_key': 'qat_step_structure_in_binary8p4', 'qat8_nan_becomes_max': 'qat_step_structure_in_binary8p4',
             'qat_eps_inside_the_root': 'eps_outside_the_root', 'stats_ulp_not_clamped_for_subnormals': 'exact_rational_sums',
             'stats8_ulp_ignores_the_descriptors_bias': 'stats_under_an_ocp_descriptor or test_oracle_format8 and exact_rational_sums',
-            'stats8_first_bin_ignored': 'stats_under_an_ocp_descriptor', 'stats8_error_sign': 'test_oracle_format8 and exact_rational_sums',
+            'stats8_first_bin_ignored': 'stats_under_an_ocp_descriptor', 'stats8_sum_y_takes_the_input': 'test_oracle_format8 and exact_rational_sums', 'stats8_error_sign': 'test_oracle_format8 and exact_rational_sums',
             'stats_sum_y_takes_the_input': 'exact_rational_sums'}
 
 MUTATIONS = [
@@ -58,7 +58,10 @@ MUTATIONS = [
     ("qat_eps_inside_the_root", "mh / (std::sqrt(vh) + a.eps)", "mh / std::sqrt(vh + a.eps)"),
     ("stats_ulp_not_clamped_for_subnormals", "return std::ldexp(1.0, rounding_exponent(a, f) - f.P + 1);",
      "return std::ldexp(1.0, std::ilogb(a) - f.P + 1);"),
-    ("stats_sum_y_takes_the_input", "    s[1] += y;\n    s[2] += e;", "    s[1] += (double)x[j];\n    s[2] += e;"),
+    ("stats_sum_y_takes_the_input", "oracle_ulp(x[j], fmt);\n    double* s = stats + 4 * bin;\n    s[0] += 1.0;\n    s[1] += y;",
+     "oracle_ulp(x[j], fmt);\n    double* s = stats + 4 * bin;\n    s[0] += 1.0;\n    s[1] += (double)x[j];"),
+    ("stats8_sum_y_takes_the_input", "/ ulp;\n    double* s = stats + 4 * bin;\n    s[0] += 1.0;\n    s[1] += y;",
+     "/ ulp;\n    double* s = stats + 4 * bin;\n    s[0] += 1.0;\n    s[1] += (double)x[j];"),
     ("stats8_ulp_ignores_the_descriptors_bias", "std::ldexp(1.0, rounding_exponent(a, g.f) - g.f.P + 1) : 1.0;",
      "std::ldexp(1.0, std::ilogb(a == 0.0 ? 1.0 : a) - g.f.P + 1) : 1.0;"),
     ("stats8_first_bin_ignored", "const uint64_t bin = i / group - first_bin;\n    const uint64_t r = variant_draws(variant)",
