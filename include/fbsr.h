@@ -66,11 +66,12 @@ typedef enum {
   FBSR_EDEVICE = 4  /* the HIP runtime reported an error at launch                               */
 } fbsr_status;
 
-/* Largest nbits.  Every entry point but the fused updates (fbsr_round, fbsr_round_from16, fbsr_round_format8,
- * fbsr_round_block_scaled, fbsr_bias_stats) takes up to FBSR_MAX_NBITS_ROUND, which covers every
+/* Largest nbits.  Every entry point but the fused updates and the 16-bit-code one (fbsr_round, fbsr_round_from16,
+ * fbsr_round_format8, fbsr_round_block_scaled, fbsr_bias_stats, fbsr_bias_stats_format8) takes up to
+ * FBSR_MAX_NBITS_ROUND, which covers every
  * bit an fp32 source can drop towards an 8-bit target (D = 20 for E4M3 and binary8p4, 21 for E5M2), so that nbits >= D
- * gives classical SR; calls with more than FBSR_MAX_NBITS bits use 32-bit slots (4 elements per Philox block) and a
- * slower rounding that keeps 32 fraction bits.  The fused updates take up to FBSR_MAX_NBITS: their rounding drops at
+ * gives classical SR; calls with more than FBSR_MAX_NBITS bits use 32-bit slots (4 elements per Philox block), where
+ * the generator's cost per element is four times that of 8-bit slots.  The fused updates take up to FBSR_MAX_NBITS: their rounding drops at
  * most 16 bits of a normal result (fp32 -> bf16 in fbsr_sgd_update, a bf16 sum -> 8 bits in the QAT steps), so 16
  * bits already are classical SR there. */
 #define FBSR_MAX_NBITS 16
