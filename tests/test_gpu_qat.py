@@ -88,7 +88,8 @@ def test_extreme_finite_values_without_nan(fbsr, oracle, fmt):
         return code | (rng.integers(0, 2, n).astype(np.uint16) << 15) if signed else code
     g, m, v = raw(True), raw(True), raw(False)
     # signed zeros everywhere (the sign of a zero moment can reach the sign of a zero weight), and moments around
-    # 2^-103, where the kernel's short division by the bias corrections hands over to the full one
+    # 2^-103: far below the limits of the kernel's short paths (first moments below 2^-40 hand the wave over to the
+    # full division; second moments below 2^-125 read a zero root), next to ordinary values in the same waves
     k = 512
     g[:k] = rng.choice(np.array([0x0000, 0x8000], dtype=np.uint16), k)
     m[:k] = rng.choice(np.array([0x0000, 0x8000], dtype=np.uint16), k)
