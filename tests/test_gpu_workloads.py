@@ -217,7 +217,8 @@ def test_workload4_sgd_1000_steps_drift(fbsr):
 def test_other_entry_points_at_bench_sizes(fbsr, oracle):
     """The paths bench.py times beside the headline, at its sizes (2^28 elements; 2^27 for the fused steps), each
     compared with the oracle on 24 sampled windows of 2^14: narrow-source, block-scaled, generic-format rounding
-    (P3109 binary8p4 from fp32 and from bf16) and both fused QAT steps."""
+    (P3109 binary8p4 from fp32 and from bf16, the latter through the table kernel), the flavours with more than 16
+    random bits, binary16 as a target, the statistics by descriptor (28 sampled bins) and both fused QAT steps."""
     from paper_2504_20634_amd import workloads
     n = 1 << 28
     width = 1 << 14
@@ -241,7 +242,38 @@ def test_other_entry_points_at_bench_sizes(fbsr, oracle):
         out = fbsr.fbsr_round_format8(datad, src, p4, variant, nbits, seed=2)
         for s in wins:
             assert first_mismatch(host(out[s:s + width]), oracle.round_format8(data[s:s + width], src, p4, variant, nbits, 2, s)) is None, s
-    del out, xd, x16d
+    print("case more than 16 bits", flush=True)
+    for fmt, variant, nbits in ((E4M3, SRFF, 20), (E4M3, SRC, 24)):
+        out = fbsr.fbsr_round(xd, fmt, variant, nbits, seed=2)
+        for s in wins:
+            assert first_mismatch(host(out[s:s + width]), oracle.round_(x[s:s + width], fmt, variant, nbits, seed=2, offset=s)) is None, s
+    out = fbsr.fbsr_round_from16(x16d, 0, E4M3, SRFF, 20, seed=2)
+    for s in wins:
+        assert first_mismatch(host(out[s:s + width]), oracle.round_from16(x16[s:s + width], 0, E4M3, SRFF, 20, seed=2, offset=s)) is None, s
+    out = fbsr.fbsr_round_format8(xd, 2, p4, SRFF, 20, seed=2)
+    for s in wins:
+        assert first_mismatch(host(out[s:s + width]), oracle.round_format8(x[s:s + width], 2, p4, SRFF, 20, 2, s)) is None, s
+    out, sc = fbsr.fbsr_round_block_scaled(xd, E4M3, SRFF, 20, seed=2)
+    for s in wins:
+        wc, wsc = oracle.round_block_scaled(x[s:s + width], E4M3, SRFF, 20, seed=2, offset=s)
+        assert first_mismatch(host(out[s:s + width]), wc) is None and first_mismatch(host(sc[s // 32:(s + width) // 32]), wsc) is None, s
+    print("case binary16 target", flush=True)
+    b16 = (16, 11, 15, 0x7BFF, 0x7C00, 0x7E00, 1, 1)
+    for variant, nbits in ((SRC, 3), (SRF, 8)):
+        out = fbsr.fbsr_round_format16(xd, 2, b16, variant, nbits, seed=2)
+        for s in wins:
+            assert first_mismatch(host(out[s:s + width]), oracle.round_format16(x[s:s + width], 2, b16, variant, nbits, 2, s)) is None, s
+    print("case statistics by descriptor", flush=True)
+    group = 1 << 18
+    xs, _ = workloads.log_bins(n // group, group, seed=5)
+    xsd = dev(xs)
+    for variant, nbits in ((SRF, 3), (SRC, 3)):
+        stats, _ = fbsr.fbsr_bias_stats_format8(xsd, p4, variant, nbits, 5, 0, group, 0, n // group)
+        got = stats.cpu().numpy()
+        for b in range(0, n // group, 37):       # 28 of the 1024 bins, subnormal and above-M bins among them
+            want, _ = oracle.bias_stats_format8(xs[b * group:(b + 1) * group], p4, variant, nbits, 5, b * group, group, b, 1)
+            assert_stats_close(got[b:b + 1], want)
+    del out, xd, x16d, xsd
     nq = 1 << 27
     w8 = (workloads.sgd_weights(nq, seed=40) & 0x7777).view(np.uint8)[:nq].copy()
     g16 = workloads.sgd_weights(nq, seed=50)
