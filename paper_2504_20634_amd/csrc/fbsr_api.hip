@@ -65,7 +65,7 @@ bool derive_format8(const fbsr_format8& d, fbsr::Fmt8* f, int max_width = 8) {
   f->nan_sign = (!has_nan || d.nan_signed != 0) ? (uint32_t)sign_bit : 0u;
   f->sign_bit = (uint32_t)sign_bit;
   f->sign_shift = (uint32_t)(32 - K);
-  f->zero_sign = d.neg_zero != 0 ? (uint32_t)sign_bit : 0u;
+  f->sign_carry = d.neg_zero != 0 ? (uint32_t)sign_bit : (uint32_t)sign_bit - 1u;
   f->unit_lsb = P == 1 ? (1u << frac) : 0u;
   return true;
 }

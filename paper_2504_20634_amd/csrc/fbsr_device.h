@@ -644,7 +644,8 @@ struct Fmt8 {
   uint32_t nan_sign;    // the sign bit if a NaN input keeps its sign, else 0
   uint32_t sign_bit;    // 1 << (K - 1)
   uint32_t sign_shift;  // 32 - K: (pattern >> sign_shift) & sign_bit is the code's sign
-  uint32_t zero_sign;   // the sign bit if the format has -0, else 0
+  uint32_t sign_carry;  // sign_bit with -0, sign_bit - 1 without: (mag + sign_carry) & sign_bit tells whether a
+                        // magnitude code keeps its sign (every code but a zero without -0), as mag < sign_bit
   uint32_t unit_lsb;    // 1 << 24 when P = 1 (the significand's last place is the implicit one), else 0
   uint32_t frac;        // fraction bits of the code space: 24 for K <= 8; 32 - K for the 16-bit-code entry point
   int32_t sub_exp;      // frac - 2 + B + P: a target-subnormal |x| maps to trunc(|x| * 2^sub_exp)
@@ -670,8 +671,8 @@ struct Mode8 {
 template <bool CHECKED>
 __device__ __forceinline__ uint32_t finish8(uint32_t mag, uint32_t bits, const Fmt8& f) {
   mag = mag > f.max_code ? f.over_code : mag;
+  uint32_t code = mag | ((bits >> f.sign_shift) & (mag + f.sign_carry) & f.sign_bit);
   const uint32_t sgn = (bits >> f.sign_shift) & f.sign_bit;
-  uint32_t code = mag | (mag == 0u ? (sgn & f.zero_sign) : sgn);
   if constexpr (CHECKED) code = (bits & 0x7FFFFFFFu) > 0x7F800000u ? (f.nan_code | (sgn & f.nan_sign)) : code;
   return code;
 }

@@ -214,8 +214,7 @@ __global__ __launch_bounds__(kLutThreads) void format8_lut_tiles(const uint16_t*
           const uint32_t entry = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(lut) + at[j]);
           const uint32_t t = entry + (n[j] << m.shift);
           const uint32_t mag = min(t >> 24, cap);
-          const uint32_t sgn = (words[j >> 1] >> ((j & 1) ? f.sign_shift : sign_lo)) & f.sign_bit;
-          c[j] = mag | (mag == 0u ? (sgn & f.zero_sign) : sgn);
+          c[j] = mag | ((words[j >> 1] >> ((j & 1) ? f.sign_shift : sign_lo)) & (mag + f.sign_carry) & f.sign_bit);
         }
       }
       if (tile < ntiles) {
