@@ -61,6 +61,7 @@ bool derive_format8(const fbsr_format8& d, fbsr::Fmt8* f, int max_width = 8) {
   f->det_add = (1u << (frac - 1)) - 1u + m_odd;
   f->max_code = (uint32_t)d.max_code;
   f->over_code = (uint32_t)(has_inf ? d.inf_code : d.max_code);
+  f->remap_over = has_inf && d.inf_code != d.max_code + 1 ? 1u : 0u;
   f->nan_code = (uint32_t)(has_nan ? d.nan_code : d.max_code);
   f->nan_sign = (!has_nan || d.nan_signed != 0) ? (uint32_t)sign_bit : 0u;
   f->sign_bit = (uint32_t)sign_bit;
@@ -104,7 +105,7 @@ bool derive_mode8(int variant, int nbits, int max_nbits, fbsr::Mode8* m, uint32_
   const uint32_t half = m->shift >= 1u ? 1u << (m->shift - 1) : 0u;   // half of the last kept place
   m->tie_xor = (variant == FBSR_SRC_TIES_ODD || variant == FBSR_RNO) ? 1u : 0u;
   m->ties = variant == FBSR_RNE || variant == FBSR_RNO || variant == FBSR_SRC || variant == FBSR_SRC_TIES_ODD;
-  m->fixed = m->ties ? half - 1u : (variant == FBSR_SRF || variant == FBSR_RNA) ? half : 0u;
+  m->fixed = m->ties ? (half != 0u ? half - 1u : 0u) : (variant == FBSR_SRF || variant == FBSR_RNA) ? half : 0u;
   return true;
 }
 

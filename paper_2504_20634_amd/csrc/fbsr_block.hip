@@ -47,6 +47,8 @@ __global__ __launch_bounds__(kThreads) void block_tiles(const float* __restrict_
   }
   constexpr bool MANY = W == 32;   // more than 16 random bits: 32-bit slots
   const Addends a = make_addends<FMT, VAR>(MANY ? kMaxTileNbits : nbits);
+  ManyAddends many = {a, 0.0f};
+  if constexpr (MANY && VAR != kRNE) many = make_many_addends<FMT, VAR>(nbits);
   HwAddends hw = {0, 0, 0, 0};
   if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
 #pragma unroll
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void block_tiles(const float* __restrict_
         uint32_t r[4] = {0, 0, 0, 0};
         if constexpr (MANY) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) r[j] = round_pattern_wide<FMT, VAR>(b[j], n4[j], (uint32_t)nbits);
+          for (int j = 0; j < 4; ++j) r[j] = round_pattern_many<FMT, VAR, false>(b[j], n4[j], (uint32_t)nbits, many);
         }
         packed = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);
       }

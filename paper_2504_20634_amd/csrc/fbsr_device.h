@@ -306,6 +306,68 @@ __device__ __forceinline__ uint32_t round_pattern_wide(uint32_t bits, uint32_t n
   }
 }
 
+// The same rounding for N = 17 .. 24 in the 24-bit code space of the main path (the tile kernels; any pattern).  A
+// target-normal |x| is exact there, and so is the addend n << (24 - N).  A target-subnormal |x| may lose bits to the
+// truncation, all of them below the code space's last place; an addend made of whole last places cannot carry out of
+// them, which settles SRFF for every N and SRF up to N = 23.  What is left takes the subnormal position from a float
+// product of its own (exact: a power-of-two scale) in units of the random grid, delta~ 2^N plus the whole part:
+//   SRF, N = 24   floor(pos + 1/2) = (trunc(2 pos) + 1) >> 1, as  pos + n + 1/2 >= k  <=>  floor(pos + 1/2) + n >= k;
+//   SRC           Round(pos) of Eq. (7) is the hardware's round-to-nearest-even of that product.
+struct ManyAddends {
+  Addends a;          // for N itself: shift = 24 - N, fixed and tie_mask 0 where the shift is 0
+  float grid_scale;   // SUB_SCALE 2^-shift: a target-subnormal |x| times this is its position on the random grid
+};
+
+template <int FMT, int VAR>
+__device__ __forceinline__ ManyAddends make_many_addends(int nbits) {
+  ManyAddends w;
+  if constexpr (Fx<FMT>::kIsFp8) {
+    w.a = make_addends<FMT, VAR>(nbits);
+    w.grid_scale = __builtin_amdgcn_ldexpf(Fx<FMT>::SUB_SCALE, -(int)w.a.shift);
+  } else {
+    w.a = make_addends<FMT, VAR>(16);   // bf16: see round_pattern_wide
+    w.grid_scale = 0.0f;
+  }
+  return w;
+}
+
+template <int FMT, int VAR, bool CHECKED>
+__device__ __forceinline__ uint32_t round_pattern_many(uint32_t bits, uint32_t n, uint32_t N, const ManyAddends& w) {
+  typedef Fx<FMT> F;
+  static_assert(VAR != kRNE, "nearest-even draws no bits");
+  if constexpr (!F::kIsFp8) {
+    return round_pattern<FMT, VAR, CHECKED>(bits, n >> (N - 16u), w.a);
+  } else {
+    const Addends& a = w.a;
+    const uint32_t u = bits & 0x7FFFFFFFu;
+    const uint32_t uc = u < F::U_CLAMP ? u : F::U_CLAMP;
+    const uint32_t normal = (uc << F::S) - (F::Q << (23 + F::S));
+    const float ax = fabsf(__uint_as_float(bits));
+    uint32_t in_normal = normal, in_sub;
+    if constexpr (VAR == kSRFF) {
+      in_sub = (uint32_t)(ax * F::SUB_SCALE);
+    } else if constexpr (VAR == kSRF) {
+      in_normal = normal + a.fixed;
+      const float scaled = ax * F::SUB_SCALE;
+      if (a.shift == 0u) in_sub = ((uint32_t)(scaled + scaled) + 1u) >> 1;   // uniform over the launch
+      else in_sub = (uint32_t)scaled + a.fixed;
+    } else {
+      in_normal = normal + a.fixed + ((normal >> a.shift) & a.tie_mask);
+      in_sub = (uint32_t)rintf(ax * w.grid_scale) << a.shift;
+    }
+    uint32_t r0 = u < F::U_SUB ? in_sub : in_normal;
+    uint32_t add = n << a.shift;
+    if constexpr (F::kDetRegion) {
+      const bool above = u > F::U_MAXFIN;
+      r0 = above ? normal : r0;
+      add = above ? F::DET_ADD : add;
+    }
+    uint32_t r = r0 + add;
+    if constexpr (CHECKED) r = u > 0x7F800000u ? F::NAN_FX : r;
+    return with_sign<FMT>(r, bits);
+  }
+}
+
 // True when round_pattern<.., CHECKED = false> is not allowed for this pattern.
 template <int FMT>
 __device__ __forceinline__ bool needs_checked(uint32_t u_max) {
@@ -646,6 +708,7 @@ struct Fmt8 {
   uint32_t sign_shift;  // 32 - K: (pattern >> sign_shift) & sign_bit is the code's sign
   uint32_t sign_carry;  // sign_bit with -0, sign_bit - 1 without: (mag + sign_carry) & sign_bit tells whether a
                         // magnitude code keeps its sign (every code but a zero without -0), as mag < sign_bit
+  uint32_t remap_over;  // 1 when over_code is neither max_code nor the code after it, else 0
   uint32_t unit_lsb;    // 1 << 24 when P = 1 (the significand's last place is the implicit one), else 0
   uint32_t frac;        // fraction bits of the code space: 24 for K <= 8; 32 - K for the 16-bit-code entry point
   int32_t sub_exp;      // frac - 2 + B + P: a target-subnormal |x| maps to trunc(|x| * 2^sub_exp)
@@ -666,22 +729,67 @@ struct Mode8 {
   bool srf;             // the mode adds half a step of the random grid (SRF)
 };
 
+// A rounded magnitude code above max_code becomes the infinity's.  The clamp of |x| keeps every rounded magnitude at
+// or below max_code + 1 (a saturating format's at or below max_code), which is where most formats have their
+// infinity: only one that lies elsewhere needs the exchange (uniform over the launch).
+__device__ __forceinline__ uint32_t cap8(uint32_t mag, const Fmt8& f) {
+  if (f.remap_over != 0u) mag = mag > f.max_code ? f.over_code : mag;
+  return mag;
+}
+
+// cap8 on four codes behind ONE branch (the empty statement keeps the compiler from turning the branch into
+// selects, which would cost every format what only the rare one needs).
+__device__ __forceinline__ void cap8x4(uint32_t (&g)[4], const Fmt8& f) {
+  if (f.remap_over != 0u) {
+    asm volatile("");
+#pragma unroll
+    for (int j = 0; j < 4; ++j) g[j] = g[j] > f.max_code ? f.over_code : g[j];
+  }
+}
+
 // From the rounded magnitude code to the output byte: codes above M become the infinity (or M, saturating),
 // the sign goes on (a zero keeps it only in formats with -0), a NaN input becomes the NaN code.
 template <bool CHECKED>
-__device__ __forceinline__ uint32_t finish8(uint32_t mag, uint32_t bits, const Fmt8& f) {
-  mag = mag > f.max_code ? f.over_code : mag;
-  uint32_t code = mag | ((bits >> f.sign_shift) & (mag + f.sign_carry) & f.sign_bit);
+__device__ __forceinline__ uint32_t signed8(uint32_t capped_mag, uint32_t bits, const Fmt8& f) {
+  uint32_t code = capped_mag | ((bits >> f.sign_shift) & (capped_mag + f.sign_carry) & f.sign_bit);
   const uint32_t sgn = (bits >> f.sign_shift) & f.sign_bit;
   if constexpr (CHECKED) code = (bits & 0x7FFFFFFFu) > 0x7F800000u ? (f.nan_code | (sgn & f.nan_sign)) : code;
   return code;
 }
 
-// The part of round8's sum that the element's random integer does not enter: the code-space pattern of |x| plus the
-// mode's fixed addend and tie bit, or, above M (*above set; no randomness there, Sec. II), plus the nearest-even addend
-// alone.  The sum stays below 2^32: the pattern is below (max_code + 2) 2^frac and an addend below 2^frac.
+template <bool CHECKED>
+__device__ __forceinline__ uint32_t finish8(uint32_t mag, uint32_t bits, const Fmt8& f) {
+  return signed8<CHECKED>(cap8(mag, f), bits, f);
+}
+
+__device__ __forceinline__ uint32_t pack4_bytes(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+  const uint32_t lo = __builtin_amdgcn_perm(c1, c0, 0x0c0c0400u);   // [c0.b0, c1.b0, 0, 0]
+  const uint32_t hi = __builtin_amdgcn_perm(c3, c2, 0x04000c0cu);   // [0, 0, c2.b0, c3.b0]
+  return lo | hi;
+}
+
+// finish8 (less its NaN case) on four bytes at once.  tops: the top bytes of the four source patterns, element 0 in
+// the low byte; mags4: the four capped magnitude codes likewise.  Every magnitude code is below the sign bit and the
+// carry at most the sign bit, so no byte's sum reaches into the next.
+__device__ __forceinline__ uint32_t with_signs4(uint32_t mags4, uint32_t tops, const Fmt8& f) {
+  const uint32_t signs = (tops >> (f.sign_shift - 24u)) & (f.sign_bit * 0x01010101u);
+  return mags4 | (signs & (mags4 + f.sign_carry * 0x01010101u));
+}
+
+// The top bytes of four fp32 patterns, element 0 in the low byte.
+__device__ __forceinline__ uint32_t top_bytes4(const uint32_t (&b)[4]) {
+  const uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0703u);   // [b0.b3, b1.b3, 0, 0]
+  const uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], 0x07030c0cu);   // [0, 0, b2.b3, b3.b3]
+  return lo | hi;
+}
+
+// round8's sum: the code-space pattern of |x| plus the mode's fixed addend, its tie bit and random_part = n << shift,
+// or, above M (*above set; no randomness there, Sec. II), plus the nearest-even addend alone.  With random_part = 0 it
+// is the part of the sum that the element's random integer does not enter.  The sum stays below 2^32: the pattern is
+// below (max_code + 2) 2^frac and the addends together below 2^frac.
 template <bool TIES, bool WIDE>
-__device__ __forceinline__ uint32_t round8_fixed_part(uint32_t bits, const Fmt8& f, const Mode8& m, bool* above) {
+__device__ __forceinline__ uint32_t round8_fixed_part(uint32_t bits, const Fmt8& f, const Mode8& m, bool* above,
+                                                      uint32_t random_part = 0u) {
   const uint32_t u = bits & 0x7FFFFFFFu;
   const uint32_t uc = u < f.u_clamp ? u : f.u_clamp;
   const uint32_t normal = (uc - f.rebias) << f.shift_p;
@@ -691,7 +799,7 @@ __device__ __forceinline__ uint32_t round8_fixed_part(uint32_t bits, const Fmt8&
   const uint32_t sub = (uint32_t)scaled;                     // truncation toward zero
   const bool is_sub = u < f.u_sub;
   uint32_t r0 = is_sub ? sub : normal;
-  uint32_t add = m.fixed;
+  uint32_t add = random_part + m.fixed;
   if constexpr (TIES) {
     // what a target-subnormal input loses to the truncation is folded into bit 0, below the tie position
     const bool lost = is_sub && ((float)sub != scaled);
@@ -709,13 +817,17 @@ __device__ __forceinline__ uint32_t round8_fixed_part(uint32_t bits, const Fmt8&
 // draws none).  CHECKED = false may be used only when the pattern is known not to be a NaN.
 // WIDE = false: the code space has 24 fraction bits (K <= 8).  WIDE = true: f.frac of them (32 - K, for codes of up to
 // 16 bits), and the subnormal scale, which may pass fp32's range as a factor, is applied to the exponent.
+template <bool TIES, bool WIDE = false>
+__device__ __forceinline__ uint32_t round8_magnitude(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m) {
+  bool above;
+  const uint32_t sum = round8_fixed_part<TIES, WIDE>(bits, f, m, &above, n << m.shift);
+  if constexpr (WIDE) return sum >> f.frac;
+  else return sum >> 24;
+}
+
 template <bool TIES, bool CHECKED, bool WIDE = false>
 __device__ __forceinline__ uint32_t round8(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m) {
-  bool above;
-  const uint32_t fixed_part = round8_fixed_part<TIES, WIDE>(bits, f, m, &above);
-  const uint32_t sum = fixed_part + (above ? 0u : n << m.shift);
-  if constexpr (WIDE) return finish8<CHECKED>(sum >> f.frac, bits, f);
-  else return finish8<CHECKED>(sum >> 24, bits, f);
+  return finish8<CHECKED>(round8_magnitude<TIES, WIDE>(bits, n, f, m), bits, f);
 }
 
 // round8 for N = 17 .. 24 (the per-element kernel; any pattern): see round_pattern_wide.
@@ -728,43 +840,74 @@ __device__ __forceinline__ uint32_t round8_wide(uint32_t bits, uint32_t n, const
   return finish8<false>(c.whole + up, bits, f);
 }
 
+// round8 for N = 17 .. 24 in the 24-bit code space (the tile kernels; any pattern): see round_pattern_many.
+// grid_scale = sub_scale 2^-shift.  Ties to odd in the subnormal range are taken from the remainder of the truncated
+// position (exact: the difference of two floats with a common exponent range).
+template <bool TIES>
+__device__ __forceinline__ uint32_t round8_many_magnitude(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m, float grid_scale) {
+  const uint32_t u = bits & 0x7FFFFFFFu;
+  const uint32_t uc = u < f.u_clamp ? u : f.u_clamp;
+  const uint32_t normal = (uc - f.rebias) << f.shift_p;
+  const float ax = __uint_as_float(uc);
+  uint32_t in_normal, in_sub;
+  if constexpr (TIES) {
+    const uint32_t tie_mask = m.shift != 0u ? 1u : 0u;   // with no bit dropped the inner rounding is the identity
+    in_normal = normal + m.fixed + (((normal >> m.shift) ^ m.tie_xor) & tie_mask);
+    const float pos = ax * grid_scale;
+    uint32_t h;
+    if (m.tie_xor == 0u) {   // uniform over the launch
+      h = (uint32_t)rintf(pos);
+    } else {
+      h = (uint32_t)pos;
+      const float rem = pos - (float)h;
+      h += (rem > 0.5f || (rem == 0.5f && (h & 1u) == 0u)) ? 1u : 0u;
+    }
+    in_sub = h << m.shift;
+  } else {
+    in_normal = normal + m.fixed;
+    const float scaled = ax * f.sub_scale;
+    if (m.srf && m.shift == 0u) in_sub = ((uint32_t)(scaled + scaled) + 1u) >> 1;   // uniform over the launch
+    else in_sub = (uint32_t)scaled + m.fixed;
+  }
+  const uint32_t r0 = u < f.u_sub ? in_sub : in_normal;
+  const uint32_t sum = u > f.u_max ? normal + f.det_add : r0 + (n << m.shift);
+  return sum >> 24;
+}
+
 // Four 16-bit codes of a generic format as two words (element 0 in the low half of the first).
 template <bool TIES>
 __device__ __forceinline__ uint2 round4_codes16(const uint32_t (&b)[4], const uint32_t (&n)[4], bool checked, const Fmt8& f,
                                                 const Mode8& m) {
   uint32_t c[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) c[j] = round8_magnitude<TIES, true>(b[j], n[j], f, m);
+  cap8x4(c, f);
   if (checked) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) c[j] = round8<TIES, true, true>(b[j], n[j], f, m);
+    for (int j = 0; j < 4; ++j) c[j] = signed8<true>(c[j], b[j], f);
   } else {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) c[j] = round8<TIES, false, true>(b[j], n[j], f, m);
+    for (int j = 0; j < 4; ++j) c[j] = signed8<false>(c[j], b[j], f);
   }
   return make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
 }
 
-__device__ __forceinline__ uint32_t pack4_bytes(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
-  const uint32_t lo = __builtin_amdgcn_perm(c1, c0, 0x0c0c0400u);   // [c0.b0, c1.b0, 0, 0]
-  const uint32_t hi = __builtin_amdgcn_perm(c3, c2, 0x04000c0cu);   // [0, 0, c2.b0, c3.b0]
-  return lo | hi;
-}
-
-// MANY: more than 16 random bits, the rounding that keeps 32 fraction bits (any pattern).
+// MANY: more than 16 random bits (grid_scale: see round8_many).
 template <bool TIES, bool MANY = false>
 __device__ __forceinline__ uint32_t round4_bytes(const uint32_t (&b)[4], const uint32_t (&n)[4], bool checked,
-                                                 const Fmt8& f, const Mode8& m) {
-  uint32_t c[4];
-  if constexpr (MANY) {
+                                                 const Fmt8& f, const Mode8& m, float grid_scale = 0.0f) {
+  uint32_t g[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) c[j] = round8_wide(b[j], n[j], f, m);
-  } else if (checked) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) c[j] = round8<TIES, true>(b[j], n[j], f, m);
-  } else {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) c[j] = round8<TIES, false>(b[j], n[j], f, m);
+  for (int j = 0; j < 4; ++j) {
+    if constexpr (MANY) g[j] = round8_many_magnitude<TIES>(b[j], n[j], f, m, grid_scale);
+    else g[j] = round8_magnitude<TIES>(b[j], n[j], f, m);
   }
-  return pack4_bytes(c[0], c[1], c[2], c[3]);
+  cap8x4(g, f);
+  if (checked) {   // a NaN among the wave's elements: each byte finished by itself
+    return pack4_bytes(signed8<true>(g[0], b[0], f), signed8<true>(g[1], b[1], f), signed8<true>(g[2], b[2], f),
+                       signed8<true>(g[3], b[3], f));
+  }
+  return with_signs4(pack4_bytes(g[0], g[1], g[2], g[3]), top_bytes4(b), f);
 }
 
 // Random integer of ONE element with global index i (the per-element kernels).

@@ -47,6 +47,7 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
                            max(__float_as_uint(v[k].z) & 0x7FFFFFFFu, __float_as_uint(v[k].w) & 0x7FFFFFFFu)));
     }
     const bool checked = __any(umax > 0x7F800000u);   // wave-uniform: a NaN among the wave's elements
+    const float grid_scale = W == 32 ? __builtin_amdgcn_ldexpf(f.sub_scale, -(int)m.shift) : 0.0f;
 #pragma unroll
     for (int k = 0; k < kRows; ++k) {
       const uint32_t b[4] = {__float_as_uint(v[k].x), __float_as_uint(v[k].y), __float_as_uint(v[k].z),
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
         const uint2 c = round4_codes16<TIES>(b, n4, checked, f, m);
         __builtin_nontemporal_store((uint64_t)c.x | ((uint64_t)c.y << 32), reinterpret_cast<uint64_t*>(out) + row0 + (uint64_t)(k * 64));
       } else {
-        __builtin_nontemporal_store(round4_bytes<TIES, W == 32>(b, n4, checked, f, m),
+        __builtin_nontemporal_store(round4_bytes<TIES, W == 32>(b, n4, checked, f, m, grid_scale),
                                     reinterpret_cast<uint32_t*>(out) + row0 + (uint64_t)(k * 64));
       }
     }
@@ -80,6 +81,7 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
       umax = max(umax, b[j] & 0x7FFFFFFFu);
     }
     const bool checked = __any(umax > 0x7F800000u);
+    const float grid_scale = W == 32 ? __builtin_amdgcn_ldexpf(f.sub_scale, -(int)m.shift) : 0.0f;
     uint32_t n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if constexpr (W != 0) read_wg_bits8<WW>(strip, e0, m.nbits, n);
     const uint32_t b_lo[4] = {b[0], b[1], b[2], b[3]}, b_hi[4] = {b[4], b[5], b[6], b[7]};
@@ -90,8 +92,8 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
       c.x = lo.x; c.y = lo.y; c.z = hi.x; c.w = hi.y;
       __builtin_nontemporal_store(c, reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(out) + g0));
     } else {
-      const uint32_t lo = round4_bytes<TIES, W == 32>(b_lo, n_lo, checked, f, m);
-      const uint32_t hi = round4_bytes<TIES, W == 32>(b_hi, n_hi, checked, f, m);
+      const uint32_t lo = round4_bytes<TIES, W == 32>(b_lo, n_lo, checked, f, m, grid_scale);
+      const uint32_t hi = round4_bytes<TIES, W == 32>(b_hi, n_hi, checked, f, m, grid_scale);
       __builtin_nontemporal_store((uint64_t)lo | ((uint64_t)hi << 32), reinterpret_cast<uint64_t*>(reinterpret_cast<uint8_t*>(out) + g0));
     }
   }
@@ -100,12 +102,11 @@ __global__ __launch_bounds__(kThreads) void format8_tiles(const void* __restrict
 // ------------------------------------------------- 16-bit sources through a table over their magnitudes ---
 // A 16-bit source has 2^15 magnitudes, and everything round8 computes before the element's random integer enters
 // depends on the magnitude alone.  One workgroup per compute unit tabulates that part once (128 KiB of LDS) and then
-// streams tiles through it: per element one table read, t = entry + (n << shift), the magnitude code min(t >> 24, cap)
-// and the sign.  An entry is round8_fixed_part's sum; above M, where no random bits apply, it is the finished
-// magnitude code in the top byte over zero fraction bits, which the n << shift of any n leaves where it is.  cap is
-// over_code, which the host has checked to be max_code (saturating) or max_code + 1 (the infinity follows M's code),
-// so that one minimum replaces the comparison with max_code.  A wave whose tile holds a NaN rounds that tile with
-// round8 itself.
+// streams tiles through it: per element one table read, the magnitude code (entry + (n << shift)) >> 24, and the
+// signs of four bytes at a time.  An entry is round8_fixed_part's sum, which at or below M stays at or below max_code
+// under every n; above M, where no random bits apply, it is the finished magnitude code in the top byte over zero
+// fraction bits, which the n << shift of any n leaves where it is.  A wave whose tile holds a NaN rounds that tile
+// with round8 itself.
 //
 // Geometry: 1024 threads in four groups of 256; a pass of the loop takes 16 consecutive tiles, group g the tiles
 // 4 q + g, q = 0 .. 3, a lane 8 consecutive codes of each (16-byte loads, issued one pass ahead; 8-byte stores).
@@ -157,8 +158,6 @@ __global__ __launch_bounds__(kLutThreads) void format8_lut_tiles(const uint16_t*
     }
   }
   __syncthreads();
-  const uint32_t cap = f.over_code;
-  const uint32_t sign_lo = f.sign_shift - 16u;
   const uint32_t passes = (ntiles + (uint32_t)kLutPassTiles - 1u) / (uint32_t)kLutPassTiles;
   uint4* const strip = strips[W == 0 ? 0 : wave];
   // a tile past the end reads the last one again and stores nothing; the loads of a pass are issued one pass ahead
@@ -201,24 +200,27 @@ __global__ __launch_bounds__(kLutThreads) void format8_lut_tiles(const uint16_t*
         at[j] = (j & 1) ? (words[j >> 1] >> 14) & 0x1FFFCu : (words[j >> 1] << 2) & 0x1FFFCu;
         at_max = max(at_max, at[j]);
       }
-      uint32_t c[8];
+      uint32_t c[8], lo, hi;
       if (__any(at_max > NAN_ABOVE)) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const uint32_t bits = widen16<SRC>((words[j >> 1] >> (16 * (j & 1))) & 0xFFFFu);
           c[j] = m.ties ? round8<true, true>(bits, n[j], f, m) : round8<false, true>(bits, n[j], f, m);
         }
+        lo = pack4_bytes(c[0], c[1], c[2], c[3]);
+        hi = pack4_bytes(c[4], c[5], c[6], c[7]);
       } else {
+        // an entry at or below M plus any n << shift stays at or below max_code; one above M is a finished code
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const uint32_t entry = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(lut) + at[j]);
-          const uint32_t t = entry + (n[j] << m.shift);
-          const uint32_t mag = min(t >> 24, cap);
-          c[j] = mag | ((words[j >> 1] >> ((j & 1) ? f.sign_shift : sign_lo)) & (mag + f.sign_carry) & f.sign_bit);
+          c[j] = (entry + (n[j] << m.shift)) >> 24;
         }
+        // the top bytes of four 16-bit codes: bytes 1 and 3 of each of two words
+        lo = with_signs4(pack4_bytes(c[0], c[1], c[2], c[3]), __builtin_amdgcn_perm(words[1], words[0], 0x07050301u), f);
+        hi = with_signs4(pack4_bytes(c[4], c[5], c[6], c[7]), __builtin_amdgcn_perm(words[3], words[2], 0x07050301u), f);
       }
       if (tile < ntiles) {
-        const uint32_t lo = pack4_bytes(c[0], c[1], c[2], c[3]), hi = pack4_bytes(c[4], c[5], c[6], c[7]);
         __builtin_nontemporal_store((uint64_t)lo | ((uint64_t)hi << 32),
                                     reinterpret_cast<uint64_t*>(out + (uint64_t)tile * kTileElems + (uint64_t)e0));
       }
@@ -270,7 +272,7 @@ hipError_t launch_tiles_w(int W, const void* x, void* out, uint64_t ntiles, cons
 }
 
 // The table kernel pays for its table (2^15 entries per workgroup) from 2^26 elements on; it needs the
-// device to grant a workgroup its 144 KiB of LDS, at most 8 random bits, and an over_code that is max_code or the code after.
+// device to grant a workgroup its 144 KiB of LDS and at most 8 random bits.
 constexpr uint64_t kLutMinTiles = (uint64_t)1 << 15;
 
 struct LutDevice {
@@ -333,8 +335,7 @@ hipError_t run(const void* xin, void* outv, uint64_t n, const Fmt8& f, const Mod
         const uint64_t blk0 = W ? (offset + first) / (uint64_t)(128 / W) : 0;
         if constexpr (SRC != kSrcFP32 && !WIDE) {
           int units = 0;
-          if (count >= kLutMinTiles && W <= 8 && (f.over_code == f.max_code || f.over_code == f.max_code + 1u) &&
-              lut_device(&units)) {
+          if (count >= kLutMinTiles && W <= 8 && lut_device(&units)) {
             return launch_lut_tiles<SRC>(W, reinterpret_cast<const uint16_t*>(x + first * isize),
                                          reinterpret_cast<uint8_t*>(out + first * osize), count, f, m, seed, blk0, units, stream);
           }

@@ -29,6 +29,8 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
   // NaN, and bf16, take the integer arithmetic, in its flavour for many bits.
   constexpr bool MANY = W == 32;
   const Addends a = make_addends<FMT, VAR>(MANY ? kMaxTileNbits : nbits);
+  ManyAddends many = {a, 0.0f};
+  if constexpr (MANY && VAR != kRNE) many = make_many_addends<FMT, VAR>(nbits);
   HwAddends hw = {0, 0, 0, 0};
   if constexpr (Fx<FMT>::kIsFp8 && VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
   uint32_t umax = 0;
@@ -65,9 +67,14 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
       }
     }
     uint32_t r[4];
-    if constexpr (MANY) {
+    if constexpr (MANY && VAR != kRNE) {
+      if (checked) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) r[j] = round_pattern_wide<FMT, VAR>(b[j], n4[j], (uint32_t)nbits);
+        for (int j = 0; j < 4; ++j) r[j] = round_pattern_many<FMT, VAR, true>(b[j], n4[j], (uint32_t)nbits, many);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = round_pattern_many<FMT, VAR, false>(b[j], n4[j], (uint32_t)nbits, many);
+      }
     } else if (checked) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) r[j] = round_pattern<FMT, VAR, true>(b[j], n4[j], a);

@@ -39,6 +39,8 @@ __global__ __launch_bounds__(kThreads) void round16_tiles(const uint16_t* __rest
   }
   constexpr bool MANY = W == 32;   // more than 16 random bits: 32-bit slots
   const Addends a = make_addends<FMT, VAR>(MANY ? kMaxTileNbits : nbits);
+  ManyAddends many = {a, 0.0f};
+  if constexpr (MANY && VAR != kRNE) many = make_many_addends<FMT, VAR>(nbits);
   HwAddends hw = {0, 0, 0, 0};
   if constexpr (VAR != kRNE) hw = make_hw_addends<FMT, VAR>(nbits);
 #pragma unroll
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void round16_tiles(const uint16_t* __rest
         uint32_t r[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          if constexpr (MANY) r[j] = round_pattern_wide<FMT, VAR>(b4[j], n4[j], (uint32_t)nbits);
+          if constexpr (MANY && VAR != kRNE) r[j] = round_pattern_many<FMT, VAR, true>(b4[j], n4[j], (uint32_t)nbits, many);
           else r[j] = round_pattern<FMT, VAR, true>(b4[j], n4[j], a);
         }
         packed[h] = pack4_fp8<FMT>(r[0], r[1], r[2], r[3]);

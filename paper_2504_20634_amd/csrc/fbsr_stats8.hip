@@ -151,8 +151,7 @@ __global__ __launch_bounds__(kThreads) void stats8_spans(const float* __restrict
           }
           if (out != nullptr) {
             reinterpret_cast<uint32_t*>(out)[(span_lo - i0) / 4 + (uint64_t)(r * 64 + lane)] =
-                pack4_bytes(finish8<false>(mag[0], b[0], a.f), finish8<false>(mag[1], b[1], a.f), finish8<false>(mag[2], b[2], a.f),
-                            finish8<false>(mag[3], b[3], a.f));
+                with_signs4(pack4_bytes(mag[0], mag[1], mag[2], mag[3]), top_bytes4(b), a.f);   // |x| <= M: no code above max_code
           }
           return;
         }
