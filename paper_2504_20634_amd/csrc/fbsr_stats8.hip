@@ -39,6 +39,7 @@ struct Stats8Args {
   uint32_t u_exact, map_add;
   float split;
   uint32_t plain_ok;         // 0: the format or the mode rules the integer path out (P = 1, more than 16 random bits)
+  uint32_t row_sum_exact;    // 1: M is below 2^22 steps of the subnormal grid, which every finite value is a multiple of
 };
 
 // The code of one element: any pattern, any bit count the entry point accepts.
@@ -131,23 +132,40 @@ __global__ __launch_bounds__(kThreads) void stats8_spans(const float* __restrict
         const uint32_t top = max(max(u0, u1), max(u2, u3));
         const uint32_t low = min(min(u0 - 1u, u1 - 1u), min(u2 - 1u, u3 - 1u));   // a zero wraps to the largest value
         if (!__any(top > a.f.u_max || low < a.u_exact - 1u)) {
-          uint32_t mag[4];
+          uint32_t mag[4], r0[4], add[4];
+          float y[4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const uint32_t u = b[j] & 0x7FFFFFFFu;
             const uint32_t normal_part = (max(u, a.f.u_sub) << a.f.shift_p) + a.map_add;
             const uint32_t sub_part = (uint32_t)fminf(__uint_as_float(u) * a.f.sub_scale, a.split);
-            const uint32_t r0 = normal_part + sub_part;
-            uint32_t add = (n[j] << a.m.shift) + a.m.fixed;
-            if (a.m.ties) add += ((r0 >> a.m.shift) & 1u) ^ a.m.tie_xor;
-            const uint32_t sum = r0 + add;
+            r0[j] = normal_part + sub_part;
+            add[j] = (n[j] << a.m.shift) + a.m.fixed;
+          }
+          if (a.m.ties) {   // one branch for the row (the empty statement keeps it a branch: the other modes skip the work)
+            asm volatile("");
+#pragma unroll
+            for (int j = 0; j < 4; ++j) add[j] += ((r0[j] >> a.m.shift) & 1u) ^ a.m.tie_xor;
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t sum = r0[j] + add[j];
             mag[j] = sum >> 24;
-            const int32_t e_int = (int32_t)((sum & 0xFF000000u) - r0);
+            const int32_t e_int = (int32_t)((sum & 0xFF000000u) - r0[j]);
             const int32_t sgn = (int32_t)b[j] >> 31;
             se_i += e_int ^ sgn;
             neg_i += sgn;
             see_i += (long long)e_int * (long long)e_int;
-            sy += (double)__uint_as_float(__float_as_uint(value_of[mag[j]]) | (b[j] & 0x80000000u));
+            y[j] = __uint_as_float(__float_as_uint(value_of[mag[j]]) | (b[j] & 0x80000000u));
+          }
+          if (a.row_sum_exact != 0u) {   // four values of at most 22 bits on one grid: their fp32 sum is exact
+            asm volatile("");
+            sy += (double)((y[0] + y[1]) + (y[2] + y[3]));
+          } else {
+            sy += (double)y[0];
+            sy += (double)y[1];
+            sy += (double)y[2];
+            sy += (double)y[3];
           }
           if (out != nullptr) {
             reinterpret_cast<uint32_t*>(out)[(span_lo - i0) / 4 + (uint64_t)(r * 64 + lane)] =
@@ -308,6 +326,7 @@ hipError_t launch_stats_format8(const float* x, uint8_t* out, uint64_t n, const 
   a.map_add = 0u - (f.rebias << f.shift_p) - ((uint32_t)1 << (23 + P));
   a.split = (float)((uint32_t)1 << (23 + P));
   a.plain_ok = f.unit_lsb == 0u && m.nbits <= (uint32_t)kMaxTileNbits && 1 - B - P + 127 >= 1 ? 1u : 0u;
+  a.row_sum_exact = (int)(f.max_code >> (P - 1)) + P - 1 <= 22 ? 1u : 0u;   // M < 2^(e_max + P - 1) grid steps
   const int W = m.nbits ? slot_width((int)m.nbits) : 0;
   const Split s = split_range(n, offset, W ? W : 8, W == 0, reinterpret_cast<uintptr_t>(x), 4, 16, reinterpret_cast<uintptr_t>(out),
                               1, 4, 0, 0, 1, kStatsPairElems);
