@@ -787,7 +787,9 @@ __device__ __forceinline__ uint32_t top_bytes4(const uint32_t (&b)[4]) {
 // or, above M (*above set; no randomness there, Sec. II), plus the nearest-even addend alone.  With random_part = 0 it
 // is the part of the sum that the element's random integer does not enter.  The sum stays below 2^32: the pattern is
 // below (max_code + 2) 2^frac and the addends together below 2^frac.
-template <bool TIES, bool WIDE>
+// UNIT = false leaves out the one case that only a format with P = 1 under a mode without random bits has (see
+// needs_unit8): the four-at-a-time callers branch on it once per four elements rather than pay for it per element.
+template <bool TIES, bool WIDE, bool UNIT = true>
 __device__ __forceinline__ uint32_t round8_fixed_part(uint32_t bits, const Fmt8& f, const Mode8& m, bool* above,
                                                       uint32_t random_part = 0u) {
   const uint32_t u = bits & 0x7FFFFFFFu;
@@ -806,7 +808,9 @@ __device__ __forceinline__ uint32_t round8_fixed_part(uint32_t bits, const Fmt8&
     r0 |= lost ? 1u : 0u;
     uint32_t parity_of = r0;
     // P = 1 stores no significand bit: a normal value's significand is its implicit one (odd)
-    if (f.unit_lsb != 0u) parity_of |= is_sub ? 0u : f.unit_lsb;
+    if constexpr (UNIT) {
+      if (f.unit_lsb != 0u) parity_of |= is_sub ? 0u : f.unit_lsb;
+    }
     add += ((parity_of >> m.shift) & 1u) ^ m.tie_xor;
   }
   *above = u > f.u_max;
@@ -817,12 +821,32 @@ __device__ __forceinline__ uint32_t round8_fixed_part(uint32_t bits, const Fmt8&
 // draws none).  CHECKED = false may be used only when the pattern is known not to be a NaN.
 // WIDE = false: the code space has 24 fraction bits (K <= 8).  WIDE = true: f.frac of them (32 - K, for codes of up to
 // 16 bits), and the subnormal scale, which may pass fp32's range as a factor, is applied to the exponent.
-template <bool TIES, bool WIDE = false>
+template <bool TIES, bool WIDE = false, bool UNIT = true>
 __device__ __forceinline__ uint32_t round8_magnitude(uint32_t bits, uint32_t n, const Fmt8& f, const Mode8& m) {
   bool above;
-  const uint32_t sum = round8_fixed_part<TIES, WIDE>(bits, f, m, &above, n << m.shift);
+  const uint32_t sum = round8_fixed_part<TIES, WIDE, UNIT>(bits, f, m, &above, n << m.shift);
   if constexpr (WIDE) return sum >> f.frac;
   else return sum >> 24;
+}
+
+// True when the tie bit of the inner rounding is the implicit one of a P = 1 significand: the unit_lsb bit sits at
+// the code space's first place above the fraction, which is the tie position only when no random bits are drawn.
+__device__ __forceinline__ bool needs_unit8(const Fmt8& f, const Mode8& m) {
+  return f.unit_lsb != 0u && m.shift == f.frac;
+}
+
+// round8_magnitude on four elements, the P = 1 case behind one branch (the empty statement keeps it a branch).
+template <bool TIES, bool WIDE>
+__device__ __forceinline__ void round8_magnitudes4(const uint32_t (&b)[4], const uint32_t (&n)[4], const Fmt8& f, const Mode8& m,
+                                                   uint32_t (&g)[4]) {
+  if (TIES && needs_unit8(f, m)) {
+    asm volatile("");
+#pragma unroll
+    for (int j = 0; j < 4; ++j) g[j] = round8_magnitude<TIES, WIDE, true>(b[j], n[j], f, m);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) g[j] = round8_magnitude<TIES, WIDE, false>(b[j], n[j], f, m);
+  }
 }
 
 template <bool TIES, bool CHECKED, bool WIDE = false>
@@ -879,8 +903,7 @@ template <bool TIES>
 __device__ __forceinline__ uint2 round4_codes16(const uint32_t (&b)[4], const uint32_t (&n)[4], bool checked, const Fmt8& f,
                                                 const Mode8& m) {
   uint32_t c[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) c[j] = round8_magnitude<TIES, true>(b[j], n[j], f, m);
+  round8_magnitudes4<TIES, true>(b, n, f, m, c);
   cap8x4(c, f);
   if (checked) {
 #pragma unroll
@@ -897,10 +920,11 @@ template <bool TIES, bool MANY = false>
 __device__ __forceinline__ uint32_t round4_bytes(const uint32_t (&b)[4], const uint32_t (&n)[4], bool checked,
                                                  const Fmt8& f, const Mode8& m, float grid_scale = 0.0f) {
   uint32_t g[4];
+  if constexpr (MANY) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    if constexpr (MANY) g[j] = round8_many_magnitude<TIES>(b[j], n[j], f, m, grid_scale);
-    else g[j] = round8_magnitude<TIES>(b[j], n[j], f, m);
+    for (int j = 0; j < 4; ++j) g[j] = round8_many_magnitude<TIES>(b[j], n[j], f, m, grid_scale);
+  } else {
+    round8_magnitudes4<TIES, false>(b, n, f, m, g);
   }
   cap8x4(g, f);
   if (checked) {   // a NaN among the wave's elements: each byte finished by itself

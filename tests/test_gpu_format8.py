@@ -210,9 +210,12 @@ def test_rejects_bad_arguments(fbsr):
             fbsr.fbsr_round_format8(x, FROM_FP32, d, variant, nbits, seed=0)
 
 
-@pytest.mark.parametrize("name,variant,nbits", [("binary8p4", SRC_ODD, 3), ("ocp_e2m1", SRF, 2), ("binary8p3", RNA, 0)])
+@pytest.mark.parametrize("name,variant,nbits", [("binary8p4", SRC_ODD, 3), ("ocp_e2m1", SRF, 2), ("binary8p3", RNA, 0),
+                                                 ("binary8p4", SRC_ODD, 23), ("binary8p7", SRF, 24), ("ocp_e2m1", SRC, 24)])
 def test_every_fp32_pattern_generic(fbsr, oracle, name, variant, nbits):
-    """All 2^32 input patterns through the generic tile kernel, in 16 slabs of 2^28: byte-identical to the oracle."""
+    """All 2^32 input patterns through the generic tile kernel, in 16 slabs of 2^28: byte-identical to the oracle.  The
+    cases with more than 16 bits are the corners of that rounding in the 24-bit code space: the inner rounding's tie at
+    the code space's last place, the half step below it, no bit dropped at all."""
     d = FORMATS[name]
     slab = 1 << 28
     for s_no in range(16):

@@ -121,7 +121,8 @@ def test_runs_on_a_side_stream(fbsr, oracle):
 @pytest.mark.parametrize("fmt,variant,nbits", [(E4M3, SRFF, 8), (E5M2, SRF, 4), (E4M3, SRC, 3), (E5M2, SRC, 8),
                                                (E5M2, SRFF, 2), (E4M3, SRF, 16), (P4, SRC, 3), (P4, SRFF, 8), (P4, SRF, 2),
                                                (E4M3, SRC, 24), (E5M2, SRF, 21), (P4, SRFF, 20),
-                                               (E4M3, SRFF, 20), (E4M3, SRF, 19), (E5M2, SRC, 20), (P4, SRC, 17)])
+                                               (E4M3, SRFF, 20), (E4M3, SRF, 19), (E5M2, SRC, 20), (P4, SRC, 17),
+                                               (E4M3, SRF, 24), (E5M2, SRC, 23), (P4, SRF, 24)])
 def test_every_fp32_pattern(fbsr, oracle, fmt, variant, nbits):
     """All 2^32 input patterns (every normal, subnormal, zero, infinity and NaN of both signs), in
     16 slabs of 2^28 consecutive patterns, through the tile kernel: byte-identical to the oracle.  This is what

@@ -1,6 +1,8 @@
 """GPU parity for more than 16 random bits per element (17..24; every entry point but the fused updates): enough bits to
-reach classical SR from fp32 (E4M3 and binary8p4 drop D = 20 bits, E5M2 21, bf16 16).  These calls run on the
-per-element kernel with 32 fraction bits; the oracle is the same one, which takes any N <= 32."""
+reach classical SR from fp32 (E4M3 and binary8p4 drop D = 20 bits, E5M2 21, bf16 16).  Aligned bodies run on the
+tile kernels (32-bit slots; the hardware converts where they are exact, else the 24-bit code space with the
+subnormal positions taken from a float product), heads and tails on the per-element kernels with 32 fraction bits;
+the oracle is the same one, which takes any N <= 32."""
 import numpy as np
 import pytest
 import torch
