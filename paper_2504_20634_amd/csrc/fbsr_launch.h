@@ -65,8 +65,9 @@ constexpr uint64_t kMaxTilesPerLaunch = (uint64_t)1 << 22;
 constexpr uint32_t kXcdLgRound = 8, kXcdLgSgd = 7, kXcdLgRound16 = 7, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 7;
 // Up to 16 random bits per element use slots of at most 16 bits and a code space with 24 fraction bits.  With more (the
 // rounding entry points take up to 24) every tile kernel has a flavour with 32-bit slots: the fp8 targets through the
-// hardware converts where those are exact and otherwise, like bf16 and the generic formats, through a rounding that
-// keeps 32 fraction bits.
+// hardware converts where those are exact and otherwise, like bf16 and the generic formats, in the same code space with
+// the target-subnormal positions taken from an exact float product (round_pattern_many); the per-element kernels keep
+// 32 fraction bits and a sticky bit (round_pattern_wide).
 constexpr int kMaxTileNbits = 16;
 // Largest n the library accepts.
 constexpr uint64_t kMaxElems = (uint64_t)1 << 38;

@@ -268,6 +268,37 @@ def test_exhaustive_round_up_counts(oracle, name, variant):
             assert got == want, (name, xv, variant, N, got, want)
 
 
+@pytest.mark.parametrize("name", ["binary8p4", "e5m2", "e2m1", "binary8p1", "binary8p7"])
+@pytest.mark.parametrize("N", [17, 20, 23, 24])
+def test_round_up_threshold_with_many_bits(oracle, name, N):
+    """With 17 to 24 bits the draws are too many to count one by one, but every variant rounds up for exactly the
+    largest draws: with U = the counting argument's number over the exact delta, n = 2^N - U is the first draw that
+    rounds up and the one before it the last that does not.  Inputs reach below the smallest subnormal, where delta
+    carries more bits than any fixed-point word of the kernels holds, and half of them have short significands (ties
+    of the inner rounding of Eq. (7))."""
+    d = ALL[name]
+    rng = np.random.default_rng(100 + N)
+    x = inputs_below_max(rng, d, 50)
+    short = inputs_below_max(rng, d, 50).view(np.uint32) & np.uint32(0xFFFF0000)
+    mask = (1 << (d[0] - 1)) - 1
+    for xv in np.concatenate([x, short.view(np.float32)]):
+        a = abs(f32_fraction(xv))
+        lo, delta = position(a, d)
+        for variant in DRAWING:
+            U = ups(delta, variant, N) if delta != 0 else 0
+            first_up = (1 << N) - U
+            probes = {0: lo if U < (1 << N) else lo + 1, (1 << N) - 1: lo + 1 if U > 0 else lo}
+            if U > 0:
+                probes[first_up] = lo + 1
+                probes[int(rng.integers(first_up, 1 << N))] = lo + 1
+            if first_up > 0:
+                probes[first_up - 1] = lo
+                probes[int(rng.integers(0, first_up))] = lo
+            for n, want in probes.items():
+                got = oracle.round_format8_with_n(xv, d, variant, N, n) & mask
+                assert got == want, (name, float(xv), variant, N, n, got, want, U)
+
+
 @pytest.mark.parametrize("N", [1, 2, 3, 4])
 def test_src_with_ties_to_odd_is_unbiased_and_differs_only_at_ties(oracle, N):
     """Sec. III-F allows ties-to-even or ties-to-odd for SRC's inner rounding: over a full grid of
