@@ -112,12 +112,28 @@ def load_counters():
     return c, "profiles/kernel_counters.json"
 
 
-def timed_launches(torch, fn, reps, warm=2):
-    """Average duration (ms) of fn()'s GPU work over `reps` launches, from events recorded on
+# Every secondary path is timed over this many launches, after launches of the same call have kept the GPU busy for
+# WARM_MS: when load sets in after a pause the part's clocks dip for some tens of milliseconds and recover, which a short
+# burst of a dozen launches of an arithmetic-heavy kernel reads as anything from 70 % to 100 % of its steady rate.
+TIMED_LAUNCHES = 12
+WARM_MS = 40.0
+
+
+def keep_busy(torch, fn, ms=WARM_MS, batch=8):
+    """Launches fn() in batches until they have kept the GPU busy for `ms` milliseconds."""
+    t0 = time.perf_counter()
+    while True:
+        for _ in range(batch):
+            fn()
+        torch.cuda.synchronize()
+        if (time.perf_counter() - t0) * 1e3 >= ms:
+            return
+
+
+def timed_launches(torch, fn, reps=TIMED_LAUNCHES):
+    """Average duration (ms) of fn()'s GPU work over `reps` launches in the steady state, from events recorded on
     the stream the kernels are launched on (torch's current stream)."""
-    for _ in range(warm):
-        fn()
-    torch.cuda.synchronize()
+    keep_busy(torch, fn)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     for a, b in evs:
         a.record()
@@ -129,9 +145,10 @@ def timed_launches(torch, fn, reps, warm=2):
 
 def timed_sweep(torch, launches, reps=3):
     """Average duration (ms) of one pass over `launches` (a list of callables), from events around whole passes."""
-    for fn in launches:
-        fn()
-    torch.cuda.synchronize()
+    def one_pass():
+        for fn in launches:
+            fn()
+    keep_busy(torch, one_pass, batch=1)
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     for _ in range(reps):
@@ -329,14 +346,14 @@ def main():
         def probe():
             turn[0] += 1
             fbsr.binding.fbsr_probe_stream41(x_rot[fbsr.FMT_E4M3][turn[0] % 3], out_rot[turn[0] % 4])
-        ms = timed_launches(torch, probe, 12)
+        ms = timed_launches(torch, probe)
         paths["stream_4to1_no_arithmetic_ceiling"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1)}
         # the RNE launch draws no random bits (same 4:1 read:write byte mix)
-        ms = timed_launches(torch, lambda: fbsr.fbsr_round(x_dev[fbsr.FMT_E4M3], fbsr.FMT_E4M3, fbsr.RNE, 0, 2, 0, out=out8), 10)
+        ms = timed_launches(torch, lambda: fbsr.fbsr_round(x_dev[fbsr.FMT_E4M3], fbsr.FMT_E4M3, fbsr.RNE, 0, 2, 0, out=out8))
         paths["round_e4m3_rne_ceiling"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1)}
         out16 = torch.empty(n, dtype=torch.uint16, device="cuda")
         for nb in (4, 8, 16):
-            ms = timed_launches(torch, lambda: fbsr.fbsr_round(x_dev[fbsr.FMT_E5M2], fbsr.FMT_BF16, fbsr.SRF, nb, 2, 0, out=out16), 10)
+            ms = timed_launches(torch, lambda: fbsr.fbsr_round(x_dev[fbsr.FMT_E5M2], fbsr.FMT_BF16, fbsr.SRF, nb, 2, 0, out=out16))
             paths["round_bf16_N%d_srf" % nb] = {"ms": round(ms, 4), "gb_s": round(6.0 * n / ms / 1e6, 1)}
         del out16
         # narrow-source rounding (bf16 -> fp8, 3 B/element), N = 3 as in the paper's experiments
@@ -347,24 +364,24 @@ def main():
             rot16[0] += 1
             fbsr.fbsr_round_from16(x16[rot16[0] % 3], fbsr.SRC_BF16, f, v, nb, seed=2, offset=0, out=out_rot[rot16[0] % 4])
         for f, v, nb in ((fbsr.FMT_E4M3, fbsr.SRC, 3), (fbsr.FMT_E5M2, fbsr.SRF, 3), (fbsr.FMT_E4M3, fbsr.SRFF, 8)):
-            ms = timed_launches(torch, lambda: from16(f, v, nb), 12)
+            ms = timed_launches(torch, lambda: from16(f, v, nb))
             paths["round_from_bf16_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
                 "ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
-        ms = timed_launches(torch, lambda: from16(fbsr.FMT_E4M3, fbsr.SRFF, 20), 8)       # more than 16 random bits: 32-bit slots
+        ms = timed_launches(torch, lambda: from16(fbsr.FMT_E4M3, fbsr.SRFF, 20))       # more than 16 random bits: 32-bit slots
         paths["round_from_bf16_e4m3_N20_srff"] = {"ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
         # the format Sec. IV trains in (P3109 binary8p4) as a target id: hardware converts on 2 x
         def p4round(v, nb):
             turn[0] += 1
             fbsr.fbsr_round(x_rot[fbsr.FMT_E4M3][turn[0] % 3], fbsr.FMT_BINARY8P4, v, nb, seed=2, offset=0, out=out_rot[turn[0] % 4])
         for v, nb in ((fbsr.SRC, 3), (fbsr.SRFF, 8)):
-            ms = timed_launches(torch, lambda: p4round(v, nb), 12)
+            ms = timed_launches(torch, lambda: p4round(v, nb))
             paths["round_binary8p4_N%d_%s" % (nb, fbsr.binding.VARIANT_NAMES[v])] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1)}
 
         # classical SR from fp32 (N = D = 20 for E4M3): more than 16 bits per element, 32-bit slots and the wide rounding
         def many_bits():
             turn[0] += 1
             fbsr.fbsr_round(x_rot[fbsr.FMT_E4M3][turn[0] % 3], fbsr.FMT_E4M3, fbsr.SRFF, 20, seed=2, offset=0, out=out_rot[turn[0] % 4])
-        ms = timed_launches(torch, many_bits, 6)
+        ms = timed_launches(torch, many_bits)
         paths["round_e4m3_N20_classical_sr"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1),
                                                                    "gelem_s": round(n / ms / 1e6, 1)}
 
@@ -373,13 +390,13 @@ def main():
         def most_bits():
             turn[0] += 1
             fbsr.fbsr_round(x_rot[fbsr.FMT_E4M3][turn[0] % 3], fbsr.FMT_E4M3, fbsr.SRC, 24, seed=2, offset=0, out=out_rot[turn[0] % 4])
-        ms = timed_launches(torch, most_bits, 6)
+        ms = timed_launches(torch, most_bits)
         paths["round_e4m3_N24_src"] = {"ms": round(ms, 4), "gb_s": round(5.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
 
         def p4from16(v, nb):
             rot16[0] += 1
             fbsr.fbsr_round_from16(x16[rot16[0] % 3], fbsr.SRC_BF16, fbsr.FMT_BINARY8P4, v, nb, seed=2, offset=0, out=out_rot[rot16[0] % 4])
-        ms = timed_launches(torch, lambda: p4from16(fbsr.SRC, 3), 12)
+        ms = timed_launches(torch, lambda: p4from16(fbsr.SRC, 3))
         paths["round_from_bf16_binary8p4_N3_src"] = {"ms": round(ms, 4), "gb_s": round(3.0 * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
         # generic-format path (descriptor given at run time): the same format, from fp32 and from bf16 (N = 3)
         p4 = fbsr.format8_named("p3109_binary8p4")
@@ -392,7 +409,7 @@ def main():
         for src, v, nb, tag in ((fbsr.FROM_FP32, fbsr.SRC, 3, "src"), (fbsr.FROM_FP32, fbsr.SRF, 8, "srf"),
                                 (fbsr.FROM_FP32, fbsr.SRC_TIES_ODD, 3, "src_ties_odd"), (fbsr.FROM_FP32, fbsr.SRFF, 20, "srff"),
                                 (fbsr.FROM_BF16, fbsr.SRC, 3, "src"), (fbsr.FROM_BF16, fbsr.SRFF, 3, "srff")):
-            ms = timed_launches(torch, lambda: generic(src, v, nb), 12)
+            ms = timed_launches(torch, lambda: generic(src, v, nb))
             bpe = 5.0 if src == fbsr.FROM_FP32 else 3.0
             paths["round_format8_binary8p4_from_%s_N%d_%s" % ("fp32" if src == fbsr.FROM_FP32 else "bf16", nb, tag)] = {
                 "ms": round(ms, 4), "gb_s": round(bpe * n / ms / 1e6, 1), "gelem_s": round(n / ms / 1e6, 1)}
@@ -405,7 +422,7 @@ def main():
             rotg[0] += 1
             fbsr.fbsr_round_format16(x_rot[fbsr.FMT_E4M3][rotg[0] % 3], fbsr.FROM_FP32, b16, v, nb, seed=2, offset=0, out=o16[rotg[0] % 2])
         for v, nb, tag in ((fbsr.SRC, 3, "src"), (fbsr.SRF, 8, "srf")):
-            ms = timed_launches(torch, lambda: wide16(v, nb), 10)
+            ms = timed_launches(torch, lambda: wide16(v, nb))
             paths["round_format16_binary16_from_fp32_N%d_%s" % (nb, tag)] = {"ms": round(ms, 4), "gb_s": round(6.0 * n / ms / 1e6, 1),
                                                                               "gelem_s": round(n / ms / 1e6, 1)}
         del o16
@@ -417,7 +434,7 @@ def main():
             rotb[0] += 1
             fbsr.fbsr_round_block_scaled(x_rot[f][rotb[0] % 3], f, v, nb, seed=2, offset=0, out=out_rot[rotb[0] % 4], scales=sc)
         for f, v, nb in ((fbsr.FMT_E4M3, fbsr.SRC, 3), (fbsr.FMT_E5M2, fbsr.SRF, 8), (fbsr.FMT_E4M3, fbsr.SRFF, 20)):
-            ms = timed_launches(torch, lambda: blockscaled(f, v, nb), 12)
+            ms = timed_launches(torch, lambda: blockscaled(f, v, nb))
             paths["round_block_scaled_%s_N%d_%s" % (target[f], nb, fbsr.binding.VARIANT_NAMES[v])] = {
                 "ms": round(ms, 4), "gb_s": round((5.0 + 1.0 / 32) * n / ms / 1e6, 1)}
         del sc
@@ -434,7 +451,7 @@ def main():
             for k in range(2):                       # so the buffers end as they began
                 w8_, g_, m_, v_ = qs[k]
                 fbsr.binding.fbsr_probe_stream75(w8_, g_, m_, v_)
-        ms = timed_launches(torch, stream75_twice, 6) / 2
+        ms = timed_launches(torch, stream75_twice) / 2
         paths["stream_7to5_no_arithmetic_ceiling"] = {"ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1),
                                                       "gelem_s": round(nq / ms / 1e6, 1)}
 
@@ -445,7 +462,7 @@ def main():
             fbsr.fbsr_qat_adamw_step(w8_, g_, m_, v_, fbsr.FMT_E4M3, (1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9 ** t, 1 - 0.999 ** t),
                                      v, 3, seed=6, step=t)
         for v in (fbsr.SRC, fbsr.SRFF):
-            ms = timed_launches(torch, lambda: qat(v), 12)
+            ms = timed_launches(torch, lambda: qat(v))
             paths["qat_adamw_e4m3_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
                 "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
         # the same step with the weights in P3109 binary8p4 (the format Sec. IV trains in): as a target id ...
@@ -460,7 +477,7 @@ def main():
             fbsr.fbsr_qat_adamw_step(w8_, g_, m_, v_, fbsr.FMT_BINARY8P4, (1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9 ** t, 1 - 0.999 ** t),
                                      v, 3, seed=6, step=t)
         for v in (fbsr.SRC, fbsr.SRFF):
-            ms = timed_launches(torch, lambda: qatp4(v), 12)
+            ms = timed_launches(torch, lambda: qatp4(v))
             paths["qat_adamw_binary8p4_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
                 "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
         # ... and through the generic entry point (descriptor at run time, weights decoded through a table)
@@ -475,7 +492,7 @@ def main():
             fbsr.fbsr_qat_adamw_step_format8(w8_, g_, m_, v_, p4q, (1e-3, 0.9, 0.999, 1e-8, 0.01, 1 - 0.9 ** t, 1 - 0.999 ** t),
                                              v, 3, seed=6, step=t)
         for v in (fbsr.SRC, fbsr.SRFF):
-            ms = timed_launches(torch, lambda: qat8(v), 12)
+            ms = timed_launches(torch, lambda: qat8(v))
             paths["qat_adamw_format8_binary8p4_N3_%s" % fbsr.binding.VARIANT_NAMES[v]] = {
                 "ms": round(ms, 4), "gb_s": round(12.0 * nq / ms / 1e6, 1), "gelem_s": round(nq / ms / 1e6, 1)}
         del qs
@@ -490,7 +507,7 @@ def main():
             fbsr.fbsr_sgd_update(ws_[k], gs_[k], 1e-3, fbsr.SRF, nb, seed=4, step=step_no[0])
             step_no[0] += 1
         for nb in (2, 4, 8):
-            ms = timed_launches(torch, lambda: sgd(nb), 12)
+            ms = timed_launches(torch, lambda: sgd(nb))
             paths["sgd_update_bf16_N%d_srf" % nb] = {"ms": round(ms, 4), "gb_s": round(8.0 * ns / ms / 1e6, 1)}
         del ws_, gs_
         # bias statistics on the fifth workload's recipe at 2^28 elements: 1024 log-spaced bins of 2^18
@@ -506,7 +523,7 @@ def main():
             rot[0] += 1
             fbsr.fbsr_bias_stats(xs_[rot[0] % 2], f, fbsr.SRF, nb, 5, 0, group, 0, nbins, stats=stats, workspace=ws)
         for f, nb in ((fbsr.FMT_E4M3, 3), (fbsr.FMT_E4M3, 8), (fbsr.FMT_BF16, 2), (fbsr.FMT_BF16, 8)):
-            ms = timed_launches(torch, lambda: stat(f, nb), 6)
+            ms = timed_launches(torch, lambda: stat(f, nb))
             paths["bias_stats_%s_N%d_srf" % (target[f], nb)] = {"ms": round(ms, 4), "gb_s": round(4.0 * n / ms / 1e6, 1)}
 
         # the same statistics with the target given by its descriptor (P3109 binary8p4, the format Sec. IV trains in)
@@ -514,7 +531,7 @@ def main():
             rot[0] += 1
             fbsr.fbsr_bias_stats_format8(xs_[rot[0] % 2], p4, v, nb, 5, 0, group, 0, nbins, stats=stats, workspace=ws)
         for v, nb, tag in ((fbsr.SRF, 3, "srf"), (fbsr.SRC, 3, "src")):
-            ms = timed_launches(torch, lambda: stat8(v, nb), 6)
+            ms = timed_launches(torch, lambda: stat8(v, nb))
             paths["bias_stats_format8_binary8p4_N%d_%s" % (nb, tag)] = {"ms": round(ms, 4), "gb_s": round(4.0 * n / ms / 1e6, 1)}
         del xs_
 
@@ -526,6 +543,7 @@ def main():
         elems = min(SGD_ELEMS, n) if name.startswith(("qat", "sgd", "stream_7to5")) else n
         entry["kernel"] = PATH_KERNELS.get(name)
         entry["elements"] = elems
+        entry["launches"] = TIMED_LAUNCHES * (2 if name.startswith("stream_7to5") else 1)   # of the kernel, in the timed region
         per_elem = counters.get("valu_per_elem", {}).get(name)
         if per_elem is not None:
             rate = per_elem * elems / (entry["ms"] * 1e-3)

@@ -57,12 +57,20 @@ def one_csv(folder, suffix):
     return found[0]
 
 
-def read_stats(folder):
-    out = {}
-    with open(one_csv(folder, "_kernel_stats.csv"), newline="") as fh:
+def read_stats(folder, timed):
+    """kernel -> launches and mean / min / max duration of its LAST timed[kernel] launches (all, for a kernel without
+    an entry): bench.py warms every path up with launches of the same call, so a kernel's last launches are the ones
+    it timed (where two of its lines share a kernel, those of the second and the end of its warm-up)."""
+    spans = defaultdict(list)
+    with open(one_csv(folder, "_kernel_trace.csv"), newline="") as fh:
         for row in csv.DictReader(fh):
-            out[short_name(row["Name"])] = {"calls": int(row["Calls"]), "avg_us": float(row["AverageNs"]) / 1e3,
-                                            "min_us": float(row["MinNs"]) / 1e3, "max_us": float(row["MaxNs"]) / 1e3}
+            spans[short_name(row["Kernel_Name"])].append((int(row["Start_Timestamp"]), int(row["End_Timestamp"])))
+    out = {}
+    for k, rows in spans.items():
+        rows.sort()
+        last = rows[-timed[k]:] if timed.get(k) else rows
+        d = [(e - s) / 1e3 for s, e in last]
+        out[k] = {"calls": len(rows), "used": len(d), "avg_us": sum(d) / len(d), "min_us": min(d), "max_us": max(d)}
     return out
 
 
@@ -86,9 +94,10 @@ def bench_entries(bench):
             k = e.get("kernel")
             if not k:
                 continue
-            d = by_kernel.setdefault(k, {"labels": [], "ms": [], "elements": e["elements"], "bytes": e["gb_s"] * e["ms"] * 1e6})
+            d = by_kernel.setdefault(k, {"labels": [], "ms": [], "elements": e["elements"], "bytes": e["gb_s"] * e["ms"] * 1e6, "launches": 0})
             d["labels"].append(label)
             d["ms"].append(e["ms"])
+            d["launches"] += e.get("launches", bench["steps"])   # a headline kernel runs once per step
     for d in by_kernel.values():
         d["ms"] = sum(d["ms"]) / len(d["ms"])
     return by_kernel
@@ -123,14 +132,14 @@ def main():
     figures = {"sources_sha256": bench_module.kernel_sources_hash(), "program": prog, "elements": n}
 
     # ---- kernel trace
-    stats = read_stats(args.kt)
+    stats = read_stats(args.kt, {k: e["launches"] for k, e in entries.items()})
     rows = []
     for k in sorted(stats, key=lambda k: (k not in entries, k)):
         if not k.startswith("fbsr::"):
             continue
         s, e = stats[k], entries.get(k)
-        rows.append("| %s | %d | %.1f | %.1f | %.1f | %s | %s | %s |" % (
-            k.replace("fbsr::", ""), s["calls"], s["avg_us"], s["min_us"], s["max_us"],
+        rows.append("| %s | %d | %d | %.1f | %.1f | %.1f | %s | %s | %s |" % (
+            k.replace("fbsr::", ""), s["calls"], s["used"], s["avg_us"], s["min_us"], s["max_us"],
             "%.1f" % (e["ms"] * 1e3) if e else "", "%.0f" % (e["bytes"] / s["avg_us"] / 1e3) if e else "",
             ", ".join(e["labels"]) if e else ""))
     head = [k for k in entries if any(l in bench["per_launch"] for l in entries[k]["labels"])]
@@ -138,13 +147,15 @@ def main():
     with open(os.path.join(args.out, "bench_%s_kernel_trace.md" % tag), "w") as fh:
         fh.write("# rocprofv3 --kernel-trace --stats of bench.py, 2^%d elements (MI355X, gfx950)\n\nCommand:\n\n" % (n.bit_length() - 1))
         fh.write("    %srocprofv3 --kernel-trace --stats --output-format csv -d %s -o kt \\\n        -- %s\n\n" % (pre, out_dir["kt"], prog))
-        fh.write("Durations in microseconds.  `bench us` is bench.py's own HIP-event timing of the same launches in the same run\n"
-                 "(events include the gap between launches, so they read a few us above the trace); GB/s = algorithmic bytes\n"
-                 "per launch / the trace's mean duration.  Kernels with no bench line are warm-up or helper launches.\n\n")
+        fh.write("Durations in microseconds, over a kernel's last `timed` launches: bench.py first keeps the GPU busy with\n"
+                 "launches of the same call for 40 ms (the clocks dip for some tens of milliseconds when load sets in) and then\n"
+                 "times a dozen.  `bench us` is bench.py's own HIP-event timing of those launches in the same run (events\n"
+                 "include the gap between launches, so they read a few us above the trace); GB/s = algorithmic bytes per\n"
+                 "launch / the trace's mean duration.  Kernels with no bench line are helper launches.\n\n")
         fh.write("Headline (`roofline` of the JSON line): the 18 `round_tiles<fmt, variant, W>` kernels of a step, fmt 1|2, variant 1..3,\n"
                  "W 2|4|8: mean of their mean durations %.1f us = %.0f GB/s of 5 B/element (bench.py's events: %.1f us, %.0f GB/s).\n\n"
                  % (head_avg, 5.0 * n / head_avg / 1e3, bench["roofline"]["avg_launch_ms"] * 1e3, bench["roofline"]["achieved"]))
-        fh.write("| kernel | launches | mean | min | max | bench us | GB/s | bench.py line |\n|---|---|---|---|---|---|---|---|\n")
+        fh.write("| kernel | launches | timed | mean | min | max | bench us | GB/s | bench.py line |\n|---|---|---|---|---|---|---|---|---|\n")
         fh.write("\n".join(rows) + "\n")
     figures["headline_trace_avg_us"] = round(head_avg, 2)
 

@@ -32,13 +32,19 @@ def test_summaries_and_counter_file(tmp_path):
     n = 1 << 28
     full = "void fbsr::round_tiles<1, 1, 2>(float const*, void*, int, unsigned long, unsigned long, unsigned int)"
     qat = "void fbsr::qat_tiles<fbsr::FixedCodec<1, 3>, 4>(unsigned char*, unsigned short const*)"
-    line = {"config": {"elements": n}, "roofline": {"avg_launch_ms": 0.2, "achieved": 6700.0},
+    line = {"config": {"elements": n}, "steps": 3, "roofline": {"avg_launch_ms": 0.2, "achieved": 6700.0},
             "per_launch": {"e4m3_N2_srff": {"ms": 0.2, "gb_s": 6710.9, "gelem_s": 1342.0, "kernel": "fbsr::round_tiles<1, 1, 2>", "elements": n}},
             "paths": {"qat_adamw_e4m3_N3_src": {"ms": 0.27, "gb_s": 5965.2, "kernel": bench.PATH_KERNELS["qat_adamw_e4m3_N3_src"],
-                                                 "elements": n // 2}}}
+                                                 "elements": n // 2, "launches": 2}}}
     (tmp_path / "bench.json").write_text("noise before the line\n" + json.dumps(line) + "\n")
-    _write(str(tmp_path / "kt" / "kt_kernel_stats.csv"), ["Name", "Calls", "TotalDurationNs", "AverageNs", "Percentage", "MinNs", "MaxNs", "StdDev"],
-           [[full, 4, 800000, 200000.0, 50.0, 190000, 210000, 1.0], [qat, 2, 540000, 270000.0, 50.0, 260000, 280000, 1.0]])
+    # one launch per step of the headline kernel after a slow warm-up step; the path's two timed launches after three
+    # slower ones of its warm-up: only the last (steps, launches) of each count
+    spans = [(full, 0, 900000), (full, 1000000, 1190000), (full, 2000000, 2200000), (full, 3000000, 3210000)]
+    spans += [(qat, 4000000 + 1000000 * i, 4000000 + 1000000 * i + d) for i, d in enumerate((400000, 350000, 300000, 260000, 280000))]
+    _write(str(tmp_path / "kt" / "kt_kernel_trace.csv"),
+           ["Kind", "Agent_Id", "Queue_Id", "Stream_Id", "Thread_Id", "Dispatch_Id", "Kernel_Id", "Kernel_Name", "Correlation_Id",
+            "Start_Timestamp", "End_Timestamp"],
+           [["KERNEL_DISPATCH", "Agent 1", 1, 0, 1, i + 1, 1, k, i + 1, a, b] for i, (k, a, b) in enumerate(spans)])
     copy = "__amd_rocclr_copyBuffer"
     for folder, name, scale in (("fetch", "FETCH_SIZE", 0.5), ("write", "WRITE_SIZE", 1.0)):
         rows = []
@@ -65,7 +71,8 @@ def test_summaries_and_counter_file(tmp_path):
     assert figures["valu_per_elem"]["qat_adamw_e4m3_N3_src"] == round(439.5 * 262144 * 64 / (n // 2), 1)
     assert figures["valu_busy_pct"]["qat_adamw_e4m3_N3_src"] == 77.5
     trace = (out / "bench_2p28_kernel_trace.md").read_text()
-    assert "round_tiles<1, 1, 2> | 4 | 200.0" in trace and "qat_adamw_e4m3_N3_src" in trace
+    assert "round_tiles<1, 1, 2> | 4 | 3 | 200.0 | 190.0 | 210.0" in trace
+    assert "| 5 | 2 | 270.0 | 260.0 | 280.0" in trace and "qat_adamw_e4m3_N3_src" in trace
     assert "1.00000" in (out / "kernels_2p28_hbm_traffic.md").read_text()
 
 
