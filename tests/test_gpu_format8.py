@@ -113,8 +113,8 @@ def test_16_bit_sources_at_the_size_of_the_table_kernel(fbsr, oracle, src, name)
     source magnitudes per workgroup.  All 65536 source codes (NaNs, infinities and both zeros among them) about 1024
     times each at different global indices, a tile count that leaves the last pass of 16 tiles ragged, an offset that
     leaves a head for the per-element kernel, a second input without a single NaN (every wave on the table path);
-    formats with and without -0, saturating and with an infinity, one whose infinity is not the code after M (which
-    stays on the other kernel, as 11 random bits do)."""
+    formats with and without -0, saturating and with an infinity, one whose infinity is not the code after M (the
+    table's entries above M hold the finished code); 11 random bits stay on the other kernel."""
     d = FORMATS[name]
     n = (1 << 26) + 21 * 2048 + 77
     rng = np.random.default_rng(7 + src)
