@@ -142,9 +142,11 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
 
   const float* xs = x + (span_lo - i0);
   f32x4 va[kRows], vb[kRows];
-  auto load_pair = [&](f32x4 (&v)[kRows], int p) {
+  // exists = false: the pair lies past the span's end; every lane then reads the span's first 16 bytes (a load is
+  // issued either way, see below, but one that moves a single cache line instead of the pair's 2 KiB).
+  auto load_pair = [&](f32x4 (&v)[kRows], int p, bool exists) {
 #pragma unroll
-    for (int k = 0; k < kRows; ++k) v[k] = load_stream4(xs + (p * kStatsPairElems + k * 256 + 4 * lane));
+    for (int k = 0; k < kRows; ++k) v[k] = load_stream4(xs + (exists ? p * kStatsPairElems + k * 256 + 4 * lane : 0));
   };
 
   // Walks the bins of the elements [lo_e, lo_e + len) of the span: add_all() adds all of them to the running sums,
@@ -432,20 +434,20 @@ __global__ __launch_bounds__(kThreads) void stats_spans(const float* __restrict_
   };
 
   if (my_pairs > 0) {
-    load_pair(va, 0);
+    load_pair(va, 0, true);
     draw(0);
     // Two pairs per trip, their loads in two register sets: the loads of a pair are in flight while the pair before
     // it is worked on, and no register is copied.  Every trip issues its loads whether or not the pair exists (past
-    // the end the span's last pair is read again and dropped): with a load that may or may not have been issued
-    // the compiler would have to wait for all of them at the point where the two cases meet.
+    // the end a single word is read and dropped): with a load that may or may not have been issued the compiler
+    // would have to wait for all of them at the point where the two cases meet.
     const int last = my_pairs - 1;
 #pragma unroll 1
     for (int p = 0; p < kStatsSpanPairs; p += 2) {
-      load_pair(vb, p + 1 < last ? p + 1 : last);
+      load_pair(vb, p + 1, p + 1 <= last);
       if (p % PPR == 0 && p / PPR + 1 < (kStatsSpanPairs + PPR - 1) / PPR) draw(p / PPR + 1);
       do_pair(va, p);
       if (p + 1 > last) break;   // uniform over the wave
-      load_pair(va, p + 2 < last ? p + 2 : last);
+      load_pair(va, p + 2, p + 2 <= last);
       if ((p + 1) % PPR == 0 && (p + 1) / PPR + 1 < (kStatsSpanPairs + PPR - 1) / PPR) draw((p + 1) / PPR + 1);
       do_pair(vb, p + 1);
       if (p + 2 > last) break;

@@ -206,8 +206,9 @@ __global__ __launch_bounds__(kThreads) void stats8_spans(const float* __restrict
       }
       add_some(from, 256);
     };
-    // two rows per trip, the next two loaded before these are worked on (past the end the last pair is read again
-    // and dropped: a load that may or may not have been issued would make the compiler wait for all of them)
+    // two rows per trip, the next two loaded before these are worked on (past the end every lane reads the span's
+    // first 16 bytes and drops them: a load that may or may not have been issued would make the compiler wait for
+    // all of them)
     f32x4 ahead[kRows];
 #pragma unroll
     for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(xs + (k * 256 + 4 * lane));
@@ -216,9 +217,9 @@ __global__ __launch_bounds__(kThreads) void stats8_spans(const float* __restrict
       f32x4 v[kRows];
 #pragma unroll
       for (int k = 0; k < kRows; ++k) v[k] = ahead[k];
-      const int nr = r + kRows < my_rows ? r + kRows : r;
+      const bool more = r + kRows < my_rows;
 #pragma unroll
-      for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(xs + ((nr + k) * 256 + 4 * lane));
+      for (int k = 0; k < kRows; ++k) ahead[k] = load_stream4(xs + (more ? (r + kRows + k) * 256 + 4 * lane : 0));
 #pragma unroll
       for (int k = 0; k < kRows; ++k) do_row(r + k, v[k]);
     }
