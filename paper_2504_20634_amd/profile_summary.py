@@ -2,7 +2,7 @@
 
 The runs this reads (each a run of its own: rocprofv3 does not split counters over passes), all of the same program,
 
-    python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --no-workloads [--copy-probe]
+    python3 bench.py --no-cpu-baseline --no-workloads [--copy-probe]
 
   --kernel-trace --stats --output-format csv           -> <kt>/..._kernel_stats.csv  and the program's JSON line
   --pmc FETCH_SIZE      (with --copy-probe)            -> <fetch>/..._counter_collection.csv
@@ -114,7 +114,7 @@ def main():
     ap.add_argument("--write")
     ap.add_argument("--sq")
     ap.add_argument("--busy")
-    ap.add_argument("--bench-args", default="--steps 3 --warmup 1 --no-cpu-baseline --no-workloads")
+    ap.add_argument("--bench-args", default="--no-cpu-baseline --no-workloads")
     ap.add_argument("--out", default=os.path.join(ROOT, "profiles"))
     args = ap.parse_args()
 
