@@ -16,7 +16,7 @@ extern "C" {
 /* Streams n floats through the rounding kernels' launch shape with no
  * arithmetic (out[j] = the top byte of x[j]'s pattern): every input byte read once, one byte written per element.
  * Its throughput is the practical ceiling for fbsr_round's 4 : 1 read : write traffic on the part at hand.
- * n must be a multiple of 2048, x 16-byte and out 4-byte aligned (else FBSR_EINVAL / FBSR_EALIGN). */
+ * n must be a multiple of 4096, x 16-byte and out 4-byte aligned (else FBSR_EINVAL / FBSR_EALIGN). */
 int fbsr_probe_stream41(const float* x, void* out, uint64_t n, void* stream);
 
 /* Streams n elements through the fused training step's launch shape with no arithmetic: per element one weight byte

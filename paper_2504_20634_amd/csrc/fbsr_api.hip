@@ -369,11 +369,11 @@ int fbsr_bias_stats_format8(const float* x, void* out, uint64_t n, const fbsr_fo
 }
 
 int fbsr_probe_stream41(const float* x, void* out, uint64_t n, void* stream) {
-  if (n > fbsr::kMaxElems || n % fbsr::kTileElems != 0) return FBSR_EINVAL;
+  if (n > fbsr::kMaxElems || n % fbsr::kRoundTileElems != 0) return FBSR_EINVAL;
   if (n == 0) return FBSR_OK;
   if (x == nullptr || out == nullptr) return FBSR_EINVAL;
   if (misaligned(x, 16) || misaligned(out, 4)) return FBSR_EALIGN;
-  const hipError_t e = fbsr::launch_stream41(x, reinterpret_cast<uint8_t*>(out), n / fbsr::kTileElems,
+  const hipError_t e = fbsr::launch_stream41(x, reinterpret_cast<uint8_t*>(out), n / fbsr::kRoundTileElems,
                                              reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? FBSR_OK : FBSR_EDEVICE;
 }

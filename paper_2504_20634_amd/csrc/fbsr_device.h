@@ -387,6 +387,7 @@ constexpr int kThreads = 64 * kWavesPerBlock;
 // every block is computed exactly once and the RNG cost per element falls with W.  The lane that
 // computes a block is not the lane that consumes its bits, so the blocks go through an LDS strip
 // laid out as the tile's linear bit string (element e at bit e W).
+// (The fp32 rounding kernels take workgroups of 8 such waves, 4096 elements: WgTile's WAVES.)
 constexpr int kRows = 2;
 constexpr int kWaveElems = kRows * 256;
 constexpr int kTileElems = kWavesPerBlock * kWaveElems;
@@ -405,19 +406,21 @@ __device__ __forceinline__ uint32_t xcd_tile(uint32_t wg, uint32_t ntiles, uint3
   return (wg - r) + ((r & 7u) << log2_run) + (r >> 3);
 }
 
-template <int W> struct WgTile {
-  static constexpr int ELEMS = kTileElems;
-  static constexpr int BLOCKS = kTileElems * W / 128;
-  static constexpr int PER_THREAD = (BLOCKS + kThreads - 1) / kThreads;
+// WAVES: waves per workgroup, 512 elements each (most kernels 4; the fp32 rounding kernels 8, see kRoundWaves).
+template <int W, int WAVES = kWavesPerBlock> struct WgTile {
+  static constexpr int THREADS = 64 * WAVES;
+  static constexpr int ELEMS = WAVES * kWaveElems;
+  static constexpr int BLOCKS = ELEMS * W / 128;
+  static constexpr int PER_THREAD = (BLOCKS + THREADS - 1) / THREADS;
 };
 
-template <int W>
+template <int W, int WAVES = kWavesPerBlock>
 __device__ __forceinline__ void fill_wg_bits(uint4* strip, int tid, uint64_t wg_blk0, uint64_t seed,
                                              uint64_t step) {
 #pragma unroll
-  for (int i = 0; i < WgTile<W>::PER_THREAD; ++i) {
-    const int b = tid + kThreads * i;
-    if (b < WgTile<W>::BLOCKS) {
+  for (int i = 0; i < WgTile<W, WAVES>::PER_THREAD; ++i) {
+    const int b = tid + WgTile<W, WAVES>::THREADS * i;
+    if (b < WgTile<W, WAVES>::BLOCKS) {
       uint32_t o[4];
       philox_block(wg_blk0 + (uint64_t)b, seed, step, o);
       strip[b] = make_uint4(o[0], o[1], o[2], o[3]);

@@ -62,7 +62,19 @@ constexpr uint64_t kMaxTilesPerLaunch = (uint64_t)1 << 22;
 // update 6.15 -> 6.38), a plain 16-bit -> 8-bit stream with 4096 elements per workgroup 5 % at runs of 128 (6.35 ->
 // 6.65), the QAT step's 7 : 5 in-place stream 3 % at runs of 128 (its no-arithmetic probe 5.64 -> 5.83); for the
 // block-scaled and the generic-format kernels no run length differs from the identity by more than run-to-run noise.
-constexpr uint32_t kXcdLgRound = 8, kXcdLgSgd = 7, kXcdLgRound16 = 7, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 7;
+constexpr uint32_t kXcdLgRound = 7, kXcdLgRoundBf16 = 8, kXcdLgSgd = 7, kXcdLgRound16 = 7, kXcdLgBlock = 0, kXcdLgFormat8 = 0, kXcdLgQat = 7;
+// The fp32 -> 8-bit rounding kernels (and their no-arithmetic probe) take workgroups of 8 waves, 4096 elements: at
+// sustained clocks 84.2 % of the HBM peak against 82.8 % with 4 waves and 75 % with 16 (runs of 128 such tiles per XCD;
+// 83.8 % with 256, 83.1 % with 64).  fp32 -> bf16 (6 bytes per element) loses 1 % that way and keeps 4 waves.
+constexpr int kRoundWaves = 8;
+constexpr int kRoundThreads = 64 * kRoundWaves;
+constexpr int kRoundTileElems = kRoundWaves * kWaveElems;
+template <int FMT> struct RoundGeometry {
+  static constexpr int WAVES = Fx<FMT>::kIsFp8 ? kRoundWaves : kWavesPerBlock;
+  static constexpr int THREADS = 64 * WAVES;
+  static constexpr int TILE_ELEMS = WAVES * kWaveElems;
+  static constexpr uint32_t XCD_LG = Fx<FMT>::kIsFp8 ? kXcdLgRound : kXcdLgRoundBf16;
+};
 // Up to 16 random bits per element use slots of at most 16 bits and a code space with 24 fraction bits.  With more (the
 // rounding entry points take up to 24) every tile kernel has a flavour with 32-bit slots: the fp8 targets through the
 // hardware converts where those are exact and otherwise, like bf16 and the generic formats, in the same code space with

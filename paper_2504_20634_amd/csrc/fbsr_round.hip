@@ -4,14 +4,16 @@
 
 namespace fbsr {
 
-// One workgroup per 2048-element tile, one wave per 512 elements.  Streaming: every input byte
+// One workgroup of RoundGeometry<FMT>::WAVES waves per tile (8 and 4096 elements for the 8-bit targets, 4 and 2048 for
+// bf16), one wave per 512 elements.  Streaming: every input byte
 // is read once (16-byte loads, fully coalesced: a row of 256 floats per load instruction) and
 // every output byte written once (4 bytes per lane for fp8, 8 for bf16).  The loads are issued
 // first so that their latency overlaps the Philox rounds.
 template <int FMT, int VAR, int W>
-__global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict__ x, void* __restrict__ out,
-                                                        int nbits, uint64_t seed, uint64_t blk0, uint32_t xcd_lg) {
-  typedef WgTile<W> T;
+__global__ __launch_bounds__(RoundGeometry<FMT>::THREADS) void round_tiles(const float* __restrict__ x, void* __restrict__ out,
+                                                                            int nbits, uint64_t seed, uint64_t blk0,
+                                                                            uint32_t xcd_lg) {
+  typedef WgTile<W, RoundGeometry<FMT>::WAVES> T;
   __shared__ uint4 strip[T::BLOCKS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -21,7 +23,7 @@ __global__ __launch_bounds__(kThreads) void round_tiles(const float* __restrict_
 #pragma unroll
   for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
   if constexpr (VAR != kRNE) {
-    fill_wg_bits<W>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
+    fill_wg_bits<W, RoundGeometry<FMT>::WAVES>(strip, threadIdx.x, blk0 + (uint64_t)tile * T::BLOCKS, seed, 0);
     __syncthreads();
   }
   // W = 32: more than 16 random bits, one 32-bit slot per element (a row's four slots are one Philox block).  The fp8
@@ -114,11 +116,11 @@ __global__ __launch_bounds__(kThreads) void round_elems(const float* __restrict_
 // Measurement aid: the same tile geometry with no arithmetic -- every float is read once (16-byte loads) and
 // its top byte written (4-byte stores), a plain 4 : 1 read : write stream.  What this reaches is the practical
 // ceiling of the rounding kernels' launch shape on the part at hand.
-__global__ __launch_bounds__(kThreads) void stream41_tiles(const float* __restrict__ x, uint8_t* __restrict__ out, uint32_t xcd_lg) {
+__global__ __launch_bounds__(kRoundThreads) void stream41_tiles(const float* __restrict__ x, uint8_t* __restrict__ out, uint32_t xcd_lg) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const uint32_t tile = xcd_tile(blockIdx.x, gridDim.x, xcd_lg);
-  const uint64_t row0 = (uint64_t)tile * (kTileElems / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);
+  const uint64_t row0 = (uint64_t)tile * (kRoundTileElems / 4) + (uint64_t)(wave * (kWaveElems / 4) + lane);
   f32x4 v[kRows];
 #pragma unroll
   for (int k = 0; k < kRows; ++k) v[k] = load_stream4(x + 4 * (row0 + (uint64_t)(k * 64)));
@@ -132,8 +134,8 @@ __global__ __launch_bounds__(kThreads) void stream41_tiles(const float* __restri
 
 hipError_t launch_stream41(const float* x, uint8_t* out, uint64_t ntiles, hipStream_t stream) {
   return in_pieces(ntiles, kMaxTilesPerLaunch, [&](uint64_t t0, uint64_t count) {
-    hipLaunchKernelGGL(stream41_tiles, dim3((unsigned)count), dim3(kThreads), 0, stream, x + t0 * kTileElems, out + t0 * kTileElems,
-                       kXcdLgRound);
+    hipLaunchKernelGGL(stream41_tiles, dim3((unsigned)count), dim3(kRoundThreads), 0, stream, x + t0 * kRoundTileElems,
+                       out + t0 * kRoundTileElems, kXcdLgRound);
     return hipGetLastError();
   });
 }
@@ -143,8 +145,8 @@ namespace {
 template <int FMT, int VAR, int W>
 hipError_t launch_tiles(const float* x, void* out, uint64_t ntiles, int nbits, uint64_t seed, uint64_t blk0,
                         hipStream_t stream) {
-  hipLaunchKernelGGL((round_tiles<FMT, VAR, W>), dim3((unsigned)ntiles), dim3(kThreads), 0, stream, x, out, nbits,
-                     seed, blk0, kXcdLgRound);
+  hipLaunchKernelGGL((round_tiles<FMT, VAR, W>), dim3((unsigned)ntiles), dim3(RoundGeometry<FMT>::THREADS), 0, stream, x, out,
+                     nbits, seed, blk0, RoundGeometry<FMT>::XCD_LG);
   return hipGetLastError();
 }
 
@@ -171,7 +173,7 @@ hipError_t run(const float* x, void* out, uint64_t n, int nbits, uint64_t seed, 
   const int W = VAR == kRNE ? 8 : slot_width(nbits);
   const uint64_t osize = sizeof(typename Fx<FMT>::code_t);
   const Split s = split_range(n, offset, W, VAR == kRNE, reinterpret_cast<uintptr_t>(x), 4, 16,
-                              reinterpret_cast<uintptr_t>(out), osize, 4 * osize);
+                              reinterpret_cast<uintptr_t>(out), osize, 4 * osize, 0, 0, 1, RoundGeometry<FMT>::TILE_ELEMS);
   char* o = reinterpret_cast<char*>(out);
   return run_split(
       s, n,

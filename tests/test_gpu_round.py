@@ -158,7 +158,7 @@ def test_fp32_subnormal_inputs_to_fp8(fbsr, oracle):
 
 def test_stream_probe_copies_top_bytes(fbsr):
     """The measurement aid writes the top byte of every pattern and nothing else."""
-    n = 7 * 2048
+    n = 7 * 4096
     bits = torch.randint(-2 ** 31, 2 ** 31 - 1, (n,), dtype=torch.int64, device="cuda").to(torch.int32)
     out = torch.full((n + 16,), 0xA5, dtype=torch.uint8, device="cuda")
     fbsr.binding.fbsr_probe_stream41(bits.view(torch.float32), out[:n])
